@@ -1,0 +1,169 @@
+"""ctypes access to the GREM CPU oracle (``grem_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()`` and by the
+``cpu_baseline`` leg of ``bench.py``.  The GPU package never imports this module and this module
+never imports the GPU package.  All arrays are host numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "grem_oracle.c")
+_LIB = os.path.join(_HERE, "libgrem_oracle.so")
+
+OK = 0
+ERR_ARG, ERR_NOMEM, ERR_RANGE, ERR_SEED, ERR_INTERNAL = -1, -2, -3, -4, -5
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code: int):
+        super().__init__(f"grem oracle returned {code}")
+        self.code = code
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, single thread, no contraction of a*b+c)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB)
+    i64p, i32p, u32p = (ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32),
+                        ctypes.POINTER(ctypes.c_uint32))
+    lib.grem_oracle_capacity.restype = ctypes.c_int64
+    lib.grem_oracle_capacity.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_double]
+    lib.grem_oracle_create.restype = ctypes.c_void_p
+    lib.grem_oracle_create.argtypes = [i64p, i32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double,
+                                       ctypes.c_int64, ctypes.c_int32, i32p,
+                                       ctypes.POINTER(ctypes.c_int)]
+    lib.grem_oracle_destroy.restype = None
+    lib.grem_oracle_destroy.argtypes = [ctypes.c_void_p]
+    lib.grem_oracle_step.restype = ctypes.c_int
+    lib.grem_oracle_step.argtypes = [ctypes.c_void_p]
+    for name, rt in (("grem_oracle_get_capacity", ctypes.c_int64), ("grem_oracle_get_pass", ctypes.c_int32),
+                     ("grem_oracle_get_next_chunk", ctypes.c_int64), ("grem_oracle_labels", i32p),
+                     ("grem_oracle_sizes", i64p), ("grem_oracle_estimates", u32p)):
+        getattr(lib, name).restype = rt
+        getattr(lib, name).argtypes = [ctypes.c_void_p]
+    lib.grem_oracle_partition_seeded.restype = ctypes.c_int
+    lib.grem_oracle_partition_seeded.argtypes = [i64p, i32p, ctypes.c_int64, ctypes.c_int32,
+                                                 ctypes.c_double, ctypes.c_int64, ctypes.c_int32,
+                                                 i32p, i32p, i64p, u32p]
+    lib.grem_oracle_edge_cut.restype = ctypes.c_int64
+    lib.grem_oracle_edge_cut.argtypes = [i64p, i32p, ctypes.c_int64, i32p]
+    _lib = lib
+    return lib
+
+
+def _p(arr, ct):
+    return None if arr is None else arr.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def _csr(rowptr, colidx):
+    rp = np.ascontiguousarray(rowptr, dtype=np.int64)
+    ci = np.ascontiguousarray(colidx, dtype=np.int32)
+    return rp, ci
+
+
+def capacity(n: int, k: int, balance_slack: float) -> int:
+    return int(_load().grem_oracle_capacity(n, k, balance_slack))
+
+
+def partition_seeded(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, seed_labels=None,
+                     return_state: bool = False):
+    """Labels (int32[n]) of the whole run; with ``return_state`` also sizes (int64[k]) and the
+    scaled estimates E (uint32[n,k])."""
+    lib = _load()
+    rp, ci = _csr(rowptr, colidx)
+    seed = None if seed_labels is None else np.ascontiguousarray(seed_labels, dtype=np.int32)
+    labels = np.empty(n, dtype=np.int32)
+    sizes = np.empty(k, dtype=np.int64) if return_state else None
+    est = np.empty((n, k), dtype=np.uint32) if return_state else None
+    rc = lib.grem_oracle_partition_seeded(_p(rp, ctypes.c_int64), _p(ci, ctypes.c_int32), n, k,
+                                          float(balance_slack), chunk, refine_passes,
+                                          _p(seed, ctypes.c_int32), _p(labels, ctypes.c_int32),
+                                          _p(sizes, ctypes.c_int64), _p(est, ctypes.c_uint32))
+    if rc != OK:
+        raise OracleError(rc)
+    if return_state:
+        return labels, sizes, est
+    return labels
+
+
+def partition(rowptr, colidx, n, k, balance_slack, chunk, refine_passes):
+    return partition_seeded(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, None)
+
+
+def edge_cut(rowptr, colidx, n, labels) -> int:
+    rp, ci = _csr(rowptr, colidx)
+    lab = np.ascontiguousarray(labels, dtype=np.int32)
+    return int(_load().grem_oracle_edge_cut(_p(rp, ctypes.c_int64), _p(ci, ctypes.c_int32), n,
+                                            _p(lab, ctypes.c_int32)))
+
+
+class Stepper:
+    """The run one chunk at a time, for tests that look at the state between chunks and for the
+    bounded CPU-baseline sample."""
+
+    def __init__(self, rowptr, colidx, n, k, balance_slack, chunk, refine_passes, seed_labels=None):
+        self._lib = _load()
+        self._rp, self._ci = _csr(rowptr, colidx)   # keep alive: the state borrows them
+        self.n, self.k = n, k
+        seed = None if seed_labels is None else np.ascontiguousarray(seed_labels, dtype=np.int32)
+        status = ctypes.c_int(0)
+        self._h = self._lib.grem_oracle_create(_p(self._rp, ctypes.c_int64), _p(self._ci, ctypes.c_int32),
+                                               n, k, float(balance_slack), chunk, refine_passes,
+                                               _p(seed, ctypes.c_int32), ctypes.byref(status))
+        if not self._h:
+            raise OracleError(status.value)
+
+    def step(self) -> bool:
+        rc = self._lib.grem_oracle_step(self._h)
+        if rc < 0:
+            raise OracleError(rc)
+        return rc == 1
+
+    @property
+    def capacity(self) -> int:
+        return int(self._lib.grem_oracle_get_capacity(self._h))
+
+    @property
+    def position(self):
+        """(pass, chunk) of the next step."""
+        return int(self._lib.grem_oracle_get_pass(self._h)), int(self._lib.grem_oracle_get_next_chunk(self._h))
+
+    def labels(self) -> np.ndarray:
+        return np.ctypeslib.as_array(self._lib.grem_oracle_labels(self._h), shape=(self.n,)).copy()
+
+    def sizes(self) -> np.ndarray:
+        return np.ctypeslib.as_array(self._lib.grem_oracle_sizes(self._h), shape=(self.k,)).copy()
+
+    def estimates(self) -> np.ndarray:
+        return np.ctypeslib.as_array(self._lib.grem_oracle_estimates(self._h), shape=(self.n, self.k)).copy()
+
+    def close(self):
+        if self._h:
+            self._lib.grem_oracle_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

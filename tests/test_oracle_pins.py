@@ -1,0 +1,358 @@
+"""CPU pins of the oracle: what the paper and the mathematics fix, checked without the GPU.
+
+Each test states which mistake it is meant to catch."""
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2502_17846_amd import synth
+from tests import ref_models as ref
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _csr_from_edges(edges, n):
+    e = np.asarray(edges, dtype=np.int64).reshape(-1, 2)
+    return synth.csr_from_pairs_np(e[:, 0], e[:, 1], n)
+
+
+# ---------------------------------------------------------------------------------------------
+# hand-worked example (tests/golden/handworked_6v.json)
+# ---------------------------------------------------------------------------------------------
+
+def test_handworked_example():
+    with open(os.path.join(GOLDEN, "handworked_6v.json")) as f:
+        g = json.load(f)
+    n, k, chunk = g["n"], g["k"], g["chunk"]
+    rowptr, colidx = _csr_from_edges(g["edges"], n)
+    c0, c1 = g["cases"]
+    assert oracle.capacity(n, k, c0["balance_slack"]) == c0["capacity"]
+    lab, sizes, est = oracle.partition_seeded(rowptr, colidx, n, k, c0["balance_slack"], chunk,
+                                              c0["refine_passes"], None, return_state=True)
+    assert lab.tolist() == c0["labels"]
+    assert sizes.tolist() == c0["sizes"]
+    assert est.tolist() == c0["estimates"]
+    assert oracle.edge_cut(rowptr, colidx, n, lab) == c0["cut_entries"]
+
+    assert oracle.capacity(n, k, c1["balance_slack"]) == c1["capacity"]
+    for r in range(c1["refine_passes"] + 1):
+        lab, sizes, est = oracle.partition_seeded(rowptr, colidx, n, k, c1["balance_slack"], chunk,
+                                                  r, None, return_state=True)
+        assert lab.tolist() == c1["labels_after_pass"][r], r
+        assert sizes.tolist() == c1["sizes_after_pass"][r], r
+        assert est.tolist() == c1["estimates_after_pass"][r], r
+        assert oracle.edge_cut(rowptr, colidx, n, lab) == c1["cut_entries_after_pass"][r], r
+
+
+# ---------------------------------------------------------------------------------------------
+# pin 1: brute force on tiny graphs (definition of the cut, balance)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(12))
+def test_tiny_bruteforce_cut_and_balance(seed):
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(2, 13))
+    m = int(rng.integers(0, 3 * n))
+    g = synth.random_graph_np(n, m, seed, simple=bool(seed % 2))   # odd seeds: simple graphs
+    A = ref.dense_adjacency(g.rowptr, g.colidx, n)
+    for k in range(1, 5):
+        for slack in (1.0, 1.05, 1.5):
+            for chunk in (1, 2, 5, 64):
+                for R in range(4):
+                    lab = oracle.partition(g.rowptr, g.colidx, n, k, slack, chunk, R)
+                    P = oracle.capacity(n, k, slack)
+                    cnt = np.bincount(lab, minlength=k)
+                    assert lab.min() >= 0 and lab.max() < k
+                    assert cnt.sum() == n and cnt.max() <= P
+                    assert oracle.edge_cut(g.rowptr, g.colidx, n, lab) == ref.brute_cut_entries(A, lab)
+
+
+def test_capacity_values():
+    # objective ceil(V/p) (Sec. 4.1) at slack 1; the slack only widens it
+    assert oracle.capacity(10, 3, 1.0) == 4
+    assert oracle.capacity(10_000, 4, 1.05) == 2625
+    assert oracle.capacity(1 << 20, 8, 1.05) == 137_626
+    assert oracle.capacity(111_000_000, 16, 1.05) == 7_284_375
+    assert oracle.capacity(1 << 27, 32, 1.03) == 4_320_134
+    assert oracle.capacity(1 << 24, 256, 1.10) == 72_090
+    assert oracle.capacity(7, 7, 1.0) == 1
+
+
+# ---------------------------------------------------------------------------------------------
+# pin 2: k = 2, chunk = 1 equals the paper's two-partition procedure run sequentially
+#   catches: wrong tie order, missing removal of v from its own part, wrong blend, seed handling
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed,slack", [(0, 1.0), (1, 1.0), (2, 1.05), (3, 1.2), (4, 1.0)])
+def test_k2_chunk1_equals_sequential_bipartition(seed, slack):
+    g = synth.planted_partition(n=600, blocks=2, mean_degree=8.0, ratio=6.0, seed=seed,
+                                rowptr_dtype=np.int64)
+    n, R = g.n, 3
+    P = oracle.capacity(n, 2, slack)
+    if slack == 1.0:
+        assert P == n // 2         # the perfectly balanced objective of Sec. 4.1
+    lab, sizes, est = oracle.partition_seeded(g.rowptr, g.colidx, n, 2, slack, 1, R, None,
+                                              return_state=True)
+    parts, rsizes, rest = ref.sequential_bipartition(g.rowptr, g.colidx, n, P, R + 1)
+    assert lab.tolist() == parts
+    assert sizes.tolist() == rsizes
+    for v in range(n):
+        assert Fraction(int(est[v, 0]), 2 ** R) == rest[v][0]
+        assert Fraction(int(est[v, 1]), 2 ** R) == rest[v][1]
+
+
+def test_k2_chunk1_seeded_equals_sequential_bipartition():
+    g = synth.planted_partition(n=400, blocks=2, mean_degree=8.0, ratio=8.0, seed=7,
+                                rowptr_dtype=np.int64)
+    n, R, slack = g.n, 2, 1.05
+    seed = np.full(n, -1, dtype=np.int32)
+    seed[:60] = g.planted[:60]
+    P = oracle.capacity(n, 2, slack)
+    lab, sizes, est = oracle.partition_seeded(g.rowptr, g.colidx, n, 2, slack, 1, R, seed,
+                                              return_state=True)
+    parts, rsizes, rest = ref.sequential_bipartition(g.rowptr, g.colidx, n, P, R + 1, seed=seed)
+    assert lab.tolist() == parts and sizes.tolist() == rsizes
+    for v in range(n):
+        assert Fraction(int(est[v, 0]), 2 ** R) == rest[v][0]
+        assert Fraction(int(est[v, 1]), 2 ** R) == rest[v][1]
+
+
+# ---------------------------------------------------------------------------------------------
+# pin 3: closed forms
+#   catches: off-by-one in the admission rank, wrong spill order, wrong arg-min tie
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("k,slack", [(1, 1.0), (2, 1.05), (4, 1.05), (7, 1.0), (8, 1.3)])
+def test_single_chunk_closed_form(k, slack):
+    g = synth.random_graph_np(1000, 4000, 3)
+    n = g.n
+    P = oracle.capacity(n, k, slack)
+    lab = oracle.partition(g.rowptr, g.colidx, n, k, slack, n + 5, 0)
+    v = np.arange(n)
+    expect = np.zeros(n, dtype=np.int64) if k == 1 else np.where(v < P, 0, 1 + (v - P) % max(k - 1, 1))
+    assert lab.tolist() == expect.tolist()
+
+
+@pytest.mark.parametrize("n,k,slack,chunk", [(1000, 4, 1.05, 64), (997, 7, 1.0, 100), (50, 3, 1.5, 7),
+                                              (4096, 16, 1.05, 1000), (300, 300, 1.0, 17)])
+def test_edgeless_graph_first_pass(n, k, slack, chunk):
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    colidx = np.zeros(0, dtype=np.int32)
+    P = oracle.capacity(n, k, slack)
+    lab = oracle.partition(rowptr, colidx, n, k, slack, chunk, 0)
+    assert lab.tolist() == ref.edgeless_pass0(n, k, P, chunk).tolist()
+
+
+# ---------------------------------------------------------------------------------------------
+# pin 4 + 5: blend weights and invariants after every chunk, via dense matrices
+#   catches: wrong power of two, blend applied at the wrong visit, counting unassigned
+#   neighbours, reading labels that are not the chunk-start snapshot
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("k,chunk,simple", [(2, 7, True), (3, 16, True), (5, 1, True), (4, 33, False)])
+def test_estimates_are_weighted_sums_of_snapshot_counts(k, chunk, simple):
+    n, R, slack = 90, 3, 1.1
+    g = synth.random_graph_np(n, 400, 11, simple=simple)
+    A = ref.dense_adjacency(g.rowptr, g.colidx, n)
+    st = oracle.Stepper(g.rowptr, g.colidx, n, k, slack, chunk, R)
+    P = st.capacity
+    expect = np.zeros((n, k), dtype=np.int64)
+    while True:
+        r, c = st.position
+        if r > R:
+            break
+        L = st.labels()
+        onehot = np.zeros((n, k), dtype=np.int64)
+        assigned = L >= 0
+        onehot[np.nonzero(assigned)[0], L[assigned]] = 1
+        H = A @ onehot                                 # counts against the chunk-start labels
+        lo, hi = c * chunk, min(n, (c + 1) * chunk)
+        w = 1 if r == 0 else 2 ** (r - 1)              # weights 1, 1, 2, 4: older visits halve
+        expect[lo:hi] += w * H[lo:hi]
+        assert st.step()
+        S, L2 = st.sizes(), st.labels()
+        assert (st.estimates()[lo:hi] == expect[lo:hi]).all()
+        assert S.max() <= P and S.min() >= 0
+        assert (np.bincount(L2[L2 >= 0], minlength=k) == S).all()
+        assert (L2[lo:hi] >= 0).all()
+        other = np.ones(n, dtype=bool)
+        other[lo:hi] = False
+        assert (L2[other] == L[other]).all()          # only the chunk's own vertices change
+    assert not st.step()
+    assert (st.estimates() == expect).all()
+
+
+def test_blend_weights_on_a_star():
+    # Stored entries only from the centre (vertex 0) to 6 leaves, 3 seeded in each of k=2 parts;
+    # capacity is ceil(7/2) = 4.  The centre ties (3,3) and takes part 0 (sizes tie, lowest id),
+    # after which part 0 is full: leaves of part 1 cannot enter it, leaves of part 0 have empty
+    # rows and equal sizes without them, so they stay.  Every visit of the centre counts (3,3).
+    n, k = 7, 2
+    rowptr, colidx = synth.csr_from_pairs_np(np.zeros(6, dtype=np.int64), np.arange(1, 7), n,
+                                             symmetrise=False)
+    seed = np.array([-1, 0, 0, 0, 1, 1, 1], dtype=np.int32)
+    for R in range(5):
+        lab, _, est = oracle.partition_seeded(rowptr, colidx, n, k, 1.0, 1, R, seed, return_state=True)
+        assert lab.tolist() == [0, 0, 0, 0, 1, 1, 1]
+        total = 1 + sum(2 ** (s - 1) for s in range(1, R + 1))      # weights 1,1,2,4,.. sum to 2^R
+        assert total == 2 ** R
+        assert est[0].tolist() == [3 * total, 3 * total]
+        assert not est[1:].any()
+
+
+def test_determinism():
+    g = synth.planted_partition(n=2000, blocks=4, seed=5, rowptr_dtype=np.int64)
+    a = oracle.partition(g.rowptr, g.colidx, g.n, 4, 1.05, 256, 2)
+    b = oracle.partition(g.rowptr, g.colidx, g.n, 4, 1.05, 256, 2)
+    assert a.tobytes() == b.tobytes()
+
+
+# ---------------------------------------------------------------------------------------------
+# k-way local check at chunk = 1: every decision is a best eligible partition
+# ---------------------------------------------------------------------------------------------
+
+def test_kway_chunk1_every_move_is_best_eligible():
+    n, k, R, slack = 120, 5, 2, 1.1
+    g = synth.random_graph_np(n, 500, 21)
+    A = ref.dense_adjacency(g.rowptr, g.colidx, n)
+    st = oracle.Stepper(g.rowptr, g.colidx, n, k, slack, 1, R)
+    P = st.capacity
+    Eprev = np.zeros((n, k), dtype=np.int64)
+    while True:
+        r, v = st.position
+        if r > R:
+            break
+        L, S = st.labels(), st.sizes()
+        h = np.zeros(k, dtype=np.int64)
+        for u in np.nonzero(A[v])[0]:
+            if L[u] >= 0:
+                h[L[u]] += A[v, u]
+        Ev = h if r == 0 else Eprev[v] + (2 ** (r - 1)) * h
+        Eprev[v] = Ev
+        Sp = S.copy()
+        if L[v] >= 0:
+            Sp[L[v]] -= 1
+        st.step()
+        t = st.labels()[v]
+        elig = Sp < P
+        assert elig[t]
+        assert Ev[t] == Ev[elig].max()                               # most neighbours among non-full
+        tied = elig & (Ev == Ev[t])
+        assert Sp[t] == Sp[tied].min()                               # then the smaller part
+        assert t == np.nonzero(tied & (Sp == Sp[t]))[0][0]           # then the lowest id
+
+
+# ---------------------------------------------------------------------------------------------
+# pin 6: seeded planted-partition recovery (first chunk seeded, as Alg. 1 seeds its first chunk)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gseed", [0, 1, 2])
+def test_planted_recovery_with_first_chunk_seed(gseed):
+    g = synth.planted_partition(seed=gseed)
+    k, slack, chunk, R = 4, 1.05, 1024, 2
+    seed = np.full(g.n, -1, dtype=np.int32)
+    seed[:chunk] = g.planted[:chunk]
+    lab = oracle.partition_seeded(g.rowptr, g.colidx, g.n, k, slack, chunk, R, seed)
+    agree = ref.best_permutation_agreement(lab, g.planted, k)
+    cut = oracle.edge_cut(g.rowptr, g.colidx, g.n, lab)
+    planted_cut = oracle.edge_cut(g.rowptr, g.colidx, g.n, g.planted)
+    assert agree >= 0.99, agree
+    assert cut <= 1.01 * planted_cut, (cut, planted_cut)
+    assert np.bincount(lab, minlength=k).max() <= oracle.capacity(g.n, k, slack)
+
+
+# ---------------------------------------------------------------------------------------------
+# pin 7: refinement does not increase the cut on these graphs (empirical, Sec. 6 "The Benefit of
+# Refinement"); the hand-worked example above shows it is not a theorem
+# ---------------------------------------------------------------------------------------------
+
+def _cuts_per_pass(g, k, slack, chunk, R, seed=None):
+    return [oracle.edge_cut(g.rowptr, g.colidx, g.n,
+                            oracle.partition_seeded(g.rowptr, g.colidx, g.n, k, slack, chunk, r, seed))
+            for r in range(R + 1)]
+
+
+def test_refinement_does_not_increase_cut_planted():
+    g = synth.planted_partition(seed=0)
+    cuts = _cuts_per_pass(g, 4, 1.05, 1024, 4)
+    assert all(b <= a for a, b in zip(cuts, cuts[1:])), cuts
+    seed = np.full(g.n, -1, dtype=np.int32)
+    seed[:1024] = g.planted[:1024]
+    cuts = _cuts_per_pass(g, 4, 1.05, 1024, 4, seed)
+    assert all(b <= a for a, b in zip(cuts, cuts[1:])), cuts
+    # unseeded, two refinement passes: clearly better than a random 4-way split (0.75)
+    assert cuts[2] / g.nnz < 0.75
+
+
+@pytest.mark.parametrize("scale,k", [(12, 8), (13, 32)])
+def test_refinement_does_not_increase_cut_rmat(scale, k):
+    g = synth.to_numpy(synth.rmat(scale, 16, seed=1, rowptr_dtype=__import__("torch").int64))
+    cuts = _cuts_per_pass(g, k, 1.05, max(1, g.n // 16), 3)
+    assert all(b <= a for a, b in zip(cuts, cuts[1:])), cuts
+
+
+# ---------------------------------------------------------------------------------------------
+# pin 8: symmetries
+# ---------------------------------------------------------------------------------------------
+
+def test_isolated_padding_does_not_change_earlier_labels():
+    g = synth.planted_partition(n=1200, blocks=3, seed=9, rowptr_dtype=np.int64)
+    k, chunk = 3, 100
+    # fix the capacity by hand: pad so that P is the same with and without padding
+    pad = 300
+    n2 = g.n + pad
+    rowptr2 = np.concatenate([g.rowptr, np.full(pad, g.rowptr[-1], dtype=np.int64)])
+    P2 = oracle.capacity(n2, k, 1.0)
+    slack1 = P2 * k / g.n                      # same P for the unpadded run
+    assert oracle.capacity(g.n, k, slack1) == P2
+    a = oracle.partition(g.rowptr, g.colidx, g.n, k, slack1, chunk, 0)
+    b = oracle.partition(rowptr2, g.colidx, n2, k, 1.0, chunk, 0)
+    assert a.tolist() == b[:g.n].tolist()
+
+
+def test_permuting_ids_inside_chunks_permutes_the_result():
+    # With capacity >= n nothing is ever full, so every move is admitted and the order inside a
+    # chunk plays no role: renaming vertices by a permutation that maps each chunk onto itself
+    # must give the renamed labels.  (Across chunks the stream order matters; no symmetry there.)
+    g = synth.planted_partition(n=900, blocks=3, seed=3, rowptr_dtype=np.int64)
+    n, k, chunk, R = g.n, 3, 128, 2
+    rng = np.random.default_rng(0)
+    perm = np.arange(n)
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        perm[lo:hi] = lo + rng.permutation(hi - lo)      # new id of old vertex
+    src = np.repeat(np.arange(n), np.diff(g.rowptr))
+    rp2, ci2 = synth.csr_from_pairs_np(perm[src], perm[g.colidx], n, symmetrise=False)
+    a = oracle.partition(g.rowptr, g.colidx, n, k, float(k), chunk, R)
+    b = oracle.partition(rp2, ci2, n, k, float(k), chunk, R)
+    assert b[perm].tolist() == a.tolist()
+
+
+# ---------------------------------------------------------------------------------------------
+# argument and range errors
+# ---------------------------------------------------------------------------------------------
+
+def test_errors():
+    g = synth.random_graph_np(10, 20, 0)
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.partition(g.rowptr, g.colidx, 10, 0, 1.05, 4, 0)
+    assert e.value.code == oracle.ERR_ARG
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.partition(g.rowptr, g.colidx, 10, 2, 0.9, 4, 0)
+    assert e.value.code == oracle.ERR_ARG
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.partition(g.rowptr, g.colidx, 10, 2, 1.05, 4, 31)
+    assert e.value.code == oracle.ERR_RANGE
+    seed = np.full(10, -1, dtype=np.int32)
+    seed[3] = 2
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.partition_seeded(g.rowptr, g.colidx, 10, 2, 1.05, 4, 0, seed)
+    assert e.value.code == oracle.ERR_SEED
+    seed[:] = 0                                     # 10 vertices in part 0 > P
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.partition_seeded(g.rowptr, g.colidx, 10, 2, 1.05, 4, 0, seed)
+    assert e.value.code == oracle.ERR_SEED
