@@ -1,0 +1,143 @@
+/*
+ * grem.h -- C ABI of the MI355X (gfx950) GREM partitioner.
+ *
+ * GREM is the streaming greedy min-edge-cut partitioner with continuous refinement of the Armada
+ * paper (Sec. 4.1, Alg. 1 "GREM Bipartite Graph Partitioning" and Alg. 2 "GREM Helper
+ * Functions").  This library computes its chunk-synchronous, direct k-way form on one GPU:
+ *
+ *   P  = max(ceil(n/k), ceil(n*balance_slack/k))          capacity of a partition (Alg. 1 input P)
+ *   L[v] = seed or -1,  S[j] = #{v: L[v]=j},  E[v][j] = 0
+ *   for pass r = 0 .. refine_passes, for each chunk C of `chunk` consecutive vertex rows:
+ *     (all reads below see L and S as they were when the chunk started)
+ *     h[v][j]  = #{entries u of row v with L[u] = j}       (cnt_nbrs, Alg. 2; unassigned skipped)
+ *     E[v][j]  = h                       in pass 0
+ *              = E[v][j] + h * 2^(r-1)   in pass r >= 1    (the running average of Alg. 1 kept as
+ *                                                           the exact integer 2^r * average)
+ *     proposal = v's seed if r = 0 and v is seeded, else the partition with room
+ *                (S'[j] < P, S' = S without v itself) that maximises (E[v][j], -S'[j], -j)
+ *                                                          (assign, Alg. 2)
+ *     admission in ascending v: a vertex whose proposal t differs from its label moves if fewer
+ *     than P - S[t] earlier vertices of the chunk proposed t; a rejected refined vertex keeps its
+ *     label; rejected new vertices are then placed one by one, in ascending v, in the currently
+ *     smallest partition (lowest id on ties)            (fix_sizes and the arg_min fallback, Alg. 2)
+ *
+ * The result is a pure function of the arguments: the same bytes on every run.
+ *
+ * Conventions for every entry point
+ *   - All array pointers are DEVICE pointers owned by the caller.  The library neither frees nor
+ *     keeps them once the work it enqueued has completed.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Argument checks and
+ *     one small validation read-back happen before the call returns; the passes themselves are
+ *     only enqueued on `stream` -- synchronise the stream before reading the outputs.
+ *   - Return value: GREM_OK or a negative GREM_ERR_* code; nothing throws or aborts.  On error the
+ *     outputs are unspecified.
+ *   - The CSR must be well formed (rowptr non-decreasing, rowptr[0] = 0, 0 <= colidx < n); this is
+ *     the caller's contract and is not checked.  Entries are counted exactly as stored (loops and
+ *     duplicates included); nothing requires symmetry.
+ *   - Calls that share the process-wide workspace (grem_set_workspace) must not overlap in time.
+ */
+#ifndef GREM_H
+#define GREM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GREM_OK 0
+#define GREM_ERR_ARG (-1)    /* null pointer, n < 1, n > 2^31-1, k < 1, k > GREM_MAX_K, chunk < 1,
+                                refine_passes < 0, balance_slack < 1 or NaN */
+#define GREM_ERR_NOMEM (-2)  /* workspace allocation failed or the given workspace is too small */
+#define GREM_ERR_HIP (-3)    /* a HIP runtime call failed */
+#define GREM_ERR_RANGE (-4)  /* max_degree * 2^refine_passes >= 2^32 (E would overflow), or a tile
+                                of rows holds 2^32 or more entries */
+#define GREM_ERR_SEED (-5)   /* a seed label outside {-1} u [0,k), or a seeded partition above P */
+
+#define GREM_MAX_K 4096
+
+/* Histogram placement for the per-vertex partition counts (Alg. 2, cnt_nbrs). */
+#define GREM_HIST_AUTO 0     /* LDS when a tile of rows fits the LDS budget (k <= 128), else global */
+#define GREM_HIST_LDS 1      /* force LDS (error GREM_ERR_ARG if k > 128) */
+#define GREM_HIST_GLOBAL 2   /* force accumulation straight into E's rows in global memory */
+
+/* Sec. 4.1 (Alg. 1 with all nodes unassigned at the start).  rowptr: n+1 entries; colidx:
+ * rowptr[n] entries; labels_out: n entries, each in [0,k) on completion. */
+int grem_partition(const int64_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
+                   double balance_slack, int64_t chunk, int32_t refine_passes,
+                   int32_t *labels_out, void *stream);
+
+/* Same, with the output of Alg. 1's `seed_algo` supplied as data: seed_labels has n entries, -1 =
+ * unassigned; a seeded vertex keeps its label at its pass-0 visit and only records its estimate
+ * (first-chunk treatment in Alg. 1).  seed_labels may be NULL (= grem_partition) and may alias
+ * labels_out. */
+int grem_partition_seeded(const int64_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
+                          double balance_slack, int64_t chunk, int32_t refine_passes,
+                          const int32_t *seed_labels, int32_t *labels_out, void *stream);
+
+/* The same two calls for a CSR whose rowptr is int32 (fewer than 2^31 entries). */
+int grem_partition_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
+                       double balance_slack, int64_t chunk, int32_t refine_passes,
+                       int32_t *labels_out, void *stream);
+int grem_partition_seeded_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
+                              double balance_slack, int64_t chunk, int32_t refine_passes,
+                              const int32_t *seed_labels, int32_t *labels_out, void *stream);
+
+/* The same run, also returning the rest of Alg. 1's state.  rowptr_bits is 32 or 64.
+ * sizes_out: k int64 partition sizes (Alg. 1 `sizes`), may be NULL.  estimates_out: n*k uint32,
+ * row-major, the scaled running estimates E (Alg. 1 `nbr_counts` times 2^refine_passes), may be
+ * NULL; when given it is used as E's storage and the workspace shrinks by n*k*4 bytes. */
+int grem_partition_state(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
+                         int32_t k, double balance_slack, int64_t chunk, int32_t refine_passes,
+                         const int32_t *seed_labels, int32_t *labels_out, int64_t *sizes_out,
+                         uint32_t *estimates_out, void *stream);
+
+/* Number of CSR entries (v,u) with labels[v] != labels[u] (Sec. 1: cut edges have their endpoints
+ * in different partitions), written to the single device int64 *cut_entries_out.  For a symmetric
+ * loop-free CSR the undirected cut is half of it and the cut fraction is cut_entries / nnz.
+ * labels: n int32 values, any values. */
+int grem_edge_cut(const int64_t *rowptr, const int32_t *colidx, int64_t n, const int32_t *labels,
+                  int64_t *cut_entries_out, void *stream);
+int grem_edge_cut_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n,
+                      const int32_t *labels, int64_t *cut_entries_out, void *stream);
+
+/* Host helpers.  grem_capacity returns P (or -1 on bad arguments). */
+int64_t grem_capacity(int64_t n, int32_t k, double balance_slack);
+
+/* Bytes of device workspace a partition call needs (E included; subtract n*k*4 when
+ * estimates_out is passed).  0 on bad arguments. */
+size_t grem_workspace_bytes(int64_t n, int32_t k, int64_t chunk);
+
+/* Optional caller-owned workspace (device memory, 256-byte aligned) used by later partition
+ * calls instead of a per-call stream-ordered allocation; (NULL, 0) removes it.  The library never
+ * frees it. */
+int grem_set_workspace(void *dev_ptr, size_t bytes);
+
+/* GREM_HIST_*; returns GREM_ERR_ARG for an unknown mode.  Process-wide. */
+int grem_set_histogram_mode(int32_t mode);
+
+/* Per-kernel timing with HIP events on the caller's stream, for measurement.  While enabled every
+ * kernel launch of a partition call is bracketed by two events.  grem_profile_read synchronises on
+ * the recorded events, adds up the launches of one kernel class since the last grem_profile_reset,
+ * and returns total milliseconds and the launch count.  Classes: */
+#define GREM_KERNEL_PREPASS 0
+#define GREM_KERNEL_SCORE 1      /* row stream + label gather + histogram + blend + argmax */
+#define GREM_KERNEL_COUNT 2
+#define GREM_KERNEL_SCAN 3
+#define GREM_KERNEL_APPLY 4
+#define GREM_KERNEL_SPILL_SCAN 5
+#define GREM_KERNEL_SPILL_FILL 6
+#define GREM_KERNEL_EXPAND 7
+#define GREM_KERNEL_CLASSES 8
+int grem_profile_enable(int32_t on);
+int grem_profile_reset(void);
+int grem_profile_read(int32_t kernel_class, double *total_ms, int64_t *launches);
+
+const char *grem_status_string(int code);
+const char *grem_kernel_name(int32_t kernel_class);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GREM_H */

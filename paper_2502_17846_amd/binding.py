@@ -1,0 +1,228 @@
+"""Thin ctypes binding of libgrem.so (see include/grem.h).  Argument marshalling only: torch is
+used for device memory and streams, every step of the computation runs in the library's kernels.
+
+The functions carry the library's names.  Device arrays are torch tensors on a ROCm device;
+there is no CPU path: a missing library or a CPU tensor is an error."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgrem.so")
+
+OK, ERR_ARG, ERR_NOMEM, ERR_HIP, ERR_RANGE, ERR_SEED = 0, -1, -2, -3, -4, -5
+HIST_AUTO, HIST_LDS, HIST_GLOBAL = 0, 1, 2
+MAX_K = 4096
+KERNEL_CLASSES = 8
+KERNEL_SCORE = 1
+
+EXPORTS = [
+    "grem_partition", "grem_partition_seeded", "grem_partition_r32", "grem_partition_seeded_r32",
+    "grem_partition_state", "grem_edge_cut", "grem_edge_cut_r32", "grem_capacity",
+    "grem_workspace_bytes", "grem_set_workspace", "grem_set_histogram_mode", "grem_profile_enable",
+    "grem_profile_reset", "grem_profile_read", "grem_status_string", "grem_kernel_name",
+]
+
+
+class GremError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {code} ({status_string(code)})")
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Loads libgrem.so; raises if it has not been built (python -m paper_2502_17846_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                           "or `python paper_2502_17846_amd/build.py`; there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
+    part = [vp, vp, i64, i32, dbl, i64, i32, vp, vp]
+    seeded = [vp, vp, i64, i32, dbl, i64, i32, vp, vp, vp]
+    for name, args in (("grem_partition", part), ("grem_partition_r32", part),
+                       ("grem_partition_seeded", seeded), ("grem_partition_seeded_r32", seeded)):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = args
+    lib.grem_partition_state.restype = ctypes.c_int
+    lib.grem_partition_state.argtypes = [vp, i32, vp, i64, i32, dbl, i64, i32, vp, vp, vp, vp, vp]
+    for name in ("grem_edge_cut", "grem_edge_cut_r32"):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = [vp, vp, i64, vp, vp, vp]
+    lib.grem_capacity.restype = i64
+    lib.grem_capacity.argtypes = [i64, i32, dbl]
+    lib.grem_workspace_bytes.restype = ctypes.c_size_t
+    lib.grem_workspace_bytes.argtypes = [i64, i32, i64]
+    lib.grem_set_workspace.restype = ctypes.c_int
+    lib.grem_set_workspace.argtypes = [vp, ctypes.c_size_t]
+    lib.grem_set_histogram_mode.restype = ctypes.c_int
+    lib.grem_set_histogram_mode.argtypes = [i32]
+    lib.grem_profile_enable.restype = ctypes.c_int
+    lib.grem_profile_enable.argtypes = [i32]
+    lib.grem_profile_reset.restype = ctypes.c_int
+    lib.grem_profile_reset.argtypes = []
+    lib.grem_profile_read.restype = ctypes.c_int
+    lib.grem_profile_read.argtypes = [i32, ctypes.POINTER(dbl), ctypes.POINTER(i64)]
+    lib.grem_status_string.restype = ctypes.c_char_p
+    lib.grem_status_string.argtypes = [ctypes.c_int]
+    lib.grem_kernel_name.restype = ctypes.c_char_p
+    lib.grem_kernel_name.argtypes = [i32]
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load().grem_status_string(code).decode()
+
+
+def kernel_name(kernel_class: int) -> str:
+    return load().grem_kernel_name(kernel_class).decode()
+
+
+def _dev(t: torch.Tensor, dtype, what: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what} must be a tensor on the GPU")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{what} must be contiguous {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+_dummy_colidx = {}
+
+
+def _colidx(colidx: torch.Tensor) -> int:
+    """colidx pointer; an edgeless graph gets a one-element stand-in so the pointer is not null."""
+    if colidx.numel() == 0:
+        key = str(colidx.device)
+        if key not in _dummy_colidx:
+            _dummy_colidx[key] = torch.zeros(1, dtype=torch.int32, device=colidx.device)
+        colidx = _dummy_colidx[key]
+    return _dev(colidx, torch.int32, "colidx")
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def _check(rc: int, what: str):
+    if rc != OK:
+        raise GremError(rc, what)
+
+
+def grem_capacity(n: int, k: int, balance_slack: float) -> int:
+    return int(load().grem_capacity(n, k, float(balance_slack)))
+
+
+def grem_workspace_bytes(n: int, k: int, chunk: int) -> int:
+    return int(load().grem_workspace_bytes(n, k, chunk))
+
+
+def grem_set_workspace(buf: Optional[torch.Tensor]):
+    """`buf`: a uint8 tensor on the GPU that the caller keeps alive, or None to remove it."""
+    if buf is None:
+        _check(load().grem_set_workspace(None, 0), "grem_set_workspace")
+    else:
+        _check(load().grem_set_workspace(_dev(buf, torch.uint8, "workspace"), buf.numel()),
+               "grem_set_workspace")
+
+
+def grem_set_histogram_mode(mode: int):
+    _check(load().grem_set_histogram_mode(mode), "grem_set_histogram_mode")
+
+
+def _rowptr_bits(rowptr: torch.Tensor) -> int:
+    if rowptr.dtype == torch.int64:
+        return 64
+    if rowptr.dtype == torch.int32:
+        return 32
+    raise TypeError("rowptr must be int32 or int64")
+
+
+def grem_partition_seeded(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, seed_labels,
+                          labels_out=None, stream=None) -> torch.Tensor:
+    lib = load()
+    bits = _rowptr_bits(rowptr)
+    if labels_out is None:
+        labels_out = torch.empty(n, dtype=torch.int32, device=colidx.device)
+    fn = lib.grem_partition_seeded if bits == 64 else lib.grem_partition_seeded_r32
+    rc = fn(_dev(rowptr, rowptr.dtype, "rowptr"), _colidx(colidx), n, k,
+            float(balance_slack), chunk, refine_passes,
+            None if seed_labels is None else _dev(seed_labels, torch.int32, "seed_labels"),
+            _dev(labels_out, torch.int32, "labels_out"), _stream(stream))
+    _check(rc, "grem_partition_seeded")
+    return labels_out
+
+
+def grem_partition(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, labels_out=None,
+                   stream=None) -> torch.Tensor:
+    lib = load()
+    bits = _rowptr_bits(rowptr)
+    if labels_out is None:
+        labels_out = torch.empty(n, dtype=torch.int32, device=colidx.device)
+    fn = lib.grem_partition if bits == 64 else lib.grem_partition_r32
+    rc = fn(_dev(rowptr, rowptr.dtype, "rowptr"), _colidx(colidx), n, k,
+            float(balance_slack), chunk, refine_passes, _dev(labels_out, torch.int32, "labels_out"),
+            _stream(stream))
+    _check(rc, "grem_partition")
+    return labels_out
+
+
+def grem_partition_state(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, seed_labels=None,
+                         want_sizes=True, want_estimates=True, stream=None):
+    """Returns (labels int32[n], sizes int64[k] or None, estimates uint32-as-int32 view [n,k] or
+    None)."""
+    lib = load()
+    bits = _rowptr_bits(rowptr)
+    dev = colidx.device
+    labels = torch.empty(n, dtype=torch.int32, device=dev)
+    sizes = torch.empty(k, dtype=torch.int64, device=dev) if want_sizes else None
+    est = torch.empty((n, k), dtype=torch.int32, device=dev) if want_estimates else None
+    rc = lib.grem_partition_state(
+        _dev(rowptr, rowptr.dtype, "rowptr"), bits, _colidx(colidx), n, k,
+        float(balance_slack), chunk, refine_passes,
+        None if seed_labels is None else _dev(seed_labels, torch.int32, "seed_labels"),
+        _dev(labels, torch.int32, "labels_out"),
+        None if sizes is None else _dev(sizes, torch.int64, "sizes_out"),
+        None if est is None else _dev(est, torch.int32, "estimates_out"), _stream(stream))
+    _check(rc, "grem_partition_state")
+    return labels, sizes, est
+
+
+def grem_edge_cut(rowptr, colidx, n, labels, stream=None) -> torch.Tensor:
+    """Device int64 tensor with one element: the number of cut CSR entries."""
+    lib = load()
+    bits = _rowptr_bits(rowptr)
+    out = torch.empty(1, dtype=torch.int64, device=colidx.device)
+    fn = lib.grem_edge_cut if bits == 64 else lib.grem_edge_cut_r32
+    rc = fn(_dev(rowptr, rowptr.dtype, "rowptr"), _colidx(colidx), n,
+            _dev(labels, torch.int32, "labels"), _dev(out, torch.int64, "cut_entries_out"),
+            _stream(stream))
+    _check(rc, "grem_edge_cut")
+    return out
+
+
+def grem_profile_enable(on: bool):
+    _check(load().grem_profile_enable(1 if on else 0), "grem_profile_enable")
+
+
+def grem_profile_reset():
+    _check(load().grem_profile_reset(), "grem_profile_reset")
+
+
+def grem_profile_read(kernel_class: int):
+    ms = ctypes.c_double(0.0)
+    cnt = ctypes.c_int64(0)
+    _check(load().grem_profile_read(kernel_class, ctypes.byref(ms), ctypes.byref(cnt)),
+           "grem_profile_read")
+    return ms.value, cnt.value

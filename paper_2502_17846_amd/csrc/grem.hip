@@ -1,0 +1,418 @@
+// Host side of the GREM library: argument checks, workspace carve-up, and the stream-ordered
+// sequence of launches for each chunk of each pass (Alg. 1's chunk loop).  See include/grem.h for
+// the contract of every entry point.
+#include "grem.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "grem_kernels.hip.h"
+
+namespace {
+
+using namespace grem;
+
+constexpr int kLdsHistBytes = 32 * 1024;   // LDS spent on one tile's histograms
+constexpr int kLdsMaxK = 128;              // above this the histograms live in E's rows
+
+struct Global {
+    std::mutex mu;
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    int hist_mode = GREM_HIST_AUTO;
+    bool prof = false;
+    struct Ev { int cls; hipEvent_t a, b; };
+    std::vector<Ev> events;
+    std::vector<hipEvent_t> pool;
+};
+Global g;
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct Layout {
+    size_t E, Lc, prop, S, cnt, room, ocnt, fillRank, fillSorted, fillC, misc, total;
+};
+
+Layout make_layout(int64_t n, int32_t k, int64_t chunk, bool external_E) {
+    Layout L{};
+    const int64_t cl = chunk < n ? chunk : n;
+    const size_t lab = k <= 255 ? 1 : 2;
+    const int64_t ntiles = (cl + kAdmitTile - 1) / kAdmitTile;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    L.E = take(external_E ? 0 : (size_t)n * (size_t)k * 4);
+    L.Lc = take((size_t)n * lab);
+    L.prop = take((size_t)cl * lab);
+    L.S = take((size_t)k * 8);
+    L.cnt = take((size_t)ntiles * (size_t)k * 4);
+    L.room = take((size_t)k * 8);
+    L.ocnt = take((size_t)ntiles * 4);
+    L.fillRank = take((size_t)k * 4);
+    L.fillSorted = take((size_t)k * 8);
+    L.fillC = take(((size_t)k + 1) * 8);
+    L.misc = take(8 * 8);
+    L.total = off;
+    return L;
+}
+
+bool args_ok(const void *rowptr, const int32_t *colidx, int64_t n, int32_t k, double slack,
+             int64_t chunk, int32_t R) {
+    if (!rowptr || !colidx) return false;
+    if (n < 1 || n > (int64_t)INT32_MAX) return false;
+    if (k < 1 || k > GREM_MAX_K) return false;
+    if (chunk < 1 || R < 0) return false;
+    if (!(slack >= 1.0) || std::isinf(slack)) return false;
+    return true;
+}
+
+// Launch bracket: optional event pair per launch, error check after it.
+struct Launcher {
+    hipStream_t stream;
+    int err = GREM_OK;
+    hipEvent_t get_event() {
+        if (!g.pool.empty()) { hipEvent_t e = g.pool.back(); g.pool.pop_back(); return e; }
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { err = GREM_ERR_HIP; return nullptr; }
+        return e;
+    }
+    template <typename F> void run(int cls, F &&f) {
+        if (err) return;
+        hipEvent_t a = nullptr, b = nullptr;
+        if (g.prof) {
+            a = get_event(); b = get_event();
+            if (err) return;
+            if (hipEventRecord(a, stream) != hipSuccess) { err = GREM_ERR_HIP; return; }
+        }
+        f();
+        if (hipGetLastError() != hipSuccess) { err = GREM_ERR_HIP; return; }
+        if (g.prof) {
+            if (hipEventRecord(b, stream) != hipSuccess) { err = GREM_ERR_HIP; return; }
+            g.events.push_back({cls, a, b});
+        }
+    }
+};
+
+template <typename RowT, typename LabelT>
+int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t k, double slack,
+                  int64_t chunk, int32_t R, const int32_t *seed, int32_t *labels_out,
+                  int64_t *sizes_out, uint32_t *estimates_out, hipStream_t stream) {
+    const long long P = grem_capacity(n, k, slack);
+    const int64_t cl = chunk < n ? chunk : n;
+    const bool external_E = estimates_out != nullptr;
+    const Layout lay = make_layout(n, k, chunk, external_E);
+
+    int hist_mode = g.hist_mode;
+    if (hist_mode == GREM_HIST_LDS && k > kLdsMaxK) return GREM_ERR_ARG;
+    const bool use_lds = hist_mode == GREM_HIST_LDS || (hist_mode == GREM_HIST_AUTO && k <= kLdsMaxK);
+
+    // workspace
+    char *ws = nullptr;
+    bool own_ws = false;
+    if (g.ws) {
+        if (g.ws_bytes < lay.total) return GREM_ERR_NOMEM;
+        ws = (char *)g.ws;
+    } else {
+        if (hipMallocAsync((void **)&ws, lay.total, stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return GREM_ERR_NOMEM;
+        }
+        own_ws = true;
+    }
+    auto release = [&]() { if (own_ws) (void)hipFreeAsync(ws, stream); };
+
+    uint32_t *E = external_E ? estimates_out : (uint32_t *)(ws + lay.E);
+    LabelT *Lc = (LabelT *)(ws + lay.Lc);
+    LabelT *prop = (LabelT *)(ws + lay.prop);
+    long long *S = (long long *)(ws + lay.S);
+    uint32_t *cnt = (uint32_t *)(ws + lay.cnt);
+    long long *room = (long long *)(ws + lay.room);
+    uint32_t *ocnt = (uint32_t *)(ws + lay.ocnt);
+    int32_t *fillRank = (int32_t *)(ws + lay.fillRank);
+    long long *fillSorted = (long long *)(ws + lay.fillSorted);
+    long long *fillC = (long long *)(ws + lay.fillC);
+    unsigned long long *misc = (unsigned long long *)(ws + lay.misc);
+
+    Launcher L{stream};
+
+    // ---- prepass + the one validation read-back
+    if (hipMemsetAsync(S, 0, (size_t)k * 8, stream) != hipSuccess ||
+        hipMemsetAsync(misc, 0, 8 * 8, stream) != hipSuccess) { release(); return GREM_ERR_HIP; }
+    {
+        int64_t blocks = (n + 255) / 256;
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        L.run(GREM_KERNEL_PREPASS, [&] {
+            hipLaunchKernelGGL((k_prepass<RowT, LabelT>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               rowptr, seed, n, (int)k, Lc, (unsigned long long *)S, misc);
+        });
+        L.run(GREM_KERNEL_PREPASS, [&] {
+            hipLaunchKernelGGL(k_check_seed_sizes, dim3((k + 255) / 256), dim3(256), 0, stream, S, (int)k,
+                               P, misc);
+        });
+    }
+    if (L.err) { release(); return L.err; }
+    unsigned long long h_misc[3] = {0, 0, 0};
+    if (hipMemcpyAsync(h_misc, misc, sizeof(h_misc), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) { release(); return GREM_ERR_HIP; }
+    if (h_misc[1] != 0 || h_misc[2] != 0) { release(); return GREM_ERR_SEED; }
+    const unsigned long long maxdeg = h_misc[0];
+    if (R >= 32 || (maxdeg << R) >= (1ull << 32)) { release(); return GREM_ERR_RANGE; }
+
+    // tile shape of the score kernel
+    int tv = kGlobalTile;
+    if (use_lds) {
+        tv = 256;
+        while (tv > 1 && (size_t)tv * k * 4 > (size_t)kLdsHistBytes) tv >>= 1;
+    }
+    if (maxdeg * (unsigned long long)tv >= (1ull << 31)) { release(); return GREM_ERR_RANGE; }
+    const size_t score_lds = use_lds ? ((size_t)tv * k + tv + 1 + k) * 4 : ((size_t)tv + 1 + k) * 4;
+    const size_t count_lds = (size_t)k * 4;
+    const size_t apply_lds = ((size_t)k + (size_t)(kAdmitThreads / 64) * k + k) * 4;
+    const size_t fill_lds = (size_t)k * 4;
+
+    if (apply_lds > 64 * 1024 &&
+        hipFuncSetAttribute((const void *)k_apply<LabelT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)apply_lds) != hipSuccess) { release(); return GREM_ERR_HIP; }
+
+    const int64_t nchunks = (n + chunk - 1) / chunk;
+    for (int pass = 0; pass <= R && !L.err; ++pass) {
+        for (int64_t c = 0; c < nchunks && !L.err; ++c) {
+            const int64_t lo = c * chunk;
+            const int64_t hi = (lo + chunk < n) ? lo + chunk : n;
+            const int64_t len = hi - lo;
+            const int64_t gather_limit = (pass == 0 && !seed) ? lo : n;
+            const unsigned score_blocks = (unsigned)((len + tv - 1) / tv);
+            const unsigned admit_blocks = (unsigned)((len + kAdmitTile - 1) / kAdmitTile);
+            if (use_lds) {
+                L.run(GREM_KERNEL_SCORE, [&] {
+                    hipLaunchKernelGGL((k_score_lds<RowT, LabelT>), dim3(score_blocks),
+                                       dim3(kScoreThreads), score_lds, stream, rowptr, colidx, Lc, S, E,
+                                       prop, lo, hi, (int)k, tv, pass, P, gather_limit);
+                });
+            } else {
+                L.run(GREM_KERNEL_SCORE, [&] {
+                    hipLaunchKernelGGL((k_score_global<RowT, LabelT>), dim3(score_blocks),
+                                       dim3(kScoreThreads), score_lds, stream, rowptr, colidx, Lc, S, E,
+                                       prop, lo, hi, (int)k, pass, P, gather_limit);
+                });
+            }
+            L.run(GREM_KERNEL_COUNT, [&] {
+                hipLaunchKernelGGL((k_count<LabelT>), dim3(admit_blocks), dim3(kAdmitThreads), count_lds,
+                                   stream, Lc, prop, lo, hi, (int)k, cnt);
+            });
+            L.run(GREM_KERNEL_SCAN, [&] {
+                hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), 0, stream, cnt, (int)admit_blocks,
+                                   (int)k, S, P, room);
+            });
+            L.run(GREM_KERNEL_APPLY, [&] {
+                hipLaunchKernelGGL((k_apply<LabelT>), dim3(admit_blocks), dim3(kAdmitThreads), apply_lds,
+                                   stream, Lc, prop, lo, hi, (int)k, cnt, room, (unsigned long long *)S,
+                                   ocnt, pass);
+            });
+            if (pass == 0) {
+                L.run(GREM_KERNEL_SPILL_SCAN, [&] {
+                    hipLaunchKernelGGL(k_spill_scan, dim3(1), dim3(kScanThreads), 0, stream, ocnt,
+                                       (int)admit_blocks, (int)k, S, fillRank, fillSorted, fillC, misc);
+                });
+                L.run(GREM_KERNEL_SPILL_FILL, [&] {
+                    hipLaunchKernelGGL((k_spill_fill<LabelT>), dim3(admit_blocks), dim3(kAdmitThreads),
+                                       fill_lds, stream, Lc, lo, hi, (int)k, ocnt, fillRank, fillC,
+                                       (unsigned long long *)S, misc);
+                });
+            }
+        }
+    }
+    {
+        int64_t blocks = (n + 255) / 256;
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        L.run(GREM_KERNEL_EXPAND, [&] {
+            hipLaunchKernelGGL((k_expand<LabelT>), dim3((unsigned)blocks), dim3(256), 0, stream, Lc, n,
+                               labels_out);
+        });
+        if (sizes_out)
+            L.run(GREM_KERNEL_EXPAND, [&] {
+                hipLaunchKernelGGL(k_copy_sizes, dim3((k + 255) / 256), dim3(256), 0, stream, S, (int)k,
+                                   sizes_out);
+            });
+    }
+    (void)cl;
+    release();
+    return L.err;
+}
+
+template <typename RowT>
+int dispatch_labels(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t k, double slack,
+                    int64_t chunk, int32_t R, const int32_t *seed, int32_t *labels_out,
+                    int64_t *sizes_out, uint32_t *estimates_out, void *stream) {
+    if (!args_ok(rowptr, colidx, n, k, slack, chunk, R) || !labels_out) return GREM_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g.mu);
+    hipStream_t s = (hipStream_t)stream;
+    if (k <= 255)
+        return run_partition<RowT, uint8_t>(rowptr, colidx, n, k, slack, chunk, R, seed, labels_out,
+                                            sizes_out, estimates_out, s);
+    return run_partition<RowT, uint16_t>(rowptr, colidx, n, k, slack, chunk, R, seed, labels_out,
+                                         sizes_out, estimates_out, s);
+}
+
+template <typename RowT>
+int run_edge_cut(const RowT *rowptr, const int32_t *colidx, int64_t n, const int32_t *labels,
+                 int64_t *out, void *stream) {
+    if (!rowptr || !colidx || !labels || !out || n < 1 || n > (int64_t)INT32_MAX) return GREM_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_zero_u64, dim3(1), dim3(64), 0, s, (unsigned long long *)out, 1);
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    hipLaunchKernelGGL((k_edge_cut<RowT>), dim3(blocks), dim3(256), 0, s, rowptr, colidx, n, labels,
+                       (unsigned long long *)out);
+    return hipGetLastError() == hipSuccess ? GREM_OK : GREM_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t grem_capacity(int64_t n, int32_t k, double balance_slack) {
+    if (n < 1 || k < 1 || !(balance_slack >= 1.0)) return -1;
+    const int64_t even = (n + k - 1) / k;
+    const double scaled = (double)n * balance_slack;
+    const double per = scaled / (double)k;
+    const int64_t widened = (int64_t)std::ceil(per);
+    return even > widened ? even : widened;
+}
+
+size_t grem_workspace_bytes(int64_t n, int32_t k, int64_t chunk) {
+    if (n < 1 || k < 1 || k > GREM_MAX_K || chunk < 1) return 0;
+    return make_layout(n, k, chunk, false).total;
+}
+
+int grem_set_workspace(void *dev_ptr, size_t bytes) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    if ((dev_ptr == nullptr) != (bytes == 0)) return GREM_ERR_ARG;
+    if (((uintptr_t)dev_ptr & 255u) != 0) return GREM_ERR_ARG;
+    g.ws = dev_ptr;
+    g.ws_bytes = bytes;
+    return GREM_OK;
+}
+
+int grem_set_histogram_mode(int32_t mode) {
+    if (mode != GREM_HIST_AUTO && mode != GREM_HIST_LDS && mode != GREM_HIST_GLOBAL) return GREM_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.hist_mode = mode;
+    return GREM_OK;
+}
+
+int grem_partition(const int64_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
+                   double balance_slack, int64_t chunk, int32_t refine_passes, int32_t *labels_out,
+                   void *stream) {
+    return dispatch_labels<int64_t>(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, nullptr,
+                                    labels_out, nullptr, nullptr, stream);
+}
+
+int grem_partition_seeded(const int64_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
+                          double balance_slack, int64_t chunk, int32_t refine_passes,
+                          const int32_t *seed_labels, int32_t *labels_out, void *stream) {
+    return dispatch_labels<int64_t>(rowptr, colidx, n, k, balance_slack, chunk, refine_passes,
+                                    seed_labels, labels_out, nullptr, nullptr, stream);
+}
+
+int grem_partition_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
+                       double balance_slack, int64_t chunk, int32_t refine_passes, int32_t *labels_out,
+                       void *stream) {
+    return dispatch_labels<int32_t>(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, nullptr,
+                                    labels_out, nullptr, nullptr, stream);
+}
+
+int grem_partition_seeded_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
+                              double balance_slack, int64_t chunk, int32_t refine_passes,
+                              const int32_t *seed_labels, int32_t *labels_out, void *stream) {
+    return dispatch_labels<int32_t>(rowptr, colidx, n, k, balance_slack, chunk, refine_passes,
+                                    seed_labels, labels_out, nullptr, nullptr, stream);
+}
+
+int grem_partition_state(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
+                         int32_t k, double balance_slack, int64_t chunk, int32_t refine_passes,
+                         const int32_t *seed_labels, int32_t *labels_out, int64_t *sizes_out,
+                         uint32_t *estimates_out, void *stream) {
+    if (rowptr_bits == 64)
+        return dispatch_labels<int64_t>((const int64_t *)rowptr, colidx, n, k, balance_slack, chunk,
+                                        refine_passes, seed_labels, labels_out, sizes_out,
+                                        estimates_out, stream);
+    if (rowptr_bits == 32)
+        return dispatch_labels<int32_t>((const int32_t *)rowptr, colidx, n, k, balance_slack, chunk,
+                                        refine_passes, seed_labels, labels_out, sizes_out,
+                                        estimates_out, stream);
+    return GREM_ERR_ARG;
+}
+
+int grem_edge_cut(const int64_t *rowptr, const int32_t *colidx, int64_t n, const int32_t *labels,
+                  int64_t *cut_entries_out, void *stream) {
+    return run_edge_cut<int64_t>(rowptr, colidx, n, labels, cut_entries_out, stream);
+}
+
+int grem_edge_cut_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n, const int32_t *labels,
+                      int64_t *cut_entries_out, void *stream) {
+    return run_edge_cut<int32_t>(rowptr, colidx, n, labels, cut_entries_out, stream);
+}
+
+int grem_profile_enable(int32_t on) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.prof = on != 0;
+    return GREM_OK;
+}
+
+int grem_profile_reset(void) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    for (auto &e : g.events) { g.pool.push_back(e.a); g.pool.push_back(e.b); }
+    g.events.clear();
+    return GREM_OK;
+}
+
+int grem_profile_read(int32_t kernel_class, double *total_ms, int64_t *launches) {
+    if (kernel_class < 0 || kernel_class >= GREM_KERNEL_CLASSES || !total_ms || !launches)
+        return GREM_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g.mu);
+    double tot = 0.0;
+    int64_t cnt = 0;
+    for (auto &e : g.events) {
+        if (e.cls != kernel_class) continue;
+        if (hipEventSynchronize(e.b) != hipSuccess) return GREM_ERR_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, e.a, e.b) != hipSuccess) return GREM_ERR_HIP;
+        tot += ms;
+        cnt += 1;
+    }
+    *total_ms = tot;
+    *launches = cnt;
+    return GREM_OK;
+}
+
+const char *grem_status_string(int code) {
+    switch (code) {
+        case GREM_OK: return "ok";
+        case GREM_ERR_ARG: return "bad argument";
+        case GREM_ERR_NOMEM: return "workspace allocation failed or workspace too small";
+        case GREM_ERR_HIP: return "HIP runtime error";
+        case GREM_ERR_RANGE: return "max degree * 2^refine_passes does not fit the estimates";
+        case GREM_ERR_SEED: return "invalid seed labels";
+        default: return "unknown status";
+    }
+}
+
+const char *grem_kernel_name(int32_t kernel_class) {
+    switch (kernel_class) {
+        case GREM_KERNEL_PREPASS: return "prepass";
+        case GREM_KERNEL_SCORE: return "score";
+        case GREM_KERNEL_COUNT: return "count";
+        case GREM_KERNEL_SCAN: return "scan";
+        case GREM_KERNEL_APPLY: return "apply";
+        case GREM_KERNEL_SPILL_SCAN: return "spill_scan";
+        case GREM_KERNEL_SPILL_FILL: return "spill_fill";
+        case GREM_KERNEL_EXPAND: return "expand";
+        default: return "?";
+    }
+}
+
+}  // extern "C"

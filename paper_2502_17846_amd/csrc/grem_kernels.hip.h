@@ -1,0 +1,633 @@
+// Device kernels of the GREM partitioner for gfx950 (wave64).  Included once, by grem.hip.
+//
+// One chunk of rows is processed by a short sequence of launches on the caller's stream:
+//   score  : stream the chunk's CSR rows, gather neighbour labels, histogram them per vertex,
+//            blend into E, and pick each vertex's proposal               (Alg. 2 cnt_nbrs, assign;
+//                                                                          Alg. 1 blend)
+//   count  : per tile of vertices, how many movers propose each partition
+//   scan   : exclusive prefix of those counts over the tiles (id order), room = P - S
+//   apply  : admit movers by rank, relabel, update sizes                 (Alg. 2 fix_sizes)
+//   spill  : (first pass only) place rejected new vertices one by one in the smallest partition
+//            -- done in closed form by levels                            (Alg. 2 arg_min fallback)
+// Every quantity is an integer and every cross-thread combination is an integer sum or a rank in
+// vertex-id order, so the result does not depend on scheduling.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace grem {
+
+constexpr int kScoreThreads = 256;
+constexpr int kAdmitThreads = 256;
+constexpr int kAdmitTile = 1024;       // vertices per tile in count/apply/spill
+constexpr int kScanThreads = 1024;
+constexpr int kGlobalTile = 64;        // vertices per tile when histograms live in E's rows
+constexpr int GREM_MAX_K_DEVICE = 4096;
+
+template <typename LabelT> struct LabelTraits;
+template <> struct LabelTraits<uint8_t> { static constexpr uint32_t kUnassigned = 0xFFu; };
+template <> struct LabelTraits<uint16_t> { static constexpr uint32_t kUnassigned = 0xFFFFu; };
+
+__device__ __forceinline__ int lane_id() { return (int)__lane_id(); }
+__device__ __forceinline__ unsigned long long lanes_below(int lane) {
+    return (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+}
+
+// Largest r in [0, tv) with rowrel[r] <= i; tv is a power of two.  Picks the row that owns entry
+// i and skips empty rows (equal offsets resolve to the last, the non-empty one).
+__device__ __forceinline__ int owning_row(const uint32_t *rowrel, uint32_t i, int tv) {
+    int r = 0;
+    for (int step = tv >> 1; step >= 1; step >>= 1)
+        if (rowrel[r + step] <= i) r += step;
+    return r;
+}
+
+// ------------------------------------------------------------------------------------------------
+// prepass: compact labels from the seed, seed sizes, maximum degree, seed validity
+// misc[0] = max degree, misc[1] = number of invalid seed labels
+// ------------------------------------------------------------------------------------------------
+template <typename RowT, typename LabelT>
+__global__ __launch_bounds__(256) void k_prepass(const RowT *__restrict__ rowptr,
+                                                 const int32_t *__restrict__ seed, int64_t n, int k,
+                                                 LabelT *__restrict__ Lc,
+                                                 unsigned long long *__restrict__ S,
+                                                 unsigned long long *__restrict__ misc) {
+    __shared__ unsigned long long s_maxdeg;
+    __shared__ unsigned int s_bad;
+    if (threadIdx.x == 0) { s_maxdeg = 0; s_bad = 0; }
+    __syncthreads();
+    unsigned long long mymax = 0;
+    unsigned int bad = 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
+        unsigned long long d = (unsigned long long)(rowptr[v + 1] - rowptr[v]);
+        if (d > mymax) mymax = d;
+        uint32_t lab = LabelTraits<LabelT>::kUnassigned;
+        if (seed) {
+            int32_t s = seed[v];
+            if (s >= 0 && s < k) {
+                lab = (uint32_t)s;
+                atomicAdd(&S[s], 1ull);
+            } else if (s != -1) {
+                bad += 1;
+            }
+        }
+        Lc[v] = (LabelT)lab;
+    }
+    atomicMax(&s_maxdeg, mymax);
+    if (bad) atomicAdd(&s_bad, bad);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        atomicMax(&misc[0], s_maxdeg);
+        if (s_bad) atomicAdd(&misc[1], (unsigned long long)s_bad);
+    }
+}
+
+// misc[2] = number of seeded partitions above capacity
+__global__ void k_check_seed_sizes(const long long *__restrict__ S, int k, long long P,
+                                   unsigned long long *__restrict__ misc) {
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < k && S[j] > P) atomicAdd(&misc[2], 1ull);
+}
+
+// ------------------------------------------------------------------------------------------------
+// score, histograms in LDS.  One workgroup owns `tv` consecutive rows (tv a power of two) and
+// walks their entries edge-parallel: consecutive lanes read consecutive colidx entries (coalesced),
+// gather the neighbour's label, find the owning row in the tile's row offsets (LDS) and add 1 to
+// that row's counter of the label (LDS atomic).  Then the tile's slice of E, which is contiguous,
+// is blended in one coalesced sweep, and one thread per vertex picks the proposal.
+//   gather_limit: neighbours with id >= gather_limit are known to be unassigned (first pass of an
+//   unseeded run: everything from the chunk's first row on), so their label is not fetched.
+// ------------------------------------------------------------------------------------------------
+template <typename RowT, typename LabelT>
+__global__ __launch_bounds__(kScoreThreads) void k_score_lds(
+    const RowT *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const LabelT *__restrict__ Lc, const long long *__restrict__ S, uint32_t *__restrict__ E,
+    LabelT *__restrict__ prop, int64_t chunk_lo, int64_t chunk_hi, int k, int tv, int pass,
+    long long P, int64_t gather_limit) {
+    extern __shared__ uint32_t smem[];
+    uint32_t *hist = smem;                  // tv * k
+    uint32_t *rowrel = hist + (size_t)tv * k;   // tv + 1
+    uint32_t *room = rowrel + tv + 1;       // k
+    constexpr uint32_t UN = LabelTraits<LabelT>::kUnassigned;
+    const int tid = threadIdx.x;
+    const int64_t v0 = chunk_lo + (int64_t)blockIdx.x * tv;
+    const int64_t left = chunk_hi - v0;
+    const int nv = left < tv ? (int)left : tv;
+    const int64_t e0 = (int64_t)rowptr[v0];
+
+    for (int i = tid; i <= tv; i += kScoreThreads) {
+        int ii = i < nv ? i : nv;
+        rowrel[i] = (uint32_t)((int64_t)rowptr[v0 + ii] - e0);
+    }
+    for (int i = tid; i < tv * k; i += kScoreThreads) hist[i] = 0;
+    for (int j = tid; j < k; j += kScoreThreads) room[j] = (uint32_t)(P - S[j]);
+    __syncthreads();
+
+    const uint32_t ne = rowrel[tv];
+    const int32_t *cbase = colidx + e0;
+    constexpr int U = 4;
+    for (uint32_t base = tid; base < ne; base += kScoreThreads * U) {
+        int32_t col[U];
+        uint32_t lab[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint32_t i = base + u * kScoreThreads;
+            col[u] = (i < ne) ? __builtin_nontemporal_load(cbase + i) : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            lab[u] = UN;
+            if (col[u] >= 0 && (int64_t)col[u] < gather_limit) lab[u] = (uint32_t)Lc[col[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (lab[u] != UN) {
+                int r = owning_row(rowrel, base + u * kScoreThreads, tv);
+                atomicAdd(&hist[r * k + (int)lab[u]], 1u);
+            }
+        }
+    }
+    __syncthreads();
+
+    // blend: E = h (first pass) or E += h * 2^(pass-1); the blended row stays in LDS
+    {
+        uint32_t *Etile = E + (size_t)v0 * (size_t)k;
+        const int total = nv * k;
+        if (pass == 0) {
+            for (int i = tid; i < total; i += kScoreThreads)
+                __builtin_nontemporal_store(hist[i], Etile + i);
+        } else {
+            const int sh = pass - 1;
+            for (int i = tid; i < total; i += kScoreThreads) {
+                uint32_t e = __builtin_nontemporal_load(Etile + i) + (hist[i] << sh);
+                hist[i] = e;
+                __builtin_nontemporal_store(e, Etile + i);
+            }
+        }
+    }
+    __syncthreads();
+
+    // proposal: best partition with room by (E desc, room desc, id asc)
+    for (int t = tid; t < nv; t += kScoreThreads) {
+        const int64_t v = v0 + t;
+        const uint32_t old = (uint32_t)Lc[v];
+        uint32_t best = old;
+        if (!(pass == 0 && old != UN)) {
+            unsigned long long bestkey = 0;
+            int bestj = 0x7fffffff;
+            int jj = t % k;
+            const uint32_t *hrow = hist + t * k;
+            for (int j = 0; j < k; ++j) {
+                uint32_t rm = room[jj] + ((uint32_t)jj == old ? 1u : 0u);
+                unsigned long long key = rm ? (((unsigned long long)hrow[jj] << 32) | rm) : 0ull;
+                if (key > bestkey || (key == bestkey && key != 0 && jj < bestj)) {
+                    bestkey = key;
+                    bestj = jj;
+                }
+                jj += 1;
+                if (jj == k) jj = 0;
+            }
+            best = (uint32_t)bestj;
+        }
+        prop[v - chunk_lo] = (LabelT)best;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// score, histograms in global memory (large k): counts are added straight into E's rows with
+// integer atomics of 2^(pass-1) (1 in the first pass, after zeroing the rows); proposals are
+// picked by one wavefront per vertex with a shuffle arg-max.
+// ------------------------------------------------------------------------------------------------
+template <typename RowT, typename LabelT>
+__global__ __launch_bounds__(kScoreThreads) void k_score_global(
+    const RowT *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const LabelT *__restrict__ Lc, const long long *__restrict__ S, uint32_t *__restrict__ E,
+    LabelT *__restrict__ prop, int64_t chunk_lo, int64_t chunk_hi, int k, int pass, long long P,
+    int64_t gather_limit) {
+    extern __shared__ uint32_t smem[];
+    constexpr int tv = kGlobalTile;
+    uint32_t *rowrel = smem;            // tv + 1
+    uint32_t *room = rowrel + tv + 1;   // k
+    constexpr uint32_t UN = LabelTraits<LabelT>::kUnassigned;
+    const int tid = threadIdx.x;
+    const int64_t v0 = chunk_lo + (int64_t)blockIdx.x * tv;
+    const int64_t left = chunk_hi - v0;
+    const int nv = left < tv ? (int)left : tv;
+    const int64_t e0 = (int64_t)rowptr[v0];
+    uint32_t *Etile = E + (size_t)v0 * (size_t)k;
+
+    for (int i = tid; i <= tv; i += kScoreThreads) {
+        int ii = i < nv ? i : nv;
+        rowrel[i] = (uint32_t)((int64_t)rowptr[v0 + ii] - e0);
+    }
+    for (int j = tid; j < k; j += kScoreThreads) room[j] = (uint32_t)(P - S[j]);
+    if (pass == 0) {
+        const int total = nv * k;
+        for (int i = tid; i < total; i += kScoreThreads) Etile[i] = 0u;
+        __threadfence();
+    }
+    __syncthreads();
+
+    const uint32_t ne = rowrel[tv];
+    const int32_t *cbase = colidx + e0;
+    const uint32_t inc = pass == 0 ? 1u : (1u << (pass - 1));
+    constexpr int U = 4;
+    for (uint32_t base = tid; base < ne; base += kScoreThreads * U) {
+        int32_t col[U];
+        uint32_t lab[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint32_t i = base + u * kScoreThreads;
+            col[u] = (i < ne) ? __builtin_nontemporal_load(cbase + i) : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            lab[u] = UN;
+            if (col[u] >= 0 && (int64_t)col[u] < gather_limit) lab[u] = (uint32_t)Lc[col[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (lab[u] != UN) {
+                int r = owning_row(rowrel, base + u * kScoreThreads, tv);
+                atomicAdd(&Etile[(size_t)r * k + lab[u]], inc);
+            }
+        }
+    }
+    __threadfence();
+    __syncthreads();
+
+    const int lane = lane_id();
+    const int wave = tid >> 6;
+    constexpr int nwaves = kScoreThreads / 64;
+    for (int t = wave; t < nv; t += nwaves) {
+        const int64_t v = v0 + t;
+        const uint32_t old = (uint32_t)Lc[v];
+        uint32_t best = old;
+        if (!(pass == 0 && old != UN)) {
+            unsigned long long bestkey = 0;
+            int bestj = 0x7fffffff;
+            const uint32_t *erow = Etile + (size_t)t * k;
+            for (int j = lane; j < k; j += 64) {
+                uint32_t e = __hip_atomic_load(erow + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                uint32_t rm = room[j] + ((uint32_t)j == old ? 1u : 0u);
+                unsigned long long key = rm ? (((unsigned long long)e << 32) | rm) : 0ull;
+                if (key > bestkey) { bestkey = key; bestj = j; }   // j ascends: first maximum kept
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                unsigned long long okey = __shfl_xor(bestkey, off);
+                int oj = __shfl_xor(bestj, off);
+                if (okey > bestkey || (okey == bestkey && oj < bestj)) { bestkey = okey; bestj = oj; }
+            }
+            best = (uint32_t)bestj;
+        }
+        if (lane == 0) prop[v - chunk_lo] = (LabelT)best;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// count: cnt[tile][t] = movers of the tile proposing t
+// ------------------------------------------------------------------------------------------------
+template <typename LabelT>
+__global__ __launch_bounds__(kAdmitThreads) void k_count(const LabelT *__restrict__ Lc,
+                                                         const LabelT *__restrict__ prop,
+                                                         int64_t chunk_lo, int64_t chunk_hi, int k,
+                                                         uint32_t *__restrict__ cnt) {
+    extern __shared__ uint32_t smem[];
+    uint32_t *c = smem;   // k
+    const int tid = threadIdx.x;
+    for (int j = tid; j < k; j += kAdmitThreads) c[j] = 0;
+    __syncthreads();
+    const int64_t lo = chunk_lo + (int64_t)blockIdx.x * kAdmitTile;
+    for (int i = tid; i < kAdmitTile; i += kAdmitThreads) {
+        int64_t v = lo + i;
+        if (v < chunk_hi) {
+            uint32_t t = prop[v - chunk_lo];
+            if (t != (uint32_t)Lc[v]) atomicAdd(&c[t], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t *out = cnt + (size_t)blockIdx.x * k;
+    for (int j = tid; j < k; j += kAdmitThreads) out[j] = c[j];
+}
+
+// ------------------------------------------------------------------------------------------------
+// scan: per partition, exclusive prefix of cnt over the tiles (in place); room[j] = P - S[j]
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kScanThreads) void k_scan(uint32_t *__restrict__ cnt, int ntiles, int k,
+                                                       const long long *__restrict__ S, long long P,
+                                                       long long *__restrict__ room) {
+    __shared__ uint32_t part[kScanThreads];
+    const int tid = threadIdx.x;
+    for (int j = tid; j < k; j += kScanThreads) room[j] = P - S[j];
+    for (int c0 = 0; c0 < k; c0 += kScanThreads) {
+        const int kc = (k - c0) < kScanThreads ? (k - c0) : kScanThreads;
+        const int nseg = kScanThreads / kc;
+        const int col = tid % kc, seg = tid / kc;
+        const bool active = seg < nseg;
+        const int tps = (ntiles + nseg - 1) / nseg;
+        const int tlo = seg * tps;
+        const int thi = (tlo + tps < ntiles) ? tlo + tps : ntiles;
+        uint32_t sum = 0;
+        if (active)
+            for (int t = tlo; t < thi; ++t) sum += cnt[(size_t)t * k + c0 + col];
+        part[tid] = active ? sum : 0u;
+        __syncthreads();
+        if (active) {
+            uint32_t base = 0;
+            for (int s = 0; s < seg; ++s) base += part[s * kc + col];
+            for (int t = tlo; t < thi; ++t) {
+                size_t idx = (size_t)t * k + c0 + col;
+                uint32_t c = cnt[idx];
+                cnt[idx] = base;
+                base += c;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Rank of each lane among the lanes of its wavefront that are `active` and hold the same `t`,
+// in lane order; *same_total = how many such lanes; *leader = is the first of them.
+__device__ __forceinline__ int rank_among_equal(bool active, uint32_t t, int lane, int *same_total,
+                                                bool *leader) {
+    int rank = 0;
+    *same_total = 0;
+    *leader = false;
+    unsigned long long remaining = __ballot(active);
+    while (remaining) {
+        int first = __ffsll((long long)remaining) - 1;
+        uint32_t lt = (uint32_t)__shfl((int)t, first);
+        unsigned long long m = __ballot(active && t == lt);
+        if (active && t == lt) {
+            rank = __popcll(m & lanes_below(lane));
+            *same_total = __popcll(m);
+            *leader = (lane == first);
+        }
+        remaining &= ~m;
+    }
+    return rank;
+}
+
+// ------------------------------------------------------------------------------------------------
+// apply: admit movers whose rank among the chunk's earlier movers to the same partition is below
+// the room; relabel; size deltas; in the first pass count the vertices left unassigned per tile.
+// ------------------------------------------------------------------------------------------------
+template <typename LabelT>
+__global__ __launch_bounds__(kAdmitThreads) void k_apply(
+    LabelT *__restrict__ Lc, const LabelT *__restrict__ prop, int64_t chunk_lo, int64_t chunk_hi,
+    int k, const uint32_t *__restrict__ base, const long long *__restrict__ room,
+    unsigned long long *__restrict__ S, uint32_t *__restrict__ ocnt, int pass) {
+    extern __shared__ uint32_t smem[];
+    constexpr int nwaves = kAdmitThreads / 64;
+    uint32_t *run = smem;                 // k       movers seen so far in this tile
+    uint32_t *wcnt = run + k;             // nwaves*k movers of this round per wave
+    int32_t *dS = (int32_t *)(wcnt + nwaves * k);   // k size deltas
+    __shared__ uint32_t s_unassigned;
+    constexpr uint32_t UN = LabelTraits<LabelT>::kUnassigned;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    for (int j = tid; j < k; j += kAdmitThreads) { run[j] = 0; dS[j] = 0; }
+    for (int j = tid; j < nwaves * k; j += kAdmitThreads) wcnt[j] = 0;
+    if (tid == 0) s_unassigned = 0;
+    __syncthreads();
+    const int64_t lo = chunk_lo + (int64_t)blockIdx.x * kAdmitTile;
+    const uint32_t *tbase = base + (size_t)blockIdx.x * k;
+    uint32_t my_unassigned = 0;
+    for (int round = 0; round < kAdmitTile / kAdmitThreads; ++round) {
+        const int64_t v = lo + round * kAdmitThreads + tid;
+        const bool inside = v < chunk_hi;
+        uint32_t t = 0, old = 0;
+        if (inside) { t = prop[v - chunk_lo]; old = (uint32_t)Lc[v]; }
+        const bool mover = inside && t != old;
+        int same_total; bool leader;
+        const int wrank = rank_among_equal(mover, t, lane, &same_total, &leader);
+        if (leader) wcnt[wave * k + t] = (uint32_t)same_total;
+        __syncthreads();
+        bool admitted = false;
+        if (mover) {
+            long long rank = (long long)tbase[t] + run[t] + wrank;
+            for (int w = 0; w < wave; ++w) rank += wcnt[w * k + t];
+            admitted = rank < room[t];
+        }
+        __syncthreads();
+        if (leader) { atomicAdd(&run[t], (uint32_t)same_total); wcnt[wave * k + t] = 0; }
+        if (admitted) {
+            Lc[v] = (LabelT)t;
+            atomicAdd(&dS[t], 1);
+            if (old != UN) atomicAdd(&dS[old], -1);
+        } else if (inside && old == UN) {
+            my_unassigned += 1;    // rejected new vertex (a new vertex is always a mover)
+        }
+        __syncthreads();
+    }
+    if (pass == 0) {
+        if (my_unassigned) atomicAdd(&s_unassigned, my_unassigned);
+    }
+    __syncthreads();
+    for (int j = tid; j < k; j += kAdmitThreads) {
+        int32_t d = dS[j];
+        if (d != 0) atomicAdd(&S[j], (unsigned long long)(long long)d);
+    }
+    if (pass == 0 && tid == 0) ocnt[blockIdx.x] = s_unassigned;
+}
+
+// ------------------------------------------------------------------------------------------------
+// spill scan (first pass): exclusive prefix of the per-tile unassigned counts, and the level
+// tables of "add one to the smallest partition, lowest id on ties, repeatedly":
+//   order the partitions by (S, id): s[0] <= s[1] <= ...;  C[a] = sum_{q<a} (s[a] - s[q]) is the
+//   number of placements made before the a+1 smallest partitions are level; while the a smallest
+//   are level, placements cycle through them in ascending id.
+// misc[3] = total to place.  fillRank[j] = position of j in that order, fillC[a] for a = 0..k
+// (C[0] = 0, C[k] = infinity).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kScanThreads) void k_spill_scan(uint32_t *__restrict__ ocnt, int ntiles,
+                                                             int k, const long long *__restrict__ S,
+                                                             int32_t *__restrict__ fillRank,
+                                                             long long *__restrict__ fillSorted,
+                                                             long long *__restrict__ fillC,
+                                                             unsigned long long *__restrict__ misc) {
+    __shared__ long long part[kScanThreads];
+    __shared__ long long Sl[GREM_MAX_K_DEVICE];
+    __shared__ long long s_total;
+    const int tid = threadIdx.x;
+    {   // prefix over tiles
+        const int tps = (ntiles + kScanThreads - 1) / kScanThreads;
+        const int tlo = tid * tps;
+        const int thi = (tlo + tps < ntiles) ? tlo + tps : ntiles;
+        long long sum = 0;
+        for (int t = tlo; t < thi; ++t) sum += ocnt[t];
+        part[tid] = sum;
+        __syncthreads();
+        long long b = 0;
+        for (int s = 0; s < tid; ++s) b += part[s];
+        if (tid == kScanThreads - 1) s_total = b + sum;
+        for (int t = tlo; t < thi; ++t) {
+            uint32_t c = ocnt[t];
+            ocnt[t] = (uint32_t)b;
+            b += c;
+        }
+        __syncthreads();
+    }
+    const long long total = s_total;
+    if (tid == 0) misc[3] = (unsigned long long)total;
+    if (total == 0) return;
+    for (int j = tid; j < k; j += kScanThreads) Sl[j] = S[j];
+    __syncthreads();
+    for (int j = tid; j < k; j += kScanThreads) {
+        const long long sj = Sl[j];
+        int rank = 0;
+        for (int i = 0; i < k; ++i) {
+            long long si = Sl[i];
+            rank += (si < sj || (si == sj && i < j)) ? 1 : 0;
+        }
+        fillRank[j] = rank;
+        fillSorted[rank] = sj;
+    }
+    __threadfence();
+    __syncthreads();
+    {   // prefix sums of the sorted sizes -> C
+        const int per = (k + kScanThreads - 1) / kScanThreads;
+        const int qlo = tid * per;
+        const int qhi = (qlo + per < k) ? qlo + per : k;
+        long long sum = 0;
+        for (int q = qlo; q < qhi; ++q)
+            sum += __hip_atomic_load(fillSorted + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        part[tid] = sum;
+        __syncthreads();
+        long long ps = 0;
+        for (int s = 0; s < tid; ++s) ps += part[s];
+        for (int q = qlo; q < qhi; ++q) {
+            long long sq = __hip_atomic_load(fillSorted + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            fillC[q] = (long long)q * sq - ps;     // sum_{p<q} (s[q] - s[p])
+            ps += sq;
+        }
+        if (tid == 0) fillC[k] = 0x7fffffffffffffffLL;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// spill fill (first pass): the i-th unassigned vertex of the chunk (ascending id) takes the i-th
+// placement of the level sequence.
+// ------------------------------------------------------------------------------------------------
+template <typename LabelT>
+__global__ __launch_bounds__(kAdmitThreads) void k_spill_fill(
+    LabelT *__restrict__ Lc, int64_t chunk_lo, int64_t chunk_hi, int k,
+    const uint32_t *__restrict__ obase, const int32_t *__restrict__ fillRank,
+    const long long *__restrict__ fillC, unsigned long long *__restrict__ S,
+    const unsigned long long *__restrict__ misc) {
+    if (misc[3] == 0) return;
+    extern __shared__ uint32_t smem[];
+    constexpr int nwaves = kAdmitThreads / 64;
+    int32_t *dS = (int32_t *)smem;        // k
+    __shared__ uint32_t wsum[nwaves];
+    __shared__ uint32_t s_run;
+    constexpr uint32_t UN = LabelTraits<LabelT>::kUnassigned;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    for (int j = tid; j < k; j += kAdmitThreads) dS[j] = 0;
+    if (tid == 0) s_run = 0;
+    __syncthreads();
+    const int64_t lo = chunk_lo + (int64_t)blockIdx.x * kAdmitTile;
+    const long long tile_base = obase[blockIdx.x];
+    for (int round = 0; round < kAdmitTile / kAdmitThreads; ++round) {
+        const int64_t v = lo + round * kAdmitThreads + tid;
+        const bool un = (v < chunk_hi) && ((uint32_t)Lc[v] == UN);
+        const unsigned long long m = __ballot(un);
+        if (lane == 0) wsum[wave] = (uint32_t)__popcll(m);
+        __syncthreads();
+        if (un) {
+            long long i = tile_base + s_run + __popcll(m & lanes_below(lane));
+            for (int w = 0; w < wave; ++w) i += wsum[w];
+            // smallest a in [1,k] with i < C[a]
+            int lo_a = 1, hi_a = k;
+            while (lo_a < hi_a) {
+                int mid = (lo_a + hi_a) >> 1;
+                if (i < fillC[mid]) hi_a = mid; else lo_a = mid + 1;
+            }
+            const int a = lo_a;
+            const long long off = i - fillC[a - 1];
+            int idx = (int)(off % a);
+            int j = idx;
+            if (a < k) {          // idx-th smallest id among the a smallest partitions
+                for (j = 0; j < k - 1; ++j) {
+                    if (fillRank[j] < a) { if (idx == 0) break; idx -= 1; }
+                }
+            }
+            Lc[v] = (LabelT)j;
+            atomicAdd(&dS[j], 1);
+        }
+        __syncthreads();
+        if (tid == 0) { uint32_t s = 0; for (int w = 0; w < nwaves; ++w) s += wsum[w]; s_run += s; }
+        __syncthreads();
+    }
+    for (int j = tid; j < k; j += kAdmitThreads) {
+        int32_t d = dS[j];
+        if (d != 0) atomicAdd(&S[j], (unsigned long long)(long long)d);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// expand: compact labels -> int32 output
+// ------------------------------------------------------------------------------------------------
+template <typename LabelT>
+__global__ __launch_bounds__(256) void k_expand(const LabelT *__restrict__ Lc, int64_t n,
+                                                int32_t *__restrict__ out) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
+        uint32_t l = Lc[v];
+        out[v] = (l == LabelTraits<LabelT>::kUnassigned) ? -1 : (int32_t)l;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// edge cut: entries whose endpoints carry different labels, one integer sum
+// ------------------------------------------------------------------------------------------------
+template <typename RowT>
+__global__ __launch_bounds__(256) void k_edge_cut(const RowT *__restrict__ rowptr,
+                                                  const int32_t *__restrict__ colidx, int64_t n,
+                                                  const int32_t *__restrict__ labels,
+                                                  unsigned long long *__restrict__ out) {
+    constexpr int tv = 256;
+    __shared__ unsigned long long rowrel[tv + 1];   // 64-bit: a tile may hold any number of entries
+    __shared__ int32_t lab[tv];
+    __shared__ unsigned long long s_sum;
+    const int tid = threadIdx.x;
+    const int64_t v0 = (int64_t)blockIdx.x * tv;
+    const int64_t left = n - v0;
+    const int nv = left < tv ? (int)left : tv;
+    const int64_t e0 = (int64_t)rowptr[v0];
+    for (int i = tid; i <= tv; i += 256) {
+        int ii = i < nv ? i : nv;
+        rowrel[i] = (unsigned long long)((int64_t)rowptr[v0 + ii] - e0);
+    }
+    if (tid < nv) lab[tid] = labels[v0 + tid];
+    if (tid == 0) s_sum = 0;
+    __syncthreads();
+    const unsigned long long ne = rowrel[tv];
+    unsigned long long mine = 0;
+    for (unsigned long long i = tid; i < ne; i += 256) {
+        int32_t c = __builtin_nontemporal_load(colidx + e0 + i);
+        int32_t lu = labels[c];
+        int r = 0;
+        for (int step = tv >> 1; step >= 1; step >>= 1)
+            if (rowrel[r + step] <= i) r += step;
+        mine += (lu != lab[r]) ? 1ull : 0ull;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off);
+    if (lane_id() == 0 && mine) atomicAdd(&s_sum, mine);
+    __syncthreads();
+    if (tid == 0 && s_sum) atomicAdd(out, s_sum);
+}
+
+__global__ void k_zero_u64(unsigned long long *p, int count) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0ull;
+}
+
+__global__ void k_copy_sizes(const long long *__restrict__ S, int k, int64_t *__restrict__ out) {
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < k) out[j] = S[j];
+}
+
+}  // namespace grem

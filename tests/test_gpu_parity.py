@@ -1,0 +1,196 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Labels, partition sizes and the scaled estimates E must be bit-identical; the cut must be equal."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_17846_amd import binding as B
+from paper_2502_17846_amd import synth
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+DEV = "cuda:0"
+
+
+def _to_dev(g, rowptr_dtype=None):
+    rp = torch.as_tensor(np.asarray(g.rowptr))
+    if rowptr_dtype is not None:
+        rp = rp.to(rowptr_dtype)
+    return rp.to(DEV), torch.as_tensor(np.asarray(g.colidx)).to(DEV)
+
+
+def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO, tag=""):
+    """Runs both sides on the same graph and compares everything."""
+    g = synth.to_numpy(g)
+    print(f"[case] {tag} {g.name} n={g.n} nnz={g.nnz} k={k} slack={slack} chunk={chunk} R={R} "
+          f"seeded={seed is not None} rowptr={rowptr_dtype} mode={mode}", flush=True)
+    rp, ci = _to_dev(g, rowptr_dtype)
+    seed_d = None if seed is None else torch.as_tensor(seed).to(DEV)
+    B.grem_set_histogram_mode(mode)
+    try:
+        lab, sizes, est = B.grem_partition_state(rp, ci, g.n, k, slack, chunk, R, seed_d)
+        cut = B.grem_edge_cut(rp, ci, g.n, lab)
+        torch.cuda.synchronize()
+    finally:
+        B.grem_set_histogram_mode(B.HIST_AUTO)
+    olab, osizes, oest = oracle.partition_seeded(g.rowptr, g.colidx, g.n, k, slack, chunk, R, seed,
+                                                 return_state=True)
+    lab_h = lab.cpu().numpy()
+    bad = np.nonzero(lab_h != olab)[0]
+    assert bad.size == 0, f"{bad.size} labels differ, first at v={bad[:5]}: gpu {lab_h[bad[:5]]} oracle {olab[bad[:5]]}"
+    assert sizes.cpu().numpy().tolist() == osizes.tolist()
+    est_h = est.cpu().numpy().view(np.uint32)
+    assert (est_h == oest).all(), f"{(est_h != oest).sum()} estimates differ"
+    assert int(cut.item()) == oracle.edge_cut(g.rowptr, g.colidx, g.n, olab)
+    assert (np.bincount(lab_h, minlength=k) == osizes).all()
+    assert osizes.max() <= B.grem_capacity(g.n, k, slack) == oracle.capacity(g.n, k, slack)
+    return lab_h
+
+
+def test_handworked_example():
+    with open(os.path.join(GOLDEN, "handworked_6v.json")) as f:
+        gj = json.load(f)
+    e = np.asarray(gj["edges"])
+    rowptr, colidx = synth.csr_from_pairs_np(e[:, 0], e[:, 1], gj["n"])
+    g = synth.Graph(rowptr, colidx, gj["n"], colidx.size, len(e), None, "handworked")
+    c0, c1 = gj["cases"]
+    lab = _check(g, gj["k"], c0["balance_slack"], gj["chunk"], c0["refine_passes"])
+    assert lab.tolist() == c0["labels"]
+    for r in range(c1["refine_passes"] + 1):
+        lab = _check(g, gj["k"], c1["balance_slack"], gj["chunk"], r)
+        assert lab.tolist() == c1["labels_after_pass"][r]
+
+
+@pytest.mark.parametrize("rowptr_dtype", [torch.int32, torch.int64])
+def test_planted_partition_config(rowptr_dtype):
+    g = synth.planted_partition(seed=0)
+    for R in (0, 1, 2):
+        _check(g, 4, 1.05, 1024, R, rowptr_dtype=rowptr_dtype, tag="unseeded")
+    seed = np.full(g.n, -1, dtype=np.int32)
+    seed[:1024] = g.planted[:1024]
+    _check(g, 4, 1.05, 1024, 2, seed=seed, rowptr_dtype=rowptr_dtype, tag="seeded")
+
+
+@pytest.mark.parametrize("gseed", range(6))
+def test_small_random_graphs(gseed):
+    rng = np.random.default_rng(gseed)
+    n = int(rng.integers(1, 700))
+    m = int(rng.integers(0, 6 * n))
+    g = synth.random_graph_np(n, m, gseed, simple=bool(gseed % 2))
+    for k in (1, 2, 3, 7, 16):
+        for chunk in (1, 5, 100, 256, 1000):
+            for slack, R in ((1.0, 2), (1.05, 1), (1.5, 3)):
+                _check(g, k, slack, chunk, R)
+
+
+@pytest.mark.parametrize("k,slack", [(1, 1.0), (2, 1.05), (4, 1.05), (7, 1.0), (8, 1.3), (200, 1.0), (300, 1.1)])
+def test_single_chunk_spill_closed_form(k, slack):
+    g = synth.random_graph_np(5000, 20000, 3)
+    lab = _check(g, k, slack, g.n + 5, 0)
+    P = oracle.capacity(g.n, k, slack)
+    v = np.arange(g.n)
+    expect = np.zeros(g.n, dtype=np.int64) if k == 1 else np.where(v < P, 0, 1 + (v - P) % max(k - 1, 1))
+    assert lab.tolist() == expect.tolist()
+
+
+@pytest.mark.parametrize("n,k,slack,chunk", [(1000, 4, 1.05, 64), (997, 7, 1.0, 100), (4096, 16, 1.05, 1000),
+                                              (300, 300, 1.0, 17), (5000, 64, 1.02, 2048)])
+def test_edgeless_graph(n, k, slack, chunk):
+    g = synth.Graph(np.zeros(n + 1, dtype=np.int64), np.zeros(0, dtype=np.int32), n, 0, 0, None, "edgeless")
+    _check(g, k, slack, chunk, 2)
+
+
+@pytest.mark.parametrize("k", [2, 5, 16, 17, 32, 33, 64, 100, 128, 129, 255, 256, 300, 1000])
+def test_many_k(k):
+    g = synth.rmat(13, 16, seed=2, rowptr_dtype=torch.int64)
+    _check(g, k, 1.05, 1000, 2)
+
+
+@pytest.mark.parametrize("k", [2, 16, 64])
+def test_forced_global_histograms_match(k):
+    g = synth.rmat(12, 16, seed=4, rowptr_dtype=torch.int32)
+    _check(g, k, 1.05, 700, 2, mode=B.HIST_GLOBAL)
+
+
+def test_rmat_ragged_chunks_and_tiles():
+    g = synth.rmat(15, 16, seed=1, rowptr_dtype=torch.int32)
+    _check(g, 8, 1.05, 3000, 2)          # chunk not a multiple of any tile
+    _check(g, 8, 1.03, g.n, 1)           # one chunk
+    _check(g, 32, 1.05, 4097, 1)
+
+
+def test_hubs():
+    g = synth.hub_stress(scale=13, edge_factor=8, hubs=4, hub_degree=5000, seed=0, rowptr_dtype=torch.int32)
+    _check(g, 16, 1.1, 1024, 2)
+    _check(g, 256, 1.1, 1024, 2)
+
+
+def test_seeded_everything_and_partial():
+    g = synth.planted_partition(n=3000, blocks=3, seed=2, rowptr_dtype=np.int64)
+    seed = g.planted.copy()
+    _check(g, 3, 1.05, 500, 2, seed=seed, tag="all seeded")
+    rng = np.random.default_rng(0)
+    seed = np.where(rng.random(g.n) < 0.3, g.planted, -1).astype(np.int32)
+    _check(g, 3, 1.05, 500, 2, seed=seed, tag="30% seeded")
+
+
+def test_rmat_scale20_config():
+    g = synth.rmat(20, 16, seed=0, device=DEV, rowptr_dtype=torch.int32)
+    _check(g, 8, 1.05, 65536, 2)
+
+
+def test_chung_lu_medium():
+    g = synth.chung_lu(2_000_000, 28_000_000, seed=0, device=DEV, rowptr_dtype=torch.int64, cap=20_000.0)
+    _check(g, 16, 1.05, 1 << 16, 2)
+
+
+def test_determinism_and_workspace():
+    g = synth.rmat(16, 16, seed=5, device=DEV, rowptr_dtype=torch.int32)
+    k, chunk = 16, 5000
+    a = B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2)
+    ws = torch.empty(B.grem_workspace_bytes(g.n, k, chunk), dtype=torch.uint8, device=DEV)
+    B.grem_set_workspace(ws)
+    try:
+        b = B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2)
+        c = B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2)
+        small = torch.empty(1024, dtype=torch.uint8, device=DEV)
+        B.grem_set_workspace(small)
+        with pytest.raises(B.GremError) as e:
+            B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2)
+        assert e.value.code == B.ERR_NOMEM
+    finally:
+        B.grem_set_workspace(None)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(a, c)
+
+
+def test_errors():
+    g = synth.random_graph_np(100, 300, 0)
+    rp, ci = _to_dev(g)
+    for bad in (dict(k=0), dict(k=B.MAX_K + 1), dict(chunk=0), dict(R=-1), dict(slack=0.99), dict(slack=float("nan"))):
+        args = dict(k=4, chunk=10, R=1, slack=1.05)
+        args.update(bad)
+        with pytest.raises(B.GremError) as e:
+            B.grem_partition(rp, ci, g.n, args["k"], args["slack"], args["chunk"], args["R"])
+        assert e.value.code == B.ERR_ARG
+    with pytest.raises(B.GremError) as e:
+        B.grem_partition(rp, ci, g.n, 4, 1.05, 10, 31)
+    assert e.value.code == B.ERR_RANGE
+    seed = torch.full((g.n,), -1, dtype=torch.int32, device=DEV)
+    seed[3] = 4
+    with pytest.raises(B.GremError) as e:
+        B.grem_partition_seeded(rp, ci, g.n, 4, 1.05, 10, 1, seed)
+    assert e.value.code == B.ERR_SEED
+    seed[:] = 0
+    with pytest.raises(B.GremError) as e:
+        B.grem_partition_seeded(rp, ci, g.n, 4, 1.05, 10, 1, seed)
+    assert e.value.code == B.ERR_SEED
+    # after errors the library still works
+    lab = B.grem_partition(rp, ci, g.n, 4, 1.05, 10, 1)
+    torch.cuda.synchronize()
+    assert lab.cpu().numpy().tolist() == oracle.partition(g.rowptr, g.colidx, g.n, 4, 1.05, 10, 1).tolist()
