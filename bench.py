@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the GREM hot path on one MI355X.
+
+One step = one whole `grem_partition` call (pass 0 plus the refinement passes, every chunk: row
+stream, label gather, histograms, blend, arg-max, admission) on a synthetic graph that is already
+resident in HBM.  Default workload: the Chung-Lu power-law graph with the vertex and edge counts of
+OGBN-Papers100M (111M vertices, 1.6B directed edges, symmetrised), k=16, slack 1.05, chunk 2^20,
+2 refinement passes.
+
+Prints ONE JSON line (see the end of main).  The CPU oracle is timed beside it on a bounded sample
+(`cpu_baseline`); it is a reported baseline, not the target."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+WORKLOADS = {
+    # name: (generator kwargs, k, slack, chunk, refine_passes, rowptr bits)
+    "chunglu-111M": dict(kind="chung_lu", n=111_000_000, m=1_600_000_000, k=16, slack=1.05,
+                         chunk=1 << 20, R=2, bits=64),
+    "chunglu-14M": dict(kind="chung_lu", n=13_875_000, m=200_000_000, k=16, slack=1.05,
+                        chunk=1 << 17, R=2, bits=64),
+    "rmat-20": dict(kind="rmat", scale=20, ef=16, k=8, slack=1.05, chunk=65_536, R=2, bits=32),
+    "rmat-27": dict(kind="rmat", scale=27, ef=32, k=32, slack=1.03, chunk=1 << 22, R=1, bits=64),
+    "hub-24": dict(kind="hub", scale=24, ef=16, k=256, slack=1.10, chunk=262_144, R=3, bits=32),
+    "sbm-10k": dict(kind="sbm", k=4, slack=1.05, chunk=1024, R=2, bits=32),
+}
+
+
+def make_graph(w, device):
+    import torch
+    from paper_2502_17846_amd import synth
+    rdt = torch.int64 if w["bits"] == 64 else torch.int32
+    if w["kind"] == "chung_lu":
+        return synth.chung_lu(w["n"], w["m"], gamma=2.1, cap=50_000.0, seed=0, device=device,
+                              rowptr_dtype=rdt)
+    if w["kind"] == "rmat":
+        return synth.rmat(w["scale"], w["ef"], seed=0, device=device, rowptr_dtype=rdt)
+    if w["kind"] == "hub":
+        return synth.hub_stress(w["scale"], w["ef"], hubs=64, hub_degree=2_000_000, seed=0,
+                                device=device, rowptr_dtype=rdt)
+    if w["kind"] == "sbm":
+        g = synth.planted_partition(seed=0)
+        g.rowptr = torch.as_tensor(g.rowptr).to(device)
+        g.colidx = torch.as_tensor(g.colidx).to(device)
+        return g
+    raise ValueError(w["kind"])
+
+
+def algorithmic_bytes(n, nnz, k, R, rowptr_bytes, label_bytes):
+    """Bytes GREM itself must move per run: per pass the row offsets and column ids once, E written
+    (pass 0) or read and written (later passes), compact labels read and written once.  The label
+    gathers are served from cache and are not counted."""
+    common = rowptr_bytes * (n + 1) + 4 * nnz + 2 * label_bytes * n
+    first = common + 4 * n * k
+    later = common + 8 * n * k
+    return first, later, first + R * later
+
+
+def cpu_baseline(g, w, budget_s=15.0, max_chunks=48):
+    """The oracle, single thread, on the first chunks of pass 0 of the same graph."""
+    import numpy as np
+    import torch
+    import oracle
+    n, chunk = g.n, w["chunk"]
+    nchunks = (n + chunk - 1) // chunk
+    m = min(max_chunks, nchunks)
+    rows = min(n, m * chunk)
+    rp_full = g.rowptr.to(torch.int64)
+    end = int(rp_full[rows].item())
+    rp_host = rp_full.cpu().numpy().copy()
+    rp_host[rows:] = end                        # rows after the sample are left empty
+    ci_host = g.colidx[:end].cpu().numpy()
+    st = oracle.Stepper(rp_host, ci_host, n, w["k"], w["slack"], chunk, 0)
+    done_chunks, entries, t0 = 0, 0, time.perf_counter()
+    while done_chunks < m:
+        st.step()
+        done_chunks += 1
+        hi = min(n, done_chunks * chunk)
+        entries = int(rp_host[hi])
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    st.close()
+    edges = entries * (g.directed_edges / g.nnz)
+    return {
+        "value": edges / dt, "unit": "edges/s per pass", "cores": 1, "kind": "oracle",
+        "sample": f"pass 0, first {done_chunks} of {nchunks} chunks ({min(n, done_chunks * chunk)} rows, "
+                  f"{entries} CSR entries) of the same graph, {dt:.1f} s, label table of all {n} vertices",
+        "csr_entries_per_s": entries / dt,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="chunglu-111M", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="skip the extra instrumented step that times the score kernel")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; run with --gpus 1 "
+              "(the partitioner has no multi-GPU path)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2502_17846_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    w = WORKLOADS[args.workload]
+    t_gen = time.perf_counter()
+    g = make_graph(w, dev)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+    n, nnz, k, R, chunk = g.n, g.nnz, w["k"], w["R"], w["chunk"]
+    print(f"[bench] {g.name}: n={n} nnz={nnz} directed={g.directed_edges} generated in {t_gen:.1f}s",
+          file=sys.stderr, flush=True)
+
+    ws = torch.empty(B.grem_workspace_bytes(n, k, chunk), dtype=torch.uint8, device=dev)
+    B.grem_set_workspace(ws)
+    labels = torch.empty(n, dtype=torch.int32, device=dev)
+
+    def step():
+        B.grem_partition(g.rowptr, g.colidx, n, k, w["slack"], chunk, R, labels_out=labels)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    passes = R + 1
+    sec_per_pass = elapsed / (args.steps * passes)
+    edges_per_s = g.directed_edges / sec_per_pass
+
+    # result summary (also a cheap sanity check of the run that was timed)
+    cut = int(B.grem_edge_cut(g.rowptr, g.colidx, n, labels).item())
+    sizes = torch.bincount(labels, minlength=k)
+    P = B.grem_capacity(n, k, w["slack"])
+    assert int(sizes.max()) <= P and int(sizes.sum()) == n and int(labels.min()) >= 0
+
+    label_bytes = 1 if k <= 255 else 2
+    b_first, b_later, b_total = algorithmic_bytes(n, nnz, k, R, w["bits"] // 8, label_bytes)
+    nchunks = (n + chunk - 1) // chunk
+    roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": None,
+                "traffic": None, "kernel": "k_score_lds" if k <= 128 else "k_score_global"}
+    if not args.no_kernel_timing:
+        B.grem_profile_enable(True)
+        B.grem_profile_reset()
+        step()
+        torch.cuda.synchronize()
+        score_ms, score_launches = B.grem_profile_read(B.KERNEL_SCORE)
+        per_class = {}
+        for c in range(B.KERNEL_CLASSES):
+            ms, cnt = B.grem_profile_read(c)
+            per_class[B.kernel_name(c)] = {"ms": round(ms, 4), "launches": cnt}
+        B.grem_profile_enable(False)
+        B.grem_profile_reset()
+        bytes_per_launch = b_total / (passes * nchunks)
+        avg_launch_s = 1e-3 * score_ms / max(score_launches, 1)
+        achieved = bytes_per_launch / avg_launch_s / 1e9
+        roofline.update(achieved=achieved, frac=achieved / HBM_PEAK_GBPS,
+                        avg_launch_us=1e6 * avg_launch_s, launches_per_step=score_launches,
+                        bytes_per_launch=bytes_per_launch, per_kernel_class_ms=per_class)
+
+    out = {
+        "metric": "edges/sec per GREM pass",
+        "value": edges_per_s,
+        "unit": "edges/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {g.name}, k={k}, slack={w['slack']}, chunk={chunk}, "
+                               f"refine_passes={R}", "n": n, "csr_entries": nnz,
+                   "directed_edges": g.directed_edges, "passes_per_step": passes,
+                   "chunks_per_pass": nchunks},
+        "csr_entries_per_s": nnz / sec_per_pass,
+        "ms_per_pass": 1e3 * sec_per_pass,
+        "algorithmic_GB_per_step": b_total / 1e9,
+        "whole_step_algorithmic_GBps": b_total / (elapsed / args.steps) / 1e9,
+        "whole_step_frac_of_hbm_peak": b_total / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
+        "cut_fraction": cut / max(nnz, 1),
+        "max_partition_size": int(sizes.max()),
+        "capacity": P,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        print("[bench] timing the CPU oracle on a sample ...", file=sys.stderr, flush=True)
+        out["cpu_baseline"] = cpu_baseline(g, w)
+    B.grem_set_workspace(None)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
