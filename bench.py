@@ -129,7 +129,7 @@ def main():
     print(f"[bench] {g.name}: n={n} nnz={nnz} directed={g.directed_edges} generated in {t_gen:.1f}s",
           file=sys.stderr, flush=True)
 
-    ws = torch.empty(B.grem_workspace_bytes(n, k, chunk), dtype=torch.uint8, device=dev)
+    ws = torch.empty(B.grem_workspace_bytes(n, nnz, k, chunk), dtype=torch.uint8, device=dev)
     B.grem_set_workspace(ws)
     labels = torch.empty(n, dtype=torch.int32, device=dev)
 

@@ -61,6 +61,10 @@ extern "C" {
 #define GREM_HIST_AUTO 0     /* LDS when a tile of rows fits the LDS budget (k <= 128), else global */
 #define GREM_HIST_LDS 1      /* force LDS (error GREM_ERR_ARG if k > 128) */
 #define GREM_HIST_GLOBAL 2   /* force accumulation straight into E's rows in global memory */
+#define GREM_HIST_SWEEP 3    /* force the column-sliced path: a re-laid-out copy of the entries, LDS
+                                histograms, look-ups in column-slice order so that they hit L2
+                                (GREM_ERR_ARG unless k <= 16 and max degree < 65536).  AUTO takes it
+                                for k <= 16 when the label table is larger than L2. */
 
 /* Sec. 4.1 (Alg. 1 with all nodes unassigned at the start).  rowptr: n+1 entries; colidx:
  * rowptr[n] entries; labels_out: n entries, each in [0,k) on completion. */
@@ -105,9 +109,10 @@ int grem_edge_cut_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n,
 /* Host helpers.  grem_capacity returns P (or -1 on bad arguments). */
 int64_t grem_capacity(int64_t n, int32_t k, double balance_slack);
 
-/* Bytes of device workspace a partition call needs (E included; subtract n*k*4 when
- * estimates_out is passed).  0 on bad arguments. */
-size_t grem_workspace_bytes(int64_t n, int32_t k, int64_t chunk);
+/* Bytes of device workspace a partition call can use (E and the re-laid-out copy of the nnz
+ * entries included; subtract n*k*4 when estimates_out is passed).  A smaller workspace that still
+ * holds everything but the entry copy makes AUTO keep the plain LDS path.  0 on bad arguments. */
+size_t grem_workspace_bytes(int64_t n, int64_t nnz, int32_t k, int64_t chunk);
 
 /* Optional caller-owned workspace (device memory, 256-byte aligned) used by later partition
  * calls instead of a per-call stream-ordered allocation; (NULL, 0) removes it.  The library never
@@ -116,6 +121,10 @@ int grem_set_workspace(void *dev_ptr, size_t bytes);
 
 /* GREM_HIST_*; returns GREM_ERR_ARG for an unknown mode.  Process-wide. */
 int grem_set_histogram_mode(int32_t mode);
+
+/* Width in bits of a column slice of the column-sliced path, 4..21 (default 21: 2^21 labels, 1 MB
+ * packed).  Smaller values only make sense for testing on small graphs.  Process-wide. */
+int grem_set_sweep_col_bits(int32_t bits);
 
 /* Per-kernel timing with HIP events on the caller's stream, for measurement.  While enabled every
  * kernel launch of a partition call is bracketed by two events.  grem_profile_read synchronises on
@@ -129,7 +138,9 @@ int grem_set_histogram_mode(int32_t mode);
 #define GREM_KERNEL_SPILL_SCAN 5
 #define GREM_KERNEL_SPILL_FILL 6
 #define GREM_KERNEL_EXPAND 7
-#define GREM_KERNEL_CLASSES 8
+#define GREM_KERNEL_RELAYOUT 8   /* one-time re-layout of the entries for the column-sliced path */
+#define GREM_KERNEL_PACK 9       /* two-labels-per-byte copy of the labels */
+#define GREM_KERNEL_CLASSES 10
 int grem_profile_enable(int32_t on);
 int grem_profile_reset(void);
 int grem_profile_read(int32_t kernel_class, double *total_ms, int64_t *launches);

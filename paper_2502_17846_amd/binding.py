@@ -15,15 +15,16 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgrem.so")
 
 OK, ERR_ARG, ERR_NOMEM, ERR_HIP, ERR_RANGE, ERR_SEED = 0, -1, -2, -3, -4, -5
-HIST_AUTO, HIST_LDS, HIST_GLOBAL = 0, 1, 2
+HIST_AUTO, HIST_LDS, HIST_GLOBAL, HIST_SWEEP = 0, 1, 2, 3
 MAX_K = 4096
-KERNEL_CLASSES = 8
+KERNEL_CLASSES = 10
 KERNEL_SCORE = 1
 
 EXPORTS = [
     "grem_partition", "grem_partition_seeded", "grem_partition_r32", "grem_partition_seeded_r32",
     "grem_partition_state", "grem_edge_cut", "grem_edge_cut_r32", "grem_capacity",
-    "grem_workspace_bytes", "grem_set_workspace", "grem_set_histogram_mode", "grem_profile_enable",
+    "grem_workspace_bytes", "grem_set_workspace", "grem_set_histogram_mode",
+    "grem_set_sweep_col_bits", "grem_profile_enable",
     "grem_profile_reset", "grem_profile_read", "grem_status_string", "grem_kernel_name",
 ]
 
@@ -61,11 +62,13 @@ def load():
     lib.grem_capacity.restype = i64
     lib.grem_capacity.argtypes = [i64, i32, dbl]
     lib.grem_workspace_bytes.restype = ctypes.c_size_t
-    lib.grem_workspace_bytes.argtypes = [i64, i32, i64]
+    lib.grem_workspace_bytes.argtypes = [i64, i64, i32, i64]
     lib.grem_set_workspace.restype = ctypes.c_int
     lib.grem_set_workspace.argtypes = [vp, ctypes.c_size_t]
     lib.grem_set_histogram_mode.restype = ctypes.c_int
     lib.grem_set_histogram_mode.argtypes = [i32]
+    lib.grem_set_sweep_col_bits.restype = ctypes.c_int
+    lib.grem_set_sweep_col_bits.argtypes = [i32]
     lib.grem_profile_enable.restype = ctypes.c_int
     lib.grem_profile_enable.argtypes = [i32]
     lib.grem_profile_reset.restype = ctypes.c_int
@@ -124,8 +127,8 @@ def grem_capacity(n: int, k: int, balance_slack: float) -> int:
     return int(load().grem_capacity(n, k, float(balance_slack)))
 
 
-def grem_workspace_bytes(n: int, k: int, chunk: int) -> int:
-    return int(load().grem_workspace_bytes(n, k, chunk))
+def grem_workspace_bytes(n: int, nnz: int, k: int, chunk: int) -> int:
+    return int(load().grem_workspace_bytes(n, nnz, k, chunk))
 
 
 def grem_set_workspace(buf: Optional[torch.Tensor]):
@@ -139,6 +142,10 @@ def grem_set_workspace(buf: Optional[torch.Tensor]):
 
 def grem_set_histogram_mode(mode: int):
     _check(load().grem_set_histogram_mode(mode), "grem_set_histogram_mode")
+
+
+def grem_set_sweep_col_bits(bits: int):
+    _check(load().grem_set_sweep_col_bits(bits), "grem_set_sweep_col_bits")
 
 
 def _rowptr_bits(rowptr: torch.Tensor) -> int:

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "grem_kernels.hip.h"
+#include "grem_sweep.hip.h"
 
 namespace {
 
@@ -19,12 +20,15 @@ using namespace grem;
 
 constexpr int kLdsHistBytes = 32 * 1024;   // LDS spent on one tile's histograms
 constexpr int kLdsMaxK = 128;              // above this the histograms live in E's rows
+constexpr int kSweepMaxK = 16;             // column-sliced path: 16-bit counters, 2048 rows, 64 KB
+constexpr int64_t kSweepMinN = 1 << 22;    // AUTO: label table must exceed L2 for the path to pay
 
 struct Global {
     std::mutex mu;
     void *ws = nullptr;
     size_t ws_bytes = 0;
     int hist_mode = GREM_HIST_AUTO;
+    int sweep_col_bits = 21;
     bool prof = false;
     struct Ev { int cls; hipEvent_t a, b; };
     std::vector<Ev> events;
@@ -36,9 +40,16 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {
     size_t E, Lc, prop, S, cnt, room, ocnt, fillRank, fillSorted, fillC, misc, total;
+    size_t Ln, boff, tup, total_sweep;   // extras of the column-sliced path, after `total`
 };
 
-Layout make_layout(int64_t n, int32_t k, int64_t chunk, bool external_E) {
+inline int64_t slices_per_chunk(int64_t n, int64_t chunk) {
+    const int64_t cl = chunk < n ? chunk : n;
+    return (cl + kSliceRows - 1) / kSliceRows;
+}
+inline int col_slices(int64_t n, int col_bits) { return (int)((n + (1ll << col_bits) - 1) >> col_bits); }
+
+Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool external_E, int col_bits) {
     Layout L{};
     const int64_t cl = chunk < n ? chunk : n;
     const size_t lab = k <= 255 ? 1 : 2;
@@ -57,6 +68,12 @@ Layout make_layout(int64_t n, int32_t k, int64_t chunk, bool external_E) {
     L.fillC = take(((size_t)k + 1) * 8);
     L.misc = take(8 * 8);
     L.total = off;
+    const int64_t nchunks = (n + chunk - 1) / chunk;
+    L.Ln = take((size_t)(n / 2 + 1));
+    L.boff = take((size_t)nchunks * (size_t)slices_per_chunk(n, chunk) *
+                  ((size_t)col_slices(n, col_bits) + 1) * 4);
+    L.tup = take((size_t)(nnz > 0 ? nnz : 1) * 4);
+    L.total_sweep = off;
     return L;
 }
 
@@ -102,16 +119,17 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                   int64_t chunk, int32_t R, const int32_t *seed, int32_t *labels_out,
                   int64_t *sizes_out, uint32_t *estimates_out, hipStream_t stream) {
     const long long P = grem_capacity(n, k, slack);
-    const int64_t cl = chunk < n ? chunk : n;
     const bool external_E = estimates_out != nullptr;
-    const Layout lay = make_layout(n, k, chunk, external_E);
+    const int col_bits = g.sweep_col_bits;
+    Layout lay = make_layout(n, 0, k, chunk, external_E, col_bits);
 
-    int hist_mode = g.hist_mode;
+    const int hist_mode = g.hist_mode;
     if (hist_mode == GREM_HIST_LDS && k > kLdsMaxK) return GREM_ERR_ARG;
-    const bool use_lds = hist_mode == GREM_HIST_LDS || (hist_mode == GREM_HIST_AUTO && k <= kLdsMaxK);
+    if (hist_mode == GREM_HIST_SWEEP && k > kSweepMaxK) return GREM_ERR_ARG;
+    const bool use_lds = hist_mode != GREM_HIST_GLOBAL && k <= kLdsMaxK;
 
     // workspace
-    char *ws = nullptr;
+    char *ws = nullptr, *ws2 = nullptr;
     bool own_ws = false;
     if (g.ws) {
         if (g.ws_bytes < lay.total) return GREM_ERR_NOMEM;
@@ -123,7 +141,10 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
         }
         own_ws = true;
     }
-    auto release = [&]() { if (own_ws) (void)hipFreeAsync(ws, stream); };
+    auto release = [&]() {
+        if (own_ws) (void)hipFreeAsync(ws, stream);
+        if (ws2) (void)hipFreeAsync(ws2, stream);
+    };
 
     uint32_t *E = external_E ? estimates_out : (uint32_t *)(ws + lay.E);
     LabelT *Lc = (LabelT *)(ws + lay.Lc);
@@ -155,14 +176,15 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
         });
     }
     if (L.err) { release(); return L.err; }
-    unsigned long long h_misc[3] = {0, 0, 0};
+    unsigned long long h_misc[4] = {0, 0, 0, 0};
     if (hipMemcpyAsync(h_misc, misc, sizeof(h_misc), hipMemcpyDeviceToHost, stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess) { release(); return GREM_ERR_HIP; }
     if (h_misc[1] != 0 || h_misc[2] != 0) { release(); return GREM_ERR_SEED; }
     const unsigned long long maxdeg = h_misc[0];
+    const int64_t nnz = (int64_t)h_misc[3];
     if (R >= 32 || (maxdeg << R) >= (1ull << 32)) { release(); return GREM_ERR_RANGE; }
 
-    // tile shape of the score kernel
+    // tile shape of the plain score kernels
     int tv = kGlobalTile;
     if (use_lds) {
         tv = 256;
@@ -178,22 +200,101 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
         hipFuncSetAttribute((const void *)k_apply<LabelT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)apply_lds) != hipSuccess) { release(); return GREM_ERR_HIP; }
 
+    // ---- column-sliced path: decide, allocate its extras, re-lay-out the entries once
     const int64_t nchunks = (n + chunk - 1) / chunk;
+    const int nsl = (int)slices_per_chunk(n, chunk);
+    const int ncs = col_slices(n, col_bits);
+    bool sweep = false;
+    uint8_t *Ln = nullptr;
+    uint32_t *boff = nullptr, *tup = nullptr;
+    size_t sweep_lds = 0;
+    if constexpr (sizeof(LabelT) == 1) {
+        const bool can = k <= kSweepMaxK && maxdeg < 65536ull && ncs <= kMaxColSlices &&
+                         nchunks * (int64_t)nsl < (1ll << 31) && (((uintptr_t)E) & 15u) == 0;
+        if (hist_mode == GREM_HIST_SWEEP && !can) { release(); return GREM_ERR_ARG; }
+        sweep = can && (hist_mode == GREM_HIST_SWEEP || (hist_mode == GREM_HIST_AUTO && n >= kSweepMinN));
+        if (sweep) {
+            lay = make_layout(n, nnz, k, chunk, external_E, col_bits);
+            char *xbase = nullptr;
+            if (g.ws) {
+                if (g.ws_bytes >= lay.total_sweep) xbase = ws;
+                else if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_NOMEM; }
+                else sweep = false;
+            } else {
+                if (hipMallocAsync((void **)&ws2, lay.total_sweep - lay.total, stream) != hipSuccess) {
+                    (void)hipGetLastError();
+                    ws2 = nullptr;
+                    if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_NOMEM; }
+                    sweep = false;
+                } else {
+                    xbase = ws2 - lay.total;
+                }
+            }
+            if (sweep) {
+                Ln = (uint8_t *)(xbase + lay.Ln);
+                boff = (uint32_t *)(xbase + lay.boff);
+                tup = (uint32_t *)(xbase + lay.tup);
+                sweep_lds = ((size_t)((kSliceRows * k + 1) >> 1) + (size_t)ncs + 1 + (size_t)k) * 4;
+                if (sweep_lds > 64 * 1024) {
+                    if (hipFuncSetAttribute((const void *)k_score_sweep<RowT, true>,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)sweep_lds) != hipSuccess ||
+                        hipFuncSetAttribute((const void *)k_score_sweep<RowT, false>,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)sweep_lds) != hipSuccess) { release(); return GREM_ERR_HIP; }
+                }
+                const size_t relayout_lds = ((size_t)kSliceRows + 1 + (size_t)ncs) * 4;
+                L.run(GREM_KERNEL_RELAYOUT, [&] {
+                    hipLaunchKernelGGL((k_relayout<RowT>), dim3((unsigned)(nchunks * nsl)), dim3(256),
+                                       relayout_lds, stream, rowptr, colidx, n, chunk, nsl, ncs, col_bits,
+                                       tup, boff);
+                });
+            }
+        }
+    } else {
+        if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
+    }
+
+    auto pack = [&](int64_t lo, int64_t hi) {
+        if constexpr (sizeof(LabelT) == 1) {
+            int64_t blocks = ((hi - lo) / 2 + 256) / 256;
+            if (blocks > 4096) blocks = 4096;
+            L.run(GREM_KERNEL_PACK, [&] {
+                hipLaunchKernelGGL(k_pack, dim3((unsigned)blocks), dim3(256), 0, stream,
+                                   (const uint8_t *)Lc, Ln, lo, hi, n);
+            });
+        }
+    };
+
     for (int pass = 0; pass <= R && !L.err; ++pass) {
+        // packed labels are valid for look-ups once nothing that is looked up is unassigned
+        const bool sweep_now = sweep && (pass >= 1 || !seed);
+        if (sweep && seed && pass == 1) pack(0, n);
         for (int64_t c = 0; c < nchunks && !L.err; ++c) {
             const int64_t lo = c * chunk;
             const int64_t hi = (lo + chunk < n) ? lo + chunk : n;
             const int64_t len = hi - lo;
             const int64_t gather_limit = (pass == 0 && !seed) ? lo : n;
-            const unsigned score_blocks = (unsigned)((len + tv - 1) / tv);
             const unsigned admit_blocks = (unsigned)((len + kAdmitTile - 1) / kAdmitTile);
-            if (use_lds) {
+            if (sweep_now) {
+                if constexpr (sizeof(LabelT) == 1) {
+                    const unsigned blocks = (unsigned)((len + kSliceRows - 1) / kSliceRows);
+                    L.run(GREM_KERNEL_SCORE, [&] {
+                        hipLaunchKernelGGL((k_score_sweep<RowT, true>), dim3(blocks), dim3(kSweepThreads),
+                                           sweep_lds, stream, rowptr, tup, boff, (const uint8_t *)Lc, Ln, S,
+                                           E, (uint8_t *)prop, lo, hi, (int)(c * nsl), (int)k, ncs, col_bits,
+                                           pass, P, gather_limit);
+                    });
+                }
+            } else if (use_lds) {
+                const unsigned score_blocks = (unsigned)((len + tv - 1) / tv);
                 L.run(GREM_KERNEL_SCORE, [&] {
                     hipLaunchKernelGGL((k_score_lds<RowT, LabelT>), dim3(score_blocks),
                                        dim3(kScoreThreads), score_lds, stream, rowptr, colidx, Lc, S, E,
                                        prop, lo, hi, (int)k, tv, pass, P, gather_limit);
                 });
             } else {
+                const unsigned score_blocks = (unsigned)((len + tv - 1) / tv);
                 L.run(GREM_KERNEL_SCORE, [&] {
                     hipLaunchKernelGGL((k_score_global<RowT, LabelT>), dim3(score_blocks),
                                        dim3(kScoreThreads), score_lds, stream, rowptr, colidx, Lc, S, E,
@@ -224,6 +325,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                                        (unsigned long long *)S, misc);
                 });
             }
+            if (sweep_now && !(pass == R && c == nchunks - 1)) pack(lo, hi);
         }
     }
     {
@@ -239,7 +341,6 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                                    sizes_out);
             });
     }
-    (void)cl;
     release();
     return L.err;
 }
@@ -283,9 +384,11 @@ int64_t grem_capacity(int64_t n, int32_t k, double balance_slack) {
     return even > widened ? even : widened;
 }
 
-size_t grem_workspace_bytes(int64_t n, int32_t k, int64_t chunk) {
-    if (n < 1 || k < 1 || k > GREM_MAX_K || chunk < 1) return 0;
-    return make_layout(n, k, chunk, false).total;
+size_t grem_workspace_bytes(int64_t n, int64_t nnz, int32_t k, int64_t chunk) {
+    if (n < 1 || nnz < 0 || k < 1 || k > GREM_MAX_K || chunk < 1) return 0;
+    std::lock_guard<std::mutex> lock(g.mu);
+    const Layout lay = make_layout(n, nnz, k, chunk, false, g.sweep_col_bits);
+    return (k <= kSweepMaxK) ? lay.total_sweep : lay.total;
 }
 
 int grem_set_workspace(void *dev_ptr, size_t bytes) {
@@ -298,9 +401,18 @@ int grem_set_workspace(void *dev_ptr, size_t bytes) {
 }
 
 int grem_set_histogram_mode(int32_t mode) {
-    if (mode != GREM_HIST_AUTO && mode != GREM_HIST_LDS && mode != GREM_HIST_GLOBAL) return GREM_ERR_ARG;
+    if (mode != GREM_HIST_AUTO && mode != GREM_HIST_LDS && mode != GREM_HIST_GLOBAL &&
+        mode != GREM_HIST_SWEEP)
+        return GREM_ERR_ARG;
     std::lock_guard<std::mutex> lock(g.mu);
     g.hist_mode = mode;
+    return GREM_OK;
+}
+
+int grem_set_sweep_col_bits(int32_t bits) {
+    if (bits < 4 || bits > 32 - kSliceRowBits) return GREM_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.sweep_col_bits = bits;
     return GREM_OK;
 }
 
@@ -411,6 +523,8 @@ const char *grem_kernel_name(int32_t kernel_class) {
         case GREM_KERNEL_SPILL_SCAN: return "spill_scan";
         case GREM_KERNEL_SPILL_FILL: return "spill_fill";
         case GREM_KERNEL_EXPAND: return "expand";
+        case GREM_KERNEL_RELAYOUT: return "relayout";
+        case GREM_KERNEL_PACK: return "pack";
         default: return "?";
     }
 }

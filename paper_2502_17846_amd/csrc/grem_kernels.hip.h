@@ -44,7 +44,7 @@ __device__ __forceinline__ int owning_row(const uint32_t *rowrel, uint32_t i, in
 
 // ------------------------------------------------------------------------------------------------
 // prepass: compact labels from the seed, seed sizes, maximum degree, seed validity
-// misc[0] = max degree, misc[1] = number of invalid seed labels
+// misc[0] = max degree, misc[1] = number of invalid seed labels, misc[3] = number of entries
 // ------------------------------------------------------------------------------------------------
 template <typename RowT, typename LabelT>
 __global__ __launch_bounds__(256) void k_prepass(const RowT *__restrict__ rowptr,
@@ -80,6 +80,7 @@ __global__ __launch_bounds__(256) void k_prepass(const RowT *__restrict__ rowptr
     if (threadIdx.x == 0) {
         atomicMax(&misc[0], s_maxdeg);
         if (s_bad) atomicAdd(&misc[1], (unsigned long long)s_bad);
+        if (blockIdx.x == 0) misc[3] = (unsigned long long)rowptr[n];
     }
 }
 
@@ -438,7 +439,7 @@ __global__ __launch_bounds__(kAdmitThreads) void k_apply(
 //   order the partitions by (S, id): s[0] <= s[1] <= ...;  C[a] = sum_{q<a} (s[a] - s[q]) is the
 //   number of placements made before the a+1 smallest partitions are level; while the a smallest
 //   are level, placements cycle through them in ascending id.
-// misc[3] = total to place.  fillRank[j] = position of j in that order, fillC[a] for a = 0..k
+// misc[4] = total to place.  fillRank[j] = position of j in that order, fillC[a] for a = 0..k
 // (C[0] = 0, C[k] = infinity).
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kScanThreads) void k_spill_scan(uint32_t *__restrict__ ocnt, int ntiles,
@@ -470,7 +471,7 @@ __global__ __launch_bounds__(kScanThreads) void k_spill_scan(uint32_t *__restric
         __syncthreads();
     }
     const long long total = s_total;
-    if (tid == 0) misc[3] = (unsigned long long)total;
+    if (tid == 0) misc[4] = (unsigned long long)total;
     if (total == 0) return;
     for (int j = tid; j < k; j += kScanThreads) Sl[j] = S[j];
     __syncthreads();
@@ -516,7 +517,7 @@ __global__ __launch_bounds__(kAdmitThreads) void k_spill_fill(
     const uint32_t *__restrict__ obase, const int32_t *__restrict__ fillRank,
     const long long *__restrict__ fillC, unsigned long long *__restrict__ S,
     const unsigned long long *__restrict__ misc) {
-    if (misc[3] == 0) return;
+    if (misc[4] == 0) return;
     extern __shared__ uint32_t smem[];
     constexpr int nwaves = kAdmitThreads / 64;
     int32_t *dS = (int32_t *)smem;        // k

@@ -53,11 +53,13 @@ def test_host_helpers(lib):
     assert lib.grem_capacity(0, 4, 1.05) == -1
     assert lib.grem_capacity(10, 4, 0.5) == -1
     lib.grem_workspace_bytes.restype = ctypes.c_size_t
-    lib.grem_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int64]
-    n, k, chunk = 1 << 20, 8, 1 << 16
-    w = lib.grem_workspace_bytes(n, k, chunk)
-    assert w >= n * k * 4 + n and w < n * k * 4 + 4 * n + (1 << 20)
-    assert lib.grem_workspace_bytes(0, k, chunk) == 0
+    lib.grem_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64]
+    n, nnz, k, chunk = 1 << 20, 30_000_000, 8, 1 << 16
+    w = lib.grem_workspace_bytes(n, nnz, k, chunk)
+    assert w >= n * k * 4 + n + 4 * nnz and w < n * k * 4 + 4 * n + 4 * nnz + (1 << 20)
+    w2 = lib.grem_workspace_bytes(n, nnz, 64, chunk)           # no entry copy above k = 16
+    assert n * 64 * 4 + n <= w2 < n * 64 * 4 + 4 * n + (1 << 20)
+    assert lib.grem_workspace_bytes(0, nnz, k, chunk) == 0
     lib.grem_status_string.restype = ctypes.c_char_p
     assert lib.grem_status_string(0) == b"ok"
     assert b"seed" in lib.grem_status_string(-5)

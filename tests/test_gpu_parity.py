@@ -24,7 +24,7 @@ def _to_dev(g, rowptr_dtype=None):
     return rp.to(DEV), torch.as_tensor(np.asarray(g.colidx)).to(DEV)
 
 
-def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO, tag=""):
+def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO, tag="", col_bits=21):
     """Runs both sides on the same graph and compares everything."""
     g = synth.to_numpy(g)
     print(f"[case] {tag} {g.name} n={g.n} nnz={g.nnz} k={k} slack={slack} chunk={chunk} R={R} "
@@ -32,12 +32,14 @@ def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO
     rp, ci = _to_dev(g, rowptr_dtype)
     seed_d = None if seed is None else torch.as_tensor(seed).to(DEV)
     B.grem_set_histogram_mode(mode)
+    B.grem_set_sweep_col_bits(col_bits)
     try:
         lab, sizes, est = B.grem_partition_state(rp, ci, g.n, k, slack, chunk, R, seed_d)
         cut = B.grem_edge_cut(rp, ci, g.n, lab)
         torch.cuda.synchronize()
     finally:
         B.grem_set_histogram_mode(B.HIST_AUTO)
+        B.grem_set_sweep_col_bits(21)
     olab, osizes, oest = oracle.partition_seeded(g.rowptr, g.colidx, g.n, k, slack, chunk, R, seed,
                                                  return_state=True)
     lab_h = lab.cpu().numpy()
@@ -117,6 +119,40 @@ def test_forced_global_histograms_match(k):
     _check(g, k, 1.05, 700, 2, mode=B.HIST_GLOBAL)
 
 
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 13, 16])
+@pytest.mark.parametrize("col_bits", [4, 9, 21])
+def test_column_sliced_path_small(k, col_bits):
+    g = synth.rmat(13, 16, seed=3, rowptr_dtype=torch.int64)
+    _check(g, k, 1.05, 3000, 2, mode=B.HIST_SWEEP, col_bits=col_bits)
+    _check(g, k, 1.2, 5000, 1, mode=B.HIST_SWEEP, col_bits=col_bits, rowptr_dtype=torch.int32)
+
+
+def test_column_sliced_path_seeded_and_edge_cases():
+    g = synth.planted_partition(n=6000, blocks=3, seed=2, rowptr_dtype=np.int64)
+    rng = np.random.default_rng(0)
+    seed = np.where(rng.random(g.n) < 0.3, g.planted, -1).astype(np.int32)
+    _check(g, 3, 1.05, 2500, 2, seed=seed, mode=B.HIST_SWEEP, col_bits=6, tag="30% seeded")
+    _check(g, 3, 1.05, 2500, 0, seed=seed, mode=B.HIST_SWEEP, col_bits=6, tag="seeded R=0")
+    _check(g, 4, 1.05, 1, 1, mode=B.HIST_SWEEP, col_bits=5, tag="chunk=1")
+    _check(g, 16, 1.0, 2049, 3, mode=B.HIST_SWEEP, col_bits=7, tag="odd chunk")
+    e = synth.Graph(np.zeros(5001, dtype=np.int64), np.zeros(0, dtype=np.int32), 5000, 0, 0, None, "edgeless")
+    _check(e, 16, 1.02, 2048, 2, mode=B.HIST_SWEEP, col_bits=8)
+    h = synth.hub_stress(scale=13, edge_factor=8, hubs=4, hub_degree=5000, seed=0, rowptr_dtype=torch.int32)
+    _check(h, 16, 1.1, 4096, 2, mode=B.HIST_SWEEP, col_bits=8)
+
+
+def test_column_sliced_path_errors():
+    g = synth.random_graph_np(100, 300, 0)
+    rp, ci = _to_dev(g)
+    B.grem_set_histogram_mode(B.HIST_SWEEP)
+    try:
+        with pytest.raises(B.GremError) as e:
+            B.grem_partition(rp, ci, g.n, 17, 1.05, 10, 1)
+        assert e.value.code == B.ERR_ARG
+    finally:
+        B.grem_set_histogram_mode(B.HIST_AUTO)
+
+
 def test_rmat_ragged_chunks_and_tiles():
     g = synth.rmat(15, 16, seed=1, rowptr_dtype=torch.int32)
     _check(g, 8, 1.05, 3000, 2)          # chunk not a multiple of any tile
@@ -146,14 +182,20 @@ def test_rmat_scale20_config():
 
 def test_chung_lu_medium():
     g = synth.chung_lu(2_000_000, 28_000_000, seed=0, device=DEV, rowptr_dtype=torch.int64, cap=20_000.0)
-    _check(g, 16, 1.05, 1 << 16, 2)
+    _check(g, 16, 1.05, 1 << 16, 2, mode=B.HIST_LDS)
+    _check(g, 16, 1.05, 1 << 16, 2, mode=B.HIST_SWEEP, col_bits=17)
+
+
+def test_chung_lu_auto_takes_column_sliced_path():
+    g = synth.chung_lu(6_000_000, 60_000_000, seed=1, device=DEV, rowptr_dtype=torch.int64, cap=30_000.0)
+    _check(g, 16, 1.05, 1 << 19, 2)
 
 
 def test_determinism_and_workspace():
     g = synth.rmat(16, 16, seed=5, device=DEV, rowptr_dtype=torch.int32)
     k, chunk = 16, 5000
     a = B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2)
-    ws = torch.empty(B.grem_workspace_bytes(g.n, k, chunk), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(B.grem_workspace_bytes(g.n, g.nnz, k, chunk), dtype=torch.uint8, device=DEV)
     B.grem_set_workspace(ws)
     try:
         b = B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2)
