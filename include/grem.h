@@ -63,7 +63,7 @@ extern "C" {
 #define GREM_HIST_GLOBAL 2   /* force accumulation straight into E's rows in global memory */
 #define GREM_HIST_SWEEP 3    /* force the column-sliced path: a re-laid-out copy of the entries, LDS
                                 histograms, look-ups in column-slice order so that they hit L2
-                                (GREM_ERR_ARG unless k <= 16 and max degree < 65536).  AUTO takes it
+                                (GREM_ERR_ARG unless k <= 16 and the plan fits LDS).  AUTO takes it
                                 for k <= 16 when the label table is larger than L2. */
 
 /* Sec. 4.1 (Alg. 1 with all nodes unassigned at the start).  rowptr: n+1 entries; colidx:
@@ -126,6 +126,11 @@ int grem_set_histogram_mode(int32_t mode);
  * packed).  Smaller values only make sense for testing on small graphs.  Process-wide. */
 int grem_set_sweep_col_bits(int32_t bits);
 
+/* Rows of at least this many entries are "hubs" of the column-sliced path: their entries are
+ * spread evenly over the chunk's workgroups.  1..65535, default 2048; smaller values only make
+ * sense for testing on small graphs.  Process-wide. */
+int grem_set_sweep_hub_degree(int32_t degree);
+
 /* Per-kernel timing with HIP events on the caller's stream, for measurement.  While enabled every
  * kernel launch of a partition call is bracketed by two events.  grem_profile_read synchronises on
  * the recorded events, adds up the launches of one kernel class since the last grem_profile_reset,
@@ -138,9 +143,10 @@ int grem_set_sweep_col_bits(int32_t bits);
 #define GREM_KERNEL_SPILL_SCAN 5
 #define GREM_KERNEL_SPILL_FILL 6
 #define GREM_KERNEL_EXPAND 7
-#define GREM_KERNEL_RELAYOUT 8   /* one-time re-layout of the entries for the column-sliced path */
+#define GREM_KERNEL_RELAYOUT 8   /* one-time planning and re-layout of the entries (column-sliced path) */
 #define GREM_KERNEL_PACK 9       /* two-labels-per-byte copy of the labels */
-#define GREM_KERNEL_CLASSES 10
+#define GREM_KERNEL_HUBS 10      /* blend and proposal of the high-degree rows of the column-sliced path */
+#define GREM_KERNEL_CLASSES 11
 int grem_profile_enable(int32_t on);
 int grem_profile_reset(void);
 int grem_profile_read(int32_t kernel_class, double *total_ms, int64_t *launches);

@@ -17,14 +17,14 @@ LIB_PATH = os.path.join(_HERE, "libgrem.so")
 OK, ERR_ARG, ERR_NOMEM, ERR_HIP, ERR_RANGE, ERR_SEED = 0, -1, -2, -3, -4, -5
 HIST_AUTO, HIST_LDS, HIST_GLOBAL, HIST_SWEEP = 0, 1, 2, 3
 MAX_K = 4096
-KERNEL_CLASSES = 10
+KERNEL_CLASSES = 11
 KERNEL_SCORE = 1
 
 EXPORTS = [
     "grem_partition", "grem_partition_seeded", "grem_partition_r32", "grem_partition_seeded_r32",
     "grem_partition_state", "grem_edge_cut", "grem_edge_cut_r32", "grem_capacity",
     "grem_workspace_bytes", "grem_set_workspace", "grem_set_histogram_mode",
-    "grem_set_sweep_col_bits", "grem_profile_enable",
+    "grem_set_sweep_col_bits", "grem_set_sweep_hub_degree", "grem_profile_enable",
     "grem_profile_reset", "grem_profile_read", "grem_status_string", "grem_kernel_name",
 ]
 
@@ -69,6 +69,8 @@ def load():
     lib.grem_set_histogram_mode.argtypes = [i32]
     lib.grem_set_sweep_col_bits.restype = ctypes.c_int
     lib.grem_set_sweep_col_bits.argtypes = [i32]
+    lib.grem_set_sweep_hub_degree.restype = ctypes.c_int
+    lib.grem_set_sweep_hub_degree.argtypes = [i32]
     lib.grem_profile_enable.restype = ctypes.c_int
     lib.grem_profile_enable.argtypes = [i32]
     lib.grem_profile_reset.restype = ctypes.c_int
@@ -146,6 +148,10 @@ def grem_set_histogram_mode(mode: int):
 
 def grem_set_sweep_col_bits(bits: int):
     _check(load().grem_set_sweep_col_bits(bits), "grem_set_sweep_col_bits")
+
+
+def grem_set_sweep_hub_degree(degree: int):
+    _check(load().grem_set_sweep_hub_degree(degree), "grem_set_sweep_hub_degree")
 
 
 def _rowptr_bits(rowptr: torch.Tensor) -> int:

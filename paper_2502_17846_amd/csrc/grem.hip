@@ -29,6 +29,7 @@ struct Global {
     size_t ws_bytes = 0;
     int hist_mode = GREM_HIST_AUTO;
     int sweep_col_bits = 21;
+    int sweep_hub_degree = 2048;
     bool prof = false;
     struct Ev { int cls; hipEvent_t a, b; };
     std::vector<Ev> events;
@@ -39,8 +40,13 @@ Global g;
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {
-    size_t E, Lc, prop, S, cnt, room, ocnt, fillRank, fillSorted, fillC, misc, total;
-    size_t Ln, boff, tup, total_sweep;   // extras of the column-sliced path, after `total`
+    size_t E, Lc, prop, S, cnt, room, ocnt, fillRank, fillSorted, fillC, misc;
+    // plan of the column-sliced path (k <= 16 only)
+    size_t sl_reg_cnt, sl_reg_start, sl_nh, sl_hub_start, sl_hent, sl_hent_start, share_h0, share_nhs,
+        ch_regtot, ch_nh, ch_H, hub_row, hub_off;
+    size_t total;
+    size_t Ln, boff, hboff, Hhub, tup, total_sweep;   // extras of the column-sliced path, after `total`
+    size_t hub_rows_cap;                              // rows of Hhub
 };
 
 inline int64_t slices_per_chunk(int64_t n, int64_t chunk) {
@@ -49,11 +55,14 @@ inline int64_t slices_per_chunk(int64_t n, int64_t chunk) {
 }
 inline int col_slices(int64_t n, int col_bits) { return (int)((n + (1ll << col_bits) - 1) >> col_bits); }
 
-Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool external_E, int col_bits) {
+Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool external_E, int col_bits,
+                   int hub_degree) {
     Layout L{};
     const int64_t cl = chunk < n ? chunk : n;
     const size_t lab = k <= 255 ? 1 : 2;
     const int64_t ntiles = (cl + kAdmitTile - 1) / kAdmitTile;
+    const int64_t nchunks = (n + chunk - 1) / chunk;
+    const size_t G = (size_t)nchunks * (size_t)slices_per_chunk(n, chunk);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
     L.E = take(external_E ? 0 : (size_t)n * (size_t)k * 4);
@@ -67,11 +76,30 @@ Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool extern
     L.fillSorted = take((size_t)k * 8);
     L.fillC = take(((size_t)k + 1) * 8);
     L.misc = take(8 * 8);
+    if (k <= kSweepMaxK) {
+        L.sl_reg_cnt = take(G * 4);
+        L.sl_reg_start = take(G * 8);
+        L.sl_nh = take(G * 4);
+        L.sl_hub_start = take(G * 4);
+        L.sl_hent = take(G * 8);
+        L.sl_hent_start = take(G * 8);
+        L.share_h0 = take(G * 4);
+        L.share_nhs = take(G * 4);
+        L.ch_regtot = take((size_t)nchunks * 8);
+        L.ch_nh = take((size_t)nchunks * 4);
+        L.ch_H = take((size_t)nchunks * 8);
+        L.hub_row = take((size_t)n * 4);
+        L.hub_off = take((size_t)(n + nchunks) * 8);
+    }
     L.total = off;
-    const int64_t nchunks = (n + chunk - 1) / chunk;
+    // a chunk cannot hold more hubs than rows, nor more than entries / hub_degree
+    size_t hubs = (size_t)(nnz / (hub_degree > 0 ? hub_degree : 1)) + 1;
+    if (hubs > (size_t)cl) hubs = (size_t)cl;
+    L.hub_rows_cap = hubs;
     L.Ln = take((size_t)(n / 2 + 1));
-    L.boff = take((size_t)nchunks * (size_t)slices_per_chunk(n, chunk) *
-                  ((size_t)col_slices(n, col_bits) + 1) * 4);
+    L.boff = take(G * ((size_t)col_slices(n, col_bits) + 1) * 4);
+    L.hboff = take(G * ((size_t)col_slices(n, col_bits) + 1) * 4);
+    L.Hhub = take(hubs * (size_t)k * 4);
     L.tup = take((size_t)(nnz > 0 ? nnz : 1) * 4);
     L.total_sweep = off;
     return L;
@@ -121,7 +149,8 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
     const long long P = grem_capacity(n, k, slack);
     const bool external_E = estimates_out != nullptr;
     const int col_bits = g.sweep_col_bits;
-    Layout lay = make_layout(n, 0, k, chunk, external_E, col_bits);
+    const int hub_degree = g.sweep_hub_degree;
+    Layout lay = make_layout(n, 0, k, chunk, external_E, col_bits, hub_degree);
 
     const int hist_mode = g.hist_mode;
     if (hist_mode == GREM_HIST_LDS && k > kLdsMaxK) return GREM_ERR_ARG;
@@ -175,8 +204,55 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                                P, misc);
         });
     }
+    // plan of the column-sliced path (needs only rowptr, so it runs before the read-back)
+    const int64_t nchunks = (n + chunk - 1) / chunk;
+    const int nsl = (int)slices_per_chunk(n, chunk);
+    const int ncs = col_slices(n, col_bits);
+    bool sweep = false;
+    SweepPlan pl{};
+    if constexpr (sizeof(LabelT) == 1) {
+        const bool can = k <= kSweepMaxK && ncs <= kMaxColSlices && nchunks * (int64_t)nsl < (1ll << 31) &&
+                         (((uintptr_t)E) & 15u) == 0;
+        if (hist_mode == GREM_HIST_SWEEP && !can) { release(); return GREM_ERR_ARG; }
+        sweep = can && (hist_mode == GREM_HIST_SWEEP || (hist_mode == GREM_HIST_AUTO && n >= kSweepMinN));
+        if (seed && R == 0) sweep = false;      // the only pass runs on the plain path
+        if (sweep) {
+            pl.sl_reg_cnt = (uint32_t *)(ws + lay.sl_reg_cnt);
+            pl.sl_reg_start = (u64 *)(ws + lay.sl_reg_start);
+            pl.sl_nh = (uint32_t *)(ws + lay.sl_nh);
+            pl.sl_hub_start = (uint32_t *)(ws + lay.sl_hub_start);
+            pl.sl_hent = (u64 *)(ws + lay.sl_hent);
+            pl.sl_hent_start = (u64 *)(ws + lay.sl_hent_start);
+            pl.share_h0 = (uint32_t *)(ws + lay.share_h0);
+            pl.share_nhs = (uint32_t *)(ws + lay.share_nhs);
+            pl.ch_regtot = (u64 *)(ws + lay.ch_regtot);
+            pl.ch_nh = (uint32_t *)(ws + lay.ch_nh);
+            pl.ch_H = (u64 *)(ws + lay.ch_H);
+            pl.hub_row = (int32_t *)(ws + lay.hub_row);
+            pl.hub_off = (u64 *)(ws + lay.hub_off);
+            const unsigned G = (unsigned)(nchunks * nsl);
+            L.run(GREM_KERNEL_RELAYOUT, [&] {
+                hipLaunchKernelGGL((k_plan_slices<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, chunk, nsl,
+                                   (uint32_t)hub_degree, pl);
+            });
+            L.run(GREM_KERNEL_RELAYOUT, [&] {
+                hipLaunchKernelGGL(k_plan_chunks, dim3((unsigned)nchunks), dim3(256), 0, stream, n, chunk, nsl,
+                                   pl, misc);
+            });
+            L.run(GREM_KERNEL_RELAYOUT, [&] {
+                hipLaunchKernelGGL((k_plan_hubs<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, chunk, nsl,
+                                   (uint32_t)hub_degree, pl);
+            });
+            L.run(GREM_KERNEL_RELAYOUT, [&] {
+                hipLaunchKernelGGL(k_plan_shares, dim3((G + 255) / 256), dim3(256), 0, stream, n, chunk, nsl,
+                                   (int)G, pl, misc);
+            });
+        }
+    } else {
+        if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
+    }
     if (L.err) { release(); return L.err; }
-    unsigned long long h_misc[4] = {0, 0, 0, 0};
+    unsigned long long h_misc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (hipMemcpyAsync(h_misc, misc, sizeof(h_misc), hipMemcpyDeviceToHost, stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess) { release(); return GREM_ERR_HIP; }
     if (h_misc[1] != 0 || h_misc[2] != 0) { release(); return GREM_ERR_SEED; }
@@ -200,21 +276,26 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
         hipFuncSetAttribute((const void *)k_apply<LabelT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)apply_lds) != hipSuccess) { release(); return GREM_ERR_HIP; }
 
-    // ---- column-sliced path: decide, allocate its extras, re-lay-out the entries once
-    const int64_t nchunks = (n + chunk - 1) / chunk;
-    const int nsl = (int)slices_per_chunk(n, chunk);
-    const int ncs = col_slices(n, col_bits);
-    bool sweep = false;
+    // ---- column-sliced path: allocate its extras, re-lay-out the entries once
     uint8_t *Ln = nullptr;
-    uint32_t *boff = nullptr, *tup = nullptr;
+    uint32_t *boff = nullptr, *hboff = nullptr, *tup = nullptr, *Hhub = nullptr;
     size_t sweep_lds = 0;
+    const int share_hubs = (int)h_misc[5];
+    const unsigned max_chunk_hubs = (unsigned)h_misc[6];
     if constexpr (sizeof(LabelT) == 1) {
-        const bool can = k <= kSweepMaxK && maxdeg < 65536ull && ncs <= kMaxColSlices &&
-                         nchunks * (int64_t)nsl < (1ll << 31) && (((uintptr_t)E) & 15u) == 0;
-        if (hist_mode == GREM_HIST_SWEEP && !can) { release(); return GREM_ERR_ARG; }
-        sweep = can && (hist_mode == GREM_HIST_SWEEP || (hist_mode == GREM_HIST_AUTO && n >= kSweepMinN));
         if (sweep) {
-            lay = make_layout(n, nnz, k, chunk, external_E, col_bits);
+            lay = make_layout(n, nnz, k, chunk, external_E, col_bits, hub_degree);
+            sweep_lds = ((size_t)((kSliceRows * k + 1) >> 1) + (size_t)share_hubs * k +
+                         2 * ((size_t)ncs + 1) + (size_t)k) * 4;
+            // two workgroups per CU must fit the 160 KB of LDS; one share may touch kMaxShareHubs hubs
+            const bool fits = sweep_lds <= 80 * 1024 && share_hubs <= kMaxShareHubs &&
+                              (size_t)max_chunk_hubs <= lay.hub_rows_cap;
+            if (!fits) {
+                if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
+                sweep = false;
+            }
+        }
+        if (sweep) {
             char *xbase = nullptr;
             if (g.ws) {
                 if (g.ws_bytes >= lay.total_sweep) xbase = ws;
@@ -233,26 +314,32 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
             if (sweep) {
                 Ln = (uint8_t *)(xbase + lay.Ln);
                 boff = (uint32_t *)(xbase + lay.boff);
+                hboff = (uint32_t *)(xbase + lay.hboff);
+                Hhub = (uint32_t *)(xbase + lay.Hhub);
                 tup = (uint32_t *)(xbase + lay.tup);
-                sweep_lds = ((size_t)((kSliceRows * k + 1) >> 1) + (size_t)ncs + 1 + (size_t)k) * 4;
+                if (hipMemsetAsync(Hhub, 0, lay.hub_rows_cap * (size_t)k * 4, stream) != hipSuccess) {
+                    release();
+                    return GREM_ERR_HIP;
+                }
                 if (sweep_lds > 64 * 1024) {
                     if (hipFuncSetAttribute((const void *)k_score_sweep<RowT, true>,
                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)sweep_lds) != hipSuccess ||
-                        hipFuncSetAttribute((const void *)k_score_sweep<RowT, false>,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                             (int)sweep_lds) != hipSuccess) { release(); return GREM_ERR_HIP; }
                 }
-                const size_t relayout_lds = ((size_t)kSliceRows + 1 + (size_t)ncs) * 4;
+                const unsigned G = (unsigned)(nchunks * nsl);
+                const size_t reg_lds = ((size_t)kSliceRows + 1 + (size_t)ncs) * 4;
+                const size_t hub_lds = (size_t)((ncs + 1) & ~1) * 4 + (size_t)(2 * kMaxShareHubs + 1) * 8;
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_relayout<RowT>), dim3((unsigned)(nchunks * nsl)), dim3(256),
-                                       relayout_lds, stream, rowptr, colidx, n, chunk, nsl, ncs, col_bits,
-                                       tup, boff);
+                    hipLaunchKernelGGL((k_relayout_regular<RowT>), dim3(G), dim3(256), reg_lds, stream, rowptr,
+                                       colidx, n, chunk, nsl, ncs, col_bits, (uint32_t)hub_degree, pl, tup,
+                                       boff);
+                });
+                L.run(GREM_KERNEL_RELAYOUT, [&] {
+                    hipLaunchKernelGGL((k_relayout_hubs<RowT>), dim3(G), dim3(256), hub_lds, stream, rowptr,
+                                       colidx, n, chunk, nsl, ncs, col_bits, pl, tup, hboff);
                 });
             }
         }
-    } else {
-        if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
     }
 
     auto pack = [&](int64_t lo, int64_t hi) {
@@ -281,10 +368,17 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                     const unsigned blocks = (unsigned)((len + kSliceRows - 1) / kSliceRows);
                     L.run(GREM_KERNEL_SCORE, [&] {
                         hipLaunchKernelGGL((k_score_sweep<RowT, true>), dim3(blocks), dim3(kSweepThreads),
-                                           sweep_lds, stream, rowptr, tup, boff, (const uint8_t *)Lc, Ln, S,
-                                           E, (uint8_t *)prop, lo, hi, (int)(c * nsl), (int)k, ncs, col_bits,
-                                           pass, P, gather_limit);
+                                           sweep_lds, stream, rowptr, tup, boff, hboff, pl,
+                                           (const uint8_t *)Lc, Ln, S, E, Hhub, (uint8_t *)prop, c, lo, hi, nsl,
+                                           (int)k, ncs, col_bits, share_hubs, (uint32_t)hub_degree, pass, P,
+                                           gather_limit);
                     });
+                    if (max_chunk_hubs > 0)
+                        L.run(GREM_KERNEL_HUBS, [&] {
+                            hipLaunchKernelGGL(k_hub_finalize, dim3((max_chunk_hubs + 255) / 256), dim3(256), 0,
+                                               stream, pl, (const uint8_t *)Lc, S, E, Hhub, (uint8_t *)prop, c,
+                                               lo, (int)k, pass, P);
+                        });
                 }
             } else if (use_lds) {
                 const unsigned score_blocks = (unsigned)((len + tv - 1) / tv);
@@ -387,7 +481,7 @@ int64_t grem_capacity(int64_t n, int32_t k, double balance_slack) {
 size_t grem_workspace_bytes(int64_t n, int64_t nnz, int32_t k, int64_t chunk) {
     if (n < 1 || nnz < 0 || k < 1 || k > GREM_MAX_K || chunk < 1) return 0;
     std::lock_guard<std::mutex> lock(g.mu);
-    const Layout lay = make_layout(n, nnz, k, chunk, false, g.sweep_col_bits);
+    const Layout lay = make_layout(n, nnz, k, chunk, false, g.sweep_col_bits, g.sweep_hub_degree);
     return (k <= kSweepMaxK) ? lay.total_sweep : lay.total;
 }
 
@@ -406,6 +500,13 @@ int grem_set_histogram_mode(int32_t mode) {
         return GREM_ERR_ARG;
     std::lock_guard<std::mutex> lock(g.mu);
     g.hist_mode = mode;
+    return GREM_OK;
+}
+
+int grem_set_sweep_hub_degree(int32_t degree) {
+    if (degree < 1 || degree > 65535) return GREM_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.sweep_hub_degree = degree;
     return GREM_OK;
 }
 
@@ -525,6 +626,7 @@ const char *grem_kernel_name(int32_t kernel_class) {
         case GREM_KERNEL_EXPAND: return "expand";
         case GREM_KERNEL_RELAYOUT: return "relayout";
         case GREM_KERNEL_PACK: return "pack";
+        case GREM_KERNEL_HUBS: return "hub_finalize";
         default: return "?";
     }
 }
