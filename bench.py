@@ -107,6 +107,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the extra instrumented step that times the score kernel")
+    ap.add_argument("--col-bits", type=int, default=0,
+                    help="log2 of the vertices per column block of the two-phase path (0 = library default)")
+    ap.add_argument("--hub-degree", type=int, default=0,
+                    help="degree from which a row is spread over the chunk's workgroups (0 = library default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; run with --gpus 1 "
@@ -129,6 +133,10 @@ def main():
     print(f"[bench] {g.name}: n={n} nnz={nnz} directed={g.directed_edges} generated in {t_gen:.1f}s",
           file=sys.stderr, flush=True)
 
+    if args.col_bits:
+        B.grem_set_sweep_col_bits(args.col_bits)
+    if args.hub_degree:
+        B.grem_set_sweep_hub_degree(args.hub_degree)
     ws = torch.empty(B.grem_workspace_bytes(n, nnz, k, chunk), dtype=torch.uint8, device=dev)
     B.grem_set_workspace(ws)
     labels = torch.empty(n, dtype=torch.int32, device=dev)
@@ -172,8 +180,14 @@ def main():
             per_class[B.kernel_name(c)] = {"ms": round(ms, 4), "launches": cnt}
         B.grem_profile_enable(False)
         B.grem_profile_reset()
+        # On the two-phase path the score of a chunk is two launches: the histogram/blend/arg-max
+        # kernel and the look-up kernel that prepares the next chunks' input; they are timed as one.
+        lookup_ms = per_class.get("lookup", {}).get("ms", 0.0)
+        if per_class.get("lookup", {}).get("launches", 0) > 0:
+            roofline["kernel"] = "k_tp_score+k_tp_lookup"
+            roofline["score_ms"], roofline["lookup_ms"] = round(score_ms, 4), round(lookup_ms, 4)
         bytes_per_launch = b_total / (passes * nchunks)
-        avg_launch_s = 1e-3 * score_ms / max(score_launches, 1)
+        avg_launch_s = 1e-3 * (score_ms + lookup_ms) / max(score_launches, 1)
         achieved = bytes_per_launch / avg_launch_s / 1e9
         roofline.update(achieved=achieved, frac=achieved / HBM_PEAK_GBPS,
                         avg_launch_us=1e6 * avg_launch_s, launches_per_step=score_launches,

@@ -61,10 +61,12 @@ extern "C" {
 #define GREM_HIST_AUTO 0     /* LDS when a tile of rows fits the LDS budget (k <= 128), else global */
 #define GREM_HIST_LDS 1      /* force LDS (error GREM_ERR_ARG if k > 128) */
 #define GREM_HIST_GLOBAL 2   /* force accumulation straight into E's rows in global memory */
-#define GREM_HIST_SWEEP 3    /* force the column-sliced path: a re-laid-out copy of the entries, LDS
-                                histograms, look-ups in column-slice order so that they hit L2
-                                (GREM_ERR_ARG unless k <= 16 and the plan fits LDS).  AUTO takes it
-                                for k <= 16 when the label table is larger than L2. */
+#define GREM_HIST_SWEEP 3    /* force the two-phase path: a re-laid-out copy of the entries; after a
+                                chunk is relabelled its labels are looked up, from LDS, for every
+                                entry that refers to them, and the rows' workgroups later count
+                                the stored results into LDS histograms (GREM_ERR_ARG unless
+                                k <= 16 and the plan fits its limits).  AUTO takes it for k <= 16
+                                when the label table is larger than L2 and chunks are large. */
 
 /* Sec. 4.1 (Alg. 1 with all nodes unassigned at the start).  rowptr: n+1 entries; colidx:
  * rowptr[n] entries; labels_out: n entries, each in [0,k) on completion. */
@@ -122,11 +124,12 @@ int grem_set_workspace(void *dev_ptr, size_t bytes);
 /* GREM_HIST_*; returns GREM_ERR_ARG for an unknown mode.  Process-wide. */
 int grem_set_histogram_mode(int32_t mode);
 
-/* Width in bits of a column slice of the column-sliced path, 4..21 (default 21: 2^21 labels, 1 MB
- * packed).  Smaller values only make sense for testing on small graphs.  Process-wide. */
+/* log2 of the vertices per column block of the two-phase path: 0 = automatic (default: 17, i.e.
+ * 64 KB of LDS with two labels per byte, or less when chunks are shorter), else 4..18.  Small
+ * values only make sense for testing on small graphs.  Process-wide. */
 int grem_set_sweep_col_bits(int32_t bits);
 
-/* Rows of at least this many entries are "hubs" of the column-sliced path: their entries are
+/* Rows of at least this many entries are "hubs" of the two-phase path: their entries are
  * spread evenly over the chunk's workgroups.  1..65535, default 2048; smaller values only make
  * sense for testing on small graphs.  Process-wide. */
 int grem_set_sweep_hub_degree(int32_t degree);
@@ -136,16 +139,17 @@ int grem_set_sweep_hub_degree(int32_t degree);
  * the recorded events, adds up the launches of one kernel class since the last grem_profile_reset,
  * and returns total milliseconds and the launch count.  Classes: */
 #define GREM_KERNEL_PREPASS 0
-#define GREM_KERNEL_SCORE 1      /* row stream + label gather + histogram + blend + argmax */
+#define GREM_KERNEL_SCORE 1      /* row stream + label gather + histogram + blend + argmax; on the
+                                    two-phase path: histogram of stored look-ups + blend + argmax */
 #define GREM_KERNEL_COUNT 2
 #define GREM_KERNEL_SCAN 3
 #define GREM_KERNEL_APPLY 4
 #define GREM_KERNEL_SPILL_SCAN 5
 #define GREM_KERNEL_SPILL_FILL 6
 #define GREM_KERNEL_EXPAND 7
-#define GREM_KERNEL_RELAYOUT 8   /* one-time planning and re-layout of the entries (column-sliced path) */
-#define GREM_KERNEL_PACK 9       /* two-labels-per-byte copy of the labels */
-#define GREM_KERNEL_HUBS 10      /* blend and proposal of the high-degree rows of the column-sliced path */
+#define GREM_KERNEL_RELAYOUT 8   /* one-time planning and re-layout of the entries (two-phase path) */
+#define GREM_KERNEL_LOOKUP 9     /* two-phase path: label look-ups for the entries that refer to a chunk */
+#define GREM_KERNEL_HUBS 10      /* blend and proposal of the high-degree rows of the two-phase path */
 #define GREM_KERNEL_CLASSES 11
 int grem_profile_enable(int32_t on);
 int grem_profile_reset(void);

@@ -12,7 +12,7 @@
 #include <vector>
 
 #include "grem_kernels.hip.h"
-#include "grem_sweep.hip.h"
+#include "grem_twophase.hip.h"
 
 namespace {
 
@@ -20,15 +20,18 @@ using namespace grem;
 
 constexpr int kLdsHistBytes = 32 * 1024;   // LDS spent on one tile's histograms
 constexpr int kLdsMaxK = 128;              // above this the histograms live in E's rows
-constexpr int kSweepMaxK = 16;             // column-sliced path: 16-bit counters, 2048 rows, 64 KB
+constexpr int kSweepMaxK = 16;             // two-phase path: 4-bit labels, 16-bit counters, 2048 rows, 64 KB
 constexpr int64_t kSweepMinN = 1 << 22;    // AUTO: label table must exceed L2 for the path to pay
+constexpr int64_t kSweepMinChunk = 1 << 14;   // AUTO: per-chunk launches must have work to do
+constexpr int kDefaultColBits = 17;        // 2^17 labels, two per byte: 64 KB of LDS, two workgroups per CU
+constexpr int64_t kMaxSegments = 1ll << 22;   // chunks * column blocks
 
 struct Global {
     std::mutex mu;
     void *ws = nullptr;
     size_t ws_bytes = 0;
     int hist_mode = GREM_HIST_AUTO;
-    int sweep_col_bits = 21;
+    int sweep_col_bits = 0;                // 0 = automatic
     int sweep_hub_degree = 2048;
     bool prof = false;
     struct Ev { int cls; hipEvent_t a, b; };
@@ -39,23 +42,51 @@ Global g;
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// Geometry of the two-phase path: chunks, row slices and column blocks (see grem_twophase.hip.h).
+struct TpGeom {
+    int cb = 0, nbc = 0, nblk = 0, nch = 0, nsl = 0, shift = -1;
+    uint32_t chunk = 0;
+    bool ok = false;
+};
+
+TpGeom tp_geometry(int64_t n, int64_t chunk, int col_bits_setting) {
+    TpGeom t;
+    const int64_t cl = chunk < n ? chunk : n;
+    const int64_t nch = (n + cl - 1) / cl;
+    const int64_t nsl = (cl + kSliceRows - 1) / kSliceRows;
+    int cb = col_bits_setting;
+    if (cb == 0) {
+        cb = 4;
+        while (cb < kDefaultColBits && (1ll << cb) < cl) ++cb;
+    }
+    const int64_t nbc = (cl + (1ll << cb) - 1) >> cb;
+    const int64_t nblk = nch * nbc;
+    t.cb = cb;
+    t.chunk = (uint32_t)cl;
+    for (int b = 0; b < 31; ++b)
+        if ((1ll << b) == cl) t.shift = b;
+    t.ok = nblk <= kMaxBlocks && nch * nblk <= kMaxSegments && nch * nsl < (1ll << 31) &&
+           nch * (nsl + 1) * nblk < (1ll << 40);
+    if (t.ok) { t.nbc = (int)nbc; t.nblk = (int)nblk; t.nch = (int)nch; t.nsl = (int)nsl; }
+    return t;
+}
+
 struct Layout {
     size_t E, Lc, prop, S, cnt, room, ocnt, fillRank, fillSorted, fillC, misc;
-    // plan of the column-sliced path (k <= 16 only)
+    // plan of the two-phase path (k <= 16 only)
     size_t sl_reg_cnt, sl_reg_start, sl_nh, sl_hub_start, sl_hent, sl_hent_start, share_h0, share_nhs,
         ch_regtot, ch_nh, ch_H, hub_row, hub_off;
     size_t total;
-    size_t Ln, boff, hboff, Hhub, tup, total_sweep;   // extras of the column-sliced path, after `total`
-    size_t hub_rows_cap;                              // rows of Hhub
+    size_t subR, subH, xstart, tstart, Hhub, T, X, total_sweep;   // extras of the two-phase path, after `total`
+    size_t hub_rows_cap;                                          // rows of Hhub
 };
 
 inline int64_t slices_per_chunk(int64_t n, int64_t chunk) {
     const int64_t cl = chunk < n ? chunk : n;
     return (cl + kSliceRows - 1) / kSliceRows;
 }
-inline int col_slices(int64_t n, int col_bits) { return (int)((n + (1ll << col_bits) - 1) >> col_bits); }
 
-Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool external_E, int col_bits,
+Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool external_E, const TpGeom &tp,
                    int hub_degree) {
     Layout L{};
     const int64_t cl = chunk < n ? chunk : n;
@@ -76,7 +107,8 @@ Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool extern
     L.fillSorted = take((size_t)k * 8);
     L.fillC = take(((size_t)k + 1) * 8);
     L.misc = take(8 * 8);
-    if (k <= kSweepMaxK) {
+    const bool tp_possible = k <= kSweepMaxK && tp.ok;
+    if (tp_possible) {
         L.sl_reg_cnt = take(G * 4);
         L.sl_reg_start = take(G * 8);
         L.sl_nh = take(G * 4);
@@ -92,15 +124,22 @@ Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool extern
         L.hub_off = take((size_t)(n + nchunks) * 8);
     }
     L.total = off;
-    // a chunk cannot hold more hubs than rows, nor more than entries / hub_degree
-    size_t hubs = (size_t)(nnz / (hub_degree > 0 ? hub_degree : 1)) + 1;
-    if (hubs > (size_t)cl) hubs = (size_t)cl;
-    L.hub_rows_cap = hubs;
-    L.Ln = take((size_t)(n / 2 + 1));
-    L.boff = take(G * ((size_t)col_slices(n, col_bits) + 1) * 4);
-    L.hboff = take(G * ((size_t)col_slices(n, col_bits) + 1) * 4);
-    L.Hhub = take(hubs * (size_t)k * 4);
-    L.tup = take((size_t)(nnz > 0 ? nnz : 1) * 4);
+    if (tp_possible) {
+        // a chunk cannot hold more hubs than rows, nor more than entries / hub_degree
+        size_t hubs = (size_t)(nnz / (hub_degree > 0 ? hub_degree : 1)) + 1;
+        if (hubs > (size_t)cl) hubs = (size_t)cl;
+        L.hub_rows_cap = hubs;
+        const size_t segs = (size_t)tp.nch * (size_t)tp.nblk;
+        const size_t rows = (size_t)tp.nch * ((size_t)tp.nsl + 1);
+        const size_t slots = (size_t)(nnz > 0 ? nnz : 0) + 8 * segs;      // every segment padded to 8
+        L.subR = take(rows * (size_t)tp.nblk * 4);
+        L.subH = take(rows * (size_t)tp.nblk * 4);
+        L.xstart = take((segs + 1) * 8);
+        L.tstart = take((segs + 1) * 8);
+        L.Hhub = take(hubs * (size_t)k * 4);
+        L.T = take(slots * 4 + 16);
+        L.X = take(slots * 2 + 16);
+    }
     L.total_sweep = off;
     return L;
 }
@@ -148,13 +187,13 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                   int64_t *sizes_out, uint32_t *estimates_out, hipStream_t stream) {
     const long long P = grem_capacity(n, k, slack);
     const bool external_E = estimates_out != nullptr;
-    const int col_bits = g.sweep_col_bits;
     const int hub_degree = g.sweep_hub_degree;
-    Layout lay = make_layout(n, 0, k, chunk, external_E, col_bits, hub_degree);
+    const TpGeom geo = tp_geometry(n, chunk, g.sweep_col_bits);
+    Layout lay = make_layout(n, 0, k, chunk, external_E, geo, hub_degree);
 
     const int hist_mode = g.hist_mode;
     if (hist_mode == GREM_HIST_LDS && k > kLdsMaxK) return GREM_ERR_ARG;
-    if (hist_mode == GREM_HIST_SWEEP && k > kSweepMaxK) return GREM_ERR_ARG;
+    if (hist_mode == GREM_HIST_SWEEP && (k > kSweepMaxK || !geo.ok)) return GREM_ERR_ARG;
     const bool use_lds = hist_mode != GREM_HIST_GLOBAL && k <= kLdsMaxK;
 
     // workspace
@@ -204,18 +243,16 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                                P, misc);
         });
     }
-    // plan of the column-sliced path (needs only rowptr, so it runs before the read-back)
+    // plan of the two-phase path (needs only rowptr, so it runs before the read-back)
     const int64_t nchunks = (n + chunk - 1) / chunk;
     const int nsl = (int)slices_per_chunk(n, chunk);
-    const int ncs = col_slices(n, col_bits);
     bool sweep = false;
     SweepPlan pl{};
     if constexpr (sizeof(LabelT) == 1) {
-        const bool can = k <= kSweepMaxK && ncs <= kMaxColSlices && nchunks * (int64_t)nsl < (1ll << 31) &&
-                         (((uintptr_t)E) & 15u) == 0;
+        const bool can = k <= kSweepMaxK && geo.ok && (((uintptr_t)E) & 15u) == 0;
         if (hist_mode == GREM_HIST_SWEEP && !can) { release(); return GREM_ERR_ARG; }
-        sweep = can && (hist_mode == GREM_HIST_SWEEP || (hist_mode == GREM_HIST_AUTO && n >= kSweepMinN));
-        if (seed && R == 0) sweep = false;      // the only pass runs on the plain path
+        sweep = can && (hist_mode == GREM_HIST_SWEEP ||
+                        (hist_mode == GREM_HIST_AUTO && n >= kSweepMinN && (int64_t)geo.chunk >= kSweepMinChunk));
         if (sweep) {
             pl.sl_reg_cnt = (uint32_t *)(ws + lay.sl_reg_cnt);
             pl.sl_reg_start = (u64 *)(ws + lay.sl_reg_start);
@@ -231,20 +268,21 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
             pl.hub_row = (int32_t *)(ws + lay.hub_row);
             pl.hub_off = (u64 *)(ws + lay.hub_off);
             const unsigned G = (unsigned)(nchunks * nsl);
+            const int64_t cl = (int64_t)geo.chunk;
             L.run(GREM_KERNEL_RELAYOUT, [&] {
-                hipLaunchKernelGGL((k_plan_slices<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, chunk, nsl,
+                hipLaunchKernelGGL((k_plan_slices<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, cl, nsl,
                                    (uint32_t)hub_degree, pl);
             });
             L.run(GREM_KERNEL_RELAYOUT, [&] {
-                hipLaunchKernelGGL(k_plan_chunks, dim3((unsigned)nchunks), dim3(256), 0, stream, n, chunk, nsl,
+                hipLaunchKernelGGL(k_plan_chunks, dim3((unsigned)nchunks), dim3(256), 0, stream, n, cl, nsl,
                                    pl, misc);
             });
             L.run(GREM_KERNEL_RELAYOUT, [&] {
-                hipLaunchKernelGGL((k_plan_hubs<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, chunk, nsl,
+                hipLaunchKernelGGL((k_plan_hubs<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, cl, nsl,
                                    (uint32_t)hub_degree, pl);
             });
             L.run(GREM_KERNEL_RELAYOUT, [&] {
-                hipLaunchKernelGGL(k_plan_shares, dim3((G + 255) / 256), dim3(256), 0, stream, n, chunk, nsl,
+                hipLaunchKernelGGL(k_plan_shares, dim3((G + 255) / 256), dim3(256), 0, stream, n, cl, nsl,
                                    (int)G, pl, misc);
             });
         }
@@ -276,20 +314,27 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
         hipFuncSetAttribute((const void *)k_apply<LabelT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)apply_lds) != hipSuccess) { release(); return GREM_ERR_HIP; }
 
-    // ---- column-sliced path: allocate its extras, re-lay-out the entries once
-    uint8_t *Ln = nullptr;
-    uint32_t *boff = nullptr, *hboff = nullptr, *tup = nullptr, *Hhub = nullptr;
-    size_t sweep_lds = 0;
+    // ---- two-phase path: allocate its extras, re-lay-out the entries once
+    TpTables tb{};
+    uint32_t *T = nullptr, *Hhub = nullptr;
+    uint16_t *X = nullptr;
+    size_t tp_score_lds = 0, tp_lookup_lds = 0;
     const int share_hubs = (int)h_misc[5];
     const unsigned max_chunk_hubs = (unsigned)h_misc[6];
+    int lookup_target = 256;                 // workgroups of one look-up launch
     if constexpr (sizeof(LabelT) == 1) {
+        auto set_lds = [&](const void *f, size_t bytes) {
+            return bytes <= 64 * 1024 ||
+                   hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+        };
         if (sweep) {
-            lay = make_layout(n, nnz, k, chunk, external_E, col_bits, hub_degree);
-            sweep_lds = ((size_t)((kSliceRows * k + 1) >> 1) + (size_t)share_hubs * k +
-                         2 * ((size_t)ncs + 1) + (size_t)k) * 4;
-            // two workgroups per CU must fit the 160 KB of LDS; one share may touch kMaxShareHubs hubs
-            const bool fits = sweep_lds <= 80 * 1024 && share_hubs <= kMaxShareHubs &&
-                              (size_t)max_chunk_hubs <= lay.hub_rows_cap;
+            lay = make_layout(n, nnz, k, chunk, external_E, geo, hub_degree);
+            tp_score_lds = ((size_t)((kSliceRows * k + 1) >> 1) + (size_t)share_hubs * k + (size_t)k) * 4;
+            tp_lookup_lds = (size_t)1 << (geo.cb > 5 ? geo.cb - 1 : 4);
+            // two score workgroups per CU must fit the 160 KB of LDS; one share may touch kMaxShareHubs
+            // hubs; sub-segment offsets are 32-bit
+            const bool fits = tp_score_lds <= 80 * 1024 && share_hubs <= kMaxShareHubs &&
+                              (size_t)max_chunk_hubs <= lay.hub_rows_cap && h_misc[7] < (1ull << 32) - 8ull * geo.nblk;
             if (!fits) {
                 if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
                 sweep = false;
@@ -312,66 +357,106 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 }
             }
             if (sweep) {
-                Ln = (uint8_t *)(xbase + lay.Ln);
-                boff = (uint32_t *)(xbase + lay.boff);
-                hboff = (uint32_t *)(xbase + lay.hboff);
+                tb.subR = (uint32_t *)(xbase + lay.subR);
+                tb.subH = (uint32_t *)(xbase + lay.subH);
+                tb.xstart = (u64 *)(xbase + lay.xstart);
+                tb.tstart = (u64 *)(xbase + lay.tstart);
+                tb.chunk = geo.chunk;
+                tb.chunk_shift = geo.shift;
+                tb.nch = geo.nch;
+                tb.nsl = geo.nsl;
+                tb.nbc = geo.nbc;
+                tb.nblk = geo.nblk;
+                tb.cb = geo.cb;
                 Hhub = (uint32_t *)(xbase + lay.Hhub);
-                tup = (uint32_t *)(xbase + lay.tup);
-                if (hipMemsetAsync(Hhub, 0, lay.hub_rows_cap * (size_t)k * 4, stream) != hipSuccess) {
+                T = (uint32_t *)(xbase + lay.T);
+                X = (uint16_t *)(xbase + lay.X);
+                const size_t reg_lds = (size_t)geo.nblk * 8 + ((size_t)kSliceRows + 1) * 4;
+                const size_t hub_lds = (size_t)geo.nblk * 8 + (size_t)(2 * kMaxShareHubs + 1) * 8;
+                if (hipMemsetAsync(Hhub, 0, lay.hub_rows_cap * (size_t)k * 4, stream) != hipSuccess ||
+                    !set_lds((const void *)k_tp_layout_regular<RowT, false>, reg_lds) ||
+                    !set_lds((const void *)k_tp_layout_regular<RowT, true>, reg_lds) ||
+                    !set_lds((const void *)k_tp_layout_hubs<RowT, false>, hub_lds) ||
+                    !set_lds((const void *)k_tp_layout_hubs<RowT, true>, hub_lds) ||
+                    !set_lds((const void *)k_tp_lookup<true>, tp_lookup_lds) ||
+                    !set_lds((const void *)k_tp_score<RowT>, tp_score_lds)) {
                     release();
                     return GREM_ERR_HIP;
                 }
-                if (sweep_lds > 64 * 1024) {
-                    if (hipFuncSetAttribute((const void *)k_score_sweep<RowT, true>,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)sweep_lds) != hipSuccess) { release(); return GREM_ERR_HIP; }
-                }
+                lookup_target = tp_lookup_lds > 80 * 1024 ? 256 : 512;
                 const unsigned G = (unsigned)(nchunks * nsl);
-                const size_t reg_lds = ((size_t)kSliceRows + 1 + (size_t)ncs) * 4;
-                const size_t hub_lds = (size_t)((ncs + 1) & ~1) * 4 + (size_t)(2 * kMaxShareHubs + 1) * 8;
+                const unsigned segs = (unsigned)((int64_t)geo.nch * geo.nblk);
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_relayout_regular<RowT>), dim3(G), dim3(256), reg_lds, stream, rowptr,
-                                       colidx, n, chunk, nsl, ncs, col_bits, (uint32_t)hub_degree, pl, tup,
-                                       boff);
+                    hipLaunchKernelGGL((k_tp_layout_regular<RowT, false>), dim3(G), dim3(256), reg_lds, stream,
+                                       rowptr, colidx, n, (uint32_t)hub_degree, pl, tb, T);
                 });
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_relayout_hubs<RowT>), dim3(G), dim3(256), hub_lds, stream, rowptr,
-                                       colidx, n, chunk, nsl, ncs, col_bits, pl, tup, hboff);
+                    hipLaunchKernelGGL((k_tp_layout_hubs<RowT, false>), dim3(G), dim3(256), hub_lds, stream,
+                                       rowptr, colidx, n, pl, tb, T);
+                });
+                L.run(GREM_KERNEL_RELAYOUT, [&] {
+                    hipLaunchKernelGGL(k_tp_scan_slices, dim3((segs + 255) / 256), dim3(256), 0, stream, tb);
+                });
+                L.run(GREM_KERNEL_RELAYOUT, [&] {
+                    hipLaunchKernelGGL(k_tp_scan_segments, dim3(2), dim3(1024), 0, stream, tb);
+                });
+                L.run(GREM_KERNEL_RELAYOUT, [&] {
+                    hipLaunchKernelGGL((k_tp_layout_regular<RowT, true>), dim3(G), dim3(256), reg_lds, stream,
+                                       rowptr, colidx, n, (uint32_t)hub_degree, pl, tb, T);
+                });
+                L.run(GREM_KERNEL_RELAYOUT, [&] {
+                    hipLaunchKernelGGL((k_tp_layout_hubs<RowT, true>), dim3(G), dim3(256), hub_lds, stream,
+                                       rowptr, colidx, n, pl, tb, T);
                 });
             }
         }
     }
 
-    auto pack = [&](int64_t lo, int64_t hi) {
+    // look-ups of the labels of chunks [c0, c0 + count): shares per column block sized so that one
+    // launch fills the chip without cutting the blocks' streams into crumbs
+    auto lookup = [&](int c0, int count, int cmin, bool from_lds) {
         if constexpr (sizeof(LabelT) == 1) {
-            int64_t blocks = ((hi - lo) / 2 + 256) / 256;
-            if (blocks > 4096) blocks = 4096;
-            L.run(GREM_KERNEL_PACK, [&] {
-                hipLaunchKernelGGL(k_pack, dim3((unsigned)blocks), dim3(256), 0, stream,
-                                   (const uint8_t *)Lc, Ln, lo, hi, n);
+            if (cmin >= geo.nch) return;
+            const int64_t per_block = nnz / geo.nblk + 1;
+            int spb = lookup_target / geo.nbc;
+            const int64_t by_work = per_block / 8192 + 1;
+            if (spb > by_work) spb = (int)by_work;
+            if (spb < 1) spb = 1;
+            L.run(GREM_KERNEL_LOOKUP, [&] {
+                if (from_lds)
+                    hipLaunchKernelGGL((k_tp_lookup<true>), dim3((unsigned)(geo.nbc * spb), (unsigned)count),
+                                       dim3(kTpThreads), tp_lookup_lds, stream, T, X, tb, (const uint8_t *)Lc, n,
+                                       c0, cmin, spb);
+                else
+                    hipLaunchKernelGGL((k_tp_lookup<false>), dim3((unsigned)(geo.nbc * spb), (unsigned)count),
+                                       dim3(kTpThreads), 0, stream, T, X, tb, (const uint8_t *)Lc, n, c0, cmin,
+                                       spb);
             });
         }
     };
+    if (sweep && seed) {        // the seeds are the labels every first-pass look-up starts from
+        for (int c0 = 0; c0 < geo.nch; c0 += 32768) {
+            const int count = geo.nch - c0 < 32768 ? geo.nch - c0 : 32768;
+            lookup(c0, count, 0, false);
+        }
+    }
 
     for (int pass = 0; pass <= R && !L.err; ++pass) {
-        // packed labels are valid for look-ups once nothing that is looked up is unassigned
-        const bool sweep_now = sweep && (pass >= 1 || !seed);
-        if (sweep && seed && pass == 1) pack(0, n);
         for (int64_t c = 0; c < nchunks && !L.err; ++c) {
             const int64_t lo = c * chunk;
             const int64_t hi = (lo + chunk < n) ? lo + chunk : n;
             const int64_t len = hi - lo;
             const int64_t gather_limit = (pass == 0 && !seed) ? lo : n;
             const unsigned admit_blocks = (unsigned)((len + kAdmitTile - 1) / kAdmitTile);
-            if (sweep_now) {
+            if (sweep) {
                 if constexpr (sizeof(LabelT) == 1) {
                     const unsigned blocks = (unsigned)((len + kSliceRows - 1) / kSliceRows);
+                    const int jlim = (pass == 0 && !seed) ? (int)c * geo.nbc : geo.nblk;
                     L.run(GREM_KERNEL_SCORE, [&] {
-                        hipLaunchKernelGGL((k_score_sweep<RowT, true>), dim3(blocks), dim3(kSweepThreads),
-                                           sweep_lds, stream, rowptr, tup, boff, hboff, pl,
-                                           (const uint8_t *)Lc, Ln, S, E, Hhub, (uint8_t *)prop, c, lo, hi, nsl,
-                                           (int)k, ncs, col_bits, share_hubs, (uint32_t)hub_degree, pass, P,
-                                           gather_limit);
+                        hipLaunchKernelGGL((k_tp_score<RowT>), dim3(blocks), dim3(kTpThreads), tp_score_lds,
+                                           stream, rowptr, X, tb, pl, (const uint8_t *)Lc, S, E, Hhub,
+                                           (uint8_t *)prop, (int)c, lo, hi, (int)k, jlim, share_hubs,
+                                           (uint32_t)hub_degree, pass, P);
                     });
                     if (max_chunk_hubs > 0)
                         L.run(GREM_KERNEL_HUBS, [&] {
@@ -419,7 +504,9 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                                        (unsigned long long *)S, misc);
                 });
             }
-            if (sweep_now && !(pass == R && c == nchunks - 1)) pack(lo, hi);
+            // the chunk's new labels, looked up for every row that will read them: rows of later
+            // chunks in this pass, rows of this and earlier chunks in the next pass (if there is one)
+            if (sweep) lookup((int)c, 1, pass == R ? (int)c + 1 : 0, true);
         }
     }
     {
@@ -481,8 +568,9 @@ int64_t grem_capacity(int64_t n, int32_t k, double balance_slack) {
 size_t grem_workspace_bytes(int64_t n, int64_t nnz, int32_t k, int64_t chunk) {
     if (n < 1 || nnz < 0 || k < 1 || k > GREM_MAX_K || chunk < 1) return 0;
     std::lock_guard<std::mutex> lock(g.mu);
-    const Layout lay = make_layout(n, nnz, k, chunk, false, g.sweep_col_bits, g.sweep_hub_degree);
-    return (k <= kSweepMaxK) ? lay.total_sweep : lay.total;
+    const TpGeom geo = tp_geometry(n, chunk, g.sweep_col_bits);
+    const Layout lay = make_layout(n, nnz, k, chunk, false, geo, g.sweep_hub_degree);
+    return lay.total_sweep;
 }
 
 int grem_set_workspace(void *dev_ptr, size_t bytes) {
@@ -511,7 +599,7 @@ int grem_set_sweep_hub_degree(int32_t degree) {
 }
 
 int grem_set_sweep_col_bits(int32_t bits) {
-    if (bits < 4 || bits > 32 - kSliceRowBits) return GREM_ERR_ARG;
+    if (bits != 0 && (bits < 4 || bits > kMaxColBits)) return GREM_ERR_ARG;
     std::lock_guard<std::mutex> lock(g.mu);
     g.sweep_col_bits = bits;
     return GREM_OK;
@@ -625,7 +713,7 @@ const char *grem_kernel_name(int32_t kernel_class) {
         case GREM_KERNEL_SPILL_FILL: return "spill_fill";
         case GREM_KERNEL_EXPAND: return "expand";
         case GREM_KERNEL_RELAYOUT: return "relayout";
-        case GREM_KERNEL_PACK: return "pack";
+        case GREM_KERNEL_LOOKUP: return "lookup";
         case GREM_KERNEL_HUBS: return "hub_finalize";
         default: return "?";
     }

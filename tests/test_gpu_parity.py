@@ -24,7 +24,7 @@ def _to_dev(g, rowptr_dtype=None):
     return rp.to(DEV), torch.as_tensor(np.asarray(g.colidx)).to(DEV)
 
 
-def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO, tag="", col_bits=21, hub_degree=2048):
+def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO, tag="", col_bits=0, hub_degree=2048):
     """Runs both sides on the same graph and compares everything."""
     g = synth.to_numpy(g)
     print(f"[case] {tag} {g.name} n={g.n} nnz={g.nnz} k={k} slack={slack} chunk={chunk} R={R} "
@@ -40,7 +40,7 @@ def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO
         torch.cuda.synchronize()
     finally:
         B.grem_set_histogram_mode(B.HIST_AUTO)
-        B.grem_set_sweep_col_bits(21)
+        B.grem_set_sweep_col_bits(0)
         B.grem_set_sweep_hub_degree(2048)
     olab, osizes, oest = oracle.partition_seeded(g.rowptr, g.colidx, g.n, k, slack, chunk, R, seed,
                                                  return_state=True)
@@ -122,22 +122,25 @@ def test_forced_global_histograms_match(k):
 
 
 @pytest.mark.parametrize("k", [1, 2, 3, 8, 13, 16])
-@pytest.mark.parametrize("col_bits", [4, 9, 21])
-def test_column_sliced_path_small(k, col_bits):
+@pytest.mark.parametrize("col_bits", [4, 9, 0])
+def test_two_phase_path_small(k, col_bits):
     g = synth.rmat(13, 16, seed=3, rowptr_dtype=torch.int64)
     _check(g, k, 1.05, 3000, 2, mode=B.HIST_SWEEP, col_bits=col_bits)                  # no hubs
     _check(g, k, 1.05, 3000, 2, mode=B.HIST_SWEEP, col_bits=col_bits, hub_degree=200)  # some rows are hubs
     _check(g, k, 1.2, 5000, 1, mode=B.HIST_SWEEP, col_bits=col_bits, rowptr_dtype=torch.int32, hub_degree=300)
 
 
-def test_column_sliced_path_seeded_and_edge_cases():
+def test_two_phase_path_seeded_and_edge_cases():
     g = synth.planted_partition(n=6000, blocks=3, seed=2, rowptr_dtype=np.int64)
     rng = np.random.default_rng(0)
     seed = np.where(rng.random(g.n) < 0.3, g.planted, -1).astype(np.int32)
     _check(g, 3, 1.05, 2500, 2, seed=seed, mode=B.HIST_SWEEP, col_bits=6, tag="30% seeded")
     _check(g, 3, 1.05, 2500, 2, seed=seed, mode=B.HIST_SWEEP, col_bits=6, hub_degree=14, tag="30% seeded, hubs")
     _check(g, 3, 1.05, 2500, 0, seed=seed, mode=B.HIST_SWEEP, col_bits=6, tag="seeded R=0")
-    _check(g, 4, 1.05, 1, 1, mode=B.HIST_SWEEP, col_bits=5, hub_degree=12, tag="chunk=1")
+    small = synth.planted_partition(n=1500, blocks=3, seed=4, rowptr_dtype=np.int64)
+    _check(small, 4, 1.05, 1, 1, mode=B.HIST_SWEEP, col_bits=5, hub_degree=12, tag="chunk=1")
+    _check(small, 5, 1.05, 7, 2, mode=B.HIST_SWEEP, col_bits=4, hub_degree=12, tag="chunk=7")
+    _check(g, 16, 1.05, 3000, 2, mode=B.HIST_SWEEP, col_bits=18, tag="largest column block")
     _check(g, 16, 1.0, 2049, 3, mode=B.HIST_SWEEP, col_bits=7, hub_degree=16, tag="odd chunk")
     _check(g, 2, 1.0, 6000, 2, mode=B.HIST_SWEEP, col_bits=7, hub_degree=1, tag="every row a hub")
     e = synth.Graph(np.zeros(5001, dtype=np.int64), np.zeros(0, dtype=np.int32), 5000, 0, 0, None, "edgeless")
@@ -148,13 +151,13 @@ def test_column_sliced_path_seeded_and_edge_cases():
     _check(h, 7, 1.1, 8192, 1, mode=B.HIST_SWEEP, col_bits=10, hub_degree=40)
 
 
-def test_column_sliced_path_big_hub():
+def test_two_phase_path_big_hub():
     # one row longer than 65535 entries: 16-bit counters would overflow if it were not a hub
     h = synth.hub_stress(scale=17, edge_factor=4, hubs=2, hub_degree=100_000, seed=1, rowptr_dtype=torch.int64)
     _check(h, 16, 1.1, 1 << 15, 2, mode=B.HIST_SWEEP, col_bits=12)
 
 
-def test_column_sliced_path_errors():
+def test_two_phase_path_errors():
     g = synth.random_graph_np(100, 300, 0)
     rp, ci = _to_dev(g)
     B.grem_set_histogram_mode(B.HIST_SWEEP)
@@ -199,7 +202,7 @@ def test_chung_lu_medium():
     _check(g, 16, 1.05, 1 << 16, 2, mode=B.HIST_SWEEP, col_bits=17)
 
 
-def test_chung_lu_auto_takes_column_sliced_path():
+def test_chung_lu_auto_takes_two_phase_path():
     g = synth.chung_lu(6_000_000, 60_000_000, seed=1, device=DEV, rowptr_dtype=torch.int64, cap=30_000.0)
     _check(g, 16, 1.05, 1 << 19, 2)
 
