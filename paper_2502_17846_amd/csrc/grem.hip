@@ -44,7 +44,7 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 // Geometry of the two-phase path: chunks, row slices and column blocks (see grem_twophase.hip.h).
 struct TpGeom {
-    int cb = 0, nbc = 0, nblk = 0, nch = 0, nsl = 0, shift = -1;
+    int cb = 0, nbc = 0, nblk = 0, nch = 0, nsl = 0, shift = -1, gb = 0, ngroups = 1;
     uint32_t chunk = 0;
     bool ok = false;
 };
@@ -67,7 +67,12 @@ TpGeom tp_geometry(int64_t n, int64_t chunk, int col_bits_setting) {
         if ((1ll << b) == cl) t.shift = b;
     t.ok = nblk <= kMaxBlocks && nch * nblk <= kMaxSegments && nch * nsl < (1ll << 31) &&
            nch * (nsl + 1) * nblk < (1ll << 40);
-    if (t.ok) { t.nbc = (int)nbc; t.nblk = (int)nblk; t.nch = (int)nch; t.nsl = (int)nsl; }
+    if (t.ok) {
+        t.nbc = (int)nbc; t.nblk = (int)nblk; t.nch = (int)nch; t.nsl = (int)nsl;
+        // the intermediate copy keeps row (11 bits), block in group (gb) and column in block (cb) in 32 bits
+        while (t.gb < 21 - cb && (1ll << t.gb) < nblk) ++t.gb;
+        t.ngroups = (int)((nblk + (1ll << t.gb) - 1) >> t.gb);
+    }
     return t;
 }
 
@@ -75,9 +80,9 @@ struct Layout {
     size_t E, Lc, prop, S, cnt, room, ocnt, fillRank, fillSorted, fillC, misc;
     // plan of the two-phase path (k <= 16 only)
     size_t sl_reg_cnt, sl_reg_start, sl_nh, sl_hub_start, sl_hent, sl_hent_start, share_h0, share_nhs,
-        ch_regtot, ch_nh, ch_H, hub_row, hub_off;
+        ch_regtot, ch_nh, ch_H, ch_nvs, ch_hbase, hub_row, hub_off;
     size_t total;
-    size_t subR, subH, xstart, tstart, Hhub, T, X, total_sweep;   // extras of the two-phase path, after `total`
+    size_t subR, subH, xstart, tstart, lo, loh, Hhub, T, X, U, Uh, total_sweep;   // extras of the two-phase path, after `total`
     size_t hub_rows_cap;                                          // rows of Hhub
 };
 
@@ -86,8 +91,8 @@ inline int64_t slices_per_chunk(int64_t n, int64_t chunk) {
     return (cl + kSliceRows - 1) / kSliceRows;
 }
 
-Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool external_E, const TpGeom &tp,
-                   int hub_degree) {
+Layout make_layout(int64_t n, int64_t nnz, int64_t hub_entries, int32_t k, int64_t chunk, bool external_E,
+                   const TpGeom &tp, int hub_degree) {
     Layout L{};
     const int64_t cl = chunk < n ? chunk : n;
     const size_t lab = k <= 255 ? 1 : 2;
@@ -106,7 +111,7 @@ Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool extern
     L.fillRank = take((size_t)k * 4);
     L.fillSorted = take((size_t)k * 8);
     L.fillC = take(((size_t)k + 1) * 8);
-    L.misc = take(8 * 8);
+    L.misc = take(16 * 8);
     const bool tp_possible = k <= kSweepMaxK && tp.ok;
     if (tp_possible) {
         L.sl_reg_cnt = take(G * 4);
@@ -120,6 +125,8 @@ Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool extern
         L.ch_regtot = take((size_t)nchunks * 8);
         L.ch_nh = take((size_t)nchunks * 4);
         L.ch_H = take((size_t)nchunks * 8);
+        L.ch_nvs = take((size_t)nchunks * 4);
+        L.ch_hbase = take(((size_t)nchunks + 1) * 8);
         L.hub_row = take((size_t)n * 4);
         L.hub_off = take((size_t)(n + nchunks) * 8);
     }
@@ -131,14 +138,19 @@ Layout make_layout(int64_t n, int64_t nnz, int32_t k, int64_t chunk, bool extern
         L.hub_rows_cap = hubs;
         const size_t segs = (size_t)tp.nch * (size_t)tp.nblk;
         const size_t rows = (size_t)tp.nch * ((size_t)tp.nsl + 1);
-        const size_t slots = (size_t)(nnz > 0 ? nnz : 0) + 8 * segs;      // every segment padded to 8
         L.subR = take(rows * (size_t)tp.nblk * 4);
         L.subH = take(rows * (size_t)tp.nblk * 4);
         L.xstart = take((segs + 1) * 8);
         L.tstart = take((segs + 1) * 8);
+        L.lo = take(G * ((size_t)tp.ngroups + 1) * 4);
+        L.loh = take(G * ((size_t)tp.ngroups + 1) * 4);
         L.Hhub = take(hubs * (size_t)k * 4);
+        // every sub-segment is padded to even, every segment to a multiple of 8
+        const size_t slots = (size_t)(nnz > 0 ? nnz : 0) + 2 * rows * (size_t)tp.nblk + 8 * segs;
         L.T = take(slots * 4 + 16);
         L.X = take(slots * 2 + 16);
+        L.U = take((size_t)(nnz > 0 ? nnz : 0) * 4 + 16);
+        L.Uh = take((size_t)(hub_entries > 0 ? hub_entries : 0) * 4 + 16);
     }
     L.total_sweep = off;
     return L;
@@ -189,7 +201,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
     const bool external_E = estimates_out != nullptr;
     const int hub_degree = g.sweep_hub_degree;
     const TpGeom geo = tp_geometry(n, chunk, g.sweep_col_bits);
-    Layout lay = make_layout(n, 0, k, chunk, external_E, geo, hub_degree);
+    Layout lay = make_layout(n, 0, 0, k, chunk, external_E, geo, hub_degree);
 
     const int hist_mode = g.hist_mode;
     if (hist_mode == GREM_HIST_LDS && k > kLdsMaxK) return GREM_ERR_ARG;
@@ -230,7 +242,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
 
     // ---- prepass + the one validation read-back
     if (hipMemsetAsync(S, 0, (size_t)k * 8, stream) != hipSuccess ||
-        hipMemsetAsync(misc, 0, 8 * 8, stream) != hipSuccess) { release(); return GREM_ERR_HIP; }
+        hipMemsetAsync(misc, 0, 16 * 8, stream) != hipSuccess) { release(); return GREM_ERR_HIP; }
     {
         int64_t blocks = (n + 255) / 256;
         if (blocks > 256 * 32) blocks = 256 * 32;
@@ -265,6 +277,8 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
             pl.ch_regtot = (u64 *)(ws + lay.ch_regtot);
             pl.ch_nh = (uint32_t *)(ws + lay.ch_nh);
             pl.ch_H = (u64 *)(ws + lay.ch_H);
+            pl.ch_nvs = (uint32_t *)(ws + lay.ch_nvs);
+            pl.ch_hbase = (u64 *)(ws + lay.ch_hbase);
             pl.hub_row = (int32_t *)(ws + lay.hub_row);
             pl.hub_off = (u64 *)(ws + lay.hub_off);
             const unsigned G = (unsigned)(nchunks * nsl);
@@ -275,8 +289,15 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
             });
             L.run(GREM_KERNEL_RELAYOUT, [&] {
                 hipLaunchKernelGGL(k_plan_chunks, dim3((unsigned)nchunks), dim3(256), 0, stream, n, cl, nsl,
-                                   pl, misc);
+                                   geo.nblk, pl, misc);
             });
+            {
+                TpTables only_nch{};
+                only_nch.nch = geo.nch;
+                L.run(GREM_KERNEL_RELAYOUT, [&] {
+                    hipLaunchKernelGGL(k_tp_scan_segments, dim3(1), dim3(1024), 0, stream, only_nch, pl.ch_hbase, 2);
+                });
+            }
             L.run(GREM_KERNEL_RELAYOUT, [&] {
                 hipLaunchKernelGGL((k_plan_hubs<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, cl, nsl,
                                    (uint32_t)hub_degree, pl);
@@ -290,7 +311,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
         if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
     }
     if (L.err) { release(); return L.err; }
-    unsigned long long h_misc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long h_misc[16] = {0};
     if (hipMemcpyAsync(h_misc, misc, sizeof(h_misc), hipMemcpyDeviceToHost, stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess) { release(); return GREM_ERR_HIP; }
     if (h_misc[1] != 0 || h_misc[2] != 0) { release(); return GREM_ERR_SEED; }
@@ -328,13 +349,14 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                    hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
         };
         if (sweep) {
-            lay = make_layout(n, nnz, k, chunk, external_E, geo, hub_degree);
-            tp_score_lds = ((size_t)((kSliceRows * k + 1) >> 1) + (size_t)share_hubs * k + (size_t)k) * 4;
+            lay = make_layout(n, nnz, (int64_t)h_misc[8], k, chunk, external_E, geo, hub_degree);
+            tp_score_lds = ((size_t)kSliceRows * 8 + (size_t)share_hubs * k + (size_t)k) * 4;
             tp_lookup_lds = (size_t)1 << (geo.cb > 5 ? geo.cb - 1 : 4);
             // two score workgroups per CU must fit the 160 KB of LDS; one share may touch kMaxShareHubs
             // hubs; sub-segment offsets are 32-bit
             const bool fits = tp_score_lds <= 80 * 1024 && share_hubs <= kMaxShareHubs &&
-                              (size_t)max_chunk_hubs <= lay.hub_rows_cap && h_misc[7] < (1ull << 32) - 8ull * geo.nblk;
+                              (size_t)max_chunk_hubs <= lay.hub_rows_cap &&
+                              h_misc[7] + 4ull * ((unsigned long long)geo.nsl + 2) * geo.nblk < (1ull << 32);
             if (!fits) {
                 if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
                 sweep = false;
@@ -361,6 +383,8 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 tb.subH = (uint32_t *)(xbase + lay.subH);
                 tb.xstart = (u64 *)(xbase + lay.xstart);
                 tb.tstart = (u64 *)(xbase + lay.tstart);
+                tb.lo = (uint32_t *)(xbase + lay.lo);
+                tb.loh = (uint32_t *)(xbase + lay.loh);
                 tb.chunk = geo.chunk;
                 tb.chunk_shift = geo.shift;
                 tb.nch = geo.nch;
@@ -368,16 +392,26 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 tb.nbc = geo.nbc;
                 tb.nblk = geo.nblk;
                 tb.cb = geo.cb;
+                tb.gb = geo.gb;
+                tb.ngroups = geo.ngroups;
                 Hhub = (uint32_t *)(xbase + lay.Hhub);
                 T = (uint32_t *)(xbase + lay.T);
                 X = (uint16_t *)(xbase + lay.X);
-                const size_t reg_lds = (size_t)geo.nblk * 8 + ((size_t)kSliceRows + 1) * 4;
-                const size_t hub_lds = (size_t)geo.nblk * 8 + (size_t)(2 * kMaxShareHubs + 1) * 8;
+                uint32_t *U = (uint32_t *)(xbase + lay.U);
+                uint32_t *Uh = (uint32_t *)(xbase + lay.Uh);
+                const int nbg = geo.nblk < (1 << geo.gb) ? geo.nblk : (1 << geo.gb);
+                int batch = 8192 / nbg;
+                if (batch > 8) batch = 8;
+                if (batch < 1) batch = 1;
+                const size_t slice_lds = ((size_t)kSliceRows + 1 + (size_t)geo.nblk + (size_t)geo.ngroups + 1) * 4;
+                const size_t share_lds = (size_t)(2 * kMaxShareHubs + 1) * 8 +
+                                         ((size_t)geo.nblk + (size_t)geo.ngroups + 1) * 4;
+                const size_t place_lds = ((size_t)nbg + (size_t)batch) * 8 +
+                                         ((size_t)batch + 1 + (size_t)batch * nbg) * 4;
                 if (hipMemsetAsync(Hhub, 0, lay.hub_rows_cap * (size_t)k * 4, stream) != hipSuccess ||
-                    !set_lds((const void *)k_tp_layout_regular<RowT, false>, reg_lds) ||
-                    !set_lds((const void *)k_tp_layout_regular<RowT, true>, reg_lds) ||
-                    !set_lds((const void *)k_tp_layout_hubs<RowT, false>, hub_lds) ||
-                    !set_lds((const void *)k_tp_layout_hubs<RowT, true>, hub_lds) ||
+                    !set_lds((const void *)k_tp_sort_slice<RowT>, slice_lds) ||
+                    !set_lds((const void *)k_tp_sort_share<RowT>, share_lds) ||
+                    !set_lds((const void *)k_tp_place<RowT>, place_lds) ||
                     !set_lds((const void *)k_tp_lookup<true>, tp_lookup_lds) ||
                     !set_lds((const void *)k_tp_score<RowT>, tp_score_lds)) {
                     release();
@@ -387,26 +421,22 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 const unsigned G = (unsigned)(nchunks * nsl);
                 const unsigned segs = (unsigned)((int64_t)geo.nch * geo.nblk);
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_tp_layout_regular<RowT, false>), dim3(G), dim3(256), reg_lds, stream,
-                                       rowptr, colidx, n, (uint32_t)hub_degree, pl, tb, T);
+                    hipLaunchKernelGGL((k_tp_sort_slice<RowT>), dim3(G), dim3(kTpThreads), slice_lds, stream,
+                                       rowptr, colidx, n, (uint32_t)hub_degree, pl, tb, U);
                 });
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_tp_layout_hubs<RowT, false>), dim3(G), dim3(256), hub_lds, stream,
-                                       rowptr, colidx, n, pl, tb, T);
+                    hipLaunchKernelGGL((k_tp_sort_share<RowT>), dim3(G), dim3(256), share_lds, stream, rowptr,
+                                       colidx, n, pl, tb, Uh);
                 });
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
                     hipLaunchKernelGGL(k_tp_scan_slices, dim3((segs + 255) / 256), dim3(256), 0, stream, tb);
                 });
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL(k_tp_scan_segments, dim3(2), dim3(1024), 0, stream, tb);
+                    hipLaunchKernelGGL(k_tp_scan_segments, dim3(2), dim3(1024), 0, stream, tb, pl.ch_hbase, 0);
                 });
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_tp_layout_regular<RowT, true>), dim3(G), dim3(256), reg_lds, stream,
-                                       rowptr, colidx, n, (uint32_t)hub_degree, pl, tb, T);
-                });
-                L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_tp_layout_hubs<RowT, true>), dim3(G), dim3(256), hub_lds, stream,
-                                       rowptr, colidx, n, pl, tb, T);
+                    hipLaunchKernelGGL((k_tp_place<RowT>), dim3((unsigned)((int64_t)geo.ngroups * geo.nch)),
+                                       dim3(256), place_lds, stream, rowptr, n, pl, tb, U, Uh, T, batch);
                 });
             }
         }
@@ -569,7 +599,7 @@ size_t grem_workspace_bytes(int64_t n, int64_t nnz, int32_t k, int64_t chunk) {
     if (n < 1 || nnz < 0 || k < 1 || k > GREM_MAX_K || chunk < 1) return 0;
     std::lock_guard<std::mutex> lock(g.mu);
     const TpGeom geo = tp_geometry(n, chunk, g.sweep_col_bits);
-    const Layout lay = make_layout(n, nnz, k, chunk, false, geo, g.sweep_hub_degree);
+    const Layout lay = make_layout(n, nnz, nnz, k, chunk, false, geo, g.sweep_hub_degree);
     return lay.total_sweep;
 }
 

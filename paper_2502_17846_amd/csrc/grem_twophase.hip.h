@@ -16,19 +16,21 @@
 //   * segment (c, jb) holds the entries of the rows of chunk c whose column lies in block jb:
 //     first the entries of the regular rows, slice by slice, then the entries of the chunk's
 //     high-degree rows ("hubs"), share by share (see below).
-// T (tuples) is ordered by (jb, c); X (16-bit look-up results, row_in_slice << 5 | valid << 4 |
-// label) is ordered by (c, jb); a segment occupies the same number of slots in both, padded to a
-// multiple of 8.  After chunk c has been relabelled, k_tp_lookup streams the tuples of c's column
+// T (tuples) is ordered by (jb, c); X (16-bit look-up results, row_in_slice << 4 | label, which
+// is the index of the row's 16-bit counter of that label; bit 15 set = nothing to count) is
+// ordered by (c, jb); a segment occupies the same number of slots in both, padded to a multiple
+// of 8, and every sub-segment is padded to an even length.  After chunk c has been relabelled, k_tp_lookup streams the tuples of c's column
 // blocks (contiguous in T), looks the labels up in an LDS copy of the block's labels (two per
 // byte) and writes X (contiguous per segment).  Before chunk c is relabelled, k_tp_score has one
 // workgroup per row slice gather that slice's sub-segment from every segment (c, *) -- each a few
 // hundred bytes, contiguous -- into 16-bit LDS counters, then blends E and proposes.
 //
 // Balance: rows of degree >= hub_degree are taken out of their slice.  Their entries,
-// concatenated in row order, are cut in as many equal shares as the chunk has slices; workgroup i
-// of k_tp_score also counts share i (32-bit counters per hub touched) and adds its partial counts
-// to a per-chunk table in global memory with integer atomics; k_hub_finalize then blends and
-// proposes for the hubs.  The order of entries inside a sub-segment and the order of the atomic
+// concatenated in row order, are cut in equal shares (k_plan_chunks picks how many); every
+// workgroup of k_tp_score also counts one share's sub-segments of some of the column blocks
+// (32-bit counters per hub touched), so that each gets the same part of the hub entries, and adds
+// its partial counts to a per-chunk table in global memory with integer atomics; k_hub_finalize
+// then blends and proposes for the hubs.  The order of entries inside a sub-segment and the order of the atomic
 // adds are arbitrary; all of it is integer sums, so the result is not.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -64,6 +66,8 @@ struct SweepPlan {
     u64 *ch_regtot;           // regular entries
     uint32_t *ch_nh;          // hubs
     u64 *ch_H;                // hub entries
+    uint32_t *ch_nvs;         // hub shares of the chunk (0 without hubs, else 1 .. its number of slices)
+    u64 *ch_hbase;            // start of the chunk's hub entry stream in the stream of all chunks (+1: total)
     // hub lists: chunk c's hubs at hub_row[chunk_lo + i]; prefix of their degrees at
     // hub_off[chunk_lo + c + i], i = 0..nh (one more slot per chunk)
     int32_t *hub_row;
@@ -77,6 +81,8 @@ struct TpTables {
     uint32_t *subH;   // same shape: start of share i's sub-segment; row nsl: end of the segment
     u64 *xstart;      // [nch][nblk] (+1): first slot of segment (c, jb) in X
     u64 *tstart;      // [nblk][nch] (+1): first slot of segment (c, jb) in T
+    uint32_t *lo;     // [nch * nsl][ngroups + 1]: start of block group g's run inside the slice's range of U
+    uint32_t *loh;    // same for the hub shares and Uh
     uint32_t chunk;   // rows per chunk (already clamped to n)
     int chunk_shift;  // log2(chunk) when it is a power of two, else -1
     int nch;          // chunks
@@ -84,6 +90,8 @@ struct TpTables {
     int nbc;          // column blocks per chunk
     int nblk;         // nch * nbc
     int cb;           // log2 of the vertices per column block
+    int gb;           // log2 of the column blocks per group of the intermediate copy U
+    int ngroups;      // ceil(nblk / 2^gb)
 };
 
 __device__ __forceinline__ uint32_t tp_block_of(uint32_t u, const TpTables &g, uint32_t *col_low) {
@@ -158,11 +166,13 @@ __global__ __launch_bounds__(256) void k_plan_slices(const RowT *__restrict__ ro
 }
 
 // ------------------------------------------------------------------------------------------------
-// plan 2: per chunk, exclusive prefixes over its slices; misc[6] = most hubs in a chunk,
-// misc[7] = most entries in a chunk
+// plan 2: per chunk, exclusive prefixes over its slices, and the number of hub shares: enough
+// shares that one touches at most about 1024 hubs, few enough that a share's sub-segment of a
+// column block still holds some 64 entries, at most one per slice.  misc[6] = most hubs in a
+// chunk, misc[7] = most entries in a chunk, misc[8] = hub entries of all chunks.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, int nsl, SweepPlan pl,
-                                                     u64 *__restrict__ misc) {
+__global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, int nsl, int nblk,
+                                                     SweepPlan pl, u64 *__restrict__ misc) {
     __shared__ u64 p_reg[256], p_hent[256];
     __shared__ uint32_t p_nh[256];
     const int tid = threadIdx.x;
@@ -196,9 +206,22 @@ __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, i
         pl.ch_regtot[c] = breg;
         pl.ch_nh[c] = bnh;
         pl.ch_H[c] = bhent;
+        pl.ch_hbase[c] = bhent;             // scanned over the chunks by k_tp_scan_segments
         pl.hub_off[chunk_lo + c + bnh] = bhent;
+        const int64_t chunk_hi = (chunk_lo + chunk < n) ? chunk_lo + chunk : n;
+        const u64 nsl_c = (u64)((chunk_hi - chunk_lo + kSliceRows - 1) / kSliceRows);
+        u64 nvs = 0;
+        if (bnh != 0) {
+            nvs = bhent / (64ull * (u64)nblk);
+            const u64 by_hubs = ((u64)bnh + 1023ull) / 1024ull;
+            if (nvs < by_hubs) nvs = by_hubs;
+            if (nvs < 1) nvs = 1;
+            if (nvs > nsl_c) nvs = nsl_c;
+        }
+        pl.ch_nvs[c] = (uint32_t)nvs;
         atomicMax(&misc[6], (u64)bnh);
         atomicMax(&misc[7], breg + bhent);
+        atomicAdd(&misc[8], bhent);
     }
 }
 
@@ -238,7 +261,7 @@ __global__ __launch_bounds__(256) void k_plan_hubs(const RowT *__restrict__ rowp
 }
 
 // ------------------------------------------------------------------------------------------------
-// plan 4: per share, the hubs it touches.  Share i of a chunk with NS slices and H hub entries is
+// plan 4: per share, the hubs it touches.  Share i of a chunk with NS shares and H hub entries is
 // [H*i/NS, H*(i+1)/NS) of the chunk's hub entry stream.  misc[5] = most hubs touched by one share.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_plan_shares(int64_t n, int64_t chunk, int nsl, int total_slices,
@@ -250,8 +273,8 @@ __global__ __launch_bounds__(256) void k_plan_shares(int64_t n, int64_t chunk, i
     const int64_t chunk_lo = c * chunk;
     const int64_t chunk_hi = (chunk_lo + chunk < n) ? chunk_lo + chunk : n;
     uint32_t h0 = 0, nhs = 0;
-    if (chunk_lo + (int64_t)i * kSliceRows < chunk_hi) {
-        const u64 NS = (u64)((chunk_hi - chunk_lo + kSliceRows - 1) / kSliceRows);
+    const u64 NS = (u64)pl.ch_nvs[c];
+    if ((u64)i < NS && chunk_lo < chunk_hi) {
         const u64 H = pl.ch_H[c];
         const u64 a = H * (u64)i / NS, b = H * (u64)(i + 1) / NS;
         if (a != b) {
@@ -271,19 +294,22 @@ __global__ __launch_bounds__(256) void k_plan_shares(int64_t n, int64_t chunk, i
 }
 
 // ------------------------------------------------------------------------------------------------
-// re-layout of the regular rows of one slice, in two launches of the same kernel:
-//   SCATTER = false: count the slice's regular entries per column block -> subR[row(c,i)][*]
-//   SCATTER = true : subR now holds sub-segment starts; write the tuples into T
-// LDS: rowrel[kSliceRows + 1] (u32) then pos[nblk] (u64, 8-byte aligned)
+// Re-layout, step 1 (regular rows of one slice): count the slice's entries per column block
+// (-> subR[row(c,i)][*], raw counts) and write them, grouped by column-block GROUP (2^gb consecutive
+// blocks), into U at the slice's own CSR positions: the slice's range of U then holds ngroups runs,
+// run g starting at lo[gs][g].  Few runs per workgroup keep every write stream in L2 until its
+// lines are full.  U tuple: row_in_slice << (cb + gb) | block_in_group << cb | column_in_block.
+// LDS: rowrel[kSliceRows + 1], cntf[nblk], cur[ngroups + 1]
 // ------------------------------------------------------------------------------------------------
-template <typename RowT, bool SCATTER>
-__global__ __launch_bounds__(256) void k_tp_layout_regular(const RowT *__restrict__ rowptr,
-                                                           const int32_t *__restrict__ colidx, int64_t n,
-                                                           uint32_t hub_degree, SweepPlan pl, TpTables tb,
-                                                           uint32_t *__restrict__ T) {
-    extern __shared__ u64 smem64[];
-    u64 *pos = smem64;                                                  // nblk
-    uint32_t *rowrel = reinterpret_cast<uint32_t *>(pos + tb.nblk);     // kSliceRows + 1
+template <typename RowT>
+__global__ __launch_bounds__(kTpThreads) void k_tp_sort_slice(const RowT *__restrict__ rowptr,
+                                                              const int32_t *__restrict__ colidx, int64_t n,
+                                                              uint32_t hub_degree, SweepPlan pl, TpTables tb,
+                                                              uint32_t *__restrict__ U) {
+    extern __shared__ uint32_t smem[];
+    uint32_t *rowrel = smem;                        // kSliceRows + 1
+    uint32_t *cntf = rowrel + kSliceRows + 1;       // nblk
+    uint32_t *cur = cntf + tb.nblk;                 // ngroups + 1
     const int tid = threadIdx.x;
     const int64_t c = blockIdx.x / tb.nsl;
     const int i = blockIdx.x % tb.nsl;
@@ -291,71 +317,95 @@ __global__ __launch_bounds__(256) void k_tp_layout_regular(const RowT *__restric
     const int64_t chunk_hi = (chunk_lo + tb.chunk < n) ? chunk_lo + tb.chunk : n;
     const int64_t v0 = chunk_lo + (int64_t)i * kSliceRows;
     uint32_t *row_out = tb.subR + ((size_t)c * (tb.nsl + 1) + i) * tb.nblk;
+    uint32_t *lo_out = tb.lo + (size_t)blockIdx.x * (tb.ngroups + 1);
     if (v0 >= chunk_hi) {                       // slice beyond the (ragged) chunk: no entries
-        if (!SCATTER) for (int j = tid; j < tb.nblk; j += 256) row_out[j] = 0;
+        for (int j = tid; j < tb.nblk; j += kTpThreads) row_out[j] = 0;
+        for (int j = tid; j <= tb.ngroups; j += kTpThreads) lo_out[j] = 0;
         return;
     }
     const int64_t left = chunk_hi - v0;
     const int nv = left < kSliceRows ? (int)left : kSliceRows;
     const int64_t e0 = (int64_t)rowptr[v0];
-    for (int q = tid; q <= kSliceRows; q += 256) {
+    for (int q = tid; q <= kSliceRows; q += kTpThreads) {
         int qq = q < nv ? q : nv;
         rowrel[q] = (uint32_t)((int64_t)rowptr[v0 + qq] - e0);
     }
-    for (int j = tid; j < tb.nblk; j += 256)
-        pos[j] = SCATTER ? tb.tstart[(size_t)j * tb.nch + c] + row_out[j] : 0ull;
+    for (int j = tid; j < tb.nblk; j += kTpThreads) cntf[j] = 0;
     __syncthreads();
     const uint32_t ne = rowrel[kSliceRows];
     const int32_t *cbase = colidx + e0;
     const bool has_hubs = pl.sl_nh[blockIdx.x] != 0;
-    for (uint32_t p = tid; p < ne; p += 256) {
-        uint32_t r = 0;
-        if (SCATTER || has_hubs) {
-            r = (uint32_t)owning_row(rowrel, p, kSliceRows);
-            if (has_hubs && rowrel[r + 1] - rowrel[r] >= hub_degree) continue;
+    for (uint32_t p = tid; p < ne; p += kTpThreads) {
+        if (has_hubs) {
+            const int r = owning_row(rowrel, p, kSliceRows);
+            if (rowrel[r + 1] - rowrel[r] >= hub_degree) continue;
         }
         uint32_t low;
-        const uint32_t jb = tp_block_of((uint32_t)__builtin_nontemporal_load(cbase + p), tb, &low);
-        const u64 w = atomicAdd(&pos[jb], 1ull);
-        if (SCATTER) T[w] = (r << tb.cb) | low;
+        const uint32_t jb = tp_block_of((uint32_t)cbase[p], tb, &low);
+        atomicAdd(&cntf[jb], 1u);
     }
-    if (!SCATTER) {
-        __syncthreads();
-        for (int j = tid; j < tb.nblk; j += 256) row_out[j] = (uint32_t)pos[j];
+    __syncthreads();
+    for (int j = tid; j < tb.nblk; j += kTpThreads) row_out[j] = cntf[j];
+    for (int gq = tid; gq < tb.ngroups; gq += kTpThreads) {
+        const int j0 = gq << tb.gb;
+        const int j1 = (j0 + (1 << tb.gb)) < tb.nblk ? j0 + (1 << tb.gb) : tb.nblk;
+        uint32_t sum = 0;
+        for (int j = j0; j < j1; ++j) sum += cntf[j];
+        cur[gq] = sum;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t run = 0;
+        for (int gq = 0; gq < tb.ngroups; ++gq) { const uint32_t t = cur[gq]; cur[gq] = run; run += t; }
+        cur[tb.ngroups] = run;
+    }
+    __syncthreads();
+    for (int gq = tid; gq <= tb.ngroups; gq += kTpThreads) lo_out[gq] = cur[gq];
+    __syncthreads();
+    const uint32_t gmask = (1u << tb.gb) - 1u;
+    uint32_t *ubase = U + e0;
+    for (uint32_t p = tid; p < ne; p += kTpThreads) {
+        const uint32_t r = (uint32_t)owning_row(rowrel, p, kSliceRows);
+        if (has_hubs && rowrel[r + 1] - rowrel[r] >= hub_degree) continue;
+        uint32_t low;
+        const uint32_t jb = tp_block_of((uint32_t)cbase[p], tb, &low);
+        const uint32_t w = atomicAdd(&cur[jb >> tb.gb], 1u);
+        ubase[w] = (r << (tb.cb + tb.gb)) | ((jb & gmask) << tb.cb) | low;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// re-layout of one share of the chunk's hub entries (see k_plan_shares), same two launches; tuples
-// carry the hub's index relative to the share's first hub.
-// LDS: pos[nblk] (u64), hoff[kMaxShareHubs + 1] (u64), hrow[kMaxShareHubs] (u64)
+// Re-layout, step 1 for one share of the chunk's hub entries (see k_plan_shares): the same, into
+// Uh at the share's range of the hub entry stream (chunk c's stream starts at ch_hbase[c]); U
+// tuples carry the hub's index relative to the share's first hub.
+// LDS: hoff[kMaxShareHubs + 1] (u64), hrow[kMaxShareHubs] (u64), cntf[nblk], cur[ngroups + 1]
 // ------------------------------------------------------------------------------------------------
-template <typename RowT, bool SCATTER>
-__global__ __launch_bounds__(256) void k_tp_layout_hubs(const RowT *__restrict__ rowptr,
-                                                        const int32_t *__restrict__ colidx, int64_t n,
-                                                        SweepPlan pl, TpTables tb, uint32_t *__restrict__ T) {
+template <typename RowT>
+__global__ __launch_bounds__(256) void k_tp_sort_share(const RowT *__restrict__ rowptr,
+                                                       const int32_t *__restrict__ colidx, int64_t n,
+                                                       SweepPlan pl, TpTables tb, uint32_t *__restrict__ Uh) {
     extern __shared__ u64 smem64[];
-    u64 *pos = smem64;                      // nblk
-    u64 *hoff = pos + tb.nblk;              // kMaxShareHubs + 1  stream offsets of the hubs
-    u64 *hrow = hoff + kMaxShareHubs + 1;   // kMaxShareHubs      rowptr of the hub
+    u64 *hoff = smem64;                      // kMaxShareHubs + 1  stream offsets of the hubs
+    u64 *hrow = hoff + kMaxShareHubs + 1;    // kMaxShareHubs      rowptr of the hub
+    uint32_t *cntf = reinterpret_cast<uint32_t *>(hrow + kMaxShareHubs);    // nblk
+    uint32_t *cur = cntf + tb.nblk;          // ngroups + 1
     const int tid = threadIdx.x;
     const int64_t c = blockIdx.x / tb.nsl;
-    const int i = blockIdx.x % tb.nsl;
+    const int sidx = blockIdx.x % tb.nsl;
     const int64_t chunk_lo = c * (int64_t)tb.chunk;
-    const int64_t chunk_hi = (chunk_lo + tb.chunk < n) ? chunk_lo + tb.chunk : n;
-    uint32_t *row_out = tb.subH + ((size_t)c * (tb.nsl + 1) + i) * tb.nblk;
-    const bool inside = chunk_lo + (int64_t)i * kSliceRows < chunk_hi;
+    uint32_t *row_out = tb.subH + ((size_t)c * (tb.nsl + 1) + sidx) * tb.nblk;
+    uint32_t *lo_out = tb.loh + (size_t)blockIdx.x * (tb.ngroups + 1);
+    const uint32_t nvs = pl.ch_nvs[c];
     const uint32_t h0 = pl.share_h0[blockIdx.x], nhs = pl.share_nhs[blockIdx.x];
-    if (!inside || nhs == 0 || nhs > kMaxShareHubs) {      // nothing to do / plan rejected by the host
-        if (!SCATTER) for (int j = tid; j < tb.nblk; j += 256) row_out[j] = 0;
+    if ((uint32_t)sidx >= nvs || nhs == 0 || nhs > kMaxShareHubs) {      // no such share / plan rejected by the host
+        for (int j = tid; j < tb.nblk; j += 256) row_out[j] = 0;
+        for (int j = tid; j <= tb.ngroups; j += 256) lo_out[j] = 0;
         return;
     }
-    const u64 NS = (u64)((chunk_hi - chunk_lo + kSliceRows - 1) / kSliceRows);
     const u64 H = pl.ch_H[c];
-    const u64 a = H * (u64)i / NS, b = H * (u64)(i + 1) / NS;
+    const u64 a = H * (u64)sidx / nvs, b = H * (u64)(sidx + 1) / nvs;
     const u64 *goff = pl.hub_off + chunk_lo + c;
-    for (int j = tid; j < tb.nblk; j += 256)
-        pos[j] = SCATTER ? tb.tstart[(size_t)j * tb.nch + c] + row_out[j] : 0ull;
+    for (int j = tid; j < tb.nblk; j += 256) cntf[j] = 0;
     for (uint32_t q = tid; q <= nhs; q += 256) hoff[q] = goff[h0 + q];
     for (uint32_t q = tid; q < nhs; q += 256) hrow[q] = (u64)rowptr[pl.hub_row[chunk_lo + h0 + q]];
     __syncthreads();
@@ -366,20 +416,46 @@ __global__ __launch_bounds__(256) void k_tp_layout_hubs(const RowT *__restrict__
         while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (hoff[mid] <= e) lo = mid; else hi = mid; }
         const int64_t at = (int64_t)(hrow[lo] + (e - hoff[lo]));
         uint32_t low;
-        const uint32_t jb = tp_block_of((uint32_t)__builtin_nontemporal_load(colidx + at), tb, &low);
-        const u64 w = atomicAdd(&pos[jb], 1ull);
-        if (SCATTER) T[w] = (lo << tb.cb) | low;
+        const uint32_t jb = tp_block_of((uint32_t)colidx[at], tb, &low);
+        atomicAdd(&cntf[jb], 1u);
     }
-    if (!SCATTER) {
-        __syncthreads();
-        for (int j = tid; j < tb.nblk; j += 256) row_out[j] = (uint32_t)pos[j];
+    __syncthreads();
+    for (int j = tid; j < tb.nblk; j += 256) row_out[j] = cntf[j];
+    for (int gq = tid; gq < tb.ngroups; gq += 256) {
+        const int j0 = gq << tb.gb;
+        const int j1 = (j0 + (1 << tb.gb)) < tb.nblk ? j0 + (1 << tb.gb) : tb.nblk;
+        uint32_t sum = 0;
+        for (int j = j0; j < j1; ++j) sum += cntf[j];
+        cur[gq] = sum;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t run = 0;
+        for (int gq = 0; gq < tb.ngroups; ++gq) { const uint32_t t = cur[gq]; cur[gq] = run; run += t; }
+        cur[tb.ngroups] = run;
+    }
+    __syncthreads();
+    for (int gq = tid; gq <= tb.ngroups; gq += 256) lo_out[gq] = cur[gq];
+    __syncthreads();
+    const uint32_t gmask = (1u << tb.gb) - 1u;
+    uint32_t *ubase = Uh + pl.ch_hbase[c] + a;
+    for (uint32_t p = tid; p < len; p += 256) {
+        const u64 e = a + p;
+        uint32_t lo = 0, hi = nhs;
+        while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (hoff[mid] <= e) lo = mid; else hi = mid; }
+        const int64_t at = (int64_t)(hrow[lo] + (e - hoff[lo]));
+        uint32_t low;
+        const uint32_t jb = tp_block_of((uint32_t)colidx[at], tb, &low);
+        const uint32_t w = atomicAdd(&cur[jb >> tb.gb], 1u);
+        ubase[w] = (lo << (tb.cb + tb.gb)) | ((jb & gmask) << tb.cb) | low;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 // counts -> starts.  One thread per segment (c, jb): exclusive prefix over the slices of the
-// regular counts, then of the share counts; the padded segment length goes to xstart and tstart
-// (each in its own order), to be scanned by k_tp_scan_segments.
+// regular counts, then of the share counts, every count rounded up to even (sub-segments start on
+// 4-byte boundaries of X); the segment length, rounded up to a multiple of 8, goes to xstart and
+// tstart (each in its own order), to be scanned by k_tp_scan_segments.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_tp_scan_slices(TpTables tb) {
     const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -387,22 +463,23 @@ __global__ __launch_bounds__(256) void k_tp_scan_slices(TpTables tb) {
     const int c = (int)(id / tb.nblk), jb = (int)(id % tb.nblk);
     uint32_t run = 0;
     uint32_t *p = tb.subR + ((size_t)c * (tb.nsl + 1)) * tb.nblk + jb;
-    for (int i = 0; i < tb.nsl; ++i, p += tb.nblk) { const uint32_t t = *p; *p = run; run += t; }
+    for (int i = 0; i < tb.nsl; ++i, p += tb.nblk) { const uint32_t t = (*p + 1u) & ~1u; *p = run; run += t; }
     *p = run;
     p = tb.subH + ((size_t)c * (tb.nsl + 1)) * tb.nblk + jb;
-    for (int i = 0; i < tb.nsl; ++i, p += tb.nblk) { const uint32_t t = *p; *p = run; run += t; }
+    for (int i = 0; i < tb.nsl; ++i, p += tb.nblk) { const uint32_t t = (*p + 1u) & ~1u; *p = run; run += t; }
     *p = run;
     const u64 padded = ((u64)run + 7ull) & ~7ull;
     tb.xstart[(size_t)c * tb.nblk + jb] = padded;
     tb.tstart[(size_t)jb * tb.nch + c] = padded;
 }
 
-// In-place exclusive prefix of a[0..m) by one workgroup, total in a[m].  Block 0 scans xstart,
-// block 1 tstart.
-__global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb) {
+// In-place exclusive prefix of a[0..m) by one workgroup, total in a[m].  Array 0 is xstart, 1 is
+// tstart, 2 (m = nch) the chunks' hub entry counts in ch_hbase; block b scans array first + b.
+__global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb, u64 *__restrict__ ch_hbase, int first) {
     __shared__ u64 part[1024];
-    u64 *a = blockIdx.x == 0 ? tb.xstart : tb.tstart;
-    const int64_t m = (int64_t)tb.nch * tb.nblk;
+    const int which = first + (int)blockIdx.x;
+    u64 *a = which == 0 ? tb.xstart : (which == 1 ? tb.tstart : ch_hbase);
+    const int64_t m = which == 2 ? (int64_t)tb.nch : (int64_t)tb.nch * tb.nblk;
     const int tid = threadIdx.x;
     const int64_t per = (m + 1023) / 1024;
     const int64_t lo = tid * per;
@@ -418,13 +495,93 @@ __global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Re-layout, step 2: workgroup c * ngroups + g moves the runs of block group g of every slice (then every
+// share) of chunk c from U (Uh) to their sub-segments in T.  The slices are taken in order, so the
+// workgroup writes 2^gb sequential streams.  Odd sub-segments get one pad tuple (row field 2048,
+// which the look-up turns into an entry the score ignores).
+// LDS: tbase[nbg] (u64), runsrc[batch] (u64), runlo[batch + 1], cur[batch][nbg]
+// ------------------------------------------------------------------------------------------------
+template <typename RowT>
+__global__ __launch_bounds__(256) void k_tp_place(const RowT *__restrict__ rowptr, int64_t n, SweepPlan pl,
+                                                  TpTables tb, const uint32_t *__restrict__ U,
+                                                  const uint32_t *__restrict__ Uh, uint32_t *__restrict__ T,
+                                                  int batch) {
+    extern __shared__ u64 smem64[];
+    const int g = (int)(blockIdx.x % (unsigned)tb.ngroups), c = (int)(blockIdx.x / (unsigned)tb.ngroups);
+    const int jb0 = g << tb.gb;
+    const int nbg = (jb0 + (1 << tb.gb)) <= tb.nblk ? (1 << tb.gb) : tb.nblk - jb0;
+    u64 *tbase = smem64;                                        // nbg
+    u64 *runsrc = tbase + nbg;                                  // batch
+    uint32_t *runlo = reinterpret_cast<uint32_t *>(runsrc + batch);     // batch + 1
+    uint32_t *cur = runlo + batch + 1;                          // batch * nbg
+    const int tid = threadIdx.x;
+    const int64_t chunk_lo = (int64_t)c * tb.chunk;
+    const int64_t chunk_hi = (chunk_lo + tb.chunk < n) ? chunk_lo + tb.chunk : n;
+    const int nsl_c = (int)((chunk_hi - chunk_lo + kSliceRows - 1) / kSliceRows);
+    const int nvs = (int)pl.ch_nvs[c];
+    const uint32_t gmask = (1u << tb.gb) - 1u, cmask = (1u << tb.cb) - 1u;
+    const uint32_t pad = 2048u << tb.cb;
+    for (int j = tid; j < nbg; j += 256) tbase[j] = tb.tstart[(size_t)(jb0 + j) * tb.nch + c];
+    for (int part = 0; part < 2; ++part) {                      // 0: regular slices, 1: hub shares
+        const int count = part == 0 ? nsl_c : nvs;
+        const uint32_t *sub = part == 0 ? tb.subR : tb.subH;
+        const uint32_t *lot = part == 0 ? tb.lo : tb.loh;
+        const uint32_t *src = part == 0 ? U : Uh;
+        for (int i0 = 0; i0 < count; i0 += batch) {
+            const int nb = count - i0 < batch ? count - i0 : batch;
+            __syncthreads();                                    // previous batch done with the LDS tables
+            if (tid < nb) {
+                const size_t gs = (size_t)c * tb.nsl + i0 + tid;
+                const uint32_t a = lot[gs * (tb.ngroups + 1) + g], b = lot[gs * (tb.ngroups + 1) + g + 1];
+                u64 at;
+                if (part == 0) {
+                    at = (u64)rowptr[chunk_lo + (int64_t)(i0 + tid) * kSliceRows];
+                } else {
+                    const u64 H = pl.ch_H[c];
+                    at = pl.ch_hbase[c] + H * (u64)(i0 + tid) / (u64)nvs;
+                }
+                runsrc[tid] = at + a;
+                runlo[tid + 1] = b - a;
+            }
+            for (int q = tid; q < nb * nbg; q += 256) {
+                const int t = q / nbg, j = q % nbg;
+                cur[q] = sub[((size_t)c * (tb.nsl + 1) + i0 + t) * tb.nblk + jb0 + j];
+            }
+            __syncthreads();
+            if (tid == 0) {
+                uint32_t run = 0;
+                runlo[0] = 0;
+                for (int t = 0; t < nb; ++t) { run += runlo[t + 1]; runlo[t + 1] = run; }
+            }
+            __syncthreads();
+            const uint32_t total = runlo[nb];
+            for (uint32_t p = tid; p < total; p += 256) {
+                int t = 0;
+                while (runlo[t + 1] <= p) ++t;                  // batch <= 8
+                const uint32_t u = __builtin_nontemporal_load(src + runsrc[t] + (p - runlo[t]));
+                const uint32_t j = (u >> tb.cb) & gmask;
+                const uint32_t w = atomicAdd(&cur[t * nbg + j], 1u);
+                T[tbase[j] + w] = ((u >> (tb.cb + tb.gb)) << tb.cb) | (u & cmask);
+            }
+            __syncthreads();
+            for (int q = tid; q < nb * nbg; q += 256) {
+                const int t = q / nbg, j = q % nbg;
+                const uint32_t end = sub[((size_t)c * (tb.nsl + 1) + i0 + t + 1) * tb.nblk + jb0 + j];
+                if (cur[q] < end) T[tbase[j] + cur[q]] = pad;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // look-up (phase 1 of the score): the tuples of the column blocks of chunk `c0 + blockIdx.y`,
 // restricted to row chunks >= cmin, get their labels.  Workgroup blockIdx.x handles share
 // (blockIdx.x % spb) of block (blockIdx.x / spb) of the chunk.
 //   FROM_LDS = true : the block's labels are copied to LDS, two per byte (every vertex of the
 //                     block is assigned: the chunk has just been relabelled)
-//   FROM_LDS = false: labels are read from global memory and may be unassigned (valid bit clear);
+//   FROM_LDS = false: labels are read from global memory and may be unassigned (bit 15 set);
 //                     used once, for the initial labels of a seeded run
+// X entry: row field << 4 | label; the pad tuples' row field 2048 sets bit 15 by itself.
 // ------------------------------------------------------------------------------------------------
 template <bool FROM_LDS>
 __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__restrict__ T,
@@ -494,13 +651,13 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
                 u32x4 t[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const uint32_t g = base + u * kTpThreads;
-                    t[u] = g < ng ? __builtin_nontemporal_load(src4 + g) : (u32x4)(0u);
+                    const uint32_t gi = base + u * kTpThreads;
+                    t[u] = gi < ng ? __builtin_nontemporal_load(src4 + gi) : (u32x4)(0u);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const uint32_t g = base + u * kTpThreads;
-                    if (g < ng) {
+                    const uint32_t gi = base + u * kTpThreads;
+                    if (gi < ng) {
                         const uint32_t ent[4] = {t[u].x, t[u].y, t[u].z, t[u].w};
                         uint32_t o[4];
 #pragma unroll
@@ -508,18 +665,18 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
                             const uint32_t col = ent[q] & cmask;
                             uint32_t lab;
                             if (FROM_LDS) {
-                                lab = 16u | (((uint32_t)tbytes[col >> 1] >> (4 * (col & 1u))) & 15u);
+                                lab = ((uint32_t)tbytes[col >> 1] >> (4 * (col & 1u))) & 15u;
                             } else {
                                 const int64_t v = block_lo + (int64_t)col;
                                 const uint32_t l = v < chunk_hi ? (uint32_t)Lc[v] : 0xFFu;
-                                lab = l == 0xFFu ? 0u : (16u | (l & 15u));
+                                lab = l == 0xFFu ? 0x8000u : (l & 15u);
                             }
-                            o[q] = (((ent[q] >> tb.cb) << 5) | lab) & 0xFFFFu;
+                            o[q] = (((ent[q] >> tb.cb) << 4) | lab) & 0xFFFFu;
                         }
                         u32x2 w;
                         w.x = o[0] | (o[1] << 16);
                         w.y = o[2] | (o[3] << 16);
-                        __builtin_nontemporal_store(w, dst2 + g);
+                        __builtin_nontemporal_store(w, dst2 + gi);
                     }
                 }
             }
@@ -529,43 +686,40 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
     }
 }
 
-// one 16-bit look-up result into the counters; COUNT16: two 16-bit counters per word, else 32-bit
+// Look-up results of two sub-segments, [sa, sa + la) and [sb, sb + lb) (even starts and lengths,
+// in 16-bit units from Xc), counted by one wavefront: lane l takes the two entries at offset 2l of
+// each, round after round.  COUNT16: regular rows, 16-bit counters, index = entry; else hub share,
+// 32-bit counters, index = hub * k + label.  Entries with bit 15 set are ignored.
 template <bool COUNT16>
-__device__ __forceinline__ void tp_count_entry(uint32_t x, int k, uint32_t *hist) {
-    if (x & 16u) {
-        const uint32_t c = (x >> 5) * (uint32_t)k + (x & 15u);
-        if (COUNT16) atomicAdd(&hist[c >> 1], 1u << (16 * (c & 1u)));
-        else atomicAdd(&hist[c], 1u);
-    }
-}
-
-// two sub-segments [sa, ea) and [sb, eb) of X, taken together by one wavefront so that the loads
-// of both are in flight at once
-template <bool COUNT16, int U>
-__device__ __forceinline__ void tp_count_pair(const uint16_t *__restrict__ X, u64 sa, u64 ea, u64 sb,
-                                              u64 eb, int lane, int k, uint32_t *hist) {
-    uint32_t va[U], vb[U];
+__device__ __forceinline__ void tp_count_pair(const uint32_t *__restrict__ Xc32, uint32_t sa, uint32_t la,
+                                              uint32_t sb, uint32_t lb, int lane, int k, uint32_t *hist) {
+    const uint32_t mx = la > lb ? la : lb;
+    for (uint32_t r = 0; r < mx; r += 128) {
+        const uint32_t off = r + 2u * (uint32_t)lane;
+        uint32_t w[2];
+        w[0] = off < la ? __builtin_nontemporal_load(Xc32 + ((sa + off) >> 1)) : 0x80008000u;
+        w[1] = off < lb ? __builtin_nontemporal_load(Xc32 + ((sb + off) >> 1)) : 0x80008000u;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const u64 qa = sa + (u64)(lane + 64 * u), qb = sb + (u64)(lane + 64 * u);
-        va[u] = qa < ea ? (uint32_t)__builtin_nontemporal_load(X + qa) : 0u;
-        vb[u] = qb < eb ? (uint32_t)__builtin_nontemporal_load(X + qb) : 0u;
-    }
+        for (int z = 0; z < 2; ++z) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        tp_count_entry<COUNT16>(va[u], k, hist);
-        tp_count_entry<COUNT16>(vb[u], k, hist);
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t x = h == 0 ? (w[z] & 0xFFFFu) : (w[z] >> 16);
+                if (x < 0x8000u) {
+                    if (COUNT16) atomicAdd(&hist[x >> 1], 1u << ((x & 1u) << 4));
+                    else atomicAdd(&hist[(x >> 4) * (uint32_t)k + (x & 15u)], 1u);
+                }
+            }
+        }
     }
-    for (u64 q = sa + (u64)(lane + 64 * U); q < ea; q += 64)
-        tp_count_entry<COUNT16>((uint32_t)__builtin_nontemporal_load(X + q), k, hist);
-    for (u64 q = sb + (u64)(lane + 64 * U); q < eb; q += 64)
-        tp_count_entry<COUNT16>((uint32_t)__builtin_nontemporal_load(X + q), k, hist);
 }
 
 // ------------------------------------------------------------------------------------------------
-// score (phase 2): one workgroup per row slice of chunk c, plus one share of the chunk's hub
-// entries.  Column blocks [0, jlim) are counted (in the first pass of an unseeded run the blocks of
-// chunks >= c hold no label yet and their part of X has not been written).
+// score (phase 2): one workgroup per row slice of chunk c.  It counts the slice's sub-segment of
+// every column block in [0, jlim) (in the first pass of an unseeded run the blocks of chunks >= c
+// hold no label yet and their part of X has not been written), and, of hub share
+// (blockIdx.x % nvs), the sub-segments of the blocks congruent to (blockIdx.x / nvs) modulo the
+// number of workgroups per share, so that the hub entries are spread evenly too.
+// LDS: hist[kSliceRows * 8] (16-bit counters, 16 per row), hhist[share_hubs * k], room[k]
 // ------------------------------------------------------------------------------------------------
 template <typename RowT>
 __global__ __launch_bounds__(kTpThreads) void k_tp_score(
@@ -574,54 +728,84 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     uint32_t *__restrict__ Hhub, uint8_t *__restrict__ prop, int c, int64_t chunk_lo, int64_t chunk_hi,
     int k, int jlim, int share_hubs, uint32_t hub_degree, int pass, long long P) {
     extern __shared__ uint32_t smem[];
-    const int hist_words = (kSliceRows * k + 1) >> 1;
-    uint32_t *hist = smem;                      // hist_words            regular rows, 16-bit counters
+    constexpr int hist_words = kSliceRows * 8;
+    uint32_t *hist = smem;                      // hist_words
     uint32_t *hhist = hist + hist_words;        // share_hubs * k        hubs of the share, 32-bit
     uint32_t *room = hhist + share_hubs * k;    // k
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     constexpr int NW = kTpThreads / 64;
-    const size_t gs = (size_t)c * tb.nsl + blockIdx.x;
     const int64_t v0 = chunk_lo + (int64_t)blockIdx.x * kSliceRows;
     const int64_t left = chunk_hi - v0;
     const int nv = left < kSliceRows ? (int)left : kSliceRows;
 
-    for (int q = tid; q < hist_words + share_hubs * k; q += kTpThreads) hist[q] = 0;
-    for (int j = tid; j < k; j += kTpThreads) room[j] = (uint32_t)(P - S[j]);
+    {
+        u32x4 *z = reinterpret_cast<u32x4 *>(hist);
+        for (int q = tid; q < hist_words / 4; q += kTpThreads) z[q] = (u32x4)(0u);
+        for (int q = tid; q < share_hubs * k; q += kTpThreads) hhist[q] = 0;
+        for (int j = tid; j < k; j += kTpThreads) room[j] = (uint32_t)(P - S[j]);
+    }
     __syncthreads();
 
-    const bool any_hub = pl.share_nhs[gs] != 0;
-    const uint32_t *r0 = tb.subR + ((size_t)c * (tb.nsl + 1) + blockIdx.x) * tb.nblk;
-    const uint32_t *r1 = r0 + tb.nblk;
-    const uint32_t *q0 = tb.subH + ((size_t)c * (tb.nsl + 1) + blockIdx.x) * tb.nblk;
-    const uint32_t *q1 = q0 + tb.nblk;
     const u64 *xs = tb.xstart + (size_t)c * tb.nblk;
-    for (int base = 0; base < jlim; base += NW * 64) {
-        // lane l of wave w holds the offsets of block base + w + NW * l
-        const int jl = base + wave + NW * lane;
-        u64 x0 = 0;
-        uint32_t a0 = 0, a1 = 0, h0 = 0, h1 = 0;
-        if (jl < jlim) {
-            x0 = xs[jl];
-            a0 = r0[jl];
-            a1 = r1[jl];
-            if (any_hub) { h0 = q0[jl]; h1 = q1[jl]; }
-        }
-        int tmax = (jlim - base - wave + NW - 1) / NW;      // blocks of this wave in this round
-        if (tmax > 64) tmax = 64;
-        for (int t = 0; t < tmax; t += 2) {
-            const int t2 = t + 1 < tmax ? t + 1 : t;
-            const u64 xa = __shfl(x0, t), xb = __shfl(x0, t2);
-            const uint32_t sa = __shfl(a0, t), ea = __shfl(a1, t);
-            const uint32_t sb = __shfl(a0, t2), eb = t2 != t ? __shfl(a1, t2) : sb;
-            tp_count_pair<true, 3>(X, xa + sa, xa + ea, xb + sb, xb + eb, lane, k, hist);
-        }
-        if (any_hub) {
+    const u64 xs0 = xs[0];
+    const uint32_t *Xc32 = reinterpret_cast<const uint32_t *>(X + xs0);     // xs0 is a multiple of 8
+    {
+        const uint32_t *r0 = tb.subR + ((size_t)c * (tb.nsl + 1) + blockIdx.x) * tb.nblk;
+        const uint32_t *r1 = r0 + tb.nblk;
+        for (int base = 0; base < jlim; base += NW * 64) {
+            // lane l of wave w holds the sub-segment of block base + w + NW * l
+            const int jl = base + wave + NW * lane;
+            uint32_t s0 = 0, l0 = 0;
+            if (jl < jlim) {
+                const uint32_t a0 = r0[jl];
+                s0 = (uint32_t)(xs[jl] - xs0) + a0;
+                l0 = r1[jl] - a0;
+            }
+            int tmax = (jlim - base - wave + NW - 1) / NW;      // blocks of this wave in this round
+            if (tmax > 64) tmax = 64;
             for (int t = 0; t < tmax; t += 2) {
-                const int t2 = t + 1 < tmax ? t + 1 : t;
-                const u64 xa = __shfl(x0, t), xb = __shfl(x0, t2);
-                const uint32_t sa = __shfl(h0, t), ea = __shfl(h1, t);
-                const uint32_t sb = __shfl(h0, t2), eb = t2 != t ? __shfl(h1, t2) : sb;
-                tp_count_pair<false, 1>(X, xa + sa, xa + ea, xb + sb, xb + eb, lane, k, hhist);
+                const uint32_t sa = __builtin_amdgcn_readlane(s0, t), la = __builtin_amdgcn_readlane(l0, t);
+                uint32_t sb = 0, lb = 0;
+                if (t + 1 < tmax) {
+                    sb = __builtin_amdgcn_readlane(s0, t + 1);
+                    lb = __builtin_amdgcn_readlane(l0, t + 1);
+                }
+                tp_count_pair<true>(Xc32, sa, la, sb, lb, lane, k, hist);
+            }
+        }
+    }
+    const uint32_t nvs = pl.ch_nvs[c];
+    uint32_t share = 0;
+    bool any_hub = false;
+    if (nvs != 0) {
+        share = blockIdx.x % nvs;
+        const int cls = (int)(blockIdx.x / nvs);
+        const int ncls = (int)((gridDim.x - share + nvs - 1) / nvs);      // workgroups that took this share
+        any_hub = pl.share_nhs[(size_t)c * tb.nsl + share] != 0;
+        if (any_hub) {
+            const uint32_t *q0 = tb.subH + ((size_t)c * (tb.nsl + 1) + share) * tb.nblk;
+            const uint32_t *q1 = q0 + tb.nblk;
+            const int mlim = jlim > cls ? (jlim - cls + ncls - 1) / ncls : 0;    // blocks cls + ncls * m < jlim
+            for (int base = 0; base < mlim; base += NW * 64) {
+                const int ml = base + wave + NW * lane;
+                uint32_t s0 = 0, l0 = 0;
+                if (ml < mlim) {
+                    const int jl = cls + ncls * ml;
+                    const uint32_t a0 = q0[jl];
+                    s0 = (uint32_t)(xs[jl] - xs0) + a0;
+                    l0 = q1[jl] - a0;
+                }
+                int tmax = (mlim - base - wave + NW - 1) / NW;
+                if (tmax > 64) tmax = 64;
+                for (int t = 0; t < tmax; t += 2) {
+                    const uint32_t sa = __builtin_amdgcn_readlane(s0, t), la = __builtin_amdgcn_readlane(l0, t);
+                    uint32_t sb = 0, lb = 0;
+                    if (t + 1 < tmax) {
+                        sb = __builtin_amdgcn_readlane(s0, t + 1);
+                        lb = __builtin_amdgcn_readlane(l0, t + 1);
+                    }
+                    tp_count_pair<false>(Xc32, sa, la, sb, lb, lane, k, hhist);
+                }
             }
         }
     }
@@ -629,7 +813,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
 
     // partial counts of the share's hubs -> the chunk's hub table
     if (any_hub) {
-        const uint32_t h0 = pl.share_h0[gs];
+        const uint32_t h0 = pl.share_h0[(size_t)c * tb.nsl + share];
         for (int q = tid; q < share_hubs * k; q += kTpThreads) {
             const uint32_t x = hhist[q];
             if (x) atomicAdd(&Hhub[(size_t)h0 * k + q], x);
@@ -647,7 +831,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
         uint32_t *Erow = E + (size_t)v * (size_t)k;
         unsigned long long bestkey = 0;
         int bestj = 0x7fffffff;
-        const uint32_t cbase = (uint32_t)t * (uint32_t)k;
+        const uint32_t cbase = (uint32_t)t * 16u;
         if ((k & 3) == 0) {
             for (int j4 = q * 4; j4 < k; j4 += 16) {
                 u32x4 e = (u32x4)(0u);

@@ -56,8 +56,9 @@ def test_host_helpers(lib):
     lib.grem_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64]
     n, nnz, k, chunk = 1 << 20, 30_000_000, 8, 1 << 16
     w = lib.grem_workspace_bytes(n, nnz, k, chunk)
-    # E, labels, and the re-laid-out entries: 4-byte tuples and 2-byte look-up results, plus offset tables
-    assert w >= n * k * 4 + n + 6 * nnz and w < n * k * 4 + 20 * n + 6 * nnz + (16 << 20)
+    # E, labels, and the re-laid-out entries: 4-byte tuples, 2-byte look-up results, the 4-byte
+    # intermediate copy (regular rows, and room for as many hub entries), plus offset tables
+    assert w >= n * k * 4 + n + 14 * nnz and w < n * k * 4 + 20 * n + 14 * nnz + (64 << 20)
     w2 = lib.grem_workspace_bytes(n, nnz, 64, chunk)           # no entry copy above k = 16
     assert n * 64 * 4 + n <= w2 < n * 64 * 4 + 4 * n + (1 << 20)
     assert lib.grem_workspace_bytes(0, nnz, k, chunk) == 0
