@@ -328,12 +328,14 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
     if (maxdeg * (unsigned long long)tv >= (1ull << 31)) { release(); return GREM_ERR_RANGE; }
     const size_t score_lds = use_lds ? ((size_t)tv * k + tv + 1 + k) * 4 : ((size_t)tv + 1 + k) * 4;
     const size_t count_lds = (size_t)k * 4;
-    const size_t apply_lds = ((size_t)k + (size_t)(kAdmitThreads / 64) * k + k) * 4;
+    const size_t apply_lds = ((size_t)k + (size_t)(kAdmitThreads / 64) * k + 2 * (size_t)k) * 4;
     const size_t fill_lds = (size_t)k * 4;
 
     if (apply_lds > 64 * 1024 &&
-        hipFuncSetAttribute((const void *)k_apply<LabelT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)apply_lds) != hipSuccess) { release(); return GREM_ERR_HIP; }
+        (hipFuncSetAttribute((const void *)k_apply<LabelT, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)apply_lds) != hipSuccess ||
+         hipFuncSetAttribute((const void *)k_apply<LabelT, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)apply_lds) != hipSuccess)) { release(); return GREM_ERR_HIP; }
 
     // ---- two-phase path: allocate its extras, re-lay-out the entries once
     TpTables tb{};
@@ -341,7 +343,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
     uint16_t *X = nullptr;
     size_t tp_score_lds = 0, tp_lookup_lds = 0;
     const int share_hubs = (int)h_misc[5];
-    const unsigned max_chunk_hubs = (unsigned)h_misc[6];
+    const size_t max_chunk_hubs = (size_t)h_misc[6];
     int lookup_target = 256;                 // workgroups of one look-up launch
     if constexpr (sizeof(LabelT) == 1) {
         auto set_lds = [&](const void *f, size_t bytes) {
@@ -350,12 +352,12 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
         };
         if (sweep) {
             lay = make_layout(n, nnz, (int64_t)h_misc[8], k, chunk, external_E, geo, hub_degree);
-            tp_score_lds = ((size_t)kSliceRows * 8 + (size_t)share_hubs * k + (size_t)k) * 4;
+            tp_score_lds = ((size_t)kSliceRows * 8 + kSliceRows / 2 + (size_t)share_hubs * k + 3 * (size_t)k) * 4;
             tp_lookup_lds = (size_t)1 << (geo.cb > 5 ? geo.cb - 1 : 4);
-            // two score workgroups per CU must fit the 160 KB of LDS; one share may touch kMaxShareHubs
-            // hubs; sub-segment offsets are 32-bit
-            const bool fits = tp_score_lds <= 80 * 1024 && share_hubs <= kMaxShareHubs &&
-                              (size_t)max_chunk_hubs <= lay.hub_rows_cap &&
+            // a score workgroup must fit the 160 KB of LDS (two per CU do when a share touches few hubs);
+            // one share may touch kMaxShareHubs hubs; sub-segment offsets are 32-bit
+            const bool fits = tp_score_lds <= 150 * 1024 && share_hubs <= kMaxShareHubs &&
+                              max_chunk_hubs <= lay.hub_rows_cap &&
                               h_misc[7] + 4ull * ((unsigned long long)geo.nsl + 2) * geo.nblk < (1ull << 32);
             if (!fits) {
                 if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
@@ -485,14 +487,14 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                     L.run(GREM_KERNEL_SCORE, [&] {
                         hipLaunchKernelGGL((k_tp_score<RowT>), dim3(blocks), dim3(kTpThreads), tp_score_lds,
                                            stream, rowptr, X, tb, pl, (const uint8_t *)Lc, S, E, Hhub,
-                                           (uint8_t *)prop, (int)c, lo, hi, (int)k, jlim, share_hubs,
-                                           (uint32_t)hub_degree, pass, P);
+                                           (uint8_t *)prop, cnt, room, (int)c, lo, hi, (int)k, jlim,
+                                           share_hubs, (uint32_t)hub_degree, pass, P);
                     });
                     if (max_chunk_hubs > 0)
                         L.run(GREM_KERNEL_HUBS, [&] {
-                            hipLaunchKernelGGL(k_hub_finalize, dim3((max_chunk_hubs + 255) / 256), dim3(256), 0,
-                                               stream, pl, (const uint8_t *)Lc, S, E, Hhub, (uint8_t *)prop, c,
-                                               lo, (int)k, pass, P);
+                            hipLaunchKernelGGL(k_hub_finalize, dim3((unsigned)((max_chunk_hubs + 15) / 16)),
+                                               dim3(256), 0, stream, pl, (const uint8_t *)Lc, room, E, Hhub,
+                                               (uint8_t *)prop, cnt, (int)c, lo, (int)k, pass);
                         });
                 }
             } else if (use_lds) {
@@ -510,19 +512,30 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                                        prop, lo, hi, (int)k, pass, P, gather_limit);
                 });
             }
-            L.run(GREM_KERNEL_COUNT, [&] {
-                hipLaunchKernelGGL((k_count<LabelT>), dim3(admit_blocks), dim3(kAdmitThreads), count_lds,
-                                   stream, Lc, prop, lo, hi, (int)k, cnt);
-            });
-            L.run(GREM_KERNEL_SCAN, [&] {
-                hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), 0, stream, cnt, (int)admit_blocks,
-                                   (int)k, S, P, room);
-            });
-            L.run(GREM_KERNEL_APPLY, [&] {
-                hipLaunchKernelGGL((k_apply<LabelT>), dim3(admit_blocks), dim3(kAdmitThreads), apply_lds,
-                                   stream, Lc, prop, lo, hi, (int)k, cnt, room, (unsigned long long *)S,
-                                   ocnt, pass);
-            });
+            // admission: per-tile mover counts, their prefix over the tiles, ranks.  The two-phase score
+            // kernel has already counted the movers and taken the sizes' snapshot, and its tiles are few
+            // enough per partition that every k_apply workgroup adds up the earlier tiles' counts itself.
+            if (!sweep) {
+                L.run(GREM_KERNEL_COUNT, [&] {
+                    hipLaunchKernelGGL((k_count<LabelT>), dim3(admit_blocks), dim3(kAdmitThreads), count_lds,
+                                       stream, Lc, prop, lo, hi, (int)k, cnt);
+                });
+                L.run(GREM_KERNEL_SCAN, [&] {
+                    hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), 0, stream, cnt, (int)admit_blocks,
+                                       (int)k, S, P, room);
+                });
+                L.run(GREM_KERNEL_APPLY, [&] {
+                    hipLaunchKernelGGL((k_apply<LabelT, false>), dim3(admit_blocks), dim3(kAdmitThreads),
+                                       apply_lds, stream, Lc, prop, lo, hi, (int)k, cnt, room,
+                                       (unsigned long long *)S, ocnt, pass);
+                });
+            } else {
+                L.run(GREM_KERNEL_APPLY, [&] {
+                    hipLaunchKernelGGL((k_apply<LabelT, true>), dim3(admit_blocks), dim3(kAdmitThreads),
+                                       apply_lds, stream, Lc, prop, lo, hi, (int)k, cnt, room,
+                                       (unsigned long long *)S, ocnt, pass);
+                });
+            }
             if (pass == 0) {
                 L.run(GREM_KERNEL_SPILL_SCAN, [&] {
                     hipLaunchKernelGGL(k_spill_scan, dim3(1), dim3(kScanThreads), 0, stream, ocnt,

@@ -374,32 +374,64 @@ __device__ __forceinline__ int rank_among_equal(bool active, uint32_t t, int lan
 // ------------------------------------------------------------------------------------------------
 // apply: admit movers whose rank among the chunk's earlier movers to the same partition is below
 // the room; relabel; size deltas; in the first pass count the vertices left unassigned per tile.
+//   SELF_PREFIX = false: base[tile][t] = movers to t in earlier tiles (k_scan's output)
+//   SELF_PREFIX = true : base[tile][t] = movers to t in that tile; the workgroup adds up the rows of
+//                        the earlier tiles itself (no k_scan launch; pays when tiles * k is small)
+// room[t] = P - S[t] as of the chunk's start.
+// LDS: run[k], wcnt[nwaves * k], dS[k], tbl[k] (SELF_PREFIX)
 // ------------------------------------------------------------------------------------------------
-template <typename LabelT>
+template <typename LabelT, bool SELF_PREFIX>
 __global__ __launch_bounds__(kAdmitThreads) void k_apply(
     LabelT *__restrict__ Lc, const LabelT *__restrict__ prop, int64_t chunk_lo, int64_t chunk_hi,
     int k, const uint32_t *__restrict__ base, const long long *__restrict__ room,
     unsigned long long *__restrict__ S, uint32_t *__restrict__ ocnt, int pass) {
     extern __shared__ uint32_t smem[];
     constexpr int nwaves = kAdmitThreads / 64;
+    constexpr int rounds = kAdmitTile / kAdmitThreads;
     uint32_t *run = smem;                 // k       movers seen so far in this tile
     uint32_t *wcnt = run + k;             // nwaves*k movers of this round per wave
     int32_t *dS = (int32_t *)(wcnt + nwaves * k);   // k size deltas
+    uint32_t *tbl = (uint32_t *)(dS + k); // k       movers in earlier tiles (SELF_PREFIX)
     __shared__ uint32_t s_unassigned;
     constexpr uint32_t UN = LabelTraits<LabelT>::kUnassigned;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    for (int j = tid; j < k; j += kAdmitThreads) { run[j] = 0; dS[j] = 0; }
+    const int64_t lo = chunk_lo + (int64_t)blockIdx.x * kAdmitTile;
+
+    // this thread's vertices, one per round
+    uint32_t tv[rounds], oldv[rounds];
+#pragma unroll
+    for (int r = 0; r < rounds; ++r) {
+        const int64_t v = lo + r * kAdmitThreads + tid;
+        tv[r] = 0;
+        oldv[r] = 0;
+        if (v < chunk_hi) { tv[r] = prop[v - chunk_lo]; oldv[r] = (uint32_t)Lc[v]; }
+    }
+
+    for (int j = tid; j < k; j += kAdmitThreads) { run[j] = 0; dS[j] = 0; if (SELF_PREFIX) tbl[j] = 0; }
     for (int j = tid; j < nwaves * k; j += kAdmitThreads) wcnt[j] = 0;
     if (tid == 0) s_unassigned = 0;
     __syncthreads();
-    const int64_t lo = chunk_lo + (int64_t)blockIdx.x * kAdmitTile;
     const uint32_t *tbase = base + (size_t)blockIdx.x * k;
+    if (SELF_PREFIX) {
+        for (int c0 = 0; c0 < k; c0 += kAdmitThreads) {
+            const int kc = (k - c0) < kAdmitThreads ? (k - c0) : kAdmitThreads;
+            const int nseg = kAdmitThreads / kc;
+            const int col = tid % kc, seg = tid / kc;
+            if (seg < nseg) {
+                uint32_t sum = 0;
+                for (int t = seg; t < (int)blockIdx.x; t += nseg) sum += base[(size_t)t * k + c0 + col];
+                if (sum) atomicAdd(&tbl[c0 + col], sum);
+            }
+        }
+        __syncthreads();
+        tbase = tbl;
+    }
     uint32_t my_unassigned = 0;
-    for (int round = 0; round < kAdmitTile / kAdmitThreads; ++round) {
+#pragma unroll
+    for (int round = 0; round < rounds; ++round) {
         const int64_t v = lo + round * kAdmitThreads + tid;
         const bool inside = v < chunk_hi;
-        uint32_t t = 0, old = 0;
-        if (inside) { t = prop[v - chunk_lo]; old = (uint32_t)Lc[v]; }
+        const uint32_t t = tv[round], old = oldv[round];
         const bool mover = inside && t != old;
         int same_total; bool leader;
         const int wrank = rank_among_equal(mover, t, lane, &same_total, &leader);

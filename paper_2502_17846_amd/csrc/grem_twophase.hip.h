@@ -686,24 +686,28 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
     }
 }
 
-// Look-up results of two sub-segments, [sa, sa + la) and [sb, sb + lb) (even starts and lengths,
-// in 16-bit units from Xc), counted by one wavefront: lane l takes the two entries at offset 2l of
-// each, round after round.  COUNT16: regular rows, 16-bit counters, index = entry; else hub share,
-// 32-bit counters, index = hub * k + label.  Entries with bit 15 set are ignored.
-template <bool COUNT16>
-__device__ __forceinline__ void tp_count_pair(const uint32_t *__restrict__ Xc32, uint32_t sa, uint32_t la,
-                                              uint32_t sb, uint32_t lb, int lane, int k, uint32_t *hist) {
-    const uint32_t mx = la > lb ? la : lb;
+// Look-up results of NB sub-segments, [s[b], s[b] + l[b]) (even starts and lengths, in 16-bit
+// units from Xc; s and l are the same in every lane), counted by one wavefront: lane i takes the
+// two entries at offset 2i of each, round after round, all NB loads of a round in flight together.
+// COUNT16: regular rows, 16-bit counters, index = entry; else hub share, 32-bit counters, index =
+// hub * k + label.  Entries with bit 15 set are ignored.
+template <bool COUNT16, int NB>
+__device__ __forceinline__ void tp_count_group(const uint32_t *__restrict__ Xc32, const uint32_t (&s)[NB],
+                                               const uint32_t (&l)[NB], int lane, int k, uint32_t *hist) {
+    uint32_t mx = 0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) mx = l[b] > mx ? l[b] : mx;
     for (uint32_t r = 0; r < mx; r += 128) {
         const uint32_t off = r + 2u * (uint32_t)lane;
-        uint32_t w[2];
-        w[0] = off < la ? __builtin_nontemporal_load(Xc32 + ((sa + off) >> 1)) : 0x80008000u;
-        w[1] = off < lb ? __builtin_nontemporal_load(Xc32 + ((sb + off) >> 1)) : 0x80008000u;
+        uint32_t w[NB];
 #pragma unroll
-        for (int z = 0; z < 2; ++z) {
+        for (int b = 0; b < NB; ++b)
+            w[b] = off < l[b] ? __builtin_nontemporal_load(Xc32 + ((s[b] + off) >> 1)) : 0x80008000u;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const uint32_t x = h == 0 ? (w[z] & 0xFFFFu) : (w[z] >> 16);
+                const uint32_t x = h == 0 ? (w[b] & 0xFFFFu) : (w[b] >> 16);
                 if (x < 0x8000u) {
                     if (COUNT16) atomicAdd(&hist[x >> 1], 1u << ((x & 1u) << 4));
                     else atomicAdd(&hist[(x >> 4) * (uint32_t)k + (x & 15u)], 1u);
@@ -713,36 +717,86 @@ __device__ __forceinline__ void tp_count_pair(const uint32_t *__restrict__ Xc32,
     }
 }
 
+// The sub-segments a wavefront owns, NB at a time: lane t of (s0, l0) holds start and length of
+// the t-th of them, t < tmax <= 64.
+template <bool COUNT16, int NB>
+__device__ __forceinline__ void tp_count_list(const uint32_t *__restrict__ Xc32, uint32_t s0, uint32_t l0,
+                                              int tmax, int lane, int k, uint32_t *hist) {
+    for (int t = 0; t < tmax; t += NB) {
+        uint32_t s[NB], l[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            s[b] = 0;
+            l[b] = 0;
+            if (t + b < tmax) {
+                s[b] = (uint32_t)__builtin_amdgcn_readlane((int)s0, t + b);
+                l[b] = (uint32_t)__builtin_amdgcn_readlane((int)l0, t + b);
+            }
+        }
+        tp_count_group<COUNT16, NB>(Xc32, s, l, lane, k, hist);
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // score (phase 2): one workgroup per row slice of chunk c.  It counts the slice's sub-segment of
 // every column block in [0, jlim) (in the first pass of an unseeded run the blocks of chunks >= c
 // hold no label yet and their part of X has not been written), and, of hub share
 // (blockIdx.x % nvs), the sub-segments of the blocks congruent to (blockIdx.x / nvs) modulo the
-// number of workgroups per share, so that the hub entries are spread evenly too.
-// LDS: hist[kSliceRows * 8] (16-bit counters, 16 per row), hhist[share_hubs * k], room[k]
+// number of workgroups per share, so that the hub entries are spread evenly too.  Then it blends E,
+// proposes, and counts the movers of its two admission tiles per proposed partition (cnt, the input
+// of the admission; k_hub_finalize adds the hubs).
+//
+// Four lanes share a vertex in the blend: lane q owns partitions 4q .. 4q+3 when k % 4 == 0 (one
+// 16-byte piece of E's row), else q, q+4, q+8, q+12.
+// LDS: hist[kSliceRows * 8] (16-bit counters, 16 per row), meta[kSliceRows / 2] (per row: old label,
+//      hub flag << 8), hhist[share_hubs * k], room[k], tcnt[2 * k]
 // ------------------------------------------------------------------------------------------------
 template <typename RowT>
 __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     const RowT *__restrict__ rowptr, const uint16_t *__restrict__ X, TpTables tb, SweepPlan pl,
     const uint8_t *__restrict__ Lc, const long long *__restrict__ S, uint32_t *__restrict__ E,
-    uint32_t *__restrict__ Hhub, uint8_t *__restrict__ prop, int c, int64_t chunk_lo, int64_t chunk_hi,
-    int k, int jlim, int share_hubs, uint32_t hub_degree, int pass, long long P) {
+    uint32_t *__restrict__ Hhub, uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
+    long long *__restrict__ room_out, int c, int64_t chunk_lo, int64_t chunk_hi, int k, int jlim,
+    int share_hubs, uint32_t hub_degree, int pass, long long P) {
     extern __shared__ uint32_t smem[];
     constexpr int hist_words = kSliceRows * 8;
+    constexpr int BU = kSliceRows * 4 / kTpThreads;     // (vertex, quarter) pairs per thread
+    static_assert(kSliceRows == 2 * kAdmitTile, "a slice is two admission tiles");
     uint32_t *hist = smem;                      // hist_words
-    uint32_t *hhist = hist + hist_words;        // share_hubs * k        hubs of the share, 32-bit
+    uint16_t *meta = reinterpret_cast<uint16_t *>(hist + hist_words);   // kSliceRows
+    uint32_t *hhist = hist + hist_words + kSliceRows / 2;               // share_hubs * k, 32-bit
     uint32_t *room = hhist + share_hubs * k;    // k
+    uint32_t *tcnt = room + k;                  // 2 * k
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     constexpr int NW = kTpThreads / 64;
     const int64_t v0 = chunk_lo + (int64_t)blockIdx.x * kSliceRows;
     const int64_t left = chunk_hi - v0;
     const int nv = left < kSliceRows ? (int)left : kSliceRows;
+    const bool vec = (k & 3) == 0;
+
+    // the hub share this workgroup helps with
+    const uint32_t nvs = pl.ch_nvs[c];
+    const uint32_t share = nvs ? blockIdx.x % nvs : 0u;
+    const int cls = nvs ? (int)(blockIdx.x / nvs) : 0;
+    const int ncls = nvs ? (int)((gridDim.x - share + nvs - 1) / nvs) : 1;   // workgroups that took this share
+    const bool any_hub = nvs != 0 && pl.share_nhs[(size_t)c * tb.nsl + share] != 0;
+    const uint32_t share_h0 = pl.share_h0[(size_t)c * tb.nsl + share];
 
     {
         u32x4 *z = reinterpret_cast<u32x4 *>(hist);
         for (int q = tid; q < hist_words / 4; q += kTpThreads) z[q] = (u32x4)(0u);
         for (int q = tid; q < share_hubs * k; q += kTpThreads) hhist[q] = 0;
-        for (int j = tid; j < k; j += kTpThreads) room[j] = (uint32_t)(P - S[j]);
+        for (int j = tid; j < k; j += kTpThreads) {
+            const long long rj = P - S[j];
+            room[j] = (uint32_t)rj;
+            if (blockIdx.x == 0) room_out[j] = rj;      // the sizes' snapshot k_apply admits against
+        }
+        for (int j = tid; j < 2 * k; j += kTpThreads) tcnt[j] = 0;
+        for (int t = tid; t < nv; t += kTpThreads) {
+            const int64_t v = v0 + t;
+            const uint32_t hub = (u64)(rowptr[v + 1] - rowptr[v]) >= hub_degree ? 0x100u : 0u;
+            meta[t] = (uint16_t)((uint32_t)Lc[v] | hub);
+        }
     }
     __syncthreads();
 
@@ -763,103 +817,96 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
             }
             int tmax = (jlim - base - wave + NW - 1) / NW;      // blocks of this wave in this round
             if (tmax > 64) tmax = 64;
-            for (int t = 0; t < tmax; t += 2) {
-                const uint32_t sa = __builtin_amdgcn_readlane(s0, t), la = __builtin_amdgcn_readlane(l0, t);
-                uint32_t sb = 0, lb = 0;
-                if (t + 1 < tmax) {
-                    sb = __builtin_amdgcn_readlane(s0, t + 1);
-                    lb = __builtin_amdgcn_readlane(l0, t + 1);
-                }
-                tp_count_pair<true>(Xc32, sa, la, sb, lb, lane, k, hist);
-            }
+            tp_count_list<true, 8>(Xc32, s0, l0, tmax, lane, k, hist);
         }
     }
-    const uint32_t nvs = pl.ch_nvs[c];
-    uint32_t share = 0;
-    bool any_hub = false;
-    if (nvs != 0) {
-        share = blockIdx.x % nvs;
-        const int cls = (int)(blockIdx.x / nvs);
-        const int ncls = (int)((gridDim.x - share + nvs - 1) / nvs);      // workgroups that took this share
-        any_hub = pl.share_nhs[(size_t)c * tb.nsl + share] != 0;
-        if (any_hub) {
-            const uint32_t *q0 = tb.subH + ((size_t)c * (tb.nsl + 1) + share) * tb.nblk;
-            const uint32_t *q1 = q0 + tb.nblk;
-            const int mlim = jlim > cls ? (jlim - cls + ncls - 1) / ncls : 0;    // blocks cls + ncls * m < jlim
-            for (int base = 0; base < mlim; base += NW * 64) {
-                const int ml = base + wave + NW * lane;
-                uint32_t s0 = 0, l0 = 0;
-                if (ml < mlim) {
-                    const int jl = cls + ncls * ml;
-                    const uint32_t a0 = q0[jl];
-                    s0 = (uint32_t)(xs[jl] - xs0) + a0;
-                    l0 = q1[jl] - a0;
-                }
-                int tmax = (mlim - base - wave + NW - 1) / NW;
-                if (tmax > 64) tmax = 64;
-                for (int t = 0; t < tmax; t += 2) {
-                    const uint32_t sa = __builtin_amdgcn_readlane(s0, t), la = __builtin_amdgcn_readlane(l0, t);
-                    uint32_t sb = 0, lb = 0;
-                    if (t + 1 < tmax) {
-                        sb = __builtin_amdgcn_readlane(s0, t + 1);
-                        lb = __builtin_amdgcn_readlane(l0, t + 1);
-                    }
-                    tp_count_pair<false>(Xc32, sa, la, sb, lb, lane, k, hhist);
-                }
+    if (any_hub) {
+        const uint32_t *q0 = tb.subH + ((size_t)c * (tb.nsl + 1) + share) * tb.nblk;
+        const uint32_t *q1 = q0 + tb.nblk;
+        const int mlim = jlim > cls ? (jlim - cls + ncls - 1) / ncls : 0;    // blocks cls + ncls * m < jlim
+        for (int base = 0; base < mlim; base += NW * 64) {
+            const int ml = base + wave + NW * lane;
+            uint32_t s0 = 0, l0 = 0;
+            if (ml < mlim) {
+                const int jl = cls + ncls * ml;
+                const uint32_t a0 = q0[jl];
+                s0 = (uint32_t)(xs[jl] - xs0) + a0;
+                l0 = q1[jl] - a0;
             }
+            int tmax = (mlim - base - wave + NW - 1) / NW;
+            if (tmax > 64) tmax = 64;
+            tp_count_list<false, 8>(Xc32, s0, l0, tmax, lane, k, hhist);
         }
     }
     __syncthreads();
 
     // partial counts of the share's hubs -> the chunk's hub table
     if (any_hub) {
-        const uint32_t h0 = pl.share_h0[(size_t)c * tb.nsl + share];
         for (int q = tid; q < share_hubs * k; q += kTpThreads) {
             const uint32_t x = hhist[q];
-            if (x) atomicAdd(&Hhub[(size_t)h0 * k + q], x);
+            if (x) atomicAdd(&Hhub[(size_t)share_h0 * k + q], x);
         }
     }
 
-    // blend and propose: four lanes per regular vertex, lane q takes partitions q*4.. (k % 4 == 0)
-    // or q, q+4, .. (otherwise); arg-max by (E desc, room desc, id asc)
+    // this thread's pieces of E, all loads in flight together
+    uint32_t ev[BU][4];
+#pragma unroll
+    for (int u = 0; u < BU; ++u) {
+#pragma unroll
+        for (int z = 0; z < 4; ++z) ev[u][z] = 0;
+        const int g = tid + u * kTpThreads;
+        if (pass > 0 && g < nv * 4) {
+            const int t = g >> 2, q = g & 3;
+            const uint32_t *Erow = E + (size_t)(v0 + t) * (size_t)k;
+            if (vec) {
+                if (4 * q < k) {
+                    const u32x4 e = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Erow + 4 * q));
+                    ev[u][0] = e.x; ev[u][1] = e.y; ev[u][2] = e.z; ev[u][3] = e.w;
+                }
+            } else {
+#pragma unroll
+                for (int z = 0; z < 4; ++z)
+                    if (q + 4 * z < k) ev[u][z] = Erow[q + 4 * z];
+            }
+        }
+    }
+
+    // blend and propose; arg-max by (E desc, room desc, id asc)
     const int sh = pass > 0 ? pass - 1 : 0;
-    for (int g = tid; g < nv * 4; g += kTpThreads) {
+#pragma unroll
+    for (int u = 0; u < BU; ++u) {
+        const int g = tid + u * kTpThreads;
+        if (g >= nv * 4) continue;
         const int t = g >> 2, q = g & 3;
+        const uint32_t mt = meta[t];
+        if (mt & 0x100u) continue;                              // hubs are k_hub_finalize's
+        const uint32_t old = mt & 0xFFu;
         const int64_t v = v0 + t;
-        if ((u64)(rowptr[v + 1] - rowptr[v]) >= hub_degree) continue;      // k_hub_finalize's
-        const uint32_t old = (uint32_t)Lc[v];
         uint32_t *Erow = E + (size_t)v * (size_t)k;
         unsigned long long bestkey = 0;
         int bestj = 0x7fffffff;
-        const uint32_t cbase = (uint32_t)t * 16u;
-        if ((k & 3) == 0) {
-            for (int j4 = q * 4; j4 < k; j4 += 16) {
-                u32x4 e = (u32x4)(0u);
-                if (pass > 0) e = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Erow + j4));
-                const uint32_t w0 = hist[(cbase + j4) >> 1], w1 = hist[((cbase + j4) >> 1) + 1];
-                const uint32_t ev[4] = {e.x + ((w0 & 0xFFFFu) << sh), e.y + ((w0 >> 16) << sh),
-                                        e.z + ((w1 & 0xFFFFu) << sh), e.w + ((w1 >> 16) << sh)};
-                u32x4 o;
-                o.x = ev[0]; o.y = ev[1]; o.z = ev[2]; o.w = ev[3];
-                __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(Erow + j4));
 #pragma unroll
-                for (int z = 0; z < 4; ++z) {
-                    const int j = j4 + z;
-                    const uint32_t rm = room[j] + ((uint32_t)j == old ? 1u : 0u);
-                    const unsigned long long key = rm ? (((unsigned long long)ev[z] << 32) | rm) : 0ull;
-                    if (key > bestkey) { bestkey = key; bestj = j; }
-                }
-            }
-        } else {
-            for (int j = q; j < k; j += 4) {
-                const uint32_t cidx = cbase + (uint32_t)j;
+        for (int z = 0; z < 4; ++z) {
+            const int j = vec ? 4 * q + z : q + 4 * z;
+            if (j < k) {
+                const uint32_t cidx = (uint32_t)t * 16u + (uint32_t)j;
                 const uint32_t h = (hist[cidx >> 1] >> (16 * (cidx & 1u))) & 0xFFFFu;
-                const uint32_t e = (pass > 0 ? Erow[j] : 0u) + (h << sh);
-                Erow[j] = e;
+                ev[u][z] += h << sh;
                 const uint32_t rm = room[j] + ((uint32_t)j == old ? 1u : 0u);
-                const unsigned long long key = rm ? (((unsigned long long)e << 32) | rm) : 0ull;
+                const unsigned long long key = rm ? (((unsigned long long)ev[u][z] << 32) | rm) : 0ull;
                 if (key > bestkey) { bestkey = key; bestj = j; }
             }
+        }
+        if (vec) {
+            if (4 * q < k) {
+                u32x4 o;
+                o.x = ev[u][0]; o.y = ev[u][1]; o.z = ev[u][2]; o.w = ev[u][3];
+                __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(Erow + 4 * q));
+            }
+        } else {
+#pragma unroll
+            for (int z = 0; z < 4; ++z)
+                if (q + 4 * z < k) Erow[q + 4 * z] = ev[u][z];
         }
 #pragma unroll
         for (int off = 1; off <= 2; off <<= 1) {
@@ -871,42 +918,63 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
             uint32_t best = (uint32_t)bestj;
             if (pass == 0 && old != 0xFFu) best = old;      // seeded vertex keeps its label
             prop[v - chunk_lo] = (uint8_t)best;
+            if (best != old) atomicAdd(&tcnt[(t >> 10) * k + (int)best], 1u);
         }
+    }
+    __syncthreads();
+    {
+        const int64_t tile0 = (v0 - chunk_lo) / kAdmitTile;
+        const int ntl = nv > kAdmitTile ? 2 : 1;
+        for (int j = tid; j < ntl * k; j += kTpThreads) cnt[(size_t)tile0 * k + j] = tcnt[j];
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 // hubs of the chunk: counts from the hub table (complete once k_tp_score has finished), blend,
-// propose; the table row is cleared for the next chunk.
+// propose, add the movers to their tiles' counts; the table row is cleared for the next chunk.
+// 16 lanes per hub, lane j takes partition j (k <= 16).
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_t *__restrict__ Lc,
-                                                      const long long *__restrict__ S,
+                                                      const long long *__restrict__ room,
                                                       uint32_t *__restrict__ E, uint32_t *__restrict__ Hhub,
-                                                      uint8_t *__restrict__ prop, int64_t chunk_idx,
-                                                      int64_t chunk_lo, int k, int pass, long long P) {
-    const uint32_t nh = pl.ch_nh[chunk_idx];
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= nh) return;
-    const int64_t v = pl.hub_row[chunk_lo + i];
-    const uint32_t old = (uint32_t)Lc[v];
-    uint32_t *Erow = E + (size_t)v * (size_t)k;
-    uint32_t *hrow = Hhub + (size_t)i * k;
+                                                      uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
+                                                      int c, int64_t chunk_lo, int k, int pass) {
+    const uint32_t nh = pl.ch_nh[c];
+    const uint32_t i = blockIdx.x * 16u + (threadIdx.x >> 4);
+    const int j = threadIdx.x & 15;
+    const bool on = i < nh;
     const int sh = pass > 0 ? pass - 1 : 0;
-    unsigned long long bestkey = 0;
-    int bestj = 0x7fffffff;
-    for (int j = 0; j < k; ++j) {
-        const uint32_t h = hrow[j];
-        hrow[j] = 0;
-        const uint32_t e = (pass > 0 ? Erow[j] : 0u) + (h << sh);
-        Erow[j] = e;
-        const long long rml = P - S[j] + ((uint32_t)j == old ? 1 : 0);
-        const uint32_t rm = (uint32_t)rml;
-        unsigned long long key = rm ? (((unsigned long long)e << 32) | rm) : 0ull;
-        if (key > bestkey) { bestkey = key; bestj = j; }
+    unsigned long long key = 0;
+    int bj = 0x7fffffff;
+    int64_t v = 0;
+    uint32_t old = 0xFFu;
+    if (on) {
+        v = pl.hub_row[chunk_lo + i];
+        old = (uint32_t)Lc[v];
+        if (j < k) {
+            uint32_t *hp = Hhub + (size_t)i * k + j;
+            const uint32_t h = *hp;
+            *hp = 0;
+            uint32_t *ep = E + (size_t)v * (size_t)k + j;
+            const uint32_t e = (pass > 0 ? *ep : 0u) + (h << sh);
+            *ep = e;
+            const uint32_t rm = (uint32_t)room[j] + ((uint32_t)j == old ? 1u : 0u);
+            key = rm ? (((unsigned long long)e << 32) | rm) : 0ull;
+            bj = j;
+        }
     }
-    uint32_t best = (uint32_t)bestj;
-    if (pass == 0 && old != 0xFFu) best = old;
-    prop[v - chunk_lo] = (uint8_t)best;
+#pragma unroll
+    for (int off = 1; off <= 8; off <<= 1) {      // every lane of the wavefront takes part
+        const unsigned long long okey = __shfl_xor(key, off);
+        const int oj = __shfl_xor(bj, off);
+        if (okey > key || (okey == key && oj < bj)) { key = okey; bj = oj; }
+    }
+    if (on && j == 0) {
+        uint32_t best = (uint32_t)bj;
+        if (pass == 0 && old != 0xFFu) best = old;
+        prop[v - chunk_lo] = (uint8_t)best;
+        if (best != old) atomicAdd(&cnt[(size_t)((v - chunk_lo) / kAdmitTile) * k + best], 1u);   // after k_tp_score's store
+    }
 }
 
 }  // namespace grem
