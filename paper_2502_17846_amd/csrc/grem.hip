@@ -65,7 +65,7 @@ TpGeom tp_geometry(int64_t n, int64_t chunk, int col_bits_setting) {
     t.chunk = (uint32_t)cl;
     for (int b = 0; b < 31; ++b)
         if ((1ll << b) == cl) t.shift = b;
-    t.ok = nblk <= kMaxBlocks && nch * nblk <= kMaxSegments && nch * nsl < (1ll << 31) &&
+    t.ok = nblk <= kMaxBlocks && nch * nblk <= kMaxSegments && nch * nsl < (1ll << 28) &&
            nch * (nsl + 1) * nblk < (1ll << 40);
     if (t.ok) {
         t.nbc = (int)nbc; t.nblk = (int)nblk; t.nch = (int)nch; t.nsl = (int)nsl;
@@ -91,8 +91,10 @@ inline int64_t slices_per_chunk(int64_t n, int64_t chunk) {
     return (cl + kSliceRows - 1) / kSliceRows;
 }
 
+constexpr int kMaxParts = 8;      // parts of a slice (hub share) in the re-layout
+
 Layout make_layout(int64_t n, int64_t nnz, int64_t hub_entries, int32_t k, int64_t chunk, bool external_E,
-                   const TpGeom &tp, int hub_degree) {
+                   const TpGeom &tp, int hub_degree, int npr = kMaxParts, int nps = kMaxParts) {
     Layout L{};
     const int64_t cl = chunk < n ? chunk : n;
     const size_t lab = k <= 255 ? 1 : 2;
@@ -142,8 +144,8 @@ Layout make_layout(int64_t n, int64_t nnz, int64_t hub_entries, int32_t k, int64
         L.subH = take(rows * (size_t)tp.nblk * 4);
         L.xstart = take((segs + 1) * 8);
         L.tstart = take((segs + 1) * 8);
-        L.lo = take(G * ((size_t)tp.ngroups + 1) * 4);
-        L.loh = take(G * ((size_t)tp.ngroups + 1) * 4);
+        L.lo = take(G * (size_t)npr * ((size_t)tp.ngroups + 1) * 4);
+        L.loh = take(G * (size_t)nps * ((size_t)tp.ngroups + 1) * 4);
         L.Hhub = take(hubs * (size_t)k * 4);
         // every sub-segment is padded to even, every segment to a multiple of 8
         const size_t slots = (size_t)(nnz > 0 ? nnz : 0) + 2 * rows * (size_t)tp.nblk + 8 * segs;
@@ -298,6 +300,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                     hipLaunchKernelGGL(k_tp_scan_segments, dim3(1), dim3(1024), 0, stream, only_nch, pl.ch_hbase, 2);
                 });
             }
+
             L.run(GREM_KERNEL_RELAYOUT, [&] {
                 hipLaunchKernelGGL((k_plan_hubs<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, cl, nsl,
                                    (uint32_t)hub_degree, pl);
@@ -385,8 +388,6 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 tb.subH = (uint32_t *)(xbase + lay.subH);
                 tb.xstart = (u64 *)(xbase + lay.xstart);
                 tb.tstart = (u64 *)(xbase + lay.tstart);
-                tb.lo = (uint32_t *)(xbase + lay.lo);
-                tb.loh = (uint32_t *)(xbase + lay.loh);
                 tb.chunk = geo.chunk;
                 tb.chunk_shift = geo.shift;
                 tb.nch = geo.nch;
@@ -394,25 +395,49 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 tb.nbc = geo.nbc;
                 tb.nblk = geo.nblk;
                 tb.cb = geo.cb;
-                tb.gb = geo.gb;
-                tb.ngroups = geo.ngroups;
                 Hhub = (uint32_t *)(xbase + lay.Hhub);
                 T = (uint32_t *)(xbase + lay.T);
                 X = (uint16_t *)(xbase + lay.X);
+                tb.gb = geo.gb;
+                tb.ngroups = geo.ngroups;
+                tb.lo = (uint32_t *)(xbase + lay.lo);
+                tb.loh = (uint32_t *)(xbase + lay.loh);
                 uint32_t *U = (uint32_t *)(xbase + lay.U);
                 uint32_t *Uh = (uint32_t *)(xbase + lay.Uh);
+                // step 1 collects a unit's tuples in LDS: cut the slices (shares) in as many parts as it
+                // takes for the largest to fit, two workgroups per CU
+                constexpr size_t kGroupLds = 79 * 1024, kPlaceLds = 52 * 1024;
+                auto group_fixed = [&](bool share, int np) {
+                    return (tp_source_words(share, np, share_hubs) + (size_t)geo.nblk + 2 * (size_t)geo.ngroups + 1) * 4;
+                };
+                auto group_cap = [&](bool share, int np) {
+                    const size_t fixed = group_fixed(share, np);
+                    return (uint32_t)(kGroupLds > fixed ? (kGroupLds - fixed) / 4 : 0);
+                };
+                int npr = 1, nps = 1;
+                while (npr < kMaxParts && group_cap(false, npr) < h_misc[9] / npr + h_misc[9] / (8ull * npr) + 64) npr *= 2;
+                while (nps < kMaxParts && group_cap(true, nps) < h_misc[10] / nps + h_misc[10] / (8ull * nps) + 64) nps += 1;
+                tb.npr = npr;
+                tb.nps = nps;
+                const uint32_t capR = group_cap(false, npr), capS = group_cap(true, nps);
+                const size_t groupR_lds = group_fixed(false, npr) + (size_t)capR * 4;
+                const size_t groupS_lds = group_fixed(true, nps) + (size_t)capS * 4;
+                // step 2: up to 8 slices at a time
                 const int nbg = geo.nblk < (1 << geo.gb) ? geo.nblk : (1 << geo.gb);
                 int batch = 8192 / nbg;
                 if (batch > 8) batch = 8;
                 if (batch < 1) batch = 1;
-                const size_t slice_lds = ((size_t)kSliceRows + 1 + (size_t)geo.nblk + (size_t)geo.ngroups + 1) * 4;
-                const size_t share_lds = (size_t)(2 * kMaxShareHubs + 1) * 8 +
-                                         ((size_t)geo.nblk + (size_t)geo.ngroups + 1) * 4;
-                const size_t place_lds = ((size_t)nbg + (size_t)batch) * 8 +
-                                         ((size_t)batch + 1 + (size_t)batch * nbg) * 4;
+                const int maxruns = batch * (npr > nps ? npr : nps);
+                const size_t place_fixed = ((size_t)nbg + maxruns) * 8 +
+                                           ((size_t)2 * maxruns + 1 + 2 * (size_t)nbg + 1 + (size_t)batch * nbg) * 4;
+                const uint32_t capP = (uint32_t)(kPlaceLds > place_fixed ? (kPlaceLds - place_fixed) / 4 : 0);
+                const size_t place_lds = place_fixed + (size_t)capP * 4;
+                const size_t rows = (size_t)geo.nch * ((size_t)geo.nsl + 1);
                 if (hipMemsetAsync(Hhub, 0, lay.hub_rows_cap * (size_t)k * 4, stream) != hipSuccess ||
-                    !set_lds((const void *)k_tp_sort_slice<RowT>, slice_lds) ||
-                    !set_lds((const void *)k_tp_sort_share<RowT>, share_lds) ||
+                    hipMemsetAsync(tb.subR, 0, rows * (size_t)geo.nblk * 4, stream) != hipSuccess ||
+                    hipMemsetAsync(tb.subH, 0, rows * (size_t)geo.nblk * 4, stream) != hipSuccess ||
+                    !set_lds((const void *)k_tp_group<RowT, false>, groupR_lds) ||
+                    !set_lds((const void *)k_tp_group<RowT, true>, groupS_lds) ||
                     !set_lds((const void *)k_tp_place<RowT>, place_lds) ||
                     !set_lds((const void *)k_tp_lookup<true>, tp_lookup_lds) ||
                     !set_lds((const void *)k_tp_score<RowT>, tp_score_lds)) {
@@ -423,12 +448,14 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 const unsigned G = (unsigned)(nchunks * nsl);
                 const unsigned segs = (unsigned)((int64_t)geo.nch * geo.nblk);
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_tp_sort_slice<RowT>), dim3(G), dim3(kTpThreads), slice_lds, stream,
-                                       rowptr, colidx, n, (uint32_t)hub_degree, pl, tb, U);
+                    hipLaunchKernelGGL((k_tp_group<RowT, false>), dim3(G * (unsigned)npr), dim3(kTpThreads),
+                                       groupR_lds, stream, rowptr, colidx, n, (uint32_t)hub_degree, pl, tb,
+                                       share_hubs, capR, U);
                 });
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_tp_sort_share<RowT>), dim3(G), dim3(256), share_lds, stream, rowptr,
-                                       colidx, n, pl, tb, Uh);
+                    hipLaunchKernelGGL((k_tp_group<RowT, true>), dim3(G * (unsigned)nps), dim3(kTpThreads),
+                                       groupS_lds, stream, rowptr, colidx, n, (uint32_t)hub_degree, pl, tb,
+                                       share_hubs, capS, Uh);
                 });
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
                     hipLaunchKernelGGL(k_tp_scan_slices, dim3((segs + 255) / 256), dim3(256), 0, stream, tb);
@@ -438,7 +465,8 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 });
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
                     hipLaunchKernelGGL((k_tp_place<RowT>), dim3((unsigned)((int64_t)geo.ngroups * geo.nch)),
-                                       dim3(256), place_lds, stream, rowptr, n, pl, tb, U, Uh, T, batch);
+                                       dim3(kPlaceThreads), place_lds, stream, rowptr, n, pl, tb, U, Uh, T, batch,
+                                       capP);
                 });
             }
         }

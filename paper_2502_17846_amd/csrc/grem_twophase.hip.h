@@ -81,8 +81,12 @@ struct TpTables {
     uint32_t *subH;   // same shape: start of share i's sub-segment; row nsl: end of the segment
     u64 *xstart;      // [nch][nblk] (+1): first slot of segment (c, jb) in X
     u64 *tstart;      // [nblk][nch] (+1): first slot of segment (c, jb) in T
-    uint32_t *lo;     // [nch * nsl][ngroups + 1]: start of block group g's run inside the slice's range of U
-    uint32_t *loh;    // same for the hub shares and Uh
+    uint32_t *lo;     // [nch * nsl * npr][ngroups + 1]: start of block group g's run inside the unit's range of U
+    uint32_t *loh;    // [nch * nsl * nps][ngroups + 1]: the same for the parts of the hub shares and Uh
+    int npr;          // parts per slice (a power of two: equal row ranges)
+    int nps;          // parts per hub share (equal ranges of its entries)
+    int gb;           // log2 of the column blocks per group of the intermediate copy U
+    int ngroups;      // ceil(nblk / 2^gb)
     uint32_t chunk;   // rows per chunk (already clamped to n)
     int chunk_shift;  // log2(chunk) when it is a power of two, else -1
     int nch;          // chunks
@@ -90,8 +94,6 @@ struct TpTables {
     int nbc;          // column blocks per chunk
     int nblk;         // nch * nbc
     int cb;           // log2 of the vertices per column block
-    int gb;           // log2 of the column blocks per group of the intermediate copy U
-    int ngroups;      // ceil(nblk / 2^gb)
 };
 
 __device__ __forceinline__ uint32_t tp_block_of(uint32_t u, const TpTables &g, uint32_t *col_low) {
@@ -169,7 +171,9 @@ __global__ __launch_bounds__(256) void k_plan_slices(const RowT *__restrict__ ro
 // plan 2: per chunk, exclusive prefixes over its slices, and the number of hub shares: enough
 // shares that one touches at most about 1024 hubs, few enough that a share's sub-segment of a
 // column block still holds some 64 entries, at most one per slice.  misc[6] = most hubs in a
-// chunk, misc[7] = most entries in a chunk, misc[8] = hub entries of all chunks.
+// chunk, misc[7] = most entries in a chunk, misc[9] = most regular entries in a slice (set here
+// from the slices' counts), misc[10] = most entries in a hub share, misc[8] = hub entries of all
+// chunks.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, int nsl, int nblk,
                                                      SweepPlan pl, u64 *__restrict__ misc) {
@@ -184,11 +188,15 @@ __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, i
     const int q1 = (q0 + per < nsl) ? q0 + per : nsl;
     u64 reg = 0, hent = 0;
     uint32_t nh = 0;
+    u64 maxreg = 0;
     for (int q = q0; q < q1; ++q) {
-        reg += pl.sl_reg_cnt[g0 + q];
+        const u64 rq = pl.sl_reg_cnt[g0 + q];
+        reg += rq;
+        maxreg = rq > maxreg ? rq : maxreg;
         nh += pl.sl_nh[g0 + q];
         hent += pl.sl_hent[g0 + q];
     }
+    if (maxreg) atomicMax(&misc[9], maxreg);
     p_reg[tid] = reg; p_nh[tid] = nh; p_hent[tid] = hent;
     __syncthreads();
     u64 breg = 0, bhent = 0;
@@ -221,6 +229,7 @@ __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, i
         pl.ch_nvs[c] = (uint32_t)nvs;
         atomicMax(&misc[6], (u64)bnh);
         atomicMax(&misc[7], breg + bhent);
+        if (nvs) atomicMax(&misc[10], bhent / nvs + 1);
         atomicAdd(&misc[8], bhent);
     }
 }
@@ -293,162 +302,271 @@ __global__ __launch_bounds__(256) void k_plan_shares(int64_t n, int64_t chunk, i
     pl.share_nhs[gs] = nhs;
 }
 
-// ------------------------------------------------------------------------------------------------
-// Re-layout, step 1 (regular rows of one slice): count the slice's entries per column block
-// (-> subR[row(c,i)][*], raw counts) and write them, grouped by column-block GROUP (2^gb consecutive
-// blocks), into U at the slice's own CSR positions: the slice's range of U then holds ngroups runs,
-// run g starting at lo[gs][g].  Few runs per workgroup keep every write stream in L2 until its
-// lines are full.  U tuple: row_in_slice << (cb + gb) | block_in_group << cb | column_in_block.
-// LDS: rowrel[kSliceRows + 1], cntf[nblk], cur[ngroups + 1]
-// ------------------------------------------------------------------------------------------------
-template <typename RowT>
-__global__ __launch_bounds__(kTpThreads) void k_tp_sort_slice(const RowT *__restrict__ rowptr,
-                                                              const int32_t *__restrict__ colidx, int64_t n,
-                                                              uint32_t hub_degree, SweepPlan pl, TpTables tb,
-                                                              uint32_t *__restrict__ U) {
-    extern __shared__ uint32_t smem[];
-    uint32_t *rowrel = smem;                        // kSliceRows + 1
-    uint32_t *cntf = rowrel + kSliceRows + 1;       // nblk
-    uint32_t *cur = cntf + tb.nblk;                 // ngroups + 1
+// The re-layout works on UNITS: part q of the `npr` equal row ranges of a slice (SHARE = false), or
+// part q of the `nps` equal ranges of a hub share's piece of the chunk's hub entry stream
+// (SHARE = true).  A unit's entries are contiguous in the CSR (or in the stream), and few enough
+// that its tuples fit in LDS.  tp_load_round hands them to the workgroup's threads: (row field,
+// column) for each, the row field being the row's index in the slice, or the hub's index among
+// the hubs the share touches.
+//   regular: rowrel[rp + 1] in LDS (rp rows per part, a power of two), entries colidx[e0 ..);
+//            rows of degree >= hub_degree are skipped
+//   share  : stream positions [a, a + len); hoff[nhs + 1] / hrow[nhs] in LDS
+struct TpEntrySource {
+    const int32_t *colidx;
+    // regular
+    const uint32_t *rowrel;
+    int64_t e0;
+    uint32_t ne, hub_degree, row0;
+    int rp;
+    bool has_hubs;
+    // share
+    const u64 *hoff, *hrow;
+    u64 a;
+    uint32_t len, nhs;
+};
+
+constexpr int kTpBatch = 8;      // entries per thread and round
+
+// The workgroup visits the unit's entries in rounds of kTpThreads * kTpBatch; tp_load_round gives a
+// thread its kTpBatch entries of a round (row field, column, on[u] = false: no entry), all loads and
+// searches side by side so that their latencies overlap.
+template <bool SHARE>
+__device__ __forceinline__ uint32_t tp_rounds(const TpEntrySource &src) {
+    const uint32_t ne = SHARE ? src.len : src.ne;
+    return (ne + kTpThreads * kTpBatch - 1) / (kTpThreads * kTpBatch);
+}
+
+template <bool SHARE>
+__device__ __forceinline__ void tp_load_round(const TpEntrySource &src, uint32_t round, uint32_t (&row)[kTpBatch],
+                                              uint32_t (&col)[kTpBatch], bool (&on)[kTpBatch]) {
+    constexpr int U = kTpBatch;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    constexpr int NW = kTpThreads / 64;
+    if (!SHARE) {
+        // a wavefront takes 64 * U consecutive entries: their rows span a short range, found once (two
+        // searches side by side), inside which every lane then looks for its own (U searches side by
+        // side, the same number of steps for all)
+        const int32_t *cbase = src.colidx + src.e0;
+        const uint32_t blk = (round * NW + (uint32_t)wave) * 64u * U;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t p = blk + u * 64 + lane;
+            on[u] = p < src.ne;
+            col[u] = on[u] ? (uint32_t)__builtin_nontemporal_load(cbase + p) : 0u;
+            row[u] = 0;
+        }
+        if (blk >= src.ne) return;
+        const uint32_t last = blk + 64u * U - 1u < src.ne ? blk + 64u * U - 1u : src.ne - 1u;
+        uint32_t rlo = 0, rhi = 0;
+        for (int step = src.rp >> 1; step >= 1; step >>= 1) {
+            if (src.rowrel[rlo + step] <= blk) rlo += step;
+            if (src.rowrel[rhi + step] <= last) rhi += step;
+        }
+        uint32_t span = 1;
+        while (span <= rhi - rlo) span <<= 1;               // > rhi - rlo
+#pragma unroll
+        for (int u = 0; u < U; ++u) row[u] = rlo;
+        for (uint32_t step = span >> 1; step >= 1; step >>= 1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t cand = row[u] + step;        // largest r in [rlo, rhi] with rowrel[r] <= p
+                const uint32_t cc = cand <= rhi ? cand : rhi;
+                if (cand <= rhi && src.rowrel[cc] <= blk + u * 64 + lane) row[u] = cand;
+            }
+        }
+        if (src.has_hubs) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (src.rowrel[row[u] + 1] - src.rowrel[row[u]] >= src.hub_degree) on[u] = false;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) row[u] += src.row0;
+    } else {
+        const uint32_t base = round * kTpThreads * U + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t p = base + u * kTpThreads;
+            on[u] = p < src.len;
+            col[u] = 0;
+            row[u] = 0;
+            if (on[u]) {
+                const u64 e = src.a + p;                     // position in the chunk's hub entry stream
+                uint32_t lo = 0, hi = src.nhs;
+                while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (src.hoff[mid] <= e) lo = mid; else hi = mid; }
+                row[u] = lo;
+                col[u] = (uint32_t)__builtin_nontemporal_load(src.colidx + (int64_t)(src.hrow[lo] + (e - src.hoff[lo])));
+            }
+        }
+    }
+}
+
+// Sets up the entry source of part q (of np) of slice or share (c, i) in LDS (`lds` must hold
+// kSliceRows / np + 1 u32 for a slice, or 2 * share_hubs + 1 u64 for a share); false if the unit
+// has no rows / does not exist.  Ends with a barrier when it returns true.
+template <typename RowT, bool SHARE>
+__device__ __forceinline__ bool tp_entry_source(const RowT *__restrict__ rowptr,
+                                                const int32_t *__restrict__ colidx, int64_t n,
+                                                uint32_t hub_degree, const SweepPlan &pl, const TpTables &tb,
+                                                int64_t c, int i, int q, int np, int share_hubs, void *lds,
+                                                TpEntrySource *src) {
     const int tid = threadIdx.x;
-    const int64_t c = blockIdx.x / tb.nsl;
-    const int i = blockIdx.x % tb.nsl;
     const int64_t chunk_lo = c * (int64_t)tb.chunk;
     const int64_t chunk_hi = (chunk_lo + tb.chunk < n) ? chunk_lo + tb.chunk : n;
-    const int64_t v0 = chunk_lo + (int64_t)i * kSliceRows;
-    uint32_t *row_out = tb.subR + ((size_t)c * (tb.nsl + 1) + i) * tb.nblk;
-    uint32_t *lo_out = tb.lo + (size_t)blockIdx.x * (tb.ngroups + 1);
-    if (v0 >= chunk_hi) {                       // slice beyond the (ragged) chunk: no entries
-        for (int j = tid; j < tb.nblk; j += kTpThreads) row_out[j] = 0;
+    const size_t gs = (size_t)c * tb.nsl + i;
+    src->colidx = colidx;
+    if (!SHARE) {
+        const int rp = kSliceRows / np;
+        const int64_t v0 = chunk_lo + (int64_t)i * kSliceRows + (int64_t)q * rp;
+        if (v0 >= chunk_hi) return false;                       // part beyond the (ragged) chunk
+        uint32_t *rowrel = reinterpret_cast<uint32_t *>(lds);
+        const int64_t left = chunk_hi - v0;
+        const int nv = left < rp ? (int)left : rp;
+        const int64_t e0 = (int64_t)rowptr[v0];
+        for (int t = tid; t <= rp; t += kTpThreads) {
+            const int tt = t < nv ? t : nv;
+            rowrel[t] = (uint32_t)((int64_t)rowptr[v0 + tt] - e0);
+        }
+        __syncthreads();
+        src->rowrel = rowrel;
+        src->e0 = e0;
+        src->ne = rowrel[rp];
+        src->hub_degree = hub_degree;
+        src->row0 = (uint32_t)(q * rp);
+        src->rp = rp;
+        src->has_hubs = pl.sl_nh[gs] != 0;
+        return true;
+    } else {
+        const uint32_t nvs = pl.ch_nvs[c];
+        const uint32_t h0 = pl.share_h0[gs], nhs = pl.share_nhs[gs];
+        if ((uint32_t)i >= nvs || nhs == 0 || nhs > (uint32_t)share_hubs) return false;
+        u64 *hoff = reinterpret_cast<u64 *>(lds);                // nhs + 1  stream offsets of the hubs
+        u64 *hrow = hoff + share_hubs + 1;                       // nhs      rowptr of the hub
+        const u64 H = pl.ch_H[c];
+        const u64 a = H * (u64)i / nvs, b = H * (u64)(i + 1) / nvs;
+        const u64 pa = a + (b - a) * (u64)q / (u64)np, pb = a + (b - a) * (u64)(q + 1) / (u64)np;
+        const u64 *goff = pl.hub_off + chunk_lo + c;
+        for (uint32_t t = tid; t <= nhs; t += kTpThreads) hoff[t] = goff[h0 + t];
+        for (uint32_t t = tid; t < nhs; t += kTpThreads) hrow[t] = (u64)rowptr[pl.hub_row[chunk_lo + h0 + t]];
+        __syncthreads();
+        src->hoff = hoff;
+        src->hrow = hrow;
+        src->a = pa;
+        src->len = (uint32_t)(pb - pa);
+        src->nhs = nhs;
+        return true;
+    }
+}
+
+// u32 words of LDS the entry source takes (even, so that what follows is 8-byte aligned)
+__device__ __host__ inline size_t tp_source_words(bool share, int np, int share_hubs) {
+    return share ? 2 * ((size_t)2 * share_hubs + 1) : (((size_t)kSliceRows / np + 2) & ~(size_t)1);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Re-layout, step 1 (one unit per workgroup, blockIdx.x = (c * nsl + i) * np + q): count the unit's
+// entries per column block (added to subR / subH [row(c,i)][*], which start at zero and become
+// starts in k_tp_scan_slices), and copy its tuples, grouped by column-block GROUP (2^gb consecutive
+// blocks), to the unit's own range of U (Uh for shares): the entries' own positions in the CSR
+// (in the hub entry stream).  Run g of the unit starts at lo[unit][g].  The tuples are collected
+// in LDS and written as one contiguous piece (a lane-by-lane scatter would cost one L2 request per
+// tuple); a unit with more than `cap` tuples writes them one by one instead.
+// U tuple: row field << (cb + gb) | block in group << cb | column in block.
+// LDS: the entry source's tables, cntf[nblk], cg[ngroups + 1], cur[ngroups], stage[cap]
+// ------------------------------------------------------------------------------------------------
+template <typename RowT, bool SHARE>
+__global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tp_group(const RowT *__restrict__ rowptr,
+                                                         const int32_t *__restrict__ colidx, int64_t n,
+                                                         uint32_t hub_degree, SweepPlan pl, TpTables tb,
+                                                         int share_hubs, uint32_t cap,
+                                                         uint32_t *__restrict__ U) {
+    extern __shared__ u64 smem64[];
+    const int np = SHARE ? tb.nps : tb.npr;
+    uint32_t *cntf = reinterpret_cast<uint32_t *>(smem64) + tp_source_words(SHARE, np, share_hubs);   // nblk
+    uint32_t *cg = cntf + tb.nblk;              // ngroups + 1: tuples per group, then starts
+    uint32_t *cur = cg + tb.ngroups + 1;        // ngroups: next free slot of the group
+    uint32_t *stage = cur + tb.ngroups;         // cap
+    const int tid = threadIdx.x;
+    const unsigned gs = blockIdx.x / (unsigned)np;
+    const int q = (int)(blockIdx.x % (unsigned)np);
+    const int64_t c = gs / tb.nsl;
+    const int i = gs % tb.nsl;
+    uint32_t *lo_out = (SHARE ? tb.loh : tb.lo) + (size_t)blockIdx.x * (tb.ngroups + 1);
+    TpEntrySource src;
+    if (!tp_entry_source<RowT, SHARE>(rowptr, colidx, n, hub_degree, pl, tb, c, i, q, np, share_hubs, smem64,
+                                      &src)) {
         for (int j = tid; j <= tb.ngroups; j += kTpThreads) lo_out[j] = 0;
         return;
     }
-    const int64_t left = chunk_hi - v0;
-    const int nv = left < kSliceRows ? (int)left : kSliceRows;
-    const int64_t e0 = (int64_t)rowptr[v0];
-    for (int q = tid; q <= kSliceRows; q += kTpThreads) {
-        int qq = q < nv ? q : nv;
-        rowrel[q] = (uint32_t)((int64_t)rowptr[v0 + qq] - e0);
-    }
     for (int j = tid; j < tb.nblk; j += kTpThreads) cntf[j] = 0;
     __syncthreads();
-    const uint32_t ne = rowrel[kSliceRows];
-    const int32_t *cbase = colidx + e0;
-    const bool has_hubs = pl.sl_nh[blockIdx.x] != 0;
-    for (uint32_t p = tid; p < ne; p += kTpThreads) {
-        if (has_hubs) {
-            const int r = owning_row(rowrel, p, kSliceRows);
-            if (rowrel[r + 1] - rowrel[r] >= hub_degree) continue;
+    // a unit of one round (the usual case) keeps its entries in registers between the two phases
+    const uint32_t rounds = tp_rounds<SHARE>(src);
+    uint32_t row[kTpBatch], col[kTpBatch];
+    bool on[kTpBatch];
+    for (uint32_t r = 0; r < rounds; ++r) {
+        tp_load_round<SHARE>(src, r, row, col, on);
+#pragma unroll
+        for (int u = 0; u < kTpBatch; ++u) {
+            uint32_t low;
+            if (on[u]) atomicAdd(&cntf[tp_block_of(col[u], tb, &low)], 1u);
         }
-        uint32_t low;
-        const uint32_t jb = tp_block_of((uint32_t)cbase[p], tb, &low);
-        atomicAdd(&cntf[jb], 1u);
     }
     __syncthreads();
-    for (int j = tid; j < tb.nblk; j += kTpThreads) row_out[j] = cntf[j];
+    uint32_t *row_out = (SHARE ? tb.subH : tb.subR) + ((size_t)c * (tb.nsl + 1) + i) * tb.nblk;
+    for (int j = tid; j < tb.nblk; j += kTpThreads)
+        if (cntf[j]) atomicAdd(&row_out[j], cntf[j]);
     for (int gq = tid; gq < tb.ngroups; gq += kTpThreads) {
         const int j0 = gq << tb.gb;
         const int j1 = (j0 + (1 << tb.gb)) < tb.nblk ? j0 + (1 << tb.gb) : tb.nblk;
         uint32_t sum = 0;
         for (int j = j0; j < j1; ++j) sum += cntf[j];
-        cur[gq] = sum;
+        cg[gq] = sum;
     }
     __syncthreads();
-    if (tid == 0) {
+    if (tb.ngroups <= 64) {
+        if (tid < 64) {                                 // exclusive prefix over the groups by one wavefront
+            const uint32_t mine = tid < tb.ngroups ? cg[tid] : 0u;
+            uint32_t inc = mine;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t o = __shfl_up(inc, off);
+                if (tid >= off) inc += o;
+            }
+            if (tid < tb.ngroups) { cg[tid] = inc - mine; cur[tid] = inc - mine; }
+            if (tid == tb.ngroups - 1) cg[tb.ngroups] = inc;
+        }
+    } else if (tid == 0) {
         uint32_t run = 0;
-        for (int gq = 0; gq < tb.ngroups; ++gq) { const uint32_t t = cur[gq]; cur[gq] = run; run += t; }
-        cur[tb.ngroups] = run;
+        for (int gq = 0; gq < tb.ngroups; ++gq) { const uint32_t t = cg[gq]; cg[gq] = run; cur[gq] = run; run += t; }
+        cg[tb.ngroups] = run;
     }
     __syncthreads();
-    for (int gq = tid; gq <= tb.ngroups; gq += kTpThreads) lo_out[gq] = cur[gq];
-    __syncthreads();
+    for (int gq = tid; gq <= tb.ngroups; gq += kTpThreads) lo_out[gq] = cg[gq];
+    const uint32_t total = cg[tb.ngroups];
+    const bool staged = total <= cap;
     const uint32_t gmask = (1u << tb.gb) - 1u;
-    uint32_t *ubase = U + e0;
-    for (uint32_t p = tid; p < ne; p += kTpThreads) {
-        const uint32_t r = (uint32_t)owning_row(rowrel, p, kSliceRows);
-        if (has_hubs && rowrel[r + 1] - rowrel[r] >= hub_degree) continue;
-        uint32_t low;
-        const uint32_t jb = tp_block_of((uint32_t)cbase[p], tb, &low);
-        const uint32_t w = atomicAdd(&cur[jb >> tb.gb], 1u);
-        ubase[w] = (r << (tb.cb + tb.gb)) | ((jb & gmask) << tb.cb) | low;
+    uint32_t *ubase = U + (SHARE ? pl.ch_hbase[c] + src.a : (u64)src.e0);
+    for (uint32_t r = 0; r < rounds; ++r) {
+        if (rounds > 1) tp_load_round<SHARE>(src, r, row, col, on);
+        uint32_t w[kTpBatch], tuple[kTpBatch];
+#pragma unroll
+        for (int u = 0; u < kTpBatch; ++u) {
+            uint32_t low;
+            const uint32_t jb = tp_block_of(col[u], tb, &low);
+            tuple[u] = (row[u] << (tb.cb + tb.gb)) | ((jb & gmask) << tb.cb) | low;
+            w[u] = on[u] ? atomicAdd(&cur[jb >> tb.gb], 1u) : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < kTpBatch; ++u) {
+            if (on[u]) {
+                if (staged) stage[w[u]] = tuple[u];
+                else ubase[w[u]] = tuple[u];
+            }
+        }
     }
-}
-
-// ------------------------------------------------------------------------------------------------
-// Re-layout, step 1 for one share of the chunk's hub entries (see k_plan_shares): the same, into
-// Uh at the share's range of the hub entry stream (chunk c's stream starts at ch_hbase[c]); U
-// tuples carry the hub's index relative to the share's first hub.
-// LDS: hoff[kMaxShareHubs + 1] (u64), hrow[kMaxShareHubs] (u64), cntf[nblk], cur[ngroups + 1]
-// ------------------------------------------------------------------------------------------------
-template <typename RowT>
-__global__ __launch_bounds__(256) void k_tp_sort_share(const RowT *__restrict__ rowptr,
-                                                       const int32_t *__restrict__ colidx, int64_t n,
-                                                       SweepPlan pl, TpTables tb, uint32_t *__restrict__ Uh) {
-    extern __shared__ u64 smem64[];
-    u64 *hoff = smem64;                      // kMaxShareHubs + 1  stream offsets of the hubs
-    u64 *hrow = hoff + kMaxShareHubs + 1;    // kMaxShareHubs      rowptr of the hub
-    uint32_t *cntf = reinterpret_cast<uint32_t *>(hrow + kMaxShareHubs);    // nblk
-    uint32_t *cur = cntf + tb.nblk;          // ngroups + 1
-    const int tid = threadIdx.x;
-    const int64_t c = blockIdx.x / tb.nsl;
-    const int sidx = blockIdx.x % tb.nsl;
-    const int64_t chunk_lo = c * (int64_t)tb.chunk;
-    uint32_t *row_out = tb.subH + ((size_t)c * (tb.nsl + 1) + sidx) * tb.nblk;
-    uint32_t *lo_out = tb.loh + (size_t)blockIdx.x * (tb.ngroups + 1);
-    const uint32_t nvs = pl.ch_nvs[c];
-    const uint32_t h0 = pl.share_h0[blockIdx.x], nhs = pl.share_nhs[blockIdx.x];
-    if ((uint32_t)sidx >= nvs || nhs == 0 || nhs > kMaxShareHubs) {      // no such share / plan rejected by the host
-        for (int j = tid; j < tb.nblk; j += 256) row_out[j] = 0;
-        for (int j = tid; j <= tb.ngroups; j += 256) lo_out[j] = 0;
-        return;
-    }
-    const u64 H = pl.ch_H[c];
-    const u64 a = H * (u64)sidx / nvs, b = H * (u64)(sidx + 1) / nvs;
-    const u64 *goff = pl.hub_off + chunk_lo + c;
-    for (int j = tid; j < tb.nblk; j += 256) cntf[j] = 0;
-    for (uint32_t q = tid; q <= nhs; q += 256) hoff[q] = goff[h0 + q];
-    for (uint32_t q = tid; q < nhs; q += 256) hrow[q] = (u64)rowptr[pl.hub_row[chunk_lo + h0 + q]];
+    if (!staged) return;
     __syncthreads();
-    const uint32_t len = (uint32_t)(b - a);
-    for (uint32_t p = tid; p < len; p += 256) {
-        const u64 e = a + p;                                 // position in the chunk's hub entry stream
-        uint32_t lo = 0, hi = nhs;
-        while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (hoff[mid] <= e) lo = mid; else hi = mid; }
-        const int64_t at = (int64_t)(hrow[lo] + (e - hoff[lo]));
-        uint32_t low;
-        const uint32_t jb = tp_block_of((uint32_t)colidx[at], tb, &low);
-        atomicAdd(&cntf[jb], 1u);
-    }
-    __syncthreads();
-    for (int j = tid; j < tb.nblk; j += 256) row_out[j] = cntf[j];
-    for (int gq = tid; gq < tb.ngroups; gq += 256) {
-        const int j0 = gq << tb.gb;
-        const int j1 = (j0 + (1 << tb.gb)) < tb.nblk ? j0 + (1 << tb.gb) : tb.nblk;
-        uint32_t sum = 0;
-        for (int j = j0; j < j1; ++j) sum += cntf[j];
-        cur[gq] = sum;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t run = 0;
-        for (int gq = 0; gq < tb.ngroups; ++gq) { const uint32_t t = cur[gq]; cur[gq] = run; run += t; }
-        cur[tb.ngroups] = run;
-    }
-    __syncthreads();
-    for (int gq = tid; gq <= tb.ngroups; gq += 256) lo_out[gq] = cur[gq];
-    __syncthreads();
-    const uint32_t gmask = (1u << tb.gb) - 1u;
-    uint32_t *ubase = Uh + pl.ch_hbase[c] + a;
-    for (uint32_t p = tid; p < len; p += 256) {
-        const u64 e = a + p;
-        uint32_t lo = 0, hi = nhs;
-        while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (hoff[mid] <= e) lo = mid; else hi = mid; }
-        const int64_t at = (int64_t)(hrow[lo] + (e - hoff[lo]));
-        uint32_t low;
-        const uint32_t jb = tp_block_of((uint32_t)colidx[at], tb, &low);
-        const uint32_t w = atomicAdd(&cur[jb >> tb.gb], 1u);
-        ubase[w] = (lo << (tb.cb + tb.gb)) | ((jb & gmask) << tb.cb) | low;
-    }
+    for (uint32_t z = tid; z < total; z += kTpThreads) __builtin_nontemporal_store(stage[z], ubase + z);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -495,25 +613,38 @@ __global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb, u64 *__r
 }
 
 // ------------------------------------------------------------------------------------------------
-// Re-layout, step 2: workgroup c * ngroups + g moves the runs of block group g of every slice (then every
-// share) of chunk c from U (Uh) to their sub-segments in T.  The slices are taken in order, so the
-// workgroup writes 2^gb sequential streams.  Odd sub-segments get one pad tuple (row field 2048,
-// which the look-up turns into an entry the score ignores).
-// LDS: tbase[nbg] (u64), runsrc[batch] (u64), runlo[batch + 1], cur[batch][nbg]
+// Re-layout, step 2: workgroup c * ngroups + g moves the runs of block group g of every unit of
+// chunk c from U (then Uh) to their sub-segments in T, `batch` slices (shares) at a time: the
+// sub-segments of consecutive slices are adjacent in T, so the tuples of a batch form one piece of
+// T per block of the group; the pieces are put together in LDS, pad tuples included (row field
+// 2048, which the look-up turns into an entry the score ignores; every odd sub-segment ends with
+// one), and written out contiguously.  A batch that does not fit `cap` slots is cut down to one
+// slice; a slice that does not fit is written tuple by tuple.
+// LDS: tbase[nbg] (u64), runsrc[batch * npmax] (u64), runlo[batch * npmax + 1], runsl[batch * npmax],
+//      joff[nbg + 1], s0[nbg], cur[batch * nbg], stage[cap]
 // ------------------------------------------------------------------------------------------------
+constexpr int kPlaceThreads = 512;
+
 template <typename RowT>
-__global__ __launch_bounds__(256) void k_tp_place(const RowT *__restrict__ rowptr, int64_t n, SweepPlan pl,
-                                                  TpTables tb, const uint32_t *__restrict__ U,
-                                                  const uint32_t *__restrict__ Uh, uint32_t *__restrict__ T,
-                                                  int batch) {
+__global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restrict__ rowptr, int64_t n,
+                                                            SweepPlan pl, TpTables tb,
+                                                            const uint32_t *__restrict__ U,
+                                                            const uint32_t *__restrict__ Uh,
+                                                            uint32_t *__restrict__ T, int batch, uint32_t cap) {
     extern __shared__ u64 smem64[];
     const int g = (int)(blockIdx.x % (unsigned)tb.ngroups), c = (int)(blockIdx.x / (unsigned)tb.ngroups);
     const int jb0 = g << tb.gb;
     const int nbg = (jb0 + (1 << tb.gb)) <= tb.nblk ? (1 << tb.gb) : tb.nblk - jb0;
+    const int npmax = tb.npr > tb.nps ? tb.npr : tb.nps;
+    const int maxruns = batch * npmax;
     u64 *tbase = smem64;                                        // nbg
-    u64 *runsrc = tbase + nbg;                                  // batch
-    uint32_t *runlo = reinterpret_cast<uint32_t *>(runsrc + batch);     // batch + 1
-    uint32_t *cur = runlo + batch + 1;                          // batch * nbg
+    u64 *runsrc = tbase + nbg;                                  // maxruns    first tuple of the run
+    uint32_t *runlo = reinterpret_cast<uint32_t *>(runsrc + maxruns);   // maxruns + 1   prefix of the runs' lengths
+    uint32_t *runsl = runlo + maxruns + 1;                      // maxruns    slice (in the batch) of the run
+    uint32_t *joff = runsl + maxruns;                           // nbg + 1    start of block j's piece in stage
+    uint32_t *s0 = joff + nbg + 1;                              // nbg        start of the piece in the segment
+    uint32_t *cur = s0 + nbg;                                   // batch * nbg  next free slot (in stage)
+    uint32_t *stage = cur + batch * nbg;                        // cap
     const int tid = threadIdx.x;
     const int64_t chunk_lo = (int64_t)c * tb.chunk;
     const int64_t chunk_hi = (chunk_lo + tb.chunk < n) ? chunk_lo + tb.chunk : n;
@@ -521,54 +652,116 @@ __global__ __launch_bounds__(256) void k_tp_place(const RowT *__restrict__ rowpt
     const int nvs = (int)pl.ch_nvs[c];
     const uint32_t gmask = (1u << tb.gb) - 1u, cmask = (1u << tb.cb) - 1u;
     const uint32_t pad = 2048u << tb.cb;
-    for (int j = tid; j < nbg; j += 256) tbase[j] = tb.tstart[(size_t)(jb0 + j) * tb.nch + c];
+    for (int j = tid; j < nbg; j += kPlaceThreads) tbase[j] = tb.tstart[(size_t)(jb0 + j) * tb.nch + c];
     for (int part = 0; part < 2; ++part) {                      // 0: regular slices, 1: hub shares
         const int count = part == 0 ? nsl_c : nvs;
-        const uint32_t *sub = part == 0 ? tb.subR : tb.subH;
+        const int np = part == 0 ? tb.npr : tb.nps;
+        const uint32_t *sub = (part == 0 ? tb.subR : tb.subH) + ((size_t)c * (tb.nsl + 1)) * tb.nblk + jb0;
         const uint32_t *lot = part == 0 ? tb.lo : tb.loh;
         const uint32_t *src = part == 0 ? U : Uh;
-        for (int i0 = 0; i0 < count; i0 += batch) {
-            const int nb = count - i0 < batch ? count - i0 : batch;
+        int i0 = 0;
+        while (i0 < count) {
             __syncthreads();                                    // previous batch done with the LDS tables
-            if (tid < nb) {
-                const size_t gs = (size_t)c * tb.nsl + i0 + tid;
-                const uint32_t a = lot[gs * (tb.ngroups + 1) + g], b = lot[gs * (tb.ngroups + 1) + g + 1];
+            // the largest batch (<= `batch` slices) whose pieces fit the stage; at least one slice
+            int nb = count - i0 < batch ? count - i0 : batch;
+            uint32_t need = 0;
+            for (;;) {
+                need = 0;
+                for (int j = 0; j < nbg; ++j)
+                    need += sub[(size_t)(i0 + nb) * tb.nblk + j] - sub[(size_t)i0 * tb.nblk + j];
+                if (need <= cap || nb == 1) break;
+                nb = 1;
+            }
+            const bool staged = need <= cap;
+            for (int z = tid; z < nb * np; z += kPlaceThreads) {
+                const int t = z / np, q = z % np;
+                const size_t unit = ((size_t)c * tb.nsl + i0 + t) * np + q;
+                const uint32_t a = lot[unit * (tb.ngroups + 1) + g], b = lot[unit * (tb.ngroups + 1) + g + 1];
                 u64 at;
                 if (part == 0) {
-                    at = (u64)rowptr[chunk_lo + (int64_t)(i0 + tid) * kSliceRows];
+                    const int64_t v = chunk_lo + (int64_t)(i0 + t) * kSliceRows + (int64_t)q * (kSliceRows / np);
+                    at = v < chunk_hi ? (u64)rowptr[v] : 0ull;   // a part beyond the chunk has no tuples
                 } else {
                     const u64 H = pl.ch_H[c];
-                    at = pl.ch_hbase[c] + H * (u64)(i0 + tid) / (u64)nvs;
+                    const u64 sa = H * (u64)(i0 + t) / (u64)nvs, sb = H * (u64)(i0 + t + 1) / (u64)nvs;
+                    at = pl.ch_hbase[c] + sa + (sb - sa) * (u64)q / (u64)np;
                 }
-                runsrc[tid] = at + a;
-                runlo[tid + 1] = b - a;
+                runsrc[z] = at + a;
+                runlo[z + 1] = b - a;
+                runsl[z] = (uint32_t)t;
             }
-            for (int q = tid; q < nb * nbg; q += 256) {
-                const int t = q / nbg, j = q % nbg;
-                cur[q] = sub[((size_t)c * (tb.nsl + 1) + i0 + t) * tb.nblk + jb0 + j];
+            for (int j = tid; j < nbg; j += kPlaceThreads) {
+                const uint32_t a = sub[(size_t)i0 * tb.nblk + j];
+                s0[j] = a;
+                joff[j + 1] = sub[(size_t)(i0 + nb) * tb.nblk + j] - a;
             }
             __syncthreads();
             if (tid == 0) {
                 uint32_t run = 0;
                 runlo[0] = 0;
-                for (int t = 0; t < nb; ++t) { run += runlo[t + 1]; runlo[t + 1] = run; }
+                for (int z = 0; z < nb * np; ++z) { run += runlo[z + 1]; runlo[z + 1] = run; }
+                run = 0;
+                joff[0] = 0;
+                for (int j = 0; j < nbg; ++j) { run += joff[j + 1]; joff[j + 1] = run; }
             }
             __syncthreads();
-            const uint32_t total = runlo[nb];
-            for (uint32_t p = tid; p < total; p += 256) {
-                int t = 0;
-                while (runlo[t + 1] <= p) ++t;                  // batch <= 8
-                const uint32_t u = __builtin_nontemporal_load(src + runsrc[t] + (p - runlo[t]));
-                const uint32_t j = (u >> tb.cb) & gmask;
-                const uint32_t w = atomicAdd(&cur[t * nbg + j], 1u);
-                T[tbase[j] + w] = ((u >> (tb.cb + tb.gb)) << tb.cb) | (u & cmask);
+            for (int z = tid; z < nb * nbg; z += kPlaceThreads) {
+                const int t = z / nbg, j = z % nbg;
+                // staged: slot in stage; else: slot in the segment
+                const uint32_t a = sub[(size_t)(i0 + t) * tb.nblk + j];
+                cur[z] = staged ? joff[j] + (a - s0[j]) : a;
+            }
+            if (staged)
+                for (uint32_t z = tid; z < need; z += kPlaceThreads) stage[z] = pad;
+            __syncthreads();
+            const int nruns = nb * np;
+            const uint32_t total = runlo[nruns];
+            int top = 1;
+            while (top < nruns) top <<= 1;
+            for (uint32_t base = tid; base < total; base += kPlaceThreads * kTpBatch) {
+                uint32_t run_of[kTpBatch], u[kTpBatch];
+#pragma unroll
+                for (int x = 0; x < kTpBatch; ++x) run_of[x] = 0;
+                for (int step = top >> 1; step >= 1; step >>= 1) {
+#pragma unroll
+                    for (int x = 0; x < kTpBatch; ++x) {
+                        const uint32_t cand = run_of[x] + step;         // largest z < nruns with runlo[z] <= p
+                        const uint32_t cc = cand < (uint32_t)nruns ? cand : (uint32_t)nruns - 1u;
+                        if (cand < (uint32_t)nruns && runlo[cc] <= base + x * kPlaceThreads) run_of[x] = cand;
+                    }
+                }
+#pragma unroll
+                for (int x = 0; x < kTpBatch; ++x) {
+                    const uint32_t p = base + x * kPlaceThreads;
+                    u[x] = p < total ? __builtin_nontemporal_load(src + runsrc[run_of[x]] + (p - runlo[run_of[x]])) : 0u;
+                }
+#pragma unroll
+                for (int x = 0; x < kTpBatch; ++x) {
+                    const uint32_t p = base + x * kPlaceThreads;
+                    if (p < total) {
+                        const uint32_t j = (u[x] >> tb.cb) & gmask;
+                        const uint32_t w = atomicAdd(&cur[runsl[run_of[x]] * nbg + j], 1u);
+                        const uint32_t tuple = ((u[x] >> (tb.cb + tb.gb)) << tb.cb) | (u[x] & cmask);
+                        if (staged) stage[w] = tuple;
+                        else T[tbase[j] + w] = tuple;
+                    }
+                }
             }
             __syncthreads();
-            for (int q = tid; q < nb * nbg; q += 256) {
-                const int t = q / nbg, j = q % nbg;
-                const uint32_t end = sub[((size_t)c * (tb.nsl + 1) + i0 + t + 1) * tb.nblk + jb0 + j];
-                if (cur[q] < end) T[tbase[j] + cur[q]] = pad;
+            if (staged) {
+                for (int j = 0; j < nbg; ++j) {
+                    const uint32_t a = joff[j], len = joff[j + 1] - a;
+                    uint32_t *out = T + tbase[j] + s0[j];
+                    for (uint32_t z = tid; z < len; z += kPlaceThreads) __builtin_nontemporal_store(stage[a + z], out + z);
+                }
+            } else {
+                for (int z = tid; z < nb * nbg; z += kPlaceThreads) {
+                    const int t = z / nbg, j = z % nbg;
+                    const uint32_t end = sub[(size_t)(i0 + t + 1) * tb.nblk + j];
+                    if (cur[z] < end) T[tbase[j] + cur[z]] = pad;
+                }
             }
+            i0 += nb;
         }
     }
 }
