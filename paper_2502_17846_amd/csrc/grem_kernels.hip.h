@@ -466,6 +466,73 @@ __global__ __launch_bounds__(kAdmitThreads) void k_apply(
 }
 
 // ------------------------------------------------------------------------------------------------
+// apply for k <= 16: the same admission, one vertex per thread and one tile per workgroup of
+// kAdmitTile threads, ranks from one ballot per partition.  cnt[tile][t] = movers to t in that tile
+// (the workgroup adds up the rows of the earlier tiles itself); room[t] = P - S[t] as of the
+// chunk's start.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc, const uint8_t *__restrict__ prop,
+                                                        int64_t chunk_lo, int64_t chunk_hi, int k,
+                                                        const uint32_t *__restrict__ cnt,
+                                                        const long long *__restrict__ room,
+                                                        unsigned long long *__restrict__ S,
+                                                        uint32_t *__restrict__ ocnt, int pass) {
+    constexpr int nwaves = kAdmitTile / 64;
+    __shared__ uint32_t tbl[16];                // movers in earlier tiles
+    __shared__ uint32_t wcnt[nwaves][16];       // movers per wave, then their exclusive prefix over the waves
+    __shared__ int32_t dS[16];
+    __shared__ long long s_room[16];
+    __shared__ uint32_t s_unassigned;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int64_t v = chunk_lo + (int64_t)blockIdx.x * kAdmitTile + tid;
+    const bool inside = v < chunk_hi;
+    uint32_t t = 0, old = 0;
+    if (inside) { t = prop[v - chunk_lo]; old = (uint32_t)Lc[v]; }
+    if (tid < 16) { tbl[tid] = 0; dS[tid] = 0; s_room[tid] = tid < k ? room[tid] : 0; }
+    if (tid == 0) s_unassigned = 0;
+    __syncthreads();
+    {   // earlier tiles: thread (seg, col) adds up rows seg, seg + 64, ...
+        const int col = tid & 15, seg = tid >> 4;
+        uint32_t sum = 0;
+        if (col < k)
+            for (int r = seg; r < (int)blockIdx.x; r += kAdmitTile / 16) sum += cnt[(size_t)r * k + col];
+        if (sum) atomicAdd(&tbl[col], sum);
+    }
+    const bool mover = inside && t != old;
+    uint32_t wrank = 0, mine = 0;
+    for (int j = 0; j < k; ++j) {
+        const unsigned long long m = __ballot(mover && t == (uint32_t)j);
+        if (mover && t == (uint32_t)j) wrank = (uint32_t)__popcll(m & lanes_below(lane));
+        if (lane == j) mine = (uint32_t)__popcll(m);
+    }
+    if (lane < 16) wcnt[wave][lane] = lane < k ? mine : 0u;
+    __syncthreads();
+    if (tid < 16) {
+        uint32_t run = 0;
+        for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[w][tid]; wcnt[w][tid] = run; run += c; }
+    }
+    __syncthreads();
+    bool admitted = false;
+    if (mover) {
+        const long long rank = (long long)tbl[t] + wcnt[wave][t] + wrank;
+        admitted = rank < s_room[t];
+    }
+    if (admitted) {
+        Lc[v] = (uint8_t)t;
+        atomicAdd(&dS[t], 1);
+        if (old != 0xFFu) atomicAdd(&dS[old], -1);
+    } else if (pass == 0 && inside && old == 0xFFu) {
+        atomicAdd(&s_unassigned, 1u);       // rejected new vertex (a new vertex is always a mover)
+    }
+    __syncthreads();
+    if (tid < k) {
+        const int32_t d = dS[tid];
+        if (d != 0) atomicAdd(&S[tid], (unsigned long long)(long long)d);
+    }
+    if (pass == 0 && tid == 0) ocnt[blockIdx.x] = s_unassigned;
+}
+
+// ------------------------------------------------------------------------------------------------
 // spill scan (first pass): exclusive prefix of the per-tile unassigned counts, and the level
 // tables of "add one to the smallest partition, lowest id on ties, repeatedly":
 //   order the partitions by (S, id): s[0] <= s[1] <= ...;  C[a] = sum_{q<a} (s[a] - s[q]) is the
