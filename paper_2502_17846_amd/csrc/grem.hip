@@ -82,7 +82,7 @@ struct Layout {
     size_t sl_reg_cnt, sl_reg_start, sl_nh, sl_hub_start, sl_hent, sl_hent_start, share_h0, share_nhs,
         ch_regtot, ch_nh, ch_H, ch_nvs, ch_hbase, hub_row, hub_off;
     size_t total;
-    size_t subR, subH, xstart, tstart, lo, loh, Hhub, T, X, U, Uh, total_sweep;   // extras of the two-phase path, after `total`
+    size_t subR, subH, xstart, tstart, lo, loh, Hhub, T, X, U, Uh, E16, total_sweep;   // extras of the two-phase path, after `total`
     size_t hub_rows_cap;                                          // rows of Hhub
 };
 
@@ -153,6 +153,7 @@ Layout make_layout(int64_t n, int64_t nnz, int64_t hub_entries, int32_t k, int64
         L.X = take(slots * 2 + 16);
         L.U = take((size_t)(nnz > 0 ? nnz : 0) * 4 + 16);
         L.Uh = take((size_t)(hub_entries > 0 ? hub_entries : 0) * 4 + 16);
+        L.E16 = take((size_t)n * (size_t)k * 2);
     }
     L.total_sweep = off;
     return L;
@@ -343,7 +344,9 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
     // ---- two-phase path: allocate its extras, re-lay-out the entries once
     TpTables tb{};
     uint32_t *T = nullptr, *Hhub = nullptr;
-    uint16_t *X = nullptr;
+    uint16_t *X = nullptr, *E16 = nullptr;
+    // estimates of the regular rows of the two-phase path stay below hub_degree * 2^R: 16 bits when that fits
+    const bool use16 = (((unsigned long long)(hub_degree - 1)) << R) <= 65535ull;
     size_t tp_score_lds = 0, tp_lookup_lds = 0;
     const int share_hubs = (int)h_misc[5];
     const size_t max_chunk_hubs = (size_t)h_misc[6];
@@ -398,6 +401,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 Hhub = (uint32_t *)(xbase + lay.Hhub);
                 T = (uint32_t *)(xbase + lay.T);
                 X = (uint16_t *)(xbase + lay.X);
+                E16 = (uint16_t *)(xbase + lay.E16);
                 tb.gb = geo.gb;
                 tb.ngroups = geo.ngroups;
                 tb.lo = (uint32_t *)(xbase + lay.lo);
@@ -440,7 +444,8 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                     !set_lds((const void *)k_tp_group<RowT, true>, groupS_lds) ||
                     !set_lds((const void *)k_tp_place<RowT>, place_lds) ||
                     !set_lds((const void *)k_tp_lookup<true>, tp_lookup_lds) ||
-                    !set_lds((const void *)k_tp_score<RowT>, tp_score_lds)) {
+                    !set_lds((const void *)k_tp_score<RowT, uint32_t>, tp_score_lds) ||
+                    !set_lds((const void *)k_tp_score<RowT, uint16_t>, tp_score_lds)) {
                     release();
                     return GREM_ERR_HIP;
                 }
@@ -512,17 +517,26 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 if constexpr (sizeof(LabelT) == 1) {
                     const unsigned blocks = (unsigned)((len + kSliceRows - 1) / kSliceRows);
                     const int jlim = (pass == 0 && !seed) ? (int)c * geo.nbc : geo.nblk;
+                    // the estimates are state between passes and, if the caller asked for them, output:
+                    // the last pass does not store them otherwise
+                    const int store_e = (pass < R || external_E) ? 1 : 0;
                     L.run(GREM_KERNEL_SCORE, [&] {
-                        hipLaunchKernelGGL((k_tp_score<RowT>), dim3(blocks), dim3(kTpThreads), tp_score_lds,
-                                           stream, rowptr, X, tb, pl, (const uint8_t *)Lc, S, E, Hhub,
-                                           (uint8_t *)prop, cnt, room, (int)c, lo, hi, (int)k, jlim,
-                                           share_hubs, (uint32_t)hub_degree, pass, P);
+                        if (use16)
+                            hipLaunchKernelGGL((k_tp_score<RowT, uint16_t>), dim3(blocks), dim3(kTpThreads),
+                                               tp_score_lds, stream, rowptr, X, tb, pl, (const uint8_t *)Lc, S, E16,
+                                               Hhub, (uint8_t *)prop, cnt, room, (int)c, lo, hi, (int)k, jlim,
+                                               share_hubs, (uint32_t)hub_degree, pass, P, store_e);
+                        else
+                            hipLaunchKernelGGL((k_tp_score<RowT, uint32_t>), dim3(blocks), dim3(kTpThreads),
+                                               tp_score_lds, stream, rowptr, X, tb, pl, (const uint8_t *)Lc, S, E,
+                                               Hhub, (uint8_t *)prop, cnt, room, (int)c, lo, hi, (int)k, jlim,
+                                               share_hubs, (uint32_t)hub_degree, pass, P, store_e);
                     });
                     if (max_chunk_hubs > 0)
                         L.run(GREM_KERNEL_HUBS, [&] {
                             hipLaunchKernelGGL(k_hub_finalize, dim3((unsigned)((max_chunk_hubs + 15) / 16)),
                                                dim3(256), 0, stream, pl, (const uint8_t *)Lc, room, E, Hhub,
-                                               (uint8_t *)prop, cnt, (int)c, lo, (int)k, pass);
+                                               (uint8_t *)prop, cnt, (int)c, lo, (int)k, pass, store_e);
                         });
                 }
             } else if (use_lds) {
@@ -589,6 +603,13 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
             hipLaunchKernelGGL((k_expand<LabelT>), dim3((unsigned)blocks), dim3(256), 0, stream, Lc, n,
                                labels_out);
         });
+        if constexpr (sizeof(LabelT) == 1) {
+            if (sweep && use16 && external_E)
+                L.run(GREM_KERNEL_EXPAND, [&] {
+                    hipLaunchKernelGGL((k_expand_estimates<RowT>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                                       rowptr, n, (int)k, (uint32_t)hub_degree, E16, estimates_out);
+                });
+        }
         if (sizes_out)
             L.run(GREM_KERNEL_EXPAND, [&] {
                 hipLaunchKernelGGL(k_copy_sizes, dim3((k + 255) / 256), dim3(256), 0, stream, S, (int)k,

@@ -930,6 +930,21 @@ __device__ __forceinline__ void tp_count_list(const uint32_t *__restrict__ Xc32,
     }
 }
 
+// start (in 16-bit units from the chunk's first slot of X) and length of the share's sub-segment of
+// its ml-th block
+__device__ __forceinline__ void tp_hub_offsets(const TpTables &tb, const u64 *__restrict__ xs, u64 xs0,
+                                               const uint32_t *__restrict__ q0, int cls, int ncls, int mlim,
+                                               int ml, uint32_t *s0, uint32_t *l0) {
+    *s0 = 0;
+    *l0 = 0;
+    if (ml < mlim) {
+        const int jl = cls + ncls * ml;
+        const uint32_t a0 = q0[jl];
+        *s0 = (uint32_t)(xs[jl] - xs0) + a0;
+        *l0 = q0[tb.nblk + jl] - a0;
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // score (phase 2): one workgroup per row slice of chunk c.  It counts the slice's sub-segment of
 // every column block in [0, jlim) (in the first pass of an unseeded run the blocks of chunks >= c
@@ -944,13 +959,13 @@ __device__ __forceinline__ void tp_count_list(const uint32_t *__restrict__ Xc32,
 // LDS: hist[kSliceRows * 8] (16-bit counters, 16 per row), meta[kSliceRows / 2] (per row: old label,
 //      hub flag << 8), hhist[share_hubs * k], room[k], tcnt[2 * k]
 // ------------------------------------------------------------------------------------------------
-template <typename RowT>
+template <typename RowT, typename ET>
 __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     const RowT *__restrict__ rowptr, const uint16_t *__restrict__ X, TpTables tb, SweepPlan pl,
-    const uint8_t *__restrict__ Lc, const long long *__restrict__ S, uint32_t *__restrict__ E,
+    const uint8_t *__restrict__ Lc, const long long *__restrict__ S, ET *__restrict__ E,
     uint32_t *__restrict__ Hhub, uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
     long long *__restrict__ room_out, int c, int64_t chunk_lo, int64_t chunk_hi, int k, int jlim,
-    int share_hubs, uint32_t hub_degree, int pass, long long P) {
+    int share_hubs, uint32_t hub_degree, int pass, long long P, int store_e) {
     extern __shared__ uint32_t smem[];
     constexpr int hist_words = kSliceRows * 8;
     constexpr int BU = kSliceRows * 4 / kTpThreads;     // (vertex, quarter) pairs per thread
@@ -996,6 +1011,11 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     const u64 *xs = tb.xstart + (size_t)c * tb.nblk;
     const u64 xs0 = xs[0];
     const uint32_t *Xc32 = reinterpret_cast<const uint32_t *>(X + xs0);     // xs0 is a multiple of 8
+    // hub sub-segments: blocks cls + ncls * m < jlim; their offsets are fetched now, counted last
+    const uint32_t *hq0 = tb.subH + ((size_t)c * (tb.nsl + 1) + share) * tb.nblk;
+    const int mlim = (any_hub && jlim > cls) ? (jlim - cls + ncls - 1) / ncls : 0;
+    uint32_t hs0 = 0, hl0 = 0;
+    if (any_hub) tp_hub_offsets(tb, xs, xs0, hq0, cls, ncls, mlim, wave + NW * lane, &hs0, &hl0);
     {
         const uint32_t *r0 = tb.subR + ((size_t)c * (tb.nsl + 1) + blockIdx.x) * tb.nblk;
         const uint32_t *r1 = r0 + tb.nblk;
@@ -1014,18 +1034,9 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
         }
     }
     if (any_hub) {
-        const uint32_t *q0 = tb.subH + ((size_t)c * (tb.nsl + 1) + share) * tb.nblk;
-        const uint32_t *q1 = q0 + tb.nblk;
-        const int mlim = jlim > cls ? (jlim - cls + ncls - 1) / ncls : 0;    // blocks cls + ncls * m < jlim
         for (int base = 0; base < mlim; base += NW * 64) {
-            const int ml = base + wave + NW * lane;
-            uint32_t s0 = 0, l0 = 0;
-            if (ml < mlim) {
-                const int jl = cls + ncls * ml;
-                const uint32_t a0 = q0[jl];
-                s0 = (uint32_t)(xs[jl] - xs0) + a0;
-                l0 = q1[jl] - a0;
-            }
+            uint32_t s0 = hs0, l0 = hl0;                 // first round: loaded before the regular blocks
+            if (base > 0) tp_hub_offsets(tb, xs, xs0, hq0, cls, ncls, mlim, base + wave + NW * lane, &s0, &l0);
             int tmax = (mlim - base - wave + NW - 1) / NW;
             if (tmax > 64) tmax = 64;
             tp_count_list<false, 8>(Xc32, s0, l0, tmax, lane, k, hhist);
@@ -1050,16 +1061,21 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
         const int g = tid + u * kTpThreads;
         if (pass > 0 && g < nv * 4) {
             const int t = g >> 2, q = g & 3;
-            const uint32_t *Erow = E + (size_t)(v0 + t) * (size_t)k;
+            const ET *Erow = E + (size_t)(v0 + t) * (size_t)k;
             if (vec) {
                 if (4 * q < k) {
-                    const u32x4 e = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Erow + 4 * q));
-                    ev[u][0] = e.x; ev[u][1] = e.y; ev[u][2] = e.z; ev[u][3] = e.w;
+                    if (sizeof(ET) == 4) {
+                        const u32x4 e = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Erow + 4 * q));
+                        ev[u][0] = e.x; ev[u][1] = e.y; ev[u][2] = e.z; ev[u][3] = e.w;
+                    } else {
+                        const u32x2 e = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(Erow + 4 * q));
+                        ev[u][0] = e.x & 0xFFFFu; ev[u][1] = e.x >> 16; ev[u][2] = e.y & 0xFFFFu; ev[u][3] = e.y >> 16;
+                    }
                 }
             } else {
 #pragma unroll
                 for (int z = 0; z < 4; ++z)
-                    if (q + 4 * z < k) ev[u][z] = Erow[q + 4 * z];
+                    if (q + 4 * z < k) ev[u][z] = (uint32_t)Erow[q + 4 * z];
             }
         }
     }
@@ -1075,7 +1091,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
         if (mt & 0x100u) continue;                              // hubs are k_hub_finalize's
         const uint32_t old = mt & 0xFFu;
         const int64_t v = v0 + t;
-        uint32_t *Erow = E + (size_t)v * (size_t)k;
+        ET *Erow = E + (size_t)v * (size_t)k;
         unsigned long long bestkey = 0;
         int bestj = 0x7fffffff;
 #pragma unroll
@@ -1090,16 +1106,25 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
                 if (key > bestkey) { bestkey = key; bestj = j; }
             }
         }
-        if (vec) {
-            if (4 * q < k) {
-                u32x4 o;
-                o.x = ev[u][0]; o.y = ev[u][1]; o.z = ev[u][2]; o.w = ev[u][3];
-                __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(Erow + 4 * q));
-            }
-        } else {
+        if (store_e) {
+            if (vec) {
+                if (4 * q < k) {
+                    if (sizeof(ET) == 4) {
+                        u32x4 o;
+                        o.x = ev[u][0]; o.y = ev[u][1]; o.z = ev[u][2]; o.w = ev[u][3];
+                        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(Erow + 4 * q));
+                    } else {
+                        u32x2 o;
+                        o.x = ev[u][0] | (ev[u][1] << 16);
+                        o.y = ev[u][2] | (ev[u][3] << 16);
+                        __builtin_nontemporal_store(o, reinterpret_cast<u32x2 *>(Erow + 4 * q));
+                    }
+                }
+            } else {
 #pragma unroll
-            for (int z = 0; z < 4; ++z)
-                if (q + 4 * z < k) Erow[q + 4 * z] = ev[u][z];
+                for (int z = 0; z < 4; ++z)
+                    if (q + 4 * z < k) Erow[q + 4 * z] = (ET)ev[u][z];
+            }
         }
 #pragma unroll
         for (int off = 1; off <= 2; off <<= 1) {
@@ -1131,7 +1156,7 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
                                                       const long long *__restrict__ room,
                                                       uint32_t *__restrict__ E, uint32_t *__restrict__ Hhub,
                                                       uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
-                                                      int c, int64_t chunk_lo, int k, int pass) {
+                                                      int c, int64_t chunk_lo, int k, int pass, int store_e) {
     const uint32_t nh = pl.ch_nh[c];
     const uint32_t i = blockIdx.x * 16u + (threadIdx.x >> 4);
     const int j = threadIdx.x & 15;
@@ -1150,7 +1175,7 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
             *hp = 0;
             uint32_t *ep = E + (size_t)v * (size_t)k + j;
             const uint32_t e = (pass > 0 ? *ep : 0u) + (h << sh);
-            *ep = e;
+            if (store_e) *ep = e;
             const uint32_t rm = (uint32_t)room[j] + ((uint32_t)j == old ? 1u : 0u);
             key = rm ? (((unsigned long long)e << 32) | rm) : 0ull;
             bj = j;
@@ -1167,6 +1192,21 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
         if (pass == 0 && old != 0xFFu) best = old;
         prop[v - chunk_lo] = (uint8_t)best;
         if (best != old) atomicAdd(&cnt[(size_t)((v - chunk_lo) / kAdmitTile) * k + best], 1u);   // after k_tp_score's store
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// 16-bit estimates of the regular rows -> the caller's 32-bit array (hub rows are already there)
+// ------------------------------------------------------------------------------------------------
+template <typename RowT>
+__global__ __launch_bounds__(256) void k_expand_estimates(const RowT *__restrict__ rowptr, int64_t n, int k,
+                                                          uint32_t hub_degree, const uint16_t *__restrict__ E16,
+                                                          uint32_t *__restrict__ out) {
+    const int64_t total = n * (int64_t)k;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        const int64_t v = idx / k;
+        if ((u64)(rowptr[v + 1] - rowptr[v]) < hub_degree) out[idx] = E16[idx];
     }
 }
 

@@ -141,6 +141,9 @@ def test_two_phase_path_seeded_and_edge_cases():
     _check(small, 4, 1.05, 1, 1, mode=B.HIST_SWEEP, col_bits=5, hub_degree=12, tag="chunk=1")
     _check(small, 5, 1.05, 7, 2, mode=B.HIST_SWEEP, col_bits=4, hub_degree=12, tag="chunk=7")
     _check(g, 16, 1.05, 3000, 2, mode=B.HIST_SWEEP, col_bits=18, tag="largest column block")
+    _check(g, 16, 1.05, 3000, 2, mode=B.HIST_SWEEP, hub_degree=40_000, tag="32-bit estimates")
+    _check(g, 12, 1.05, 3000, 5, mode=B.HIST_SWEEP, hub_degree=2049, tag="32-bit estimates, R=5")
+    _check(g, 12, 1.05, 3000, 4, mode=B.HIST_SWEEP, hub_degree=4096, tag="16-bit estimates at the limit")
     _check(g, 16, 1.0, 2049, 3, mode=B.HIST_SWEEP, col_bits=7, hub_degree=16, tag="odd chunk")
     _check(g, 2, 1.0, 6000, 2, mode=B.HIST_SWEEP, col_bits=7, hub_degree=1, tag="every row a hub")
     e = synth.Graph(np.zeros(5001, dtype=np.int64), np.zeros(0, dtype=np.int32), 5000, 0, 0, None, "edgeless")
