@@ -107,6 +107,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the extra instrumented step that times the score kernel")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain device copy of 2 GiB (8 launches): under rocprofv3 --pmc its "
+                         "FETCH_SIZE / WRITE_SIZE give the factor that scales those counters to bytes")
     ap.add_argument("--col-bits", type=int, default=0,
                     help="log2 of the vertices per column block of the two-phase path (0 = library default)")
     ap.add_argument("--hub-degree", type=int, default=0,
@@ -124,6 +127,17 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     dev = "cuda:0"
+    if args.calibrate_copy:
+        nbytes = 2 << 30
+        a = torch.ones(nbytes // 4, dtype=torch.int32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        for _ in range(8):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "device copy", "bytes_read_per_launch": nbytes,
+                          "bytes_written_per_launch": nbytes, "launches": 8}))
+        return
     w = WORKLOADS[args.workload]
     t_gen = time.perf_counter()
     g = make_graph(w, dev)

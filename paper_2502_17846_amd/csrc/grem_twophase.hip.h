@@ -977,15 +977,20 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     uint32_t *tcnt = room + k;                  // 2 * k
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     constexpr int NW = kTpThreads / 64;
-    const int64_t v0 = chunk_lo + (int64_t)blockIdx.x * kSliceRows;
+    // Workgroups are dispatched round-robin over the 8 XCDs, each with its own L2: give XCD x a
+    // contiguous range of slices, so that neighbouring slices, whose sub-segments share cache lines
+    // of X, meet in one L2.
+    const unsigned xcd = blockIdx.x & 7u, turn = blockIdx.x >> 3;
+    const unsigned slice = xcd * (gridDim.x >> 3) + (xcd < (gridDim.x & 7u) ? xcd : (gridDim.x & 7u)) + turn;
+    const int64_t v0 = chunk_lo + (int64_t)slice * kSliceRows;
     const int64_t left = chunk_hi - v0;
     const int nv = left < kSliceRows ? (int)left : kSliceRows;
     const bool vec = (k & 3) == 0;
 
     // the hub share this workgroup helps with
     const uint32_t nvs = pl.ch_nvs[c];
-    const uint32_t share = nvs ? blockIdx.x % nvs : 0u;
-    const int cls = nvs ? (int)(blockIdx.x / nvs) : 0;
+    const uint32_t share = nvs ? slice % nvs : 0u;
+    const int cls = nvs ? (int)(slice / nvs) : 0;
     const int ncls = nvs ? (int)((gridDim.x - share + nvs - 1) / nvs) : 1;   // workgroups that took this share
     const bool any_hub = nvs != 0 && pl.share_nhs[(size_t)c * tb.nsl + share] != 0;
     const uint32_t share_h0 = pl.share_h0[(size_t)c * tb.nsl + share];
@@ -997,7 +1002,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
         for (int j = tid; j < k; j += kTpThreads) {
             const long long rj = P - S[j];
             room[j] = (uint32_t)rj;
-            if (blockIdx.x == 0) room_out[j] = rj;      // the sizes' snapshot k_apply admits against
+            if (slice == 0) room_out[j] = rj;           // the sizes' snapshot k_apply admits against
         }
         for (int j = tid; j < 2 * k; j += kTpThreads) tcnt[j] = 0;
         for (int t = tid; t < nv; t += kTpThreads) {
@@ -1017,7 +1022,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     uint32_t hs0 = 0, hl0 = 0;
     if (any_hub) tp_hub_offsets(tb, xs, xs0, hq0, cls, ncls, mlim, wave + NW * lane, &hs0, &hl0);
     {
-        const uint32_t *r0 = tb.subR + ((size_t)c * (tb.nsl + 1) + blockIdx.x) * tb.nblk;
+        const uint32_t *r0 = tb.subR + ((size_t)c * (tb.nsl + 1) + slice) * tb.nblk;
         const uint32_t *r1 = r0 + tb.nblk;
         for (int base = 0; base < jlim; base += NW * 64) {
             // lane l of wave w holds the sub-segment of block base + w + NW * l
