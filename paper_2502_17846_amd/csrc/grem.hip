@@ -393,6 +393,15 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 tb.tstart = (u64 *)(xbase + lay.tstart);
                 tb.chunk = geo.chunk;
                 tb.chunk_shift = geo.shift;
+                {   // round-up magic number: exact for dividends below 2^31 (vertex ids are)
+                    uint32_t sh = 0;
+                    while ((1ull << sh) < geo.chunk) ++sh;
+                    tb.chunk_magic_shift = sh > 0 ? sh - 1 : 0;
+                    tb.chunk_magic = geo.chunk > 1
+                        ? (uint32_t)((((unsigned long long)1 << (32 + tb.chunk_magic_shift)) + geo.chunk - 1) / geo.chunk)
+                        : 0u;
+                    if (geo.chunk == 1) tb.chunk_shift = 0;
+                }
                 tb.nch = geo.nch;
                 tb.nsl = geo.nsl;
                 tb.nbc = geo.nbc;
@@ -419,8 +428,22 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                     return (uint32_t)(kGroupLds > fixed ? (kGroupLds - fixed) / 4 : 0);
                 };
                 int npr = 1, nps = 1;
-                while (npr < kMaxParts && group_cap(false, npr) < h_misc[9] / npr + h_misc[9] / (8ull * npr) + 64) npr *= 2;
-                while (nps < kMaxParts && group_cap(true, nps) < h_misc[10] / nps + h_misc[10] / (8ull * nps) + 64) nps += 1;
+                // ... and, if that takes no more than kMaxParts, so small that a thread holds its share of the
+                // unit's entries in registers (one round of kTpThreads * kTpBatch entries)
+                const unsigned long long one_round = (unsigned long long)kTpThreads * kTpBatch;
+                auto fits = [&](bool share, int np, unsigned long long most, bool in_regs) {
+                    const unsigned long long unit = most / np + most / (8ull * np) + 64;
+                    return group_cap(share, np) >= unit && (!in_regs || unit <= one_round);
+                };
+                while (npr < kMaxParts && !fits(false, npr, h_misc[9], false)) npr *= 2;
+                while (nps < kMaxParts && !fits(true, nps, h_misc[10], false)) nps += 1;
+                {
+                    int a = npr, b = nps;
+                    while (a < kMaxParts && !fits(false, a, h_misc[9], true)) a *= 2;
+                    while (b < kMaxParts && !fits(true, b, h_misc[10], true)) b += 1;
+                    if (fits(false, a, h_misc[9], true)) npr = a;
+                    if (fits(true, b, h_misc[10], true)) nps = b;
+                }
                 tb.npr = npr;
                 tb.nps = nps;
                 const uint32_t capR = group_cap(false, npr), capS = group_cap(true, nps);

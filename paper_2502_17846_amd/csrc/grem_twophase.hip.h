@@ -89,6 +89,7 @@ struct TpTables {
     int ngroups;      // ceil(nblk / 2^gb)
     uint32_t chunk;   // rows per chunk (already clamped to n)
     int chunk_shift;  // log2(chunk) when it is a power of two, else -1
+    uint32_t chunk_magic, chunk_magic_shift;   // u / chunk = mulhi(u, magic) >> shift for every u < 2^31
     int nch;          // chunks
     int nsl;          // row slices per chunk
     int nbc;          // column blocks per chunk
@@ -97,7 +98,7 @@ struct TpTables {
 };
 
 __device__ __forceinline__ uint32_t tp_block_of(uint32_t u, const TpTables &g, uint32_t *col_low) {
-    const uint32_t cu = g.chunk_shift >= 0 ? (u >> g.chunk_shift) : (u / g.chunk);
+    const uint32_t cu = g.chunk_shift >= 0 ? (u >> g.chunk_shift) : (__umulhi(u, g.chunk_magic) >> g.chunk_magic_shift);
     const uint32_t rel = u - cu * g.chunk;
     *col_low = rel & ((1u << g.cb) - 1u);
     return cu * (uint32_t)g.nbc + (rel >> g.cb);
