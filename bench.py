@@ -21,6 +21,42 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM traffic of the dominant kernels on the default workload, from two `rocprofv3 --pmc` runs
+# (FETCH_SIZE, then WRITE_SIZE; KiB summed over the launches of one step, see profiles/), scaled by
+# what the same counters read for a plain 2 GiB device copy (`bench.py --calibrate-copy`).  Only valid
+# for the kernel sources they were taken with: `sources_sha256` is the hash of the library's sources
+# at that time, and `traffic` is reported as null when the sources have changed since.
+PMC = {
+    "workload": "chunglu-111M",
+    "sources_sha256": "9c04dde0df4b2b88626f3786732804583c681d73ae72aa9369b9283c0bad169f",
+    "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,590 KiB
+    "write_factor": 1.0,        # 2 GiB written -> WRITE_SIZE 2,097,150 KiB
+    "fetch_kib": {"k_tp_score": 1.47216e7, "k_tp_lookup": 1.73555e7},
+    "write_kib": {"k_tp_score": 7.36997e6, "k_tp_lookup": 1.64364e7},
+    "launches": {"k_tp_score": 318, "k_tp_lookup": 317},
+}
+
+
+def sources_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2502_17846_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic_bytes_per_chunk(workload):
+    """HBM bytes one k_tp_score launch plus one k_tp_lookup launch move on average, or None."""
+    if workload != PMC["workload"] or not PMC["sources_sha256"] or PMC["sources_sha256"] != sources_sha256():
+        return None
+    total = 0.0
+    for kern in ("k_tp_score", "k_tp_lookup"):
+        kib = PMC["fetch_kib"][kern] * PMC["fetch_factor"] + PMC["write_kib"][kern] * PMC["write_factor"]
+        total += kib * 1024.0 / PMC["launches"][kern]
+    return total
+
 WORKLOADS = {
     # name: (generator kwargs, k, slack, chunk, refine_passes, rowptr bits)
     "chunglu-111M": dict(kind="chung_lu", n=111_000_000, m=1_600_000_000, k=16, slack=1.05,
@@ -200,6 +236,9 @@ def main():
         if per_class.get("lookup", {}).get("launches", 0) > 0:
             roofline["kernel"] = "k_tp_score+k_tp_lookup"
             roofline["score_ms"], roofline["lookup_ms"] = round(score_ms, 4), round(lookup_ms, 4)
+            roofline["traffic"] = measured_traffic_bytes_per_chunk(args.workload)
+            relayout_ms = per_class.get("relayout", {}).get("ms", 0.0)
+            roofline["relayout_ms"] = round(relayout_ms, 4)
         bytes_per_launch = b_total / (passes * nchunks)
         avg_launch_s = 1e-3 * (score_ms + lookup_ms) / max(score_launches, 1)
         achieved = bytes_per_launch / avg_launch_s / 1e9
@@ -229,6 +268,8 @@ def main():
         "algorithmic_GB_per_step": b_total / 1e9,
         "whole_step_algorithmic_GBps": b_total / (elapsed / args.steps) / 1e9,
         "whole_step_frac_of_hbm_peak": b_total / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
+        "ms_per_pass_without_relayout": (None if roofline.get("relayout_ms") is None
+                                         else (ms_per_step - roofline["relayout_ms"]) / passes),
         "cut_fraction": cut / max(nnz, 1),
         "max_partition_size": int(sizes.max()),
         "capacity": P,
