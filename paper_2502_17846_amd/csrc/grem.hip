@@ -478,13 +478,17 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
                     hipLaunchKernelGGL((k_tp_group<RowT, false>), dim3(G * (unsigned)npr), dim3(kTpThreads),
                                        groupR_lds, stream, rowptr, colidx, n, (uint32_t)hub_degree, pl, tb,
-                                       share_hubs, capR, U);
+                                       share_hubs, capR, (int)nsl, U);
                 });
-                L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_tp_group<RowT, true>), dim3(G * (unsigned)nps), dim3(kTpThreads),
-                                       groupS_lds, stream, rowptr, colidx, n, (uint32_t)hub_degree, pl, tb,
-                                       share_hubs, capS, Uh);
-                });
+                // shares: no chunk has more than max_shares of them (none at all: nothing to launch)
+                const unsigned max_shares = (unsigned)h_misc[11];
+                if (max_shares != 0)
+                    L.run(GREM_KERNEL_RELAYOUT, [&] {
+                        hipLaunchKernelGGL((k_tp_group<RowT, true>),
+                                           dim3((unsigned)nchunks * max_shares * (unsigned)nps), dim3(kTpThreads),
+                                           groupS_lds, stream, rowptr, colidx, n, (uint32_t)hub_degree, pl, tb,
+                                           share_hubs, capS, (int)max_shares, Uh);
+                    });
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
                     hipLaunchKernelGGL(k_tp_scan_slices, dim3((segs + 255) / 256), dim3(256), 0, stream, tb);
                 });

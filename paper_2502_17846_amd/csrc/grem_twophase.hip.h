@@ -173,8 +173,8 @@ __global__ __launch_bounds__(256) void k_plan_slices(const RowT *__restrict__ ro
 // shares that one touches at most about 1024 hubs, few enough that a share's sub-segment of a
 // column block still holds some 64 entries, at most one per slice.  misc[6] = most hubs in a
 // chunk, misc[7] = most entries in a chunk, misc[9] = most regular entries in a slice (set here
-// from the slices' counts), misc[10] = most entries in a hub share, misc[8] = hub entries of all
-// chunks.
+// from the slices' counts), misc[10] = most entries in a hub share, misc[11] = most hub shares in a
+// chunk, misc[8] = hub entries of all chunks.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, int nsl, int nblk,
                                                      SweepPlan pl, u64 *__restrict__ misc) {
@@ -231,6 +231,7 @@ __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, i
         atomicMax(&misc[6], (u64)bnh);
         atomicMax(&misc[7], breg + bhent);
         if (nvs) atomicMax(&misc[10], bhent / nvs + 1);
+        if (nvs) atomicMax(&misc[11], nvs);
         atomicAdd(&misc[8], bhent);
     }
 }
@@ -464,7 +465,8 @@ __device__ __host__ inline size_t tp_source_words(bool share, int np, int share_
 }
 
 // ------------------------------------------------------------------------------------------------
-// Re-layout, step 1 (one unit per workgroup, blockIdx.x = (c * nsl + i) * np + q): count the unit's
+// Re-layout, step 1 (one unit per workgroup, blockIdx.x = (c * per_chunk + i) * np + q, per_chunk
+// being nsl for slices and the largest number of shares of a chunk for shares): count the unit's
 // entries per column block (added to subR / subH [row(c,i)][*], which start at zero and become
 // starts in k_tp_scan_slices), and copy its tuples, grouped by column-block GROUP (2^gb consecutive
 // blocks), to the unit's own range of U (Uh for shares): the entries' own positions in the CSR
@@ -478,7 +480,7 @@ template <typename RowT, bool SHARE>
 __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tp_group(const RowT *__restrict__ rowptr,
                                                          const int32_t *__restrict__ colidx, int64_t n,
                                                          uint32_t hub_degree, SweepPlan pl, TpTables tb,
-                                                         int share_hubs, uint32_t cap,
+                                                         int share_hubs, uint32_t cap, int per_chunk,
                                                          uint32_t *__restrict__ U) {
     extern __shared__ u64 smem64[];
     const int np = SHARE ? tb.nps : tb.npr;
@@ -489,17 +491,16 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
     const int tid = threadIdx.x;
     const unsigned gs = blockIdx.x / (unsigned)np;
     const int q = (int)(blockIdx.x % (unsigned)np);
-    const int64_t c = gs / tb.nsl;
-    const int i = gs % tb.nsl;
-    uint32_t *lo_out = (SHARE ? tb.loh : tb.lo) + (size_t)blockIdx.x * (tb.ngroups + 1);
+    const int64_t c = gs / (unsigned)per_chunk;
+    const int i = gs % (unsigned)per_chunk;
+    uint32_t *lo_out = (SHARE ? tb.loh : tb.lo) + (((size_t)c * tb.nsl + i) * np + q) * (tb.ngroups + 1);
     TpEntrySource src;
+    for (int j = tid; j < tb.nblk; j += kTpThreads) cntf[j] = 0;    // the source's closing barrier covers this too
     if (!tp_entry_source<RowT, SHARE>(rowptr, colidx, n, hub_degree, pl, tb, c, i, q, np, share_hubs, smem64,
                                       &src)) {
         for (int j = tid; j <= tb.ngroups; j += kTpThreads) lo_out[j] = 0;
         return;
     }
-    for (int j = tid; j < tb.nblk; j += kTpThreads) cntf[j] = 0;
-    __syncthreads();
     // a unit of one round (the usual case) keeps its entries in registers between the two phases
     const uint32_t rounds = tp_rounds<SHARE>(src);
     uint32_t row[kTpBatch], col[kTpBatch];
@@ -513,20 +514,16 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
         }
     }
     __syncthreads();
-    uint32_t *row_out = (SHARE ? tb.subH : tb.subR) + ((size_t)c * (tb.nsl + 1) + i) * tb.nblk;
-    for (int j = tid; j < tb.nblk; j += kTpThreads)
-        if (cntf[j]) atomicAdd(&row_out[j], cntf[j]);
-    for (int gq = tid; gq < tb.ngroups; gq += kTpThreads) {
-        const int j0 = gq << tb.gb;
-        const int j1 = (j0 + (1 << tb.gb)) < tb.nblk ? j0 + (1 << tb.gb) : tb.nblk;
-        uint32_t sum = 0;
-        for (int j = j0; j < j1; ++j) sum += cntf[j];
-        cg[gq] = sum;
-    }
-    __syncthreads();
+    // tuples per group -> starts: one wavefront (a lane per group) while the others add the unit's
+    // counts to the slice's
     if (tb.ngroups <= 64) {
-        if (tid < 64) {                                 // exclusive prefix over the groups by one wavefront
-            const uint32_t mine = tid < tb.ngroups ? cg[tid] : 0u;
+        if (tid < 64) {
+            uint32_t mine = 0;
+            if (tid < tb.ngroups) {
+                const int j0 = tid << tb.gb;
+                const int j1 = (j0 + (1 << tb.gb)) < tb.nblk ? j0 + (1 << tb.gb) : tb.nblk;
+                for (int j = j0; j < j1; ++j) mine += cntf[j];
+            }
             uint32_t inc = mine;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
@@ -536,11 +533,24 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
             if (tid < tb.ngroups) { cg[tid] = inc - mine; cur[tid] = inc - mine; }
             if (tid == tb.ngroups - 1) cg[tb.ngroups] = inc;
         }
-    } else if (tid == 0) {
-        uint32_t run = 0;
-        for (int gq = 0; gq < tb.ngroups; ++gq) { const uint32_t t = cg[gq]; cg[gq] = run; cur[gq] = run; run += t; }
-        cg[tb.ngroups] = run;
+    } else {
+        for (int gq = tid; gq < tb.ngroups; gq += kTpThreads) {
+            const int j0 = gq << tb.gb;
+            const int j1 = (j0 + (1 << tb.gb)) < tb.nblk ? j0 + (1 << tb.gb) : tb.nblk;
+            uint32_t sum = 0;
+            for (int j = j0; j < j1; ++j) sum += cntf[j];
+            cg[gq] = sum;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t run = 0;
+            for (int gq = 0; gq < tb.ngroups; ++gq) { const uint32_t t = cg[gq]; cg[gq] = run; cur[gq] = run; run += t; }
+            cg[tb.ngroups] = run;
+        }
     }
+    uint32_t *row_out = (SHARE ? tb.subH : tb.subR) + ((size_t)c * (tb.nsl + 1) + i) * tb.nblk;
+    for (int j = tid; j < tb.nblk; j += kTpThreads)
+        if (cntf[j]) atomicAdd(&row_out[j], cntf[j]);
     __syncthreads();
     for (int gq = tid; gq <= tb.ngroups; gq += kTpThreads) lo_out[gq] = cg[gq];
     const uint32_t total = cg[tb.ngroups];
@@ -621,7 +631,7 @@ __global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb, u64 *__r
 // 2048, which the look-up turns into an entry the score ignores; every odd sub-segment ends with
 // one), and written out contiguously.  A batch that does not fit `cap` slots is cut down to one
 // slice; a slice that does not fit is written tuple by tuple.
-// LDS: tbase[nbg] (u64), runsrc[batch * npmax] (u64), runlo[batch * npmax + 1], runsl[batch * npmax],
+// LDS: tbase[nbg] (u64), runsrc[batch * npmax] (u64), runlen[batch * npmax + 1], runsl[batch * npmax],
 //      joff[nbg + 1], s0[nbg], cur[batch * nbg], stage[cap]
 // ------------------------------------------------------------------------------------------------
 constexpr int kPlaceThreads = 512;
@@ -640,13 +650,14 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
     const int maxruns = batch * npmax;
     u64 *tbase = smem64;                                        // nbg
     u64 *runsrc = tbase + nbg;                                  // maxruns    first tuple of the run
-    uint32_t *runlo = reinterpret_cast<uint32_t *>(runsrc + maxruns);   // maxruns + 1   prefix of the runs' lengths
-    uint32_t *runsl = runlo + maxruns + 1;                      // maxruns    slice (in the batch) of the run
+    uint32_t *runlen = reinterpret_cast<uint32_t *>(runsrc + maxruns);  // maxruns + 1   tuples in the run
+    uint32_t *runsl = runlen + maxruns + 1;                     // maxruns    slice (in the batch) of the run
     uint32_t *joff = runsl + maxruns;                           // nbg + 1    start of block j's piece in stage
     uint32_t *s0 = joff + nbg + 1;                              // nbg        start of the piece in the segment
     uint32_t *cur = s0 + nbg;                                   // batch * nbg  next free slot (in stage)
     uint32_t *stage = cur + batch * nbg;                        // cap
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int kNW = kPlaceThreads / 64, kRU = 8, kXU = 3;
     const int64_t chunk_lo = (int64_t)c * tb.chunk;
     const int64_t chunk_hi = (chunk_lo + tb.chunk < n) ? chunk_lo + tb.chunk : n;
     const int nsl_c = (int)((chunk_hi - chunk_lo + kSliceRows - 1) / kSliceRows);
@@ -662,50 +673,56 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
         const uint32_t *src = part == 0 ? U : Uh;
         int i0 = 0;
         while (i0 < count) {
-            __syncthreads();                                    // previous batch done with the LDS tables
             // the largest batch (<= `batch` slices) whose pieces fit the stage; at least one slice
             int nb = count - i0 < batch ? count - i0 : batch;
-            uint32_t need = 0;
+            uint32_t need;
             for (;;) {
-                need = 0;
-                for (int j = 0; j < nbg; ++j)
-                    need += sub[(size_t)(i0 + nb) * tb.nblk + j] - sub[(size_t)i0 * tb.nblk + j];
+                __syncthreads();                                // previous batch (attempt) done with the LDS tables
+                for (int z = tid; z < nb * np; z += kPlaceThreads) {
+                    const int t = z / np, q = z % np;
+                    const size_t unit = ((size_t)c * tb.nsl + i0 + t) * np + q;
+                    const uint32_t a = lot[unit * (tb.ngroups + 1) + g], b = lot[unit * (tb.ngroups + 1) + g + 1];
+                    u64 at;
+                    if (part == 0) {
+                        const int64_t v = chunk_lo + (int64_t)(i0 + t) * kSliceRows + (int64_t)q * (kSliceRows / np);
+                        at = v < chunk_hi ? (u64)rowptr[v] : 0ull;   // a part beyond the chunk has no tuples
+                    } else {
+                        const u64 H = pl.ch_H[c];
+                        const u64 sa = H * (u64)(i0 + t) / (u64)nvs, sb = H * (u64)(i0 + t + 1) / (u64)nvs;
+                        at = pl.ch_hbase[c] + sa + (sb - sa) * (u64)q / (u64)np;
+                    }
+                    runsrc[z] = at + a;
+                    runlen[z] = b - a;
+                    runsl[z] = (uint32_t)t;
+                }
+                for (int j = tid; j < nbg; j += kPlaceThreads) {
+                    const uint32_t a = sub[(size_t)i0 * tb.nblk + j];
+                    s0[j] = a;
+                    joff[j + 1] = sub[(size_t)(i0 + nb) * tb.nblk + j] - a;
+                }
+                __syncthreads();
+                if (nbg <= 64) {                                // lengths of the pieces -> their starts in stage
+                    if (tid < 64) {
+                        uint32_t inc = tid < nbg ? joff[tid + 1] : 0u;
+#pragma unroll
+                        for (int off = 1; off < 64; off <<= 1) {
+                            const uint32_t o = __shfl_up(inc, off);
+                            if (tid >= off) inc += o;
+                        }
+                        if (tid < nbg) joff[tid + 1] = inc;
+                        if (tid == 0) joff[0] = 0;
+                    }
+                } else if (tid == 0) {
+                    uint32_t run = 0;
+                    joff[0] = 0;
+                    for (int j = 0; j < nbg; ++j) { run += joff[j + 1]; joff[j + 1] = run; }
+                }
+                __syncthreads();
+                need = joff[nbg];
                 if (need <= cap || nb == 1) break;
                 nb = 1;
             }
             const bool staged = need <= cap;
-            for (int z = tid; z < nb * np; z += kPlaceThreads) {
-                const int t = z / np, q = z % np;
-                const size_t unit = ((size_t)c * tb.nsl + i0 + t) * np + q;
-                const uint32_t a = lot[unit * (tb.ngroups + 1) + g], b = lot[unit * (tb.ngroups + 1) + g + 1];
-                u64 at;
-                if (part == 0) {
-                    const int64_t v = chunk_lo + (int64_t)(i0 + t) * kSliceRows + (int64_t)q * (kSliceRows / np);
-                    at = v < chunk_hi ? (u64)rowptr[v] : 0ull;   // a part beyond the chunk has no tuples
-                } else {
-                    const u64 H = pl.ch_H[c];
-                    const u64 sa = H * (u64)(i0 + t) / (u64)nvs, sb = H * (u64)(i0 + t + 1) / (u64)nvs;
-                    at = pl.ch_hbase[c] + sa + (sb - sa) * (u64)q / (u64)np;
-                }
-                runsrc[z] = at + a;
-                runlo[z + 1] = b - a;
-                runsl[z] = (uint32_t)t;
-            }
-            for (int j = tid; j < nbg; j += kPlaceThreads) {
-                const uint32_t a = sub[(size_t)i0 * tb.nblk + j];
-                s0[j] = a;
-                joff[j + 1] = sub[(size_t)(i0 + nb) * tb.nblk + j] - a;
-            }
-            __syncthreads();
-            if (tid == 0) {
-                uint32_t run = 0;
-                runlo[0] = 0;
-                for (int z = 0; z < nb * np; ++z) { run += runlo[z + 1]; runlo[z + 1] = run; }
-                run = 0;
-                joff[0] = 0;
-                for (int j = 0; j < nbg; ++j) { run += joff[j + 1]; joff[j + 1] = run; }
-            }
-            __syncthreads();
             for (int z = tid; z < nb * nbg; z += kPlaceThreads) {
                 const int t = z / nbg, j = z % nbg;
                 // staged: slot in stage; else: slot in the segment
@@ -715,45 +732,52 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
             if (staged)
                 for (uint32_t z = tid; z < need; z += kPlaceThreads) stage[z] = pad;
             __syncthreads();
+            // a wavefront takes whole runs, kRU at a time, the first kXU * 64 tuples of each loaded side
+            // by side before any is placed
             const int nruns = nb * np;
-            const uint32_t total = runlo[nruns];
-            int top = 1;
-            while (top < nruns) top <<= 1;
-            for (uint32_t base = tid; base < total; base += kPlaceThreads * kTpBatch) {
-                uint32_t run_of[kTpBatch], u[kTpBatch];
+            auto put = [&](uint32_t u, uint32_t sl) {
+                const uint32_t j = (u >> tb.cb) & gmask;
+                const uint32_t w = atomicAdd(&cur[sl * nbg + j], 1u);
+                const uint32_t tuple = ((u >> (tb.cb + tb.gb)) << tb.cb) | (u & cmask);
+                if (staged) stage[w] = tuple;
+                else T[tbase[j] + w] = tuple;
+            };
+            for (int z0 = wave; z0 < nruns; z0 += kNW * kRU) {
+                uint32_t u[kRU][kXU], len[kRU], sl[kRU];
+                const uint32_t *from[kRU];
 #pragma unroll
-                for (int x = 0; x < kTpBatch; ++x) run_of[x] = 0;
-                for (int step = top >> 1; step >= 1; step >>= 1) {
+                for (int r = 0; r < kRU; ++r) {
+                    const int z = z0 + r * kNW;
+                    const int zz = z < nruns ? z : z0;
+                    len[r] = z < nruns ? (uint32_t)__builtin_amdgcn_readfirstlane((int)runlen[zz]) : 0u;
+                    sl[r] = (uint32_t)__builtin_amdgcn_readfirstlane((int)runsl[zz]);
+                    const u64 at = runsrc[zz];
+                    from[r] = src + (((u64)(uint32_t)__builtin_amdgcn_readfirstlane((int)(at >> 32)) << 32) |
+                                     (u64)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)at));
 #pragma unroll
-                    for (int x = 0; x < kTpBatch; ++x) {
-                        const uint32_t cand = run_of[x] + step;         // largest z < nruns with runlo[z] <= p
-                        const uint32_t cc = cand < (uint32_t)nruns ? cand : (uint32_t)nruns - 1u;
-                        if (cand < (uint32_t)nruns && runlo[cc] <= base + x * kPlaceThreads) run_of[x] = cand;
+                    for (int x = 0; x < kXU; ++x) {
+                        const uint32_t p = (uint32_t)(x * 64 + lane);
+                        u[r][x] = p < len[r] ? __builtin_nontemporal_load(from[r] + p) : 0u;
                     }
                 }
 #pragma unroll
-                for (int x = 0; x < kTpBatch; ++x) {
-                    const uint32_t p = base + x * kPlaceThreads;
-                    u[x] = p < total ? __builtin_nontemporal_load(src + runsrc[run_of[x]] + (p - runlo[run_of[x]])) : 0u;
+                for (int r = 0; r < kRU; ++r) {
+#pragma unroll
+                    for (int x = 0; x < kXU; ++x)
+                        if ((uint32_t)(x * 64 + lane) < len[r]) put(u[r][x], sl[r]);
                 }
 #pragma unroll
-                for (int x = 0; x < kTpBatch; ++x) {
-                    const uint32_t p = base + x * kPlaceThreads;
-                    if (p < total) {
-                        const uint32_t j = (u[x] >> tb.cb) & gmask;
-                        const uint32_t w = atomicAdd(&cur[runsl[run_of[x]] * nbg + j], 1u);
-                        const uint32_t tuple = ((u[x] >> (tb.cb + tb.gb)) << tb.cb) | (u[x] & cmask);
-                        if (staged) stage[w] = tuple;
-                        else T[tbase[j] + w] = tuple;
-                    }
-                }
+                for (int r = 0; r < kRU; ++r)
+                    for (uint32_t p = (uint32_t)(kXU * 64 + lane); p < len[r]; p += 64)
+                        put(__builtin_nontemporal_load(from[r] + p), sl[r]);
             }
             __syncthreads();
             if (staged) {
-                for (int j = 0; j < nbg; ++j) {
+                for (int j = wave; j < nbg; j += kNW) {         // a piece per wavefront
                     const uint32_t a = joff[j], len = joff[j + 1] - a;
                     uint32_t *out = T + tbase[j] + s0[j];
-                    for (uint32_t z = tid; z < len; z += kPlaceThreads) __builtin_nontemporal_store(stage[a + z], out + z);
+#pragma unroll 4
+                    for (uint32_t z = lane; z < len; z += 64) __builtin_nontemporal_store(stage[a + z], out + z);
                 }
             } else {
                 for (int z = tid; z < nb * nbg; z += kPlaceThreads) {
