@@ -466,10 +466,10 @@ __global__ __launch_bounds__(kAdmitThreads) void k_apply(
 }
 
 // ------------------------------------------------------------------------------------------------
-// apply for k <= 16: the same admission, one vertex per thread and one tile per workgroup of
-// kAdmitTile threads, ranks from one ballot per partition.  cnt[tile][t] = movers to t in that tile
-// (the workgroup adds up the rows of the earlier tiles itself); room[t] = P - S[t] as of the
-// chunk's start.
+// apply for k <= 16: the same admission, one vertex of each of two neighbouring tiles per thread,
+// a workgroup of kAdmitTile threads per pair of tiles, ranks from one ballot per partition and
+// tile.  cnt[tile][t] = movers to t in that tile (the workgroup adds up the rows of the earlier
+// tiles itself); room[t] = P - S[t] as of the chunk's start.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc, const uint8_t *__restrict__ prop,
                                                         int64_t chunk_lo, int64_t chunk_hi, int k,
@@ -478,58 +478,94 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
                                                         unsigned long long *__restrict__ S,
                                                         uint32_t *__restrict__ ocnt, int pass) {
     constexpr int nwaves = kAdmitTile / 64;
-    __shared__ uint32_t tbl[16];                // movers in earlier tiles
-    __shared__ uint32_t wcnt[nwaves][16];       // movers per wave, then their exclusive prefix over the waves
+    __shared__ uint32_t tbl[16];                // movers in the tiles before the pair
+    __shared__ uint32_t wcnt[2][nwaves][16];    // movers per tile and wave, then their exclusive prefix over the waves
     __shared__ int32_t dS[16];
     __shared__ long long s_room[16];
-    __shared__ uint32_t s_unassigned;
+    __shared__ uint32_t s_unassigned[2];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const int64_t v = chunk_lo + (int64_t)blockIdx.x * kAdmitTile + tid;
-    const bool inside = v < chunk_hi;
-    uint32_t t = 0, old = 0;
-    if (inside) { t = prop[v - chunk_lo]; old = (uint32_t)Lc[v]; }
+    const int tile0 = 2 * (int)blockIdx.x;
+    int64_t v[2];
+    bool inside[2];
+    uint32_t t[2] = {0, 0}, old[2] = {0, 0};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        v[h] = chunk_lo + (int64_t)(tile0 + h) * kAdmitTile + tid;
+        inside[h] = v[h] < chunk_hi;
+        if (inside[h]) { t[h] = prop[v[h] - chunk_lo]; old[h] = (uint32_t)Lc[v[h]]; }
+    }
     if (tid < 16) { tbl[tid] = 0; dS[tid] = 0; s_room[tid] = tid < k ? room[tid] : 0; }
-    if (tid == 0) s_unassigned = 0;
+    if (tid < 2) s_unassigned[tid] = 0;
     __syncthreads();
+    const int col = tid & 15, seg = tid >> 4;
     {   // earlier tiles: thread (seg, col) adds up rows seg, seg + 64, ...
-        const int col = tid & 15, seg = tid >> 4;
         uint32_t sum = 0;
         if (col < k)
-            for (int r = seg; r < (int)blockIdx.x; r += kAdmitTile / 16) sum += cnt[(size_t)r * k + col];
+            for (int r = seg; r < tile0; r += kAdmitTile / 16) sum += cnt[(size_t)r * k + col];
         if (sum) atomicAdd(&tbl[col], sum);
     }
-    const bool mover = inside && t != old;
-    uint32_t wrank = 0, mine = 0;
-    for (int j = 0; j < k; ++j) {
-        const unsigned long long m = __ballot(mover && t == (uint32_t)j);
-        if (mover && t == (uint32_t)j) wrank = (uint32_t)__popcll(m & lanes_below(lane));
-        if (lane == j) mine = (uint32_t)__popcll(m);
+    const uint32_t first_tile = (tid < 16 && tid < k) ? cnt[(size_t)tile0 * k + tid] : 0u;   // movers of the pair's first tile
+    bool mover[2];
+    uint32_t wrank[2] = {0, 0};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        mover[h] = inside[h] && t[h] != old[h];
+        uint32_t mine = 0;
+        for (int j = 0; j < k; ++j) {
+            const unsigned long long m = __ballot(mover[h] && t[h] == (uint32_t)j);
+            if (mover[h] && t[h] == (uint32_t)j) wrank[h] = (uint32_t)__popcll(m & lanes_below(lane));
+            if (lane == j) mine = (uint32_t)__popcll(m);
+        }
+        if (lane < 16) wcnt[h][wave][lane] = lane < k ? mine : 0u;
     }
-    if (lane < 16) wcnt[wave][lane] = lane < k ? mine : 0u;
     __syncthreads();
     if (tid < 16) {
         uint32_t run = 0;
-        for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[w][tid]; wcnt[w][tid] = run; run += c; }
+        for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[0][w][tid]; wcnt[0][w][tid] = run; run += c; }
+        run = first_tile;
+        for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[1][w][tid]; wcnt[1][w][tid] = run; run += c; }
     }
     __syncthreads();
-    bool admitted = false;
-    if (mover) {
-        const long long rank = (long long)tbl[t] + wcnt[wave][t] + wrank;
-        admitted = rank < s_room[t];
-    }
-    if (admitted) {
-        Lc[v] = (uint8_t)t;
-        atomicAdd(&dS[t], 1);
-        if (old != 0xFFu) atomicAdd(&dS[old], -1);
-    } else if (pass == 0 && inside && old == 0xFFu) {
-        atomicAdd(&s_unassigned, 1u);       // rejected new vertex (a new vertex is always a mover)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        bool admitted = false;
+        if (mover[h]) {
+            const long long rank = (long long)tbl[t[h]] + wcnt[h][wave][t[h]] + wrank[h];
+            admitted = rank < s_room[t[h]];
+        }
+        if (admitted) {
+            Lc[v[h]] = (uint8_t)t[h];
+            atomicAdd(&dS[t[h]], 1);
+            if (old[h] != 0xFFu) atomicAdd(&dS[old[h]], -1);
+        } else if (pass == 0 && inside[h] && old[h] == 0xFFu) {
+            atomicAdd(&s_unassigned[h], 1u);    // rejected new vertex (a new vertex is always a mover)
+        }
     }
     __syncthreads();
     if (tid < k) {
         const int32_t d = dS[tid];
         if (d != 0) atomicAdd(&S[tid], (unsigned long long)(long long)d);
     }
-    if (pass == 0 && tid == 0) ocnt[blockIdx.x] = s_unassigned;
+    if (pass == 0 && tid < 2 && chunk_lo + (int64_t)(tile0 + tid) * kAdmitTile < chunk_hi)
+        ocnt[tile0 + tid] = s_unassigned[tid];
+}
+
+// Exclusive prefix of `mine` over the threads of a workgroup (every thread calls it): shuffles
+// inside the wavefront, then the totals of the earlier wavefronts from `wave_total` (LDS, one slot
+// per wavefront, free for reuse after the next barrier).
+__device__ __forceinline__ long long block_exclusive_sum(long long mine, long long *wave_total) {
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    long long inc = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const long long o = __shfl_up(inc, off);
+        if (lane >= off) inc += o;
+    }
+    if (lane == 63) wave_total[wave] = inc;
+    __syncthreads();
+    long long before = inc - mine;
+    for (int w = 0; w < wave; ++w) before += wave_total[w];
+    return before;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -547,7 +583,7 @@ __global__ __launch_bounds__(kScanThreads) void k_spill_scan(uint32_t *__restric
                                                              long long *__restrict__ fillSorted,
                                                              long long *__restrict__ fillC,
                                                              unsigned long long *__restrict__ misc) {
-    __shared__ long long part[kScanThreads];
+    __shared__ long long part[kScanThreads / 64];
     __shared__ long long Sl[GREM_MAX_K_DEVICE];
     __shared__ long long s_total;
     const int tid = threadIdx.x;
@@ -557,10 +593,7 @@ __global__ __launch_bounds__(kScanThreads) void k_spill_scan(uint32_t *__restric
         const int thi = (tlo + tps < ntiles) ? tlo + tps : ntiles;
         long long sum = 0;
         for (int t = tlo; t < thi; ++t) sum += ocnt[t];
-        part[tid] = sum;
-        __syncthreads();
-        long long b = 0;
-        for (int s = 0; s < tid; ++s) b += part[s];
+        long long b = block_exclusive_sum(sum, part);
         if (tid == kScanThreads - 1) s_total = b + sum;
         for (int t = tlo; t < thi; ++t) {
             uint32_t c = ocnt[t];
@@ -593,10 +626,7 @@ __global__ __launch_bounds__(kScanThreads) void k_spill_scan(uint32_t *__restric
         long long sum = 0;
         for (int q = qlo; q < qhi; ++q)
             sum += __hip_atomic_load(fillSorted + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        part[tid] = sum;
-        __syncthreads();
-        long long ps = 0;
-        for (int s = 0; s < tid; ++s) ps += part[s];
+        long long ps = block_exclusive_sum(sum, part);
         for (int q = qlo; q < qhi; ++q) {
             long long sq = __hip_atomic_load(fillSorted + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             fillC[q] = (long long)q * sq - ps;     // sum_{p<q} (s[q] - s[p])

@@ -384,19 +384,31 @@ __device__ __forceinline__ void tp_load_round(const TpEntrySource &src, uint32_t
 #pragma unroll
         for (int u = 0; u < U; ++u) row[u] += src.row0;
     } else {
-        const uint32_t base = round * kTpThreads * U + threadIdx.x;
+        // a wavefront takes 64 * U consecutive positions of the hub entry stream: the hub of the first is
+        // found once, the others' hubs lie a step or two further on (hubs are long rows)
+        const uint32_t blk = (round * NW + (uint32_t)wave) * 64u * U;
+#pragma unroll
+        for (int u = 0; u < U; ++u) { on[u] = false; col[u] = 0; row[u] = 0; }
+        if (blk >= src.len) return;
+        uint32_t first = 0, hi = src.nhs;
+        {
+            const u64 e = src.a + blk;
+            while (hi - first > 1) { const uint32_t mid = (first + hi) >> 1; if (src.hoff[mid] <= e) first = mid; else hi = mid; }
+        }
+        const u64 next = src.hoff[first + 1];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t p = base + u * kTpThreads;
+            const uint32_t p = blk + u * 64 + lane;
             on[u] = p < src.len;
-            col[u] = 0;
-            row[u] = 0;
             if (on[u]) {
                 const u64 e = src.a + p;                     // position in the chunk's hub entry stream
-                uint32_t lo = 0, hi = src.nhs;
-                while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (src.hoff[mid] <= e) lo = mid; else hi = mid; }
-                row[u] = lo;
-                col[u] = (uint32_t)__builtin_nontemporal_load(src.colidx + (int64_t)(src.hrow[lo] + (e - src.hoff[lo])));
+                uint32_t h = first;
+                if (e >= next) {
+                    h = first + 1;
+                    while (src.hoff[h + 1] <= e) ++h;        // hoff[nhs] is beyond the share's last entry
+                }
+                row[u] = h;
+                col[u] = (uint32_t)__builtin_nontemporal_load(src.colidx + (int64_t)(src.hrow[h] + (e - src.hoff[h])));
             }
         }
     }
