@@ -58,8 +58,8 @@ extern "C" {
 #define GREM_MAX_K 4096
 
 /* Histogram placement for the per-vertex partition counts (Alg. 2, cnt_nbrs). */
-#define GREM_HIST_AUTO 0     /* LDS when a tile of rows fits the LDS budget (k <= 128), else global */
-#define GREM_HIST_LDS 1      /* force LDS (error GREM_ERR_ARG if k > 128) */
+#define GREM_HIST_AUTO 0     /* LDS when a tile of rows fits the LDS budget (k <= 1024), else global */
+#define GREM_HIST_LDS 1      /* force LDS (error GREM_ERR_ARG if k > 1024) */
 #define GREM_HIST_GLOBAL 2   /* force accumulation straight into E's rows in global memory */
 #define GREM_HIST_SWEEP 3    /* force the two-phase path: a re-laid-out copy of the entries; after a
                                 chunk is relabelled its labels are looked up, from LDS, for every
@@ -133,6 +133,12 @@ int grem_set_sweep_col_bits(int32_t bits);
  * spread evenly over the chunk's workgroups.  1..65535, default 2048; smaller values only make
  * sense for testing on small graphs.  Process-wide. */
 int grem_set_sweep_hub_degree(int32_t degree);
+
+/* Outside the two-phase path a tile of rows is scored by one workgroup; rows of at least this
+ * many entries are taken out of their tile and spread over a grid of their own (a hub's row is
+ * the work of many workgroups, as the paper's power-law graphs need).  0 = default (16384);
+ * smaller values only make sense for testing on small graphs.  Process-wide. */
+int grem_set_long_row_degree(int32_t degree);
 
 /* Per-kernel timing with HIP events on the caller's stream, for measurement.  While enabled every
  * kernel launch of a partition call is bracketed by two events.  grem_profile_read synchronises on

@@ -24,7 +24,7 @@ EXPORTS = [
     "grem_partition", "grem_partition_seeded", "grem_partition_r32", "grem_partition_seeded_r32",
     "grem_partition_state", "grem_edge_cut", "grem_edge_cut_r32", "grem_capacity",
     "grem_workspace_bytes", "grem_set_workspace", "grem_set_histogram_mode",
-    "grem_set_sweep_col_bits", "grem_set_sweep_hub_degree", "grem_profile_enable",
+    "grem_set_sweep_col_bits", "grem_set_sweep_hub_degree", "grem_set_long_row_degree", "grem_profile_enable",
     "grem_profile_reset", "grem_profile_read", "grem_status_string", "grem_kernel_name",
 ]
 
@@ -71,6 +71,8 @@ def load():
     lib.grem_set_sweep_col_bits.argtypes = [i32]
     lib.grem_set_sweep_hub_degree.restype = ctypes.c_int
     lib.grem_set_sweep_hub_degree.argtypes = [i32]
+    lib.grem_set_long_row_degree.restype = ctypes.c_int
+    lib.grem_set_long_row_degree.argtypes = [i32]
     lib.grem_profile_enable.restype = ctypes.c_int
     lib.grem_profile_enable.argtypes = [i32]
     lib.grem_profile_reset.restype = ctypes.c_int
@@ -152,6 +154,10 @@ def grem_set_sweep_col_bits(bits: int):
 
 def grem_set_sweep_hub_degree(degree: int):
     _check(load().grem_set_sweep_hub_degree(degree), "grem_set_sweep_hub_degree")
+
+
+def grem_set_long_row_degree(degree: int):
+    _check(load().grem_set_long_row_degree(degree), "grem_set_long_row_degree")
 
 
 def _rowptr_bits(rowptr: torch.Tensor) -> int:

@@ -19,7 +19,10 @@ namespace {
 using namespace grem;
 
 constexpr int kLdsHistBytes = 32 * 1024;   // LDS spent on one tile's histograms
-constexpr int kLdsMaxK = 128;              // above this the histograms live in E's rows
+constexpr int kLdsMaxK = 1024;             // above this the histograms live in E's rows
+constexpr int kLongRowDegree = 16384;      // plain score kernels: rows this long get a grid of their own ...
+constexpr uint32_t kLongRowPart = 16384;   // ... that many entries per workgroup and turn
+constexpr unsigned kLongRowGrid = 512;
 constexpr int kSweepMaxK = 16;             // two-phase path: 4-bit labels, 16-bit counters, 2048 rows, 64 KB
 constexpr int64_t kSweepMinN = 1 << 22;    // AUTO: label table must exceed L2 for the path to pay
 constexpr int64_t kSweepMinChunk = 1 << 14;   // AUTO: per-chunk launches must have work to do
@@ -31,6 +34,7 @@ struct Global {
     void *ws = nullptr;
     size_t ws_bytes = 0;
     int hist_mode = GREM_HIST_AUTO;
+    int long_row_degree = kLongRowDegree;
     int sweep_col_bits = 0;                // 0 = automatic
     int sweep_hub_degree = 2048;
     bool prof = false;
@@ -77,7 +81,7 @@ TpGeom tp_geometry(int64_t n, int64_t chunk, int col_bits_setting) {
 }
 
 struct Layout {
-    size_t E, Lc, prop, S, cnt, room, ocnt, fillRank, fillSorted, fillC, misc;
+    size_t E, Lc, prop, S, cnt, room, ocnt, fillRank, fillSorted, fillC, misc, long_cnt, long_list;
     // plan of the two-phase path (k <= 16 only)
     size_t sl_reg_cnt, sl_reg_start, sl_nh, sl_hub_start, sl_hent, sl_hent_start, share_h0, share_nhs,
         ch_regtot, ch_nh, ch_H, ch_nvs, ch_hbase, hub_row, hub_off;
@@ -114,6 +118,8 @@ Layout make_layout(int64_t n, int64_t nnz, int64_t hub_entries, int32_t k, int64
     L.fillSorted = take((size_t)k * 8);
     L.fillC = take(((size_t)k + 1) * 8);
     L.misc = take(16 * 8);
+    L.long_cnt = take((size_t)nchunks * 4);
+    L.long_list = take((size_t)cl * 4);
     const bool tp_possible = k <= kSweepMaxK && tp.ok;
     if (tp_possible) {
         L.sl_reg_cnt = take(G * 4);
@@ -240,6 +246,8 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
     long long *fillSorted = (long long *)(ws + lay.fillSorted);
     long long *fillC = (long long *)(ws + lay.fillC);
     unsigned long long *misc = (unsigned long long *)(ws + lay.misc);
+    uint32_t *long_cnt = (uint32_t *)(ws + lay.long_cnt);
+    uint32_t *long_list = (uint32_t *)(ws + lay.long_list);
 
     Launcher L{stream};
 
@@ -421,7 +429,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 // takes for the largest to fit, two workgroups per CU
                 constexpr size_t kGroupLds = 79 * 1024, kPlaceLds = 52 * 1024;
                 auto group_fixed = [&](bool share, int np) {
-                    return (tp_source_words(share, np, share_hubs) + (size_t)geo.nblk + 2 * (size_t)geo.ngroups + 1) * 4;
+                    return (tp_source_words(share, np, share_hubs) + (size_t)geo.nblk + (size_t)geo.ngroups + 1 + kTpThreads / 64) * 4;
                 };
                 auto group_cap = [&](bool share, int np) {
                     const size_t fixed = group_fixed(share, np);
@@ -533,7 +541,18 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
         }
     }
 
+    // plain score kernels: rows this long are taken out of their tile and spread over a grid of their own
+    const bool split_long = !sweep && maxdeg >= (unsigned long long)g.long_row_degree;
+    const size_t long_lds = (size_t)k * 4;
+    if (split_long && long_lds > 64 * 1024 &&
+        hipFuncSetAttribute((const void *)k_long_rows<RowT, LabelT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)long_lds) != hipSuccess) { release(); return GREM_ERR_HIP; }
+
     for (int pass = 0; pass <= R && !L.err; ++pass) {
+        if (split_long && hipMemsetAsync(long_cnt, 0, (size_t)nchunks * 4, stream) != hipSuccess) {
+            release();
+            return GREM_ERR_HIP;
+        }
         for (int64_t c = 0; c < nchunks && !L.err; ++c) {
             const int64_t lo = c * chunk;
             const int64_t hi = (lo + chunk < n) ? lo + chunk : n;
@@ -566,20 +585,30 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                                                (uint8_t *)prop, cnt, (int)c, lo, (int)k, pass, store_e);
                         });
                 }
-            } else if (use_lds) {
-                const unsigned score_blocks = (unsigned)((len + tv - 1) / tv);
-                L.run(GREM_KERNEL_SCORE, [&] {
-                    hipLaunchKernelGGL((k_score_lds<RowT, LabelT>), dim3(score_blocks),
-                                       dim3(kScoreThreads), score_lds, stream, rowptr, colidx, Lc, S, E,
-                                       prop, lo, hi, (int)k, tv, pass, P, gather_limit);
-                });
             } else {
+                const LongRows lr{split_long ? (uint32_t)g.long_row_degree : 0xFFFFFFFFu, kLongRowPart,
+                                  long_cnt + c, long_list};
                 const unsigned score_blocks = (unsigned)((len + tv - 1) / tv);
                 L.run(GREM_KERNEL_SCORE, [&] {
-                    hipLaunchKernelGGL((k_score_global<RowT, LabelT>), dim3(score_blocks),
-                                       dim3(kScoreThreads), score_lds, stream, rowptr, colidx, Lc, S, E,
-                                       prop, lo, hi, (int)k, pass, P, gather_limit);
+                    if (use_lds)
+                        hipLaunchKernelGGL((k_score_lds<RowT, LabelT>), dim3(score_blocks),
+                                           dim3(kScoreThreads), score_lds, stream, rowptr, colidx, Lc, S, E,
+                                           prop, lo, hi, (int)k, tv, pass, P, gather_limit, lr);
+                    else
+                        hipLaunchKernelGGL((k_score_global<RowT, LabelT>), dim3(score_blocks),
+                                           dim3(kScoreThreads), score_lds, stream, rowptr, colidx, Lc, S, E,
+                                           prop, lo, hi, (int)k, pass, P, gather_limit, lr);
                 });
+                if (split_long) {
+                    L.run(GREM_KERNEL_HUBS, [&] {
+                        hipLaunchKernelGGL((k_long_rows<RowT, LabelT>), dim3(kLongRowGrid), dim3(kScoreThreads),
+                                           long_lds, stream, rowptr, colidx, Lc, E, (int)k, pass, gather_limit, lr);
+                    });
+                    L.run(GREM_KERNEL_HUBS, [&] {
+                        hipLaunchKernelGGL((k_long_propose<LabelT>), dim3(64), dim3(64), 0, stream, Lc, S, E, prop,
+                                           lo, (int)k, pass, P, lr);
+                    });
+                }
             }
             // admission: per-tile mover counts, their prefix over the tiles, ranks.  The two-phase score
             // kernel has already counted the movers and taken the sizes' snapshot, and its tiles are few
@@ -716,6 +745,13 @@ int grem_set_sweep_hub_degree(int32_t degree) {
     if (degree < 1 || degree > 65535) return GREM_ERR_ARG;
     std::lock_guard<std::mutex> lock(g.mu);
     g.sweep_hub_degree = degree;
+    return GREM_OK;
+}
+
+int grem_set_long_row_degree(int32_t degree) {
+    if (degree < 0) return GREM_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.long_row_degree = degree == 0 ? kLongRowDegree : degree;
     return GREM_OK;
 }
 

@@ -92,6 +92,121 @@ __global__ void k_check_seed_sizes(const long long *__restrict__ S, int k, long 
 }
 
 // ------------------------------------------------------------------------------------------------
+// Long rows of the plain score kernels.  A tile's workgroup leaves out rows of `degree` entries or
+// more (it would walk them alone) and appends them to the chunk's list; k_long_rows then spreads
+// the entries of the listed rows over a whole grid, `part` entries per workgroup and turn, and
+// k_long_propose picks their proposals.  degree = 0xFFFFFFFF: nothing is ever left out.
+// ------------------------------------------------------------------------------------------------
+struct LongRows {
+    uint32_t degree;
+    uint32_t part;
+    uint32_t *count;        // rows in the list (zero before the chunk's score kernel)
+    uint32_t *list;         // their vertex ids, in no particular order
+};
+
+// Every thread of the tile's workgroup calls this after rowrel is complete and *flag is 0; true
+// if the tile has a long row.
+__device__ __forceinline__ bool note_long_rows(const uint32_t *rowrel, int nv, int64_t v0, const LongRows &lr,
+                                               int *flag) {
+    if (lr.degree == 0xFFFFFFFFu) return false;
+    for (int i = threadIdx.x; i < nv; i += blockDim.x) {
+        if (rowrel[i + 1] - rowrel[i] >= lr.degree) {
+            *flag = 1;
+            lr.list[atomicAdd(lr.count, 1u)] = (uint32_t)(v0 + i);
+        }
+    }
+    __syncthreads();
+    return *flag != 0;
+}
+
+// Adds the neighbour-label counts of the listed rows, times 2^(pass-1) (1 in the first pass), to
+// their rows of E with integer atomics; the counts of one part are collected in LDS first (k
+// words).  Parts are dealt out round-robin over the workgroups across all listed rows.
+template <typename RowT, typename LabelT>
+__global__ __launch_bounds__(kScoreThreads) void k_long_rows(
+    const RowT *__restrict__ rowptr, const int32_t *__restrict__ colidx, const LabelT *__restrict__ Lc,
+    uint32_t *__restrict__ E, int k, int pass, int64_t gather_limit, LongRows lr) {
+    extern __shared__ uint32_t smem[];
+    uint32_t *hist = smem;                  // k
+    constexpr uint32_t UN = LabelTraits<LabelT>::kUnassigned;
+    const int tid = threadIdx.x;
+    const uint32_t nlong = *lr.count;
+    const uint32_t inc = pass == 0 ? 1u : (1u << (pass - 1));
+    constexpr int U = 4;
+    unsigned long long dealt = 0;           // parts of the rows before this one
+    for (uint32_t i = 0; i < nlong; ++i) {
+        const int64_t v = (int64_t)lr.list[i];
+        const int64_t e0 = (int64_t)rowptr[v];
+        const uint32_t deg = (uint32_t)((int64_t)rowptr[v + 1] - e0);
+        const uint32_t nparts = (deg + lr.part - 1) / lr.part;
+        // first part of this row that falls to this workgroup
+        uint32_t q = (uint32_t)((blockIdx.x + gridDim.x - (uint32_t)(dealt % gridDim.x)) % gridDim.x);
+        dealt += nparts;
+        const int32_t *cbase = colidx + e0;
+        for (; q < nparts; q += gridDim.x) {
+            for (int j = tid; j < k; j += kScoreThreads) hist[j] = 0;
+            __syncthreads();
+            const uint32_t from = q * lr.part;
+            const uint32_t to = (deg - from < lr.part) ? deg : from + lr.part;
+            for (uint32_t base = from + tid; base < to; base += kScoreThreads * U) {
+                int32_t col[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t e = base + u * kScoreThreads;
+                    col[u] = (e < to) ? __builtin_nontemporal_load(cbase + e) : -1;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (col[u] >= 0 && (int64_t)col[u] < gather_limit) {
+                        const uint32_t lab = (uint32_t)Lc[col[u]];
+                        if (lab != UN) atomicAdd(&hist[lab], 1u);
+                    }
+                }
+            }
+            __syncthreads();
+            uint32_t *erow = E + (size_t)v * (size_t)k;
+            for (int j = tid; j < k; j += kScoreThreads)
+                if (hist[j]) atomicAdd(&erow[j], hist[j] * inc);
+            __syncthreads();
+        }
+    }
+}
+
+// One wavefront per listed row: the proposal from its (now complete) row of E, by the rule of the
+// score kernels.
+template <typename LabelT>
+__global__ __launch_bounds__(64) void k_long_propose(const LabelT *__restrict__ Lc, const long long *__restrict__ S,
+                                                     const uint32_t *__restrict__ E, LabelT *__restrict__ prop,
+                                                     int64_t chunk_lo, int k, int pass, long long P, LongRows lr) {
+    constexpr uint32_t UN = LabelTraits<LabelT>::kUnassigned;
+    const int lane = lane_id();
+    const uint32_t nlong = *lr.count;
+    for (uint32_t i = blockIdx.x; i < nlong; i += gridDim.x) {
+        const int64_t v = (int64_t)lr.list[i];
+        const uint32_t old = (uint32_t)Lc[v];
+        uint32_t best = old;
+        if (!(pass == 0 && old != UN)) {
+            unsigned long long bestkey = 0;
+            int bestj = 0x7fffffff;
+            const uint32_t *erow = E + (size_t)v * (size_t)k;
+            for (int j = lane; j < k; j += 64) {
+                const uint32_t rm = (uint32_t)(P - S[j]) + ((uint32_t)j == old ? 1u : 0u);
+                const unsigned long long key = rm ? (((unsigned long long)erow[j] << 32) | rm) : 0ull;
+                if (key > bestkey) { bestkey = key; bestj = j; }   // j ascends: first maximum kept
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const unsigned long long okey = __shfl_xor(bestkey, off);
+                const int oj = __shfl_xor(bestj, off);
+                if (okey > bestkey || (okey == bestkey && oj < bestj)) { bestkey = okey; bestj = oj; }
+            }
+            best = (uint32_t)bestj;
+        }
+        if (lane == 0) prop[v - chunk_lo] = (LabelT)best;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // score, histograms in LDS.  One workgroup owns `tv` consecutive rows (tv a power of two) and
 // walks their entries edge-parallel: consecutive lanes read consecutive colidx entries (coalesced),
 // gather the neighbour's label, find the owning row in the tile's row offsets (LDS) and add 1 to
@@ -105,8 +220,9 @@ __global__ __launch_bounds__(kScoreThreads) void k_score_lds(
     const RowT *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const LabelT *__restrict__ Lc, const long long *__restrict__ S, uint32_t *__restrict__ E,
     LabelT *__restrict__ prop, int64_t chunk_lo, int64_t chunk_hi, int k, int tv, int pass,
-    long long P, int64_t gather_limit) {
+    long long P, int64_t gather_limit, LongRows lr) {
     extern __shared__ uint32_t smem[];
+    __shared__ int s_long;
     uint32_t *hist = smem;                  // tv * k
     uint32_t *rowrel = hist + (size_t)tv * k;   // tv + 1
     uint32_t *room = rowrel + tv + 1;       // k
@@ -123,39 +239,66 @@ __global__ __launch_bounds__(kScoreThreads) void k_score_lds(
     }
     for (int i = tid; i < tv * k; i += kScoreThreads) hist[i] = 0;
     for (int j = tid; j < k; j += kScoreThreads) room[j] = (uint32_t)(P - S[j]);
+    if (tid == 0) s_long = 0;
     __syncthreads();
+    const bool any_long = note_long_rows(rowrel, nv, v0, lr, &s_long);
 
     const uint32_t ne = rowrel[tv];
     const int32_t *cbase = colidx + e0;
     constexpr int U = 4;
-    for (uint32_t base = tid; base < ne; base += kScoreThreads * U) {
-        int32_t col[U];
-        uint32_t lab[U];
+    auto count_entries = [&](uint32_t from, uint32_t to) {
+        for (uint32_t base = from + tid; base < to; base += kScoreThreads * U) {
+            int32_t col[U];
+            uint32_t lab[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            uint32_t i = base + u * kScoreThreads;
-            col[u] = (i < ne) ? __builtin_nontemporal_load(cbase + i) : -1;
-        }
+            for (int u = 0; u < U; ++u) {
+                uint32_t i = base + u * kScoreThreads;
+                col[u] = (i < to) ? __builtin_nontemporal_load(cbase + i) : -1;
+            }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            lab[u] = UN;
-            if (col[u] >= 0 && (int64_t)col[u] < gather_limit) lab[u] = (uint32_t)Lc[col[u]];
-        }
+            for (int u = 0; u < U; ++u) {
+                lab[u] = UN;
+                if (col[u] >= 0 && (int64_t)col[u] < gather_limit) lab[u] = (uint32_t)Lc[col[u]];
+            }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (lab[u] != UN) {
-                int r = owning_row(rowrel, base + u * kScoreThreads, tv);
-                atomicAdd(&hist[r * k + (int)lab[u]], 1u);
+            for (int u = 0; u < U; ++u) {
+                if (lab[u] != UN) {
+                    int r = owning_row(rowrel, base + u * kScoreThreads, tv);
+                    atomicAdd(&hist[r * k + (int)lab[u]], 1u);
+                }
             }
         }
+    };
+    if (!any_long) {
+        count_entries(0, ne);
+    } else {                                    // the stretches between the long rows
+        uint32_t from = 0;
+        for (int r = 0; r < nv; ++r) {
+            const uint32_t a = rowrel[r], b = rowrel[r + 1];
+            if (b - a >= lr.degree) { count_entries(from, a); from = b; }
+        }
+        count_entries(from, ne);
     }
     __syncthreads();
 
-    // blend: E = h (first pass) or E += h * 2^(pass-1); the blended row stays in LDS
+    // blend: E = h (first pass) or E += h * 2^(pass-1); the blended row stays in LDS.  A long row's
+    // estimates are only cleared here (first pass): k_long_rows adds its counts to them.
     {
         uint32_t *Etile = E + (size_t)v0 * (size_t)k;
         const int total = nv * k;
-        if (pass == 0) {
+        if (any_long) {
+            const int sh = pass - 1;
+            for (int i = tid; i < total; i += kScoreThreads) {
+                const int r = i / k;
+                if (rowrel[r + 1] - rowrel[r] >= lr.degree) {
+                    if (pass == 0) Etile[i] = 0u;
+                } else {
+                    const uint32_t e = pass == 0 ? hist[i] : Etile[i] + (hist[i] << sh);
+                    hist[i] = e;
+                    Etile[i] = e;
+                }
+            }
+        } else if (pass == 0) {
             for (int i = tid; i < total; i += kScoreThreads)
                 __builtin_nontemporal_store(hist[i], Etile + i);
         } else {
@@ -169,8 +312,38 @@ __global__ __launch_bounds__(kScoreThreads) void k_score_lds(
     }
     __syncthreads();
 
-    // proposal: best partition with room by (E desc, room desc, id asc)
+    // proposal: best partition with room by (E desc, room desc, id asc); a thread per vertex, or, when
+    // there are many partitions, a wavefront per vertex
+    if (k >= 64) {
+        const int lane = lane_id();
+        for (int t = tid >> 6; t < nv; t += kScoreThreads / 64) {
+            if (any_long && rowrel[t + 1] - rowrel[t] >= lr.degree) continue;     // k_long_propose's
+            const int64_t v = v0 + t;
+            const uint32_t old = (uint32_t)Lc[v];
+            uint32_t best = old;
+            if (!(pass == 0 && old != UN)) {
+                unsigned long long bestkey = 0;
+                int bestj = 0x7fffffff;
+                const uint32_t *hrow = hist + t * k;
+                for (int j = lane; j < k; j += 64) {
+                    const uint32_t rm = room[j] + ((uint32_t)j == old ? 1u : 0u);
+                    const unsigned long long key = rm ? (((unsigned long long)hrow[j] << 32) | rm) : 0ull;
+                    if (key > bestkey) { bestkey = key; bestj = j; }   // j ascends: first maximum kept
+                }
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) {
+                    const unsigned long long okey = __shfl_xor(bestkey, off);
+                    const int oj = __shfl_xor(bestj, off);
+                    if (okey > bestkey || (okey == bestkey && oj < bestj)) { bestkey = okey; bestj = oj; }
+                }
+                best = (uint32_t)bestj;
+            }
+            if (lane == 0) prop[v - chunk_lo] = (LabelT)best;
+        }
+        return;
+    }
     for (int t = tid; t < nv; t += kScoreThreads) {
+        if (any_long && rowrel[t + 1] - rowrel[t] >= lr.degree) continue;     // k_long_propose's
         const int64_t v = v0 + t;
         const uint32_t old = (uint32_t)Lc[v];
         uint32_t best = old;
@@ -205,8 +378,9 @@ __global__ __launch_bounds__(kScoreThreads) void k_score_global(
     const RowT *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const LabelT *__restrict__ Lc, const long long *__restrict__ S, uint32_t *__restrict__ E,
     LabelT *__restrict__ prop, int64_t chunk_lo, int64_t chunk_hi, int k, int pass, long long P,
-    int64_t gather_limit) {
+    int64_t gather_limit, LongRows lr) {
     extern __shared__ uint32_t smem[];
+    __shared__ int s_long;
     constexpr int tv = kGlobalTile;
     uint32_t *rowrel = smem;            // tv + 1
     uint32_t *room = rowrel + tv + 1;   // k
@@ -228,32 +402,46 @@ __global__ __launch_bounds__(kScoreThreads) void k_score_global(
         for (int i = tid; i < total; i += kScoreThreads) Etile[i] = 0u;
         __threadfence();
     }
+    if (tid == 0) s_long = 0;
     __syncthreads();
+    const bool any_long = note_long_rows(rowrel, nv, v0, lr, &s_long);
 
     const uint32_t ne = rowrel[tv];
     const int32_t *cbase = colidx + e0;
     const uint32_t inc = pass == 0 ? 1u : (1u << (pass - 1));
     constexpr int U = 4;
-    for (uint32_t base = tid; base < ne; base += kScoreThreads * U) {
-        int32_t col[U];
-        uint32_t lab[U];
+    auto count_entries = [&](uint32_t from, uint32_t to) {
+        for (uint32_t base = from + tid; base < to; base += kScoreThreads * U) {
+            int32_t col[U];
+            uint32_t lab[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            uint32_t i = base + u * kScoreThreads;
-            col[u] = (i < ne) ? __builtin_nontemporal_load(cbase + i) : -1;
-        }
+            for (int u = 0; u < U; ++u) {
+                uint32_t i = base + u * kScoreThreads;
+                col[u] = (i < to) ? __builtin_nontemporal_load(cbase + i) : -1;
+            }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            lab[u] = UN;
-            if (col[u] >= 0 && (int64_t)col[u] < gather_limit) lab[u] = (uint32_t)Lc[col[u]];
-        }
+            for (int u = 0; u < U; ++u) {
+                lab[u] = UN;
+                if (col[u] >= 0 && (int64_t)col[u] < gather_limit) lab[u] = (uint32_t)Lc[col[u]];
+            }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (lab[u] != UN) {
-                int r = owning_row(rowrel, base + u * kScoreThreads, tv);
-                atomicAdd(&Etile[(size_t)r * k + lab[u]], inc);
+            for (int u = 0; u < U; ++u) {
+                if (lab[u] != UN) {
+                    int r = owning_row(rowrel, base + u * kScoreThreads, tv);
+                    atomicAdd(&Etile[(size_t)r * k + lab[u]], inc);
+                }
             }
         }
+    };
+    if (!any_long) {
+        count_entries(0, ne);
+    } else {                                    // the stretches between the long rows
+        uint32_t from = 0;
+        for (int r = 0; r < nv; ++r) {
+            const uint32_t a = rowrel[r], b = rowrel[r + 1];
+            if (b - a >= lr.degree) { count_entries(from, a); from = b; }
+        }
+        count_entries(from, ne);
     }
     __threadfence();
     __syncthreads();
@@ -262,6 +450,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_score_global(
     const int wave = tid >> 6;
     constexpr int nwaves = kScoreThreads / 64;
     for (int t = wave; t < nv; t += nwaves) {
+        if (any_long && rowrel[t + 1] - rowrel[t] >= lr.degree) continue;     // k_long_propose's
         const int64_t v = v0 + t;
         const uint32_t old = (uint32_t)Lc[v];
         uint32_t best = old;

@@ -486,7 +486,7 @@ __device__ __host__ inline size_t tp_source_words(bool share, int np, int share_
 // in LDS and written as one contiguous piece (a lane-by-lane scatter would cost one L2 request per
 // tuple); a unit with more than `cap` tuples writes them one by one instead.
 // U tuple: row field << (cb + gb) | block in group << cb | column in block.
-// LDS: the entry source's tables, cntf[nblk], cg[ngroups + 1], cur[ngroups], stage[cap]
+// LDS: the entry source's tables, cntf[nblk], cg[ngroups + 1], wtot[kTpThreads / 64], stage[cap]
 // ------------------------------------------------------------------------------------------------
 template <typename RowT, bool SHARE>
 __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tp_group(const RowT *__restrict__ rowptr,
@@ -497,9 +497,9 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
     extern __shared__ u64 smem64[];
     const int np = SHARE ? tb.nps : tb.npr;
     uint32_t *cntf = reinterpret_cast<uint32_t *>(smem64) + tp_source_words(SHARE, np, share_hubs);   // nblk
-    uint32_t *cg = cntf + tb.nblk;              // ngroups + 1: tuples per group, then starts
-    uint32_t *cur = cg + tb.ngroups + 1;        // ngroups: next free slot of the group
-    uint32_t *stage = cur + tb.ngroups;         // cap
+    uint32_t *cg = cntf + tb.nblk;              // ngroups + 1: starts of the groups' runs
+    uint32_t *wtot = cg + tb.ngroups + 1;       // kTpThreads / 64: scratch of the prefix sum
+    uint32_t *stage = wtot + kTpThreads / 64;   // cap
     const int tid = threadIdx.x;
     const unsigned gs = blockIdx.x / (unsigned)np;
     const int q = (int)(blockIdx.x % (unsigned)np);
@@ -526,43 +526,43 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
         }
     }
     __syncthreads();
-    // tuples per group -> starts: one wavefront (a lane per group) while the others add the unit's
-    // counts to the slice's
-    if (tb.ngroups <= 64) {
-        if (tid < 64) {
-            uint32_t mine = 0;
-            if (tid < tb.ngroups) {
-                const int j0 = tid << tb.gb;
-                const int j1 = (j0 + (1 << tb.gb)) < tb.nblk ? j0 + (1 << tb.gb) : tb.nblk;
-                for (int j = j0; j < j1; ++j) mine += cntf[j];
-            }
-            uint32_t inc = mine;
+    // counts -> starts (cntf becomes the blocks' cursors: inside a group's run the tuples end up
+    // ordered by block, and neighbouring threads seldom meet on a cursor); a thread takes
+    // kMaxBlocks / kTpThreads consecutive blocks
+    {
+        constexpr int kPer = kMaxBlocks / kTpThreads;
+        const int lane = lane_id(), wave = tid >> 6;
+        uint32_t *row_out = (SHARE ? tb.subH : tb.subR) + ((size_t)c * (tb.nsl + 1) + i) * tb.nblk;
+        uint32_t mine[kPer], sum = 0;
 #pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const uint32_t o = __shfl_up(inc, off);
-                if (tid >= off) inc += o;
-            }
-            if (tid < tb.ngroups) { cg[tid] = inc - mine; cur[tid] = inc - mine; }
-            if (tid == tb.ngroups - 1) cg[tb.ngroups] = inc;
+        for (int x = 0; x < kPer; ++x) {
+            const int j = tid * kPer + x;
+            mine[x] = j < tb.nblk ? cntf[j] : 0u;
+            if (mine[x]) atomicAdd(&row_out[j], mine[x]);
+            sum += mine[x];
         }
-    } else {
-        for (int gq = tid; gq < tb.ngroups; gq += kTpThreads) {
-            const int j0 = gq << tb.gb;
-            const int j1 = (j0 + (1 << tb.gb)) < tb.nblk ? j0 + (1 << tb.gb) : tb.nblk;
-            uint32_t sum = 0;
-            for (int j = j0; j < j1; ++j) sum += cntf[j];
-            cg[gq] = sum;
+        uint32_t inc = sum;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t o = __shfl_up(inc, off);
+            if (lane >= off) inc += o;
         }
+        if (lane == 63) wtot[wave] = inc;
         __syncthreads();
-        if (tid == 0) {
-            uint32_t run = 0;
-            for (int gq = 0; gq < tb.ngroups; ++gq) { const uint32_t t = cg[gq]; cg[gq] = run; cur[gq] = run; run += t; }
-            cg[tb.ngroups] = run;
+        uint32_t run = inc - sum;
+        for (int w = 0; w < wave; ++w) run += wtot[w];
+        const uint32_t gmask0 = (1u << tb.gb) - 1u;
+#pragma unroll
+        for (int x = 0; x < kPer; ++x) {
+            const int j = tid * kPer + x;
+            if (j < tb.nblk) {
+                cntf[j] = run;
+                if (((uint32_t)j & gmask0) == 0) cg[j >> tb.gb] = run;
+            }
+            run += mine[x];
         }
+        if (tid == kTpThreads - 1) cg[tb.ngroups] = run;
     }
-    uint32_t *row_out = (SHARE ? tb.subH : tb.subR) + ((size_t)c * (tb.nsl + 1) + i) * tb.nblk;
-    for (int j = tid; j < tb.nblk; j += kTpThreads)
-        if (cntf[j]) atomicAdd(&row_out[j], cntf[j]);
     __syncthreads();
     for (int gq = tid; gq <= tb.ngroups; gq += kTpThreads) lo_out[gq] = cg[gq];
     const uint32_t total = cg[tb.ngroups];
@@ -577,7 +577,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
             uint32_t low;
             const uint32_t jb = tp_block_of(col[u], tb, &low);
             tuple[u] = (row[u] << (tb.cb + tb.gb)) | ((jb & gmask) << tb.cb) | low;
-            w[u] = on[u] ? atomicAdd(&cur[jb >> tb.gb], 1u) : 0u;
+            w[u] = on[u] ? atomicAdd(&cntf[jb], 1u) : 0u;
         }
 #pragma unroll
         for (int u = 0; u < kTpBatch; ++u) {

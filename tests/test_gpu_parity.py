@@ -24,7 +24,8 @@ def _to_dev(g, rowptr_dtype=None):
     return rp.to(DEV), torch.as_tensor(np.asarray(g.colidx)).to(DEV)
 
 
-def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO, tag="", col_bits=0, hub_degree=2048):
+def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO, tag="", col_bits=0, hub_degree=2048,
+           long_row_degree=0):
     """Runs both sides on the same graph and compares everything."""
     g = synth.to_numpy(g)
     print(f"[case] {tag} {g.name} n={g.n} nnz={g.nnz} k={k} slack={slack} chunk={chunk} R={R} "
@@ -34,6 +35,7 @@ def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO
     B.grem_set_histogram_mode(mode)
     B.grem_set_sweep_col_bits(col_bits)
     B.grem_set_sweep_hub_degree(hub_degree)
+    B.grem_set_long_row_degree(long_row_degree)
     try:
         lab, sizes, est = B.grem_partition_state(rp, ci, g.n, k, slack, chunk, R, seed_d)
         cut = B.grem_edge_cut(rp, ci, g.n, lab)
@@ -42,6 +44,7 @@ def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO
         B.grem_set_histogram_mode(B.HIST_AUTO)
         B.grem_set_sweep_col_bits(0)
         B.grem_set_sweep_hub_degree(2048)
+        B.grem_set_long_row_degree(0)
     olab, osizes, oest = oracle.partition_seeded(g.rowptr, g.colidx, g.n, k, slack, chunk, R, seed,
                                                  return_state=True)
     lab_h = lab.cpu().numpy()
@@ -109,7 +112,7 @@ def test_edgeless_graph(n, k, slack, chunk):
     _check(g, k, slack, chunk, 2)
 
 
-@pytest.mark.parametrize("k", [2, 5, 16, 17, 32, 33, 64, 100, 128, 129, 255, 256, 300, 1000])
+@pytest.mark.parametrize("k", [2, 5, 16, 17, 32, 33, 63, 64, 100, 128, 129, 255, 256, 300, 1000, 1024, 1025, 3000])
 def test_many_k(k):
     g = synth.rmat(13, 16, seed=2, rowptr_dtype=torch.int64)
     _check(g, k, 1.05, 1000, 2)
@@ -183,6 +186,24 @@ def test_hubs():
     g = synth.hub_stress(scale=13, edge_factor=8, hubs=4, hub_degree=5000, seed=0, rowptr_dtype=torch.int32)
     _check(g, 16, 1.1, 1024, 2)
     _check(g, 256, 1.1, 1024, 2)
+
+
+def test_long_rows_get_a_grid_of_their_own():
+    # plain score kernels (histograms in LDS, then in E's rows), long rows split off at several thresholds
+    g = synth.hub_stress(scale=13, edge_factor=8, hubs=4, hub_degree=5000, seed=0, rowptr_dtype=torch.int32)
+    _check(g, 16, 1.1, 1024, 2, mode=B.HIST_LDS, long_row_degree=1000, tag="4 long rows")
+    _check(g, 256, 1.1, 1024, 2, long_row_degree=1000, tag="4 long rows, k=256")
+    _check(g, 16, 1.1, 3000, 2, mode=B.HIST_LDS, long_row_degree=40, tag="many long rows")
+    _check(g, 200, 1.1, 3000, 3, mode=B.HIST_GLOBAL, long_row_degree=40, rowptr_dtype=torch.int64,
+           tag="many long rows, global")
+    _check(g, 5, 1.0, 777, 1, mode=B.HIST_LDS, long_row_degree=1, tag="every non-empty row long")
+    rng = np.random.default_rng(3)
+    seed = np.where(rng.random(g.n) < 0.4, rng.integers(0, 6, g.n), -1).astype(np.int32)
+    _check(g, 6, 1.3, 2048, 2, seed=seed, mode=B.HIST_LDS, long_row_degree=64, tag="seeded, long rows")
+    # default threshold: two rows of 100,000 entries, many parts each
+    h = synth.hub_stress(scale=17, edge_factor=4, hubs=2, hub_degree=100_000, seed=1, rowptr_dtype=torch.int64)
+    _check(h, 16, 1.1, 1 << 15, 2, mode=B.HIST_LDS, tag="default threshold")
+    _check(h, 300, 1.1, 1 << 15, 1, tag="default threshold, k=300")
 
 
 def test_seeded_everything_and_partial():
