@@ -1,0 +1,113 @@
+"""Full-size checks of the high-k skew workload (R-MAT scale 24 plus 64 rows of 2,000,000 entries,
+0.78e9 CSR entries, k=256, chunk 262,144, 3 refinement passes).  As for the bench workload:
+  * refine_passes = 0: the labels and estimates of the first chunks are final after pass 0 and depend
+    only on those chunks' rows; they are compared element by element with the oracle stepped over the
+    same prefix (which holds at least one of the long rows);
+  * the whole 4-pass run is checked through properties that hold at any size, and three independent
+    routes must agree bit for bit: LDS histograms with long rows split off, the same with nothing split
+    off, and histograms in E's rows;
+  * the complete 4-pass run is replayed on the oracle and every label compared."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_17846_amd import binding as B
+from paper_2502_17846_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+K, SLACK, CHUNK, R = 256, 1.10, 262_144, 3
+HUB_DEGREE = 2_000_000
+
+
+@pytest.fixture(scope="module")
+def graph():
+    g = synth.hub_stress(24, 16, hubs=64, hub_degree=HUB_DEGREE, seed=0, device=DEV, rowptr_dtype=torch.int32)
+    ws = torch.empty(B.grem_workspace_bytes(g.n, g.nnz, K, CHUNK), dtype=torch.uint8, device=DEV)
+    B.grem_set_workspace(ws)
+    yield g
+    B.grem_set_workspace(None)
+    B.grem_set_histogram_mode(B.HIST_AUTO)
+    B.grem_set_long_row_degree(0)
+
+
+def test_first_chunks_of_pass0_equal_the_oracle(graph):
+    g = graph
+    deg = (g.rowptr[1:] - g.rowptr[:-1])
+    long_rows = torch.nonzero(deg >= HUB_DEGREE).flatten()
+    assert long_rows.numel() == 64
+    # enough chunks to hold the first long row (and at least 2)
+    chunks = max(2, int(long_rows.min().item()) // CHUNK + 1)
+    chunks = min(chunks, 6)
+    rows = chunks * CHUNK
+    print(f"[case] hub workload prefix parity, {chunks} chunks, long rows in it: "
+          f"{int((long_rows < rows).sum())}", flush=True)
+    end = int(g.rowptr[rows].item())
+    rp = g.rowptr.cpu().numpy().copy()
+    rp[rows:] = end
+    ci = g.colidx[:end].cpu().numpy()
+    st = oracle.Stepper(rp, ci, g.n, K, SLACK, CHUNK, 0)
+    for _ in range(chunks):
+        st.step()
+    olab, oest = st.labels()[:rows].copy(), st.estimates()[:rows].copy()
+    st.close()
+    for mode, long_deg in ((B.HIST_AUTO, 0), (B.HIST_GLOBAL, 0)):
+        B.grem_set_histogram_mode(mode)
+        B.grem_set_long_row_degree(long_deg)
+        lab, sizes, est = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(lab[:rows].cpu().numpy(), olab), f"mode {mode}"
+        assert np.array_equal(est[:rows].cpu().numpy().view(np.uint32), oest), f"mode {mode}"
+        del lab, sizes, est
+    B.grem_set_histogram_mode(B.HIST_AUTO)
+
+
+def test_four_pass_run_properties_and_route_agreement(graph):
+    g = graph
+    P = B.grem_capacity(g.n, K, SLACK)
+    assert P == oracle.capacity(g.n, K, SLACK) == 72_090
+    outs = []
+    for mode, long_deg, what in ((B.HIST_AUTO, 0, "LDS histograms, long rows split off"),
+                                 (B.HIST_AUTO, 2**31 - 1, "LDS histograms, nothing split off"),
+                                 (B.HIST_GLOBAL, 0, "histograms in E's rows")):
+        print(f"[case] hub workload 4-pass run: {what}", flush=True)
+        B.grem_set_histogram_mode(mode)
+        B.grem_set_long_row_degree(long_deg)
+        lab, sizes, _ = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, R, want_estimates=False)
+        cut = B.grem_edge_cut(g.rowptr, g.colidx, g.n, lab)
+        torch.cuda.synchronize()
+        assert int(lab.min()) >= 0 and int(lab.max()) < K
+        cnt = torch.bincount(lab, minlength=K)
+        assert torch.equal(cnt, sizes) and int(cnt.max()) <= P and int(cnt.sum()) == g.n
+        outs.append((lab, int(cut.item())))
+    B.grem_set_histogram_mode(B.HIST_AUTO)
+    B.grem_set_long_row_degree(0)
+    assert torch.equal(outs[0][0], outs[1][0])
+    assert torch.equal(outs[0][0], outs[2][0])
+    assert outs[0][1] == outs[1][1] == outs[2][1]
+    # independent count of the cut
+    lab = outs[0][0]
+    deg = (g.rowptr[1:] - g.rowptr[:-1]).to(torch.int64)
+    src_lab = torch.repeat_interleave(lab, deg)
+    cut_t = int((src_lab != lab[g.colidx.long()]).sum().item())
+    assert cut_t == outs[0][1]
+    assert cut_t / g.nnz < 255 / 256        # better than a random 256-way split
+
+
+def test_whole_run_equals_the_oracle(graph):
+    # about half a minute of single-thread oracle time
+    g = graph
+    rp, ci = g.rowptr.cpu().numpy(), g.colidx.cpu().numpy()
+    print("[case] hub workload whole-run oracle replay", flush=True)
+    st = oracle.Stepper(rp, ci, g.n, K, SLACK, CHUNK, R)
+    steps = 0
+    while st.step():
+        steps += 1
+        if steps % 16 == 0:
+            print(f"[oracle] {steps} chunk steps", flush=True)
+    olab = st.labels().copy()
+    st.close()
+    lab = B.grem_partition(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, R)
+    torch.cuda.synchronize()
+    assert np.array_equal(lab.cpu().numpy(), olab)
