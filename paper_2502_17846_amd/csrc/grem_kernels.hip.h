@@ -121,29 +121,54 @@ __device__ __forceinline__ bool note_long_rows(const uint32_t *rowrel, int nv, i
 
 // Adds the neighbour-label counts of the listed rows, times 2^(pass-1) (1 in the first pass), to
 // their rows of E with integer atomics; the counts of one part are collected in LDS first (k
-// words).  Parts are dealt out round-robin over the workgroups across all listed rows.
+// words).  The parts of all listed rows, numbered in list order, are dealt out round-robin over
+// the workgroups; the list is taken kScoreThreads rows at a time (a thread per row works out its
+// number of parts, a prefix sum tells every workgroup which parts of the batch are its own).
 template <typename RowT, typename LabelT>
 __global__ __launch_bounds__(kScoreThreads) void k_long_rows(
     const RowT *__restrict__ rowptr, const int32_t *__restrict__ colidx, const LabelT *__restrict__ Lc,
     uint32_t *__restrict__ E, int k, int pass, int64_t gather_limit, LongRows lr) {
     extern __shared__ uint32_t smem[];
     uint32_t *hist = smem;                  // k
+    __shared__ uint32_t s_pre[kScoreThreads + 1];
+    __shared__ uint32_t s_wtot[kScoreThreads / 64];
     constexpr uint32_t UN = LabelTraits<LabelT>::kUnassigned;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const uint32_t nlong = *lr.count;
     const uint32_t inc = pass == 0 ? 1u : (1u << (pass - 1));
     constexpr int U = 4;
-    unsigned long long dealt = 0;           // parts of the rows before this one
-    for (uint32_t i = 0; i < nlong; ++i) {
-        const int64_t v = (int64_t)lr.list[i];
-        const int64_t e0 = (int64_t)rowptr[v];
-        const uint32_t deg = (uint32_t)((int64_t)rowptr[v + 1] - e0);
-        const uint32_t nparts = (deg + lr.part - 1) / lr.part;
-        // first part of this row that falls to this workgroup
-        uint32_t q = (uint32_t)((blockIdx.x + gridDim.x - (uint32_t)(dealt % gridDim.x)) % gridDim.x);
-        dealt += nparts;
-        const int32_t *cbase = colidx + e0;
-        for (; q < nparts; q += gridDim.x) {
+    unsigned long long dealt = 0;           // parts of the batches before this one
+    for (uint32_t i0 = 0; i0 < nlong; i0 += kScoreThreads) {
+        uint32_t mine = 0;
+        if (i0 + tid < nlong) {
+            const int64_t v = (int64_t)lr.list[i0 + tid];
+            const uint32_t deg = (uint32_t)((int64_t)rowptr[v + 1] - (int64_t)rowptr[v]);
+            mine = (deg + lr.part - 1) / lr.part;
+        }
+        uint32_t run = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t o = __shfl_up(run, off);
+            if (lane >= off) run += o;
+        }
+        if (lane == 63) s_wtot[wave] = run;
+        __syncthreads();
+        for (int w = 0; w < wave; ++w) run += s_wtot[w];
+        s_pre[tid] = run - mine;
+        if (tid == kScoreThreads - 1) s_pre[kScoreThreads] = run;
+        __syncthreads();
+        const uint32_t batch_parts = s_pre[kScoreThreads];
+        // first part of this batch that falls to this workgroup
+        uint32_t x = (uint32_t)((blockIdx.x + gridDim.x - (uint32_t)(dealt % gridDim.x)) % gridDim.x);
+        for (; x < batch_parts; x += gridDim.x) {
+            int r = 0;                      // largest r with s_pre[r] <= x
+            for (int step = kScoreThreads >> 1; step >= 1; step >>= 1)
+                if (s_pre[r + step] <= x) r += step;
+            const uint32_t q = x - s_pre[r];
+            const int64_t v = (int64_t)lr.list[i0 + r];
+            const int64_t e0 = (int64_t)rowptr[v];
+            const uint32_t deg = (uint32_t)((int64_t)rowptr[v + 1] - e0);
+            const int32_t *cbase = colidx + e0;
             for (int j = tid; j < k; j += kScoreThreads) hist[j] = 0;
             __syncthreads();
             const uint32_t from = q * lr.part;
@@ -169,6 +194,8 @@ __global__ __launch_bounds__(kScoreThreads) void k_long_rows(
                 if (hist[j]) atomicAdd(&erow[j], hist[j] * inc);
             __syncthreads();
         }
+        dealt += batch_parts;
+        __syncthreads();                    // s_pre is rewritten by the next batch
     }
 }
 

@@ -131,6 +131,7 @@ def random_graph_np(n: int, m: int, seed: int, rowptr_dtype=np.int64, simple: bo
 # --------------------------------------------------------------------------------------------
 
 _BLOCK_ENTRIES = 1 << 27   # target entries per sorted block (torch.sort takes < 2^31 elements)
+_SEGMENT = 1 << 30         # samples per boolean-mask / index operation
 
 
 def csr_from_samples(src: torch.Tensor, dst: torch.Tensor, n: int, rowptr_dtype=torch.int64,
@@ -148,11 +149,18 @@ def csr_from_samples(src: torch.Tensor, dst: torch.Tensor, n: int, rowptr_dtype=
         hi = min(n, lo + rows_per_block)
         if lo >= hi:
             break
-        m1 = (src >= lo) & (src < hi)
-        m2 = (dst >= lo) & (dst < hi)
-        rows = torch.cat([src[m1], dst[m2]]).to(torch.int64)
-        cols = torch.cat([dst[m1], src[m2]]).to(torch.int64)
-        del m1, m2
+        # masks over at most _SEGMENT samples at a time (boolean indexing of longer tensors overflows)
+        rparts, cparts = [], []
+        for s0 in range(0, M, _SEGMENT):
+            ss, dd = src[s0:s0 + _SEGMENT], dst[s0:s0 + _SEGMENT]
+            m1 = (ss >= lo) & (ss < hi)
+            m2 = (dd >= lo) & (dd < hi)
+            rparts += [ss[m1], dd[m2]]
+            cparts += [dd[m1], ss[m2]]
+            del m1, m2
+        rows = torch.cat(rparts).to(torch.int64)
+        cols = torch.cat(cparts).to(torch.int64)
+        del rparts, cparts
         keep = rows != cols
         key = ((rows[keep] - lo) << 32) | cols[keep]
         del rows, cols, keep
@@ -202,8 +210,9 @@ def rmat(scale: int, edge_factor: int = 16, abcd=(0.57, 0.19, 0.19, 0.05), seed:
     gen.manual_seed(seed)
     src, dst = _rmat_samples(scale, m, abcd, gen, device)
     perm = _permutation(n, gen, device)
-    src = perm[src.long()]
-    dst = perm[dst.long()]
+    for s0 in range(0, m, _SEGMENT):
+        src[s0:s0 + _SEGMENT] = perm[src[s0:s0 + _SEGMENT].long()]
+        dst[s0:s0 + _SEGMENT] = perm[dst[s0:s0 + _SEGMENT].long()]
     rowptr, colidx = csr_from_samples(src, dst, n, rowptr_dtype)
     return Graph(rowptr, colidx, n, int(colidx.numel()), m, None,
                  f"rmat scale={scale} ef={edge_factor} seed={seed}")

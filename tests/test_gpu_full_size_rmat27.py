@@ -1,0 +1,73 @@
+"""Full-size checks of the R-MAT scale 27 workload (134M vertices, 8.4e9 CSR entries, int64 rowptr,
+k=32, slack 1.03, chunk 2^22, 1 refinement pass): the largest graph of the set, more than 2^32 entries.
+  * refine_passes = 0: labels and estimates of the first chunk are final after pass 0 and depend only on
+    that chunk's rows; they are compared element by element with the oracle stepped over the same prefix;
+  * the 2-pass run is checked through properties that hold at any size, and two routes must agree bit
+    for bit: LDS histograms with long rows split off, and histograms in E's rows with nothing split off."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_17846_amd import binding as B
+from paper_2502_17846_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+K, SLACK, CHUNK, R = 32, 1.03, 1 << 22, 1
+
+
+@pytest.fixture(scope="module")
+def graph():
+    g = synth.rmat(27, 32, seed=0, device=DEV, rowptr_dtype=torch.int64)
+    ws = torch.empty(B.grem_workspace_bytes(g.n, g.nnz, K, CHUNK), dtype=torch.uint8, device=DEV)
+    B.grem_set_workspace(ws)
+    yield g
+    B.grem_set_workspace(None)
+    B.grem_set_histogram_mode(B.HIST_AUTO)
+    B.grem_set_long_row_degree(0)
+
+
+def test_first_chunk_of_pass0_equals_the_oracle(graph):
+    g = graph
+    assert g.nnz > 2**32
+    rows = CHUNK
+    end = int(g.rowptr[rows].item())
+    deg = g.rowptr[1:rows + 1] - g.rowptr[:rows]
+    print(f"[case] rmat-27 prefix parity, 1 chunk, {end} entries, rows of >= 16384 entries in it: "
+          f"{int((deg >= 16384).sum())}", flush=True)
+    rp = g.rowptr.cpu().numpy().copy()
+    rp[rows:] = end
+    ci = g.colidx[:end].cpu().numpy()
+    st = oracle.Stepper(rp, ci, g.n, K, SLACK, CHUNK, 0)
+    st.step()
+    olab, oest = st.labels()[:rows].copy(), st.estimates()[:rows].copy()
+    st.close()
+    lab, sizes, est = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(lab[:rows].cpu().numpy(), olab)
+    assert np.array_equal(est[:rows].cpu().numpy().view(np.uint32), oest)
+
+
+def test_two_pass_run_properties_and_route_agreement(graph):
+    g = graph
+    P = B.grem_capacity(g.n, K, SLACK)
+    assert P == oracle.capacity(g.n, K, SLACK) == 4_320_134
+    outs = []
+    for mode, long_deg, what in ((B.HIST_AUTO, 0, "LDS histograms, long rows split off"),
+                                 (B.HIST_GLOBAL, 2**31 - 1, "histograms in E's rows, nothing split off")):
+        print(f"[case] rmat-27 2-pass run: {what}", flush=True)
+        B.grem_set_histogram_mode(mode)
+        B.grem_set_long_row_degree(long_deg)
+        lab, sizes, _ = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, R, want_estimates=False)
+        cut = B.grem_edge_cut(g.rowptr, g.colidx, g.n, lab)
+        torch.cuda.synchronize()
+        assert int(lab.min()) >= 0 and int(lab.max()) < K
+        cnt = torch.bincount(lab, minlength=K)
+        assert torch.equal(cnt, sizes) and int(cnt.max()) <= P and int(cnt.sum()) == g.n
+        outs.append((lab, int(cut.item())))
+    B.grem_set_histogram_mode(B.HIST_AUTO)
+    B.grem_set_long_row_degree(0)
+    assert torch.equal(outs[0][0], outs[1][0])
+    assert outs[0][1] == outs[1][1]
+    assert outs[0][1] / g.nnz < 31 / 32         # better than a random 32-way split
