@@ -921,49 +921,72 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
 // two entries at offset 2i of each, round after round, all NB loads of a round in flight together.
 // COUNT16: regular rows, 16-bit counters, index = entry; else hub share, 32-bit counters, index =
 // hub * k + label.  Entries with bit 15 set are ignored.
-template <bool COUNT16, int NB>
-__device__ __forceinline__ void tp_count_group(const uint32_t *__restrict__ Xc32, const uint32_t (&s)[NB],
-                                               const uint32_t (&l)[NB], int lane, int k, uint32_t *hist) {
-    uint32_t mx = 0;
+// Counting the entries of sub-segments of X.  A sub-segment holds some 70 entries, so a whole
+// wavefront on one of them would leave half its lanes idle: a QUARTER of the wavefront takes one,
+// six entries (three dwords) per lane, which covers 96 entries at once; longer ones take further
+// turns.  x < 0x8000: entry (row field << 4 | label) is counted; else it is padding or an
+// unassigned neighbour.
+typedef uint32_t u32x3a __attribute__((ext_vector_type(3), aligned(4)));
+
+template <bool COUNT16>
+__device__ __forceinline__ void tp_count_dword(uint32_t w, int k, uint32_t *hist) {
 #pragma unroll
-    for (int b = 0; b < NB; ++b) mx = l[b] > mx ? l[b] : mx;
-    for (uint32_t r = 0; r < mx; r += 128) {
-        const uint32_t off = r + 2u * (uint32_t)lane;
-        uint32_t w[NB];
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-            w[b] = off < l[b] ? __builtin_nontemporal_load(Xc32 + ((s[b] + off) >> 1)) : 0x80008000u;
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t x = h == 0 ? (w[b] & 0xFFFFu) : (w[b] >> 16);
-                if (x < 0x8000u) {
-                    if (COUNT16) atomicAdd(&hist[x >> 1], 1u << ((x & 1u) << 4));
-                    else atomicAdd(&hist[(x >> 4) * (uint32_t)k + (x & 15u)], 1u);
-                }
-            }
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t x = h == 0 ? (w & 0xFFFFu) : (w >> 16);
+        if (x < 0x8000u) {
+            if (COUNT16) atomicAdd(&hist[x >> 1], 1u << ((x & 1u) << 4));
+            else atomicAdd(&hist[(x >> 4) * (uint32_t)k + (x & 15u)], 1u);
         }
     }
 }
 
-// The sub-segments a wavefront owns, NB at a time: lane t of (s0, l0) holds start and length of
-// the t-th of them, t < tmax <= 64.
-template <bool COUNT16, int NB>
+// three dwords of a sub-segment of `len` entries from entry `off` (a multiple of 6) on; dwords past
+// the end read as padding.  The load may reach 8 bytes past the sub-segment: X has that much slack.
+__device__ __forceinline__ u32x3a tp_load_six(const uint32_t *__restrict__ Xc32, uint32_t start, uint32_t off,
+                                              uint32_t len) {
+    u32x3a w = {0x80008000u, 0x80008000u, 0x80008000u};
+    if (off < len) {
+        w = __builtin_nontemporal_load(reinterpret_cast<const u32x3a *>(Xc32 + ((start + off) >> 1)));
+        const uint32_t rem = len - off;         // even
+        if (rem <= 2) w.y = 0x80008000u;
+        if (rem <= 4) w.z = 0x80008000u;
+    }
+    return w;
+}
+
+// The sub-segments a wavefront owns, 4 * NBQ at a time: lane t of (s0, l0) holds start and length
+// (both even) of the t-th of them, t < tmax <= 64.
+template <bool COUNT16, int NBQ>
 __device__ __forceinline__ void tp_count_list(const uint32_t *__restrict__ Xc32, uint32_t s0, uint32_t l0,
                                               int tmax, int lane, int k, uint32_t *hist) {
-    for (int t = 0; t < tmax; t += NB) {
-        uint32_t s[NB], l[NB];
+    const int quarter = lane >> 4;
+    const uint32_t off = 6u * (uint32_t)(lane & 15);
+    for (int t = 0; t < tmax; t += 4 * NBQ) {
+        uint32_t st[NBQ], ln[NBQ];
+        u32x3a w[NBQ];
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            s[b] = 0;
-            l[b] = 0;
-            if (t + b < tmax) {
-                s[b] = (uint32_t)__builtin_amdgcn_readlane((int)s0, t + b);
-                l[b] = (uint32_t)__builtin_amdgcn_readlane((int)l0, t + b);
+        for (int b = 0; b < NBQ; ++b) {
+            const int tq = t + 4 * b + quarter;
+            st[b] = (uint32_t)__shfl((int)s0, tq & 63);
+            ln[b] = (uint32_t)__shfl((int)l0, tq & 63);
+            if (tq >= tmax) ln[b] = 0;
+            w[b] = tp_load_six(Xc32, st[b], off, ln[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < NBQ; ++b) {
+            tp_count_dword<COUNT16>(w[b].x, k, hist);
+            tp_count_dword<COUNT16>(w[b].y, k, hist);
+            tp_count_dword<COUNT16>(w[b].z, k, hist);
+        }
+#pragma unroll
+        for (int b = 0; b < NBQ; ++b) {         // the rare sub-segment of more than 96 entries
+            for (uint32_t r = 96; __any(r < ln[b]); r += 96) {
+                const u32x3a v = tp_load_six(Xc32, st[b], r + off, ln[b]);
+                tp_count_dword<COUNT16>(v.x, k, hist);
+                tp_count_dword<COUNT16>(v.y, k, hist);
+                tp_count_dword<COUNT16>(v.z, k, hist);
             }
         }
-        tp_count_group<COUNT16, NB>(Xc32, s, l, lane, k, hist);
     }
 }
 
@@ -1072,7 +1095,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
             }
             int tmax = (jlim - base - wave + NW - 1) / NW;      // blocks of this wave in this round
             if (tmax > 64) tmax = 64;
-            tp_count_list<true, 8>(Xc32, s0, l0, tmax, lane, k, hist);
+            tp_count_list<true, 4>(Xc32, s0, l0, tmax, lane, k, hist);
         }
     }
     if (any_hub) {
@@ -1081,7 +1104,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
             if (base > 0) tp_hub_offsets(tb, xs, xs0, hq0, cls, ncls, mlim, base + wave + NW * lane, &s0, &l0);
             int tmax = (mlim - base - wave + NW - 1) / NW;
             if (tmax > 64) tmax = 64;
-            tp_count_list<false, 8>(Xc32, s0, l0, tmax, lane, k, hhist);
+            tp_count_list<false, 2>(Xc32, s0, l0, tmax, lane, k, hhist);
         }
     }
     __syncthreads();
