@@ -929,33 +929,37 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
 typedef uint32_t u32x3a __attribute__((ext_vector_type(3), aligned(4)));
 
 template <bool COUNT16>
-__device__ __forceinline__ void tp_count_dword(uint32_t w, int k, uint32_t *hist) {
+__device__ __forceinline__ void tp_count_dword(uint32_t w, bool valid, int k, uint32_t *hist) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const uint32_t x = h == 0 ? (w & 0xFFFFu) : (w >> 16);
-        if (x < 0x8000u) {
-            if (COUNT16) atomicAdd(&hist[x >> 1], 1u << ((x & 1u) << 4));
-            else atomicAdd(&hist[(x >> 4) * (uint32_t)k + (x & 15u)], 1u);
+        if (COUNT16) {
+            // no branch: what is not to be counted adds zero (to a counter its bits happen to name)
+            const uint32_t one = (valid && x < 0x8000u) ? 1u : 0u;
+            atomicAdd(&hist[(x >> 1) & 0x3FFFu], one << ((x & 1u) << 4));
+        } else if (valid && x < 0x8000u) {
+            atomicAdd(&hist[(x >> 4) * (uint32_t)k + (x & 15u)], 1u);
         }
     }
 }
 
-// three dwords of a sub-segment of `len` entries from entry `off` (a multiple of 6) on; dwords past
-// the end read as padding.  The load may reach 8 bytes past the sub-segment: X has that much slack.
-__device__ __forceinline__ u32x3a tp_load_six(const uint32_t *__restrict__ Xc32, uint32_t start, uint32_t off,
-                                              uint32_t len) {
-    u32x3a w = {0x80008000u, 0x80008000u, 0x80008000u};
-    if (off < len) {
-        w = __builtin_nontemporal_load(reinterpret_cast<const u32x3a *>(Xc32 + ((start + off) >> 1)));
-        const uint32_t rem = len - off;         // even
-        if (rem <= 2) w.y = 0x80008000u;
-        if (rem <= 4) w.z = 0x80008000u;
-    }
-    return w;
+// The six entries (three dwords) of a sub-segment of `len` entries from entry `off` (a multiple of
+// 6, below len) on.  The load may reach 8 bytes past the sub-segment: X has that much slack; what
+// lies past the end is not counted.
+__device__ __forceinline__ u32x3a tp_load_six(const uint32_t *__restrict__ Xc32, uint32_t start, uint32_t off) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x3a *>(Xc32 + ((start + off) >> 1)));
+}
+
+template <bool COUNT16>
+__device__ __forceinline__ void tp_count_six(const u32x3a &w, uint32_t rem, int k, uint32_t *hist) {
+    tp_count_dword<COUNT16>(w.x, true, k, hist);
+    tp_count_dword<COUNT16>(w.y, rem > 2, k, hist);
+    tp_count_dword<COUNT16>(w.z, rem > 4, k, hist);
 }
 
 // The sub-segments a wavefront owns, 4 * NBQ at a time: lane t of (s0, l0) holds start and length
-// (both even) of the t-th of them, t < tmax <= 64.
+// (both even) of the t-th of them, t < tmax <= 64.  All loads of a turn are issued before the first
+// entry is counted.
 template <bool COUNT16, int NBQ>
 __device__ __forceinline__ void tp_count_list(const uint32_t *__restrict__ Xc32, uint32_t s0, uint32_t l0,
                                               int tmax, int lane, int k, uint32_t *hist) {
@@ -970,21 +974,19 @@ __device__ __forceinline__ void tp_count_list(const uint32_t *__restrict__ Xc32,
             st[b] = (uint32_t)__shfl((int)s0, tq & 63);
             ln[b] = (uint32_t)__shfl((int)l0, tq & 63);
             if (tq >= tmax) ln[b] = 0;
-            w[b] = tp_load_six(Xc32, st[b], off, ln[b]);
+            w[b] = (u32x3a){0u, 0u, 0u};
+            if (off < ln[b]) w[b] = tp_load_six(Xc32, st[b], off);
         }
 #pragma unroll
-        for (int b = 0; b < NBQ; ++b) {
-            tp_count_dword<COUNT16>(w[b].x, k, hist);
-            tp_count_dword<COUNT16>(w[b].y, k, hist);
-            tp_count_dword<COUNT16>(w[b].z, k, hist);
-        }
+        for (int b = 0; b < NBQ; ++b)
+            if (off < ln[b]) tp_count_six<COUNT16>(w[b], ln[b] - off, k, hist);
 #pragma unroll
         for (int b = 0; b < NBQ; ++b) {         // the rare sub-segment of more than 96 entries
             for (uint32_t r = 96; __any(r < ln[b]); r += 96) {
-                const u32x3a v = tp_load_six(Xc32, st[b], r + off, ln[b]);
-                tp_count_dword<COUNT16>(v.x, k, hist);
-                tp_count_dword<COUNT16>(v.y, k, hist);
-                tp_count_dword<COUNT16>(v.z, k, hist);
+                if (r + off < ln[b]) {
+                    const u32x3a v = tp_load_six(Xc32, st[b], r + off);
+                    tp_count_six<COUNT16>(v, ln[b] - (r + off), k, hist);
+                }
             }
         }
     }
