@@ -921,6 +921,13 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
 // two entries at offset 2i of each, round after round, all NB loads of a round in flight together.
 // COUNT16: regular rows, 16-bit counters, index = entry; else hub share, 32-bit counters, index =
 // hub * k + label.  Entries with bit 15 set are ignored.
+// The value of lane (l ^ 1) (CTRL = 0xB1: quad_perm [1,0,3,2]) or (l ^ 2) (0x4E: [2,3,0,1]) of the
+// lane's quad, by a data-parallel-primitive move instead of a trip through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ uint32_t quad_swap(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+
 // Counting the entries of sub-segments of X.  A sub-segment holds some 70 entries, so a whole
 // wavefront on one of them would leave half its lanes idle: a QUARTER of the wavefront takes one,
 // six entries (three dwords) per lane, which covers 96 entries at once; longer ones take further
@@ -1147,8 +1154,15 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
         }
     }
 
-    // blend and propose; arg-max by (E desc, room desc, id asc)
+    // blend and propose; arg-max by (E desc, room desc, id asc).  The four lanes of a vertex are a quad
+    // of the wavefront, and a thread meets the same four partitions in every turn.
     const int sh = pass > 0 ? pass - 1 : 0;
+    uint32_t myroom[4];
+#pragma unroll
+    for (int z = 0; z < 4; ++z) {
+        const int j = vec ? 4 * (tid & 3) + z : (tid & 3) + 4 * z;
+        myroom[z] = j < k ? room[j] : 0u;
+    }
 #pragma unroll
     for (int u = 0; u < BU; ++u) {
         const int g = tid + u * kTpThreads;
@@ -1168,7 +1182,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
                 const uint32_t cidx = (uint32_t)t * 16u + (uint32_t)j;
                 const uint32_t h = (hist[cidx >> 1] >> (16 * (cidx & 1u))) & 0xFFFFu;
                 ev[u][z] += h << sh;
-                const uint32_t rm = room[j] + ((uint32_t)j == old ? 1u : 0u);
+                const uint32_t rm = myroom[z] + ((uint32_t)j == old ? 1u : 0u);
                 const unsigned long long key = rm ? (((unsigned long long)ev[u][z] << 32) | rm) : 0ull;
                 if (key > bestkey) { bestkey = key; bestj = j; }
             }
@@ -1193,10 +1207,14 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
                     if (q + 4 * z < k) Erow[q + 4 * z] = (ET)ev[u][z];
             }
         }
-#pragma unroll
-        for (int off = 1; off <= 2; off <<= 1) {
-            const unsigned long long okey = __shfl_xor(bestkey, off);
-            const int oj = __shfl_xor(bestj, off);
+        {   // lanes q ^ 1, then q ^ 2, by quad permutes
+            unsigned long long okey = ((unsigned long long)quad_swap<0xB1>((uint32_t)(bestkey >> 32)) << 32) |
+                                      quad_swap<0xB1>((uint32_t)bestkey);
+            int oj = (int)quad_swap<0xB1>((uint32_t)bestj);
+            if (okey > bestkey || (okey == bestkey && oj < bestj)) { bestkey = okey; bestj = oj; }
+            okey = ((unsigned long long)quad_swap<0x4E>((uint32_t)(bestkey >> 32)) << 32) |
+                   quad_swap<0x4E>((uint32_t)bestkey);
+            oj = (int)quad_swap<0x4E>((uint32_t)bestj);
             if (okey > bestkey || (okey == bestkey && oj < bestj)) { bestkey = okey; bestj = oj; }
         }
         if (q == 0) {
