@@ -1126,6 +1126,71 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
         }
     }
 
+    // k a multiple of 4 with 16-bit estimates (and sizes below 2^27): a thread's four partitions are
+    // one 8-byte piece of E and one of the counters; two packed adds blend them (no carry between the
+    // halves: an estimate stays below 2^16), and the arg-max by (E desc, room desc, id asc) is the
+    // maximum of one 64-bit key per partition, E << 40 | room << 4 | 15 - id, 0 if the partition is
+    // full (or does not exist: the lanes past k of a vertex's quad hold no partition).
+    if (sizeof(ET) == 2 && vec && P < (1ll << 27)) {
+        const int q = tid & 3;
+        const bool mine = 4 * q < k;
+        const int sh = pass > 0 ? pass - 1 : 0;
+        u32x2 e[BU];
+#pragma unroll
+        for (int u = 0; u < BU; ++u) {
+            const int g = tid + u * kTpThreads;
+            e[u] = (u32x2)(0u);
+            if (pass > 0 && mine && g < nv * 4)
+                e[u] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x2 *>(E + (size_t)(v0 + (g >> 2)) * (size_t)k + 4 * q));
+        }
+        uint32_t lo_base[4];
+#pragma unroll
+        for (int z = 0; z < 4; ++z) lo_base[z] = mine ? (room[4 * q + z] << 4) | (uint32_t)(15 - (4 * q + z)) : 0u;
+#pragma unroll
+        for (int u = 0; u < BU; ++u) {
+            const int g = tid + u * kTpThreads;
+            if (g >= nv * 4) continue;
+            const int t = g >> 2;
+            const uint32_t mt = meta[t];
+            if (mt & 0x100u) continue;                              // hubs are k_hub_finalize's
+            const uint32_t old = mt & 0xFFu;
+            const uint32_t oldz = old - 4u * (uint32_t)q;           // < 4: the old label is one of this thread's
+            const uint2 hw = *reinterpret_cast<const uint2 *>(hist + t * 8 + 2 * q);
+            u32x2 o;
+            o.x = e[u].x + (hw.x << sh);
+            o.y = e[u].y + (hw.y << sh);
+            if (store_e && mine)
+                __builtin_nontemporal_store(o, reinterpret_cast<u32x2 *>(E + (size_t)(v0 + t) * (size_t)k + 4 * q));
+            unsigned long long best = 0;
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                const uint32_t ez = z == 0 ? (o.x & 0xFFFFu) : z == 1 ? (o.x >> 16) : z == 2 ? (o.y & 0xFFFFu) : (o.y >> 16);
+                const uint32_t lo = lo_base[z] + (oldz == (uint32_t)z ? 16u : 0u);      // room + 1 without the vertex itself
+                const unsigned long long key = lo >= 16u ? (((unsigned long long)(ez << 8) << 32) | lo) : 0ull;
+                best = key > best ? key : best;
+            }
+#pragma unroll
+            for (int step = 0; step < 2; ++step) {
+                const unsigned long long other =
+                    step == 0 ? (((unsigned long long)quad_swap<0xB1>((uint32_t)(best >> 32)) << 32) | quad_swap<0xB1>((uint32_t)best))
+                              : (((unsigned long long)quad_swap<0x4E>((uint32_t)(best >> 32)) << 32) | quad_swap<0x4E>((uint32_t)best));
+                best = other > best ? other : best;
+            }
+            if (q == 0) {
+                uint32_t bj = 15u - ((uint32_t)best & 15u);
+                if (pass == 0 && old != 0xFFu) bj = old;        // seeded vertex keeps its label
+                prop[v0 + t - chunk_lo] = (uint8_t)bj;
+                if (bj != old) atomicAdd(&tcnt[(t >> 10) * k + (int)bj], 1u);
+            }
+        }
+        __syncthreads();
+        const int64_t tile0 = (v0 - chunk_lo) / kAdmitTile;
+        const int ntl = nv > kAdmitTile ? 2 : 1;
+        for (int j = tid; j < ntl * k; j += kTpThreads) cnt[(size_t)tile0 * k + j] = tcnt[j];
+        return;
+    }
+
     // this thread's pieces of E, all loads in flight together
     uint32_t ev[BU][4];
 #pragma unroll
@@ -1155,14 +1220,8 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     }
 
     // blend and propose; arg-max by (E desc, room desc, id asc).  The four lanes of a vertex are a quad
-    // of the wavefront, and a thread meets the same four partitions in every turn.
+    // of the wavefront.
     const int sh = pass > 0 ? pass - 1 : 0;
-    uint32_t myroom[4];
-#pragma unroll
-    for (int z = 0; z < 4; ++z) {
-        const int j = vec ? 4 * (tid & 3) + z : (tid & 3) + 4 * z;
-        myroom[z] = j < k ? room[j] : 0u;
-    }
 #pragma unroll
     for (int u = 0; u < BU; ++u) {
         const int g = tid + u * kTpThreads;
@@ -1182,7 +1241,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
                 const uint32_t cidx = (uint32_t)t * 16u + (uint32_t)j;
                 const uint32_t h = (hist[cidx >> 1] >> (16 * (cidx & 1u))) & 0xFFFFu;
                 ev[u][z] += h << sh;
-                const uint32_t rm = myroom[z] + ((uint32_t)j == old ? 1u : 0u);
+                const uint32_t rm = room[j] + ((uint32_t)j == old ? 1u : 0u);
                 const unsigned long long key = rm ? (((unsigned long long)ev[u][z] << 32) | rm) : 0ull;
                 if (key > bestkey) { bestkey = key; bestj = j; }
             }
