@@ -366,11 +366,12 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
         };
         if (sweep) {
             lay = make_layout(n, nnz, (int64_t)h_misc[8], k, chunk, external_E, geo, hub_degree);
-            tp_score_lds = ((size_t)kSliceRows * 8 + kSliceRows / 2 + (size_t)share_hubs * k + 3 * (size_t)k) * 4;
+            // (dynamic part: the 64 KB of counters are a static array of the kernel)
+            tp_score_lds = ((size_t)kSliceRows / 2 + (size_t)share_hubs * k + 3 * (size_t)k) * 4;
             tp_lookup_lds = (size_t)1 << (geo.cb > 5 ? geo.cb - 1 : 4);
             // a score workgroup must fit the 160 KB of LDS (two per CU do when a share touches few hubs);
             // one share may touch kMaxShareHubs hubs; sub-segment offsets are 32-bit
-            const bool fits = tp_score_lds <= 150 * 1024 && share_hubs <= kMaxShareHubs &&
+            const bool fits = tp_score_lds + (size_t)kSliceRows * 32 <= 150 * 1024 && share_hubs <= kMaxShareHubs &&
                               max_chunk_hubs <= lay.hub_rows_cap &&
                               h_misc[7] + 4ull * ((unsigned long long)geo.nsl + 2) * geo.nblk < (1ull << 32);
             if (!fits) {

@@ -1039,9 +1039,11 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     constexpr int hist_words = kSliceRows * 8;
     constexpr int BU = kSliceRows * 4 / kTpThreads;     // (vertex, quarter) pairs per thread
     static_assert(kSliceRows == 2 * kAdmitTile, "a slice is two admission tiles");
-    uint32_t *hist = smem;                      // hist_words
-    uint16_t *meta = reinterpret_cast<uint16_t *>(hist + hist_words);   // kSliceRows
-    uint32_t *hhist = hist + hist_words + kSliceRows / 2;               // share_hubs * k, 32-bit
+    // the counters are a static array: its address is a compile-time constant, which spares an add
+    // per counted entry
+    __shared__ uint32_t hist[hist_words];
+    uint16_t *meta = reinterpret_cast<uint16_t *>(smem);                // kSliceRows
+    uint32_t *hhist = smem + kSliceRows / 2;                            // share_hubs * k, 32-bit
     uint32_t *room = hhist + share_hubs * k;    // k
     uint32_t *tcnt = room + k;                  // 2 * k
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
