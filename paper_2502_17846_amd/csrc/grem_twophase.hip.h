@@ -855,7 +855,6 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
             }
             tab[w] = packed;
         }
-        __syncthreads();
     }
     const uint8_t *tbytes = reinterpret_cast<const uint8_t *>(tab);
     const uint32_t cmask = (1u << tb.cb) - 1u;
@@ -867,54 +866,76 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
         while (a < b) { const int mid = (a + b) >> 1; if (ts[mid + 1] > p0) b = mid; else a = mid + 1; }
         cc = a;
     }
+    // The share's range [p0, p1) of T crosses a few segments (c', jb), each with its own place in X.
+    // Their ends and X offsets are fetched side by side, kSegBatch segments at a time, so that the
+    // stream over the tuples never waits for them: a thread walks its groups of four tuples in
+    // ascending order and steps to the next segment when it passes an end.
+    constexpr int kSegBatch = 64;
+    __shared__ u64 s_end[kSegBatch];        // end of segment cc + i in T, cut at p1
+    __shared__ u64 s_xoff[kSegBatch];       // its start in X minus its start in T
     u64 p = p0;
+    bool first = true;
     while (p < p1 && cc < tb.nch) {
-        const u64 seg_lo = ts[cc], seg_hi = ts[cc + 1];
-        const u64 e = seg_hi < p1 ? seg_hi : p1;
-        if (e > p) {
-            const u64 xp = tb.xstart[(size_t)cc * tb.nblk + jb] + (p - seg_lo);
-            const u32x4 *src4 = reinterpret_cast<const u32x4 *>(T + p);
-            u32x2 *dst2 = reinterpret_cast<u32x2 *>(X + xp);
-            const uint32_t ng = (uint32_t)((e - p) >> 2);
-            constexpr int U = 2;
-            for (uint32_t base = tid; base < ng; base += kTpThreads * U) {
-                u32x4 t[U];
+        if (!first) __syncthreads();        // the previous batch is done with the tables
+        if (tid < kSegBatch) {
+            const int ci = cc + tid;
+            u64 e = p1, xo = 0;
+            if (ci < tb.nch) {
+                const u64 seg_lo = ts[ci], seg_hi = ts[ci + 1];
+                e = seg_hi < p1 ? seg_hi : p1;
+                if (e < p) e = p;
+                xo = tb.xstart[(size_t)ci * tb.nblk + jb] - seg_lo;
+            }
+            s_end[tid] = e;
+            s_xoff[tid] = xo;
+        }
+        __syncthreads();                    // also: the label table is complete
+        first = false;
+        const u64 pe = s_end[kSegBatch - 1];
+        const u32x4 *src4 = reinterpret_cast<const u32x4 *>(T + p);
+        const uint32_t ng = (uint32_t)((pe - p) >> 2);
+        constexpr int U = 4;
+        int si = 0;
+        for (uint32_t base = tid; base < ng; base += kTpThreads * U) {
+            u32x4 t[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t gi = base + u * kTpThreads;
-                    t[u] = gi < ng ? __builtin_nontemporal_load(src4 + gi) : (u32x4)(0u);
-                }
+            for (int u = 0; u < U; ++u) {
+                const uint32_t gi = base + u * kTpThreads;
+                t[u] = gi < ng ? __builtin_nontemporal_load(src4 + gi) : (u32x4)(0u);
+            }
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t gi = base + u * kTpThreads;
-                    if (gi < ng) {
-                        const uint32_t ent[4] = {t[u].x, t[u].y, t[u].z, t[u].w};
-                        uint32_t o[4];
+            for (int u = 0; u < U; ++u) {
+                const uint32_t gi = base + u * kTpThreads;
+                if (gi < ng) {
+                    const u64 pos = p + ((u64)gi << 2);
+                    while (pos >= s_end[si]) ++si;          // s_end[kSegBatch - 1] = pe > pos
+                    const uint32_t ent[4] = {t[u].x, t[u].y, t[u].z, t[u].w};
+                    uint32_t o[4];
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const uint32_t col = ent[q] & cmask;
-                            uint32_t lab;
-                            if (FROM_LDS) {
-                                lab = ((uint32_t)tbytes[col >> 1] >> (4 * (col & 1u))) & 15u;
-                            } else {
-                                const int64_t v = block_lo + (int64_t)col;
-                                const uint32_t l = v < chunk_hi ? (uint32_t)Lc[v] : 0xFFu;
-                                lab = l == 0xFFu ? 0x8000u : (l & 15u);
-                            }
-                            o[q] = (((ent[q] >> tb.cb) << 4) | lab) & 0xFFFFu;
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t col = ent[q] & cmask;
+                        uint32_t lab;
+                        if (FROM_LDS) {
+                            lab = ((uint32_t)tbytes[col >> 1] >> (4 * (col & 1u))) & 15u;
+                        } else {
+                            const int64_t v = block_lo + (int64_t)col;
+                            const uint32_t l = v < chunk_hi ? (uint32_t)Lc[v] : 0xFFu;
+                            lab = l == 0xFFu ? 0x8000u : (l & 15u);
                         }
-                        u32x2 w;
-                        w.x = o[0] | (o[1] << 16);
-                        w.y = o[2] | (o[3] << 16);
-                        __builtin_nontemporal_store(w, dst2 + gi);
+                        o[q] = (((ent[q] >> tb.cb) << 4) | lab) & 0xFFFFu;
                     }
+                    u32x2 w;
+                    w.x = o[0] | (o[1] << 16);
+                    w.y = o[2] | (o[3] << 16);
+                    __builtin_nontemporal_store(w, reinterpret_cast<u32x2 *>(X + s_xoff[si] + pos));
                 }
             }
-            p = e;
         }
-        cc += 1;
+        p = pe;
+        cc += kSegBatch;
     }
 }
+
 
 // Look-up results of NB sub-segments, [s[b], s[b] + l[b]) (even starts and lengths, in 16-bit
 // units from Xc; s and l are the same in every lane), counted by one wavefront: lane i takes the
