@@ -447,10 +447,14 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 while (npr < kMaxParts && !fits(false, npr, h_misc[9], false)) npr *= 2;
                 while (nps < kMaxParts && !fits(true, nps, h_misc[10], false)) nps += 1;
                 {
+                    // slices differ in size: it is the average one whose parts should take one round (the
+                    // larger ones take two, and their tuples still fit LDS)
+                    const unsigned long long avg_slice =
+                        ((unsigned long long)nnz - h_misc[8]) / (unsigned long long)(nchunks * nsl) + 1;
                     int a = npr, b = nps;
-                    while (a < kMaxParts && !fits(false, a, h_misc[9], true)) a *= 2;
+                    while (a < kMaxParts && !fits(false, a, avg_slice, true)) a *= 2;
                     while (b < kMaxParts && !fits(true, b, h_misc[10], true)) b += 1;
-                    if (fits(false, a, h_misc[9], true)) npr = a;
+                    if (fits(false, a, avg_slice, true) && fits(false, a, h_misc[9], false)) npr = a;
                     if (fits(true, b, h_misc[10], true)) nps = b;
                 }
                 tb.npr = npr;
