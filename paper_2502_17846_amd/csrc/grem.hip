@@ -81,7 +81,7 @@ TpGeom tp_geometry(int64_t n, int64_t chunk, int col_bits_setting) {
 }
 
 struct Layout {
-    size_t E, Lc, prop, S, cnt, room, ocnt, fillRank, fillSorted, fillC, misc, long_cnt, long_list;
+    size_t E, Lc, prop, S, cnt, tot, room, ocnt, fillRank, fillSorted, fillC, misc, long_cnt, long_list;
     // plan of the two-phase path (k <= 16 only)
     size_t sl_reg_cnt, sl_reg_start, sl_nh, sl_hub_start, sl_hent, sl_hent_start, share_h0, share_nhs,
         ch_regtot, ch_nh, ch_H, ch_nvs, ch_hbase, hub_row, hub_off;
@@ -112,6 +112,7 @@ Layout make_layout(int64_t n, int64_t nnz, int64_t hub_entries, int32_t k, int64
     L.prop = take((size_t)cl * lab);
     L.S = take((size_t)k * 8);
     L.cnt = take((size_t)ntiles * (size_t)k * 4);
+    L.tot = take(2 * (size_t)k * 4);
     L.room = take((size_t)k * 8);
     L.ocnt = take((size_t)ntiles * 4);
     L.fillRank = take((size_t)k * 4);
@@ -240,6 +241,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
     LabelT *prop = (LabelT *)(ws + lay.prop);
     long long *S = (long long *)(ws + lay.S);
     uint32_t *cnt = (uint32_t *)(ws + lay.cnt);
+    uint32_t *tot = (uint32_t *)(ws + lay.tot);      // two-phase path: upper bounds of the chunk's movers per partition
     long long *room = (long long *)(ws + lay.room);
     uint32_t *ocnt = (uint32_t *)(ws + lay.ocnt);
     int32_t *fillRank = (int32_t *)(ws + lay.fillRank);
@@ -583,12 +585,13 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                                                Hhub, (uint8_t *)prop, cnt, room, (int)c, lo, hi, (int)k, jlim,
                                                share_hubs, (uint32_t)hub_degree, pass, P, store_e);
                     });
-                    if (max_chunk_hubs > 0)
-                        L.run(GREM_KERNEL_HUBS, [&] {
-                            hipLaunchKernelGGL(k_hub_finalize, dim3((unsigned)((max_chunk_hubs + 15) / 16)),
-                                               dim3(256), 0, stream, pl, (const uint8_t *)Lc, room, E, Hhub,
-                                               (uint8_t *)prop, cnt, (int)c, lo, (int)k, pass, store_e);
-                        });
+                    // (one workgroup more than the hubs need: it adds up the chunk's mover counts)
+                    L.run(GREM_KERNEL_HUBS, [&] {
+                        hipLaunchKernelGGL(k_hub_finalize, dim3((unsigned)((max_chunk_hubs + 15) / 16) + 1),
+                                           dim3(256), 0, stream, pl, (const uint8_t *)Lc, room, E, Hhub,
+                                           (uint8_t *)prop, cnt, (int)c, lo, (int)k, pass, store_e,
+                                           (int)admit_blocks, tot);
+                    });
                 }
             } else {
                 const LongRows lr{split_long ? (uint32_t)g.long_row_degree : 0xFFFFFFFFu, kLongRowPart,
@@ -637,7 +640,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                     L.run(GREM_KERNEL_APPLY, [&] {
                         hipLaunchKernelGGL(k_apply16, dim3((admit_blocks + 1) / 2), dim3(kAdmitTile), 0, stream,
                                            (uint8_t *)Lc, (const uint8_t *)prop, lo, hi, (int)k, cnt, room,
-                                           (unsigned long long *)S, ocnt, pass);
+                                           tot, (unsigned long long *)S, ocnt, pass);
                     });
                 }
             }

@@ -683,14 +683,17 @@ __global__ __launch_bounds__(kAdmitThreads) void k_apply(
 
 // ------------------------------------------------------------------------------------------------
 // apply for k <= 16: the same admission, one vertex of each of two neighbouring tiles per thread,
-// a workgroup of kAdmitTile threads per pair of tiles, ranks from one ballot per partition and
-// tile.  cnt[tile][t] = movers to t in that tile (the workgroup adds up the rows of the earlier
-// tiles itself); room[t] = P - S[t] as of the chunk's start.
+// a workgroup of kAdmitTile threads per pair of tiles.  cnt[tile][t] = movers to t in that tile,
+// tot[t] >= movers to t in the whole chunk, room[t] = P - S[t] as of the chunk's start.  A partition
+// with no room admits nobody, one with room for all its movers admits everybody; only for the
+// others (room for some) are ranks needed: the workgroup adds up their columns of the earlier tiles'
+// counts and takes one ballot per such partition and tile.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc, const uint8_t *__restrict__ prop,
                                                         int64_t chunk_lo, int64_t chunk_hi, int k,
                                                         const uint32_t *__restrict__ cnt,
                                                         const long long *__restrict__ room,
+                                                        const uint32_t *__restrict__ tot,
                                                         unsigned long long *__restrict__ S,
                                                         uint32_t *__restrict__ ocnt, int pass) {
     constexpr int nwaves = kAdmitTile / 64;
@@ -698,6 +701,7 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
     __shared__ uint32_t wcnt[2][nwaves][16];    // movers per tile and wave, then their exclusive prefix over the waves
     __shared__ int32_t dS[16];
     __shared__ long long s_room[16];
+    __shared__ uint32_t s_ranked;               // bit t: partition t has room for some of its movers only
     __shared__ uint32_t s_unassigned[2];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int tile0 = 2 * (int)blockIdx.x;
@@ -710,44 +714,62 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
         inside[h] = v[h] < chunk_hi;
         if (inside[h]) { t[h] = prop[v[h] - chunk_lo]; old[h] = (uint32_t)Lc[v[h]]; }
     }
-    if (tid < 16) { tbl[tid] = 0; dS[tid] = 0; s_room[tid] = tid < k ? room[tid] : 0; }
-    if (tid < 2) s_unassigned[tid] = 0;
-    __syncthreads();
-    const int col = tid & 15, seg = tid >> 4;
-    {   // earlier tiles: thread (seg, col) adds up rows seg, seg + 64, ...
-        uint32_t sum = 0;
-        if (col < k)
-            for (int r = seg; r < tile0; r += kAdmitTile / 16) sum += cnt[(size_t)r * k + col];
-        if (sum) atomicAdd(&tbl[col], sum);
+    if (tid < 64) {
+        long long rm = 0;
+        bool some = false;
+        if (tid < k) {
+            rm = room[tid];
+            some = rm > 0 && (long long)tot[tid] > rm;
+        }
+        const unsigned long long m = __ballot(some);
+        if (tid < 16) { tbl[tid] = 0; dS[tid] = 0; s_room[tid] = rm; }
+        if (tid == 0) { s_ranked = (uint32_t)m; s_unassigned[0] = 0; s_unassigned[1] = 0; }
     }
-    const uint32_t first_tile = (tid < 16 && tid < k) ? cnt[(size_t)tile0 * k + tid] : 0u;   // movers of the pair's first tile
+    __syncthreads();
+    const uint32_t ranked = s_ranked;
     bool mover[2];
     uint32_t wrank[2] = {0, 0};
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        mover[h] = inside[h] && t[h] != old[h];
-        uint32_t mine = 0;
-        for (int j = 0; j < k; ++j) {
-            const unsigned long long m = __ballot(mover[h] && t[h] == (uint32_t)j);
-            if (mover[h] && t[h] == (uint32_t)j) wrank[h] = (uint32_t)__popcll(m & lanes_below(lane));
-            if (lane == j) mine = (uint32_t)__popcll(m);
+    for (int h = 0; h < 2; ++h) mover[h] = inside[h] && t[h] != old[h];
+    if (ranked) {
+        const int col = tid & 15, seg = tid >> 4;
+        if ((ranked >> col) & 1u) {   // earlier tiles: thread (seg, col) adds up rows seg, seg + 64, ...
+            uint32_t sum = 0;
+            for (int r = seg; r < tile0; r += kAdmitTile / 16) sum += cnt[(size_t)r * k + col];
+            if (sum) atomicAdd(&tbl[col], sum);
         }
-        if (lane < 16) wcnt[h][wave][lane] = lane < k ? mine : 0u;
+        const uint32_t first_tile = (tid < k) ? cnt[(size_t)tile0 * k + tid] : 0u;   // movers of the pair's first tile
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t mine = 0;
+            for (uint32_t left = ranked; left; left &= left - 1) {
+                const uint32_t j = (uint32_t)__ffs(left) - 1u;
+                const unsigned long long m = __ballot(mover[h] && t[h] == j);
+                if (mover[h] && t[h] == j) wrank[h] = (uint32_t)__popcll(m & lanes_below(lane));
+                if ((uint32_t)lane == j) mine = (uint32_t)__popcll(m);
+            }
+            if (lane < 16) wcnt[h][wave][lane] = mine;
+        }
+        __syncthreads();
+        if (tid < 16) {
+            uint32_t run = 0;
+            for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[0][w][tid]; wcnt[0][w][tid] = run; run += c; }
+            run = first_tile;
+            for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[1][w][tid]; wcnt[1][w][tid] = run; run += c; }
+        }
+        __syncthreads();
     }
-    __syncthreads();
-    if (tid < 16) {
-        uint32_t run = 0;
-        for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[0][w][tid]; wcnt[0][w][tid] = run; run += c; }
-        run = first_tile;
-        for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[1][w][tid]; wcnt[1][w][tid] = run; run += c; }
-    }
-    __syncthreads();
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         bool admitted = false;
         if (mover[h]) {
-            const long long rank = (long long)tbl[t[h]] + wcnt[h][wave][t[h]] + wrank[h];
-            admitted = rank < s_room[t[h]];
+            const long long rm = s_room[t[h]];
+            if ((ranked >> t[h]) & 1u) {
+                const long long rank = (long long)tbl[t[h]] + wcnt[h][wave][t[h]] + wrank[h];
+                admitted = rank < rm;
+            } else {
+                admitted = rm > 0;          // room for all of the partition's movers, or for none
+            }
         }
         if (admitted) {
             Lc[v[h]] = (uint8_t)t[h];

@@ -1323,8 +1323,36 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
                                                       const long long *__restrict__ room,
                                                       uint32_t *__restrict__ E, uint32_t *__restrict__ Hhub,
                                                       uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
-                                                      int c, int64_t chunk_lo, int k, int pass, int store_e) {
+                                                      int c, int64_t chunk_lo, int k, int pass, int store_e,
+                                                      int ntiles, uint32_t *__restrict__ tot) {
     const uint32_t nh = pl.ch_nh[c];
+    if (blockIdx.x == gridDim.x - 1) {
+        // the last workgroup: tot[t] = an upper bound of the chunk's movers to partition t, for
+        // k_apply16: the tiles' counts as far as they are complete, plus one for every hub
+        __shared__ uint32_t part[256];
+        const int col = threadIdx.x & 15, seg = threadIdx.x >> 4;
+        uint32_t sum = 0;
+        if (col < k) {
+            for (int r0 = seg; r0 < ntiles; r0 += 16 * 16) {    // 16 loads side by side
+                uint32_t x[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int r = r0 + 16 * u;
+                    x[u] = r < ntiles ? cnt[(size_t)r * k + col] : 0u;
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) sum += x[u];
+            }
+        }
+        part[threadIdx.x] = sum;
+        __syncthreads();
+        if (threadIdx.x < 16 && threadIdx.x < (unsigned)k) {
+            uint32_t total = nh;
+            for (int q = 0; q < 16; ++q) total += part[q * 16 + threadIdx.x];
+            tot[threadIdx.x] = total;
+        }
+        return;
+    }
     const uint32_t i = blockIdx.x * 16u + (threadIdx.x >> 4);
     const int j = threadIdx.x & 15;
     const bool on = i < nh;
