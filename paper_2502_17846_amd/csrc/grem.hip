@@ -638,7 +638,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
             } else {
                 if constexpr (sizeof(LabelT) == 1) {
                     L.run(GREM_KERNEL_APPLY, [&] {
-                        hipLaunchKernelGGL(k_apply16, dim3((admit_blocks + 1) / 2), dim3(kAdmitTile), 0, stream,
+                        hipLaunchKernelGGL(k_apply16, dim3((admit_blocks + kApply16Tiles - 1) / kApply16Tiles), dim3(kAdmitTile), 0, stream,
                                            (uint8_t *)Lc, (const uint8_t *)prop, lo, hi, (int)k, cnt, room,
                                            tot, (unsigned long long *)S, ocnt, pass);
                     });

@@ -682,13 +682,15 @@ __global__ __launch_bounds__(kAdmitThreads) void k_apply(
 }
 
 // ------------------------------------------------------------------------------------------------
-// apply for k <= 16: the same admission, one vertex of each of two neighbouring tiles per thread,
-// a workgroup of kAdmitTile threads per pair of tiles.  cnt[tile][t] = movers to t in that tile,
+// apply for k <= 16: the same admission, one vertex of each of kApply16Tiles neighbouring tiles per
+// thread, a workgroup of kAdmitTile threads per such group of tiles.  cnt[tile][t] = movers to t in that tile,
 // tot[t] >= movers to t in the whole chunk, room[t] = P - S[t] as of the chunk's start.  A partition
 // with no room admits nobody, one with room for all its movers admits everybody; only for the
 // others (room for some) are ranks needed: the workgroup adds up their columns of the earlier tiles'
 // counts and takes one ballot per such partition and tile.
 // ------------------------------------------------------------------------------------------------
+constexpr int kApply16Tiles = 4;     // neighbouring tiles per workgroup of k_apply16
+
 __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc, const uint8_t *__restrict__ prop,
                                                         int64_t chunk_lo, int64_t chunk_hi, int k,
                                                         const uint32_t *__restrict__ cnt,
@@ -697,21 +699,24 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
                                                         unsigned long long *__restrict__ S,
                                                         uint32_t *__restrict__ ocnt, int pass) {
     constexpr int nwaves = kAdmitTile / 64;
-    __shared__ uint32_t tbl[16];                // movers in the tiles before the pair
-    __shared__ uint32_t wcnt[2][nwaves][16];    // movers per tile and wave, then their exclusive prefix over the waves
+    constexpr int TPW = kApply16Tiles;
+    __shared__ uint32_t tbl[16];                    // movers in the tiles before the workgroup's
+    __shared__ uint32_t wcnt[TPW][nwaves][16];      // movers per tile and wave, then their exclusive prefix
     __shared__ int32_t dS[16];
     __shared__ long long s_room[16];
-    __shared__ uint32_t s_ranked;               // bit t: partition t has room for some of its movers only
-    __shared__ uint32_t s_unassigned[2];
+    __shared__ uint32_t s_ranked;                   // bit t: partition t has room for some of its movers only
+    __shared__ uint32_t s_unassigned[TPW];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const int tile0 = 2 * (int)blockIdx.x;
-    int64_t v[2];
-    bool inside[2];
-    uint32_t t[2] = {0, 0}, old[2] = {0, 0};
+    const int tile0 = TPW * (int)blockIdx.x;
+    int64_t v[TPW];
+    bool inside[TPW];
+    uint32_t t[TPW], old[TPW];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < TPW; ++h) {
         v[h] = chunk_lo + (int64_t)(tile0 + h) * kAdmitTile + tid;
         inside[h] = v[h] < chunk_hi;
+        t[h] = 0;
+        old[h] = 0;
         if (inside[h]) { t[h] = prop[v[h] - chunk_lo]; old[h] = (uint32_t)Lc[v[h]]; }
     }
     if (tid < 64) {
@@ -723,14 +728,15 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
         }
         const unsigned long long m = __ballot(some);
         if (tid < 16) { tbl[tid] = 0; dS[tid] = 0; s_room[tid] = rm; }
-        if (tid == 0) { s_ranked = (uint32_t)m; s_unassigned[0] = 0; s_unassigned[1] = 0; }
+        if (tid < TPW) s_unassigned[tid] = 0;
+        if (tid == 0) s_ranked = (uint32_t)m;
     }
     __syncthreads();
     const uint32_t ranked = s_ranked;
-    bool mover[2];
-    uint32_t wrank[2] = {0, 0};
+    bool mover[TPW];
+    uint32_t wrank[TPW];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) mover[h] = inside[h] && t[h] != old[h];
+    for (int h = 0; h < TPW; ++h) { mover[h] = inside[h] && t[h] != old[h]; wrank[h] = 0; }
     if (ranked) {
         const int col = tid & 15, seg = tid >> 4;
         if ((ranked >> col) & 1u) {   // earlier tiles: thread (seg, col) adds up rows seg, seg + 64, ...
@@ -738,9 +744,13 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
             for (int r = seg; r < tile0; r += kAdmitTile / 16) sum += cnt[(size_t)r * k + col];
             if (sum) atomicAdd(&tbl[col], sum);
         }
-        const uint32_t first_tile = (tid < k) ? cnt[(size_t)tile0 * k + tid] : 0u;   // movers of the pair's first tile
+        // movers of the workgroup's own tiles (a tile past the chunk's end has none)
+        uint32_t own[TPW];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < TPW; ++h)
+            own[h] = (tid < k && chunk_lo + (int64_t)(tile0 + h) * kAdmitTile < chunk_hi) ? cnt[(size_t)(tile0 + h) * k + tid] : 0u;
+#pragma unroll
+        for (int h = 0; h < TPW; ++h) {
             uint32_t mine = 0;
             for (uint32_t left = ranked; left; left &= left - 1) {
                 const uint32_t j = (uint32_t)__ffs(left) - 1u;
@@ -752,15 +762,18 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
         }
         __syncthreads();
         if (tid < 16) {
-            uint32_t run = 0;
-            for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[0][w][tid]; wcnt[0][w][tid] = run; run += c; }
-            run = first_tile;
-            for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[1][w][tid]; wcnt[1][w][tid] = run; run += c; }
+            uint32_t before = 0;                    // movers in the workgroup's earlier tiles
+#pragma unroll
+            for (int h = 0; h < TPW; ++h) {
+                uint32_t run = before;
+                for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[h][w][tid]; wcnt[h][w][tid] = run; run += c; }
+                before += own[h];
+            }
         }
         __syncthreads();
     }
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < TPW; ++h) {
         bool admitted = false;
         if (mover[h]) {
             const long long rm = s_room[t[h]];
@@ -784,7 +797,7 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
         const int32_t d = dS[tid];
         if (d != 0) atomicAdd(&S[tid], (unsigned long long)(long long)d);
     }
-    if (pass == 0 && tid < 2 && chunk_lo + (int64_t)(tile0 + tid) * kAdmitTile < chunk_hi)
+    if (pass == 0 && tid < TPW && chunk_lo + (int64_t)(tile0 + tid) * kAdmitTile < chunk_hi)
         ocnt[tile0 + tid] = s_unassigned[tid];
 }
 
