@@ -834,6 +834,36 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
     const u64 p1 = lo + ((units * (u64)(s + 1) / (u64)spb) << 3);
     if (p0 >= p1) return;
 
+    // first row chunk whose segment ends after p0
+    int cc = cmin;
+    {
+        int a = cmin, b = tb.nch - 1;       // ts[b + 1] = hi > p0 always holds
+        while (a < b) { const int mid = (a + b) >> 1; if (ts[mid + 1] > p0) b = mid; else a = mid + 1; }
+        cc = a;
+    }
+    // The share's range [p0, p1) of T crosses a few segments (c', jb), each with its own place in X.
+    // Their ends and X offsets are fetched side by side, kSegBatch segments at a time, so that the
+    // stream over the tuples never waits for them: a thread walks its groups of four tuples in
+    // ascending order and steps to the next segment when it passes an end.  The first tuples are
+    // requested before the label table is built, so that the two latencies overlap.
+    constexpr int kSegBatch = 64;
+    constexpr int U = 4;
+    __shared__ u64 s_end[kSegBatch];        // end of segment cc + i in T, cut at p1
+    __shared__ u64 s_xoff[kSegBatch];       // its start in X minus its start in T
+    u32x4 t[U];
+    {
+        const int cend = cc + kSegBatch < tb.nch ? cc + kSegBatch : tb.nch;
+        u64 pe = ts[cend];
+        if (pe > p1) pe = p1;
+        const uint32_t ng = (uint32_t)((pe - p0) >> 2);
+        const u32x4 *src4 = reinterpret_cast<const u32x4 *>(T + p0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t gi = tid + u * kTpThreads;
+            t[u] = gi < ng ? __builtin_nontemporal_load(src4 + gi) : (u32x4)(0u);
+        }
+    }
+
     if (FROM_LDS) {
         const int64_t bv = (chunk_hi - block_lo) < (1ll << tb.cb) ? (chunk_hi - block_lo) : (1ll << tb.cb);
         const int words = (int)((bv + 7) >> 3);
@@ -859,20 +889,6 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
     const uint8_t *tbytes = reinterpret_cast<const uint8_t *>(tab);
     const uint32_t cmask = (1u << tb.cb) - 1u;
 
-    // first row chunk whose segment ends after p0
-    int cc = cmin;
-    {
-        int a = cmin, b = tb.nch - 1;       // ts[b + 1] = hi > p0 always holds
-        while (a < b) { const int mid = (a + b) >> 1; if (ts[mid + 1] > p0) b = mid; else a = mid + 1; }
-        cc = a;
-    }
-    // The share's range [p0, p1) of T crosses a few segments (c', jb), each with its own place in X.
-    // Their ends and X offsets are fetched side by side, kSegBatch segments at a time, so that the
-    // stream over the tuples never waits for them: a thread walks its groups of four tuples in
-    // ascending order and steps to the next segment when it passes an end.
-    constexpr int kSegBatch = 64;
-    __shared__ u64 s_end[kSegBatch];        // end of segment cc + i in T, cut at p1
-    __shared__ u64 s_xoff[kSegBatch];       // its start in X minus its start in T
     u64 p = p0;
     bool first = true;
     while (p < p1 && cc < tb.nch) {
@@ -890,18 +906,17 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
             s_xoff[tid] = xo;
         }
         __syncthreads();                    // also: the label table is complete
-        first = false;
         const u64 pe = s_end[kSegBatch - 1];
         const u32x4 *src4 = reinterpret_cast<const u32x4 *>(T + p);
         const uint32_t ng = (uint32_t)((pe - p) >> 2);
-        constexpr int U = 4;
         int si = 0;
         for (uint32_t base = tid; base < ng; base += kTpThreads * U) {
-            u32x4 t[U];
+            if (!(first && base == (uint32_t)tid)) {        // (the batch's first turn is already on its way)
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t gi = base + u * kTpThreads;
-                t[u] = gi < ng ? __builtin_nontemporal_load(src4 + gi) : (u32x4)(0u);
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t gi = base + u * kTpThreads;
+                    t[u] = gi < ng ? __builtin_nontemporal_load(src4 + gi) : (u32x4)(0u);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -931,10 +946,12 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
                 }
             }
         }
+        first = false;
         p = pe;
         cc += kSegBatch;
     }
 }
+
 
 
 // Look-up results of NB sub-segments, [s[b], s[b] + l[b]) (even starts and lengths, in 16-bit
