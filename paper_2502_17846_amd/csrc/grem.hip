@@ -86,7 +86,7 @@ struct Layout {
     size_t sl_reg_cnt, sl_reg_start, sl_nh, sl_hub_start, sl_hent, sl_hent_start, share_h0, share_nhs,
         ch_regtot, ch_nh, ch_H, ch_nvs, ch_hbase, hub_row, hub_off;
     size_t total;
-    size_t subR, subH, xstart, tstart, lo, loh, Hhub, T, X, U, Uh, E16, total_sweep;   // extras of the two-phase path, after `total`
+    size_t subR, subH, xstart, tstart, lo, loh, Hhub, T, R, Lx, Rdyn, U, Uh, E16, total_sweep;   // extras of the two-phase path, after `total`
     size_t hub_rows_cap;                                          // rows of Hhub
 };
 
@@ -98,7 +98,7 @@ inline int64_t slices_per_chunk(int64_t n, int64_t chunk) {
 constexpr int kMaxParts = 8;      // parts of a slice (hub share) in the re-layout
 
 Layout make_layout(int64_t n, int64_t nnz, int64_t hub_entries, int32_t k, int64_t chunk, bool external_E,
-                   const TpGeom &tp, int hub_degree, int npr = kMaxParts, int nps = kMaxParts) {
+                   const TpGeom &tp, int hub_degree, bool seeded, int npr = kMaxParts, int nps = kMaxParts) {
     Layout L{};
     const int64_t cl = chunk < n ? chunk : n;
     const size_t lab = k <= 255 ? 1 : 2;
@@ -154,10 +154,12 @@ Layout make_layout(int64_t n, int64_t nnz, int64_t hub_entries, int32_t k, int64
         L.lo = take(G * (size_t)npr * ((size_t)tp.ngroups + 1) * 4);
         L.loh = take(G * (size_t)nps * ((size_t)tp.ngroups + 1) * 4);
         L.Hhub = take(hubs * (size_t)k * 4);
-        // every sub-segment is padded to even, every segment to a multiple of 8
-        const size_t slots = (size_t)(nnz > 0 ? nnz : 0) + 2 * rows * (size_t)tp.nblk + 8 * segs;
-        L.T = take(slots * 4 + 16);
-        L.X = take(slots * 2 + 16);
+        // every sub-segment is padded to a multiple of 4 tuples, every segment to a multiple of 8
+        const size_t slots = (size_t)(nnz > 0 ? nnz : 0) + 6 * rows * (size_t)tp.nblk + 8 * segs;
+        L.T = take(slots * 3 + 16);                 // column in block, 3 bytes per tuple
+        L.R = take(slots * 2 + 16);                 // row field, 2 bytes per tuple
+        L.Lx = take(slots / 2 + 16);                // label, 4 bits per tuple
+        L.Rdyn = take(seeded ? slots * 2 + 16 : 0); // seeded runs: R with the unassigned neighbours marked
         L.U = take((size_t)(nnz > 0 ? nnz : 0) * 4 + 16);
         L.Uh = take((size_t)(hub_entries > 0 ? hub_entries : 0) * 4 + 16);
         L.E16 = take((size_t)n * (size_t)k * 2);
@@ -211,7 +213,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
     const bool external_E = estimates_out != nullptr;
     const int hub_degree = g.sweep_hub_degree;
     const TpGeom geo = tp_geometry(n, chunk, g.sweep_col_bits);
-    Layout lay = make_layout(n, 0, 0, k, chunk, external_E, geo, hub_degree);
+    Layout lay = make_layout(n, 0, 0, k, chunk, external_E, geo, hub_degree, seed != nullptr);
 
     const int hist_mode = g.hist_mode;
     if (hist_mode == GREM_HIST_LDS && k > kLdsMaxK) return GREM_ERR_ARG;
@@ -354,7 +356,8 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
     // ---- two-phase path: allocate its extras, re-lay-out the entries once
     TpTables tb{};
     uint32_t *T = nullptr, *Hhub = nullptr;
-    uint16_t *X = nullptr, *E16 = nullptr;
+    uint16_t *Rw = nullptr, *Rdyn = nullptr, *E16 = nullptr;      // Rw: the tuples' row fields
+    uint32_t *Lx = nullptr;
     // estimates of the regular rows of the two-phase path stay below hub_degree * 2^R: 16 bits when that fits
     const bool use16 = (((unsigned long long)(hub_degree - 1)) << R) <= 65535ull;
     size_t tp_score_lds = 0, tp_lookup_lds = 0;
@@ -367,7 +370,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                    hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
         };
         if (sweep) {
-            lay = make_layout(n, nnz, (int64_t)h_misc[8], k, chunk, external_E, geo, hub_degree);
+            lay = make_layout(n, nnz, (int64_t)h_misc[8], k, chunk, external_E, geo, hub_degree, seed != nullptr);
             // (dynamic part: the 64 KB of counters are a static array of the kernel)
             tp_score_lds = ((size_t)kSliceRows / 2 + (size_t)share_hubs * k + 3 * (size_t)k) * 4;
             tp_lookup_lds = (size_t)1 << (geo.cb > 5 ? geo.cb - 1 : 4);
@@ -375,7 +378,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
             // one share may touch kMaxShareHubs hubs; sub-segment offsets are 32-bit
             const bool fits = tp_score_lds + (size_t)kSliceRows * 32 <= 150 * 1024 && share_hubs <= kMaxShareHubs &&
                               max_chunk_hubs <= lay.hub_rows_cap &&
-                              h_misc[7] + 4ull * ((unsigned long long)geo.nsl + 2) * geo.nblk < (1ull << 32);
+                              h_misc[7] + 8ull * ((unsigned long long)geo.nsl + 2) * geo.nblk < (1ull << 32);
             if (!fits) {
                 if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
                 sweep = false;
@@ -420,7 +423,9 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 tb.cb = geo.cb;
                 Hhub = (uint32_t *)(xbase + lay.Hhub);
                 T = (uint32_t *)(xbase + lay.T);
-                X = (uint16_t *)(xbase + lay.X);
+                Rw = (uint16_t *)(xbase + lay.R);
+                Lx = (uint32_t *)(xbase + lay.Lx);
+                Rdyn = seed ? (uint16_t *)(xbase + lay.Rdyn) : nullptr;
                 E16 = (uint16_t *)(xbase + lay.E16);
                 tb.gb = geo.gb;
                 tb.ngroups = geo.ngroups;
@@ -470,7 +475,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 if (batch > 8) batch = 8;
                 if (batch < 1) batch = 1;
                 const int maxruns = batch * (npr > nps ? npr : nps);
-                const size_t place_fixed = ((size_t)nbg + maxruns) * 8 +
+                const size_t place_fixed = (2 * (size_t)nbg + maxruns) * 8 +
                                            ((size_t)2 * maxruns + 1 + 2 * (size_t)nbg + 1 + (size_t)batch * nbg) * 4;
                 const uint32_t capP = (uint32_t)(kPlaceLds > place_fixed ? (kPlaceLds - place_fixed) / 4 : 0);
                 const size_t place_lds = place_fixed + (size_t)capP * 4;
@@ -481,7 +486,8 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                     !set_lds((const void *)k_tp_group<RowT, false>, groupR_lds) ||
                     !set_lds((const void *)k_tp_group<RowT, true>, groupS_lds) ||
                     !set_lds((const void *)k_tp_place<RowT>, place_lds) ||
-                    !set_lds((const void *)k_tp_lookup<true>, tp_lookup_lds) ||
+                    !set_lds((const void *)k_tp_lookup<true, false>, tp_lookup_lds) ||
+                    !set_lds((const void *)k_tp_lookup<true, true>, tp_lookup_lds) ||
                     !set_lds((const void *)k_tp_score<RowT, uint32_t>, tp_score_lds) ||
                     !set_lds((const void *)k_tp_score<RowT, uint16_t>, tp_score_lds)) {
                     release();
@@ -512,7 +518,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                 });
                 L.run(GREM_KERNEL_RELAYOUT, [&] {
                     hipLaunchKernelGGL((k_tp_place<RowT>), dim3((unsigned)((int64_t)geo.ngroups * geo.nch)),
-                                       dim3(kPlaceThreads), place_lds, stream, rowptr, n, pl, tb, U, Uh, T, batch,
+                                       dim3(kPlaceThreads), place_lds, stream, rowptr, n, pl, tb, U, Uh, T, Rw, batch,
                                        capP);
                 });
             }
@@ -521,7 +527,10 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
 
     // look-ups of the labels of chunks [c0, c0 + count): shares per column block sized so that one
     // launch fills the chip without cutting the blocks' streams into crumbs
-    auto lookup = [&](int c0, int count, int cmin, bool from_lds) {
+    // `mark`: seeded runs, first pass: the row fields the score kernels read are those of Rdyn, where
+    // bit 15 also marks the tuples whose neighbour is unassigned (set by the initial look-up from global
+    // memory, cleared by the look-up of the neighbour's chunk)
+    auto lookup = [&](int c0, int count, int cmin, bool from_lds, bool mark) {
         if constexpr (sizeof(LabelT) == 1) {
             if (cmin >= geo.nch) return;
             const int64_t per_block = nnz / geo.nblk + 1;
@@ -529,22 +538,24 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
             const int64_t by_work = per_block / 8192 + 1;
             if (spb > by_work) spb = (int)by_work;
             if (spb < 1) spb = 1;
+            const dim3 grid((unsigned)(geo.nbc * spb), (unsigned)count);
             L.run(GREM_KERNEL_LOOKUP, [&] {
-                if (from_lds)
-                    hipLaunchKernelGGL((k_tp_lookup<true>), dim3((unsigned)(geo.nbc * spb), (unsigned)count),
-                                       dim3(kTpThreads), tp_lookup_lds, stream, T, X, tb, (const uint8_t *)Lc, n,
-                                       c0, cmin, spb);
+                if (!from_lds)
+                    hipLaunchKernelGGL((k_tp_lookup<false, true>), grid, dim3(kTpThreads), 0, stream, T, Lx, Rw, Rdyn,
+                                       tb, (const uint8_t *)Lc, n, c0, cmin, spb);
+                else if (mark)
+                    hipLaunchKernelGGL((k_tp_lookup<true, true>), grid, dim3(kTpThreads), tp_lookup_lds, stream, T,
+                                       Lx, Rw, Rdyn, tb, (const uint8_t *)Lc, n, c0, cmin, spb);
                 else
-                    hipLaunchKernelGGL((k_tp_lookup<false>), dim3((unsigned)(geo.nbc * spb), (unsigned)count),
-                                       dim3(kTpThreads), 0, stream, T, X, tb, (const uint8_t *)Lc, n, c0, cmin,
-                                       spb);
+                    hipLaunchKernelGGL((k_tp_lookup<true, false>), grid, dim3(kTpThreads), tp_lookup_lds, stream, T,
+                                       Lx, Rw, Rdyn, tb, (const uint8_t *)Lc, n, c0, cmin, spb);
             });
         }
     };
     if (sweep && seed) {        // the seeds are the labels every first-pass look-up starts from
         for (int c0 = 0; c0 < geo.nch; c0 += 32768) {
             const int count = geo.nch - c0 < 32768 ? geo.nch - c0 : 32768;
-            lookup(c0, count, 0, false);
+            lookup(c0, count, 0, false, true);
         }
     }
 
@@ -573,15 +584,16 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                     // the estimates are state between passes and, if the caller asked for them, output:
                     // the last pass does not store them otherwise
                     const int store_e = (pass < R || external_E) ? 1 : 0;
+                    const uint16_t *rows_now = (seed && pass == 0) ? Rdyn : Rw;
                     L.run(GREM_KERNEL_SCORE, [&] {
                         if (use16)
                             hipLaunchKernelGGL((k_tp_score<RowT, uint16_t>), dim3(blocks), dim3(kTpThreads),
-                                               tp_score_lds, stream, rowptr, X, tb, pl, (const uint8_t *)Lc, S, E16,
+                                               tp_score_lds, stream, rowptr, rows_now, Lx, tb, pl, (const uint8_t *)Lc, S, E16,
                                                Hhub, (uint8_t *)prop, cnt, room, (int)c, lo, hi, (int)k, jlim,
                                                share_hubs, (uint32_t)hub_degree, pass, P, store_e);
                         else
                             hipLaunchKernelGGL((k_tp_score<RowT, uint32_t>), dim3(blocks), dim3(kTpThreads),
-                                               tp_score_lds, stream, rowptr, X, tb, pl, (const uint8_t *)Lc, S, E,
+                                               tp_score_lds, stream, rowptr, rows_now, Lx, tb, pl, (const uint8_t *)Lc, S, E,
                                                Hhub, (uint8_t *)prop, cnt, room, (int)c, lo, hi, (int)k, jlim,
                                                share_hubs, (uint32_t)hub_degree, pass, P, store_e);
                     });
@@ -657,7 +669,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
             }
             // the chunk's new labels, looked up for every row that will read them: rows of later
             // chunks in this pass, rows of this and earlier chunks in the next pass (if there is one)
-            if (sweep) lookup((int)c, 1, pass == R ? (int)c + 1 : 0, true);
+            if (sweep) lookup((int)c, 1, pass == R ? (int)c + 1 : 0, true, seed != nullptr && pass == 0);
         }
     }
     {
@@ -727,7 +739,7 @@ size_t grem_workspace_bytes(int64_t n, int64_t nnz, int32_t k, int64_t chunk) {
     if (n < 1 || nnz < 0 || k < 1 || k > GREM_MAX_K || chunk < 1) return 0;
     std::lock_guard<std::mutex> lock(g.mu);
     const TpGeom geo = tp_geometry(n, chunk, g.sweep_col_bits);
-    const Layout lay = make_layout(n, nnz, nnz, k, chunk, false, geo, g.sweep_hub_degree);
+    const Layout lay = make_layout(n, nnz, nnz, k, chunk, false, geo, g.sweep_hub_degree, true);
     return lay.total_sweep;
 }
 

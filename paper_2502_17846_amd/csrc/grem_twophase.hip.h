@@ -51,6 +51,7 @@ constexpr int kMaxColBits = 18;                    // 2^18 labels, two per byte:
 typedef unsigned long long u64;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x3a __attribute__((ext_vector_type(3), aligned(4)));     // 12 bytes at any 4-byte boundary
 
 struct SweepPlan {
     // per slice (global slice index gs = chunk * nsl + i)
@@ -604,10 +605,10 @@ __global__ __launch_bounds__(256) void k_tp_scan_slices(TpTables tb) {
     const int c = (int)(id / tb.nblk), jb = (int)(id % tb.nblk);
     uint32_t run = 0;
     uint32_t *p = tb.subR + ((size_t)c * (tb.nsl + 1)) * tb.nblk + jb;
-    for (int i = 0; i < tb.nsl; ++i, p += tb.nblk) { const uint32_t t = (*p + 1u) & ~1u; *p = run; run += t; }
+    for (int i = 0; i < tb.nsl; ++i, p += tb.nblk) { const uint32_t t = (*p + 3u) & ~3u; *p = run; run += t; }
     *p = run;
     p = tb.subH + ((size_t)c * (tb.nsl + 1)) * tb.nblk + jb;
-    for (int i = 0; i < tb.nsl; ++i, p += tb.nblk) { const uint32_t t = (*p + 1u) & ~1u; *p = run; run += t; }
+    for (int i = 0; i < tb.nsl; ++i, p += tb.nblk) { const uint32_t t = (*p + 3u) & ~3u; *p = run; run += t; }
     *p = run;
     const u64 padded = ((u64)run + 7ull) & ~7ull;
     tb.xstart[(size_t)c * tb.nblk + jb] = padded;
@@ -643,25 +644,27 @@ __global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb, u64 *__r
 // 2048, which the look-up turns into an entry the score ignores; every odd sub-segment ends with
 // one), and written out contiguously.  A batch that does not fit `cap` slots is cut down to one
 // slice; a slice that does not fit is written tuple by tuple.
-// LDS: tbase[nbg] (u64), runsrc[batch * npmax] (u64), runlen[batch * npmax + 1], runsl[batch * npmax],
+// LDS: tbase[nbg], xbase[nbg] (u64), runsrc[batch * npmax] (u64), runlen[batch * npmax + 1], runsl[batch * npmax],
 //      joff[nbg + 1], s0[nbg], cur[batch * nbg], stage[cap]
 // ------------------------------------------------------------------------------------------------
 constexpr int kPlaceThreads = 512;
 
 template <typename RowT>
-__global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restrict__ rowptr, int64_t n,
+__global__ __launch_bounds__(kPlaceThreads) __attribute__((amdgpu_waves_per_eu(6, 6))) void k_tp_place(const RowT *__restrict__ rowptr, int64_t n,
                                                             SweepPlan pl, TpTables tb,
                                                             const uint32_t *__restrict__ U,
                                                             const uint32_t *__restrict__ Uh,
-                                                            uint32_t *__restrict__ T, int batch, uint32_t cap) {
+                                                            uint32_t *__restrict__ T, uint16_t *__restrict__ R,
+                                                            int batch, uint32_t cap) {
     extern __shared__ u64 smem64[];
     const int g = (int)(blockIdx.x % (unsigned)tb.ngroups), c = (int)(blockIdx.x / (unsigned)tb.ngroups);
     const int jb0 = g << tb.gb;
     const int nbg = (jb0 + (1 << tb.gb)) <= tb.nblk ? (1 << tb.gb) : tb.nblk - jb0;
     const int npmax = tb.npr > tb.nps ? tb.npr : tb.nps;
     const int maxruns = batch * npmax;
-    u64 *tbase = smem64;                                        // nbg
-    u64 *runsrc = tbase + nbg;                                  // maxruns    first tuple of the run
+    u64 *tbase = smem64;                                        // nbg        segment (jb, c) in T
+    u64 *xbase = tbase + nbg;                                   // nbg        segment (c, jb) in R
+    u64 *runsrc = xbase + nbg;                                  // maxruns    first tuple of the run
     uint32_t *runlen = reinterpret_cast<uint32_t *>(runsrc + maxruns);  // maxruns + 1   tuples in the run
     uint32_t *runsl = runlen + maxruns + 1;                     // maxruns    slice (in the batch) of the run
     uint32_t *joff = runsl + maxruns;                           // nbg + 1    start of block j's piece in stage
@@ -676,7 +679,18 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
     const int nvs = (int)pl.ch_nvs[c];
     const uint32_t gmask = (1u << tb.gb) - 1u, cmask = (1u << tb.cb) - 1u;
     const uint32_t pad = 2048u << tb.cb;
-    for (int j = tid; j < nbg; j += kPlaceThreads) tbase[j] = tb.tstart[(size_t)(jb0 + j) * tb.nch + c];
+    for (int j = tid; j < nbg; j += kPlaceThreads) {
+        tbase[j] = tb.tstart[(size_t)(jb0 + j) * tb.nch + c];
+        xbase[j] = tb.xstart[(size_t)c * tb.nblk + jb0 + j];
+    }
+    uint8_t *T8 = reinterpret_cast<uint8_t *>(T);
+    // entry w of segment j, written on its own (the slow way): 3 bytes of T, 2 of R
+    auto put_entry = [&](uint32_t j, uint32_t w, uint32_t tuple) {
+        const uint32_t col = tuple & cmask, row = tuple >> tb.cb;
+        uint8_t *t3 = T8 + (tbase[j] + w) * 3ull;
+        t3[0] = (uint8_t)col; t3[1] = (uint8_t)(col >> 8); t3[2] = (uint8_t)(col >> 16);
+        R[xbase[j] + w] = (uint16_t)(row >= (uint32_t)kSliceRows ? 0x8000u : row);
+    };
     for (int part = 0; part < 2; ++part) {                      // 0: regular slices, 1: hub shares
         const int count = part == 0 ? nsl_c : nvs;
         const int np = part == 0 ? tb.npr : tb.nps;
@@ -752,7 +766,7 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
                 const uint32_t w = atomicAdd(&cur[sl * nbg + j], 1u);
                 const uint32_t tuple = ((u >> (tb.cb + tb.gb)) << tb.cb) | (u & cmask);
                 if (staged) stage[w] = tuple;
-                else T[tbase[j] + w] = tuple;
+                else put_entry(j, w, tuple);
             };
             for (int z0 = wave; z0 < nruns; z0 += kNW * kRU) {
                 uint32_t u[kRU][kXU], len[kRU], sl[kRU];
@@ -785,17 +799,37 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
             }
             __syncthreads();
             if (staged) {
-                for (int j = wave; j < nbg; j += kNW) {         // a piece per wavefront
-                    const uint32_t a = joff[j], len = joff[j + 1] - a;
-                    uint32_t *out = T + tbase[j] + s0[j];
-#pragma unroll 4
-                    for (uint32_t z = lane; z < len; z += 64) __builtin_nontemporal_store(stage[a + z], out + z);
+                // a piece per wavefront, four tuples (12 bytes of T, 8 of R) per lane; starts and lengths are
+                // multiples of 4 tuples
+                for (int j = wave; j < nbg; j += kNW) {
+                    const uint32_t a = joff[j], len4 = (joff[j + 1] - a) >> 2;
+                    uint32_t *outT = T + ((tbase[j] + s0[j]) >> 2) * 3ull;
+                    uint32_t *outR = reinterpret_cast<uint32_t *>(R + xbase[j] + s0[j]);
+                    for (uint32_t z = lane; z < len4; z += 64) {
+                        uint32_t col[4], row[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const uint32_t tuple = stage[a + 4 * z + q];
+                            col[q] = tuple & cmask;
+                            const uint32_t r = tuple >> tb.cb;
+                            row[q] = r >= (uint32_t)kSliceRows ? 0x8000u : r;
+                        }
+                        u32x3a t3;
+                        t3.x = col[0] | (col[1] << 24);
+                        t3.y = (col[1] >> 8) | (col[2] << 16);
+                        t3.z = (col[2] >> 16) | (col[3] << 8);
+                        __builtin_nontemporal_store(t3, reinterpret_cast<u32x3a *>(outT + 3 * z));
+                        u32x2 r2;
+                        r2.x = row[0] | (row[1] << 16);
+                        r2.y = row[2] | (row[3] << 16);
+                        __builtin_nontemporal_store(r2, reinterpret_cast<u32x2 *>(outR + 2 * z));
+                    }
                 }
             } else {
                 for (int z = tid; z < nb * nbg; z += kPlaceThreads) {
                     const int t = z / nbg, j = z % nbg;
                     const uint32_t end = sub[(size_t)(i0 + t + 1) * tb.nblk + j];
-                    if (cur[z] < end) T[tbase[j] + cur[z]] = pad;
+                    for (uint32_t w = cur[z]; w < end; ++w) put_entry((uint32_t)j, w, pad);
                 }
             }
             i0 += nb;
@@ -807,15 +841,24 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
 // look-up (phase 1 of the score): the tuples of the column blocks of chunk `c0 + blockIdx.y`,
 // restricted to row chunks >= cmin, get their labels.  Workgroup blockIdx.x handles share
 // (blockIdx.x % spb) of block (blockIdx.x / spb) of the chunk.
+//   T  (read)   : the column in its block of every tuple, 3 bytes each, segments ordered (jb, c')
+//   Lx (written): the label of every tuple, 4 bits each, segments ordered (c', jb)
+//   R           : the row field of every tuple (0x8000: padding), 16 bits each, ordered like Lx; written
+//                 once by the re-layout
 //   FROM_LDS = true : the block's labels are copied to LDS, two per byte (every vertex of the
 //                     block is assigned: the chunk has just been relabelled)
-//   FROM_LDS = false: labels are read from global memory and may be unassigned (bit 15 set);
-//                     used once, for the initial labels of a seeded run
-// X entry: row field << 4 | label; the pad tuples' row field 2048 sets bit 15 by itself.
+//   FROM_LDS = false: labels are read from global memory and may be unassigned; used once, for the
+//                     initial labels of a seeded run
+//   WRITE_R         : seeded runs only.  Their first pass reads the row fields from a copy Rdyn in
+//                     which bit 15 also marks tuples whose neighbour is unassigned: the initial
+//                     look-up (FROM_LDS = false) sets it, the first pass's look-ups clear it.
+// A thread takes 8 tuples at a time: 24 bytes of T, one 32-bit word of Lx (16 bytes of R / Rdyn).
 // ------------------------------------------------------------------------------------------------
-template <bool FROM_LDS>
+template <bool FROM_LDS, bool WRITE_R>
 __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__restrict__ T,
-                                                          uint16_t *__restrict__ X, TpTables tb,
+                                                          uint32_t *__restrict__ Lx,
+                                                          const uint16_t *__restrict__ R,
+                                                          uint16_t *__restrict__ Rdyn, TpTables tb,
                                                           const uint8_t *__restrict__ Lc, int64_t n, int c0,
                                                           int cmin, int spb) {
     extern __shared__ uint32_t tab[];      // 2^cb / 8 words (FROM_LDS)
@@ -841,27 +884,34 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
         while (a < b) { const int mid = (a + b) >> 1; if (ts[mid + 1] > p0) b = mid; else a = mid + 1; }
         cc = a;
     }
-    // The share's range [p0, p1) of T crosses a few segments (c', jb), each with its own place in X.
-    // Their ends and X offsets are fetched side by side, kSegBatch segments at a time, so that the
-    // stream over the tuples never waits for them: a thread walks its groups of four tuples in
+    // The share's range [p0, p1) of T crosses a few segments (c', jb), each with its own place in Lx.
+    // Their ends and offsets are fetched side by side, kSegBatch segments at a time, so that the
+    // stream over the tuples never waits for them: a thread walks its groups of eight tuples in
     // ascending order and steps to the next segment when it passes an end.  The first tuples are
     // requested before the label table is built, so that the two latencies overlap.
     constexpr int kSegBatch = 64;
-    constexpr int U = 4;
+    constexpr int U = 2;
     __shared__ u64 s_end[kSegBatch];        // end of segment cc + i in T, cut at p1
-    __shared__ u64 s_xoff[kSegBatch];       // its start in X minus its start in T
-    u32x4 t[U];
+    __shared__ u64 s_xoff[kSegBatch];       // its start in Lx minus its start in T (in tuples)
+    u32x3a t[U][2];
+    auto load_groups = [&](u64 from, uint32_t ng, uint32_t base) {
+        const uint32_t *src = T + (from >> 2) * 3ull;       // `from` is a multiple of 8 tuples
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t gi = base + u * kTpThreads;
+            t[u][0] = (u32x3a){0u, 0u, 0u};
+            t[u][1] = (u32x3a){0u, 0u, 0u};
+            if (gi < ng) {
+                t[u][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x3a *>(src + 6ull * gi));
+                t[u][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x3a *>(src + 6ull * gi + 3));
+            }
+        }
+    };
     {
         const int cend = cc + kSegBatch < tb.nch ? cc + kSegBatch : tb.nch;
         u64 pe = ts[cend];
         if (pe > p1) pe = p1;
-        const uint32_t ng = (uint32_t)((pe - p0) >> 2);
-        const u32x4 *src4 = reinterpret_cast<const u32x4 *>(T + p0);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t gi = tid + u * kTpThreads;
-            t[u] = gi < ng ? __builtin_nontemporal_load(src4 + gi) : (u32x4)(0u);
-        }
+        load_groups(p0, (uint32_t)((pe - p0) >> 3), (uint32_t)tid);
     }
 
     if (FROM_LDS) {
@@ -907,42 +957,51 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
         }
         __syncthreads();                    // also: the label table is complete
         const u64 pe = s_end[kSegBatch - 1];
-        const u32x4 *src4 = reinterpret_cast<const u32x4 *>(T + p);
-        const uint32_t ng = (uint32_t)((pe - p) >> 2);
+        const uint32_t ng = (uint32_t)((pe - p) >> 3);
         int si = 0;
         for (uint32_t base = tid; base < ng; base += kTpThreads * U) {
-            if (!(first && base == (uint32_t)tid)) {        // (the batch's first turn is already on its way)
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t gi = base + u * kTpThreads;
-                    t[u] = gi < ng ? __builtin_nontemporal_load(src4 + gi) : (u32x4)(0u);
-                }
-            }
+            if (!(first && base == (uint32_t)tid)) load_groups(p, ng, base);    // (the first turn is on its way)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const uint32_t gi = base + u * kTpThreads;
                 if (gi < ng) {
-                    const u64 pos = p + ((u64)gi << 2);
+                    const u64 pos = p + ((u64)gi << 3);
                     while (pos >= s_end[si]) ++si;          // s_end[kSegBatch - 1] = pe > pos
-                    const uint32_t ent[4] = {t[u].x, t[u].y, t[u].z, t[u].w};
-                    uint32_t o[4];
+                    const u64 q = s_xoff[si] + pos;         // the group's place in Lx / R (a multiple of 8)
+                    uint32_t col[8];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const uint32_t col = ent[q] & cmask;
+                    for (int h = 0; h < 2; ++h) {
+                        const u32x3a d = t[u][h];
+                        // (masked: the few slots between a segment's last tuple and its end hold anything)
+                        col[4 * h + 0] = d.x & cmask;
+                        col[4 * h + 1] = ((d.x >> 24) | (d.y << 8)) & cmask;
+                        col[4 * h + 2] = ((d.y >> 16) | (d.z << 16)) & cmask;
+                        col[4 * h + 3] = (d.z >> 8) & cmask;
+                    }
+                    uint32_t word = 0, unassigned = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
                         uint32_t lab;
                         if (FROM_LDS) {
-                            lab = ((uint32_t)tbytes[col >> 1] >> (4 * (col & 1u))) & 15u;
+                            lab = ((uint32_t)tbytes[col[e] >> 1] >> (4 * (col[e] & 1u))) & 15u;
                         } else {
-                            const int64_t v = block_lo + (int64_t)col;
+                            const int64_t v = block_lo + (int64_t)col[e];
                             const uint32_t l = v < chunk_hi ? (uint32_t)Lc[v] : 0xFFu;
-                            lab = l == 0xFFu ? 0x8000u : (l & 15u);
+                            if (l == 0xFFu) unassigned |= 1u << e;
+                            lab = l & 15u;
                         }
-                        o[q] = (((ent[q] >> tb.cb) << 4) | lab) & 0xFFFFu;
+                        word |= lab << (4 * e);
                     }
-                    u32x2 w;
-                    w.x = o[0] | (o[1] << 16);
-                    w.y = o[2] | (o[3] << 16);
-                    __builtin_nontemporal_store(w, reinterpret_cast<u32x2 *>(X + s_xoff[si] + pos));
+                    __builtin_nontemporal_store(word, Lx + (q >> 3));
+                    if (WRITE_R) {
+                        const u32x4 r = *reinterpret_cast<const u32x4 *>(R + q);
+                        u32x4 o;
+                        o.x = r.x | ((unassigned & 1u) << 15) | ((unassigned & 2u) << 30);
+                        o.y = r.y | ((unassigned & 4u) << 13) | ((unassigned & 8u) << 28);
+                        o.z = r.z | ((unassigned & 16u) << 11) | ((unassigned & 32u) << 26);
+                        o.w = r.w | ((unassigned & 64u) << 9) | ((unassigned & 128u) << 24);
+                        *reinterpret_cast<u32x4 *>(Rdyn + q) = o;
+                    }
                 }
             }
         }
@@ -952,13 +1011,6 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
     }
 }
 
-
-
-// Look-up results of NB sub-segments, [s[b], s[b] + l[b]) (even starts and lengths, in 16-bit
-// units from Xc; s and l are the same in every lane), counted by one wavefront: lane i takes the
-// two entries at offset 2i of each, round after round, all NB loads of a round in flight together.
-// COUNT16: regular rows, 16-bit counters, index = entry; else hub share, 32-bit counters, index =
-// hub * k + label.  Entries with bit 15 set are ignored.
 // The value of lane (l ^ 1) (CTRL = 0xB1: quad_perm [1,0,3,2]) or (l ^ 2) (0x4E: [2,3,0,1]) of the
 // lane's quad, by a data-parallel-primitive move instead of a trip through the LDS crossbar.
 template <int CTRL>
@@ -966,70 +1018,84 @@ __device__ __forceinline__ uint32_t quad_swap(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 
-// Counting the entries of sub-segments of X.  A sub-segment holds some 70 entries, so a whole
+// Counting the tuples of sub-segments: row fields from R (16 bits each, 0x8000 and above: not to be
+// counted), labels from Lx (4 bits each).  A sub-segment holds some 70 tuples, so a whole
 // wavefront on one of them would leave half its lanes idle: a QUARTER of the wavefront takes one,
-// six entries (three dwords) per lane, which covers 96 entries at once; longer ones take further
-// turns.  x < 0x8000: entry (row field << 4 | label) is counted; else it is padding or an
-// unassigned neighbour.
-typedef uint32_t u32x3a __attribute__((ext_vector_type(3), aligned(4)));
+// six tuples (12 bytes of R, 3 of Lx) per lane, which covers 96 at once; longer ones take further
+// turns.
+typedef uint32_t u32a1 __attribute__((aligned(1)));      // four bytes at any address
 
+struct TpSix {
+    u32x3a rows;        // six row fields
+    uint32_t labels;    // six labels in the low 24 bits
+};
+
+// The six tuples of a sub-segment from tuple `off` (a multiple of 6, below its length) on.  The
+// loads may reach 8 bytes (R) or 3 bytes (Lx) past the sub-segment: the arrays have that much
+// slack; what lies past the end is not counted.
+__device__ __forceinline__ TpSix tp_load_six(const uint32_t *__restrict__ R32, const uint8_t *__restrict__ Lx8,
+                                             uint32_t start, uint32_t off) {
+    TpSix x;
+    const uint32_t at = (start + off) >> 1;        // start and off are even
+    x.rows = __builtin_nontemporal_load(reinterpret_cast<const u32x3a *>(R32 + at));
+    x.labels = *reinterpret_cast<const u32a1 *>(Lx8 + at);
+    return x;
+}
+
+// one tuple: row field r (16 bits), label lab (4 bits)
 template <bool COUNT16>
-__device__ __forceinline__ void tp_count_dword(uint32_t w, bool valid, int k, uint32_t *hist) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const uint32_t x = h == 0 ? (w & 0xFFFFu) : (w >> 16);
-        if (COUNT16) {
-            // no branch: what is not to be counted adds zero (to a counter its bits happen to name)
-            const uint32_t one = (valid && x < 0x8000u) ? 1u : 0u;
-            atomicAdd(&hist[(x >> 1) & 0x3FFFu], one << ((x & 1u) << 4));
-        } else if (valid && x < 0x8000u) {
-            atomicAdd(&hist[(x >> 4) * (uint32_t)k + (x & 15u)], 1u);
-        }
+__device__ __forceinline__ void tp_count_one(uint32_t r, uint32_t lab, bool valid, int k, uint32_t *hist) {
+    const uint32_t x = (r << 4) | lab;                  // >= 0x8000: padding or an unassigned neighbour
+    if (COUNT16) {
+        // no branch: what is not to be counted adds zero (to a counter its bits happen to name)
+        const uint32_t one = (valid && x < 0x8000u) ? 1u : 0u;
+        atomicAdd(&hist[(x >> 1) & 0x3FFFu], one << ((x & 1u) << 4));
+    } else if (valid && x < 0x8000u) {
+        atomicAdd(&hist[r * (uint32_t)k + lab], 1u);
     }
 }
 
-// The six entries (three dwords) of a sub-segment of `len` entries from entry `off` (a multiple of
-// 6, below len) on.  The load may reach 8 bytes past the sub-segment: X has that much slack; what
-// lies past the end is not counted.
-__device__ __forceinline__ u32x3a tp_load_six(const uint32_t *__restrict__ Xc32, uint32_t start, uint32_t off) {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x3a *>(Xc32 + ((start + off) >> 1)));
-}
-
 template <bool COUNT16>
-__device__ __forceinline__ void tp_count_six(const u32x3a &w, uint32_t rem, int k, uint32_t *hist) {
-    tp_count_dword<COUNT16>(w.x, true, k, hist);
-    tp_count_dword<COUNT16>(w.y, rem > 2, k, hist);
-    tp_count_dword<COUNT16>(w.z, rem > 4, k, hist);
+__device__ __forceinline__ void tp_count_six(const TpSix &x, uint32_t rem, int k, uint32_t *hist) {
+    const uint32_t w[3] = {x.rows.x, x.rows.y, x.rows.z};
+#pragma unroll
+    for (int d = 0; d < 3; ++d) {
+        const bool valid = rem > 2u * d;                // rem is even
+        tp_count_one<COUNT16>(w[d] & 0xFFFFu, (x.labels >> (8 * d)) & 15u, valid, k, hist);
+        tp_count_one<COUNT16>(w[d] >> 16, (x.labels >> (8 * d + 4)) & 15u, valid, k, hist);
+    }
 }
 
 // The sub-segments a wavefront owns, 4 * NBQ at a time: lane t of (s0, l0) holds start and length
-// (both even) of the t-th of them, t < tmax <= 64.  All loads of a turn are issued before the first
-// entry is counted.
+// (multiples of 4) of the t-th of them, t < tmax <= 64.  All loads of a turn are issued before the
+// first tuple is counted.
 template <bool COUNT16, int NBQ>
-__device__ __forceinline__ void tp_count_list(const uint32_t *__restrict__ Xc32, uint32_t s0, uint32_t l0,
-                                              int tmax, int lane, int k, uint32_t *hist) {
+__device__ __forceinline__ void tp_count_list(const uint32_t *__restrict__ R32, const uint8_t *__restrict__ Lx8,
+                                              uint32_t s0, uint32_t l0, int tmax, int lane, int k,
+                                              uint32_t *hist) {
     const int quarter = lane >> 4;
     const uint32_t off = 6u * (uint32_t)(lane & 15);
     for (int t = 0; t < tmax; t += 4 * NBQ) {
         uint32_t st[NBQ], ln[NBQ];
-        u32x3a w[NBQ];
+        TpSix w[NBQ];
 #pragma unroll
         for (int b = 0; b < NBQ; ++b) {
             const int tq = t + 4 * b + quarter;
             st[b] = (uint32_t)__shfl((int)s0, tq & 63);
             ln[b] = (uint32_t)__shfl((int)l0, tq & 63);
             if (tq >= tmax) ln[b] = 0;
-            w[b] = (u32x3a){0u, 0u, 0u};
-            if (off < ln[b]) w[b] = tp_load_six(Xc32, st[b], off);
+            w[b].rows = (u32x3a){0u, 0u, 0u};
+            w[b].labels = 0;
+            if (off < ln[b]) w[b] = tp_load_six(R32, Lx8, st[b], off);
         }
 #pragma unroll
         for (int b = 0; b < NBQ; ++b)
             if (off < ln[b]) tp_count_six<COUNT16>(w[b], ln[b] - off, k, hist);
 #pragma unroll
-        for (int b = 0; b < NBQ; ++b) {         // the rare sub-segment of more than 96 entries
+        for (int b = 0; b < NBQ; ++b) {         // the rare sub-segment of more than 96 tuples
             for (uint32_t r = 96; __any(r < ln[b]); r += 96) {
                 if (r + off < ln[b]) {
-                    const u32x3a v = tp_load_six(Xc32, st[b], r + off);
+                    const TpSix v = tp_load_six(R32, Lx8, st[b], r + off);
                     tp_count_six<COUNT16>(v, ln[b] - (r + off), k, hist);
                 }
             }
@@ -1068,7 +1134,8 @@ __device__ __forceinline__ void tp_hub_offsets(const TpTables &tb, const u64 *__
 // ------------------------------------------------------------------------------------------------
 template <typename RowT, typename ET>
 __global__ __launch_bounds__(kTpThreads) void k_tp_score(
-    const RowT *__restrict__ rowptr, const uint16_t *__restrict__ X, TpTables tb, SweepPlan pl,
+    const RowT *__restrict__ rowptr, const uint16_t *__restrict__ R, const uint32_t *__restrict__ Lx,
+    TpTables tb, SweepPlan pl,
     const uint8_t *__restrict__ Lc, const long long *__restrict__ S, ET *__restrict__ E,
     uint32_t *__restrict__ Hhub, uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
     long long *__restrict__ room_out, int c, int64_t chunk_lo, int64_t chunk_hi, int k, int jlim,
@@ -1124,7 +1191,8 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
 
     const u64 *xs = tb.xstart + (size_t)c * tb.nblk;
     const u64 xs0 = xs[0];
-    const uint32_t *Xc32 = reinterpret_cast<const uint32_t *>(X + xs0);     // xs0 is a multiple of 8
+    const uint32_t *R32 = reinterpret_cast<const uint32_t *>(R + xs0);      // xs0 is a multiple of 8
+    const uint8_t *Lx8 = reinterpret_cast<const uint8_t *>(Lx) + (xs0 >> 1);
     // hub sub-segments: blocks cls + ncls * m < jlim; their offsets are fetched now, counted last
     const uint32_t *hq0 = tb.subH + ((size_t)c * (tb.nsl + 1) + share) * tb.nblk;
     const int mlim = (any_hub && jlim > cls) ? (jlim - cls + ncls - 1) / ncls : 0;
@@ -1144,7 +1212,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
             }
             int tmax = (jlim - base - wave + NW - 1) / NW;      // blocks of this wave in this round
             if (tmax > 64) tmax = 64;
-            tp_count_list<true, 4>(Xc32, s0, l0, tmax, lane, k, hist);
+            tp_count_list<true, 4>(R32, Lx8, s0, l0, tmax, lane, k, hist);
         }
     }
     if (any_hub) {
@@ -1153,7 +1221,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
             if (base > 0) tp_hub_offsets(tb, xs, xs0, hq0, cls, ncls, mlim, base + wave + NW * lane, &s0, &l0);
             int tmax = (mlim - base - wave + NW - 1) / NW;
             if (tmax > 64) tmax = 64;
-            tp_count_list<false, 2>(Xc32, s0, l0, tmax, lane, k, hhist);
+            tp_count_list<false, 2>(R32, Lx8, s0, l0, tmax, lane, k, hhist);
         }
     }
     __syncthreads();
