@@ -650,7 +650,7 @@ __global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb, u64 *__r
 constexpr int kPlaceThreads = 512;
 
 template <typename RowT>
-__global__ __launch_bounds__(kPlaceThreads) __attribute__((amdgpu_waves_per_eu(6, 6))) void k_tp_place(const RowT *__restrict__ rowptr, int64_t n,
+__global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restrict__ rowptr, int64_t n,
                                                             SweepPlan pl, TpTables tb,
                                                             const uint32_t *__restrict__ U,
                                                             const uint32_t *__restrict__ Uh,
@@ -672,7 +672,7 @@ __global__ __launch_bounds__(kPlaceThreads) __attribute__((amdgpu_waves_per_eu(6
     uint32_t *cur = s0 + nbg;                                   // batch * nbg  next free slot (in stage)
     uint32_t *stage = cur + batch * nbg;                        // cap
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    constexpr int kNW = kPlaceThreads / 64, kRU = 8, kXU = 3;
+    constexpr int kNW = kPlaceThreads / 64, kRU = 4, kXU = 3;
     const int64_t chunk_lo = (int64_t)c * tb.chunk;
     const int64_t chunk_hi = (chunk_lo + tb.chunk < n) ? chunk_lo + tb.chunk : n;
     const int nsl_c = (int)((chunk_hi - chunk_lo + kSliceRows - 1) / kSliceRows);
@@ -890,7 +890,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
     // ascending order and steps to the next segment when it passes an end.  The first tuples are
     // requested before the label table is built, so that the two latencies overlap.
     constexpr int kSegBatch = 64;
-    constexpr int U = 2;
+    constexpr int U = 1;
     __shared__ u64 s_end[kSegBatch];        // end of segment cc + i in T, cut at p1
     __shared__ u64 s_xoff[kSegBatch];       // its start in Lx minus its start in T (in tuples)
     u32x3a t[U][2];
