@@ -689,7 +689,7 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
         const uint32_t col = tuple & cmask, row = tuple >> tb.cb;
         uint8_t *t3 = T8 + (tbase[j] + w) * 3ull;
         t3[0] = (uint8_t)col; t3[1] = (uint8_t)(col >> 8); t3[2] = (uint8_t)(col >> 16);
-        R[xbase[j] + w] = (uint16_t)(row >= (uint32_t)kSliceRows ? 0x8000u : row);
+        R[xbase[j] + w] = (uint16_t)(row >= (uint32_t)kSliceRows ? 0x8000u : row << 4);
     };
     for (int part = 0; part < 2; ++part) {                      // 0: regular slices, 1: hub shares
         const int count = part == 0 ? nsl_c : nvs;
@@ -812,7 +812,7 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
                             const uint32_t tuple = stage[a + 4 * z + q];
                             col[q] = tuple & cmask;
                             const uint32_t r = tuple >> tb.cb;
-                            row[q] = r >= (uint32_t)kSliceRows ? 0x8000u : r;
+                            row[q] = r >= (uint32_t)kSliceRows ? 0x8000u : r << 4;
                         }
                         u32x3a t3;
                         t3.x = col[0] | (col[1] << 24);
@@ -843,7 +843,7 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
 // (blockIdx.x % spb) of block (blockIdx.x / spb) of the chunk.
 //   T  (read)   : the column in its block of every tuple, 3 bytes each, segments ordered (jb, c')
 //   Lx (written): the label of every tuple, 4 bits each, segments ordered (c', jb)
-//   R           : the row field of every tuple (0x8000: padding), 16 bits each, ordered like Lx; written
+//   R           : the row field of every tuple << 4 (0x8000: padding), 16 bits each, ordered like Lx; written
 //                 once by the re-layout
 //   FROM_LDS = true : the block's labels are copied to LDS, two per byte (every vertex of the
 //                     block is assigned: the chunk has just been relabelled)
@@ -1018,8 +1018,8 @@ __device__ __forceinline__ uint32_t quad_swap(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 
-// Counting the tuples of sub-segments: row fields from R (16 bits each, 0x8000 and above: not to be
-// counted), labels from Lx (4 bits each).  A sub-segment holds some 70 tuples, so a whole
+// Counting the tuples of sub-segments: row fields (<< 4) from R (16 bits each, 0x8000 and above: not to
+// be counted), labels from Lx (4 bits each).  A sub-segment holds some 70 tuples, so a whole
 // wavefront on one of them would leave half its lanes idle: a QUARTER of the wavefront takes one,
 // six tuples (12 bytes of R, 3 of Lx) per lane, which covers 96 at once; longer ones take further
 // turns.
@@ -1042,16 +1042,16 @@ __device__ __forceinline__ TpSix tp_load_six(const uint32_t *__restrict__ R32, c
     return x;
 }
 
-// one tuple: row field r (16 bits), label lab (4 bits)
+// one tuple: r = its 16 bits of R (row field << 4, or something >= 0x8000), label lab (4 bits)
 template <bool COUNT16>
 __device__ __forceinline__ void tp_count_one(uint32_t r, uint32_t lab, bool valid, int k, uint32_t *hist) {
-    const uint32_t x = (r << 4) | lab;                  // >= 0x8000: padding or an unassigned neighbour
+    const uint32_t x = r | lab;                         // >= 0x8000: padding or an unassigned neighbour
     if (COUNT16) {
         // no branch: what is not to be counted adds zero (to a counter its bits happen to name)
         const uint32_t one = (valid && x < 0x8000u) ? 1u : 0u;
         atomicAdd(&hist[(x >> 1) & 0x3FFFu], one << ((x & 1u) << 4));
     } else if (valid && x < 0x8000u) {
-        atomicAdd(&hist[r * (uint32_t)k + lab], 1u);
+        atomicAdd(&hist[(r >> 4) * (uint32_t)k + lab], 1u);
     }
 }
 
