@@ -918,22 +918,39 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
         const int64_t bv = (chunk_hi - block_lo) < (1ll << tb.cb) ? (chunk_hi - block_lo) : (1ll << tb.cb);
         const int words = (int)((bv + 7) >> 3);
         const uint8_t *src = Lc + block_lo;
-        const bool aligned = (((uintptr_t)src) & 7u) == 0;
-        for (int w = tid; w < words; w += kTpThreads) {
-            uint32_t packed = 0;
-            if (aligned && (int64_t)w * 8 + 8 <= bv) {
-                const u32x2 v = *reinterpret_cast<const u32x2 *>(src + (size_t)w * 8);
-                const uint32_t a = v.x, b = v.y;
-                const uint32_t p = (a & 15u) | ((a >> 4) & 0xF0u) | ((a >> 8) & 0xF00u) | ((a >> 12) & 0xF000u);
-                const uint32_t q = (b & 15u) | ((b >> 4) & 0xF0u) | ((b >> 8) & 0xF00u) | ((b >> 12) & 0xF000u);
-                packed = p | (q << 16);
-            } else {
+        const bool aligned = (((uintptr_t)src) & 15u) == 0;
+        auto pack4 = [](uint32_t a) {       // four labels, one per byte -> 16 bits
+            return (a & 15u) | ((a >> 4) & 0xF0u) | ((a >> 8) & 0xF00u) | ((a >> 12) & 0xF000u);
+        };
+        if (aligned && bv == (1ll << tb.cb) && (words % (2 * kTpThreads)) == 0) {
+            // a whole block at a 16-byte boundary (the usual case): 16 labels per load, all loads of a
+            // thread side by side
+            constexpr int kFill = 8;
+            const int per = words / (2 * kTpThreads);          // 16-label pieces per thread
+            for (int i0 = 0; i0 < per; i0 += kFill) {
+                u32x4 v[kFill];
+#pragma unroll
+                for (int i = 0; i < kFill; ++i)
+                    if (i0 + i < per)
+                        v[i] = *reinterpret_cast<const u32x4 *>(src + ((size_t)(i0 + i) * kTpThreads + tid) * 16);
+#pragma unroll
+                for (int i = 0; i < kFill; ++i)
+                    if (i0 + i < per) {
+                        u32x2 o;
+                        o.x = pack4(v[i].x) | (pack4(v[i].y) << 16);
+                        o.y = pack4(v[i].z) | (pack4(v[i].w) << 16);
+                        *reinterpret_cast<u32x2 *>(tab + 2 * ((size_t)(i0 + i) * kTpThreads + tid)) = o;
+                    }
+            }
+        } else {
+            for (int w = tid; w < words; w += kTpThreads) {
+                uint32_t packed = 0;
                 for (int q = 0; q < 8; ++q) {
                     const int64_t o = (int64_t)w * 8 + q;
                     if (o < bv) packed |= ((uint32_t)src[o] & 15u) << (4 * q);
                 }
+                tab[w] = packed;
             }
-            tab[w] = packed;
         }
     }
     const uint8_t *tbytes = reinterpret_cast<const uint8_t *>(tab);
