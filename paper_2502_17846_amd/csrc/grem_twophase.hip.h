@@ -9,21 +9,28 @@
 // chunk, by workgroups that hold those labels in LDS -- for every row that refers to them, in this
 // pass (rows of later chunks) or the next (rows of earlier chunks and of the chunk itself).
 //
-// How: once per call the CSR entries are re-laid-out into 32-bit tuples
-// (row_in_slice << cb | column_in_block), grouped by (column block, row chunk):
+// How: once per call the CSR entries are re-laid-out into tuples (row in slice, column in block),
+// grouped by (column block, row chunk):
 //   * a column block is 2^cb consecutive vertices counted from the start of their chunk;
 //   * a row slice is 2048 consecutive rows counted from the start of their chunk;
 //   * segment (c, jb) holds the entries of the rows of chunk c whose column lies in block jb:
 //     first the entries of the regular rows, slice by slice, then the entries of the chunk's
 //     high-degree rows ("hubs"), share by share (see below).
-// T (tuples) is ordered by (jb, c); X (16-bit look-up results, row_in_slice << 4 | label, which
-// is the index of the row's 16-bit counter of that label; bit 15 set = nothing to count) is
-// ordered by (c, jb); a segment occupies the same number of slots in both, padded to a multiple
-// of 8, and every sub-segment is padded to an even length.  After chunk c has been relabelled, k_tp_lookup streams the tuples of c's column
-// blocks (contiguous in T), looks the labels up in an LDS copy of the block's labels (two per
-// byte) and writes X (contiguous per segment).  Before chunk c is relabelled, k_tp_score has one
-// workgroup per row slice gather that slice's sub-segment from every segment (c, *) -- each a few
-// hundred bytes, contiguous -- into 16-bit LDS counters, then blends E and proposes.
+// A tuple lives in three streams, each with as few bytes as its reader needs:
+//   T  : its column in the block, 3 bytes, segments ordered (jb, c)   -- read by k_tp_lookup
+//   Lx : the label of that column, 4 bits, segments ordered (c, jb)   -- written by k_tp_lookup,
+//                                                                        read by k_tp_score
+//   R  : its row in the slice << 4, 16 bits (0x8000 = padding), ordered like Lx; written once by the
+//        re-layout, read by k_tp_score (R | label is the index of the row's 16-bit counter of that
+//        label)
+// A segment occupies the same number of slots in all three, padded to a multiple of 8; every
+// sub-segment is padded to a multiple of 4.  After chunk c has been relabelled, k_tp_lookup streams
+// the columns of c's column blocks (contiguous in T), looks the labels up in an LDS copy of the
+// block's labels (two per byte) and writes Lx (contiguous per segment).  Before chunk c is
+// relabelled, k_tp_score has one workgroup per row slice gather that slice's sub-segment from
+// every segment (c, *) -- each a few hundred bytes, contiguous -- into 16-bit LDS counters, then
+// blends E and proposes.  (Seeded runs: in their first pass a neighbour may be unassigned; the
+// score kernel then reads the row fields from a copy of R in which bit 15 marks such tuples.)
 //
 // Balance: rows of degree >= hub_degree are taken out of their slice.  Their entries,
 // concatenated in row order, are cut in equal shares (k_plan_chunks picks how many); every
@@ -41,11 +48,11 @@
 namespace grem {
 
 constexpr int kSliceRowBits = 11;
-constexpr int kSliceRows = 1 << kSliceRowBits;     // rows per slice (row index fits the X entry)
+constexpr int kSliceRows = 1 << kSliceRowBits;     // rows per slice (row index << 4 fits 15 bits of R)
 constexpr int kPlanThreads = 256;
 constexpr int kTpThreads = 1024;                   // k_tp_lookup and k_tp_score
 constexpr int kMaxBlocks = 4096;                   // column blocks (LDS tables in the re-layout kernels)
-constexpr int kMaxShareHubs = 2048;                // hubs one share may touch (index fits the X entry)
+constexpr int kMaxShareHubs = 2048;                // hubs one share may touch (index fits the row field)
 constexpr int kMaxColBits = 18;                    // 2^18 labels, two per byte: 128 KB of LDS
 
 typedef unsigned long long u64;
@@ -80,7 +87,7 @@ struct TpTables {
     uint32_t *subR;   // [nch * (nsl + 1)][nblk]: start of slice i's regular sub-segment inside segment
                       // (c, jb), row c * (nsl + 1) + i; row i = nsl: end of the regular part
     uint32_t *subH;   // same shape: start of share i's sub-segment; row nsl: end of the segment
-    u64 *xstart;      // [nch][nblk] (+1): first slot of segment (c, jb) in X
+    u64 *xstart;      // [nch][nblk] (+1): first slot of segment (c, jb) in Lx and R
     u64 *tstart;      // [nblk][nch] (+1): first slot of segment (c, jb) in T
     uint32_t *lo;     // [nch * nsl * npr][ngroups + 1]: start of block group g's run inside the unit's range of U
     uint32_t *loh;    // [nch * nsl * nps][ngroups + 1]: the same for the parts of the hub shares and Uh
@@ -595,8 +602,8 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
 
 // ------------------------------------------------------------------------------------------------
 // counts -> starts.  One thread per segment (c, jb): exclusive prefix over the slices of the
-// regular counts, then of the share counts, every count rounded up to even (sub-segments start on
-// 4-byte boundaries of X); the segment length, rounded up to a multiple of 8, goes to xstart and
+// regular counts, then of the share counts, every count rounded up to a multiple of 4 (four tuples
+// are 12 bytes of T, 8 of R, 2 of Lx: sub-segments start on 4-byte boundaries of T); the segment length, rounded up to a multiple of 8, goes to xstart and
 // tstart (each in its own order), to be scanned by k_tp_scan_segments.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_tp_scan_slices(TpTables tb) {
@@ -638,12 +645,13 @@ __global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb, u64 *__r
 
 // ------------------------------------------------------------------------------------------------
 // Re-layout, step 2: workgroup c * ngroups + g moves the runs of block group g of every unit of
-// chunk c from U (then Uh) to their sub-segments in T, `batch` slices (shares) at a time: the
-// sub-segments of consecutive slices are adjacent in T, so the tuples of a batch form one piece of
-// T per block of the group; the pieces are put together in LDS, pad tuples included (row field
-// 2048, which the look-up turns into an entry the score ignores; every odd sub-segment ends with
-// one), and written out contiguously.  A batch that does not fit `cap` slots is cut down to one
-// slice; a slice that does not fit is written tuple by tuple.
+// chunk c from U (then Uh) to their sub-segments, `batch` slices (shares) at a time: the
+// sub-segments of consecutive slices are adjacent, so the tuples of a batch form one piece per block
+// of the group; the pieces are put together in LDS, pad tuples included (row field 2048: the score
+// kernel ignores them; they fill every sub-segment up to a multiple of 4), and written out
+// contiguously, the columns (3 bytes each) to T, the row fields (16 bits each) to R.  A batch that
+// does not fit `cap` slots is cut down to one slice; a slice that does not fit is written tuple by
+// tuple.
 // LDS: tbase[nbg], xbase[nbg] (u64), runsrc[batch * npmax] (u64), runlen[batch * npmax + 1], runsl[batch * npmax],
 //      joff[nbg + 1], s0[nbg], cur[batch * nbg], stage[cap]
 // ------------------------------------------------------------------------------------------------
@@ -1120,7 +1128,7 @@ __device__ __forceinline__ void tp_count_list(const uint32_t *__restrict__ R32, 
     }
 }
 
-// start (in 16-bit units from the chunk's first slot of X) and length of the share's sub-segment of
+// start (in tuples from the chunk's first slot of Lx / R) and length of the share's sub-segment of
 // its ml-th block
 __device__ __forceinline__ void tp_hub_offsets(const TpTables &tb, const u64 *__restrict__ xs, u64 xs0,
                                                const uint32_t *__restrict__ q0, int cls, int ncls, int mlim,
@@ -1138,7 +1146,7 @@ __device__ __forceinline__ void tp_hub_offsets(const TpTables &tb, const u64 *__
 // ------------------------------------------------------------------------------------------------
 // score (phase 2): one workgroup per row slice of chunk c.  It counts the slice's sub-segment of
 // every column block in [0, jlim) (in the first pass of an unseeded run the blocks of chunks >= c
-// hold no label yet and their part of X has not been written), and, of hub share
+// hold no label yet and their part of Lx has not been written), and, of hub share
 // (blockIdx.x % nvs), the sub-segments of the blocks congruent to (blockIdx.x / nvs) modulo the
 // number of workgroups per share, so that the hub entries are spread evenly too.  Then it blends E,
 // proposes, and counts the movers of its two admission tiles per proposed partition (cnt, the input
@@ -1172,7 +1180,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     constexpr int NW = kTpThreads / 64;
     // Workgroups are dispatched round-robin over the 8 XCDs, each with its own L2: give XCD x a
     // contiguous range of slices, so that neighbouring slices, whose sub-segments share cache lines
-    // of X, meet in one L2.
+    // of R and Lx, meet in one L2.
     const unsigned xcd = blockIdx.x & 7u, turn = blockIdx.x >> 3;
     const unsigned slice = xcd * (gridDim.x >> 3) + (xcd < (gridDim.x & 7u) ? xcd : (gridDim.x & 7u)) + turn;
     const int64_t v0 = chunk_lo + (int64_t)slice * kSliceRows;
