@@ -20,9 +20,8 @@
 //   T  : its column in the block, 3 bytes, segments ordered (jb, c)   -- read by k_tp_lookup
 //   Lx : the label of that column, 4 bits, segments ordered (c, jb)   -- written by k_tp_lookup,
 //                                                                        read by k_tp_score
-//   R  : its row in the slice << 4, 16 bits (0x8000 = padding), ordered like Lx; written once by the
-//        re-layout, read by k_tp_score (R | label is the index of the row's 16-bit counter of that
-//        label)
+//   R  : its row in the slice << 5, 16 bits (bit 0 = padding), ordered like Lx; written once by the
+//        re-layout, read by k_tp_score (row << 5 is the byte offset of the row's 16-bit counters)
 // A segment occupies the same number of slots in all three, padded to a multiple of 8; every
 // sub-segment is padded to a multiple of 4.  After chunk c has been relabelled, k_tp_lookup streams
 // the columns of c's column blocks (contiguous in T), looks the labels up in an LDS copy of the
@@ -30,7 +29,7 @@
 // relabelled, k_tp_score has one workgroup per row slice gather that slice's sub-segment from
 // every segment (c, *) -- each a few hundred bytes, contiguous -- into 16-bit LDS counters, then
 // blends E and proposes.  (Seeded runs: in their first pass a neighbour may be unassigned; the
-// score kernel then reads the row fields from a copy of R in which bit 15 marks such tuples.)
+// score kernel then reads the row fields from a copy of R in which bit 0 marks such tuples.)
 //
 // Balance: rows of degree >= hub_degree are taken out of their slice.  Their entries,
 // concatenated in row order, are cut in equal shares (k_plan_chunks picks how many); every
@@ -48,7 +47,7 @@
 namespace grem {
 
 constexpr int kSliceRowBits = 11;
-constexpr int kSliceRows = 1 << kSliceRowBits;     // rows per slice (row index << 4 fits 15 bits of R)
+constexpr int kSliceRows = 1 << kSliceRowBits;     // rows per slice (row index << 5 fits the 16 bits of R)
 constexpr int kPlanThreads = 256;
 constexpr int kTpThreads = 1024;                   // k_tp_lookup and k_tp_score
 constexpr int kMaxBlocks = 4096;                   // column blocks (LDS tables in the re-layout kernels)
@@ -697,7 +696,7 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
         const uint32_t col = tuple & cmask, row = tuple >> tb.cb;
         uint8_t *t3 = T8 + (tbase[j] + w) * 3ull;
         t3[0] = (uint8_t)col; t3[1] = (uint8_t)(col >> 8); t3[2] = (uint8_t)(col >> 16);
-        R[xbase[j] + w] = (uint16_t)(row >= (uint32_t)kSliceRows ? 0x8000u : row << 4);
+        R[xbase[j] + w] = (uint16_t)(row >= (uint32_t)kSliceRows ? 1u : row << 5);
     };
     for (int part = 0; part < 2; ++part) {                      // 0: regular slices, 1: hub shares
         const int count = part == 0 ? nsl_c : nvs;
@@ -820,7 +819,7 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
                             const uint32_t tuple = stage[a + 4 * z + q];
                             col[q] = tuple & cmask;
                             const uint32_t r = tuple >> tb.cb;
-                            row[q] = r >= (uint32_t)kSliceRows ? 0x8000u : r << 4;
+                            row[q] = r >= (uint32_t)kSliceRows ? 1u : r << 5;
                         }
                         u32x3a t3;
                         t3.x = col[0] | (col[1] << 24);
@@ -851,14 +850,14 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
 // (blockIdx.x % spb) of block (blockIdx.x / spb) of the chunk.
 //   T  (read)   : the column in its block of every tuple, 3 bytes each, segments ordered (jb, c')
 //   Lx (written): the label of every tuple, 4 bits each, segments ordered (c', jb)
-//   R           : the row field of every tuple << 4 (0x8000: padding), 16 bits each, ordered like Lx; written
+//   R           : the row field of every tuple << 5 (bit 0: padding), 16 bits each, ordered like Lx; written
 //                 once by the re-layout
 //   FROM_LDS = true : the block's labels are copied to LDS, two per byte (every vertex of the
 //                     block is assigned: the chunk has just been relabelled)
 //   FROM_LDS = false: labels are read from global memory and may be unassigned; used once, for the
 //                     initial labels of a seeded run
 //   WRITE_R         : seeded runs only.  Their first pass reads the row fields from a copy Rdyn in
-//                     which bit 15 also marks tuples whose neighbour is unassigned: the initial
+//                     which bit 0 also marks tuples whose neighbour is unassigned: the initial
 //                     look-up (FROM_LDS = false) sets it, the first pass's look-ups clear it.
 // A thread takes 8 tuples at a time: 24 bytes of T, one 32-bit word of Lx (16 bytes of R / Rdyn).
 // ------------------------------------------------------------------------------------------------
@@ -1021,10 +1020,10 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
                     if (WRITE_R) {
                         const u32x4 r = *reinterpret_cast<const u32x4 *>(R + q);
                         u32x4 o;
-                        o.x = r.x | ((unassigned & 1u) << 15) | ((unassigned & 2u) << 30);
-                        o.y = r.y | ((unassigned & 4u) << 13) | ((unassigned & 8u) << 28);
-                        o.z = r.z | ((unassigned & 16u) << 11) | ((unassigned & 32u) << 26);
-                        o.w = r.w | ((unassigned & 64u) << 9) | ((unassigned & 128u) << 24);
+                        o.x = r.x | (unassigned & 1u) | ((unassigned & 2u) << 15);
+                        o.y = r.y | ((unassigned >> 2) & 1u) | ((unassigned & 8u) << 13);
+                        o.z = r.z | ((unassigned >> 4) & 1u) | ((unassigned & 32u) << 11);
+                        o.w = r.w | ((unassigned >> 6) & 1u) | ((unassigned & 128u) << 9);
                         *reinterpret_cast<u32x4 *>(Rdyn + q) = o;
                     }
                 }
@@ -1043,8 +1042,8 @@ __device__ __forceinline__ uint32_t quad_swap(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 
-// Counting the tuples of sub-segments: row fields (<< 4) from R (16 bits each, 0x8000 and above: not to
-// be counted), labels from Lx (4 bits each).  A sub-segment holds some 70 tuples, so a whole
+// Counting the tuples of sub-segments: row fields from R (16 bits each, bit 0 set: not to be
+// counted), labels from Lx (4 bits each).  A sub-segment holds some 70 tuples, so a whole
 // wavefront on one of them would leave half its lanes idle: a QUARTER of the wavefront takes one,
 // six tuples (12 bytes of R, 3 of Lx) per lane, which covers 96 at once; longer ones take further
 // turns.
@@ -1067,28 +1066,33 @@ __device__ __forceinline__ TpSix tp_load_six(const uint32_t *__restrict__ R32, c
     return x;
 }
 
-// one tuple: r = its 16 bits of R (row field << 4, or something >= 0x8000), label lab (4 bits)
-template <bool COUNT16>
-__device__ __forceinline__ void tp_count_one(uint32_t r, uint32_t lab, bool valid, int k, uint32_t *hist) {
-    const uint32_t x = r | lab;                         // >= 0x8000: padding or an unassigned neighbour
-    if (COUNT16) {
-        // no branch: what is not to be counted adds zero (to a counter its bits happen to name)
-        const uint32_t one = (valid && x < 0x8000u) ? 1u : 0u;
-        atomicAdd(&hist[(x >> 1) & 0x3FFFu], one << ((x & 1u) << 4));
-    } else if (valid && x < 0x8000u) {
-        atomicAdd(&hist[(r >> 4) * (uint32_t)k + lab], 1u);
+// The two tuples of one 32-bit word w of R; their labels are bits sh .. sh + 7 of `labels`; `on`:
+// the word lies inside the sub-segment.  16 bits of R: row field << 5 | skip (bit 0: padding, or an
+// unassigned neighbour), so row field << 5 is the byte offset of the row's 16 counters of 16 bits,
+// to which (label >> 1) << 2 adds the counter pair's; the label's bit 0 picks the half.
+template <bool COUNT16, int SH>
+__device__ __forceinline__ void tp_count_word(uint32_t w, uint32_t labels, bool on, int k, uint32_t *hist) {
+    const uint32_t live = on ? ~w : 0u;                 // bit 0 / bit 16: the tuple is to be counted
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t lab = (labels >> (SH + 4 * h)) & 15u;
+        const uint32_t r = h == 0 ? (w & 0xFFE0u) : ((w >> 16) & 0xFFE0u);
+        const uint32_t one = (live >> (16 * h)) & 1u;
+        if (COUNT16) {
+            // no branch: what is not to be counted adds zero (to a counter its bits happen to name)
+            uint32_t *ctr = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(hist) + (r | ((lab & 14u) << 1)));
+            atomicAdd(ctr, one << ((lab & 1u) << 4));
+        } else if (one) {
+            atomicAdd(&hist[(r >> 5) * (uint32_t)k + lab], 1u);
+        }
     }
 }
 
 template <bool COUNT16>
 __device__ __forceinline__ void tp_count_six(const TpSix &x, uint32_t rem, int k, uint32_t *hist) {
-    const uint32_t w[3] = {x.rows.x, x.rows.y, x.rows.z};
-#pragma unroll
-    for (int d = 0; d < 3; ++d) {
-        const bool valid = rem > 2u * d;                // rem is even
-        tp_count_one<COUNT16>(w[d] & 0xFFFFu, (x.labels >> (8 * d)) & 15u, valid, k, hist);
-        tp_count_one<COUNT16>(w[d] >> 16, (x.labels >> (8 * d + 4)) & 15u, valid, k, hist);
-    }
+    tp_count_word<COUNT16, 0>(x.rows.x, x.labels, true, k, hist);
+    tp_count_word<COUNT16, 8>(x.rows.y, x.labels, rem > 2, k, hist);        // rem is even
+    tp_count_word<COUNT16, 16>(x.rows.z, x.labels, rem > 4, k, hist);
 }
 
 // The sub-segments a wavefront owns, 4 * NBQ at a time: lane t of (s0, l0) holds start and length
