@@ -28,11 +28,11 @@ HBM_PEAK_GBPS = 8000.0
 # at that time, and `traffic` is reported as null when the sources have changed since.
 PMC = {
     "workload": "chunglu-111M",
-    "sources_sha256": "ffea15e26625e1c52595dcd77b6bf55709af81e4de2466f41f60f3b33596d46b",
+    "sources_sha256": "bc02145ee7f3bf144a723d263920eb67ac4c344022e00c73d74e6f566639d6ad",
     "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,590 KiB
     "write_factor": 1.0,        # 2 GiB written -> WRITE_SIZE 2,097,150 KiB
-    "fetch_kib": {"k_tp_score": 1.81051e7, "k_tp_lookup": 1.35281e7},
-    "write_kib": {"k_tp_score": 7.36998e6, "k_tp_lookup": 4.55347e6},
+    "fetch_kib": {"k_tp_score": 1.83156e+07, "k_tp_lookup": 1.3527e+07},
+    "write_kib": {"k_tp_score": 7.36998e+06, "k_tp_lookup": 4.55356e+06},
     "launches": {"k_tp_score": 318, "k_tp_lookup": 317},
 }
 
