@@ -62,6 +62,45 @@ def test_first_chunks_of_pass0_equal_the_oracle(graph):
     B.grem_set_histogram_mode(B.HIST_AUTO)
 
 
+def test_seeded_first_chunks_of_pass0_equal_the_oracle(graph):
+    # a tenth of all vertices start with a (random) label: in the first pass their rows keep it, and every
+    # other row counts them wherever they lie, while the rest of its neighbours further on are unassigned
+    g = graph
+    chunks = 2
+    rows = chunks * CHUNK
+    rng = np.random.default_rng(7)
+    seed = np.where(rng.random(g.n) < 0.1, rng.integers(0, K, g.n), -1).astype(np.int32)
+    print(f"[case] full-size seeded prefix parity, {chunks} chunks, {(seed >= 0).sum()} seeds", flush=True)
+    end = int(g.rowptr[rows].item())
+    rp = g.rowptr.cpu().numpy().copy()
+    rp[rows:] = end
+    ci = g.colidx[:end].cpu().numpy()
+    st = oracle.Stepper(rp, ci, g.n, K, SLACK, CHUNK, 0, seed_labels=seed)
+    for _ in range(chunks):
+        st.step()
+    olab, oest = st.labels()[:rows].copy(), st.estimates()[:rows].copy()
+    st.close()
+    seed_d = torch.as_tensor(seed).to(DEV)
+    lab, sizes, est = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 0, seed_d)
+    torch.cuda.synchronize()
+    assert np.array_equal(lab[:rows].cpu().numpy(), olab)
+    assert np.array_equal(est[:rows].cpu().numpy().view(np.uint32), oest)
+    keep = torch.as_tensor(seed >= 0).to(DEV)
+    assert torch.equal(lab[keep], seed_d[keep])         # a seeded vertex keeps its seed in the first pass
+    del lab, sizes, est
+    # one refinement pass on top: the two-phase path and the plain path agree on the whole seeded run
+    outs = []
+    for mode in (B.HIST_AUTO, B.HIST_LDS):
+        B.grem_set_histogram_mode(mode)
+        lab, sizes, _ = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 1, seed_d,
+                                               want_estimates=False)
+        torch.cuda.synchronize()
+        assert torch.equal(torch.bincount(lab, minlength=K), sizes)
+        outs.append(lab)
+    B.grem_set_histogram_mode(B.HIST_AUTO)
+    assert torch.equal(outs[0], outs[1])
+
+
 def test_three_pass_run_properties_and_path_agreement(graph):
     g = graph
     P = B.grem_capacity(g.n, K, SLACK)
