@@ -229,6 +229,11 @@ def test_chung_lu_medium():
 def test_chung_lu_auto_takes_two_phase_path():
     g = synth.chung_lu(6_000_000, 60_000_000, seed=1, device=DEV, rowptr_dtype=torch.int64, cap=30_000.0)
     _check(g, 16, 1.05, 1 << 19, 2)
+    # a chunk size that is no power of two (and no multiple of a slice or a column block), fewer partitions
+    _check(g, 12, 1.02, 777_777, 1, tag="ragged geometry")
+    rng = np.random.default_rng(11)
+    seed = np.where(rng.random(g.n) < 0.05, rng.integers(0, 8, g.n), -1).astype(np.int32)
+    _check(g, 8, 1.1, 500_000, 1, seed=seed, tag="seeded, two-phase by AUTO")
 
 
 def test_determinism_and_workspace():
