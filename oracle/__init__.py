@@ -1,4 +1,5 @@
-"""ctypes access to the GREM CPU oracle (``grem_oracle.c``).
+"""ctypes access to the GREM CPU oracles (``grem_oracle.c``: chunks of CSR rows, k-way;
+``grem_edge_oracle.c``: chunks of an edge list, two partitions).
 
 TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()`` and by the
 ``cpu_baseline`` leg of ``bench.py``.  The GPU package never imports this module and this module
@@ -14,6 +15,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "grem_oracle.c")
+_SRC_EDGE = os.path.join(_HERE, "grem_edge_oracle.c")
 _LIB = os.path.join(_HERE, "libgrem_oracle.so")
 
 OK = 0
@@ -28,9 +30,10 @@ class OracleError(RuntimeError):
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, single thread, no contraction of a*b+c)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_EDGE))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC, "-lm"]
+               "-o", _LIB, _SRC, _SRC_EDGE, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -67,6 +70,28 @@ def _load():
                                                  i32p, i32p, i64p, u32p]
     lib.grem_oracle_edge_cut.restype = ctypes.c_int64
     lib.grem_oracle_edge_cut.argtypes = [i64p, i32p, ctypes.c_int64, i32p]
+    f64p = ctypes.POINTER(ctypes.c_double)
+    lib.grem_edge_oracle_create.restype = ctypes.c_void_p
+    lib.grem_edge_oracle_create.argtypes = [i32p, i32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                            ctypes.c_int64, i32p, ctypes.c_int32,
+                                            ctypes.POINTER(ctypes.c_int)]
+    lib.grem_edge_oracle_destroy.restype = None
+    lib.grem_edge_oracle_destroy.argtypes = [ctypes.c_void_p]
+    lib.grem_edge_oracle_step.restype = ctypes.c_int
+    lib.grem_edge_oracle_step.argtypes = [ctypes.c_void_p]
+    for name, rt in (("grem_edge_oracle_parts", i32p), ("grem_edge_oracle_sizes", i64p),
+                     ("grem_edge_oracle_nbr_counts", f64p), ("grem_edge_oracle_next_chunk", ctypes.c_int64),
+                     ("grem_edge_oracle_chunk_count", ctypes.c_int64)):
+        getattr(lib, name).restype = rt
+        getattr(lib, name).argtypes = [ctypes.c_void_p]
+    lib.grem_edge_oracle_last_nodes.restype = ctypes.c_int64
+    lib.grem_edge_oracle_last_nodes.argtypes = [ctypes.c_void_p, ctypes.POINTER(i32p), ctypes.POINTER(i64p),
+                                                ctypes.POINTER(i32p)]
+    lib.grem_edge_oracle_run.restype = ctypes.c_int
+    lib.grem_edge_oracle_run.argtypes = [i32p, i32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                         ctypes.c_int64, i32p, ctypes.c_int32, i32p, i64p, f64p]
+    lib.grem_edge_oracle_cut.restype = ctypes.c_int64
+    lib.grem_edge_oracle_cut.argtypes = [i32p, i32p, ctypes.c_int64, i32p]
     _lib = lib
     return lib
 
@@ -160,6 +185,105 @@ class Stepper:
     def close(self):
         if self._h:
             self._lib.grem_oracle_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# --------------------------------------------------------------------------------------------
+# chunks of an edge list, two partitions (Alg. 1 in the paper's own stream model)
+# --------------------------------------------------------------------------------------------
+
+EDGE_REFINE, EDGE_FIXED = 0, 1
+
+
+def _edges(src, dst):
+    return np.ascontiguousarray(src, dtype=np.int32), np.ascontiguousarray(dst, dtype=np.int32)
+
+
+def edge_stream_bipartition(src, dst, n, c_size, P, seed_parts, mode=EDGE_REFINE, return_state: bool = False):
+    """parts (int32[n], -1 for nodes in no edge); with ``return_state`` also sizes (int64[2]) and
+    nbr_counts (float64[n,2])."""
+    lib = _load()
+    s, d = _edges(src, dst)
+    seed = np.ascontiguousarray(seed_parts, dtype=np.int32)
+    parts = np.empty(n, dtype=np.int32)
+    sizes = np.empty(2, dtype=np.int64) if return_state else None
+    est = np.empty((n, 2), dtype=np.float64) if return_state else None
+    rc = lib.grem_edge_oracle_run(_p(s, ctypes.c_int32), _p(d, ctypes.c_int32), s.size, n, c_size, P,
+                                  _p(seed, ctypes.c_int32), mode, _p(parts, ctypes.c_int32),
+                                  _p(sizes, ctypes.c_int64), _p(est, ctypes.c_double))
+    if rc != OK:
+        raise OracleError(rc)
+    if return_state:
+        return parts, sizes, est
+    return parts
+
+
+def edge_list_cut(src, dst, parts) -> int:
+    s, d = _edges(src, dst)
+    lab = np.ascontiguousarray(parts, dtype=np.int32)
+    return int(_load().grem_edge_oracle_cut(_p(s, ctypes.c_int32), _p(d, ctypes.c_int32), s.size,
+                                            _p(lab, ctypes.c_int32)))
+
+
+class EdgeStepper:
+    """The edge-chunk run one chunk at a time."""
+
+    def __init__(self, src, dst, n, c_size, P, seed_parts, mode=EDGE_REFINE):
+        self._lib = _load()
+        self._s, self._d = _edges(src, dst)           # keep alive: the state borrows them
+        self._seed = np.ascontiguousarray(seed_parts, dtype=np.int32)
+        self.n = n
+        status = ctypes.c_int(0)
+        self._h = self._lib.grem_edge_oracle_create(_p(self._s, ctypes.c_int32), _p(self._d, ctypes.c_int32),
+                                                    self._s.size, n, c_size, P,
+                                                    _p(self._seed, ctypes.c_int32), mode, ctypes.byref(status))
+        if not self._h:
+            raise OracleError(status.value)
+
+    def step(self) -> bool:
+        rc = self._lib.grem_edge_oracle_step(self._h)
+        if rc < 0:
+            raise OracleError(rc)
+        return rc == 1
+
+    @property
+    def next_chunk(self) -> int:
+        return int(self._lib.grem_edge_oracle_next_chunk(self._h))
+
+    @property
+    def chunk_count(self) -> int:
+        return int(self._lib.grem_edge_oracle_chunk_count(self._h))
+
+    def parts(self) -> np.ndarray:
+        return np.ctypeslib.as_array(self._lib.grem_edge_oracle_parts(self._h), shape=(self.n,)).copy()
+
+    def sizes(self) -> np.ndarray:
+        return np.ctypeslib.as_array(self._lib.grem_edge_oracle_sizes(self._h), shape=(2,)).copy()
+
+    def nbr_counts(self) -> np.ndarray:
+        return np.ctypeslib.as_array(self._lib.grem_edge_oracle_nbr_counts(self._h), shape=(self.n, 2)).copy()
+
+    def last_chunk(self):
+        """(nodes, fresh counts [c,2], proposals; -2 = not evaluated) of the chunk just processed."""
+        i32p, i64p = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+        nodes, fresh, prop = i32p(), i64p(), i32p()
+        c = int(self._lib.grem_edge_oracle_last_nodes(self._h, ctypes.byref(nodes), ctypes.byref(fresh),
+                                                      ctypes.byref(prop)))
+        if c == 0:
+            return np.empty(0, np.int32), np.empty((0, 2), np.int64), np.empty(0, np.int32)
+        return (np.ctypeslib.as_array(nodes, shape=(c,)).copy(),
+                np.ctypeslib.as_array(fresh, shape=(c, 2)).copy(),
+                np.ctypeslib.as_array(prop, shape=(c,)).copy())
+
+    def close(self):
+        if self._h:
+            self._lib.grem_edge_oracle_destroy(self._h)
             self._h = None
 
     def __del__(self):

@@ -304,3 +304,65 @@ def to_numpy(g: Graph) -> Graph:
         return g
     return Graph(g.rowptr.cpu().numpy(), g.colidx.cpu().numpy(), g.n, g.nnz, g.directed_edges,
                  None if g.planted is None else g.planted.cpu().numpy(), g.name)
+
+
+# --------------------------------------------------------------------------------------------
+# edge lists in random order (the partitioner's input as the paper states it, Sec. 4.1)
+# --------------------------------------------------------------------------------------------
+
+@dataclass
+class EdgeStream:
+    src: object      # (m,) int32; numpy array or torch tensor
+    dst: object      # (m,) int32
+    n: int
+    m: int
+    name: str = ""
+
+
+def edge_stream(g: Graph, seed: int = 0) -> EdgeStream:
+    """Every undirected edge of a symmetric CSR once, in random order and with a random orientation.
+    Works on numpy- and torch-backed graphs (the result lives where the graph does)."""
+    if isinstance(g.rowptr, np.ndarray):
+        rng = np.random.default_rng(seed)
+        deg = np.diff(g.rowptr.astype(np.int64))
+        rows = np.repeat(np.arange(g.n, dtype=np.int64), deg)
+        cols = g.colidx.astype(np.int64)
+        keep = rows <= cols
+        s, d = rows[keep], cols[keep]
+        order = rng.permutation(s.size)
+        s, d = s[order], d[order]
+        flip = rng.random(s.size) < 0.5
+        s, d = np.where(flip, d, s), np.where(flip, s, d)
+        return EdgeStream(s.astype(np.int32), d.astype(np.int32), g.n, int(s.size),
+                          f"edge stream of [{g.name}] seed={seed}")
+    dev = g.colidx.device
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    # upper-triangle entries, one segment of rows at a time so that no temporary exceeds a few GB
+    parts_s, parts_d = [], []
+    rowptr = g.rowptr.to(torch.int64)
+    lo = 0
+    while lo < g.n:
+        # rows whose entries fill about one segment
+        target = int(rowptr[lo].item()) + _SEGMENT // 4
+        hi = int(torch.searchsorted(rowptr, torch.tensor([target], device=dev)).item())
+        hi = min(max(hi, lo + 1), g.n)
+        a, b = int(rowptr[lo].item()), int(rowptr[hi].item())
+        deg = (rowptr[lo + 1:hi + 1] - rowptr[lo:hi])
+        rows = torch.repeat_interleave(torch.arange(lo, hi, device=dev, dtype=torch.int32), deg)
+        cols = g.colidx[a:b]
+        keep = rows <= cols
+        parts_s.append(rows[keep])
+        parts_d.append(cols[keep])
+        del rows, cols, keep, deg
+        lo = hi
+    s = torch.cat(parts_s)
+    d = torch.cat(parts_d)
+    del parts_s, parts_d
+    order = _permutation(int(s.numel()), gen, dev)
+    s, d = s[order], d[order]
+    del order
+    flip = torch.rand(int(s.numel()), generator=gen, device=dev) < 0.5
+    s2 = torch.where(flip, d, s)
+    d2 = torch.where(flip, s, d)
+    return EdgeStream(s2, d2, g.n, int(s2.numel()), f"edge stream of [{g.name}] seed={seed}")

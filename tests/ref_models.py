@@ -110,3 +110,73 @@ def best_permutation_agreement(labels, planted, k):
     for perm in permutations(range(k)):
         best = max(best, sum(conf[i, perm[i]] for i in range(k)))
     return best / len(labels)
+
+
+def sequential_edge_stream(src, dst, n, c_size, P, seed_parts, refine=True):
+    """Alg. 1 / Alg. 2 over chunks of an edge list, one node at a time (ascending id inside a chunk),
+    every node reading the most recent labels and sizes, exact rational averages, `cnt_nbrs` as the
+    literal scan of the chunk's edges.  A node being re-assigned is first removed from its
+    partition's size.  With refine=False an assigned node is never looked at again.
+
+    Also reports whether any decision depended on something that changed inside its own chunk:
+    a neighbour's label, a size that alters `assign`'s answer, or a partition filled up by this
+    chunk's arrivals.  When nothing did, processing the chunk's nodes all at once from the state at
+    the chunk's start must give the same result."""
+    m = len(src)
+    parts = [-1] * n
+    sizes = [0, 0]
+    est = [[Fraction(0), Fraction(0)] for _ in range(n)]
+    dependent = False
+    for i in range((m + c_size - 1) // c_size):
+        c_edges = [(int(src[e]), int(dst[e])) for e in range(i * c_size, min(m, (i + 1) * c_size))]
+        c_nodes = sorted({a for a, _ in c_edges} | {b for _, b in c_edges})
+
+        def cnt_nbrs(node, labels):
+            cnt = [Fraction(0), Fraction(0)]
+            for a, b in c_edges:
+                if a == node or b == node:
+                    nbr = a if b == node else b
+                    if labels[nbr] != -1:
+                        cnt[labels[nbr]] += 1
+            return cnt
+
+        if i == 0:
+            for v in c_nodes:
+                parts[v] = int(seed_parts[v])
+            sizes = [parts.count(0), parts.count(1)]
+            for v in c_nodes:
+                est[v] = cnt_nbrs(v, parts)
+            continue
+        start_parts, start_sizes, arrivals = list(parts), list(sizes), [0, 0]
+        for v in c_nodes:
+            old = parts[v]
+            if old != -1 and not refine:
+                continue
+            cnt = cnt_nbrs(v, parts)
+            if cnt != cnt_nbrs(v, start_parts):
+                dependent = True
+            if old != -1:
+                cnt = [(est[v][0] + cnt[0]) / 2, (est[v][1] + cnt[1]) / 2]
+                sizes[old] -= 1
+            new = _assign2(cnt[0], cnt[1], sizes, P)
+            at_start = [start_sizes[0] - (old == 0), start_sizes[1] - (old == 1)]
+            if new != _assign2(cnt[0], cnt[1], at_start, P):
+                dependent = True
+            if new != old:
+                if start_sizes[new] + arrivals[new] >= P:
+                    dependent = True
+                arrivals[new] += 1
+            sizes[new] += 1
+            parts[v] = new
+            est[v] = cnt
+    return parts, sizes, est, dependent
+
+
+def chunk_incidence(src, dst, n):
+    """M[v,u] = number of listed edges joining v and u, a loop counted once on the diagonal."""
+    M = np.zeros((n, n), dtype=np.int64)
+    for a, b in zip(src, dst):
+        M[int(a), int(b)] += 1
+        if a != b:
+            M[int(b), int(a)] += 1
+    return M

@@ -1,0 +1,220 @@
+"""CPU pins of the edge-chunk oracle (Alg. 1 in the paper's own stream model, two partitions).
+
+Each test states which mistake it is meant to catch."""
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2502_17846_amd import synth
+from tests import ref_models as ref
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _run(src, dst, n, c_size, P, seed, mode=oracle.EDGE_REFINE):
+    return oracle.edge_stream_bipartition(src, dst, n, c_size, P, seed, mode, return_state=True)
+
+
+# ---------------------------------------------------------------------------------------------
+# hand-worked examples: the whole rule on inputs small enough to follow on paper (wrong tie
+# direction, missing removal before assign, rank test off by one, spill target, blend weights,
+# loops, unassigned neighbours, the fixed-greedy switch)
+# ---------------------------------------------------------------------------------------------
+
+def test_handworked_examples():
+    with open(os.path.join(GOLDEN, "handworked_edge_stream.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        e = np.asarray(c["edges"], dtype=np.int32)
+        seed = np.asarray(c["seed_parts"], dtype=np.int32)
+        for key, mode in (("refine", oracle.EDGE_REFINE), ("fixed", oracle.EDGE_FIXED)):
+            if key not in c:
+                continue
+            parts, sizes, est = _run(e[:, 0], e[:, 1], c["n"], c["c_size"], c["P"], seed, mode)
+            want = c[key]
+            assert parts.tolist() == want["parts"], (c["name"], key)
+            assert sizes.tolist() == want["sizes"], (c["name"], key)
+            assert est.tolist() == want["nbr_counts"], (c["name"], key)
+            assert oracle.edge_list_cut(e[:, 0], e[:, 1], parts) == want["cut"], (c["name"], key)
+
+
+# ---------------------------------------------------------------------------------------------
+# the literal node-at-a-time procedure, wherever it detects no dependence inside a chunk
+# ---------------------------------------------------------------------------------------------
+
+def _growing_stream(rng, n, m, p_new):
+    """Edges whose new endpoint (if any) has the next unused id, so that a new node's chunk
+    neighbours have lower ids and are evaluated before it; the first two nodes start the stream."""
+    src, dst = [0], [1]
+    used = 2
+    while len(src) < m:
+        if used < n and rng.random() < p_new:
+            a, b = int(rng.integers(0, used)), used
+            used += 1
+        else:
+            a, b = int(rng.integers(0, used)), int(rng.integers(0, used))
+        if rng.random() < 0.5:
+            a, b = b, a
+        src.append(a)
+        dst.append(b)
+    return np.asarray(src, np.int32), np.asarray(dst, np.int32), used
+
+
+@pytest.mark.parametrize("refine", [True, False])
+def test_equals_sequential_procedure_when_chunks_have_no_inner_dependence(refine):
+    rng = np.random.default_rng(5 if refine else 6)
+    compared = tight = 0
+    for trial in range(1500):
+        n = int(rng.integers(4, 14))
+        m = int(rng.integers(3, 30))
+        c_size = int(rng.integers(1, 5))
+        src, dst, used = _growing_stream(rng, n, m, float(rng.uniform(0.2, 0.7)))
+        P = int(rng.integers((n + 1) // 2, n + 1))
+        seed = rng.integers(0, 2, n).astype(np.int32)
+        first = np.unique(np.concatenate([src[:c_size], dst[:c_size]]))
+        if max(np.sum(seed[first] == 0), np.sum(seed[first] == 1)) > P:
+            continue
+        sp, ss, se, dependent = ref.sequential_edge_stream(src, dst, n, c_size, P, seed, refine)
+        if dependent:
+            continue
+        parts, sizes, est = _run(src, dst, n, c_size, P, seed,
+                                 oracle.EDGE_REFINE if refine else oracle.EDGE_FIXED)
+        assert parts.tolist() == sp, (trial, src.tolist(), dst.tolist(), c_size, P, seed.tolist())
+        assert sizes.tolist() == ss
+        assert [[Fraction(x) for x in row] for row in est.tolist()] == se
+        compared += 1
+        tight += int(max(ss) == P)
+    assert compared >= 100 and tight >= 10, (compared, tight)
+
+
+# ---------------------------------------------------------------------------------------------
+# counts and chunk nodes against dense incidence algebra; invariants after every chunk; the
+# closed-form chunk weights of Sec. 4.1 (first two appearances equal, then halving)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed_,loops", [(0, False), (1, True), (2, True)])
+def test_counts_weights_and_invariants_chunk_by_chunk(seed_, loops):
+    rng = np.random.default_rng(seed_)
+    n, m, c_size = 40, 300, 17
+    src = rng.integers(0, n - 3, m).astype(np.int32)       # the last 3 nodes never occur
+    dst = rng.integers(0, n - 3, m).astype(np.int32)
+    if not loops:
+        dst = np.where(dst == src, (dst + 1) % (n - 3), dst).astype(np.int32)
+    P = 21
+    seed = rng.integers(0, 2, n).astype(np.int32)
+    st = oracle.EdgeStepper(src, dst, n, c_size, P, seed)
+    history = [[] for _ in range(n)]           # per node: fresh counts of every chunk it occurred in
+    prev = st.parts()
+    chunk = 0
+    while True:
+        before = prev.copy()
+        if not st.step():
+            break
+        lo, hi = chunk * c_size, min(m, (chunk + 1) * c_size)
+        nodes, fresh, prop = st.last_chunk()
+        assert nodes.tolist() == np.unique(np.concatenate([src[lo:hi], dst[lo:hi]])).tolist()
+        if chunk == 0:
+            before[nodes] = seed[nodes]
+        M = ref.chunk_incidence(src[lo:hi], dst[lo:hi], n)
+        onehot = np.stack([(before == 0), (before == 1)], axis=1).astype(np.int64)
+        assert np.array_equal(fresh, (M @ onehot)[nodes])
+        now, sizes = st.parts(), st.sizes()
+        assert sizes.tolist() == [int((now == 0).sum()), int((now == 1).sum())]
+        assert sizes.max() <= P
+        changed = np.nonzero(now != before)[0]
+        assert set(changed.tolist()) <= set(nodes.tolist())
+        assert np.all(now[nodes] >= 0)
+        for v, f in zip(nodes.tolist(), fresh.tolist()):
+            history[v].append(f)
+        est = st.nbr_counts()
+        for v in nodes.tolist():
+            h = history[v]
+            j = len(h)
+            want = [sum(Fraction(h[i][t], 2 ** (j - max(i, 1))) for i in range(j)) for t in (0, 1)]
+            assert [Fraction(x) for x in est[v].tolist()] == want
+        prev = now
+        chunk += 1
+    assert chunk == (m + c_size - 1) // c_size
+    assert np.all(prev[n - 3:] == -1) and np.all(st.nbr_counts()[n - 3:] == 0)
+    st.close()
+
+
+def test_fixed_mode_never_changes_a_label_and_keeps_first_estimates():
+    rng = np.random.default_rng(3)
+    n, m, c_size, P = 60, 500, 25, 33
+    src = rng.integers(0, n, m).astype(np.int32)
+    dst = rng.integers(0, n, m).astype(np.int32)
+    seed = rng.integers(0, 2, n).astype(np.int32)
+    st = oracle.EdgeStepper(src, dst, n, c_size, P, seed, oracle.EDGE_FIXED)
+    prev, prev_est = st.parts(), st.nbr_counts()
+    first = True
+    while st.step():
+        now, est = st.parts(), st.nbr_counts()
+        was = prev >= 0
+        assert np.array_equal(now[was], prev[was])
+        if not first:
+            assert np.array_equal(est[was], prev_est[was])
+        nodes, fresh, prop = st.last_chunk()
+        new = nodes[prev[nodes] < 0]
+        assert np.array_equal(est[new], fresh[np.isin(nodes, new)].astype(np.float64))
+        prev, prev_est, first = now, est, False
+    st.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# what the method is for (Sec. 4.1, 4.2): a seeded first chunk lets the stream recover a planted
+# bisection, and refinement cuts fewer edges than fixed greedy decisions on small chunks
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gseed", [0, 1])
+def test_planted_bisection_refined_beats_fixed(gseed):
+    g = synth.planted_partition(n=4000, blocks=2, mean_degree=12.0, seed=gseed)
+    es = synth.edge_stream(g, seed=gseed + 10)
+    P = oracle.capacity(g.n, 2, 1.05)
+    seed = g.planted.astype(np.int32)            # only the first chunk's nodes are read
+    planted_cut = oracle.edge_list_cut(es.src, es.dst, g.planted)
+    cuts = {}
+    for mode in (oracle.EDGE_REFINE, oracle.EDGE_FIXED):
+        parts, sizes, _ = _run(es.src, es.dst, g.n, es.m // 20, P, seed, mode)
+        assert sizes.max() <= P and sizes.sum() == int((parts >= 0).sum())
+        cuts[mode] = oracle.edge_list_cut(es.src, es.dst, parts)
+    assert cuts[oracle.EDGE_REFINE] < 0.6 * cuts[oracle.EDGE_FIXED]
+    assert cuts[oracle.EDGE_REFINE] < 3.0 * planted_cut
+    # one chunk holding every edge: every node is seeded, nothing else happens
+    parts, sizes, est = _run(es.src, es.dst, g.n, es.m, P, seed)
+    touched = np.zeros(g.n, bool)
+    touched[es.src] = True
+    touched[es.dst] = True
+    assert np.array_equal(parts[touched], g.planted[touched]) and np.all(parts[~touched] == -1)
+    deg0 = np.zeros((g.n, 2))
+    np.add.at(deg0, (es.src, g.planted[es.dst]), 1)
+    np.add.at(deg0, (es.dst, g.planted[es.src]), 1)
+    assert np.array_equal(est, deg0)
+
+
+def test_determinism_and_errors():
+    rng = np.random.default_rng(9)
+    n, m = 50, 200
+    src = rng.integers(0, n, m).astype(np.int32)
+    dst = rng.integers(0, n, m).astype(np.int32)
+    seed = rng.integers(0, 2, n).astype(np.int32)
+    a = _run(src, dst, n, 16, 26, seed)
+    b = _run(src, dst, n, 16, 26, seed)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    with pytest.raises(oracle.OracleError) as ei:       # 2P < n
+        _run(src, dst, n, 16, 24, seed)
+    assert ei.value.code == oracle.ERR_ARG
+    bad = seed.copy()
+    bad[src[0]] = -1                                     # a first-chunk node without a seed label
+    with pytest.raises(oracle.OracleError) as ei:
+        _run(src, dst, n, 16, 26, bad)
+    assert ei.value.code == oracle.ERR_SEED
+    with pytest.raises(oracle.OracleError) as ei:       # the seed overfills a partition
+        _run(src, dst, n, m, 26, np.zeros(n, np.int32))
+    assert ei.value.code == oracle.ERR_SEED
+    with pytest.raises(oracle.OracleError):              # endpoint out of range
+        _run(np.array([0, n], np.int32), np.array([1, 2], np.int32), n, 1, 26, seed)
