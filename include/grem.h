@@ -161,6 +161,53 @@ int grem_profile_enable(int32_t on);
 int grem_profile_reset(void);
 int grem_profile_read(int32_t kernel_class, double *total_ms, int64_t *launches);
 
+/* ---- Alg. 1 in the stream model the paper states it in (Sec. 4.1): chunks of an edge list, two
+ * partitions ----------------------------------------------------------------------------------
+ *
+ * Input: m edges (src[e], dst[e]), 0 <= ids < n, in the caller's (random) order; loops and repeated
+ * edges are allowed and count as listed.  Chunk i is edges [i*c_size, (i+1)*c_size); its nodes are
+ * the distinct endpoints of its edges, taken in ascending id.
+ *   first chunk:  its nodes take seed_parts[v] (the output of Alg. 1's `seed_algo`, handed in as
+ *                 data; must be 0 or 1), sizes = label counts, nbr_counts[v] = cnt_nbrs of the chunk
+ *   later chunks, all reads seeing parts and sizes as they were when the chunk started:
+ *     fresh[v][j] = chunk edges at v whose other end (v itself for a loop) is in partition j
+ *     nbr_counts[v] = fresh if v has no label, else (nbr_counts[v] + fresh) * 0.5 in IEEE double
+ *     request = assign(nbr_counts[v], sizes without v, P) of Alg. 2, arg_min ties -> 0
+ *     admission in ascending v: a node whose request t differs from its label moves if fewer than
+ *     P - sizes[t] earlier nodes of the chunk asked for t; a rejected node that has a label keeps
+ *     it; rejected new nodes are then placed one by one, ascending v, in the currently smaller
+ *     partition (0 on a tie)
+ *   mode GREM_EDGE_FIXED: a node that has a label is never looked at again (Sec. 4.1, "fixed
+ *   assignments"; the ablation of Sec. 4.2 and Fig. 7).
+ * Nodes in no edge end with -1 and zero counts.  P is Alg. 1's input (e.g. grem_capacity(n, 2, s));
+ * 2P >= n is required.
+ *
+ * src, dst: m int32 each; seed_parts: n int32, read only at the first chunk's nodes; parts_out: n
+ * int32; sizes_out: 2 int64 or NULL; nbr_counts_out: n*2 doubles, row-major, or NULL (when given it
+ * is the working storage).  All device pointers.  Scratch memory is allocated on `stream` for the
+ * call (about 9n bytes, plus 16n when nbr_counts_out is NULL).  The call checks the endpoints' range
+ * and the seed (two small read-backs) before it enqueues the remaining chunks.
+ * Errors: GREM_ERR_ARG (null pointer, m < 1, n < 1, n > 2^31-1, c_size < 1, P < 1, 2P < n, unknown
+ * mode, an endpoint outside [0,n)), GREM_ERR_SEED (a first-chunk node whose seed is not 0 or 1, or
+ * a seeded partition above P), GREM_ERR_NOMEM, GREM_ERR_HIP. */
+#define GREM_EDGE_REFINE 0
+#define GREM_EDGE_FIXED 1
+int grem_edge_stream_bipartition(const int32_t *src, const int32_t *dst, int64_t m, int64_t n,
+                                 int64_t c_size, int64_t P, const int32_t *seed_parts, int32_t mode,
+                                 int32_t *parts_out, int64_t *sizes_out, double *nbr_counts_out,
+                                 void *stream);
+
+/* Number of listed edges whose ends carry different labels (Sec. 1), written to the single device
+ * int64 *cut_out.  parts: int32 labels covering every listed id, any values. */
+int grem_edge_list_cut(const int32_t *src, const int32_t *dst, int64_t m, const int32_t *parts,
+                       int64_t *cut_out, void *stream);
+
+/* Timing of the edge kernel (cnt_nbrs over a chunk's edges) with HIP events on the caller's stream,
+ * for measurement: while enabled each launch is bracketed by two events; the read synchronises on
+ * them, returns their total in milliseconds and the launch count, and forgets them. */
+int grem_edge_stream_profile_enable(int32_t on);
+int grem_edge_stream_profile_read(double *count_ms, int64_t *launches);
+
 const char *grem_status_string(int code);
 const char *grem_kernel_name(int32_t kernel_class);
 

@@ -26,7 +26,10 @@ EXPORTS = [
     "grem_workspace_bytes", "grem_set_workspace", "grem_set_histogram_mode",
     "grem_set_sweep_col_bits", "grem_set_sweep_hub_degree", "grem_set_long_row_degree", "grem_profile_enable",
     "grem_profile_reset", "grem_profile_read", "grem_status_string", "grem_kernel_name",
+    "grem_edge_stream_bipartition", "grem_edge_list_cut", "grem_edge_stream_profile_enable",
+    "grem_edge_stream_profile_read",
 ]
+EDGE_REFINE, EDGE_FIXED = 0, 1
 
 
 class GremError(RuntimeError):
@@ -83,6 +86,14 @@ def load():
     lib.grem_status_string.argtypes = [ctypes.c_int]
     lib.grem_kernel_name.restype = ctypes.c_char_p
     lib.grem_kernel_name.argtypes = [i32]
+    lib.grem_edge_stream_bipartition.restype = ctypes.c_int
+    lib.grem_edge_stream_bipartition.argtypes = [vp, vp, i64, i64, i64, i64, vp, i32, vp, vp, vp, vp]
+    lib.grem_edge_list_cut.restype = ctypes.c_int
+    lib.grem_edge_list_cut.argtypes = [vp, vp, i64, vp, vp, vp]
+    lib.grem_edge_stream_profile_enable.restype = ctypes.c_int
+    lib.grem_edge_stream_profile_enable.argtypes = [i32]
+    lib.grem_edge_stream_profile_read.restype = ctypes.c_int
+    lib.grem_edge_stream_profile_read.argtypes = [ctypes.POINTER(dbl), ctypes.POINTER(i64)]
     _lib = lib
     return lib
 
@@ -244,4 +255,49 @@ def grem_profile_read(kernel_class: int):
     cnt = ctypes.c_int64(0)
     _check(load().grem_profile_read(kernel_class, ctypes.byref(ms), ctypes.byref(cnt)),
            "grem_profile_read")
+    return ms.value, cnt.value
+
+
+def grem_edge_stream_bipartition(src, dst, n, c_size, P, seed_parts, mode=EDGE_REFINE, want_sizes=True,
+                                 want_nbr_counts=True, stream=None):
+    """Returns (parts int32[n], sizes int64[2] or None, nbr_counts float64[n,2] or None)."""
+    lib = load()
+    dev = src.device
+    m = src.numel()
+    if dst.numel() != m:
+        raise ValueError("src and dst differ in length")
+    if seed_parts.numel() != n:
+        raise ValueError("seed_parts must have n entries")
+    parts = torch.empty(n, dtype=torch.int32, device=dev)
+    sizes = torch.empty(2, dtype=torch.int64, device=dev) if want_sizes else None
+    est = torch.empty((n, 2), dtype=torch.float64, device=dev) if want_nbr_counts else None
+    rc = lib.grem_edge_stream_bipartition(
+        _dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"), m, n, c_size, P,
+        _dev(seed_parts, torch.int32, "seed_parts"), mode, _dev(parts, torch.int32, "parts_out"),
+        None if sizes is None else _dev(sizes, torch.int64, "sizes_out"),
+        None if est is None else _dev(est, torch.float64, "nbr_counts_out"), _stream(stream))
+    _check(rc, "grem_edge_stream_bipartition")
+    return parts, sizes, est
+
+
+def grem_edge_list_cut(src, dst, parts, stream=None) -> torch.Tensor:
+    """Device int64 tensor with one element: the number of listed edges that are cut."""
+    lib = load()
+    out = torch.empty(1, dtype=torch.int64, device=src.device)
+    rc = lib.grem_edge_list_cut(_dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"), src.numel(),
+                                _dev(parts, torch.int32, "parts"), _dev(out, torch.int64, "cut_out"),
+                                _stream(stream))
+    _check(rc, "grem_edge_list_cut")
+    return out
+
+
+def grem_edge_stream_profile_enable(on: bool):
+    _check(load().grem_edge_stream_profile_enable(1 if on else 0), "grem_edge_stream_profile_enable")
+
+
+def grem_edge_stream_profile_read():
+    ms = ctypes.c_double(0.0)
+    cnt = ctypes.c_int64(0)
+    _check(load().grem_edge_stream_profile_read(ctypes.byref(ms), ctypes.byref(cnt)),
+           "grem_edge_stream_profile_read")
     return ms.value, cnt.value

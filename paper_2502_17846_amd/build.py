@@ -7,6 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "grem.hip")
+SRC_EDGE = os.path.join(HERE, "csrc", "grem_edge_stream.hip")
 LIB = os.path.join(HERE, "libgrem.so")
 
 FLAGS = [
@@ -19,7 +20,7 @@ FLAGS = [
 
 def build_library(verbose: bool = False, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, *extra, "-o", LIB, SRC]
+    cmd = [hipcc, *FLAGS, *extra, "-o", LIB, SRC, SRC_EDGE]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -1,0 +1,520 @@
+// GREM over a stream of edge chunks, two partitions, for gfx950 (Armada paper, Sec. 4.1, Alg. 1
+// "GREM Bipartite Graph Partitioning" with the helpers of Alg. 2, in the stream model the paper
+// states them in: an edge list in random order, a chunk is c_size consecutive edges, the chunk's
+// nodes are the distinct endpoints of its edges and each is (re)evaluated from the chunk's edges).
+//
+// Chunk-synchronous form: every decision of a chunk reads labels and sizes as of the chunk's start;
+// moves are admitted in ascending node id while the target has room; rejected refined nodes stay;
+// rejected new nodes are placed one by one, ascending id, in the currently smaller partition.
+//
+// Data layout (device memory)
+//   Lb    uint8[n]      label 0/1, 0xFF = unassigned (one byte per random look-up)
+//   hc    uint64[n]     fresh counts of the current chunk: low half = neighbours in partition 0, high
+//                       half = neighbours in partition 1; one 64-bit atomic per edge end.  All zero
+//                       between chunks (the scoring kernel clears what it reads).
+//   est   double[n][2]  Alg. 1's nbr_counts
+//   mark  uint64[n/64]  bit v set = v is an endpoint of the current chunk.  The bitmap IS the ordered
+//                       set c_nodes: bit order is id order, so ranks by id are prefix pop-counts.
+//   mv0, mv1, ov        bitmaps of the same shape: nodes asking to move to partition 0 / 1, and new
+//                       nodes whose request was rejected
+// Per chunk: k_es_count (the edges: two label look-ups, bitmap marks and count atomics per edge) ->
+// k_es_score (one lane per node, one wave per bitmap word: blend, assign, mover ballots) -> a
+// one-workgroup scan of the per-workgroup mover counts -> k_es_apply (ranks = scanned offset +
+// pop-count prefix; admitted moves relabel) -> a one-workgroup scan (overflow ranks, size deltas,
+// closed-form sizes after the spill) -> k_es_spill (closed-form target of the j-th rejected node).
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "grem.h"
+
+namespace {
+
+constexpr int kBlock = 1024;                 // per-node kernels: 16 waves = 16 bitmap words
+constexpr int kWordsPerBlock = kBlock / 64;
+constexpr uint32_t kNone = 0xFFu;
+constexpr int kCountBlock = 256;
+constexpr int kCountUnroll = 4;              // edges in flight per thread of k_es_count
+
+typedef unsigned long long u64;
+
+__global__ __launch_bounds__(256) void k_es_fill64(u64* p, size_t count, u64 value)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) p[i] = value;
+}
+
+// flags[0] = 1 if any endpoint lies outside [0, n)
+__global__ __launch_bounds__(256) void k_es_check(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                                  int64_t m, uint32_t n, uint32_t* flags)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < m; e += stride)
+        bad |= ((uint32_t)src[e] >= n) | ((uint32_t)dst[e] >= n);
+    if (bad) flags[0] = 1u;
+}
+
+// c_nodes of a chunk as a bitmap (Alg. 1: unique_nodes_in_edges)
+__global__ __launch_bounds__(kCountBlock) void k_es_mark(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                                         int64_t lo, int64_t hi, u64* mark)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = lo + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < hi; e += stride) {
+        const uint32_t s = (uint32_t)src[e], d = (uint32_t)dst[e];
+        atomicOr(&mark[s >> 6], 1ull << (s & 63u));
+        atomicOr(&mark[d >> 6], 1ull << (d & 63u));
+    }
+}
+
+// Alg. 1, first chunk: the chunk's nodes take seed_algo's labels; sizes are counted.
+// flags[1] = 1 if a node of the chunk has a seed label other than 0 or 1.
+__global__ __launch_bounds__(kBlock) void k_es_seed(int64_t words, const u64* __restrict__ mark,
+                                                    const int32_t* __restrict__ seed, uint8_t* Lb,
+                                                    u64* S, uint32_t* flags)
+{
+    __shared__ uint32_t c0[kWordsPerBlock], c1[kWordsPerBlock];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t w = (int64_t)blockIdx.x * kWordsPerBlock + wave;
+    const u64 word = w < words ? mark[w] : 0ull;
+    const bool on = (word >> lane) & 1ull;
+    int s = -1;
+    if (on) {
+        const int64_t v = w * 64 + lane;
+        s = seed[v];
+        if (s == 0 || s == 1) Lb[v] = (uint8_t)s;
+        else flags[1] = 1u;
+    }
+    const u64 b0 = __ballot(on && s == 0), b1 = __ballot(on && s == 1);
+    if (lane == 0) { c0[wave] = __popcll(b0); c1[wave] = __popcll(b1); }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t a = 0, b = 0;
+        for (int i = 0; i < kWordsPerBlock; ++i) { a += c0[i]; b += c1[i]; }
+        if (a) atomicAdd(&S[0], (u64)a);
+        if (b) atomicAdd(&S[1], (u64)b);
+    }
+}
+
+// cnt_nbrs (Alg. 2) for every node of the chunk at once: each edge adds one to the count its two
+// ends keep for the partition of the other end (a loop counts once, for the node itself); an
+// unassigned end adds nothing.  Also marks both ends as nodes of the chunk.
+__global__ __launch_bounds__(kCountBlock) void k_es_count(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                                          int64_t lo, int64_t hi, const uint8_t* __restrict__ Lb,
+                                                          u64* mark, u64* hc)
+{
+    const int64_t threads = (int64_t)gridDim.x * blockDim.x;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t base = lo + tid; base < hi; base += threads * kCountUnroll) {
+        uint32_t s[kCountUnroll], d[kCountUnroll], ls[kCountUnroll], ld[kCountUnroll];
+        bool in[kCountUnroll];
+#pragma unroll
+        for (int u = 0; u < kCountUnroll; ++u) {
+            const int64_t e = base + (int64_t)u * threads;
+            in[u] = e < hi;
+            s[u] = in[u] ? (uint32_t)src[e] : 0u;
+            d[u] = in[u] ? (uint32_t)dst[e] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < kCountUnroll; ++u) {
+            ls[u] = in[u] ? (uint32_t)Lb[s[u]] : kNone;
+            ld[u] = in[u] ? (uint32_t)Lb[d[u]] : kNone;
+        }
+#pragma unroll
+        for (int u = 0; u < kCountUnroll; ++u) {
+            if (!in[u]) continue;
+            atomicOr(&mark[s[u] >> 6], 1ull << (s[u] & 63u));
+            if (ld[u] != kNone) atomicAdd(&hc[s[u]], ld[u] ? (1ull << 32) : 1ull);
+            if (d[u] != s[u]) {
+                atomicOr(&mark[d[u] >> 6], 1ull << (d[u] & 63u));
+                if (ls[u] != kNone) atomicAdd(&hc[d[u]], ls[u] ? (1ull << 32) : 1ull);
+            }
+        }
+    }
+}
+
+// assign (Alg. 2) on sizes from which the node itself has been taken out; arg_min ties -> 0
+__device__ __forceinline__ int es_assign(double nbrs0, double nbrs1, long long s0, long long s1, long long P)
+{
+    if (nbrs0 < nbrs1 && s1 < P) return 1;
+    if (nbrs1 < nbrs0 && s0 < P) return 0;
+    return s1 < s0 ? 1 : 0;
+}
+
+// One lane per node, one wave per bitmap word.  Alg. 1: blend the stored estimate with the fresh
+// counts when the node has a label, store the estimate, ask `assign` for a partition.  Nodes that
+// want to move are recorded in mv0 / mv1 (wave ballots), their numbers per workgroup in bs0 / bs1.
+// Clears what it consumed (hc, mark).  first: the seeded first chunk (estimates only).
+// fixed: fixed greedy decisions (a node that has a label is left alone).
+__global__ __launch_bounds__(kBlock) void k_es_score(int64_t words, int first, int fixed, long long P,
+                                                     const u64* __restrict__ S, u64* mark, u64* hc,
+                                                     const uint8_t* __restrict__ Lb, double2* est,
+                                                     u64* mv0, u64* mv1, uint32_t* bs0, uint32_t* bs1)
+{
+    __shared__ uint32_t c0[kWordsPerBlock], c1[kWordsPerBlock];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t w = (int64_t)blockIdx.x * kWordsPerBlock + wave;
+    const u64 word = w < words ? mark[w] : 0ull;
+    const bool on = (word >> lane) & 1ull;
+    int want = -1;
+    if (on) {
+        const int64_t v = w * 64 + lane;
+        const u64 h = hc[v];
+        if (h) hc[v] = 0ull;
+        const uint32_t old = Lb[v];
+        double nbrs0 = (double)(uint32_t)h, nbrs1 = (double)(uint32_t)(h >> 32);
+        if (first) {
+            est[v] = make_double2(nbrs0, nbrs1);
+        } else if (!(fixed && old != kNone)) {
+            if (old != kNone) {
+                const double2 prev = est[v];
+                nbrs0 = (prev.x + nbrs0) * 0.5;
+                nbrs1 = (prev.y + nbrs1) * 0.5;
+            }
+            est[v] = make_double2(nbrs0, nbrs1);
+            const long long s0 = (long long)S[0] - (old == 0u), s1 = (long long)S[1] - (old == 1u);
+            const int t = es_assign(nbrs0, nbrs1, s0, s1, P);
+            if ((uint32_t)t != old) want = t;
+        }
+    }
+    const u64 m0 = __ballot(want == 0), m1 = __ballot(want == 1);
+    if (lane == 0) {
+        if (w < words) {
+            mv0[w] = m0; mv1[w] = m1;
+            if (word) mark[w] = 0ull;
+        }
+        c0[wave] = __popcll(m0); c1[wave] = __popcll(m1);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t a = 0, b = 0;
+        for (int i = 0; i < kWordsPerBlock; ++i) { a += c0[i]; b += c1[i]; }
+        bs0[blockIdx.x] = a; bs1[blockIdx.x] = b;
+    }
+}
+
+// exclusive prefix sums of in[0..len) into out, by one workgroup of kBlock threads; returns the total
+__device__ uint32_t es_block_scan(const uint32_t* __restrict__ in, uint32_t* __restrict__ out, int64_t len,
+                                  uint32_t* wsum /* kWordsPerBlock + 1 words of LDS */)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t carry = 0;
+    for (int64_t base = 0; base < len; base += kBlock) {
+        const int64_t i = base + threadIdx.x;
+        const uint32_t x = i < len ? in[i] : 0u;
+        uint32_t incl = x;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t y = __shfl_up(incl, o);
+            if (lane >= o) incl += y;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        uint32_t before = 0, all = 0;
+        for (int q = 0; q < kWordsPerBlock; ++q) {
+            const uint32_t t = wsum[q];
+            if (q < wave) before += t;
+            all += t;
+        }
+        if (i < len) out[i] = carry + before + incl - x;
+        carry += all;
+        __syncthreads();
+    }
+    return carry;
+}
+
+__global__ __launch_bounds__(kBlock) void k_es_scan_movers(int64_t blocks, const uint32_t* bs0, const uint32_t* bs1,
+                                                           uint32_t* bo0, uint32_t* bo1)
+{
+    __shared__ uint32_t wsum[kWordsPerBlock + 1];
+    (void)es_block_scan(bs0, bo0, blocks, wsum);
+    (void)es_block_scan(bs1, bo1, blocks, wsum);
+}
+
+// Admission: a mover whose rank among the chunk's requests for its target (ascending id) is below
+// the room the target had when the chunk started is relabelled (fix_sizes, Alg. 2, as per-workgroup
+// deltas); a rejected node without a label is recorded in ov.
+__global__ __launch_bounds__(kBlock) void k_es_apply(int64_t words, long long P, const u64* __restrict__ S,
+                                                     const u64* __restrict__ mv0, const u64* __restrict__ mv1,
+                                                     const uint32_t* __restrict__ bo0, const uint32_t* __restrict__ bo1,
+                                                     uint8_t* Lb, u64* ov, uint32_t* bso, int32_t* bd0, int32_t* bd1)
+{
+    __shared__ uint32_t c0[kWordsPerBlock], c1[kWordsPerBlock], co[kWordsPerBlock];
+    __shared__ int32_t d0[kWordsPerBlock], d1[kWordsPerBlock];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t w = (int64_t)blockIdx.x * kWordsPerBlock + wave;
+    const u64 m0 = w < words ? mv0[w] : 0ull, m1 = w < words ? mv1[w] : 0ull;
+    if (lane == 0) { c0[wave] = __popcll(m0); c1[wave] = __popcll(m1); }
+    __syncthreads();
+    uint32_t r0 = bo0[blockIdx.x], r1 = bo1[blockIdx.x];
+    for (int q = 0; q < wave; ++q) { r0 += c0[q]; r1 += c1[q]; }
+    const u64 below = (1ull << lane) - 1ull;
+    const int t = ((m0 >> lane) & 1ull) ? 0 : (((m1 >> lane) & 1ull) ? 1 : -1);
+    bool admitted = false, spilled = false;
+    uint32_t old = kNone;
+    if (t >= 0) {
+        const int64_t v = w * 64 + lane;
+        old = Lb[v];
+        const long long rank = t == 0 ? (long long)r0 + __popcll(m0 & below) : (long long)r1 + __popcll(m1 & below);
+        const long long room = P - (long long)S[t];
+        admitted = rank < room;
+        if (admitted) Lb[v] = (uint8_t)t;
+        else spilled = old == kNone;
+    }
+    const u64 a0 = __ballot(admitted && t == 0), a1 = __ballot(admitted && t == 1);
+    const u64 l0 = __ballot(admitted && old == 0u), l1 = __ballot(admitted && old == 1u);
+    const u64 o = __ballot(spilled);
+    if (lane == 0) {
+        if (w < words) ov[w] = o;
+        co[wave] = __popcll(o);
+        d0[wave] = __popcll(a0) - __popcll(l0);
+        d1[wave] = __popcll(a1) - __popcll(l1);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t so = 0; int32_t x = 0, y = 0;
+        for (int i = 0; i < kWordsPerBlock; ++i) { so += co[i]; x += d0[i]; y += d1[i]; }
+        bso[blockIdx.x] = so; bd0[blockIdx.x] = x; bd1[blockIdx.x] = y;
+    }
+}
+
+// One workgroup: ranks of the rejected new nodes, sizes after the admissions (Sp[0..1], Sp[2] = how
+// many nodes are to be placed), and the sizes after placing them one by one in the smaller
+// partition (0 on a tie): the first |difference| go to the smaller one, the rest alternate 0,1,...
+__global__ __launch_bounds__(kBlock) void k_es_scan_spill(int64_t blocks, const uint32_t* bso, uint32_t* boo,
+                                                          const int32_t* bd0, const int32_t* bd1, u64* S, long long* Sp)
+{
+    __shared__ uint32_t wsum[kWordsPerBlock + 1];
+    __shared__ long long part0[kWordsPerBlock], part1[kWordsPerBlock];
+    const uint32_t total = es_block_scan(bso, boo, blocks, wsum);
+    long long x = 0, y = 0;
+    for (int64_t i = threadIdx.x; i < blocks; i += kBlock) { x += bd0[i]; y += bd1[i]; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { x += __shfl_down(x, o); y += __shfl_down(y, o); }
+    if ((threadIdx.x & 63) == 0) { part0[threadIdx.x >> 6] = x; part1[threadIdx.x >> 6] = y; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long a = (long long)S[0], b = (long long)S[1];
+        for (int i = 0; i < kWordsPerBlock; ++i) { a += part0[i]; b += part1[i]; }
+        Sp[0] = a; Sp[1] = b; Sp[2] = (long long)total;
+        const long long gap = a <= b ? b - a : a - b;
+        const long long lead = (long long)total < gap ? (long long)total : gap;
+        const long long rest = (long long)total - lead;
+        if (a <= b) a += lead; else b += lead;
+        a += (rest + 1) / 2;
+        b += rest / 2;
+        S[0] = (u64)a; S[1] = (u64)b;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_es_spill(int64_t words, const u64* __restrict__ ov,
+                                                     const uint32_t* __restrict__ boo, const long long* __restrict__ Sp,
+                                                     uint8_t* Lb)
+{
+    if (Sp[2] == 0) return;
+    __shared__ uint32_t co[kWordsPerBlock];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t w = (int64_t)blockIdx.x * kWordsPerBlock + wave;
+    const u64 o = w < words ? ov[w] : 0ull;
+    if (lane == 0) co[wave] = __popcll(o);
+    __syncthreads();
+    if (!((o >> lane) & 1ull)) return;
+    long long j = boo[blockIdx.x];
+    for (int q = 0; q < wave; ++q) j += co[q];
+    j += __popcll(o & ((1ull << lane) - 1ull));
+    const long long a = Sp[0], b = Sp[1];
+    const long long gap = a <= b ? b - a : a - b;
+    const int t = j < gap ? (a <= b ? 0 : 1) : (int)((j - gap) & 1);
+    Lb[w * 64 + lane] = (uint8_t)t;
+}
+
+__global__ __launch_bounds__(256) void k_es_expand(int64_t n, const uint8_t* __restrict__ Lb, int32_t* parts,
+                                                   const u64* S, int64_t* sizes_out)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
+        const uint32_t l = Lb[v];
+        parts[v] = l == kNone ? -1 : (int32_t)l;
+    }
+    if (sizes_out && blockIdx.x == 0 && threadIdx.x < 2) sizes_out[threadIdx.x] = (int64_t)S[threadIdx.x];
+}
+
+// listed edges whose ends carry different labels (Sec. 1)
+__global__ __launch_bounds__(256) void k_es_cut(const int32_t* __restrict__ src, const int32_t* __restrict__ dst, int64_t m,
+                                                const int32_t* __restrict__ parts, u64* cut)
+{
+    __shared__ u64 wsum[4];
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    u64 c = 0;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < m; e += stride)
+        c += parts[src[e]] != parts[dst[e]];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const u64 t = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+        if (t) atomicAdd(cut, t);
+    }
+}
+
+// ---- host side ---------------------------------------------------------------------------------
+
+struct EsProfile {
+    std::mutex mu;
+    bool on = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> count_events;
+} es_prof;
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+inline int grid_for(int64_t items, int block, int64_t cap)
+{
+    int64_t g = (items + block - 1) / block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+}  // namespace
+
+extern "C" {
+
+int grem_edge_stream_bipartition(const int32_t* src, const int32_t* dst, int64_t m, int64_t n,
+                                 int64_t c_size, int64_t P, const int32_t* seed_parts, int32_t mode,
+                                 int32_t* parts_out, int64_t* sizes_out, double* nbr_counts_out,
+                                 void* stream_)
+{
+    if (!src || !dst || !seed_parts || !parts_out || m < 1 || n < 1 || n > INT32_MAX || c_size < 1 ||
+        P < 1 || 2 * P < n || (mode != GREM_EDGE_REFINE && mode != GREM_EDGE_FIXED))
+        return GREM_ERR_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    const int64_t words = (n + 63) / 64;
+    const int64_t blocks = (words + kWordsPerBlock - 1) / kWordsPerBlock;
+
+    // one stream-ordered allocation, carved up
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return at; };
+    const size_t o_small = carve(256);                       // S[2], Sp[3], flags[2]
+    const size_t o_lb = carve((size_t)n);
+    const size_t o_hc = carve((size_t)n * 8);
+    const size_t o_est = nbr_counts_out ? 0 : carve((size_t)n * 16);
+    const size_t o_mark = carve((size_t)words * 8), o_mv0 = carve((size_t)words * 8);
+    const size_t o_mv1 = carve((size_t)words * 8), o_ov = carve((size_t)words * 8);
+    size_t o_b[8];
+    for (int i = 0; i < 8; ++i) o_b[i] = carve((size_t)blocks * 4);
+    uint8_t* ws = nullptr;
+    if (hipMallocAsync((void**)&ws, off, stream) != hipSuccess) { (void)hipGetLastError(); return GREM_ERR_NOMEM; }
+    u64* S = (u64*)(ws + o_small);
+    long long* Sp = (long long*)(ws + o_small + 16);
+    uint32_t* flags = (uint32_t*)(ws + o_small + 64);
+    uint8_t* Lb = ws + o_lb;
+    u64* hc = (u64*)(ws + o_hc);
+    double2* est = nbr_counts_out ? (double2*)nbr_counts_out : (double2*)(ws + o_est);
+    u64 *mark = (u64*)(ws + o_mark), *mv0 = (u64*)(ws + o_mv0), *mv1 = (u64*)(ws + o_mv1), *ov = (u64*)(ws + o_ov);
+    uint32_t *bs0 = (uint32_t*)(ws + o_b[0]), *bs1 = (uint32_t*)(ws + o_b[1]), *bso = (uint32_t*)(ws + o_b[2]);
+    uint32_t *bo0 = (uint32_t*)(ws + o_b[3]), *bo1 = (uint32_t*)(ws + o_b[4]), *boo = (uint32_t*)(ws + o_b[5]);
+    int32_t *bd0 = (int32_t*)(ws + o_b[6]), *bd1 = (int32_t*)(ws + o_b[7]);
+
+    int rc = GREM_OK;
+    auto fail = [&](int code) { (void)hipGetLastError(); (void)hipFreeAsync(ws, stream); return code; };
+    auto fill = [&](void* p, size_t bytes, u64 value) {
+        const size_t count = bytes / 8;
+        hipLaunchKernelGGL(k_es_fill64, dim3(grid_for((int64_t)count, 256, 16384)), dim3(256), 0, stream, (u64*)p, count, value);
+    };
+    fill(ws + o_small, 256, 0ull);
+    fill(Lb, align256((size_t)n), ~0ull);
+    fill(hc, (size_t)n * 8, 0ull);
+    fill(est, (size_t)n * 16, 0ull);
+    fill(mark, (size_t)words * 8, 0ull);
+
+    const int egrid_all = grid_for(m, 256, 8192);
+    hipLaunchKernelGGL(k_es_check, dim3(egrid_all), dim3(256), 0, stream, src, dst, m, (uint32_t)n, flags);
+    // the range check must be known before any kernel indexes with the endpoints
+    struct { u64 S[2]; long long Sp[3]; long long pad[3]; uint32_t flags[2]; } host;
+    static_assert(sizeof(host) >= 72, "layout");
+    if (hipMemcpyAsync(&host, ws + o_small, sizeof(host), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        return fail(GREM_ERR_HIP);
+    if (host.flags[0]) return fail(GREM_ERR_ARG);
+
+    const int64_t nchunks = (m + c_size - 1) / c_size;
+    bool profile;
+    { std::lock_guard<std::mutex> lock(es_prof.mu); profile = es_prof.on; }
+    for (int64_t i = 0; i < nchunks; ++i) {
+        const int64_t lo = i * c_size, hi = (lo + c_size < m) ? lo + c_size : m;
+        const int egrid = grid_for((hi - lo + kCountUnroll - 1) / kCountUnroll, kCountBlock, 1 << 20);
+        if (i == 0) {
+            hipLaunchKernelGGL(k_es_mark, dim3(grid_for(hi - lo, kCountBlock, 8192)), dim3(kCountBlock), 0, stream, src, dst, lo, hi, mark);
+            hipLaunchKernelGGL(k_es_seed, dim3((int)blocks), dim3(kBlock), 0, stream, words, mark, seed_parts, Lb, S, flags);
+            if (hipMemcpyAsync(&host, ws + o_small, sizeof(host), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+                hipStreamSynchronize(stream) != hipSuccess)
+                return fail(GREM_ERR_HIP);
+            if (host.flags[1] || (long long)host.S[0] > P || (long long)host.S[1] > P) return fail(GREM_ERR_SEED);
+        }
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (profile) {
+            if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return fail(GREM_ERR_HIP);
+            (void)hipEventRecord(e0, stream);
+        }
+        hipLaunchKernelGGL(k_es_count, dim3(egrid), dim3(kCountBlock), 0, stream, src, dst, lo, hi, Lb, mark, hc);
+        if (profile) {
+            (void)hipEventRecord(e1, stream);
+            std::lock_guard<std::mutex> lock(es_prof.mu);
+            es_prof.count_events.emplace_back(e0, e1);
+        }
+        hipLaunchKernelGGL(k_es_score, dim3((int)blocks), dim3(kBlock), 0, stream, words, i == 0 ? 1 : 0,
+                           mode == GREM_EDGE_FIXED ? 1 : 0, (long long)P, S, mark, hc, Lb, est, mv0, mv1, bs0, bs1);
+        if (i == 0) continue;
+        hipLaunchKernelGGL(k_es_scan_movers, dim3(1), dim3(kBlock), 0, stream, blocks, bs0, bs1, bo0, bo1);
+        hipLaunchKernelGGL(k_es_apply, dim3((int)blocks), dim3(kBlock), 0, stream, words, (long long)P, S, mv0, mv1,
+                           bo0, bo1, Lb, ov, bso, bd0, bd1);
+        hipLaunchKernelGGL(k_es_scan_spill, dim3(1), dim3(kBlock), 0, stream, blocks, bso, boo, bd0, bd1, S, Sp);
+        hipLaunchKernelGGL(k_es_spill, dim3((int)blocks), dim3(kBlock), 0, stream, words, ov, boo, Sp, Lb);
+    }
+    hipLaunchKernelGGL(k_es_expand, dim3(grid_for(n, 256, 16384)), dim3(256), 0, stream, n, Lb, parts_out, S, sizes_out);
+    if (hipGetLastError() != hipSuccess) rc = GREM_ERR_HIP;
+    if (hipFreeAsync(ws, stream) != hipSuccess) rc = GREM_ERR_HIP;
+    return rc;
+}
+
+int grem_edge_list_cut(const int32_t* src, const int32_t* dst, int64_t m, const int32_t* parts,
+                       int64_t* cut_out, void* stream_)
+{
+    if (!src || !dst || !parts || !cut_out || m < 0) return GREM_ERR_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    hipLaunchKernelGGL(k_es_fill64, dim3(1), dim3(256), 0, stream, (u64*)cut_out, (size_t)1, 0ull);
+    if (m > 0)
+        hipLaunchKernelGGL(k_es_cut, dim3(grid_for(m, 256, 8192)), dim3(256), 0, stream, src, dst, m, parts, (u64*)cut_out);
+    return hipGetLastError() == hipSuccess ? GREM_OK : GREM_ERR_HIP;
+}
+
+int grem_edge_stream_profile_enable(int32_t on)
+{
+    std::lock_guard<std::mutex> lock(es_prof.mu);
+    es_prof.on = on != 0;
+    return GREM_OK;
+}
+
+int grem_edge_stream_profile_read(double* count_ms, int64_t* launches)
+{
+    std::lock_guard<std::mutex> lock(es_prof.mu);
+    double total = 0.0;
+    int rc = GREM_OK;
+    for (auto& ev : es_prof.count_events) {
+        float ms = 0.f;
+        if (hipEventSynchronize(ev.second) != hipSuccess || hipEventElapsedTime(&ms, ev.first, ev.second) != hipSuccess)
+            rc = GREM_ERR_HIP;
+        total += ms;
+        (void)hipEventDestroy(ev.first);
+        (void)hipEventDestroy(ev.second);
+    }
+    if (count_ms) *count_ms = total;
+    if (launches) *launches = (int64_t)es_prof.count_events.size();
+    es_prof.count_events.clear();
+    return rc;
+}
+
+}  // extern "C"
