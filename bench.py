@@ -68,6 +68,14 @@ WORKLOADS = {
     "rmat-27": dict(kind="rmat", scale=27, ef=32, k=32, slack=1.03, chunk=1 << 22, R=1, bits=64),
     "hub-24": dict(kind="hub", scale=24, ef=16, k=256, slack=1.10, chunk=262_144, R=3, bits=32),
     "sbm-10k": dict(kind="sbm", k=4, slack=1.05, chunk=1024, R=2, bits=32),
+    # Alg. 1 in the paper's own stream model (two partitions, chunks of a randomly ordered edge list);
+    # c_frac is the chunk size as a fraction of the edges (Sec. 6.2 uses 1 % and 10 %)
+    "edges-chunglu-111M-c1pct": dict(kind="chung_lu", n=111_000_000, m=1_600_000_000, bits=64, stream=True,
+                                     c_frac=0.01, slack=1.05),
+    "edges-chunglu-111M-c10pct": dict(kind="chung_lu", n=111_000_000, m=1_600_000_000, bits=64, stream=True,
+                                      c_frac=0.10, slack=1.05),
+    "edges-chunglu-14M-c1pct": dict(kind="chung_lu", n=13_875_000, m=200_000_000, bits=64, stream=True,
+                                    c_frac=0.01, slack=1.05),
 }
 
 
@@ -135,6 +143,103 @@ def cpu_baseline(g, w, budget_s=15.0, max_chunks=48):
     }
 
 
+def bench_edge_stream(args, w, dev):
+    """The edge-chunk path: a step is one whole run of Alg. 1 over the stream (every chunk once)."""
+    import numpy as np
+    import torch
+    from paper_2502_17846_amd import binding as B
+    from paper_2502_17846_amd import synth
+    t_gen = time.perf_counter()
+    g = make_graph(w, dev)
+    es = synth.edge_stream(g, seed=1)
+    n, m = es.n, es.m
+    gname = g.name
+    del g
+    torch.cuda.empty_cache()
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+    c_size = max(1, int(round(m * w["c_frac"])))
+    nchunks = (m + c_size - 1) // c_size
+    P = B.grem_capacity(n, 2, w["slack"])
+    # stands for seed_algo's output on the first chunk: id parity, balanced by construction
+    seed = (torch.arange(n, device=dev, dtype=torch.int32) & 1)
+    print(f"[bench] {es.name}: n={n} edges={m} c_size={c_size} ({nchunks} chunks) generated in {t_gen:.1f}s",
+          file=sys.stderr, flush=True)
+    est = torch.empty((n, 2), dtype=torch.float64, device=dev)
+    out_parts = [None]
+
+    def step():
+        lib = B.load()
+        parts = torch.empty(n, dtype=torch.int32, device=dev)
+        rc = lib.grem_edge_stream_bipartition(es.src.data_ptr(), es.dst.data_ptr(), m, n, c_size, P,
+                                              seed.data_ptr(), B.EDGE_REFINE, parts.data_ptr(), None,
+                                              est.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            raise RuntimeError(f"grem_edge_stream_bipartition returned {rc}")
+        out_parts[0] = parts
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    parts = out_parts[0]
+    cut = int(B.grem_edge_list_cut(es.src, es.dst, parts).item())
+    assigned = parts >= 0
+    sizes = torch.bincount(parts[assigned], minlength=2)
+    assert int(sizes.max()) <= P
+
+    # dominant kernel: k_es_count reads each edge's two ids once (8 bytes); its label look-ups and count
+    # atomics are random accesses whose useful bytes are 2 and 16 per edge
+    roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": None,
+                "traffic": None, "kernel": "k_es_count"}
+    if not args.no_kernel_timing:
+        B.grem_edge_stream_profile_enable(True)
+        step()
+        torch.cuda.synchronize()
+        count_ms, launches = B.grem_edge_stream_profile_read()
+        B.grem_edge_stream_profile_enable(False)
+        bytes_per_launch = 8.0 * m / launches
+        avg_s = 1e-3 * count_ms / launches
+        achieved = bytes_per_launch / avg_s / 1e9
+        roofline.update(achieved=achieved, frac=achieved / HBM_PEAK_GBPS, avg_launch_us=1e6 * avg_s,
+                        launches_per_step=launches, bytes_per_launch=bytes_per_launch,
+                        count_ms_per_step=round(count_ms, 3))
+    out = {
+        "metric": "edges/sec per GREM pass", "value": m / (elapsed / args.steps), "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {es.name} of {gname}; two partitions, c_size={c_size} "
+                               f"({100 * w['c_frac']:g} % of the edges), P={P}, first chunk seeded by id parity",
+                   "n": n, "edges": m, "chunks_per_step": nchunks},
+        "cut_fraction": cut / m, "sizes": sizes.tolist(), "capacity": P,
+        "unassigned_nodes": int((~assigned).sum()),
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        print("[bench] timing the CPU oracle on a sample ...", file=sys.stderr, flush=True)
+        take = min(nchunks, 12)
+        ms_ = min(m, take * c_size)
+        hs, hd = es.src[:ms_].cpu().numpy(), es.dst[:ms_].cpu().numpy()
+        st = oracle.EdgeStepper(hs, hd, n, c_size, P, seed.cpu().numpy())
+        done, t0 = 0, time.perf_counter()
+        while done < take and st.step():
+            done += 1
+            if time.perf_counter() - t0 > 15.0:
+                break
+        dt = time.perf_counter() - t0
+        st.close()
+        out["cpu_baseline"] = {"value": min(ms_, done * c_size) / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {done} of {nchunks} chunks ({min(ms_, done * c_size)} edges) of the "
+                                         f"same stream, {dt:.1f} s, state for all {n} nodes"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -176,6 +281,9 @@ def main():
                           "bytes_written_per_launch": nbytes, "launches": 8}))
         return
     w = WORKLOADS[args.workload]
+    if w.get("stream"):
+        bench_edge_stream(args, w, dev)
+        return
     t_gen = time.perf_counter()
     g = make_graph(w, dev)
     torch.cuda.synchronize()

@@ -18,10 +18,11 @@
 //   mv0, mv1, ov        bitmaps of the same shape: nodes asking to move to partition 0 / 1, and new
 //                       nodes whose request was rejected
 // Per chunk: k_es_count (the edges: two label look-ups, bitmap marks and count atomics per edge) ->
-// k_es_score (one lane per node, one wave per bitmap word: blend, assign, mover ballots) -> a
-// one-workgroup scan of the per-workgroup mover counts -> k_es_apply (ranks = scanned offset +
-// pop-count prefix; admitted moves relabel) -> a one-workgroup scan (overflow ranks, size deltas,
-// closed-form sizes after the spill) -> k_es_spill (closed-form target of the j-th rejected node).
+// k_es_score (one lane per node, a wave walking over its 64 bitmap words: blend, assign, mover
+// ballots) -> a one-workgroup scan of the per-workgroup mover counts -> k_es_apply (ranks = scanned
+// offset + pop-count prefix; admitted moves relabel) -> a one-workgroup scan (overflow ranks, size
+// deltas, closed-form sizes after the spill) -> k_es_spill (closed-form target of the j-th rejected
+// node).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -32,8 +33,9 @@
 
 namespace {
 
-constexpr int kBlock = 1024;                 // per-node kernels: 16 waves = 16 bitmap words
-constexpr int kWordsPerBlock = kBlock / 64;
+constexpr int kBlock = 1024;                 // per-node kernels: 16 waves
+constexpr int kWordsPerBlock = kBlock / 64;   // waves per workgroup
+constexpr int kWaveWords = 64;               // bitmap words a wave of the per-node kernels owns
 constexpr uint32_t kNone = 0xFFu;
 constexpr int kCountBlock = 256;
 constexpr int kCountUnroll = 4;              // edges in flight per thread of k_es_count
@@ -143,11 +145,42 @@ __device__ __forceinline__ int es_assign(double nbrs0, double nbrs1, long long s
     return s1 < s0 ? 1 : 0;
 }
 
-// One lane per node, one wave per bitmap word.  Alg. 1: blend the stored estimate with the fresh
-// counts when the node has a label, store the estimate, ask `assign` for a partition.  Nodes that
-// want to move are recorded in mv0 / mv1 (wave ballots), their numbers per workgroup in bs0 / bs1.
-// Clears what it consumed (hc, mark).  first: the seeded first chunk (estimates only).
-// fixed: fixed greedy decisions (a node that has a label is left alone).
+// value of x in lane i, i uniform over the wave
+__device__ __forceinline__ u64 es_bcast(u64 x, int i)
+{
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)x, i);
+    const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(x >> 32), i);
+    return ((u64)hi << 32) | lo;
+}
+
+__device__ __forceinline__ uint32_t es_wave_sum(uint32_t x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+// exclusive prefix sum over the lanes of a wave
+__device__ __forceinline__ uint32_t es_wave_exclusive(uint32_t x, int lane)
+{
+    uint32_t incl = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t y = __shfl_up(incl, o);
+        if (lane >= o) incl += y;
+    }
+    return incl - x;
+}
+
+// The per-node kernels: a wave owns kWaveWords = 64 consecutive bitmap words (lane i holds word i)
+// and walks over those that have a bit set, one lane per node of the word; a workgroup of 16 waves
+// owns 1024 words = 65536 nodes.
+//
+// k_es_score -- Alg. 1: blend the stored estimate with the fresh counts when the node has a label,
+// store the estimate, ask `assign` for a partition.  Nodes that want to move are recorded in mv0 /
+// mv1 (wave ballots), their numbers per workgroup in bs0 / bs1.  Clears what it consumed (hc, mark).
+// first: the seeded first chunk (estimates only).  fixed: fixed greedy decisions (a node that has a
+// label is left alone).
 __global__ __launch_bounds__(kBlock) void k_es_score(int64_t words, int first, int fixed, long long P,
                                                      const u64* __restrict__ S, u64* mark, u64* hc,
                                                      const uint8_t* __restrict__ Lb, double2* est,
@@ -155,62 +188,62 @@ __global__ __launch_bounds__(kBlock) void k_es_score(int64_t words, int first, i
 {
     __shared__ uint32_t c0[kWordsPerBlock], c1[kWordsPerBlock];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t w = (int64_t)blockIdx.x * kWordsPerBlock + wave;
-    const u64 word = w < words ? mark[w] : 0ull;
-    const bool on = (word >> lane) & 1ull;
-    int want = -1;
-    if (on) {
-        const int64_t v = w * 64 + lane;
-        const u64 h = hc[v];
-        if (h) hc[v] = 0ull;
-        const uint32_t old = Lb[v];
-        double nbrs0 = (double)(uint32_t)h, nbrs1 = (double)(uint32_t)(h >> 32);
-        if (first) {
-            est[v] = make_double2(nbrs0, nbrs1);
-        } else if (!(fixed && old != kNone)) {
-            if (old != kNone) {
-                const double2 prev = est[v];
-                nbrs0 = (prev.x + nbrs0) * 0.5;
-                nbrs1 = (prev.y + nbrs1) * 0.5;
+    const int64_t word0 = ((int64_t)blockIdx.x * kWordsPerBlock + wave) * kWaveWords;
+    const bool mine = word0 + lane < words;
+    const u64 myword = mine ? mark[word0 + lane] : 0ull;
+    const long long S0 = (long long)S[0], S1 = (long long)S[1];
+    u64 out0 = 0ull, out1 = 0ull;
+    for (u64 todo = __ballot(myword != 0ull); todo; todo &= todo - 1ull) {
+        const int i = __builtin_ctzll(todo);
+        const u64 word = es_bcast(myword, i);
+        int want = -1;
+        if ((word >> lane) & 1ull) {
+            const int64_t v = (word0 + i) * 64 + lane;
+            const u64 h = hc[v];
+            if (h) hc[v] = 0ull;
+            const uint32_t old = Lb[v];
+            double nbrs0 = (double)(uint32_t)h, nbrs1 = (double)(uint32_t)(h >> 32);
+            if (first) {
+                est[v] = make_double2(nbrs0, nbrs1);
+            } else if (!(fixed && old != kNone)) {
+                if (old != kNone) {
+                    const double2 prev = est[v];
+                    nbrs0 = (prev.x + nbrs0) * 0.5;
+                    nbrs1 = (prev.y + nbrs1) * 0.5;
+                }
+                est[v] = make_double2(nbrs0, nbrs1);
+                const int t = es_assign(nbrs0, nbrs1, S0 - (old == 0u), S1 - (old == 1u), P);
+                if ((uint32_t)t != old) want = t;
             }
-            est[v] = make_double2(nbrs0, nbrs1);
-            const long long s0 = (long long)S[0] - (old == 0u), s1 = (long long)S[1] - (old == 1u);
-            const int t = es_assign(nbrs0, nbrs1, s0, s1, P);
-            if ((uint32_t)t != old) want = t;
         }
+        const u64 m0 = __ballot(want == 0), m1 = __ballot(want == 1);
+        if (lane == i) { out0 = m0; out1 = m1; }
     }
-    const u64 m0 = __ballot(want == 0), m1 = __ballot(want == 1);
-    if (lane == 0) {
-        if (w < words) {
-            mv0[w] = m0; mv1[w] = m1;
-            if (word) mark[w] = 0ull;
-        }
-        c0[wave] = __popcll(m0); c1[wave] = __popcll(m1);
+    if (mine) {
+        mv0[word0 + lane] = out0; mv1[word0 + lane] = out1;
+        if (myword) mark[word0 + lane] = 0ull;
     }
+    const uint32_t a = es_wave_sum(__popcll(out0)), b = es_wave_sum(__popcll(out1));
+    if (lane == 0) { c0[wave] = a; c1[wave] = b; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        uint32_t a = 0, b = 0;
-        for (int i = 0; i < kWordsPerBlock; ++i) { a += c0[i]; b += c1[i]; }
-        bs0[blockIdx.x] = a; bs1[blockIdx.x] = b;
+        uint32_t x = 0, y = 0;
+        for (int q = 0; q < kWordsPerBlock; ++q) { x += c0[q]; y += c1[q]; }
+        bs0[blockIdx.x] = x; bs1[blockIdx.x] = y;
     }
 }
 
 // exclusive prefix sums of in[0..len) into out, by one workgroup of kBlock threads; returns the total
 __device__ uint32_t es_block_scan(const uint32_t* __restrict__ in, uint32_t* __restrict__ out, int64_t len,
-                                  uint32_t* wsum /* kWordsPerBlock + 1 words of LDS */)
+                                  uint32_t* wsum /* kWordsPerBlock words of LDS */)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t carry = 0;
     for (int64_t base = 0; base < len; base += kBlock) {
         const int64_t i = base + threadIdx.x;
         const uint32_t x = i < len ? in[i] : 0u;
-        uint32_t incl = x;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t y = __shfl_up(incl, o);
-            if (lane >= o) incl += y;
-        }
-        if (lane == 63) wsum[wave] = incl;
+        const uint32_t excl = es_wave_exclusive(x, lane);
+        if (lane == 63) wsum[wave] = excl + x;
         __syncthreads();
         uint32_t before = 0, all = 0;
         for (int q = 0; q < kWordsPerBlock; ++q) {
@@ -218,7 +251,7 @@ __device__ uint32_t es_block_scan(const uint32_t* __restrict__ in, uint32_t* __r
             if (q < wave) before += t;
             all += t;
         }
-        if (i < len) out[i] = carry + before + incl - x;
+        if (i < len) out[i] = carry + before + excl;
         carry += all;
         __syncthreads();
     }
@@ -228,7 +261,7 @@ __device__ uint32_t es_block_scan(const uint32_t* __restrict__ in, uint32_t* __r
 __global__ __launch_bounds__(kBlock) void k_es_scan_movers(int64_t blocks, const uint32_t* bs0, const uint32_t* bs1,
                                                            uint32_t* bo0, uint32_t* bo1)
 {
-    __shared__ uint32_t wsum[kWordsPerBlock + 1];
+    __shared__ uint32_t wsum[kWordsPerBlock];
     (void)es_block_scan(bs0, bo0, blocks, wsum);
     (void)es_block_scan(bs1, bo1, blocks, wsum);
 }
@@ -244,39 +277,49 @@ __global__ __launch_bounds__(kBlock) void k_es_apply(int64_t words, long long P,
     __shared__ uint32_t c0[kWordsPerBlock], c1[kWordsPerBlock], co[kWordsPerBlock];
     __shared__ int32_t d0[kWordsPerBlock], d1[kWordsPerBlock];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t w = (int64_t)blockIdx.x * kWordsPerBlock + wave;
-    const u64 m0 = w < words ? mv0[w] : 0ull, m1 = w < words ? mv1[w] : 0ull;
-    if (lane == 0) { c0[wave] = __popcll(m0); c1[wave] = __popcll(m1); }
+    const int64_t word0 = ((int64_t)blockIdx.x * kWordsPerBlock + wave) * kWaveWords;
+    const bool mine = word0 + lane < words;
+    const u64 my0 = mine ? mv0[word0 + lane] : 0ull, my1 = mine ? mv1[word0 + lane] : 0ull;
+    const uint32_t p0 = __popcll(my0), p1 = __popcll(my1);
+    const uint32_t ex0 = es_wave_exclusive(p0, lane), ex1 = es_wave_exclusive(p1, lane);
+    if (lane == 63) { c0[wave] = ex0 + p0; c1[wave] = ex1 + p1; }
     __syncthreads();
-    uint32_t r0 = bo0[blockIdx.x], r1 = bo1[blockIdx.x];
-    for (int q = 0; q < wave; ++q) { r0 += c0[q]; r1 += c1[q]; }
+    uint32_t base0 = bo0[blockIdx.x], base1 = bo1[blockIdx.x];
+    for (int q = 0; q < wave; ++q) { base0 += c0[q]; base1 += c1[q]; }
+    const long long room0 = P - (long long)S[0], room1 = P - (long long)S[1];
     const u64 below = (1ull << lane) - 1ull;
-    const int t = ((m0 >> lane) & 1ull) ? 0 : (((m1 >> lane) & 1ull) ? 1 : -1);
-    bool admitted = false, spilled = false;
-    uint32_t old = kNone;
-    if (t >= 0) {
-        const int64_t v = w * 64 + lane;
-        old = Lb[v];
-        const long long rank = t == 0 ? (long long)r0 + __popcll(m0 & below) : (long long)r1 + __popcll(m1 & below);
-        const long long room = P - (long long)S[t];
-        admitted = rank < room;
-        if (admitted) Lb[v] = (uint8_t)t;
-        else spilled = old == kNone;
+    u64 outo = 0ull;
+    int32_t delta0 = 0, delta1 = 0;
+    for (u64 todo = __ballot((my0 | my1) != 0ull); todo; todo &= todo - 1ull) {
+        const int i = __builtin_ctzll(todo);
+        const u64 m0 = es_bcast(my0, i), m1 = es_bcast(my1, i);
+        const long long r0 = (long long)base0 + __builtin_amdgcn_readlane(ex0, i);
+        const long long r1 = (long long)base1 + __builtin_amdgcn_readlane(ex1, i);
+        const int t = ((m0 >> lane) & 1ull) ? 0 : (((m1 >> lane) & 1ull) ? 1 : -1);
+        bool admitted = false, spilled = false;
+        uint32_t old = kNone;
+        if (t >= 0) {
+            const int64_t v = (word0 + i) * 64 + lane;
+            old = Lb[v];
+            admitted = t == 0 ? r0 + __popcll(m0 & below) < room0 : r1 + __popcll(m1 & below) < room1;
+            if (admitted) Lb[v] = (uint8_t)t;
+            else spilled = old == kNone;
+        }
+        const u64 a0 = __ballot(admitted && t == 0), a1 = __ballot(admitted && t == 1);
+        const u64 l0 = __ballot(admitted && old == 0u), l1 = __ballot(admitted && old == 1u);
+        const u64 o = __ballot(spilled);
+        delta0 += __popcll(a0) - __popcll(l0);
+        delta1 += __popcll(a1) - __popcll(l1);
+        if (lane == i) outo = o;
     }
-    const u64 a0 = __ballot(admitted && t == 0), a1 = __ballot(admitted && t == 1);
-    const u64 l0 = __ballot(admitted && old == 0u), l1 = __ballot(admitted && old == 1u);
-    const u64 o = __ballot(spilled);
-    if (lane == 0) {
-        if (w < words) ov[w] = o;
-        co[wave] = __popcll(o);
-        d0[wave] = __popcll(a0) - __popcll(l0);
-        d1[wave] = __popcll(a1) - __popcll(l1);
-    }
+    if (mine) ov[word0 + lane] = outo;
+    const uint32_t so = es_wave_sum(__popcll(outo));
+    if (lane == 0) { co[wave] = so; d0[wave] = delta0; d1[wave] = delta1; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        uint32_t so = 0; int32_t x = 0, y = 0;
-        for (int i = 0; i < kWordsPerBlock; ++i) { so += co[i]; x += d0[i]; y += d1[i]; }
-        bso[blockIdx.x] = so; bd0[blockIdx.x] = x; bd1[blockIdx.x] = y;
+        uint32_t z = 0; int32_t x = 0, y = 0;
+        for (int q = 0; q < kWordsPerBlock; ++q) { z += co[q]; x += d0[q]; y += d1[q]; }
+        bso[blockIdx.x] = z; bd0[blockIdx.x] = x; bd1[blockIdx.x] = y;
     }
 }
 
@@ -286,7 +329,7 @@ __global__ __launch_bounds__(kBlock) void k_es_apply(int64_t words, long long P,
 __global__ __launch_bounds__(kBlock) void k_es_scan_spill(int64_t blocks, const uint32_t* bso, uint32_t* boo,
                                                           const int32_t* bd0, const int32_t* bd1, u64* S, long long* Sp)
 {
-    __shared__ uint32_t wsum[kWordsPerBlock + 1];
+    __shared__ uint32_t wsum[kWordsPerBlock];
     __shared__ long long part0[kWordsPerBlock], part1[kWordsPerBlock];
     const uint32_t total = es_block_scan(bso, boo, blocks, wsum);
     long long x = 0, y = 0;
@@ -297,7 +340,7 @@ __global__ __launch_bounds__(kBlock) void k_es_scan_spill(int64_t blocks, const 
     __syncthreads();
     if (threadIdx.x == 0) {
         long long a = (long long)S[0], b = (long long)S[1];
-        for (int i = 0; i < kWordsPerBlock; ++i) { a += part0[i]; b += part1[i]; }
+        for (int q = 0; q < kWordsPerBlock; ++q) { a += part0[q]; b += part1[q]; }
         Sp[0] = a; Sp[1] = b; Sp[2] = (long long)total;
         const long long gap = a <= b ? b - a : a - b;
         const long long lead = (long long)total < gap ? (long long)total : gap;
@@ -316,18 +359,25 @@ __global__ __launch_bounds__(kBlock) void k_es_spill(int64_t words, const u64* _
     if (Sp[2] == 0) return;
     __shared__ uint32_t co[kWordsPerBlock];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t w = (int64_t)blockIdx.x * kWordsPerBlock + wave;
-    const u64 o = w < words ? ov[w] : 0ull;
-    if (lane == 0) co[wave] = __popcll(o);
+    const int64_t word0 = ((int64_t)blockIdx.x * kWordsPerBlock + wave) * kWaveWords;
+    const u64 myo = word0 + lane < words ? ov[word0 + lane] : 0ull;
+    const uint32_t p = __popcll(myo);
+    const uint32_t ex = es_wave_exclusive(p, lane);
+    if (lane == 63) co[wave] = ex + p;
     __syncthreads();
-    if (!((o >> lane) & 1ull)) return;
-    long long j = boo[blockIdx.x];
-    for (int q = 0; q < wave; ++q) j += co[q];
-    j += __popcll(o & ((1ull << lane) - 1ull));
+    long long base = boo[blockIdx.x];
+    for (int q = 0; q < wave; ++q) base += co[q];
     const long long a = Sp[0], b = Sp[1];
     const long long gap = a <= b ? b - a : a - b;
-    const int t = j < gap ? (a <= b ? 0 : 1) : (int)((j - gap) & 1);
-    Lb[w * 64 + lane] = (uint8_t)t;
+    for (u64 todo = __ballot(myo != 0ull); todo; todo &= todo - 1ull) {
+        const int i = __builtin_ctzll(todo);
+        const u64 o = es_bcast(myo, i);
+        if ((o >> lane) & 1ull) {
+            const long long j = base + __builtin_amdgcn_readlane(ex, i) + __popcll(o & ((1ull << lane) - 1ull));
+            const int t = j < gap ? (a <= b ? 0 : 1) : (int)((j - gap) & 1);
+            Lb[(word0 + i) * 64 + lane] = (uint8_t)t;
+        }
+    }
 }
 
 __global__ __launch_bounds__(256) void k_es_expand(int64_t n, const uint8_t* __restrict__ Lb, int32_t* parts,
@@ -392,7 +442,8 @@ int grem_edge_stream_bipartition(const int32_t* src, const int32_t* dst, int64_t
         return GREM_ERR_ARG;
     hipStream_t stream = (hipStream_t)stream_;
     const int64_t words = (n + 63) / 64;
-    const int64_t blocks = (words + kWordsPerBlock - 1) / kWordsPerBlock;
+    const int64_t seed_blocks = (words + kWordsPerBlock - 1) / kWordsPerBlock;         // a wave per word
+    const int64_t blocks = (words + kWordsPerBlock * kWaveWords - 1) / (kWordsPerBlock * kWaveWords);
 
     // one stream-ordered allocation, carved up
     size_t off = 0;
@@ -448,7 +499,7 @@ int grem_edge_stream_bipartition(const int32_t* src, const int32_t* dst, int64_t
         const int egrid = grid_for((hi - lo + kCountUnroll - 1) / kCountUnroll, kCountBlock, 1 << 20);
         if (i == 0) {
             hipLaunchKernelGGL(k_es_mark, dim3(grid_for(hi - lo, kCountBlock, 8192)), dim3(kCountBlock), 0, stream, src, dst, lo, hi, mark);
-            hipLaunchKernelGGL(k_es_seed, dim3((int)blocks), dim3(kBlock), 0, stream, words, mark, seed_parts, Lb, S, flags);
+            hipLaunchKernelGGL(k_es_seed, dim3((int)seed_blocks), dim3(kBlock), 0, stream, words, mark, seed_parts, Lb, S, flags);
             if (hipMemcpyAsync(&host, ws + o_small, sizeof(host), hipMemcpyDeviceToHost, stream) != hipSuccess ||
                 hipStreamSynchronize(stream) != hipSuccess)
                 return fail(GREM_ERR_HIP);

@@ -359,10 +359,58 @@ def edge_stream(g: Graph, seed: int = 0) -> EdgeStream:
     s = torch.cat(parts_s)
     d = torch.cat(parts_d)
     del parts_s, parts_d
-    order = _permutation(int(s.numel()), gen, dev)
-    s, d = s[order], d[order]
-    del order
-    flip = torch.rand(int(s.numel()), generator=gen, device=dev) < 0.5
-    s2 = torch.where(flip, d, s)
-    d2 = torch.where(flip, s, d)
-    return EdgeStream(s2, d2, g.n, int(s2.numel()), f"edge stream of [{g.name}] seed={seed}")
+    s, d = _shuffle_pairs(s, d, gen)
+    m = int(s.numel())
+    for a in range(0, m, _SEGMENT):          # random orientation, a segment at a time
+        b = min(m, a + _SEGMENT)
+        flip = torch.rand(b - a, generator=gen, device=dev) < 0.5
+        sa, da = s[a:b].clone(), d[a:b]
+        s[a:b] = torch.where(flip, da, sa)
+        d[a:b] = torch.where(flip, sa, da)
+        del flip, sa, da
+    return EdgeStream(s, d, g.n, m, f"edge stream of [{g.name}] seed={seed}")
+
+
+def _shuffle_pairs(s: torch.Tensor, d: torch.Tensor, gen: torch.Generator):
+    """Both arrays in one uniformly random order.  Up to 2^30 elements this is one random permutation;
+    longer arrays are cut in two halves, each half is permuted, and the halves are merged by a random
+    pattern holding exactly as many positions for each half as it has elements (a random permutation
+    restricted to two blocks is exactly that)."""
+    m, dev = int(s.numel()), s.device
+    if m <= _SEGMENT:
+        order = _permutation(m, gen, dev)
+        return s[order], d[order]
+    if m > 2 * _SEGMENT:
+        raise ValueError("edge lists longer than 2^31 are not generated")
+    h = m // 2
+    pattern = torch.empty(m, dtype=torch.bool, device=dev)      # True: the position takes from the first half
+    for a in range(0, m, _SEGMENT):
+        b = min(m, a + _SEGMENT)
+        pattern[a:b] = torch.rand(b - a, generator=gen, device=dev) < (h / m)
+    # make the count exact by flipping randomly chosen positions of the surplus kind in the first segment
+    surplus = sum(int(pattern[a:min(m, a + _SEGMENT)].sum().item()) for a in range(0, m, _SEGMENT)) - h
+    if surplus != 0:
+        head = pattern[:_SEGMENT]
+        where = torch.nonzero(head if surplus > 0 else ~head).flatten()
+        pick = where[_permutation(int(where.numel()), gen, dev)[:abs(surplus)].long()]
+        head[pick] = surplus < 0
+        del where, pick
+    out_s, out_d = torch.empty_like(s), torch.empty_like(d)
+    for src_arr, out in ((s, out_s), (d, out_d)):
+        gen_state = gen.get_state()           # the same permutations for both arrays
+        first = src_arr[:h][_permutation(h, gen, dev)]
+        second = src_arr[h:][_permutation(m - h, gen, dev)]
+        if src_arr is s:
+            gen.set_state(gen_state)
+        used_first = used_second = 0
+        for a in range(0, m, _SEGMENT):
+            b = min(m, a + _SEGMENT)
+            pat = pattern[a:b]
+            c = int(pat.sum().item())
+            seg = out[a:b]
+            seg[pat] = first[used_first:used_first + c]
+            seg[~pat] = second[used_second:used_second + (b - a - c)]
+            used_first += c
+            used_second += b - a - c
+        del first, second
+    return out_s, out_d
