@@ -13,8 +13,10 @@
 //                       half = neighbours in partition 1; one 64-bit atomic per edge end.  All zero
 //                       between chunks (the scoring kernel clears what it reads).
 //   est   double[n][2]  Alg. 1's nbr_counts
-//   mark  uint64[n/64]  bit v set = v is an endpoint of the current chunk.  The bitmap IS the ordered
-//                       set c_nodes: bit order is id order, so ranks by id are prefix pop-counts.
+//   mark  uint64[n/64]  bit v set = v is an endpoint of a chunk edge whose other end has no label.
+//                       A node belongs to the current chunk iff hc[v] != 0 or its bit is set.
+//                       Bitmaps are ordered sets: bit order is id order, so ranks by id are prefix
+//                       pop-counts.
 //   mv0, mv1, ov        bitmaps of the same shape: nodes asking to move to partition 0 / 1, and new
 //                       nodes whose request was rejected
 // Per chunk: k_es_count (the edges: two label look-ups, bitmap marks and count atomics per edge) ->
@@ -101,8 +103,9 @@ __global__ __launch_bounds__(kBlock) void k_es_seed(int64_t words, const u64* __
 }
 
 // cnt_nbrs (Alg. 2) for every node of the chunk at once: each edge adds one to the count its two
-// ends keep for the partition of the other end (a loop counts once, for the node itself); an
-// unassigned end adds nothing.  Also marks both ends as nodes of the chunk.
+// ends keep for the partition of the other end (a loop counts once, for the node itself).  An
+// unassigned other end adds nothing; the node's bit in `mark` is set instead, so that a node of the
+// chunk is known by a non-zero count or its bit: one atomic per edge end either way.
 __global__ __launch_bounds__(kCountBlock) void k_es_count(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
                                                           int64_t lo, int64_t hi, const uint8_t* __restrict__ Lb,
                                                           u64* mark, u64* hc)
@@ -127,11 +130,11 @@ __global__ __launch_bounds__(kCountBlock) void k_es_count(const int32_t* __restr
 #pragma unroll
         for (int u = 0; u < kCountUnroll; ++u) {
             if (!in[u]) continue;
-            atomicOr(&mark[s[u] >> 6], 1ull << (s[u] & 63u));
             if (ld[u] != kNone) atomicAdd(&hc[s[u]], ld[u] ? (1ull << 32) : 1ull);
+            else atomicOr(&mark[s[u] >> 6], 1ull << (s[u] & 63u));
             if (d[u] != s[u]) {
-                atomicOr(&mark[d[u] >> 6], 1ull << (d[u] & 63u));
                 if (ls[u] != kNone) atomicAdd(&hc[d[u]], ls[u] ? (1ull << 32) : 1ull);
+                else atomicOr(&mark[d[u] >> 6], 1ull << (d[u] & 63u));
             }
         }
     }
@@ -173,15 +176,16 @@ __device__ __forceinline__ uint32_t es_wave_exclusive(uint32_t x, int lane)
 }
 
 // The per-node kernels: a wave owns kWaveWords = 64 consecutive bitmap words (lane i holds word i)
-// and walks over those that have a bit set, one lane per node of the word; a workgroup of 16 waves
-// owns 1024 words = 65536 nodes.
+// and walks over them (k_es_score: all of them, reading the counts of their nodes; the others: those
+// that have a bit set), one lane per node of the word; a workgroup of 16 waves owns 1024 words =
+// 65536 nodes.
 //
 // k_es_score -- Alg. 1: blend the stored estimate with the fresh counts when the node has a label,
 // store the estimate, ask `assign` for a partition.  Nodes that want to move are recorded in mv0 /
 // mv1 (wave ballots), their numbers per workgroup in bs0 / bs1.  Clears what it consumed (hc, mark).
 // first: the seeded first chunk (estimates only).  fixed: fixed greedy decisions (a node that has a
 // label is left alone).
-__global__ __launch_bounds__(kBlock) void k_es_score(int64_t words, int first, int fixed, long long P,
+__global__ __launch_bounds__(kBlock) void k_es_score(int64_t n, int64_t words, int first, int fixed, long long P,
                                                      const u64* __restrict__ S, u64* mark, u64* hc,
                                                      const uint8_t* __restrict__ Lb, double2* est,
                                                      u64* mv0, u64* mv1, uint32_t* bs0, uint32_t* bs1)
@@ -192,14 +196,16 @@ __global__ __launch_bounds__(kBlock) void k_es_score(int64_t words, int first, i
     const bool mine = word0 + lane < words;
     const u64 myword = mine ? mark[word0 + lane] : 0ull;
     const long long S0 = (long long)S[0], S1 = (long long)S[1];
+    const int count = words - word0 < kWaveWords ? (int)(words - word0) : kWaveWords;   // <= 0: nothing
     u64 out0 = 0ull, out1 = 0ull;
-    for (u64 todo = __ballot(myword != 0ull); todo; todo &= todo - 1ull) {
-        const int i = __builtin_ctzll(todo);
+    int64_t v = word0 * 64 + lane;
+    u64 hnext = (count > 0 && v < n) ? hc[v] : 0ull;
+    for (int i = 0; i < count; ++i, v += 64) {
+        const u64 h = hnext;
+        hnext = (i + 1 < count && v + 64 < n) ? hc[v + 64] : 0ull;
         const u64 word = es_bcast(myword, i);
         int want = -1;
-        if ((word >> lane) & 1ull) {
-            const int64_t v = (word0 + i) * 64 + lane;
-            const u64 h = hc[v];
+        if (h != 0ull || ((word >> lane) & 1ull)) {
             if (h) hc[v] = 0ull;
             const uint32_t old = Lb[v];
             double nbrs0 = (double)(uint32_t)h, nbrs1 = (double)(uint32_t)(h >> 32);
@@ -516,7 +522,7 @@ int grem_edge_stream_bipartition(const int32_t* src, const int32_t* dst, int64_t
             std::lock_guard<std::mutex> lock(es_prof.mu);
             es_prof.count_events.emplace_back(e0, e1);
         }
-        hipLaunchKernelGGL(k_es_score, dim3((int)blocks), dim3(kBlock), 0, stream, words, i == 0 ? 1 : 0,
+        hipLaunchKernelGGL(k_es_score, dim3((int)blocks), dim3(kBlock), 0, stream, n, words, i == 0 ? 1 : 0,
                            mode == GREM_EDGE_FIXED ? 1 : 0, (long long)P, S, mark, hc, Lb, est, mv0, mv1, bs0, bs1);
         if (i == 0) continue;
         hipLaunchKernelGGL(k_es_scan_movers, dim3(1), dim3(kBlock), 0, stream, blocks, bs0, bs1, bo0, bo1);
