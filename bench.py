@@ -37,6 +37,22 @@ PMC = {
 }
 
 
+# The same for the edge-chunk path's dominant kernel on its 111M-node workload.
+PMC_EDGE = {
+    "workload": "edges-chunglu-111M-c1pct",
+    "sources_sha256": "a0962f549d201cf419c7c0f0c5dacd3742221a484f1f980aca059ebd204f694e",
+    "fetch_kib": {"k_es_count": 1.928254e+08},
+    "write_kib": {"k_es_count": 9.980970e+07},
+    "launches": {"k_es_count": 100},
+}
+
+
+def edge_sources_sha256():
+    import hashlib
+    with open(os.path.join(ROOT, "paper_2502_17846_amd", "csrc", "grem_edge_stream.hip"), "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
+
+
 def sources_sha256():
     import hashlib
     h = hashlib.sha256()
@@ -209,6 +225,10 @@ def bench_edge_stream(args, w, dev):
         roofline.update(achieved=achieved, frac=achieved / HBM_PEAK_GBPS, avg_launch_us=1e6 * avg_s,
                         launches_per_step=launches, bytes_per_launch=bytes_per_launch,
                         count_ms_per_step=round(count_ms, 3))
+        if args.workload == PMC_EDGE["workload"] and PMC_EDGE["sources_sha256"] == edge_sources_sha256():
+            kib = (PMC_EDGE["fetch_kib"]["k_es_count"] * PMC["fetch_factor"]
+                   + PMC_EDGE["write_kib"]["k_es_count"] * PMC["write_factor"])
+            roofline["traffic"] = kib * 1024.0 / PMC_EDGE["launches"]["k_es_count"]
     out = {
         "metric": "edges/sec per GREM pass", "value": m / (elapsed / args.steps), "unit": "edges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
