@@ -291,3 +291,53 @@ class EdgeStepper:
             self.close()
         except Exception:
             pass
+
+
+# --------------------------------------------------------------------------------------------
+# recursive bisection (Sec. 4.1: more than two partitions by re-partitioning each part in two)
+# --------------------------------------------------------------------------------------------
+
+def recursive_bisection(src, dst, n, levels, chunks, balance_slack, seed_bits, mode=EDGE_REFINE,
+                        return_levels: bool = False):
+    """Labels in [0, 2^levels) for all n nodes.
+
+    Every node starts in group 0.  At each level every group g (ascending) is split in two by the
+    edge-chunk procedure run on the group's own subgraph: its nodes renumbered 0..nv-1 in ascending
+    id, the edges of the stream with both ends in the group, in stream order, in ceil(m_g / chunks)-edge
+    chunks, capacity P = capacity(nv, 2, balance_slack), first chunk seeded with
+    seed_bits[level] of its nodes (seed_bits: levels x n, the seed algorithm's answer at each level).  Nodes of the group that no such edge touches are then placed one by one, ascending id,
+    in the currently smaller half (0 on a tie).  A node of group g in half b moves to group 2g + b."""
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    dst = np.ascontiguousarray(dst, dtype=np.int32)
+    seed_bits = np.ascontiguousarray(seed_bits, dtype=np.int32).reshape(levels, n)
+    label = np.zeros(n, dtype=np.int32)
+    history = []
+    for level in range(levels):
+        nxt = np.empty(n, dtype=np.int32)
+        for g in range(1 << level):
+            members = np.nonzero(label == g)[0]
+            nv = members.size
+            if nv == 0:
+                continue
+            local = np.full(n, -1, dtype=np.int64)
+            local[members] = np.arange(nv)
+            inside = (label[src] == g) & (label[dst] == g)
+            s, d = local[src[inside]].astype(np.int32), local[dst[inside]].astype(np.int32)
+            parts = np.full(nv, -1, dtype=np.int32)
+            sizes = [0, 0]
+            if s.size > 0:
+                c_size = (s.size + chunks - 1) // chunks
+                P = capacity(nv, 2, balance_slack)
+                parts, sz, _ = edge_stream_bipartition(s, d, nv, c_size, P, seed_bits[level][members], mode,
+                                                       return_state=True)
+                sizes = [int(sz[0]), int(sz[1])]
+            for i in np.nonzero(parts < 0)[0]:
+                t = 1 if sizes[1] < sizes[0] else 0
+                parts[i] = t
+                sizes[t] += 1
+            nxt[members] = 2 * g + parts
+        label = nxt
+        history.append(label.copy())
+    if return_levels:
+        return label, history
+    return label

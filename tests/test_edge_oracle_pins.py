@@ -218,3 +218,96 @@ def test_determinism_and_errors():
     assert ei.value.code == oracle.ERR_SEED
     with pytest.raises(oracle.OracleError):              # endpoint out of range
         _run(np.array([0, n], np.int32), np.array([1, 2], np.int32), n, 1, 26, seed)
+
+
+# ---------------------------------------------------------------------------------------------
+# recursive bisection (Sec. 4.1): the driver around the two-partition procedure
+# ---------------------------------------------------------------------------------------------
+
+def _tiny_stream(rng, n, m):
+    src = rng.integers(0, n, m).astype(np.int32)
+    dst = rng.integers(0, n, m).astype(np.int32)
+    return src, dst
+
+
+def test_recursive_bisection_one_chunk_per_group_is_the_seed_bits():
+    # with a single chunk every group's run consists of its seeded first chunk only: a node touched by
+    # an inside edge takes its seed bit, the others alternate by size -- a closed form for the driver
+    # (grouping, renumbering, inside edges, placement, 2g+b) that needs no partitioner arithmetic
+    rng = np.random.default_rng(1)
+    n, m, levels = 64, 90, 3
+    src, dst = _tiny_stream(rng, n, m)
+    # slack 2: a half may hold the whole group, so any seed bits fit
+    for trial in range(5):
+        bits = rng.integers(0, 2, (levels, n)).astype(np.int32)
+        try:
+            lab, hist = oracle.recursive_bisection(src, dst, n, levels, 1, 2.0, bits, return_levels=True)
+        except oracle.OracleError:
+            continue            # the random bits overfilled a half
+        label = [0] * n
+        for level in range(levels):
+            nxt = list(label)
+            for g in range(1 << level):
+                mem = [v for v in range(n) if label[v] == g]
+                touched = set()
+                for a, b in zip(src.tolist(), dst.tolist()):
+                    if label[a] == g and label[b] == g:
+                        touched.add(a); touched.add(b)
+                sz = [sum(1 for v in mem if v in touched and bits[level][v] == 0),
+                      sum(1 for v in mem if v in touched and bits[level][v] == 1)]
+                for v in mem:
+                    if v in touched:
+                        nxt[v] = 2 * g + int(bits[level][v])
+                    else:
+                        t = 1 if sz[1] < sz[0] else 0
+                        sz[t] += 1
+                        nxt[v] = 2 * g + t
+            label = nxt
+            assert hist[level].tolist() == label, (trial, level)
+        return
+    raise AssertionError("no trial fitted the capacity")
+
+
+def test_recursive_bisection_groups_are_runs_of_the_pinned_two_partition_oracle():
+    # second level rebuilt by hand from the first level's labels, with python lists, and handed to the
+    # two-partition oracle that the tests above pin
+    rng = np.random.default_rng(2)
+    n, m, chunks, slack = 60, 400, 5, 1.2
+    src, dst = _tiny_stream(rng, n, m)
+    bits = np.stack([np.arange(n) % 2, (np.arange(n) // 2) % 2]).astype(np.int32)
+    lab2, hist = oracle.recursive_bisection(src, dst, n, 2, chunks, slack, bits, return_levels=True)
+    lab1 = oracle.recursive_bisection(src, dst, n, 1, chunks, slack, bits[:1])
+    assert hist[0].tolist() == lab1.tolist()                  # deeper levels do not change earlier ones
+    assert (lab2 >> 1).tolist() == lab1.tolist()
+    for g in (0, 1):
+        mem = [v for v in range(n) if lab1[v] == g]
+        pos = {v: i for i, v in enumerate(mem)}
+        sub = [(pos[a], pos[b]) for a, b in zip(src.tolist(), dst.tolist()) if a in pos and b in pos]
+        s = np.array([e[0] for e in sub], np.int32)
+        d = np.array([e[1] for e in sub], np.int32)
+        c_size = -(-len(sub) // chunks)
+        P = oracle.capacity(len(mem), 2, slack)
+        parts, sizes, _ = _run(s, d, len(mem), c_size, P, bits[1][mem])
+        sz = sizes.tolist()
+        for i in range(len(mem)):
+            if parts[i] < 0:
+                t = 1 if sz[1] < sz[0] else 0
+                sz[t] += 1
+                parts[i] = t
+        assert lab2[mem].tolist() == (2 * g + parts).tolist()
+        assert max(sz) <= P and sum(sz) == len(mem)
+
+
+def test_recursive_bisection_recovers_four_planted_blocks():
+    g = synth.planted_partition(n=4000, blocks=4, mean_degree=14.0, seed=3)
+    es = synth.edge_stream(g, seed=4)
+    # seed_algo stands in as the planted block's high bit at the first level and its low bit at the second
+    bits = np.stack([g.planted >> 1, g.planted & 1]).astype(np.int32)
+    lab, hist = oracle.recursive_bisection(es.src, es.dst, g.n, 2, 10, 1.05, bits, return_levels=True)
+    assert (hist[0] == bits[0]).mean() > 0.9
+    assert (lab == g.planted).mean() > 0.8
+    sizes = np.bincount(lab, minlength=4)
+    assert sizes.sum() == g.n and sizes.max() <= oracle.capacity(oracle.capacity(g.n, 2, 1.05), 2, 1.05)
+    assert oracle.edge_list_cut(es.src, es.dst, lab) < 2.0 * oracle.edge_list_cut(es.src, es.dst, g.planted)
+    fixed = oracle.recursive_bisection(es.src, es.dst, g.n, 2, 10, 1.05, bits, oracle.EDGE_FIXED)
+    assert oracle.edge_list_cut(es.src, es.dst, lab) < oracle.edge_list_cut(es.src, es.dst, fixed)
