@@ -197,6 +197,23 @@ int grem_edge_stream_bipartition(const int32_t *src, const int32_t *dst, int64_t
                                  int32_t *parts_out, int64_t *sizes_out, double *nbr_counts_out,
                                  void *stream);
 
+/* More than two partitions the paper's way (Sec. 4.1: partition into two, then re-partition each
+ * part in two; Sec. 6.2: GREM partitions recursively for p > 2): 2^levels partitions.
+ * Every node starts in group 0.  At level l = 0..levels-1 every group g (ascending) is split by
+ * grem_edge_stream_bipartition run on the group's own subgraph: its nodes renumbered 0..nv-1 in
+ * ascending id; the listed edges with both ends in the group, in stream order, in chunks of
+ * ceil(m_g / chunks) edges; P = grem_capacity(nv, 2, balance_slack); first chunk seeded with
+ * seed_bits[l*n + v] (the seed algorithm's answer at that level, handed in as data; 0 or 1).  Nodes of
+ * the group that no such edge touches are then placed one by one, ascending id, in the currently
+ * smaller half (0 on a tie).  A node of group g in half b moves to group 2g + b.
+ * seed_bits: levels*n int32; labels_out: n int32, each in [0, 2^levels).  Device pointers.  Scratch
+ * (about 24 bytes per edge and 30 per node) is allocated on `stream`; the call reads back a few
+ * counters per group.  Errors as for grem_edge_stream_bipartition, plus GREM_ERR_ARG for levels
+ * outside 1..20, chunks < 1, balance_slack < 1. */
+int grem_recursive_bisection(const int32_t *src, const int32_t *dst, int64_t m, int64_t n,
+                             int32_t levels, int64_t chunks, double balance_slack,
+                             const int32_t *seed_bits, int32_t mode, int32_t *labels_out, void *stream);
+
 /* Number of listed edges whose ends carry different labels (Sec. 1), written to the single device
  * int64 *cut_out.  parts: int32 labels covering every listed id, any values. */
 int grem_edge_list_cut(const int32_t *src, const int32_t *dst, int64_t m, const int32_t *parts,

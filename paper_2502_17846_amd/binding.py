@@ -27,7 +27,7 @@ EXPORTS = [
     "grem_set_sweep_col_bits", "grem_set_sweep_hub_degree", "grem_set_long_row_degree", "grem_profile_enable",
     "grem_profile_reset", "grem_profile_read", "grem_status_string", "grem_kernel_name",
     "grem_edge_stream_bipartition", "grem_edge_list_cut", "grem_edge_stream_profile_enable",
-    "grem_edge_stream_profile_read",
+    "grem_edge_stream_profile_read", "grem_recursive_bisection",
 ]
 EDGE_REFINE, EDGE_FIXED = 0, 1
 
@@ -88,6 +88,8 @@ def load():
     lib.grem_kernel_name.argtypes = [i32]
     lib.grem_edge_stream_bipartition.restype = ctypes.c_int
     lib.grem_edge_stream_bipartition.argtypes = [vp, vp, i64, i64, i64, i64, vp, i32, vp, vp, vp, vp]
+    lib.grem_recursive_bisection.restype = ctypes.c_int
+    lib.grem_recursive_bisection.argtypes = [vp, vp, i64, i64, i32, i64, dbl, vp, i32, vp, vp]
     lib.grem_edge_list_cut.restype = ctypes.c_int
     lib.grem_edge_list_cut.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.grem_edge_stream_profile_enable.restype = ctypes.c_int
@@ -301,3 +303,16 @@ def grem_edge_stream_profile_read():
     _check(load().grem_edge_stream_profile_read(ctypes.byref(ms), ctypes.byref(cnt)),
            "grem_edge_stream_profile_read")
     return ms.value, cnt.value
+
+
+def grem_recursive_bisection(src, dst, n, levels, chunks, balance_slack, seed_bits, mode=EDGE_REFINE, stream=None):
+    """Labels int32[n] in [0, 2^levels); seed_bits: int32 tensor of levels*n entries (levels x n)."""
+    lib = load()
+    if seed_bits.numel() != levels * n:
+        raise ValueError("seed_bits must have levels*n entries")
+    labels = torch.empty(n, dtype=torch.int32, device=src.device)
+    rc = lib.grem_recursive_bisection(_dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"), src.numel(), n,
+                                      levels, chunks, float(balance_slack), _dev(seed_bits, torch.int32, "seed_bits"),
+                                      mode, _dev(labels, torch.int32, "labels_out"), _stream(stream))
+    _check(rc, "grem_recursive_bisection")
+    return labels

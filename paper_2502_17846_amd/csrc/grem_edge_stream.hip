@@ -416,6 +416,178 @@ __global__ __launch_bounds__(256) void k_es_cut(const int32_t* __restrict__ src,
     }
 }
 
+// ---- recursive bisection (Sec. 4.1: more than two partitions by splitting every part in two) ------
+//
+// Per level the edges that still lie inside a group are kept grouped by group, in stream order; a
+// group's nodes are renumbered 0..nv-1 in ascending id for the two-partition run on its subgraph.
+
+constexpr int kSelBlock = 1024;     // stable selection of edges: a thread owns kSelPer consecutive edges
+constexpr int kSelPer = 4;
+constexpr int kSelTile = kSelBlock * kSelPer;
+
+// flag bitmap of a predicate over items 0..count-1 (what = 0: value[i] == key, what = 1: value[i] < 0)
+// and the number of flagged items per workgroup of kBlock items
+__global__ __launch_bounds__(kBlock) void k_rb_flags(int64_t count, const int32_t* __restrict__ value, int32_t key,
+                                                     int what, u64* flag, uint32_t* bsum)
+{
+    __shared__ uint32_t c[kWordsPerBlock];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    bool on = false;
+    if (i < count) { const int32_t x = value[i]; on = what == 0 ? x == key : x < 0; }
+    const u64 b = __ballot(on);
+    if (lane == 0) {
+        const int64_t w = (int64_t)blockIdx.x * kWordsPerBlock + wave;
+        if (w * 64 < count) flag[w] = b;
+        c[wave] = __popcll(b);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int q = 0; q < kWordsPerBlock; ++q) t += c[q];
+        bsum[blockIdx.x] = t;
+    }
+}
+
+// exclusive scan of the per-workgroup counts; the total goes to total_out[0]
+__global__ __launch_bounds__(kBlock) void k_rb_scan(int64_t blocks, const uint32_t* bsum, uint32_t* boff, long long* total_out)
+{
+    __shared__ uint32_t wsum[kWordsPerBlock];
+    const uint32_t total = es_block_scan(bsum, boff, blocks, wsum);
+    if (threadIdx.x == 0) total_out[0] = (long long)total;
+}
+
+// rank of a flagged item among the flagged ones, ascending index
+__device__ __forceinline__ uint32_t rb_rank(const u64* __restrict__ flag, const uint32_t* __restrict__ boff,
+                                            uint32_t* c /* kWordsPerBlock words of LDS */, int64_t count, bool& on)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t w = (int64_t)blockIdx.x * kWordsPerBlock + wave;
+    const u64 word = w * 64 < count ? flag[w] : 0ull;
+    if (lane == 0) c[wave] = __popcll(word);
+    __syncthreads();
+    uint32_t r = boff[blockIdx.x];
+    for (int q = 0; q < wave; ++q) r += c[q];
+    on = (word >> lane) & 1ull;
+    return r + __popcll(word & ((1ull << lane) - 1ull));
+}
+
+// members of a group get their number inside the group; the group's tables are filled
+__global__ __launch_bounds__(kBlock) void k_rb_number(int64_t n, const u64* __restrict__ flag, const uint32_t* __restrict__ boff,
+                                                      const int32_t* __restrict__ seed_bits, int32_t* local_id,
+                                                      int32_t* global_of, int32_t* sub_seed)
+{
+    __shared__ uint32_t c[kWordsPerBlock];
+    bool on;
+    const uint32_t r = rb_rank(flag, boff, c, n, on);
+    const int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (on) { local_id[v] = (int32_t)r; global_of[r] = (int32_t)v; sub_seed[r] = seed_bits[v]; }
+}
+
+__global__ __launch_bounds__(256) void k_rb_map(int64_t m, const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                                const int32_t* __restrict__ local_id, int32_t* sub_src, int32_t* sub_dst)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < m; e += stride) {
+        sub_src[e] = local_id[src[e]];
+        sub_dst[e] = local_id[dst[e]];
+    }
+}
+
+// A group's nodes move to group 2g + half; nodes the two-partition run left without a label (no edge
+// inside the group) are placed one by one, ascending id, in the currently smaller half (0 on a tie):
+// closed form from the run's sizes, as for the spill of the two-partition run.
+__global__ __launch_bounds__(kBlock) void k_rb_finish(int64_t nv, const u64* __restrict__ flag, const uint32_t* __restrict__ boff,
+                                                      const int32_t* __restrict__ sub_parts, const int64_t* __restrict__ sub_sizes,
+                                                      const int32_t* __restrict__ global_of, int32_t g, int32_t* next_label)
+{
+    __shared__ uint32_t c[kWordsPerBlock];
+    bool on;
+    const long long j = rb_rank(flag, boff, c, nv, on);
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= nv) return;
+    int part = sub_parts[i];
+    if (on) {
+        const long long a = sub_sizes[0], b = sub_sizes[1];
+        const long long gap = a <= b ? b - a : a - b;
+        part = j < gap ? (a <= b ? 0 : 1) : (int)((j - gap) & 1);
+    }
+    next_label[global_of[i]] = 2 * g + part;
+}
+
+// which child group an edge of group g goes to in the next level: 0 / 1, or 2 when its ends part
+__device__ __forceinline__ int rb_child(int32_t a, int32_t b, int32_t g) { return a == b ? a - 2 * g : 2; }
+
+__global__ __launch_bounds__(kSelBlock) void k_rb_split_count(int64_t m, const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                                              const int32_t* __restrict__ next_label, int32_t g,
+                                                              uint32_t* bc0, uint32_t* bc1)
+{
+    __shared__ uint32_t c0[kSelBlock / 64], c1[kSelBlock / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t e0 = (int64_t)blockIdx.x * kSelTile + (int64_t)threadIdx.x * kSelPer;
+    uint32_t n0 = 0, n1 = 0;
+#pragma unroll
+    for (int u = 0; u < kSelPer; ++u) {
+        const int64_t e = e0 + u;
+        if (e < m) {
+            const int k = rb_child(next_label[src[e]], next_label[dst[e]], g);
+            n0 += k == 0; n1 += k == 1;
+        }
+    }
+    n0 = es_wave_sum(n0); n1 = es_wave_sum(n1);
+    if (lane == 0) { c0[wave] = n0; c1[wave] = n1; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t x = 0, y = 0;
+        for (int q = 0; q < kSelBlock / 64; ++q) { x += c0[q]; y += c1[q]; }
+        bc0[blockIdx.x] = x; bc1[blockIdx.x] = y;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_rb_split_scan(int64_t blocks, const uint32_t* bc0, const uint32_t* bc1,
+                                                          uint32_t* bo0, uint32_t* bo1, long long* totals)
+{
+    __shared__ uint32_t wsum[kWordsPerBlock];
+    const uint32_t t0 = es_block_scan(bc0, bo0, blocks, wsum);
+    const uint32_t t1 = es_block_scan(bc1, bo1, blocks, wsum);
+    if (threadIdx.x == 0) { totals[0] = (long long)t0; totals[1] = (long long)t1; }
+}
+
+// stable: the edges of child 0 keep their order and land at out0 + ..., those of child 1 at out1 + ...
+__global__ __launch_bounds__(kSelBlock) void k_rb_split_scatter(int64_t m, const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                                                const int32_t* __restrict__ next_label, int32_t g,
+                                                                const uint32_t* __restrict__ bo0, const uint32_t* __restrict__ bo1,
+                                                                int32_t* out_src, int32_t* out_dst, int64_t at0,
+                                                                const long long* __restrict__ totals)
+{
+    __shared__ uint32_t c0[kSelBlock / 64], c1[kSelBlock / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t e0 = (int64_t)blockIdx.x * kSelTile + (int64_t)threadIdx.x * kSelPer;
+    int32_t s[kSelPer], d[kSelPer];
+    int k[kSelPer];
+    uint32_t n0 = 0, n1 = 0;
+#pragma unroll
+    for (int u = 0; u < kSelPer; ++u) {
+        const int64_t e = e0 + u;
+        k[u] = 2; s[u] = 0; d[u] = 0;
+        if (e < m) {
+            s[u] = src[e]; d[u] = dst[e];
+            k[u] = rb_child(next_label[s[u]], next_label[d[u]], g);
+            n0 += k[u] == 0; n1 += k[u] == 1;
+        }
+    }
+    const uint32_t x0 = es_wave_exclusive(n0, lane), x1 = es_wave_exclusive(n1, lane);
+    if (lane == 63) { c0[wave] = x0 + n0; c1[wave] = x1 + n1; }
+    __syncthreads();
+    int64_t p0 = at0 + bo0[blockIdx.x] + x0, p1 = at0 + totals[0] + bo1[blockIdx.x] + x1;
+    for (int q = 0; q < wave; ++q) { p0 += c0[q]; p1 += c1[q]; }
+#pragma unroll
+    for (int u = 0; u < kSelPer; ++u) {
+        if (k[u] == 0) { out_src[p0] = s[u]; out_dst[p0] = d[u]; ++p0; }
+        else if (k[u] == 1) { out_src[p1] = s[u]; out_dst[p1] = d[u]; ++p1; }
+    }
+}
+
 // ---- host side ---------------------------------------------------------------------------------
 
 struct EsProfile {
@@ -533,6 +705,120 @@ int grem_edge_stream_bipartition(const int32_t* src, const int32_t* dst, int64_t
     }
     hipLaunchKernelGGL(k_es_expand, dim3(grid_for(n, 256, 16384)), dim3(256), 0, stream, n, Lb, parts_out, S, sizes_out);
     if (hipGetLastError() != hipSuccess) rc = GREM_ERR_HIP;
+    if (hipFreeAsync(ws, stream) != hipSuccess) rc = GREM_ERR_HIP;
+    return rc;
+}
+
+int grem_recursive_bisection(const int32_t* src, const int32_t* dst, int64_t m, int64_t n, int32_t levels,
+                             int64_t chunks, double balance_slack, const int32_t* seed_bits, int32_t mode,
+                             int32_t* labels_out, void* stream_)
+{
+    if (!src || !dst || !seed_bits || !labels_out || m < 1 || n < 1 || n > INT32_MAX || levels < 1 || levels > 20 ||
+        chunks < 1 || !(balance_slack >= 1.0) || (mode != GREM_EDGE_REFINE && mode != GREM_EDGE_FIXED))
+        return GREM_ERR_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    const int64_t node_blocks = (n + kBlock - 1) / kBlock;
+    const int64_t sel_blocks = (m + kSelTile - 1) / kSelTile;
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return at; };
+    const size_t o_small = carve(256);                 // totals[2], nv, flags
+    const size_t o_label = carve((size_t)n * 4), o_next = carve((size_t)n * 4);
+    const size_t o_local = carve((size_t)n * 4), o_global = carve((size_t)n * 4), o_seed = carve((size_t)n * 4);
+    const size_t o_parts = carve((size_t)n * 4 + 8), o_sizes = carve(16);
+    const size_t o_flag = carve((size_t)((n + 63) / 64) * 8);
+    const size_t o_bsum = carve((size_t)node_blocks * 4), o_boff = carve((size_t)node_blocks * 4);
+    size_t o_sel[4];
+    for (int i = 0; i < 4; ++i) o_sel[i] = carve((size_t)sel_blocks * 4);
+    const size_t o_subs = carve((size_t)m * 4), o_subd = carve((size_t)m * 4);
+    size_t o_lev[4];                                   // two generations of the grouped edge list
+    for (int i = 0; i < 4; ++i) o_lev[i] = carve((size_t)m * 4);
+    uint8_t* ws = nullptr;
+    if (hipMallocAsync((void**)&ws, off, stream) != hipSuccess) { (void)hipGetLastError(); return GREM_ERR_NOMEM; }
+    auto fail = [&](int code) { (void)hipGetLastError(); (void)hipStreamSynchronize(stream); (void)hipFreeAsync(ws, stream); return code; };
+    long long* totals = (long long*)(ws + o_small);    // [0..1] split totals, [2] member / unassigned count
+    uint32_t* flags = (uint32_t*)(ws + o_small + 64);
+    int32_t *label = (int32_t*)(ws + o_label), *next = (int32_t*)(ws + o_next);
+    int32_t *local_id = (int32_t*)(ws + o_local), *global_of = (int32_t*)(ws + o_global), *sub_seed = (int32_t*)(ws + o_seed);
+    int32_t* sub_parts = (int32_t*)(ws + o_parts);
+    int64_t* sub_sizes = (int64_t*)(ws + o_sizes);
+    u64* flag = (u64*)(ws + o_flag);
+    uint32_t *bsum = (uint32_t*)(ws + o_bsum), *boff = (uint32_t*)(ws + o_boff);
+    uint32_t *bc0 = (uint32_t*)(ws + o_sel[0]), *bc1 = (uint32_t*)(ws + o_sel[1]);
+    uint32_t *bo0 = (uint32_t*)(ws + o_sel[2]), *bo1 = (uint32_t*)(ws + o_sel[3]);
+    int32_t *sub_src = (int32_t*)(ws + o_subs), *sub_dst = (int32_t*)(ws + o_subd);
+
+    auto fill = [&](void* p, size_t bytes, u64 value) {
+        const size_t count = bytes / 8;
+        hipLaunchKernelGGL(k_es_fill64, dim3(grid_for((int64_t)count, 256, 16384)), dim3(256), 0, stream, (u64*)p, count, value);
+    };
+    struct { long long totals[3]; long long pad[5]; uint32_t flags[2]; } host;
+    auto read_small = [&]() {
+        return hipMemcpyAsync(&host, ws + o_small, sizeof(host), hipMemcpyDeviceToHost, stream) == hipSuccess &&
+               hipStreamSynchronize(stream) == hipSuccess;
+    };
+    fill(ws + o_small, 256, 0ull);
+    fill(label, align256((size_t)n * 4), 0ull);        // every node starts in group 0
+    hipLaunchKernelGGL(k_es_check, dim3(grid_for(m, 256, 8192)), dim3(256), 0, stream, src, dst, m, (uint32_t)n, flags);
+    if (!read_small()) return fail(GREM_ERR_HIP);
+    if (host.flags[0]) return fail(GREM_ERR_ARG);
+
+    // edges grouped by group: level 0 is the input itself, one group
+    const int32_t *cur_s = src, *cur_d = dst;
+    std::vector<int64_t> goff{0, m};
+    for (int32_t level = 0; level < levels; ++level) {
+        int32_t* out_s = (int32_t*)(ws + o_lev[(level & 1) * 2]);
+        int32_t* out_d = (int32_t*)(ws + o_lev[(level & 1) * 2 + 1]);
+        const int32_t groups = 1 << level;
+        std::vector<int64_t> next_off((size_t)2 * groups + 1, 0);
+        const int32_t* bits = seed_bits + (size_t)level * (size_t)n;
+        for (int32_t g = 0; g < groups; ++g) {
+            const int64_t e_lo = goff[g], mg = goff[g + 1] - goff[g];
+            next_off[2 * g + 1] = next_off[2 * g + 2] = next_off[2 * g];
+            // the group's nodes, numbered in ascending id
+            hipLaunchKernelGGL(k_rb_flags, dim3((int)node_blocks), dim3(kBlock), 0, stream, n, label, g, 0, flag, bsum);
+            hipLaunchKernelGGL(k_rb_scan, dim3(1), dim3(kBlock), 0, stream, node_blocks, bsum, boff, totals + 2);
+            if (!read_small()) return fail(GREM_ERR_HIP);
+            const int64_t nv = host.totals[2];
+            if (nv == 0) continue;
+            hipLaunchKernelGGL(k_rb_number, dim3((int)node_blocks), dim3(kBlock), 0, stream, n, flag, boff, bits,
+                               local_id, global_of, sub_seed);
+            if (mg > 0) {
+                hipLaunchKernelGGL(k_rb_map, dim3(grid_for(mg, 256, 16384)), dim3(256), 0, stream, mg, cur_s + e_lo, cur_d + e_lo,
+                                   local_id, sub_src, sub_dst);
+                const int64_t c_size = (mg + chunks - 1) / chunks;
+                const int64_t P = grem_capacity(nv, 2, balance_slack);
+                const int rc = grem_edge_stream_bipartition(sub_src, sub_dst, mg, nv, c_size, P, sub_seed, mode, sub_parts,
+                                                            sub_sizes, nullptr, stream_);
+                if (rc != GREM_OK) return fail(rc);
+            } else {
+                fill(sub_parts, ((size_t)nv * 4 + 7) & ~(size_t)7, ~0ull);
+                fill(sub_sizes, 16, 0ull);
+            }
+            // unlabelled nodes are placed, everyone moves to 2g + half
+            const int64_t vb = (nv + kBlock - 1) / kBlock;
+            hipLaunchKernelGGL(k_rb_flags, dim3((int)vb), dim3(kBlock), 0, stream, nv, sub_parts, 0, 1, flag, bsum);
+            hipLaunchKernelGGL(k_rb_scan, dim3(1), dim3(kBlock), 0, stream, vb, bsum, boff, totals + 2);
+            hipLaunchKernelGGL(k_rb_finish, dim3((int)vb), dim3(kBlock), 0, stream, nv, flag, boff, sub_parts, sub_sizes,
+                               global_of, g, next);
+            // the group's edges that stay inside a half, for the next level
+            if (mg > 0 && level + 1 < levels) {
+                const int64_t sb = (mg + kSelTile - 1) / kSelTile;
+                hipLaunchKernelGGL(k_rb_split_count, dim3((int)sb), dim3(kSelBlock), 0, stream, mg, cur_s + e_lo, cur_d + e_lo,
+                                   next, g, bc0, bc1);
+                hipLaunchKernelGGL(k_rb_split_scan, dim3(1), dim3(kBlock), 0, stream, sb, bc0, bc1, bo0, bo1, totals);
+                hipLaunchKernelGGL(k_rb_split_scatter, dim3((int)sb), dim3(kSelBlock), 0, stream, mg, cur_s + e_lo, cur_d + e_lo,
+                                   next, g, bo0, bo1, out_s, out_d, next_off[2 * g], totals);
+                if (!read_small()) return fail(GREM_ERR_HIP);
+                next_off[2 * g + 1] = next_off[2 * g] + host.totals[0];
+                next_off[2 * g + 2] = next_off[2 * g + 1] + host.totals[1];
+            }
+        }
+        std::swap(label, next);
+        cur_s = out_s; cur_d = out_d;
+        goff.swap(next_off);
+    }
+    if (hipMemcpyAsync(labels_out, label, (size_t)n * 4, hipMemcpyDeviceToDevice, stream) != hipSuccess) return fail(GREM_ERR_HIP);
+    int rc = hipGetLastError() == hipSuccess ? GREM_OK : GREM_ERR_HIP;
     if (hipFreeAsync(ws, stream) != hipSuccess) rc = GREM_ERR_HIP;
     return rc;
 }

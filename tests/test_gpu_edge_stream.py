@@ -132,3 +132,57 @@ def test_errors():
     parts, sizes, _ = B.grem_edge_stream_bipartition(src, dst, n, 10, 60, ok)
     torch.cuda.synchronize()
     assert int(sizes.sum()) == 100 and int(parts.min()) >= 0
+
+
+# ---------------------------------------------------------------------------------------------
+# recursive bisection
+# ---------------------------------------------------------------------------------------------
+
+def _check_rb(src, dst, n, levels, chunks, slack, bits, mode=B.EDGE_REFINE, tag=""):
+    print(f"[case] recursive bisection {tag} n={n} m={len(src)} levels={levels} chunks={chunks} slack={slack}", flush=True)
+    lab = B.grem_recursive_bisection(_t(src), _t(dst), n, levels, chunks, slack, _t(bits).reshape(-1), mode)
+    torch.cuda.synchronize()
+    olab = oracle.recursive_bisection(src, dst, n, levels, chunks, slack, bits, mode)
+    assert np.array_equal(lab.cpu().numpy(), olab), tag
+    return olab
+
+
+def test_recursive_bisection_planted_blocks():
+    g = synth.planted_partition(n=10_000, blocks=4, mean_degree=12.0, seed=5)
+    es = synth.edge_stream(g, seed=6)
+    bits = np.stack([g.planted >> 1, g.planted & 1]).astype(np.int32)
+    for mode in (B.EDGE_REFINE, B.EDGE_FIXED):
+        lab = _check_rb(es.src, es.dst, g.n, 2, 20, 1.05, bits, mode, tag="planted 4 blocks")
+        assert np.bincount(lab, minlength=4).max() <= oracle.capacity(oracle.capacity(g.n, 2, 1.05), 2, 1.05)
+
+
+@pytest.mark.parametrize("seed_", range(3))
+def test_recursive_bisection_random_multigraphs(seed_):
+    # loops, repeated edges, nodes in no edge (placed by size), groups that run out of inside edges
+    rng = np.random.default_rng(100 + seed_)
+    n = int(rng.integers(2_000, 9_000))
+    m = int(rng.integers(n, 6 * n))
+    src = rng.integers(0, n - 50, m).astype(np.int32)
+    dst = np.where(rng.random(m) < 0.02, src, rng.integers(0, n - 50, m)).astype(np.int32)
+    levels = int(rng.integers(1, 6))
+    bits = np.stack([(np.arange(n) >> l) & 1 for l in range(levels)]).astype(np.int32)
+    _check_rb(src, dst, n, levels, int(rng.integers(1, 30)), 1.1, bits, tag=f"multigraph {seed_}")
+
+
+def test_recursive_bisection_sparse_graph_deep_levels():
+    # fewer edges than nodes: deep levels meet groups without inside edges and empty chunks' tails
+    rng = np.random.default_rng(7)
+    n, m = 3_000, 2_000
+    src = rng.integers(0, n, m).astype(np.int32)
+    dst = rng.integers(0, n, m).astype(np.int32)
+    bits = np.stack([(np.arange(n) >> l) & 1 for l in range(7)]).astype(np.int32)
+    lab = _check_rb(src, dst, n, 7, 4, 1.3, bits, tag="sparse deep")
+    assert lab.max() < 128
+
+
+def test_recursive_bisection_rmat():
+    g = synth.rmat(16, 8, seed=3)
+    es = synth.edge_stream(g, seed=4)
+    src, dst = es.src.numpy(), es.dst.numpy()
+    bits = np.stack([(np.arange(g.n) >> l) & 1 for l in range(4)]).astype(np.int32)
+    _check_rb(src, dst, g.n, 4, 25, 1.05, bits, tag="rmat-16 k=16")
