@@ -90,6 +90,12 @@ WORKLOADS = {
                                      c_frac=0.01, slack=1.05),
     "edges-chunglu-111M-c10pct": dict(kind="chung_lu", n=111_000_000, m=1_600_000_000, bits=64, stream=True,
                                       c_frac=0.10, slack=1.05),
+    # 16 partitions by recursive bisection (Sec. 4.1, 6.2): 4 levels, every subgraph streamed in 100 chunks;
+    # the per-level slack is chosen so that the compound bound equals the direct 16-way run's 1.05
+    "rb-chunglu-111M-k16": dict(kind="chung_lu", n=111_000_000, m=1_600_000_000, bits=64, stream=True, levels=4,
+                                chunks=100, slack=1.05 ** 0.25, direct=dict(k=16, slack=1.05, chunk=1 << 20, R=2)),
+    "rb-chunglu-14M-k16": dict(kind="chung_lu", n=13_875_000, m=200_000_000, bits=64, stream=True, levels=4,
+                               chunks=100, slack=1.05 ** 0.25, direct=dict(k=16, slack=1.05, chunk=1 << 17, R=2)),
     "edges-chunglu-14M-c1pct": dict(kind="chung_lu", n=13_875_000, m=200_000_000, bits=64, stream=True,
                                     c_frac=0.01, slack=1.05),
 }
@@ -217,7 +223,7 @@ def bench_edge_stream(args, w, dev):
         B.grem_edge_stream_profile_enable(True)
         step()
         torch.cuda.synchronize()
-        count_ms, launches = B.grem_edge_stream_profile_read()
+        count_ms, launches, _ = B.grem_edge_stream_profile_read()
         B.grem_edge_stream_profile_enable(False)
         bytes_per_launch = 8.0 * m / launches
         avg_s = 1e-3 * count_ms / launches
@@ -257,6 +263,75 @@ def bench_edge_stream(args, w, dev):
         out["cpu_baseline"] = {"value": min(ms_, done * c_size) / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
                                "sample": f"first {done} of {nchunks} chunks ({min(ms_, done * c_size)} edges) of the "
                                          f"same stream, {dt:.1f} s, state for all {n} nodes"}
+    print(json.dumps(out))
+
+
+def bench_recursive(args, w, dev):
+    """2^levels partitions by recursive bisection: a step is the whole recursion."""
+    import torch
+    from paper_2502_17846_amd import binding as B
+    from paper_2502_17846_amd import synth
+    t_gen = time.perf_counter()
+    g = make_graph(w, dev)
+    es = synth.edge_stream(g, seed=1)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+    n, m, levels, chunks = es.n, es.m, w["levels"], w["chunks"]
+    ids = torch.arange(n, device=dev, dtype=torch.int32)
+    seed_bits = torch.stack([(ids >> l) & 1 for l in range(levels)]).contiguous()   # stands for seed_algo
+    print(f"[bench] {es.name}: n={n} edges={m} levels={levels} chunks={chunks} generated in {t_gen:.1f}s",
+          file=sys.stderr, flush=True)
+    out_lab = [None]
+
+    def step():
+        out_lab[0] = B.grem_recursive_bisection(es.src, es.dst, n, levels, chunks, w["slack"], seed_bits.reshape(-1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    lab = out_lab[0]
+    k = 1 << levels
+    sizes = torch.bincount(lab, minlength=k)
+    cut = int(B.grem_edge_list_cut(es.src, es.dst, lab).item())
+    roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": None,
+                "traffic": None, "kernel": "k_es_count"}
+    if not args.no_kernel_timing:
+        B.grem_edge_stream_profile_enable(True)
+        step()
+        torch.cuda.synchronize()
+        count_ms, launches, streamed = B.grem_edge_stream_profile_read()
+        B.grem_edge_stream_profile_enable(False)
+        # algorithmic bytes of k_es_count: the two ids of every edge it is handed
+        bytes_per_launch = 8.0 * streamed / launches
+        avg_s = 1e-3 * count_ms / launches
+        achieved = bytes_per_launch / avg_s / 1e9
+        roofline.update(achieved=achieved, frac=achieved / HBM_PEAK_GBPS, avg_launch_us=1e6 * avg_s,
+                        launches_per_step=launches, bytes_per_launch=bytes_per_launch,
+                        count_ms_per_step=round(count_ms, 3), edges_streamed_per_step=streamed)
+    # the direct k-way run of the row-chunk path on the same graph, for the cut comparison
+    d = w["direct"]
+    dlab = B.grem_partition(g.rowptr, g.colidx, n, d["k"], d["slack"], d["chunk"], d["R"])
+    dcut = int(B.grem_edge_list_cut(es.src, es.dst, dlab).item())
+    torch.cuda.synchronize()
+    out = {
+        "metric": "edges/sec per GREM pass",
+        "value": (roofline.get("edges_streamed_per_step") or m * levels) / (elapsed / args.steps), "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {es.name}; {k} partitions by {levels} levels of bisection, "
+                               f"{chunks} chunks per subgraph, slack {w['slack']:.5f} per level, seeds = id bits",
+                   "n": n, "edges": m, "levels": levels},
+        "note": "value counts the edges actually streamed over all levels (edges cut at a level leave the stream)",
+        "cut_fraction": cut / m, "max_partition_size": int(sizes.max()), "min_partition_size": int(sizes.min()),
+        "direct_kway": {"cut_fraction": dcut / m, "config": d,
+                        "max_partition_size": int(torch.bincount(dlab, minlength=k).max())},
+        "roofline": roofline,
+    }
     print(json.dumps(out))
 
 
@@ -301,6 +376,9 @@ def main():
                           "bytes_written_per_launch": nbytes, "launches": 8}))
         return
     w = WORKLOADS[args.workload]
+    if w.get("levels"):
+        bench_recursive(args, w, dev)
+        return
     if w.get("stream"):
         bench_edge_stream(args, w, dev)
         return

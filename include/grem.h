@@ -221,9 +221,11 @@ int grem_edge_list_cut(const int32_t *src, const int32_t *dst, int64_t m, const 
 
 /* Timing of the edge kernel (cnt_nbrs over a chunk's edges) with HIP events on the caller's stream,
  * for measurement: while enabled each launch is bracketed by two events; the read synchronises on
- * them, returns their total in milliseconds and the launch count, and forgets them. */
+ * them, returns their total in milliseconds, the launch count and the number of edges those
+ * launches processed (each may be NULL), and forgets them.  Calls made by
+ * grem_recursive_bisection are included. */
 int grem_edge_stream_profile_enable(int32_t on);
-int grem_edge_stream_profile_read(double *count_ms, int64_t *launches);
+int grem_edge_stream_profile_read(double *count_ms, int64_t *launches, int64_t *edges);
 
 const char *grem_status_string(int code);
 const char *grem_kernel_name(int32_t kernel_class);

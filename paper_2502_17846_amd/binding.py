@@ -95,7 +95,7 @@ def load():
     lib.grem_edge_stream_profile_enable.restype = ctypes.c_int
     lib.grem_edge_stream_profile_enable.argtypes = [i32]
     lib.grem_edge_stream_profile_read.restype = ctypes.c_int
-    lib.grem_edge_stream_profile_read.argtypes = [ctypes.POINTER(dbl), ctypes.POINTER(i64)]
+    lib.grem_edge_stream_profile_read.argtypes = [ctypes.POINTER(dbl), ctypes.POINTER(i64), ctypes.POINTER(i64)]
     _lib = lib
     return lib
 
@@ -300,9 +300,10 @@ def grem_edge_stream_profile_enable(on: bool):
 def grem_edge_stream_profile_read():
     ms = ctypes.c_double(0.0)
     cnt = ctypes.c_int64(0)
-    _check(load().grem_edge_stream_profile_read(ctypes.byref(ms), ctypes.byref(cnt)),
+    edges = ctypes.c_int64(0)
+    _check(load().grem_edge_stream_profile_read(ctypes.byref(ms), ctypes.byref(cnt), ctypes.byref(edges)),
            "grem_edge_stream_profile_read")
-    return ms.value, cnt.value
+    return ms.value, cnt.value, edges.value
 
 
 def grem_recursive_bisection(src, dst, n, levels, chunks, balance_slack, seed_bits, mode=EDGE_REFINE, stream=None):

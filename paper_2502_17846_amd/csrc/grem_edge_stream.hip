@@ -594,6 +594,7 @@ struct EsProfile {
     std::mutex mu;
     bool on = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> count_events;
+    int64_t edges = 0;      // edges handed to the timed launches
 } es_prof;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -693,6 +694,7 @@ int grem_edge_stream_bipartition(const int32_t* src, const int32_t* dst, int64_t
             (void)hipEventRecord(e1, stream);
             std::lock_guard<std::mutex> lock(es_prof.mu);
             es_prof.count_events.emplace_back(e0, e1);
+            es_prof.edges += hi - lo;
         }
         hipLaunchKernelGGL(k_es_score, dim3((int)blocks), dim3(kBlock), 0, stream, n, words, i == 0 ? 1 : 0,
                            mode == GREM_EDGE_FIXED ? 1 : 0, (long long)P, S, mark, hc, Lb, est, mv0, mv1, bs0, bs1);
@@ -841,7 +843,7 @@ int grem_edge_stream_profile_enable(int32_t on)
     return GREM_OK;
 }
 
-int grem_edge_stream_profile_read(double* count_ms, int64_t* launches)
+int grem_edge_stream_profile_read(double* count_ms, int64_t* launches, int64_t* edges)
 {
     std::lock_guard<std::mutex> lock(es_prof.mu);
     double total = 0.0;
@@ -856,7 +858,9 @@ int grem_edge_stream_profile_read(double* count_ms, int64_t* launches)
     }
     if (count_ms) *count_ms = total;
     if (launches) *launches = (int64_t)es_prof.count_events.size();
+    if (edges) *edges = es_prof.edges;
     es_prof.count_events.clear();
+    es_prof.edges = 0;
     return rc;
 }
 

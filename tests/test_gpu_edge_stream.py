@@ -186,3 +186,14 @@ def test_recursive_bisection_rmat():
     src, dst = es.src.numpy(), es.dst.numpy()
     bits = np.stack([(np.arange(g.n) >> l) & 1 for l in range(4)]).astype(np.int32)
     _check_rb(src, dst, g.n, 4, 25, 1.05, bits, tag="rmat-16 k=16")
+
+
+def test_recursive_bisection_chung_lu_million_nodes():
+    # 1.4M nodes, 20M edges, 16 partitions: every level spans many workgroups of every kernel; the oracle
+    # needs about a quarter of a minute
+    g = synth.chung_lu(1_387_500, 20_000_000, seed=2, device=DEV, rowptr_dtype=torch.int64, cap=20_000.0)
+    es = synth.edge_stream(g, seed=3)
+    src, dst = es.src.cpu().numpy(), es.dst.cpu().numpy()
+    bits = np.stack([(np.arange(g.n) >> l) & 1 for l in range(4)]).astype(np.int32)
+    lab = _check_rb(src, dst, g.n, 4, 50, 1.05 ** 0.25, bits, tag="chung-lu 1.4M k=16")
+    assert np.bincount(lab, minlength=16).max() <= 1.05 * g.n / 16 + 16

@@ -71,3 +71,43 @@ def test_whole_run_properties(stream):
     print(f"[result] cut fraction refined {cuts[B.EDGE_REFINE] / es.m:.4f}, fixed {cuts[B.EDGE_FIXED] / es.m:.4f}", flush=True)
     assert cuts[B.EDGE_REFINE] < cuts[B.EDGE_FIXED]
     assert cuts[B.EDGE_REFINE] < 0.5 * es.m               # better than a random bisection
+
+
+def test_recursive_bisection_full_size_properties(stream):
+    # 16 partitions of the same stream by four levels of bisection: label range, the compound capacity
+    # bound, the levels' prefix property (a shallower run equals the deeper run's leading bits), and the
+    # first level equal to the two-partition entry point followed by the placement of untouched nodes
+    es, _, _, _ = stream
+    n, levels, chunks, slack = es.n, 4, 100, 1.05 ** 0.25
+    ids = torch.arange(n, device=DEV, dtype=torch.int32)
+    bits = torch.stack([(ids >> l) & 1 for l in range(levels)]).contiguous()
+    print("[case] recursive bisection, 4 levels, full size", flush=True)
+    lab4 = B.grem_recursive_bisection(es.src, es.dst, n, levels, chunks, slack, bits.reshape(-1))
+    torch.cuda.synchronize()
+    assert int(lab4.min()) >= 0 and int(lab4.max()) < 16
+    sizes = torch.bincount(lab4, minlength=16)
+    cap = n
+    for _ in range(levels):
+        cap = B.grem_capacity(cap, 2, slack)
+    assert int(sizes.sum()) == n and int(sizes.max()) <= cap
+    print("[case] recursive bisection, 1 level, full size", flush=True)
+    lab1 = B.grem_recursive_bisection(es.src, es.dst, n, 1, chunks, slack, bits[0].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(lab1, lab4 >> 3)
+    c_size = (es.m + chunks - 1) // chunks
+    P = B.grem_capacity(n, 2, slack)
+    parts, psizes, _ = B.grem_edge_stream_bipartition(es.src, es.dst, n, c_size, P, bits[0].contiguous(),
+                                                      want_nbr_counts=False)
+    torch.cuda.synchronize()
+    touched = parts >= 0
+    assert torch.equal(lab1[touched], parts[touched])
+    # untouched nodes, ascending id: the first |S0 - S1| go to the smaller half, the rest alternate 0,1,...
+    a, b = int(psizes[0]), int(psizes[1])
+    free = torch.nonzero(~touched).flatten()
+    j = torch.arange(free.numel(), device=DEV)
+    gap = abs(a - b)
+    want = torch.where(j < gap, torch.full_like(j, 0 if a <= b else 1), (j - gap) & 1).to(torch.int32)
+    assert torch.equal(lab1[free], want)
+    cut = int(B.grem_edge_list_cut(es.src, es.dst, lab4).item())
+    print(f"[result] 16-way cut fraction by recursive bisection {cut / es.m:.4f}", flush=True)
+    assert cut < (15 / 16) * es.m
