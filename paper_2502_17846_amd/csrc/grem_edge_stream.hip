@@ -512,7 +512,7 @@ __global__ __launch_bounds__(kBlock) void k_rb_finish(int64_t nv, const u64* __r
         const long long gap = a <= b ? b - a : a - b;
         part = j < gap ? (a <= b ? 0 : 1) : (int)((j - gap) & 1);
     }
-    next_label[global_of[i]] = 2 * g + part;
+    next_label[global_of ? global_of[i] : i] = 2 * g + part;
 }
 
 // which child group an edge of group g goes to in the next level: 0 / 1, or 2 when its ends part
@@ -520,7 +520,7 @@ __device__ __forceinline__ int rb_child(int32_t a, int32_t b, int32_t g) { retur
 
 __global__ __launch_bounds__(kSelBlock) void k_rb_split_count(int64_t m, const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
                                                               const int32_t* __restrict__ next_label, int32_t g,
-                                                              uint32_t* bc0, uint32_t* bc1)
+                                                              uint8_t* __restrict__ key, uint32_t* bc0, uint32_t* bc1)
 {
     __shared__ uint32_t c0[kSelBlock / 64], c1[kSelBlock / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -531,6 +531,7 @@ __global__ __launch_bounds__(kSelBlock) void k_rb_split_count(int64_t m, const i
         const int64_t e = e0 + u;
         if (e < m) {
             const int k = rb_child(next_label[src[e]], next_label[dst[e]], g);
+            key[e] = (uint8_t)k;
             n0 += k == 0; n1 += k == 1;
         }
     }
@@ -553,9 +554,10 @@ __global__ __launch_bounds__(kBlock) void k_rb_split_scan(int64_t blocks, const 
     if (threadIdx.x == 0) { totals[0] = (long long)t0; totals[1] = (long long)t1; }
 }
 
-// stable: the edges of child 0 keep their order and land at out0 + ..., those of child 1 at out1 + ...
+// stable: the edges of child 0 (key 0, as k_rb_split_count stored it) keep their order and land from
+// at0 on, those of child 1 right after them
 __global__ __launch_bounds__(kSelBlock) void k_rb_split_scatter(int64_t m, const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
-                                                                const int32_t* __restrict__ next_label, int32_t g,
+                                                                const uint8_t* __restrict__ key,
                                                                 const uint32_t* __restrict__ bo0, const uint32_t* __restrict__ bo1,
                                                                 int32_t* out_src, int32_t* out_dst, int64_t at0,
                                                                 const long long* __restrict__ totals)
@@ -572,7 +574,7 @@ __global__ __launch_bounds__(kSelBlock) void k_rb_split_scatter(int64_t m, const
         k[u] = 2; s[u] = 0; d[u] = 0;
         if (e < m) {
             s[u] = src[e]; d[u] = dst[e];
-            k[u] = rb_child(next_label[s[u]], next_label[d[u]], g);
+            k[u] = key[e];
             n0 += k[u] == 0; n1 += k[u] == 1;
         }
     }
@@ -731,7 +733,7 @@ int grem_recursive_bisection(const int32_t* src, const int32_t* dst, int64_t m, 
     const size_t o_bsum = carve((size_t)node_blocks * 4), o_boff = carve((size_t)node_blocks * 4);
     size_t o_sel[4];
     for (int i = 0; i < 4; ++i) o_sel[i] = carve((size_t)sel_blocks * 4);
-    const size_t o_subs = carve((size_t)m * 4), o_subd = carve((size_t)m * 4);
+    const size_t o_subs = carve((size_t)m * 4), o_subd = carve((size_t)m * 4), o_key = carve((size_t)m);
     size_t o_lev[4];                                   // two generations of the grouped edge list
     for (int i = 0; i < 4; ++i) o_lev[i] = carve((size_t)m * 4);
     uint8_t* ws = nullptr;
@@ -748,6 +750,7 @@ int grem_recursive_bisection(const int32_t* src, const int32_t* dst, int64_t m, 
     uint32_t *bc0 = (uint32_t*)(ws + o_sel[0]), *bc1 = (uint32_t*)(ws + o_sel[1]);
     uint32_t *bo0 = (uint32_t*)(ws + o_sel[2]), *bo1 = (uint32_t*)(ws + o_sel[3]);
     int32_t *sub_src = (int32_t*)(ws + o_subs), *sub_dst = (int32_t*)(ws + o_subd);
+    uint8_t* key = ws + o_key;
 
     auto fill = [&](void* p, size_t bytes, u64 value) {
         const size_t count = bytes / 8;
@@ -776,21 +779,27 @@ int grem_recursive_bisection(const int32_t* src, const int32_t* dst, int64_t m, 
         for (int32_t g = 0; g < groups; ++g) {
             const int64_t e_lo = goff[g], mg = goff[g + 1] - goff[g];
             next_off[2 * g + 1] = next_off[2 * g + 2] = next_off[2 * g];
-            // the group's nodes, numbered in ascending id
-            hipLaunchKernelGGL(k_rb_flags, dim3((int)node_blocks), dim3(kBlock), 0, stream, n, label, g, 0, flag, bsum);
-            hipLaunchKernelGGL(k_rb_scan, dim3(1), dim3(kBlock), 0, stream, node_blocks, bsum, boff, totals + 2);
-            if (!read_small()) return fail(GREM_ERR_HIP);
-            const int64_t nv = host.totals[2];
-            if (nv == 0) continue;
-            hipLaunchKernelGGL(k_rb_number, dim3((int)node_blocks), dim3(kBlock), 0, stream, n, flag, boff, bits,
-                               local_id, global_of, sub_seed);
+            // the group's nodes, numbered in ascending id (the first level's only group is everyone, as is)
+            const bool whole = level == 0;
+            int64_t nv = n;
+            if (!whole) {
+                hipLaunchKernelGGL(k_rb_flags, dim3((int)node_blocks), dim3(kBlock), 0, stream, n, label, g, 0, flag, bsum);
+                hipLaunchKernelGGL(k_rb_scan, dim3(1), dim3(kBlock), 0, stream, node_blocks, bsum, boff, totals + 2);
+                if (!read_small()) return fail(GREM_ERR_HIP);
+                nv = host.totals[2];
+                if (nv == 0) continue;
+                hipLaunchKernelGGL(k_rb_number, dim3((int)node_blocks), dim3(kBlock), 0, stream, n, flag, boff, bits,
+                                   local_id, global_of, sub_seed);
+            }
             if (mg > 0) {
-                hipLaunchKernelGGL(k_rb_map, dim3(grid_for(mg, 256, 16384)), dim3(256), 0, stream, mg, cur_s + e_lo, cur_d + e_lo,
-                                   local_id, sub_src, sub_dst);
+                if (!whole)
+                    hipLaunchKernelGGL(k_rb_map, dim3(grid_for(mg, 256, 16384)), dim3(256), 0, stream, mg, cur_s + e_lo,
+                                       cur_d + e_lo, local_id, sub_src, sub_dst);
                 const int64_t c_size = (mg + chunks - 1) / chunks;
                 const int64_t P = grem_capacity(nv, 2, balance_slack);
-                const int rc = grem_edge_stream_bipartition(sub_src, sub_dst, mg, nv, c_size, P, sub_seed, mode, sub_parts,
-                                                            sub_sizes, nullptr, stream_);
+                const int rc = grem_edge_stream_bipartition(whole ? cur_s : sub_src, whole ? cur_d : sub_dst, mg, nv, c_size, P,
+                                                            whole ? bits : sub_seed, mode, sub_parts, sub_sizes, nullptr,
+                                                            stream_);
                 if (rc != GREM_OK) return fail(rc);
             } else {
                 fill(sub_parts, ((size_t)nv * 4 + 7) & ~(size_t)7, ~0ull);
@@ -801,15 +810,15 @@ int grem_recursive_bisection(const int32_t* src, const int32_t* dst, int64_t m, 
             hipLaunchKernelGGL(k_rb_flags, dim3((int)vb), dim3(kBlock), 0, stream, nv, sub_parts, 0, 1, flag, bsum);
             hipLaunchKernelGGL(k_rb_scan, dim3(1), dim3(kBlock), 0, stream, vb, bsum, boff, totals + 2);
             hipLaunchKernelGGL(k_rb_finish, dim3((int)vb), dim3(kBlock), 0, stream, nv, flag, boff, sub_parts, sub_sizes,
-                               global_of, g, next);
+                               whole ? (const int32_t*)nullptr : global_of, g, next);
             // the group's edges that stay inside a half, for the next level
             if (mg > 0 && level + 1 < levels) {
                 const int64_t sb = (mg + kSelTile - 1) / kSelTile;
                 hipLaunchKernelGGL(k_rb_split_count, dim3((int)sb), dim3(kSelBlock), 0, stream, mg, cur_s + e_lo, cur_d + e_lo,
-                                   next, g, bc0, bc1);
+                                   next, g, key, bc0, bc1);
                 hipLaunchKernelGGL(k_rb_split_scan, dim3(1), dim3(kBlock), 0, stream, sb, bc0, bc1, bo0, bo1, totals);
                 hipLaunchKernelGGL(k_rb_split_scatter, dim3((int)sb), dim3(kSelBlock), 0, stream, mg, cur_s + e_lo, cur_d + e_lo,
-                                   next, g, bo0, bo1, out_s, out_d, next_off[2 * g], totals);
+                                   key, bo0, bo1, out_s, out_d, next_off[2 * g], totals);
                 if (!read_small()) return fail(GREM_ERR_HIP);
                 next_off[2 * g + 1] = next_off[2 * g] + host.totals[0];
                 next_off[2 * g + 2] = next_off[2 * g + 1] + host.totals[1];
