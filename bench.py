@@ -40,8 +40,8 @@ PMC = {
 # The same for the edge-chunk path's dominant kernel on its 111M-node workload.
 PMC_EDGE = {
     "workload": "edges-chunglu-111M-c1pct",
-    "sources_sha256": "a0962f549d201cf419c7c0f0c5dacd3742221a484f1f980aca059ebd204f694e",
-    "fetch_kib": {"k_es_count": 1.928254e+08},
+    "sources_sha256": "e811a4681a3682e228b07df7f4bd32b29428915550adb95510264981f6292ae1",
+    "fetch_kib": {"k_es_count": 1.928282e+08},
     "write_kib": {"k_es_count": 9.980970e+07},
     "launches": {"k_es_count": 100},
 }
