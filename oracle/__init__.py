@@ -341,3 +341,22 @@ def recursive_bisection(src, dst, n, levels, chunks, balance_slack, seed_bits, m
     if return_levels:
         return label, history
     return label
+
+
+# --------------------------------------------------------------------------------------------
+# edge buckets (Sec. 3, storage layer: bucket (i, j) holds the edges from partition i to j)
+# --------------------------------------------------------------------------------------------
+
+def edge_buckets(src, dst, labels, k):
+    """(out_src, out_dst, offsets): the edges grouped by (labels[src], labels[dst]) in the order of
+    i*k + j, each bucket keeping the stream order; offsets has k*k+1 entries (int64)."""
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    dst = np.ascontiguousarray(dst, dtype=np.int32)
+    lab = np.asarray(labels).astype(np.int64)
+    if lab.size and (lab[src].min() < 0 or lab[src].max() >= k or lab[dst].min() < 0 or lab[dst].max() >= k):
+        raise OracleError(ERR_ARG)
+    key = lab[src] * k + lab[dst]
+    order = np.argsort(key, kind="stable")
+    offsets = np.zeros(k * k + 1, dtype=np.int64)
+    np.cumsum(np.bincount(key, minlength=k * k), out=offsets[1:])
+    return src[order], dst[order], offsets

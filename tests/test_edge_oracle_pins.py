@@ -311,3 +311,29 @@ def test_recursive_bisection_recovers_four_planted_blocks():
     assert oracle.edge_list_cut(es.src, es.dst, lab) < 2.0 * oracle.edge_list_cut(es.src, es.dst, g.planted)
     fixed = oracle.recursive_bisection(es.src, es.dst, g.n, 2, 10, 1.05, bits, oracle.EDGE_FIXED)
     assert oracle.edge_list_cut(es.src, es.dst, lab) < oracle.edge_list_cut(es.src, es.dst, fixed)
+
+
+# ---------------------------------------------------------------------------------------------
+# edge buckets (Sec. 3, storage layer)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("k", [1, 2, 5])
+def test_edge_buckets_against_a_bucket_by_bucket_listing(k):
+    # the definition read literally: for every pair (i, j) in order, walk the stream and keep the edges
+    # that go from partition i to partition j (catches a swapped pair, a transposed key, an unstable order)
+    rng = np.random.default_rng(k)
+    n, m = 30, 200
+    src = rng.integers(0, n, m).astype(np.int32)
+    dst = rng.integers(0, n, m).astype(np.int32)
+    lab = rng.integers(0, k, n).astype(np.int32)
+    os_, od_, off = oracle.edge_buckets(src, dst, lab, k)
+    want_s, want_d, want_off = [], [], [0]
+    for i in range(k):
+        for j in range(k):
+            for a, b in zip(src.tolist(), dst.tolist()):
+                if lab[a] == i and lab[b] == j:
+                    want_s.append(a); want_d.append(b)
+            want_off.append(len(want_s))
+    assert os_.tolist() == want_s and od_.tolist() == want_d and off.tolist() == want_off
+    with pytest.raises(oracle.OracleError):
+        oracle.edge_buckets(src, dst, np.full(n, k, np.int32), k)
