@@ -214,6 +214,20 @@ int grem_recursive_bisection(const int32_t *src, const int32_t *dst, int64_t m, 
                              int32_t levels, int64_t chunks, double balance_slack,
                              const int32_t *seed_bits, int32_t mode, int32_t *labels_out, void *stream);
 
+/* The storage layer's edge buckets (Sec. 3: bucket (i, j) holds all edges from nodes of partition i
+ * to nodes of partition j, each bucket stored sequentially): the m listed edges are written to
+ * out_src / out_dst grouped by (labels[src], labels[dst]) in the order of i*k + j; inside a bucket
+ * the edges keep their stream order (a reading: the paper fixes none; it makes the result unique).
+ * bucket_offsets: k*k+1 int64, bucket (i, j) is out[bucket_offsets[i*k+j] .. bucket_offsets[i*k+j+1]).
+ * labels: n int32, every endpoint's label must lie in [0, k).  All device pointers; out_* must not
+ * alias the inputs.  Scratch (n + 2m bytes plus at most 512 MB of tile histograms) is allocated on
+ * `stream`; two flag read-backs happen inside the call.
+ * Errors: GREM_ERR_ARG (null pointer, m < 1, m >= 2^32, n < 1, n > 2^31-1, k < 1, k > 128, an endpoint
+ * outside [0,n), an endpoint's label outside [0,k)), GREM_ERR_NOMEM, GREM_ERR_HIP. */
+int grem_edge_buckets(const int32_t *src, const int32_t *dst, int64_t m, int64_t n,
+                      const int32_t *labels, int32_t k, int32_t *out_src, int32_t *out_dst,
+                      int64_t *bucket_offsets, void *stream);
+
 /* Number of listed edges whose ends carry different labels (Sec. 1), written to the single device
  * int64 *cut_out.  parts: int32 labels covering every listed id, any values. */
 int grem_edge_list_cut(const int32_t *src, const int32_t *dst, int64_t m, const int32_t *parts,

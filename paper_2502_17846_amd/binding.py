@@ -27,7 +27,7 @@ EXPORTS = [
     "grem_set_sweep_col_bits", "grem_set_sweep_hub_degree", "grem_set_long_row_degree", "grem_profile_enable",
     "grem_profile_reset", "grem_profile_read", "grem_status_string", "grem_kernel_name",
     "grem_edge_stream_bipartition", "grem_edge_list_cut", "grem_edge_stream_profile_enable",
-    "grem_edge_stream_profile_read", "grem_recursive_bisection",
+    "grem_edge_stream_profile_read", "grem_recursive_bisection", "grem_edge_buckets",
 ]
 EDGE_REFINE, EDGE_FIXED = 0, 1
 
@@ -90,6 +90,8 @@ def load():
     lib.grem_edge_stream_bipartition.argtypes = [vp, vp, i64, i64, i64, i64, vp, i32, vp, vp, vp, vp]
     lib.grem_recursive_bisection.restype = ctypes.c_int
     lib.grem_recursive_bisection.argtypes = [vp, vp, i64, i64, i32, i64, dbl, vp, i32, vp, vp]
+    lib.grem_edge_buckets.restype = ctypes.c_int
+    lib.grem_edge_buckets.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, vp, vp]
     lib.grem_edge_list_cut.restype = ctypes.c_int
     lib.grem_edge_list_cut.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.grem_edge_stream_profile_enable.restype = ctypes.c_int
@@ -317,3 +319,17 @@ def grem_recursive_bisection(src, dst, n, levels, chunks, balance_slack, seed_bi
                                       mode, _dev(labels, torch.int32, "labels_out"), _stream(stream))
     _check(rc, "grem_recursive_bisection")
     return labels
+
+
+def grem_edge_buckets(src, dst, n, labels, k, stream=None):
+    """Returns (out_src int32[m], out_dst int32[m], bucket_offsets int64[k*k+1])."""
+    lib = load()
+    m = src.numel()
+    out_s, out_d = torch.empty_like(src), torch.empty_like(dst)
+    offsets = torch.empty(k * k + 1, dtype=torch.int64, device=src.device)
+    rc = lib.grem_edge_buckets(_dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"), m, n,
+                               _dev(labels, torch.int32, "labels"), k, _dev(out_s, torch.int32, "out_src"),
+                               _dev(out_d, torch.int32, "out_dst"), _dev(offsets, torch.int64, "bucket_offsets"),
+                               _stream(stream))
+    _check(rc, "grem_edge_buckets")
+    return out_s, out_d, offsets

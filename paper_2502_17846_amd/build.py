@@ -8,6 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "grem.hip")
 SRC_EDGE = os.path.join(HERE, "csrc", "grem_edge_stream.hip")
+SRC_BUCKETS = os.path.join(HERE, "csrc", "grem_edge_buckets.hip")
 LIB = os.path.join(HERE, "libgrem.so")
 
 FLAGS = [
@@ -20,7 +21,7 @@ FLAGS = [
 
 def build_library(verbose: bool = False, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, *extra, "-o", LIB, SRC, SRC_EDGE]
+    cmd = [hipcc, *FLAGS, *extra, "-o", LIB, SRC, SRC_EDGE, SRC_BUCKETS]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
