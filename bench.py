@@ -96,6 +96,11 @@ WORKLOADS = {
                                 chunks=100, slack=1.05 ** 0.25, direct=dict(k=16, slack=1.05, chunk=1 << 20, R=2)),
     "rb-chunglu-14M-k16": dict(kind="chung_lu", n=13_875_000, m=200_000_000, bits=64, stream=True, levels=4,
                                chunks=100, slack=1.05 ** 0.25, direct=dict(k=16, slack=1.05, chunk=1 << 17, R=2)),
+    # the storage layer's edge buckets for the 16-way partition of the row-chunk path (Sec. 3)
+    "buckets-chunglu-111M-k16": dict(kind="chung_lu", n=111_000_000, m=1_600_000_000, bits=64, stream=True, buckets=True,
+                                     direct=dict(k=16, slack=1.05, chunk=1 << 20, R=2)),
+    "buckets-chunglu-14M-k16": dict(kind="chung_lu", n=13_875_000, m=200_000_000, bits=64, stream=True, buckets=True,
+                                    direct=dict(k=16, slack=1.05, chunk=1 << 17, R=2)),
     "edges-chunglu-14M-c1pct": dict(kind="chung_lu", n=13_875_000, m=200_000_000, bits=64, stream=True,
                                     c_frac=0.01, slack=1.05),
 }
@@ -266,6 +271,53 @@ def bench_edge_stream(args, w, dev):
     print(json.dumps(out))
 
 
+def bench_buckets(args, w, dev):
+    """Edge buckets of a partitioned graph: a step is one grouping of the whole edge list."""
+    import torch
+    from paper_2502_17846_amd import binding as B
+    from paper_2502_17846_amd import synth
+    g = make_graph(w, dev)
+    es = synth.edge_stream(g, seed=1)
+    d = w["direct"]
+    n, m, k = es.n, es.m, d["k"]
+    lab = B.grem_partition(g.rowptr, g.colidx, n, k, d["slack"], d["chunk"], d["R"])
+    del g
+    torch.cuda.empty_cache()
+    torch.cuda.synchronize()
+    print(f"[bench] {es.name}: n={n} edges={m} k={k}", file=sys.stderr, flush=True)
+    res = [None]
+
+    def step():
+        res[0] = B.grem_edge_buckets(es.src, es.dst, n, lab, k)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    out_s, out_d, off = res[0]
+    sizes = (off[1:] - off[:-1]).reshape(k, k)
+    assert int(off[-1]) == m
+    # algorithmic bytes of the whole grouping: every edge read once and written once (8 + 8 bytes)
+    sec = elapsed / args.steps
+    out = {
+        "metric": "edges/sec per GREM pass", "value": m / sec, "unit": "edges/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * sec, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {es.name}; edge buckets for the {k}-way partition of the row-chunk "
+                               f"path ({d})", "n": n, "edges": m, "buckets": k * k},
+        "uncut_fraction": float(sizes.diag().sum()) / m,
+        "largest_bucket": int(sizes.max()), "smallest_bucket": int(sizes.min()),
+        "roofline": {"bound": "hbm", "achieved": 16.0 * m / sec / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": 16.0 * m / sec / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "whole call (k_eb_hist + k_eb_scatter and the scans, timed together)"},
+    }
+    print(json.dumps(out))
+
+
 def bench_recursive(args, w, dev):
     """2^levels partitions by recursive bisection: a step is the whole recursion."""
     import torch
@@ -376,6 +428,9 @@ def main():
                           "bytes_written_per_launch": nbytes, "launches": 8}))
         return
     w = WORKLOADS[args.workload]
+    if w.get("buckets"):
+        bench_buckets(args, w, dev)
+        return
     if w.get("levels"):
         bench_recursive(args, w, dev)
         return
