@@ -360,3 +360,31 @@ def edge_buckets(src, dst, labels, k):
     offsets = np.zeros(k * k + 1, dtype=np.int64)
     np.cumsum(np.bincount(key, minlength=k * k), out=offsets[1:])
     return src[order], dst[order], offsets
+
+
+# --------------------------------------------------------------------------------------------
+# expected number of edge cuts of fixed greedy decisions (Sec. 4.2, Eq. (1))
+# --------------------------------------------------------------------------------------------
+
+def expected_cut(rowptr, colidx, n, labels, x):
+    """Eq. (1) for a two-way labelling: sum over nodes i of
+    (k_i - k0_i) * (1 - q_i) + k0_i * q_i, with k_i the node's labelled neighbours, k0_i those in the
+    partition that holds more of them, and q_i = Pr(K < d_i / 2) for K ~ Hypergeometric(population k_i,
+    successes k0_i, draws d_i), d_i = floor(k_i * x + 0.5) (the paper's k*x draws, made an integer).
+    Also returns sum_i (k_i - k0_i), the value at x = 1.  Every edge is seen from both its ends."""
+    from scipy.stats import hypergeom
+    rp, ci = _csr(rowptr, colidx)
+    lab = np.asarray(labels)
+    deg_rows = np.repeat(np.arange(n), np.diff(rp))
+    nl = lab[ci]
+    c0 = np.bincount(deg_rows[nl == 0], minlength=n).astype(np.int64)
+    c1 = np.bincount(deg_rows[nl == 1], minlength=n).astype(np.int64)
+    k = c0 + c1
+    k0 = np.maximum(c0, c1)
+    d = np.floor(k.astype(np.float64) * float(x) + 0.5).astype(np.int64)
+    d = np.minimum(d, k)
+    # K < d/2  <=>  K <= ceil(d/2) - 1
+    q = hypergeom.cdf((d + 1) // 2 - 1, k, k0, d)
+    q = np.where(k > 0, q, 0.0)
+    total = np.sum((k - k0) * (1.0 - q) + k0 * q)
+    return float(total), int(np.sum(k - k0))

@@ -337,3 +337,51 @@ def test_edge_buckets_against_a_bucket_by_bucket_listing(k):
     assert os_.tolist() == want_s and od_.tolist() == want_d and off.tolist() == want_off
     with pytest.raises(oracle.OracleError):
         oracle.edge_buckets(src, dst, np.full(n, k, np.int32), k)
+
+
+# ---------------------------------------------------------------------------------------------
+# Eq. (1): expected cuts of fixed greedy decisions from a fraction x of the edges (Sec. 4.2)
+# ---------------------------------------------------------------------------------------------
+
+def test_expected_cut_against_exact_rational_enumeration():
+    # the hypergeometric tail written out with binomial coefficients in exact rationals (catches swapped
+    # distribution parameters, '<=' for '<', a wrong rounding of the draws)
+    from math import comb, floor
+    rng = np.random.default_rng(0)
+    n, m = 40, 300
+    u, v = rng.integers(0, n, m), rng.integers(0, n, m)
+    rowptr, colidx = synth.csr_from_pairs_np(u, v, n)
+    lab = rng.integers(0, 2, n).astype(np.int32)
+    for x in (0.1, 0.25, 0.5, 0.77, 1.0):
+        want = Fraction(0)
+        base = 0
+        for i in range(n):
+            nb = colidx[rowptr[i]:rowptr[i + 1]]
+            c = [int((lab[nb] == 0).sum()), int((lab[nb] == 1).sum())]
+            k, k0 = c[0] + c[1], max(c)
+            base += k - k0
+            if k == 0:
+                continue
+            d = min(k, floor(k * x + 0.5))
+            q = Fraction(0)
+            for j in range(0, d + 1):
+                if 2 * j < d and j <= k0 and d - j <= k - k0:
+                    q += Fraction(comb(k0, j) * comb(k - k0, d - j), comb(k, d))
+            want += (k - k0) * (1 - q) + k0 * q
+        got, at_one = oracle.expected_cut(rowptr, colidx, n, lab, x)
+        assert at_one == base
+        assert abs(got - float(want)) <= 1e-9 * max(1.0, float(want)), x
+    # with every edge in hand the greedy decision is the right one: the cut seen from both ends
+    got, at_one = oracle.expected_cut(rowptr, colidx, n, lab, 1.0)
+    assert abs(got - at_one) < 1e-9
+
+
+def test_expected_cut_falls_with_chunk_size_on_a_planted_bisection():
+    g = synth.planted_partition(n=3000, blocks=2, mean_degree=16.0, seed=1)
+    # from the fraction at which a typical node draws one neighbour (below it the rounded number of draws is
+    # zero for most nodes and the formula counts the empty draw as a tie, i.e. as a right decision)
+    vals = [oracle.expected_cut(g.rowptr, g.colidx, g.n, g.planted, x)[0] for x in (0.05, 0.1, 0.2, 0.4, 1.0)]
+    assert all(a >= b - 1e-9 for a, b in zip(vals, vals[1:]))
+    assert vals[0] > 1.5 * vals[-1]
+    # refinement over two chunks = Eq. (1) at 2x (Sec. 4.2): fewer expected cuts than at x
+    assert oracle.expected_cut(g.rowptr, g.colidx, g.n, g.planted, 0.2)[0] < vals[1]
