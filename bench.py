@@ -101,6 +101,9 @@ WORKLOADS = {
                                      direct=dict(k=16, slack=1.05, chunk=1 << 20, R=2)),
     "buckets-chunglu-14M-k16": dict(kind="chung_lu", n=13_875_000, m=200_000_000, bits=64, stream=True, buckets=True,
                                     direct=dict(k=16, slack=1.05, chunk=1 << 17, R=2)),
+    # Eq. (1) of Sec. 4.2 evaluated for a two-way labelling of the bench graph at x = 1 %
+    "eq1-chunglu-111M": dict(kind="chung_lu", n=111_000_000, m=1_600_000_000, bits=64, eq1=True, x=0.01),
+    "eq1-chunglu-14M": dict(kind="chung_lu", n=13_875_000, m=200_000_000, bits=64, eq1=True, x=0.01),
     "edges-chunglu-14M-c1pct": dict(kind="chung_lu", n=13_875_000, m=200_000_000, bits=64, stream=True,
                                     c_frac=0.01, slack=1.05),
 }
@@ -271,6 +274,42 @@ def bench_edge_stream(args, w, dev):
     print(json.dumps(out))
 
 
+def bench_eq1(args, w, dev):
+    """Eq. (1): a step is one evaluation of E[C](x) over the whole graph."""
+    import torch
+    from paper_2502_17846_amd import binding as B
+    g = make_graph(w, dev)
+    n, nnz, x = g.n, g.nnz, w["x"]
+    labels = (torch.arange(n, device=dev, dtype=torch.int32) & 1)     # any two-way labelling is a valid input
+    res = [None]
+
+    def step():
+        res[0] = B.grem_expected_cut(g.rowptr, g.colidx, n, labels, x)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    ec, base = res[0].cpu().numpy().tolist()
+    # algorithmic bytes: row offsets, column ids and labels once (the label look-ups would be cache traffic)
+    nbytes = (w["bits"] // 8) * (n + 1) + 4 * nnz + 4 * n
+    out = {
+        "metric": "edges/sec per GREM pass", "value": g.directed_edges / sec, "unit": "edges/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * sec, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {g.name}; Eq. (1) at x={x} for the id-parity labelling", "n": n,
+                   "csr_entries": nnz},
+        "expected_cut_fraction": ec / nnz, "cut_fraction_at_x_1": base / nnz,
+        "roofline": {"bound": "hbm", "achieved": nbytes / sec / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": nbytes / sec / 1e9 / HBM_PEAK_GBPS, "traffic": None, "kernel": "k_xc_terms"},
+    }
+    print(json.dumps(out))
+
+
 def bench_buckets(args, w, dev):
     """Edge buckets of a partitioned graph: a step is one grouping of the whole edge list."""
     import torch
@@ -428,6 +467,9 @@ def main():
                           "bytes_written_per_launch": nbytes, "launches": 8}))
         return
     w = WORKLOADS[args.workload]
+    if w.get("eq1"):
+        bench_eq1(args, w, dev)
+        return
     if w.get("buckets"):
         bench_buckets(args, w, dev)
         return

@@ -228,6 +228,20 @@ int grem_edge_buckets(const int32_t *src, const int32_t *dst, int64_t m, int64_t
                       const int32_t *labels, int32_t k, int32_t *out_src, int32_t *out_dst,
                       int64_t *bucket_offsets, void *stream);
 
+/* Eq. (1) of Sec. 4.2: the expected number of cut edges when every node is assigned greedily from a
+ * fraction x of the edges while all other nodes hold the given two-way labelling.  For node i with
+ * k_i labelled neighbours (labels 0 or 1; others are skipped), k0_i of them in the partition holding
+ * more, and d_i = min(k_i, floor(k_i*x + 0.5)) draws (the paper's k*x, made an integer):
+ *   out[0] = sum_i (k_i - k0_i)(1 - q_i) + k0_i q_i,  q_i = Pr(K < d_i/2), K ~ Hypergeometric(k_i, k0_i, d_i)
+ *   out[1] = sum_i (k_i - k0_i)                        (the value at x = 1)
+ * Every edge of a symmetric CSR is seen from both ends.  The expected cuts with refinement over two
+ * chunks are the same expression at 2x.  rowptr (rowptr_bits 32 or 64), colidx, labels (n int32), out
+ * (2 doubles): device pointers.  Floating point: the tail is summed in the log domain in double;
+ * agreement with an exact evaluation to about 1e-9 relative.  Errors: GREM_ERR_ARG (null pointer,
+ * n < 1, bad rowptr_bits, x outside (0, 1]), GREM_ERR_NOMEM, GREM_ERR_HIP. */
+int grem_expected_cut(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
+                      const int32_t *labels, double x, double *out, void *stream);
+
 /* Number of listed edges whose ends carry different labels (Sec. 1), written to the single device
  * int64 *cut_out.  parts: int32 labels covering every listed id, any values. */
 int grem_edge_list_cut(const int32_t *src, const int32_t *dst, int64_t m, const int32_t *parts,

@@ -27,7 +27,7 @@ EXPORTS = [
     "grem_set_sweep_col_bits", "grem_set_sweep_hub_degree", "grem_set_long_row_degree", "grem_profile_enable",
     "grem_profile_reset", "grem_profile_read", "grem_status_string", "grem_kernel_name",
     "grem_edge_stream_bipartition", "grem_edge_list_cut", "grem_edge_stream_profile_enable",
-    "grem_edge_stream_profile_read", "grem_recursive_bisection", "grem_edge_buckets",
+    "grem_edge_stream_profile_read", "grem_recursive_bisection", "grem_edge_buckets", "grem_expected_cut",
 ]
 EDGE_REFINE, EDGE_FIXED = 0, 1
 
@@ -92,6 +92,8 @@ def load():
     lib.grem_recursive_bisection.argtypes = [vp, vp, i64, i64, i32, i64, dbl, vp, i32, vp, vp]
     lib.grem_edge_buckets.restype = ctypes.c_int
     lib.grem_edge_buckets.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, vp, vp]
+    lib.grem_expected_cut.restype = ctypes.c_int
+    lib.grem_expected_cut.argtypes = [vp, i32, vp, i64, vp, dbl, vp, vp]
     lib.grem_edge_list_cut.restype = ctypes.c_int
     lib.grem_edge_list_cut.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.grem_edge_stream_profile_enable.restype = ctypes.c_int
@@ -333,3 +335,14 @@ def grem_edge_buckets(src, dst, n, labels, k, stream=None):
                                _stream(stream))
     _check(rc, "grem_edge_buckets")
     return out_s, out_d, offsets
+
+
+def grem_expected_cut(rowptr, colidx, n, labels, x, stream=None) -> torch.Tensor:
+    """Device float64 tensor [E[C](x), sum_i (k_i - k0_i)] of Eq. (1) for a two-way labelling."""
+    lib = load()
+    out = torch.empty(2, dtype=torch.float64, device=colidx.device)
+    rc = lib.grem_expected_cut(_dev(rowptr, rowptr.dtype, "rowptr"), _rowptr_bits(rowptr), _colidx(colidx), n,
+                               _dev(labels, torch.int32, "labels"), float(x), _dev(out, torch.float64, "out"),
+                               _stream(stream))
+    _check(rc, "grem_expected_cut")
+    return out

@@ -9,6 +9,7 @@ ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "grem.hip")
 SRC_EDGE = os.path.join(HERE, "csrc", "grem_edge_stream.hip")
 SRC_BUCKETS = os.path.join(HERE, "csrc", "grem_edge_buckets.hip")
+SRC_EXPECTED = os.path.join(HERE, "csrc", "grem_expected_cut.hip")
 LIB = os.path.join(HERE, "libgrem.so")
 
 FLAGS = [
@@ -21,7 +22,7 @@ FLAGS = [
 
 def build_library(verbose: bool = False, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, *extra, "-o", LIB, SRC, SRC_EDGE, SRC_BUCKETS]
+    cmd = [hipcc, *FLAGS, *extra, "-o", LIB, SRC, SRC_EDGE, SRC_BUCKETS, SRC_EXPECTED]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

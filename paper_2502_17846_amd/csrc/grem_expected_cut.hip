@@ -1,0 +1,118 @@
+// Expected number of edge cuts of fixed greedy decisions made from a fraction x of the edges, for gfx950
+// (Armada paper, Sec. 4.2, Eq. (1)): for a two-way labelling, node i has k_i labelled neighbours, k0_i of
+// them in the partition that holds more; with d_i = floor(k_i x + 0.5) of its edges in hand the greedy
+// decision is wrong with probability q_i = Pr(K < d_i / 2), K ~ Hypergeometric(k_i, k0_i, d_i), and
+//   E[C] = sum_i (k_i - k0_i) (1 - q_i) + k0_i q_i.
+// Refinement over two chunks is the same expression at 2x (Sec. 4.2, "The Benefit of Refinement").
+//
+// One thread per node: counts from its CSR row, then the tail of the distribution term by term in the log
+// domain (first term from lgamma, the following ones by the ratio of consecutive probabilities).  Sums
+// are reduced per workgroup and then by one workgroup in a fixed order, so the result is reproducible.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "grem.h"
+
+namespace {
+
+constexpr int kXcBlock = 256;
+
+__device__ __forceinline__ double xc_log_choose(double a, double b)
+{
+    return lgamma(a + 1.0) - lgamma(b + 1.0) - lgamma(a - b + 1.0);
+}
+
+template <typename RowT>
+__global__ __launch_bounds__(kXcBlock) void k_xc_terms(const RowT* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                                                       int64_t n, const int32_t* __restrict__ labels, double x,
+                                                       double* partial_ec, double* partial_base)
+{
+    __shared__ double s_ec[kXcBlock / 64], s_base[kXcBlock / 64];
+    const int64_t v = (int64_t)blockIdx.x * kXcBlock + threadIdx.x;
+    double ec = 0.0, base = 0.0;
+    if (v < n) {
+        long long c0 = 0, c1 = 0;
+        for (int64_t e = (int64_t)rowptr[v]; e < (int64_t)rowptr[v + 1]; ++e) {
+            const int32_t l = labels[colidx[e]];
+            c0 += l == 0; c1 += l == 1;
+        }
+        const long long k = c0 + c1, k0 = c0 > c1 ? c0 : c1, r = k - k0;
+        if (k > 0) {
+            long long d = (long long)floor((double)k * x + 0.5);
+            if (d > k) d = k;
+            if (d < 0) d = 0;
+            // q = sum of pmf(j) over the support with 2j < d
+            const long long jlo = d - r > 0 ? d - r : 0;
+            long long jhi = (d + 1) / 2 - 1;
+            if (jhi > k0) jhi = k0;
+            double q = 0.0;
+            if (jhi >= jlo) {
+                double logp = xc_log_choose((double)k0, (double)jlo) + xc_log_choose((double)r, (double)(d - jlo)) -
+                              xc_log_choose((double)k, (double)d);
+                q = exp(logp);
+                for (long long j = jlo; j < jhi; ++j) {
+                    // pmf(j+1) / pmf(j)
+                    logp += log((double)(k0 - j)) + log((double)(d - j)) - log((double)(j + 1)) - log((double)(r - d + j + 1));
+                    q += exp(logp);
+                }
+                if (q > 1.0) q = 1.0;
+            }
+            ec = (double)r * (1.0 - q) + (double)k0 * q;
+            base = (double)r;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { ec += __shfl_down(ec, o); base += __shfl_down(base, o); }
+    if ((threadIdx.x & 63) == 0) { s_ec[threadIdx.x >> 6] = ec; s_base[threadIdx.x >> 6] = base; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double a = 0.0, b = 0.0;
+        for (int q = 0; q < kXcBlock / 64; ++q) { a += s_ec[q]; b += s_base[q]; }
+        partial_ec[blockIdx.x] = a; partial_base[blockIdx.x] = b;
+    }
+}
+
+__global__ __launch_bounds__(1024) void k_xc_total(const double* __restrict__ partial_ec, const double* __restrict__ partial_base,
+                                                   int64_t blocks, double* out)
+{
+    __shared__ double s_ec[16], s_base[16];
+    double a = 0.0, b = 0.0;
+    for (int64_t i = threadIdx.x; i < blocks; i += 1024) { a += partial_ec[i]; b += partial_base[i]; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { a += __shfl_down(a, o); b += __shfl_down(b, o); }
+    if ((threadIdx.x & 63) == 0) { s_ec[threadIdx.x >> 6] = a; s_base[threadIdx.x >> 6] = b; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double x = 0.0, y = 0.0;
+        for (int q = 0; q < 16; ++q) { x += s_ec[q]; y += s_base[q]; }
+        out[0] = x; out[1] = y;
+    }
+}
+
+}  // namespace
+
+extern "C" int grem_expected_cut(const void* rowptr, int32_t rowptr_bits, const int32_t* colidx, int64_t n,
+                                 const int32_t* labels, double x, double* out, void* stream_)
+{
+    if (!rowptr || !colidx || !labels || !out || n < 1 || n > INT32_MAX || (rowptr_bits != 32 && rowptr_bits != 64) ||
+        !(x > 0.0) || !(x <= 1.0))
+        return GREM_ERR_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    const int64_t blocks = (n + kXcBlock - 1) / kXcBlock;
+    double* partial = nullptr;
+    if (hipMallocAsync((void**)&partial, (size_t)blocks * 2 * sizeof(double), stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return GREM_ERR_NOMEM;
+    }
+    if (rowptr_bits == 64)
+        hipLaunchKernelGGL(k_xc_terms<int64_t>, dim3((unsigned)blocks), dim3(kXcBlock), 0, stream, (const int64_t*)rowptr, colidx, n,
+                           labels, x, partial, partial + blocks);
+    else
+        hipLaunchKernelGGL(k_xc_terms<int32_t>, dim3((unsigned)blocks), dim3(kXcBlock), 0, stream, (const int32_t*)rowptr, colidx, n,
+                           labels, x, partial, partial + blocks);
+    hipLaunchKernelGGL(k_xc_total, dim3(1), dim3(1024), 0, stream, partial, partial + blocks, blocks, out);
+    int rc = hipGetLastError() == hipSuccess ? GREM_OK : GREM_ERR_HIP;
+    if (hipFreeAsync(partial, stream) != hipSuccess) rc = GREM_ERR_HIP;
+    return rc;
+}
