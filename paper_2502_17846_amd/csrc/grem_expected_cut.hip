@@ -5,8 +5,8 @@
 //   E[C] = sum_i (k_i - k0_i) (1 - q_i) + k0_i q_i.
 // Refinement over two chunks is the same expression at 2x (Sec. 4.2, "The Benefit of Refinement").
 //
-// One thread per node: counts from its CSR row, then the tail of the distribution term by term in the log
-// domain (first term from lgamma, the following ones by the ratio of consecutive probabilities).  Sums
+// Sixteen lanes per node count its CSR row's labels; one of them then sums the tail of the distribution
+// term by term in the log domain (first term from lgamma, the following ones by the ratio of consecutive probabilities).  Sums
 // are reduced per workgroup and then by one workgroup in a fixed order, so the result is reproducible.
 #include <hip/hip_runtime.h>
 
@@ -23,21 +23,30 @@ __device__ __forceinline__ double xc_log_choose(double a, double b)
     return lgamma(a + 1.0) - lgamma(b + 1.0) - lgamma(a - b + 1.0);
 }
 
+constexpr int kXcGroup = 16;                       // lanes that share one node's row
+constexpr int kXcRows = kXcBlock / kXcGroup;       // nodes per workgroup
+
 template <typename RowT>
 __global__ __launch_bounds__(kXcBlock) void k_xc_terms(const RowT* __restrict__ rowptr, const int32_t* __restrict__ colidx,
                                                        int64_t n, const int32_t* __restrict__ labels, double x,
                                                        double* partial_ec, double* partial_base)
 {
     __shared__ double s_ec[kXcBlock / 64], s_base[kXcBlock / 64];
-    const int64_t v = (int64_t)blockIdx.x * kXcBlock + threadIdx.x;
+    const int sub = threadIdx.x & (kXcGroup - 1);
+    const int64_t v = (int64_t)blockIdx.x * kXcRows + threadIdx.x / kXcGroup;
     double ec = 0.0, base = 0.0;
+    uint32_t c0 = 0, c1 = 0;
     if (v < n) {
-        long long c0 = 0, c1 = 0;
-        for (int64_t e = (int64_t)rowptr[v]; e < (int64_t)rowptr[v + 1]; ++e) {
+        const int64_t end = (int64_t)rowptr[v + 1];
+        for (int64_t e = (int64_t)rowptr[v] + sub; e < end; e += kXcGroup) {
             const int32_t l = labels[colidx[e]];
             c0 += l == 0; c1 += l == 1;
         }
-        const long long k = c0 + c1, k0 = c0 > c1 ? c0 : c1, r = k - k0;
+    }
+#pragma unroll
+    for (int o = kXcGroup / 2; o > 0; o >>= 1) { c0 += __shfl_xor(c0, o); c1 += __shfl_xor(c1, o); }
+    if (v < n && sub == 0) {
+        const long long k = (long long)c0 + c1, k0 = c0 > c1 ? c0 : c1, r = k - k0;
         if (k > 0) {
             long long d = (long long)floor((double)k * x + 0.5);
             if (d > k) d = k;
@@ -99,7 +108,7 @@ extern "C" int grem_expected_cut(const void* rowptr, int32_t rowptr_bits, const 
         !(x > 0.0) || !(x <= 1.0))
         return GREM_ERR_ARG;
     hipStream_t stream = (hipStream_t)stream_;
-    const int64_t blocks = (n + kXcBlock - 1) / kXcBlock;
+    const int64_t blocks = (n + kXcRows - 1) / kXcRows;
     double* partial = nullptr;
     if (hipMallocAsync((void**)&partial, (size_t)blocks * 2 * sizeof(double), stream) != hipSuccess) {
         (void)hipGetLastError();
