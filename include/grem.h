@@ -221,7 +221,7 @@ int grem_recursive_bisection(const int32_t *src, const int32_t *dst, int64_t m, 
  * bucket_offsets: k*k+1 int64, bucket (i, j) is out[bucket_offsets[i*k+j] .. bucket_offsets[i*k+j+1]).
  * labels: n int32, every endpoint's label must lie in [0, k).  All device pointers; out_* must not
  * alias the inputs.  Scratch (n + 2m bytes plus at most 512 MB of tile histograms) is allocated on
- * `stream`; two flag read-backs happen inside the call.
+ * `stream`; one flag read-back happens inside the call.
  * Errors: GREM_ERR_ARG (null pointer, m < 1, m >= 2^32, n < 1, n > 2^31-1, k < 1, k > 128, an endpoint
  * outside [0,n), an endpoint's label outside [0,k)), GREM_ERR_NOMEM, GREM_ERR_HIP. */
 int grem_edge_buckets(const int32_t *src, const int32_t *dst, int64_t m, int64_t n,
