@@ -28,11 +28,11 @@ HBM_PEAK_GBPS = 8000.0
 # at that time, and `traffic` is reported as null when the sources have changed since.
 PMC = {
     "workload": "chunglu-111M",
-    "sources_sha256": "bc02145ee7f3bf144a723d263920eb67ac4c344022e00c73d74e6f566639d6ad",
+    "sources_sha256": "924f71701811d9bbb16e675b2d82608d8605cd5075c4f20a3b0ea40be9623407",
     "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,590 KiB
     "write_factor": 1.0,        # 2 GiB written -> WRITE_SIZE 2,097,150 KiB
-    "fetch_kib": {"k_tp_score": 1.83156e+07, "k_tp_lookup": 1.3527e+07},
-    "write_kib": {"k_tp_score": 7.36998e+06, "k_tp_lookup": 4.55356e+06},
+    "fetch_kib": {"k_tp_score": 1.83367e+07, "k_tp_lookup": 1.35275e+07},
+    "write_kib": {"k_tp_score": 7.36998e+06, "k_tp_lookup": 4.55374e+06},
     "launches": {"k_tp_score": 318, "k_tp_lookup": 317},
 }
 
@@ -40,7 +40,7 @@ PMC = {
 # The same for the edge-chunk path's dominant kernel on its 111M-node workload.
 PMC_EDGE = {
     "workload": "edges-chunglu-111M-c1pct",
-    "sources_sha256": "e811a4681a3682e228b07df7f4bd32b29428915550adb95510264981f6292ae1",
+    "sources_sha256": "8f9f7152a02d469e2349e576e917df92112363e5a9879fa830a68978d43a0675",
     "fetch_kib": {"k_es_count": 1.928282e+08},
     "write_kib": {"k_es_count": 9.980970e+07},
     "launches": {"k_es_count": 100},

@@ -185,7 +185,8 @@ struct Launcher {
     hipEvent_t get_event() {
         if (!g.pool.empty()) { hipEvent_t e = g.pool.back(); g.pool.pop_back(); return e; }
         hipEvent_t e;
-        if (hipEventCreate(&e) != hipSuccess) { err = GREM_ERR_HIP; return nullptr; }
+        // timing only: no system-scope fence (and the cache write-back it implies) when the event completes
+        if (hipEventCreateWithFlags(&e, hipEventDisableSystemFence) != hipSuccess) { err = GREM_ERR_HIP; return nullptr; }
         return e;
     }
     template <typename F> void run(int cls, F &&f) {

@@ -688,7 +688,10 @@ int grem_edge_stream_bipartition(const int32_t* src, const int32_t* dst, int64_t
         }
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (profile) {
-            if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return fail(GREM_ERR_HIP);
+            // timing only: no system-scope fence when the events complete
+            if (hipEventCreateWithFlags(&e0, hipEventDisableSystemFence) != hipSuccess ||
+                hipEventCreateWithFlags(&e1, hipEventDisableSystemFence) != hipSuccess)
+                return fail(GREM_ERR_HIP);
             (void)hipEventRecord(e0, stream);
         }
         hipLaunchKernelGGL(k_es_count, dim3(egrid), dim3(kCountBlock), 0, stream, src, dst, lo, hi, Lb, mark, hc);
