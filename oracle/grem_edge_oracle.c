@@ -37,6 +37,8 @@
  * on instances where it detects no dependence inside any chunk; counts against dense incidence
  * algebra; the closed-form chunk weights of Sec. 4.1; a hand-worked example; invariants; seeded
  * planted-partition recovery and the refined-below-fixed cut ordering of Sec. 4.2.
+ * Labels on graphs outside those pins (e.g. power-law streams with many chunks) are "parity
+ * unpinned" beyond the invariants.
  */
 #include <stdint.h>
 #include <stdlib.h>
