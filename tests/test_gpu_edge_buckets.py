@@ -26,7 +26,7 @@ def _check(src, dst, n, lab, k, tag=""):
     assert np.array_equal(od_.cpu().numpy(), wd), tag
 
 
-@pytest.mark.parametrize("k", [1, 2, 3, 16, 17, 64, 128])
+@pytest.mark.parametrize("k", [1, 2, 3, 16, 17, 32, 33, 64, 128])
 def test_random_edges_all_bucket_counts(k):
     rng = np.random.default_rng(k)
     n, m = 5_000, 70_001                       # several tiles and a ragged tail
@@ -62,6 +62,17 @@ def test_partitioned_graph_buckets():
     cut = int(B.grem_edge_list_cut(_t(src), _t(dst), lab).item())
     sizes = (off[1:] - off[:-1]).reshape(16, 16)
     assert int(sizes.sum() - sizes.diag().sum()) == cut
+
+
+def test_many_buckets_long_stream_takes_larger_tiles():
+    # 16,384 buckets and 40M edges: tiles grow beyond 4,096 edges so that the tile histograms stay within their
+    # limit, every workgroup walks its tile in many steps with 64 KB of LDS cursors
+    rng = np.random.default_rng(5)
+    n, m, k = 200_000, 40_000_000, 128
+    src = rng.integers(0, n, m).astype(np.int32)
+    dst = rng.integers(0, n, m).astype(np.int32)
+    lab = rng.integers(0, k, n).astype(np.int32)
+    _check(src, dst, n, lab, k, tag="k=128 long")
 
 
 def test_errors():
