@@ -40,7 +40,7 @@ PMC = {
 # The same for the edge-chunk path's dominant kernel on its 111M-node workload.
 PMC_EDGE = {
     "workload": "edges-chunglu-111M-c1pct",
-    "sources_sha256": "8f9f7152a02d469e2349e576e917df92112363e5a9879fa830a68978d43a0675",
+    "sources_sha256": "411c69cf98832f1a1fd19065d0deb9870c6f07abbfe2ca7e1073018044bce778",
     "fetch_kib": {"k_es_count": 1.928282e+08},
     "write_kib": {"k_es_count": 9.980970e+07},
     "launches": {"k_es_count": 100},

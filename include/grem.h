@@ -207,7 +207,7 @@ int grem_edge_stream_bipartition(const int32_t *src, const int32_t *dst, int64_t
  * the group that no such edge touches are then placed one by one, ascending id, in the currently
  * smaller half (0 on a tie).  A node of group g in half b moves to group 2g + b.
  * seed_bits: levels*n int32; labels_out: n int32, each in [0, 2^levels).  Device pointers.  Scratch
- * (about 24 bytes per edge and 30 per node) is allocated on `stream`; the call reads back a few
+ * (about 25 bytes per edge and 30 per node) is allocated on `stream`; the call reads back a few
  * counters per group.  Errors as for grem_edge_stream_bipartition, plus GREM_ERR_ARG for levels
  * outside 1..20, chunks < 1, balance_slack < 1. */
 int grem_recursive_bisection(const int32_t *src, const int32_t *dst, int64_t m, int64_t n,

@@ -418,8 +418,13 @@ __global__ __launch_bounds__(256) void k_es_cut(const int32_t* __restrict__ src,
 
 // ---- recursive bisection (Sec. 4.1: more than two partitions by splitting every part in two) ------
 //
-// Per level the edges that still lie inside a group are kept grouped by group, in stream order; a
-// group's nodes are renumbered 0..nv-1 in ascending id for the two-partition run on its subgraph.
+// Per level the edges that still lie inside a group are kept grouped by group, in stream order, and
+// already written in the group's own node numbers (0..nv-1 in ascending id), so that a group's
+// segment is the input of the two-partition run as it stands.  Per level and group there is also
+// the list of its nodes' ids (and their seed bits) in that numbering.  When a group has been split,
+// every node gets its number inside its half (its rank among the nodes of the same half), the
+// halves' node lists are written, and the group's edges are rewritten in those numbers while they
+// are sorted into "both ends in half 0", "both ends in half 1" and "ends part" (dropped).
 
 constexpr int kSelBlock = 1024;     // stable selection of edges: a thread owns kSelPer consecutive edges
 constexpr int kSelPer = 4;
@@ -472,55 +477,53 @@ __device__ __forceinline__ uint32_t rb_rank(const u64* __restrict__ flag, const 
     return r + __popcll(word & ((1ull << lane) - 1ull));
 }
 
-// members of a group get their number inside the group; the group's tables are filled
-__global__ __launch_bounds__(kBlock) void k_rb_number(int64_t n, const u64* __restrict__ flag, const uint32_t* __restrict__ boff,
-                                                      const int32_t* __restrict__ seed_bits, int32_t* local_id,
-                                                      int32_t* global_of, int32_t* sub_seed)
-{
-    __shared__ uint32_t c[kWordsPerBlock];
-    bool on;
-    const uint32_t r = rb_rank(flag, boff, c, n, on);
-    const int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (on) { local_id[v] = (int32_t)r; global_of[r] = (int32_t)v; sub_seed[r] = seed_bits[v]; }
-}
-
-__global__ __launch_bounds__(256) void k_rb_map(int64_t m, const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
-                                                const int32_t* __restrict__ local_id, int32_t* sub_src, int32_t* sub_dst)
-{
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < m; e += stride) {
-        sub_src[e] = local_id[src[e]];
-        sub_dst[e] = local_id[dst[e]];
-    }
-}
-
-// A group's nodes move to group 2g + half; nodes the two-partition run left without a label (no edge
-// inside the group) are placed one by one, ascending id, in the currently smaller half (0 on a tie):
-// closed form from the run's sizes, as for the spill of the two-partition run.
-__global__ __launch_bounds__(kBlock) void k_rb_finish(int64_t nv, const u64* __restrict__ flag, const uint32_t* __restrict__ boff,
-                                                      const int32_t* __restrict__ sub_parts, const int64_t* __restrict__ sub_sizes,
-                                                      const int32_t* __restrict__ global_of, int32_t g, int32_t* next_label)
+// Nodes the two-partition run left without a label (no edge inside the group) are placed one by one,
+// ascending id, in the currently smaller half (0 on a tie): closed form from the run's sizes, as for
+// the spill of the two-partition run.  flag / boff: the unlabelled nodes and their scanned counts.
+__global__ __launch_bounds__(kBlock) void k_rb_place(int64_t nv, const u64* __restrict__ flag, const uint32_t* __restrict__ boff,
+                                                     int32_t* sub_parts, const int64_t* __restrict__ sub_sizes)
 {
     __shared__ uint32_t c[kWordsPerBlock];
     bool on;
     const long long j = rb_rank(flag, boff, c, nv, on);
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i >= nv) return;
-    int part = sub_parts[i];
-    if (on) {
-        const long long a = sub_sizes[0], b = sub_sizes[1];
-        const long long gap = a <= b ? b - a : a - b;
-        part = j < gap ? (a <= b ? 0 : 1) : (int)((j - gap) & 1);
-    }
-    next_label[global_of ? global_of[i] : i] = 2 * g + part;
+    if (i >= nv || !on) return;
+    const long long a = sub_sizes[0], b = sub_sizes[1];
+    const long long gap = a <= b ? b - a : a - b;
+    sub_parts[i] = j < gap ? (a <= b ? 0 : 1) : (int)((j - gap) & 1);
 }
 
-// which child group an edge of group g goes to in the next level: 0 / 1, or 2 when its ends part
-__device__ __forceinline__ int rb_child(int32_t a, int32_t b, int32_t g) { return a == b ? a - 2 * g : 2; }
+// flag / boff: the nodes of half 0 and their scanned counts; count0[0] = how many.  A node of half b gets
+// its number inside the half (its rank among the nodes of the same half); packed[i] = that number with
+// the half in bit 31; the halves' node lists (ids and next level's seed bits) are written, half 0 first.
+// At the last level the labels 2g + half go out instead.  gof == nullptr: node i has id i.
+__global__ __launch_bounds__(kBlock) void k_rb_children(int64_t nv, const u64* __restrict__ flag, const uint32_t* __restrict__ boff,
+                                                        const int32_t* __restrict__ sub_parts, const int32_t* __restrict__ gof,
+                                                        int32_t g, const long long* __restrict__ count0,
+                                                        const int32_t* __restrict__ next_bits, uint32_t* packed,
+                                                        int32_t* gof_next, int32_t* seed_next, int32_t* labels_out)
+{
+    __shared__ uint32_t c[kWordsPerBlock];
+    bool on;
+    const uint32_t r0 = rb_rank(flag, boff, c, nv, on);      // nodes of half 0 before this one
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= nv) return;
+    const int32_t id = gof ? gof[i] : (int32_t)i;
+    const uint32_t half = on ? 0u : 1u;
+    if (labels_out) { labels_out[id] = 2 * g + (int32_t)half; return; }
+    const uint32_t num = on ? r0 : (uint32_t)i - r0;
+    packed[i] = num | (half << 31);
+    const int64_t at = on ? (int64_t)num : count0[0] + (int64_t)num;
+    gof_next[at] = id;
+    seed_next[at] = next_bits[id];
+}
 
+// An edge of the group goes to the half both its ends are in (key 0 / 1) or is dropped (key 2); its
+// ends are rewritten in the halves' node numbers (tmp_s, tmp_d) for the scatter.
 __global__ __launch_bounds__(kSelBlock) void k_rb_split_count(int64_t m, const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
-                                                              const int32_t* __restrict__ next_label, int32_t g,
-                                                              uint8_t* __restrict__ key, uint32_t* bc0, uint32_t* bc1)
+                                                              const uint32_t* __restrict__ packed, uint8_t* __restrict__ key,
+                                                              int32_t* __restrict__ tmp_s, int32_t* __restrict__ tmp_d,
+                                                              uint32_t* bc0, uint32_t* bc1)
 {
     __shared__ uint32_t c0[kSelBlock / 64], c1[kSelBlock / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -530,8 +533,11 @@ __global__ __launch_bounds__(kSelBlock) void k_rb_split_count(int64_t m, const i
     for (int u = 0; u < kSelPer; ++u) {
         const int64_t e = e0 + u;
         if (e < m) {
-            const int k = rb_child(next_label[src[e]], next_label[dst[e]], g);
+            const uint32_t a = packed[src[e]], b = packed[dst[e]];
+            const int k = (a >> 31) == (b >> 31) ? (int)(a >> 31) : 2;
             key[e] = (uint8_t)k;
+            tmp_s[e] = (int32_t)(a & 0x7FFFFFFFu);
+            tmp_d[e] = (int32_t)(b & 0x7FFFFFFFu);
             n0 += k == 0; n1 += k == 1;
         }
     }
@@ -728,31 +734,31 @@ int grem_recursive_bisection(const int32_t* src, const int32_t* dst, int64_t m, 
     const int64_t sel_blocks = (m + kSelTile - 1) / kSelTile;
     size_t off = 0;
     auto carve = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return at; };
-    const size_t o_small = carve(256);                 // totals[2], nv, flags
-    const size_t o_label = carve((size_t)n * 4), o_next = carve((size_t)n * 4);
-    const size_t o_local = carve((size_t)n * 4), o_global = carve((size_t)n * 4), o_seed = carve((size_t)n * 4);
+    const size_t o_small = carve(256);                 // totals[3], flags
+    size_t o_gof[2], o_seed[2];                        // two generations of the groups' node lists
+    for (int i = 0; i < 2; ++i) { o_gof[i] = carve((size_t)n * 4); o_seed[i] = carve((size_t)n * 4); }
+    const size_t o_packed = carve((size_t)n * 4);
     const size_t o_parts = carve((size_t)n * 4 + 8), o_sizes = carve(16);
     const size_t o_flag = carve((size_t)((n + 63) / 64) * 8);
     const size_t o_bsum = carve((size_t)node_blocks * 4), o_boff = carve((size_t)node_blocks * 4);
     size_t o_sel[4];
     for (int i = 0; i < 4; ++i) o_sel[i] = carve((size_t)sel_blocks * 4);
-    const size_t o_subs = carve((size_t)m * 4), o_subd = carve((size_t)m * 4), o_key = carve((size_t)m);
+    const size_t o_tmps = carve((size_t)m * 4), o_tmpd = carve((size_t)m * 4), o_key = carve((size_t)m);
     size_t o_lev[4];                                   // two generations of the grouped edge list
     for (int i = 0; i < 4; ++i) o_lev[i] = carve((size_t)m * 4);
     uint8_t* ws = nullptr;
     if (hipMallocAsync((void**)&ws, off, stream) != hipSuccess) { (void)hipGetLastError(); return GREM_ERR_NOMEM; }
     auto fail = [&](int code) { (void)hipGetLastError(); (void)hipStreamSynchronize(stream); (void)hipFreeAsync(ws, stream); return code; };
-    long long* totals = (long long*)(ws + o_small);    // [0..1] split totals, [2] member / unassigned count
+    long long* totals = (long long*)(ws + o_small);    // [0..1] edges kept per half, [2] nodes in half 0
     uint32_t* flags = (uint32_t*)(ws + o_small + 64);
-    int32_t *label = (int32_t*)(ws + o_label), *next = (int32_t*)(ws + o_next);
-    int32_t *local_id = (int32_t*)(ws + o_local), *global_of = (int32_t*)(ws + o_global), *sub_seed = (int32_t*)(ws + o_seed);
+    uint32_t* packed = (uint32_t*)(ws + o_packed);
     int32_t* sub_parts = (int32_t*)(ws + o_parts);
     int64_t* sub_sizes = (int64_t*)(ws + o_sizes);
     u64* flag = (u64*)(ws + o_flag);
     uint32_t *bsum = (uint32_t*)(ws + o_bsum), *boff = (uint32_t*)(ws + o_boff);
     uint32_t *bc0 = (uint32_t*)(ws + o_sel[0]), *bc1 = (uint32_t*)(ws + o_sel[1]);
     uint32_t *bo0 = (uint32_t*)(ws + o_sel[2]), *bo1 = (uint32_t*)(ws + o_sel[3]);
-    int32_t *sub_src = (int32_t*)(ws + o_subs), *sub_dst = (int32_t*)(ws + o_subd);
+    int32_t *tmp_s = (int32_t*)(ws + o_tmps), *tmp_d = (int32_t*)(ws + o_tmpd);
     uint8_t* key = ws + o_key;
 
     auto fill = [&](void* p, size_t bytes, u64 value) {
@@ -765,73 +771,73 @@ int grem_recursive_bisection(const int32_t* src, const int32_t* dst, int64_t m, 
                hipStreamSynchronize(stream) == hipSuccess;
     };
     fill(ws + o_small, 256, 0ull);
-    fill(label, align256((size_t)n * 4), 0ull);        // every node starts in group 0
     hipLaunchKernelGGL(k_es_check, dim3(grid_for(m, 256, 8192)), dim3(256), 0, stream, src, dst, m, (uint32_t)n, flags);
     if (!read_small()) return fail(GREM_ERR_HIP);
     if (host.flags[0]) return fail(GREM_ERR_ARG);
 
-    // edges grouped by group: level 0 is the input itself, one group
+    // level 0: one group, everyone, numbered by id; its edges and seed bits are the inputs themselves
     const int32_t *cur_s = src, *cur_d = dst;
-    std::vector<int64_t> goff{0, m};
+    const int32_t *cur_gof = nullptr, *cur_seed = seed_bits;
+    std::vector<int64_t> eoff{0, m}, noff{0, n};
     for (int32_t level = 0; level < levels; ++level) {
+        const bool last = level + 1 == levels;
         int32_t* out_s = (int32_t*)(ws + o_lev[(level & 1) * 2]);
         int32_t* out_d = (int32_t*)(ws + o_lev[(level & 1) * 2 + 1]);
+        int32_t* gof_next = (int32_t*)(ws + o_gof[level & 1]);
+        int32_t* seed_next = (int32_t*)(ws + o_seed[level & 1]);
         const int32_t groups = 1 << level;
-        std::vector<int64_t> next_off((size_t)2 * groups + 1, 0);
-        const int32_t* bits = seed_bits + (size_t)level * (size_t)n;
+        std::vector<int64_t> eoff_next((size_t)2 * groups + 1, 0), noff_next((size_t)2 * groups + 1, 0);
+        const int32_t* next_bits = last ? seed_bits : seed_bits + (size_t)(level + 1) * (size_t)n;
         for (int32_t g = 0; g < groups; ++g) {
-            const int64_t e_lo = goff[g], mg = goff[g + 1] - goff[g];
-            next_off[2 * g + 1] = next_off[2 * g + 2] = next_off[2 * g];
-            // the group's nodes, numbered in ascending id (the first level's only group is everyone, as is)
-            const bool whole = level == 0;
-            int64_t nv = n;
-            if (!whole) {
-                hipLaunchKernelGGL(k_rb_flags, dim3((int)node_blocks), dim3(kBlock), 0, stream, n, label, g, 0, flag, bsum);
-                hipLaunchKernelGGL(k_rb_scan, dim3(1), dim3(kBlock), 0, stream, node_blocks, bsum, boff, totals + 2);
-                if (!read_small()) return fail(GREM_ERR_HIP);
-                nv = host.totals[2];
-                if (nv == 0) continue;
-                hipLaunchKernelGGL(k_rb_number, dim3((int)node_blocks), dim3(kBlock), 0, stream, n, flag, boff, bits,
-                                   local_id, global_of, sub_seed);
-            }
+            const int64_t e_lo = eoff[g], mg = eoff[g + 1] - eoff[g];
+            const int64_t v_lo = noff[g], nv = noff[g + 1] - noff[g];
+            eoff_next[2 * g + 1] = eoff_next[2 * g + 2] = eoff_next[2 * g];
+            noff_next[2 * g + 1] = noff_next[2 * g + 2] = noff_next[2 * g];
+            if (nv == 0) continue;
             if (mg > 0) {
-                if (!whole)
-                    hipLaunchKernelGGL(k_rb_map, dim3(grid_for(mg, 256, 16384)), dim3(256), 0, stream, mg, cur_s + e_lo,
-                                       cur_d + e_lo, local_id, sub_src, sub_dst);
                 const int64_t c_size = (mg + chunks - 1) / chunks;
                 const int64_t P = grem_capacity(nv, 2, balance_slack);
-                const int rc = grem_edge_stream_bipartition(whole ? cur_s : sub_src, whole ? cur_d : sub_dst, mg, nv, c_size, P,
-                                                            whole ? bits : sub_seed, mode, sub_parts, sub_sizes, nullptr,
-                                                            stream_);
+                const int rc = grem_edge_stream_bipartition(cur_s + e_lo, cur_d + e_lo, mg, nv, c_size, P, cur_seed + v_lo, mode,
+                                                            sub_parts, sub_sizes, nullptr, stream_);
                 if (rc != GREM_OK) return fail(rc);
             } else {
                 fill(sub_parts, ((size_t)nv * 4 + 7) & ~(size_t)7, ~0ull);
                 fill(sub_sizes, 16, 0ull);
             }
-            // unlabelled nodes are placed, everyone moves to 2g + half
             const int64_t vb = (nv + kBlock - 1) / kBlock;
+            // unlabelled nodes are placed
             hipLaunchKernelGGL(k_rb_flags, dim3((int)vb), dim3(kBlock), 0, stream, nv, sub_parts, 0, 1, flag, bsum);
             hipLaunchKernelGGL(k_rb_scan, dim3(1), dim3(kBlock), 0, stream, vb, bsum, boff, totals + 2);
-            hipLaunchKernelGGL(k_rb_finish, dim3((int)vb), dim3(kBlock), 0, stream, nv, flag, boff, sub_parts, sub_sizes,
-                               whole ? (const int32_t*)nullptr : global_of, g, next);
-            // the group's edges that stay inside a half, for the next level
-            if (mg > 0 && level + 1 < levels) {
+            hipLaunchKernelGGL(k_rb_place, dim3((int)vb), dim3(kBlock), 0, stream, nv, flag, boff, sub_parts, sub_sizes);
+            // numbers inside the halves, the halves' node lists (or, at the last level, the labels)
+            hipLaunchKernelGGL(k_rb_flags, dim3((int)vb), dim3(kBlock), 0, stream, nv, sub_parts, 0, 0, flag, bsum);
+            hipLaunchKernelGGL(k_rb_scan, dim3(1), dim3(kBlock), 0, stream, vb, bsum, boff, totals + 2);
+            hipLaunchKernelGGL(k_rb_children, dim3((int)vb), dim3(kBlock), 0, stream, nv, flag, boff, sub_parts,
+                               cur_gof ? cur_gof + v_lo : (const int32_t*)nullptr, g, totals + 2, next_bits, packed,
+                               gof_next + v_lo, seed_next + v_lo, last ? labels_out : (int32_t*)nullptr);
+            if (last) continue;
+            // the group's edges that stay inside a half, in the halves' numbers, for the next level
+            if (mg > 0) {
                 const int64_t sb = (mg + kSelTile - 1) / kSelTile;
                 hipLaunchKernelGGL(k_rb_split_count, dim3((int)sb), dim3(kSelBlock), 0, stream, mg, cur_s + e_lo, cur_d + e_lo,
-                                   next, g, key, bc0, bc1);
+                                   packed, key, tmp_s, tmp_d, bc0, bc1);
                 hipLaunchKernelGGL(k_rb_split_scan, dim3(1), dim3(kBlock), 0, stream, sb, bc0, bc1, bo0, bo1, totals);
-                hipLaunchKernelGGL(k_rb_split_scatter, dim3((int)sb), dim3(kSelBlock), 0, stream, mg, cur_s + e_lo, cur_d + e_lo,
-                                   key, bo0, bo1, out_s, out_d, next_off[2 * g], totals);
-                if (!read_small()) return fail(GREM_ERR_HIP);
-                next_off[2 * g + 1] = next_off[2 * g] + host.totals[0];
-                next_off[2 * g + 2] = next_off[2 * g + 1] + host.totals[1];
+                hipLaunchKernelGGL(k_rb_split_scatter, dim3((int)sb), dim3(kSelBlock), 0, stream, mg, tmp_s, tmp_d,
+                                   key, bo0, bo1, out_s, out_d, eoff_next[2 * g], totals);
+            } else {
+                fill(totals, 16, 0ull);
             }
+            if (!read_small()) return fail(GREM_ERR_HIP);
+            eoff_next[2 * g + 1] = eoff_next[2 * g] + host.totals[0];
+            eoff_next[2 * g + 2] = eoff_next[2 * g + 1] + host.totals[1];
+            noff_next[2 * g + 1] = noff_next[2 * g] + host.totals[2];
+            noff_next[2 * g + 2] = noff_next[2 * g] + nv;
         }
-        std::swap(label, next);
         cur_s = out_s; cur_d = out_d;
-        goff.swap(next_off);
+        cur_gof = gof_next; cur_seed = seed_next;
+        eoff.swap(eoff_next);
+        noff.swap(noff_next);
     }
-    if (hipMemcpyAsync(labels_out, label, (size_t)n * 4, hipMemcpyDeviceToDevice, stream) != hipSuccess) return fail(GREM_ERR_HIP);
     int rc = hipGetLastError() == hipSuccess ? GREM_OK : GREM_ERR_HIP;
     if (hipFreeAsync(ws, stream) != hipSuccess) rc = GREM_ERR_HIP;
     return rc;
