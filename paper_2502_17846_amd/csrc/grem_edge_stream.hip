@@ -274,12 +274,17 @@ __global__ __launch_bounds__(kBlock) void k_es_scan_movers(int64_t blocks, const
 
 // Admission: a mover whose rank among the chunk's requests for its target (ascending id) is below
 // the room the target had when the chunk started is relabelled (fix_sizes, Alg. 2, as per-workgroup
-// deltas); a rejected node without a label is recorded in ov.
+// deltas); a rejected node without a label is recorded in ov.  A wave that has movers copies the
+// 4,096 labels of its 64 words into LDS with wide loads, every lane then walks the movers of its own
+// word there, and the labels are written back if any changed (lb_bytes: the label array's allocated
+// size, a multiple of 16).
 __global__ __launch_bounds__(kBlock) void k_es_apply(int64_t words, long long P, const u64* __restrict__ S,
                                                      const u64* __restrict__ mv0, const u64* __restrict__ mv1,
                                                      const uint32_t* __restrict__ bo0, const uint32_t* __restrict__ bo1,
-                                                     uint8_t* Lb, u64* ov, uint32_t* bso, int32_t* bd0, int32_t* bd1)
+                                                     uint8_t* Lb, int64_t lb_bytes, u64* ov, uint32_t* bso, int32_t* bd0,
+                                                     int32_t* bd1)
 {
+    extern __shared__ uint4 slab4[];                  // kBlock * 64 bytes: 4 KB per wave
     __shared__ uint32_t c0[kWordsPerBlock], c1[kWordsPerBlock], co[kWordsPerBlock];
     __shared__ int32_t d0[kWordsPerBlock], d1[kWordsPerBlock];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -293,30 +298,42 @@ __global__ __launch_bounds__(kBlock) void k_es_apply(int64_t words, long long P,
     uint32_t base0 = bo0[blockIdx.x], base1 = bo1[blockIdx.x];
     for (int q = 0; q < wave; ++q) { base0 += c0[q]; base1 += c1[q]; }
     const long long room0 = P - (long long)S[0], room1 = P - (long long)S[1];
-    const u64 below = (1ull << lane) - 1ull;
     u64 outo = 0ull;
     int32_t delta0 = 0, delta1 = 0;
-    for (u64 todo = __ballot((my0 | my1) != 0ull); todo; todo &= todo - 1ull) {
-        const int i = __builtin_ctzll(todo);
-        const u64 m0 = es_bcast(my0, i), m1 = es_bcast(my1, i);
-        const long long r0 = (long long)base0 + __builtin_amdgcn_readlane(ex0, i);
-        const long long r1 = (long long)base1 + __builtin_amdgcn_readlane(ex1, i);
-        const int t = ((m0 >> lane) & 1ull) ? 0 : (((m1 >> lane) & 1ull) ? 1 : -1);
-        bool admitted = false, spilled = false;
-        uint32_t old = kNone;
-        if (t >= 0) {
-            const int64_t v = (word0 + i) * 64 + lane;
-            old = Lb[v];
-            admitted = t == 0 ? r0 + __popcll(m0 & below) < room0 : r1 + __popcll(m1 & below) < room1;
-            if (admitted) Lb[v] = (uint8_t)t;
-            else spilled = old == kNone;
+    const u64 movers = __ballot((my0 | my1) != 0ull);
+    uint4* wslab4 = slab4 + wave * (kWaveWords * 64 / 16);
+    const int64_t byte0 = word0 * 64;
+    if (movers) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = u * 64 + lane;
+            if (byte0 + (int64_t)(q + 1) * 16 <= lb_bytes) wslab4[q] = *reinterpret_cast<const uint4*>(Lb + byte0 + (int64_t)q * 16);
         }
-        const u64 a0 = __ballot(admitted && t == 0), a1 = __ballot(admitted && t == 1);
-        const u64 l0 = __ballot(admitted && old == 0u), l1 = __ballot(admitted && old == 1u);
-        const u64 o = __ballot(spilled);
-        delta0 += __popcll(a0) - __popcll(l0);
-        delta1 += __popcll(a1) - __popcll(l1);
-        if (lane == i) outo = o;
+    }
+    // a lane walks the movers of its own word, in id order; ranks continue from the words before it
+    uint8_t* mine64 = reinterpret_cast<uint8_t*>(wslab4) + lane * 64;
+    bool dirty = false;
+    long long r0 = (long long)base0 + ex0, r1 = (long long)base1 + ex1;
+    for (u64 todo = my0; todo; todo &= todo - 1ull, ++r0) {
+        const int b = __builtin_ctzll(todo);
+        const uint32_t old = mine64[b];
+        if (r0 < room0) { mine64[b] = 0; dirty = true; delta0 += 1; delta1 -= (int32_t)(old == 1u); }
+        else if (old == kNone) outo |= 1ull << b;
+    }
+    for (u64 todo = my1; todo; todo &= todo - 1ull, ++r1) {
+        const int b = __builtin_ctzll(todo);
+        const uint32_t old = mine64[b];
+        if (r1 < room1) { mine64[b] = 1; dirty = true; delta1 += 1; delta0 -= (int32_t)(old == 0u); }
+        else if (old == kNone) outo |= 1ull << b;
+    }
+    delta0 = (int32_t)es_wave_sum((uint32_t)delta0);
+    delta1 = (int32_t)es_wave_sum((uint32_t)delta1);
+    if (__ballot(dirty)) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = u * 64 + lane;
+            if (byte0 + (int64_t)(q + 1) * 16 <= lb_bytes) *reinterpret_cast<uint4*>(Lb + byte0 + (int64_t)q * 16) = wslab4[q];
+        }
     }
     if (mine) ov[word0 + lane] = outo;
     const uint32_t so = es_wave_sum(__popcll(outo));
@@ -678,6 +695,8 @@ int grem_edge_stream_bipartition(const int32_t* src, const int32_t* dst, int64_t
         return fail(GREM_ERR_HIP);
     if (host.flags[0]) return fail(GREM_ERR_ARG);
 
+    if (hipFuncSetAttribute((const void*)k_es_apply, hipFuncAttributeMaxDynamicSharedMemorySize, kBlock * 64) != hipSuccess)
+        return fail(GREM_ERR_HIP);
     const int64_t nchunks = (m + c_size - 1) / c_size;
     bool profile;
     { std::lock_guard<std::mutex> lock(es_prof.mu); profile = es_prof.on; }
@@ -711,8 +730,8 @@ int grem_edge_stream_bipartition(const int32_t* src, const int32_t* dst, int64_t
                            mode == GREM_EDGE_FIXED ? 1 : 0, (long long)P, S, mark, hc, Lb, est, mv0, mv1, bs0, bs1);
         if (i == 0) continue;
         hipLaunchKernelGGL(k_es_scan_movers, dim3(1), dim3(kBlock), 0, stream, blocks, bs0, bs1, bo0, bo1);
-        hipLaunchKernelGGL(k_es_apply, dim3((int)blocks), dim3(kBlock), 0, stream, words, (long long)P, S, mv0, mv1,
-                           bo0, bo1, Lb, ov, bso, bd0, bd1);
+        hipLaunchKernelGGL(k_es_apply, dim3((int)blocks), dim3(kBlock), (size_t)kBlock * 64, stream, words, (long long)P, S, mv0,
+                           mv1, bo0, bo1, Lb, (int64_t)align256((size_t)n), ov, bso, bd0, bd1);
         hipLaunchKernelGGL(k_es_scan_spill, dim3(1), dim3(kBlock), 0, stream, blocks, bso, boo, bd0, bd1, S, Sp);
         hipLaunchKernelGGL(k_es_spill, dim3((int)blocks), dim3(kBlock), 0, stream, words, ov, boo, Sp, Lb);
     }
