@@ -197,3 +197,16 @@ def test_recursive_bisection_chung_lu_million_nodes():
     bits = np.stack([(np.arange(g.n) >> l) & 1 for l in range(4)]).astype(np.int32)
     lab = _check_rb(src, dst, g.n, 4, 50, 1.05 ** 0.25, bits, tag="chung-lu 1.4M k=16")
     assert np.bincount(lab, minlength=16).max() <= 1.05 * g.n / 16 + 16
+
+
+def test_degenerate_streams():
+    # one node with a loop; a stream of identical edges; only loops; more chunks than distinct nodes
+    _check(np.array([0], np.int32), np.array([0], np.int32), 1, 1, 1, np.array([1], np.int32), tag="single loop")
+    _check(np.full(500, 3, np.int32), np.full(500, 68, np.int32), 70, 7, 35, (np.arange(70) % 2).astype(np.int32),
+           tag="identical edges")
+    ids = (np.arange(300) % 65).astype(np.int32)
+    _check(ids, ids, 65, 10, 33, (np.arange(65) % 2).astype(np.int32), tag="only loops")
+    _check(ids, ids[::-1].copy(), 65, 1, 33, (np.arange(65) % 2).astype(np.int32), mode=B.EDGE_FIXED, tag="one edge per chunk, fixed")
+    lab = _check_rb(ids, ids[::-1].copy(), 65, 3, 2, 1.5, np.stack([(np.arange(65) >> l) & 1 for l in range(3)]).astype(np.int32),
+                    tag="tiny recursion")
+    assert lab.max() < 8
