@@ -276,6 +276,7 @@ def bench_edge_stream(args, w, dev):
 
 def bench_eq1(args, w, dev):
     """Eq. (1): a step is one evaluation of E[C](x) over the whole graph."""
+    import numpy as np
     import torch
     from paper_2502_17846_amd import binding as B
     g = make_graph(w, dev)
@@ -307,6 +308,19 @@ def bench_eq1(args, w, dev):
         "roofline": {"bound": "hbm", "achieved": nbytes / sec / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": nbytes / sec / 1e9 / HBM_PEAK_GBPS, "traffic": None, "kernel": "k_xc_terms"},
     }
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = min(n, 2_000_000)
+        rp = g.rowptr[:rows + 1].cpu().numpy()
+        end = int(rp[-1])
+        rp_full = np.concatenate([rp, np.full(n - rows, end, dtype=rp.dtype)])
+        ci = g.colidx[:end].cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.expected_cut(rp_full, ci, n, labels.cpu().numpy(), x)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": end * (g.directed_edges / nnz) / dt, "unit": "edges/s", "cores": 1,
+                               "kind": "oracle", "sample": f"the first {rows} rows ({end} CSR entries) of the same graph, "
+                                                           f"labels of all {n} nodes, {dt:.1f} s"}
     print(json.dumps(out))
 
 
@@ -354,6 +368,15 @@ def bench_buckets(args, w, dev):
                      "frac": 16.0 * m / sec / 1e9 / HBM_PEAK_GBPS, "traffic": None,
                      "kernel": "whole call (k_eb_hist + k_eb_scatter and the scans, timed together)"},
     }
+    if not args.no_cpu_baseline:
+        import oracle
+        take = min(m, 30_000_000)
+        hs, hd, hl = es.src[:take].cpu().numpy(), es.dst[:take].cpu().numpy(), lab.cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.edge_buckets(hs, hd, hl, k)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": take / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the first {take} edges of the same stream with the same labels, {dt:.1f} s"}
     print(json.dumps(out))
 
 
@@ -423,6 +446,23 @@ def bench_recursive(args, w, dev):
                         "max_partition_size": int(torch.bincount(dlab, minlength=k).max())},
         "roofline": roofline,
     }
+    if not args.no_cpu_baseline:
+        import oracle
+        c_size = (m + chunks - 1) // chunks
+        take = min(chunks, 12)
+        ms_ = min(m, take * c_size)
+        st = oracle.EdgeStepper(es.src[:ms_].cpu().numpy(), es.dst[:ms_].cpu().numpy(), n, c_size,
+                                B.grem_capacity(n, 2, w["slack"]), seed_bits[0].cpu().numpy())
+        done, t0 = 0, time.perf_counter()
+        while done < take and st.step():
+            done += 1
+            if time.perf_counter() - t0 > 15.0:
+                break
+        dt = time.perf_counter() - t0
+        st.close()
+        out["cpu_baseline"] = {"value": min(ms_, done * c_size) / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first level only: first {done} of {chunks} chunks ({min(ms_, done * c_size)} edges) of "
+                                         f"the same stream, {dt:.1f} s (the recursion's oracle runs the same stepper per group)"}
     print(json.dumps(out))
 
 
