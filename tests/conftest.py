@@ -10,5 +10,3 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    config.addinivalue_line("markers", "full: full-size workload, minutes of CPU oracle time; "
-                                       "enabled with GREM_FULL=1")

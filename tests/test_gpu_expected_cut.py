@@ -34,6 +34,57 @@ def test_expected_cut_equals_the_oracle(x):
             assert abs(got - want) <= RTOL * max(1.0, want), (x, got, want)
 
 
+def _hub_graph(hub_degree, n, extra_edges, seed):
+    """One row of `hub_degree` entries (vertex 0 joined to 1..hub_degree) plus random edges among the other
+    vertices; symmetric, loop-free, deduplicated CSR."""
+    rng = np.random.default_rng(seed)
+    a = rng.integers(1, n, extra_edges)
+    b = rng.integers(1, n, extra_edges)
+    keep = a != b
+    src = np.concatenate([np.zeros(hub_degree, np.int64), np.arange(1, hub_degree + 1), a[keep], b[keep]])
+    dst = np.concatenate([np.arange(1, hub_degree + 1), np.zeros(hub_degree, np.int64), b[keep], a[keep]])
+    key = np.unique(src * n + dst)
+    src, dst = key // n, key % n
+    rowptr = np.zeros(n + 1, np.int64)
+    np.add.at(rowptr, src + 1, 1)
+    return np.cumsum(rowptr), dst.astype(np.int32)
+
+
+def _hub_case(x, extra_edges):
+    """A row of 60,000 entries whose 59,000 labelled neighbours are split so unevenly that the mean of the
+    majority count in x * 59,000 draws lies about one standard deviation above half the draws: the hub's
+    probability of a wrong decision is then neither 0 nor 1 at any x, and its tail has up to x/2 * 59,000 terms."""
+    n, hub, k = 80_000, 60_000, 59_000
+    rowptr, colidx = _hub_graph(hub, n, extra_edges, seed=21)
+    assert rowptr[1] - rowptr[0] == hub
+    delta = int(np.sqrt(k * (1.0 - x) / x)) & ~1           # majority minus minority
+    labels = np.random.default_rng(22).integers(0, 2, n).astype(np.int32)
+    labels[1:hub + 1] = -1
+    labels[1:1 + (k + delta) // 2] = 0
+    labels[1 + (k + delta) // 2:1 + k] = 1
+    if extra_edges == 0:
+        labels[0] = -1            # a pure star with an unlabelled centre: the hub's term is the whole sum
+    return n, rowptr, colidx, labels, delta
+
+
+@pytest.mark.parametrize("x", [0.003, 0.05, 0.5, 0.97])
+def test_a_row_of_60000_entries(x):
+    for extra in (0, 150_000):
+        n, rowptr, colidx, labels, delta = _hub_case(x, extra)
+        want, want_base = oracle.expected_cut(rowptr, colidx, n, labels, x)
+        if extra == 0:
+            # E[C] = minority + delta * q for the one row that counts
+            q = (want - want_base) / delta
+            print(f"[case] star, x={x}: delta={delta} q={q:.4f}", flush=True)
+            assert want_base == (59_000 - delta) // 2 and 0.03 < q < 0.97
+        for rdt in (torch.int64, torch.int32):
+            out = B.grem_expected_cut(_t(rowptr, rdt), _t(colidx), n, _t(labels), x)
+            torch.cuda.synchronize()
+            got, base = out.cpu().numpy().tolist()
+            assert base == want_base
+            assert abs(got - want) <= RTOL * max(1.0, want), (x, extra, got, want)
+
+
 def test_ablation_shape_on_a_planted_bisection():
     g = synth.planted_partition(n=20_000, blocks=2, mean_degree=12.0, seed=7)
     es = synth.edge_stream(g, seed=8)

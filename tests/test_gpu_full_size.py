@@ -1,14 +1,14 @@
 """Full-size checks of the bench workload (111M vertices, 3.19e9 CSR entries, k=16, chunk 2^20) in the
-launch configuration bench.py times.  The oracle cannot replay the whole run in test time (minutes per
-pass), so:
+launch configuration bench.py times:
   * with refine_passes = 0 the labels of the first chunks are final after pass 0 and depend only on those
-    chunks' rows: they are compared, element by element, with the oracle stepped over the same prefix;
+    chunks' rows: they are compared, element by element, with the oracle stepped over the same prefix
+    (unseeded and seeded);
   * the whole 3-pass run is checked through properties that hold at any size (label range, sizes equal
     the label counts and respect the capacity, two runs give the same bytes) and the two independent
-    score paths (plain LDS and column-sliced) must agree bit for bit.
-Set GREM_FULL=1 to also replay the complete run on the oracle (several minutes of CPU time)."""
-import os
-
+    score paths (plain LDS and two-phase) must agree bit for bit;
+  * the complete 3-pass run (pass 0 and two refinement passes, 318 chunk steps) is replayed on the oracle
+    (two to three minutes of single-thread CPU time) and labels, sizes and estimates are compared element
+    by element with the library's."""
 import numpy as np
 import pytest
 import torch
@@ -125,8 +125,6 @@ def test_three_pass_run_properties_and_path_agreement(graph):
     assert outs[0][1] / g.nnz < 15 / 16
 
 
-@pytest.mark.full
-@pytest.mark.skipif(os.environ.get("GREM_FULL") != "1", reason="minutes of single-thread oracle time; set GREM_FULL=1")
 def test_whole_run_equals_the_oracle(graph):
     g = graph
     rp, ci = g.rowptr.cpu().numpy(), g.colidx.cpu().numpy()
@@ -137,8 +135,18 @@ def test_whole_run_equals_the_oracle(graph):
         steps += 1
         if steps % 20 == 0:
             print(f"[oracle] {steps} chunk steps", flush=True)
-    olab = st.labels()
+    assert steps == 3 * ((g.n + CHUNK - 1) // CHUNK)
+    olab, osizes, oest = st.labels(), st.sizes(), st.estimates()
     st.close()
+    del rp, ci
+    # the call bench.py times (labels only: the last pass does not store the estimates) ...
     lab = B.grem_partition(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 2)
     torch.cuda.synchronize()
     assert np.array_equal(lab.cpu().numpy(), olab)
+    del lab
+    # ... and the same run returning all of Alg. 1's state
+    lab, sizes, est = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 2)
+    torch.cuda.synchronize()
+    assert np.array_equal(lab.cpu().numpy(), olab)
+    assert sizes.cpu().numpy().tolist() == osizes.tolist()
+    assert np.array_equal(est.cpu().numpy().view(np.uint32), oest)

@@ -2,6 +2,9 @@
 111M nodes, 1.6e9 undirected edges in random order, chunks of 1 % of the edges, two partitions):
   * the run over the first three chunks alone equals the oracle's element by element (parts, sizes,
     estimates as raw doubles);
+  * a longer prefix whose first chunk is seeded entirely with partition 0, so that partition 0 reaches its
+    capacity inside the prefix (requests rejected by rank, new nodes placed in the other partition, and
+    later chunks deciding against a full partition), equals the oracle's in the same way;
   * the whole run is checked through properties that hold at any size, is repeatable bit for bit,
     and refined decisions cut fewer edges than fixed greedy ones (Sec. 4.2, Fig. 7)."""
 import numpy as np
@@ -41,6 +44,43 @@ def test_first_chunks_equal_the_oracle(stream):
     assert sizes.cpu().numpy().tolist() == osizes.tolist()
     assert np.array_equal(est.cpu().numpy().view(np.uint64), oest.view(np.uint64))
     assert int((oparts >= 0).sum()) > 30_000_000          # the prefix does reach a large part of the graph
+
+
+def test_prefix_that_fills_a_partition_equals_the_oracle(stream):
+    es, _, c_size, P = stream
+    seed0 = np.zeros(es.n, dtype=np.int32)        # every first-chunk node starts in partition 0
+    # partition 0 then grows fastest and runs out of room after about ten chunks.  The oracle is stepped until
+    # two chunks after the first one in which requests were turned down (a node's request differs from the
+    # partition it ends the chunk in: refused by rank, and placed in the other partition if it was new).
+    limit = 20
+    m = limit * c_size
+    src_h, dst_h = es.src[:m].cpu().numpy(), es.dst[:m].cpu().numpy()
+    st = oracle.EdgeStepper(src_h, dst_h, es.n, c_size, P, seed0)
+    chunks, first_refusal, refused = 0, None, 0
+    while chunks < limit and (first_refusal is None or chunks < first_refusal + 3):
+        assert st.step()
+        chunks += 1
+        nodes, _, prop = st.last_chunk()
+        if chunks > 1:
+            after = st.parts()[nodes]
+            turned_down = int(((prop >= 0) & (prop != after)).sum())
+            print(f"[oracle] chunk {chunks}: {nodes.size} nodes, {turned_down} requests turned down, sizes "
+                  f"{st.sizes().tolist()}", flush=True)
+            if turned_down and first_refusal is None:
+                first_refusal = chunks
+            refused += turned_down
+    assert first_refusal is not None, f"no request was turned down within {limit} chunks"
+    oparts, osizes, oest = st.parts(), st.sizes(), st.nbr_counts()
+    st.close()
+    m = chunks * c_size
+    print(f"[case] edge stream prefix parity with a full partition: {chunks} chunks of {c_size} edges, "
+          f"{refused} requests turned down", flush=True)
+    src, dst = es.src[:m].contiguous(), es.dst[:m].contiguous()
+    parts, sizes, est = B.grem_edge_stream_bipartition(src, dst, es.n, c_size, P, torch.as_tensor(seed0).to(DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(parts.cpu().numpy(), oparts)
+    assert sizes.cpu().numpy().tolist() == osizes.tolist()
+    assert np.array_equal(est.cpu().numpy().view(np.uint64), oest.view(np.uint64))
 
 
 def test_whole_run_properties(stream):

@@ -1,7 +1,9 @@
 """Full-size checks of the R-MAT scale 27 workload (134M vertices, 8.4e9 CSR entries, int64 rowptr,
 k=32, slack 1.03, chunk 2^22, 1 refinement pass): the largest graph of the set, more than 2^32 entries.
-  * refine_passes = 0: labels and estimates of the first chunk are final after pass 0 and depend only on
-    that chunk's rows; they are compared element by element with the oracle stepped over the same prefix;
+  * refine_passes = 0: labels and estimates of the first chunks are final after pass 0 and depend only on
+    those chunks' rows; they are compared element by element with the oracle stepped over the same prefix,
+    which is long enough that its last chunk's entries lie beyond offset 2^32 of colidx, holds rows of
+    16,384 entries and more, and (from the second chunk on) counts labelled neighbours;
   * the 2-pass run is checked through properties that hold at any size, and two routes must agree bit
     for bit: LDS histograms with long rows split off, and histograms in E's rows with nothing split off."""
 import numpy as np
@@ -28,21 +30,32 @@ def graph():
     B.grem_set_long_row_degree(0)
 
 
-def test_first_chunk_of_pass0_equals_the_oracle(graph):
+def test_first_chunks_of_pass0_equal_the_oracle(graph):
     g = graph
     assert g.nnz > 2**32
-    rows = CHUNK
+    # the shortest prefix of whole chunks whose last chunk starts beyond entry 2^32
+    nchunks = (g.n + CHUNK - 1) // CHUNK
+    starts = g.rowptr[torch.arange(nchunks, device=DEV) * CHUNK]
+    chunks = int((starts <= 2**32).sum().item()) + 1
+    assert 2 <= chunks <= nchunks and int(starts[chunks - 1].item()) > 2**32
+    rows = chunks * CHUNK
     end = int(g.rowptr[rows].item())
     deg = g.rowptr[1:rows + 1] - g.rowptr[:rows]
-    print(f"[case] rmat-27 prefix parity, 1 chunk, {end} entries, rows of >= 16384 entries in it: "
+    print(f"[case] rmat-27 prefix parity, {chunks} chunks, {end} entries, rows of >= 16384 entries in it: "
           f"{int((deg >= 16384).sum())}", flush=True)
+    assert int((deg >= 16384).sum()) > 0
+    del deg
     rp = g.rowptr.cpu().numpy().copy()
     rp[rows:] = end
     ci = g.colidx[:end].cpu().numpy()
     st = oracle.Stepper(rp, ci, g.n, K, SLACK, CHUNK, 0)
-    st.step()
+    for c in range(chunks):
+        st.step()
+        print(f"[oracle] chunk {c + 1} of {chunks}", flush=True)
     olab, oest = st.labels()[:rows].copy(), st.estimates()[:rows].copy()
     st.close()
+    del rp, ci
+    assert oest[CHUNK:].any() and oest[(chunks - 1) * CHUNK:].any()     # labelled neighbours were counted
     lab, sizes, est = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 0)
     torch.cuda.synchronize()
     assert np.array_equal(lab[:rows].cpu().numpy(), olab)
