@@ -54,6 +54,7 @@ extern "C" {
 #define GREM_ERR_RANGE (-4)  /* max_degree * 2^refine_passes >= 2^32 (E would overflow), or a tile
                                 of rows holds 2^32 or more entries */
 #define GREM_ERR_SEED (-5)   /* a seed label outside {-1} u [0,k), or a seeded partition above P */
+#define GREM_ERR_LIMIT (-6)  /* the input is larger than a fixed-size buffer of the entry point allows */
 
 #define GREM_MAX_K 4096
 
@@ -241,6 +242,24 @@ int grem_edge_buckets(const int32_t *src, const int32_t *dst, int64_t m, int64_t
  * n < 1, bad rowptr_bits, x outside (0, 1]), GREM_ERR_NOMEM, GREM_ERR_HIP. */
 int grem_expected_cut(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
                       const int32_t *labels, double x, double *out, void *stream);
+
+/* grem_expected_cut for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * result, bit for bit, as grem_expected_cut, but the per-workgroup partial sums go to a fixed 4 MiB
+ * buffer that is part of the library's device image (one copy per GPU, held until the process
+ * ends) instead of a stream-ordered allocation; the call allocates and frees nothing.
+ *   - n may be at most grem_expected_cut_noalloc_max_n() (4,194,304 rows: one workgroup per 16
+ *     rows, two doubles per workgroup); a larger n returns GREM_ERR_LIMIT and launches nothing.
+ *   - The device that owns the arrays and `stream` must be the current device.  The first call on
+ *     a device looks up that device's copy of the buffer (hipGetSymbolAddress; no allocation, but
+ *     make that first call outside graph capture).
+ *   - All calls on one GPU share the buffer: calls that overlap in time on one GPU (different
+ *     streams, different threads) race and must be serialised by the caller.  Nothing in the
+ *     buffer has to survive or be cleared between calls: every slot a call reads it has written.
+ * Errors: GREM_ERR_ARG as for grem_expected_cut, GREM_ERR_LIMIT, GREM_ERR_HIP. */
+int grem_expected_cut_noalloc(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
+                              const int32_t *labels, double x, double *out, void *stream);
+int64_t grem_expected_cut_noalloc_max_n(void);
 
 /* Number of listed edges whose ends carry different labels (Sec. 1), written to the single device
  * int64 *cut_out.  parts: int32 labels covering every listed id, any values. */

@@ -14,7 +14,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgrem.so")
 
-OK, ERR_ARG, ERR_NOMEM, ERR_HIP, ERR_RANGE, ERR_SEED = 0, -1, -2, -3, -4, -5
+OK, ERR_ARG, ERR_NOMEM, ERR_HIP, ERR_RANGE, ERR_SEED, ERR_LIMIT = 0, -1, -2, -3, -4, -5, -6
 HIST_AUTO, HIST_LDS, HIST_GLOBAL, HIST_SWEEP = 0, 1, 2, 3
 MAX_K = 4096
 KERNEL_CLASSES = 11
@@ -28,6 +28,7 @@ EXPORTS = [
     "grem_profile_reset", "grem_profile_read", "grem_status_string", "grem_kernel_name",
     "grem_edge_stream_bipartition", "grem_edge_list_cut", "grem_edge_stream_profile_enable",
     "grem_edge_stream_profile_read", "grem_recursive_bisection", "grem_edge_buckets", "grem_expected_cut",
+    "grem_expected_cut_noalloc", "grem_expected_cut_noalloc_max_n",
 ]
 EDGE_REFINE, EDGE_FIXED = 0, 1
 
@@ -94,6 +95,10 @@ def load():
     lib.grem_edge_buckets.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, vp, vp]
     lib.grem_expected_cut.restype = ctypes.c_int
     lib.grem_expected_cut.argtypes = [vp, i32, vp, i64, vp, dbl, vp, vp]
+    lib.grem_expected_cut_noalloc.restype = ctypes.c_int
+    lib.grem_expected_cut_noalloc.argtypes = [vp, i32, vp, i64, vp, dbl, vp, vp]
+    lib.grem_expected_cut_noalloc_max_n.restype = i64
+    lib.grem_expected_cut_noalloc_max_n.argtypes = []
     lib.grem_edge_list_cut.restype = ctypes.c_int
     lib.grem_edge_list_cut.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.grem_edge_stream_profile_enable.restype = ctypes.c_int
@@ -346,3 +351,16 @@ def grem_expected_cut(rowptr, colidx, n, labels, x, stream=None) -> torch.Tensor
                                _stream(stream))
     _check(rc, "grem_expected_cut")
     return out
+
+
+def grem_expected_cut_noalloc(rowptr, colidx, n, labels, x, out, stream=None) -> torch.Tensor:
+    """grem_expected_cut through the entry point that allocates nothing; `out`: the caller's float64[2]."""
+    rc = load().grem_expected_cut_noalloc(_dev(rowptr, rowptr.dtype, "rowptr"), _rowptr_bits(rowptr), _colidx(colidx),
+                                          n, _dev(labels, torch.int32, "labels"), float(x),
+                                          _dev(out, torch.float64, "out"), _stream(stream))
+    _check(rc, "grem_expected_cut_noalloc")
+    return out
+
+
+def grem_expected_cut_noalloc_max_n() -> int:
+    return int(load().grem_expected_cut_noalloc_max_n())

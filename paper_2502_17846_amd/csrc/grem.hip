@@ -876,6 +876,7 @@ const char *grem_status_string(int code) {
         case GREM_ERR_HIP: return "HIP runtime error";
         case GREM_ERR_RANGE: return "max degree * 2^refine_passes does not fit the estimates";
         case GREM_ERR_SEED: return "invalid seed labels";
+        case GREM_ERR_LIMIT: return "input larger than the entry point's fixed-size buffer allows";
         default: return "unknown status";
     }
 }

@@ -11,8 +11,15 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <mutex>
 
 #include "grem.h"
+
+// Per-workgroup partial sums of the entry point that allocates nothing (grem_expected_cut_noalloc).
+// One copy per GPU, held until the process ends; host code reaches it only through the address
+// hipGetSymbolAddress returns for the current device, never through this name.
+constexpr int64_t kXcStaticBlocks = 262144;        // 4 MiB: two doubles per workgroup
+static __device__ __align__(256) double scratch[2 * kXcStaticBlocks];
 
 namespace {
 
@@ -99,7 +106,54 @@ __global__ __launch_bounds__(1024) void k_xc_total(const double* __restrict__ pa
     }
 }
 
+template <typename RowT>
+void xc_launch(const void* rowptr, const int32_t* colidx, int64_t n, const int32_t* labels, double x, double* partial,
+               int64_t blocks, double* out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_xc_terms<RowT>, dim3((unsigned)blocks), dim3(kXcBlock), 0, stream, (const RowT*)rowptr, colidx, n,
+                       labels, x, partial, partial + blocks);
+    hipLaunchKernelGGL(k_xc_total, dim3(1), dim3(1024), 0, stream, partial, partial + blocks, blocks, out);
+}
+
+constexpr int kXcMaxDevices = 64;
+std::mutex xc_mu;
+double* xc_scratch_ptr[kXcMaxDevices] = {};        // device address of `scratch`, per GPU
+
 }  // namespace
+
+extern "C" int64_t grem_expected_cut_noalloc_max_n(void) { return kXcStaticBlocks * kXcRows; }
+
+extern "C" int grem_expected_cut_noalloc(const void* rowptr, int32_t rowptr_bits, const int32_t* colidx, int64_t n,
+                                         const int32_t* labels, double x, double* out, void* stream_)
+{
+    if (!rowptr || !colidx || !labels || !out || n < 1 || (rowptr_bits != 32 && rowptr_bits != 64) || !(x > 0.0) ||
+        !(x <= 1.0))
+        return GREM_ERR_ARG;
+    if (n > kXcStaticBlocks * kXcRows) return GREM_ERR_LIMIT;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return GREM_ERR_HIP;
+    if (dev < 0 || dev >= kXcMaxDevices) return GREM_ERR_LIMIT;
+    double* partial = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(xc_mu);
+        if (!xc_scratch_ptr[dev]) {          // first call on this GPU: look its copy of the array up
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+                (void)hipGetLastError();
+                return GREM_ERR_HIP;
+            }
+            xc_scratch_ptr[dev] = (double*)p;
+        }
+        partial = xc_scratch_ptr[dev];
+    }
+    // every workgroup writes its own two slots and the reduction reads exactly those: nothing has to
+    // start at zero, whatever an earlier call left behind
+    hipStream_t stream = (hipStream_t)stream_;
+    const int64_t blocks = (n + kXcRows - 1) / kXcRows;
+    if (rowptr_bits == 64) xc_launch<int64_t>(rowptr, colidx, n, labels, x, partial, blocks, out, stream);
+    else xc_launch<int32_t>(rowptr, colidx, n, labels, x, partial, blocks, out, stream);
+    return hipGetLastError() == hipSuccess ? GREM_OK : GREM_ERR_HIP;
+}
 
 extern "C" int grem_expected_cut(const void* rowptr, int32_t rowptr_bits, const int32_t* colidx, int64_t n,
                                  const int32_t* labels, double x, double* out, void* stream_)
@@ -114,13 +168,8 @@ extern "C" int grem_expected_cut(const void* rowptr, int32_t rowptr_bits, const 
         (void)hipGetLastError();
         return GREM_ERR_NOMEM;
     }
-    if (rowptr_bits == 64)
-        hipLaunchKernelGGL(k_xc_terms<int64_t>, dim3((unsigned)blocks), dim3(kXcBlock), 0, stream, (const int64_t*)rowptr, colidx, n,
-                           labels, x, partial, partial + blocks);
-    else
-        hipLaunchKernelGGL(k_xc_terms<int32_t>, dim3((unsigned)blocks), dim3(kXcBlock), 0, stream, (const int32_t*)rowptr, colidx, n,
-                           labels, x, partial, partial + blocks);
-    hipLaunchKernelGGL(k_xc_total, dim3(1), dim3(1024), 0, stream, partial, partial + blocks, blocks, out);
+    if (rowptr_bits == 64) xc_launch<int64_t>(rowptr, colidx, n, labels, x, partial, blocks, out, stream);
+    else xc_launch<int32_t>(rowptr, colidx, n, labels, x, partial, blocks, out, stream);
     int rc = hipGetLastError() == hipSuccess ? GREM_OK : GREM_ERR_HIP;
     if (hipFreeAsync(partial, stream) != hipSuccess) rc = GREM_ERR_HIP;
     return rc;
