@@ -122,9 +122,10 @@ grem_oracle_state *grem_oracle_create(const int64_t *rowptr, const int32_t *coli
     if (!st) { *status = GREM_ORACLE_ERR_NOMEM; return NULL; }
     st->rowptr = rowptr; st->colidx = colidx; st->n = n; st->k = k;
     st->P = grem_oracle_capacity(n, k, balance_slack);
-    st->chunk = chunk; st->R = refine_passes;
-    st->nchunks = (n + chunk - 1) / chunk;
+    /* a chunk at least as long as the graph is the whole graph (and n + chunk cannot overflow) */
     int64_t cl = chunk < n ? chunk : n;
+    st->chunk = cl; st->R = refine_passes;
+    st->nchunks = (n + cl - 1) / cl;
     st->L = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
     st->S = (int64_t *)calloc((size_t)k, sizeof(int64_t));
     st->E = (uint32_t *)calloc((size_t)n * (size_t)k, sizeof(uint32_t));

@@ -135,6 +135,9 @@ def test_single_chunk_closed_form(k, slack):
     v = np.arange(n)
     expect = np.zeros(n, dtype=np.int64) if k == 1 else np.where(v < P, 0, 1 + (v - P) % max(k - 1, 1))
     assert lab.tolist() == expect.tolist()
+    # any chunk size from n on is the same single chunk, up to the largest representable one
+    assert oracle.partition(g.rowptr, g.colidx, n, k, slack, n, 0).tolist() == expect.tolist()
+    assert oracle.partition(g.rowptr, g.colidx, n, k, slack, 2**63 - 1, 0).tolist() == expect.tolist()
 
 
 @pytest.mark.parametrize("n,k,slack,chunk", [(1000, 4, 1.05, 64), (997, 7, 1.0, 100), (50, 3, 1.5, 7),
