@@ -139,12 +139,35 @@ def algorithmic_bytes(n, nnz, k, R, rowptr_bytes, label_bytes):
     return first, later, first + R * later
 
 
-def cpu_baseline(g, w, budget_s=15.0, max_chunks=48):
-    """The oracle, single thread, on the first chunks of pass 0 of the same graph."""
+def emit(out):
+    """Prints the one JSON line; the host the oracle ran on goes beside its rate."""
+    if isinstance(out.get("cpu_baseline"), dict) and "cpu_model" not in out["cpu_baseline"]:
+        out["cpu_baseline"].update(host_info())
+    print(json.dumps(out))
+
+
+def host_info():
+    """CPU model and core count of the host the oracle is timed on."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"cpu_model": model, "nproc": os.cpu_count()}
+
+
+def cpu_baseline(g, w, budget_s=9.0, max_chunks=24):
+    """The oracle, single thread, on the first chunks of the same graph: a sample of pass 0, and a sample of
+    a refinement pass.  The rows after the sample are left empty, so that the oracle gets through the rest of
+    pass 0 quickly (untimed) and the sample's rows can be refined with every vertex labelled."""
     import numpy as np
     import torch
     import oracle
-    n, chunk = g.n, w["chunk"]
+    n, chunk, R = g.n, w["chunk"], w["R"]
     nchunks = (n + chunk - 1) // chunk
     m = min(max_chunks, nchunks)
     rows = min(n, m * chunk)
@@ -153,24 +176,66 @@ def cpu_baseline(g, w, budget_s=15.0, max_chunks=48):
     rp_host = rp_full.cpu().numpy().copy()
     rp_host[rows:] = end                        # rows after the sample are left empty
     ci_host = g.colidx[:end].cpu().numpy()
-    st = oracle.Stepper(rp_host, ci_host, n, w["k"], w["slack"], chunk, 0)
-    done_chunks, entries, t0 = 0, 0, time.perf_counter()
-    while done_chunks < m:
+    st = oracle.Stepper(rp_host, ci_host, n, w["k"], w["slack"], chunk, min(R, 1))
+    done0, t0 = 0, time.perf_counter()
+    while done0 < m:
         st.step()
-        done_chunks += 1
-        hi = min(n, done_chunks * chunk)
-        entries = int(rp_host[hi])
+        done0 += 1
         if time.perf_counter() - t0 > budget_s:
             break
-    dt = time.perf_counter() - t0
+    dt0 = time.perf_counter() - t0
+    entries0 = int(rp_host[min(n, done0 * chunk)])
+    rate0 = entries0 / dt0
+    rate1, done1, dt1, entries1 = None, 0, 0.0, 0
+    if R >= 1:
+        while st.position[0] == 0:              # the rest of pass 0: rows without entries (untimed)
+            st.step()
+        t1 = time.perf_counter()
+        while done1 < done0:
+            st.step()
+            done1 += 1
+            if time.perf_counter() - t1 > budget_s:
+                break
+        dt1 = time.perf_counter() - t1
+        entries1 = int(rp_host[min(n, done1 * chunk)])
+        rate1 = entries1 / dt1
     st.close()
-    edges = entries * (g.directed_edges / g.nnz)
-    return {
-        "value": edges / dt, "unit": "edges/s per pass", "cores": 1, "kind": "oracle",
-        "sample": f"pass 0, first {done_chunks} of {nchunks} chunks ({min(n, done_chunks * chunk)} rows, "
-                  f"{entries} CSR entries) of the same graph, {dt:.1f} s, label table of all {n} vertices",
-        "csr_entries_per_s": entries / dt,
+    # CSR entries per second averaged over the passes of one step (pass 0 once, a refinement pass R times)
+    per_entry = (1.0 / rate0 + (R / rate1 if rate1 else 0.0)) / (R + 1 if rate1 else 1)
+    entries_per_s = 1.0 / per_entry
+    out = {
+        "value": entries_per_s * (g.directed_edges / g.nnz), "unit": "edges/s per pass", "cores": 1, "kind": "oracle",
+        "sample": f"the first {done0} of {nchunks} chunks ({entries0} CSR entries) of the same graph in pass 0, "
+                  f"{dt0:.1f} s" + (f"; the first {done1} chunks ({entries1} entries) in a refinement pass, {dt1:.1f} s "
+                                    f"(rows after the sample left empty, every vertex labelled)" if rate1 else "")
+                  + f"; label table and estimates of all {n} vertices; averaged over 1 + {R} passes",
+        "csr_entries_per_s": entries_per_s,
+        "pass0_csr_entries_per_s": rate0,
+        "refine_pass_csr_entries_per_s": rate1,
     }
+    out.update(host_info())
+    return out
+
+
+def copy_bandwidth_gbps(dev, nbytes=4 << 30, reps=5):
+    """Measured rate of a plain device-to-device copy (bytes read plus bytes written per second)."""
+    import torch
+    a = torch.empty(nbytes // 4, dtype=torch.int32, device=dev).fill_(1)
+    b = torch.empty_like(a)
+    b.copy_(a)
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        b.copy_(a)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None or ms < best else best
+    del a, b
+    torch.cuda.empty_cache()
+    return 2.0 * nbytes / (best * 1e-3) / 1e9
 
 
 def bench_edge_stream(args, w, dev):
@@ -271,7 +336,7 @@ def bench_edge_stream(args, w, dev):
         out["cpu_baseline"] = {"value": min(ms_, done * c_size) / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
                                "sample": f"first {done} of {nchunks} chunks ({min(ms_, done * c_size)} edges) of the "
                                          f"same stream, {dt:.1f} s, state for all {n} nodes"}
-    print(json.dumps(out))
+    emit(out)
 
 
 def bench_eq1(args, w, dev):
@@ -321,7 +386,7 @@ def bench_eq1(args, w, dev):
         out["cpu_baseline"] = {"value": end * (g.directed_edges / nnz) / dt, "unit": "edges/s", "cores": 1,
                                "kind": "oracle", "sample": f"the first {rows} rows ({end} CSR entries) of the same graph, "
                                                            f"labels of all {n} nodes, {dt:.1f} s"}
-    print(json.dumps(out))
+    emit(out)
 
 
 def bench_buckets(args, w, dev):
@@ -377,7 +442,7 @@ def bench_buckets(args, w, dev):
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": take / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
                                "sample": f"the first {take} edges of the same stream with the same labels, {dt:.1f} s"}
-    print(json.dumps(out))
+    emit(out)
 
 
 def bench_recursive(args, w, dev):
@@ -463,18 +528,19 @@ def bench_recursive(args, w, dev):
         out["cpu_baseline"] = {"value": min(ms_, done * c_size) / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
                                "sample": f"first level only: first {done} of {chunks} chunks ({min(ms_, done * c_size)} edges) of "
                                          f"the same stream, {dt:.1f} s (the recursion's oracle runs the same stepper per group)"}
-    print(json.dumps(out))
+    emit(out)
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="chunglu-111M", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
-                    help="skip the extra instrumented step that times the score kernel")
+                    help="skip the extra instrumented steps (per-pass and per-kernel times, the planned call)")
+    ap.add_argument("--no-copy-bandwidth", action="store_true", help="skip the device-copy rate measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of 2 GiB (8 launches): under rocprofv3 --pmc its "
                          "FETCH_SIZE / WRITE_SIZE give the factor that scales those counters to bytes")
@@ -527,24 +593,36 @@ def main():
     print(f"[bench] {g.name}: n={n} nnz={nnz} directed={g.directed_edges} generated in {t_gen:.1f}s",
           file=sys.stderr, flush=True)
 
-    if args.col_bits:
-        B.grem_set_sweep_col_bits(args.col_bits)
-    if args.hub_degree:
-        B.grem_set_sweep_hub_degree(args.hub_degree)
-    ws = torch.empty(B.grem_workspace_bytes(n, nnz, k, chunk), dtype=torch.uint8, device=dev)
+    opts = B.options(col_bits=args.col_bits, hub_degree=args.hub_degree) if (args.col_bits or args.hub_degree) else None
+    ws_bytes = B.grem_workspace_bytes_two_phase(n, nnz, k, chunk, opts)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     B.grem_set_workspace(ws)
     labels = torch.empty(n, dtype=torch.int32, device=dev)
 
     def step():
-        B.grem_partition(g.rowptr, g.colidx, n, k, w["slack"], chunk, R, labels_out=labels)
+        B.grem_partition(g.rowptr, g.colidx, n, k, w["slack"], chunk, R, labels_out=labels, options=opts)
+
+    def timed(fn, reps):
+        """Each repetition bracketed by a device synchronisation; milliseconds per repetition."""
+        out = []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            out.append(1e3 * (time.perf_counter() - t))
+        return out
+
+    def stats(ms):
+        srt = sorted(ms)
+        return {"median_ms": srt[len(srt) // 2] if len(srt) % 2 else 0.5 * (srt[len(srt) // 2 - 1] + srt[len(srt) // 2]),
+                "min_ms": srt[0], "mean_ms": sum(srt) / len(srt), "repetitions": len(srt)}
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
+    per_step = timed(step, args.steps)
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
     passes = R + 1
@@ -560,10 +638,44 @@ def main():
     label_bytes = 1 if k <= 255 else 2
     b_first, b_later, b_total = algorithmic_bytes(n, nnz, k, R, w["bits"] // 8, label_bytes)
     nchunks = (n + chunk - 1) // chunk
+    frac_of_peak = lambda nbytes, ms: nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
     roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": None,
-                "traffic": None, "kernel": "k_score_lds" if k <= 128 else "k_score_global"}
+                "traffic": None, "kernel": "k_score_lds" if k <= 128 else "k_score_global",
+                "frac_is": "the dominant kernel's: algorithmic bytes of one chunk / its average launch time",
+                "whole_call_frac": frac_of_peak(b_total, ms_per_step),
+                "whole_call_frac_is": "algorithmic bytes of all passes / ms_per_step (validation, re-layout and "
+                                      "every kernel of every chunk included)"}
+
+    def per_pass_marks(fn):
+        """[ms before the first pass, pass 0, ..., pass R, output expansion] of one call, from events at the passes'
+        boundaries on the caller's stream."""
+        B.grem_profile_enable(1)
+        B.grem_profile_reset()
+        fn()
+        torch.cuda.synchronize()
+        marks = B.grem_profile_read_marks()
+        B.grem_profile_enable(0)
+        B.grem_profile_reset()
+        return marks
+
+    def pass_report(marks):
+        # marks: call start .. (plan) .. first pass | passes | outputs; the passes are the R + 1 before the last
+        p = marks[-(passes + 1):-1]
+        rep = {"before_first_pass_ms": round(sum(marks[:-(passes + 1)]), 4), "pass_ms": [round(x, 4) for x in p],
+               "after_last_pass_ms": round(marks[-1], 4),
+               "pass0_frac": frac_of_peak(b_first, p[0]),
+               "pass0_csr_entries_per_s": nnz / (p[0] * 1e-3)}
+        if R >= 1:
+            later = sorted(p[1:])
+            med = later[len(later) // 2]
+            rep.update(refine_pass_median_ms=round(med, 4), refine_pass_frac=frac_of_peak(b_later, med),
+                       refine_pass_csr_entries_per_s=nnz / (med * 1e-3))
+        return rep
+
+    planned = None
     if not args.no_kernel_timing:
-        B.grem_profile_enable(True)
+        roofline["cold_call"] = pass_report(per_pass_marks(step))
+        B.grem_profile_enable(2)
         B.grem_profile_reset()
         step()
         torch.cuda.synchronize()
@@ -572,23 +684,48 @@ def main():
         for c in range(B.KERNEL_CLASSES):
             ms, cnt = B.grem_profile_read(c)
             per_class[B.kernel_name(c)] = {"ms": round(ms, 4), "launches": cnt}
-        B.grem_profile_enable(False)
+        B.grem_profile_enable(0)
         B.grem_profile_reset()
         # On the two-phase path the score of a chunk is two launches: the histogram/blend/arg-max
         # kernel and the look-up kernel that prepares the next chunks' input; they are timed as one.
         lookup_ms = per_class.get("lookup", {}).get("ms", 0.0)
-        if per_class.get("lookup", {}).get("launches", 0) > 0:
+        two_phase = per_class.get("lookup", {}).get("launches", 0) > 0
+        if two_phase:
             roofline["kernel"] = "k_tp_score+k_tp_lookup"
             roofline["score_ms"], roofline["lookup_ms"] = round(score_ms, 4), round(lookup_ms, 4)
             roofline["traffic"] = measured_traffic_bytes_per_chunk(args.workload)
-            relayout_ms = per_class.get("relayout", {}).get("ms", 0.0)
-            roofline["relayout_ms"] = round(relayout_ms, 4)
+            roofline["relayout_ms"] = round(per_class.get("relayout", {}).get("ms", 0.0), 4)
         bytes_per_launch = b_total / (passes * nchunks)
         avg_launch_s = 1e-3 * (score_ms + lookup_ms) / max(score_launches, 1)
         achieved = bytes_per_launch / avg_launch_s / 1e9
         roofline.update(achieved=achieved, frac=achieved / HBM_PEAK_GBPS,
                         avg_launch_us=1e6 * avg_launch_s, launches_per_step=score_launches,
                         bytes_per_launch=bytes_per_launch, per_kernel_class_ms=per_class)
+        if two_phase:
+            # the same run on a plan: the re-laid-out copy is built once per graph and kept
+            B.grem_set_workspace(None)
+            del ws
+            torch.cuda.empty_cache()
+            t_plan = time.perf_counter()
+            plan = B.Plan(g.rowptr, g.colidx, n, chunk, opts)
+            torch.cuda.synchronize()
+            t_plan = 1e3 * (time.perf_counter() - t_plan)
+            plabels = torch.empty(n, dtype=torch.int32, device=dev)
+
+            def pstep():
+                B.grem_partition_planned(plan, k, w["slack"], R, labels_out=plabels)
+
+            for _ in range(max(1, args.warmup)):
+                pstep()
+            pms = timed(pstep, args.steps)
+            assert torch.equal(plabels, labels)
+            planned = stats(pms)
+            planned.update(plan_create_ms=round(t_plan, 3), plan_device_bytes=plan.device_bytes,
+                           value=g.directed_edges / (planned["mean_ms"] * 1e-3 / passes), unit="edges/s",
+                           whole_call_frac=frac_of_peak(b_total, planned["mean_ms"]))
+            planned.update(pass_report(per_pass_marks(pstep)))
+            roofline["planned_call_frac"] = planned["whole_call_frac"]
+            plan.close()
 
     out = {
         "metric": "edges/sec per GREM pass",
@@ -607,23 +744,34 @@ def main():
                                f"refine_passes={R}", "n": n, "csr_entries": nnz,
                    "directed_edges": g.directed_edges, "passes_per_step": passes,
                    "chunks_per_pass": nchunks},
+        "step_is": "one whole grem_partition call on a graph it has not seen: validation, re-layout of the entries, "
+                   "pass 0 and the refinement passes",
+        "step_ms": stats(per_step),
         "csr_entries_per_s": nnz / sec_per_pass,
         "ms_per_pass": 1e3 * sec_per_pass,
         "algorithmic_GB_per_step": b_total / 1e9,
+        "algorithmic_GB_pass0": b_first / 1e9,
+        "algorithmic_GB_refine_pass": b_later / 1e9,
         "whole_step_algorithmic_GBps": b_total / (elapsed / args.steps) / 1e9,
-        "whole_step_frac_of_hbm_peak": b_total / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
-        "ms_per_pass_without_relayout": (None if roofline.get("relayout_ms") is None
-                                         else (ms_per_step - roofline["relayout_ms"]) / passes),
+        "workspace_bytes": ws_bytes,
         "cut_fraction": cut / max(nnz, 1),
         "max_partition_size": int(sizes.max()),
         "capacity": P,
         "roofline": roofline,
     }
+    if planned is not None:
+        out["planned_call"] = planned
+        out["planned_call_is"] = ("grem_partition_planned on a grem_plan of the same graph (the re-laid-out copy built "
+                                  "once by grem_plan_create, plan_create_ms, and kept): the passes alone")
+    B.grem_set_workspace(None)
+    if not args.no_copy_bandwidth:
+        bw = copy_bandwidth_gbps(dev)
+        out["device_copy_GBps"] = bw
+        roofline["whole_call_frac_of_copy_rate"] = b_total / (ms_per_step * 1e-3) / 1e9 / bw
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a sample ...", file=sys.stderr, flush=True)
         out["cpu_baseline"] = cpu_baseline(g, w)
-    B.grem_set_workspace(None)
-    print(json.dumps(out))
+    emit(out)
 
 
 if __name__ == "__main__":

@@ -34,7 +34,14 @@
  *   - The CSR must be well formed (rowptr non-decreasing, rowptr[0] = 0, 0 <= colidx < n); this is
  *     the caller's contract and is not checked.  Entries are counted exactly as stored (loops and
  *     duplicates included); nothing requires symmetry.
- *   - Calls that share the process-wide workspace (grem_set_workspace) must not overlap in time.
+ *   - Concurrency: entry points may be called from several host threads and on several streams at
+ *     once; a call keeps its state in memory of its own (allocated stream-ordered on `stream` and
+ *     released when its work is done).  The one exception is the optional caller-owned workspace
+ *     (grem_set_workspace): calls that use it share it and must not overlap in time.
+ *   - Host synchronisation: a call reads a few counters back before it enqueues its passes (the
+ *     graph's largest degree and number of entries, the sizes of the re-laid-out copy, the seed's
+ *     validity): one read-back on the plain route, two or three on the two-phase route;
+ *     grem_partition_planned without a seed reads nothing back.
  */
 #ifndef GREM_H
 #define GREM_H
@@ -58,7 +65,8 @@ extern "C" {
 
 #define GREM_MAX_K 4096
 
-/* Histogram placement for the per-vertex partition counts (Alg. 2, cnt_nbrs). */
+/* Histogram placement for the per-vertex partition counts (Alg. 2, cnt_nbrs): the route a
+ * partition call takes.  All routes give the same result, bit for bit. */
 #define GREM_HIST_AUTO 0     /* LDS when a tile of rows fits the LDS budget (k <= 1024), else global */
 #define GREM_HIST_LDS 1      /* force LDS (error GREM_ERR_ARG if k > 1024) */
 #define GREM_HIST_GLOBAL 2   /* force accumulation straight into E's rows in global memory */
@@ -100,6 +108,62 @@ int grem_partition_state(const void *rowptr, int32_t rowptr_bits, const int32_t 
                          const int32_t *seed_labels, int32_t *labels_out, int64_t *sizes_out,
                          uint32_t *estimates_out, void *stream);
 
+/* Per-call options: how the run is carried out, never what it computes.  All zero (or a NULL
+ * pointer where one is taken) = the defaults. */
+typedef struct grem_options {
+    int32_t histogram_mode;   /* GREM_HIST_*; AUTO picks by k, graph size and chunk size */
+    int32_t col_bits;         /* two-phase route: log2 of the vertices per column block; 0 = automatic
+                                 (17, i.e. 64 KB of LDS with two labels per byte, or less when chunks are
+                                 shorter), else 4..18.  Small values only make sense on small graphs */
+    int32_t hub_degree;       /* two-phase route: rows of at least this many entries are "hubs", whose
+                                 entries are spread evenly over the chunk's workgroups; 0 = default
+                                 (2048), else 1..65535 */
+    int32_t long_row_degree;  /* plain route: a tile of rows is scored by one workgroup; rows of at least
+                                 this many entries are taken out of their tile and spread over a grid of
+                                 their own; 0 = default (16384) */
+    int32_t reserved[4];      /* must be zero */
+} grem_options;
+
+/* grem_partition_state with options.  GREM_ERR_ARG also for an unknown histogram mode, an option out
+ * of range, GREM_HIST_LDS with k > 1024, GREM_HIST_SWEEP with k > 16 or a geometry the two-phase
+ * route cannot take. */
+int grem_partition_opt(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
+                       int32_t k, double balance_slack, int64_t chunk, int32_t refine_passes,
+                       const int32_t *seed_labels, int32_t *labels_out, int64_t *sizes_out,
+                       uint32_t *estimates_out, const grem_options *options, void *stream);
+
+/* ---- Several runs on one graph -----------------------------------------------------------------
+ * The two-phase route (k <= 16) works on a re-laid-out copy of the CSR entries that depends only on
+ * the graph, `chunk` and the two-phase options -- not on k, the slack, the seed or the number of
+ * passes.  A plan holds that copy, so that further runs on the same graph (other seeds, slacks, k,
+ * pass counts; the levels of a recursive driver) skip the re-layout, which otherwise is about half
+ * of a call.
+ *
+ * grem_plan_create re-lays the entries out (synchronous: it returns when the plan is complete) into
+ * device memory the plan owns (hipMalloc; about 5.2 bytes per entry plus tables; an intermediate
+ * copy of 4 bytes per entry is allocated stream-ordered and released before the call returns).
+ * rowptr must stay valid and unchanged while the plan lives; colidx is not read after the call
+ * returns.  Errors: GREM_ERR_ARG (bad arguments or options, or a geometry the two-phase route cannot
+ * take: more than 4096 column blocks, ...), GREM_ERR_NOMEM, GREM_ERR_HIP, GREM_ERR_RANGE.
+ * grem_plan_destroy synchronises the device and frees the plan (NULL is allowed).
+ *
+ * grem_partition_planned: the run of grem_partition_opt for the plan's graph and chunk size, k <= 16,
+ * same result bit for bit.  Per-call state (labels, estimates, the looked-up labels: about 0.5
+ * bytes per entry plus n*(2k+1) bytes) comes from the workspace or a stream-ordered allocation.
+ * Several runs may use one plan at the same time (it is read-only).  Without a seed the call reads
+ * nothing back and returns as soon as its work is enqueued. */
+typedef struct grem_plan grem_plan;
+int grem_plan_create(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
+                     int64_t chunk, const grem_options *options, void *stream, grem_plan **plan_out);
+int grem_plan_destroy(grem_plan *plan);
+size_t grem_plan_device_bytes(const grem_plan *plan);
+/* Largest k the plan serves: 16, or less for a graph so full of hubs that the hub counters of a
+ * workgroup would not fit its LDS at k = 16 (GREM_ERR_ARG beyond it). */
+int32_t grem_plan_max_k(const grem_plan *plan);
+int grem_partition_planned(const grem_plan *plan, int32_t k, double balance_slack,
+                           int32_t refine_passes, const int32_t *seed_labels, int32_t *labels_out,
+                           int64_t *sizes_out, uint32_t *estimates_out, void *stream);
+
 /* Number of CSR entries (v,u) with labels[v] != labels[u] (Sec. 1: cut edges have their endpoints
  * in different partitions), written to the single device int64 *cut_entries_out.  For a symmetric
  * loop-free CSR the undirected cut is half of it and the cut fraction is cut_entries / nnz.
@@ -112,39 +176,35 @@ int grem_edge_cut_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n,
 /* Host helpers.  grem_capacity returns P (or -1 on bad arguments). */
 int64_t grem_capacity(int64_t n, int32_t k, double balance_slack);
 
-/* Bytes of device workspace a partition call can use (E and the re-laid-out copy of the nnz
- * entries included; subtract n*k*4 when estimates_out is passed).  A smaller workspace that still
- * holds everything but the entry copy makes AUTO keep the plain LDS path.  0 on bad arguments. */
-size_t grem_workspace_bytes(int64_t n, int64_t nnz, int32_t k, int64_t chunk);
+/* Bytes of device workspace with which any partition call on such a graph runs on the plain route
+ * without allocating: E (n*k*4; subtract it when estimates_out is passed), the compact labels, the
+ * chunk's proposals and the admission tables.  0 on bad arguments. */
+size_t grem_workspace_bytes(int64_t n, int32_t k, int64_t chunk);
+
+/* Bytes with which a call can also take the two-phase route (k <= 16) without allocating: an upper
+ * bound for any graph of n rows and nnz entries under the given options (NULL = defaults): the
+ * re-laid-out copy and its tables, and, sharing one region, the intermediate copy of the re-layout
+ * (4 bytes per entry) and the per-call state.  Never less than grem_workspace_bytes.  A workspace
+ * between the two sizes makes GREM_HIST_AUTO keep the plain route.  0 on bad arguments. */
+size_t grem_workspace_bytes_two_phase(int64_t n, int64_t nnz, int32_t k, int64_t chunk,
+                                      const grem_options *options);
 
 /* Optional caller-owned workspace (device memory, 256-byte aligned) used by later partition
- * calls instead of a per-call stream-ordered allocation; (NULL, 0) removes it.  The library never
- * frees it. */
+ * calls (not by plans) instead of per-call stream-ordered allocations; (NULL, 0) removes it.  The
+ * library never frees it.  Process-wide; calls that use it must not overlap in time. */
 int grem_set_workspace(void *dev_ptr, size_t bytes);
 
-/* GREM_HIST_*; returns GREM_ERR_ARG for an unknown mode.  Process-wide. */
-int grem_set_histogram_mode(int32_t mode);
-
-/* log2 of the vertices per column block of the two-phase path: 0 = automatic (default: 17, i.e.
- * 64 KB of LDS with two labels per byte, or less when chunks are shorter), else 4..18.  Small
- * values only make sense for testing on small graphs.  Process-wide. */
-int grem_set_sweep_col_bits(int32_t bits);
-
-/* Rows of at least this many entries are "hubs" of the two-phase path: their entries are
- * spread evenly over the chunk's workgroups.  1..65535, default 2048; smaller values only make
- * sense for testing on small graphs.  Process-wide. */
-int grem_set_sweep_hub_degree(int32_t degree);
-
-/* Outside the two-phase path a tile of rows is scored by one workgroup; rows of at least this
- * many entries are taken out of their tile and spread over a grid of their own (a hub's row is
- * the work of many workgroups, as the paper's power-law graphs need).  0 = default (16384);
- * smaller values only make sense for testing on small graphs.  Process-wide. */
-int grem_set_long_row_degree(int32_t degree);
-
-/* Per-kernel timing with HIP events on the caller's stream, for measurement.  While enabled every
- * kernel launch of a partition call is bracketed by two events.  grem_profile_read synchronises on
- * the recorded events, adds up the launches of one kernel class since the last grem_profile_reset,
- * and returns total milliseconds and the launch count.  Classes: */
+/* ---- Measurement aids (process-wide; not meant for concurrent runs) ------------------------------
+ * Timing with HIP events on the caller's stream.  Level 0: off.  Level 1: one event at the start
+ * of a partition call, one before its first pass and one after every pass and after the final
+ * expansion of the outputs (grem_profile_read_marks).  Level 2: also two events around every kernel
+ * launch (grem_profile_read; the brackets slow a call down by a few per cent).
+ * grem_profile_read synchronises on the recorded events, adds up the launches of one kernel class
+ * since the last grem_profile_reset, and returns total milliseconds and the launch count.
+ * grem_profile_read_marks writes the milliseconds between consecutive marks since the last reset:
+ * [0] everything before the first pass (validation, plan, re-layout), [1 .. refine_passes + 1] the
+ * passes, then the expansion of the outputs; returns the number of intervals written (at most
+ * `capacity`) or a negative error code.  Classes: */
 #define GREM_KERNEL_PREPASS 0
 #define GREM_KERNEL_SCORE 1      /* row stream + label gather + histogram + blend + argmax; on the
                                     two-phase path: histogram of stored look-ups + blend + argmax */
@@ -158,9 +218,10 @@ int grem_set_long_row_degree(int32_t degree);
 #define GREM_KERNEL_LOOKUP 9     /* two-phase path: label look-ups for the entries that refer to a chunk */
 #define GREM_KERNEL_HUBS 10      /* blend and proposal of the high-degree rows of the two-phase path */
 #define GREM_KERNEL_CLASSES 11
-int grem_profile_enable(int32_t on);
+int grem_profile_enable(int32_t level);
 int grem_profile_reset(void);
 int grem_profile_read(int32_t kernel_class, double *total_ms, int64_t *launches);
+int grem_profile_read_marks(double *ms_out, int32_t capacity);
 
 /* ---- Alg. 1 in the stream model the paper states it in (Sec. 4.1): chunks of an edge list, two
  * partitions ----------------------------------------------------------------------------------

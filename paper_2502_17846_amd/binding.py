@@ -22,15 +22,31 @@ KERNEL_SCORE = 1
 
 EXPORTS = [
     "grem_partition", "grem_partition_seeded", "grem_partition_r32", "grem_partition_seeded_r32",
-    "grem_partition_state", "grem_edge_cut", "grem_edge_cut_r32", "grem_capacity",
-    "grem_workspace_bytes", "grem_set_workspace", "grem_set_histogram_mode",
-    "grem_set_sweep_col_bits", "grem_set_sweep_hub_degree", "grem_set_long_row_degree", "grem_profile_enable",
-    "grem_profile_reset", "grem_profile_read", "grem_status_string", "grem_kernel_name",
+    "grem_partition_state", "grem_partition_opt", "grem_plan_create", "grem_plan_destroy",
+    "grem_plan_device_bytes", "grem_plan_max_k", "grem_partition_planned", "grem_edge_cut", "grem_edge_cut_r32", "grem_capacity",
+    "grem_workspace_bytes", "grem_workspace_bytes_two_phase", "grem_set_workspace", "grem_profile_enable",
+    "grem_profile_reset", "grem_profile_read", "grem_profile_read_marks", "grem_status_string", "grem_kernel_name",
     "grem_edge_stream_bipartition", "grem_edge_list_cut", "grem_edge_stream_profile_enable",
     "grem_edge_stream_profile_read", "grem_recursive_bisection", "grem_edge_buckets", "grem_expected_cut",
     "grem_expected_cut_noalloc", "grem_expected_cut_noalloc_max_n",
 ]
 EDGE_REFINE, EDGE_FIXED = 0, 1
+
+
+class Options(ctypes.Structure):
+    """grem_options of include/grem.h: how a run is carried out, never what it computes."""
+    _fields_ = [("histogram_mode", ctypes.c_int32), ("col_bits", ctypes.c_int32), ("hub_degree", ctypes.c_int32),
+                ("long_row_degree", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+
+
+def options(histogram_mode: int = 0, col_bits: int = 0, hub_degree: int = 0, long_row_degree: int = 0) -> Options:
+    o = Options()
+    o.histogram_mode, o.col_bits, o.hub_degree, o.long_row_degree = histogram_mode, col_bits, hub_degree, long_row_degree
+    return o
+
+
+def _opt(o):
+    return None if o is None else ctypes.byref(o)
 
 
 class GremError(RuntimeError):
@@ -65,18 +81,27 @@ def load():
         getattr(lib, name).argtypes = [vp, vp, i64, vp, vp, vp]
     lib.grem_capacity.restype = i64
     lib.grem_capacity.argtypes = [i64, i32, dbl]
+    optp = ctypes.POINTER(Options)
+    lib.grem_partition_opt.restype = ctypes.c_int
+    lib.grem_partition_opt.argtypes = [vp, i32, vp, i64, i32, dbl, i64, i32, vp, vp, vp, vp, optp, vp]
+    lib.grem_plan_create.restype = ctypes.c_int
+    lib.grem_plan_create.argtypes = [vp, i32, vp, i64, i64, optp, vp, ctypes.POINTER(vp)]
+    lib.grem_plan_destroy.restype = ctypes.c_int
+    lib.grem_plan_destroy.argtypes = [vp]
+    lib.grem_plan_device_bytes.restype = ctypes.c_size_t
+    lib.grem_plan_device_bytes.argtypes = [vp]
+    lib.grem_plan_max_k.restype = ctypes.c_int32
+    lib.grem_plan_max_k.argtypes = [vp]
+    lib.grem_partition_planned.restype = ctypes.c_int
+    lib.grem_partition_planned.argtypes = [vp, i32, dbl, i32, vp, vp, vp, vp, vp]
     lib.grem_workspace_bytes.restype = ctypes.c_size_t
-    lib.grem_workspace_bytes.argtypes = [i64, i64, i32, i64]
+    lib.grem_workspace_bytes.argtypes = [i64, i32, i64]
+    lib.grem_workspace_bytes_two_phase.restype = ctypes.c_size_t
+    lib.grem_workspace_bytes_two_phase.argtypes = [i64, i64, i32, i64, optp]
     lib.grem_set_workspace.restype = ctypes.c_int
     lib.grem_set_workspace.argtypes = [vp, ctypes.c_size_t]
-    lib.grem_set_histogram_mode.restype = ctypes.c_int
-    lib.grem_set_histogram_mode.argtypes = [i32]
-    lib.grem_set_sweep_col_bits.restype = ctypes.c_int
-    lib.grem_set_sweep_col_bits.argtypes = [i32]
-    lib.grem_set_sweep_hub_degree.restype = ctypes.c_int
-    lib.grem_set_sweep_hub_degree.argtypes = [i32]
-    lib.grem_set_long_row_degree.restype = ctypes.c_int
-    lib.grem_set_long_row_degree.argtypes = [i32]
+    lib.grem_profile_read_marks.restype = ctypes.c_int
+    lib.grem_profile_read_marks.argtypes = [ctypes.POINTER(dbl), i32]
     lib.grem_profile_enable.restype = ctypes.c_int
     lib.grem_profile_enable.argtypes = [i32]
     lib.grem_profile_reset.restype = ctypes.c_int
@@ -153,8 +178,12 @@ def grem_capacity(n: int, k: int, balance_slack: float) -> int:
     return int(load().grem_capacity(n, k, float(balance_slack)))
 
 
-def grem_workspace_bytes(n: int, nnz: int, k: int, chunk: int) -> int:
-    return int(load().grem_workspace_bytes(n, nnz, k, chunk))
+def grem_workspace_bytes(n: int, k: int, chunk: int) -> int:
+    return int(load().grem_workspace_bytes(n, k, chunk))
+
+
+def grem_workspace_bytes_two_phase(n: int, nnz: int, k: int, chunk: int, options: Optional[Options] = None) -> int:
+    return int(load().grem_workspace_bytes_two_phase(n, nnz, k, chunk, _opt(options)))
 
 
 def grem_set_workspace(buf: Optional[torch.Tensor]):
@@ -166,22 +195,6 @@ def grem_set_workspace(buf: Optional[torch.Tensor]):
                "grem_set_workspace")
 
 
-def grem_set_histogram_mode(mode: int):
-    _check(load().grem_set_histogram_mode(mode), "grem_set_histogram_mode")
-
-
-def grem_set_sweep_col_bits(bits: int):
-    _check(load().grem_set_sweep_col_bits(bits), "grem_set_sweep_col_bits")
-
-
-def grem_set_sweep_hub_degree(degree: int):
-    _check(load().grem_set_sweep_hub_degree(degree), "grem_set_sweep_hub_degree")
-
-
-def grem_set_long_row_degree(degree: int):
-    _check(load().grem_set_long_row_degree(degree), "grem_set_long_row_degree")
-
-
 def _rowptr_bits(rowptr: torch.Tensor) -> int:
     if rowptr.dtype == torch.int64:
         return 64
@@ -191,11 +204,19 @@ def _rowptr_bits(rowptr: torch.Tensor) -> int:
 
 
 def grem_partition_seeded(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, seed_labels,
-                          labels_out=None, stream=None) -> torch.Tensor:
+                          labels_out=None, stream=None, options: Optional[Options] = None) -> torch.Tensor:
     lib = load()
     bits = _rowptr_bits(rowptr)
     if labels_out is None:
         labels_out = torch.empty(n, dtype=torch.int32, device=colidx.device)
+    if options is not None:
+        rc = lib.grem_partition_opt(_dev(rowptr, rowptr.dtype, "rowptr"), bits, _colidx(colidx), n, k,
+                                    float(balance_slack), chunk, refine_passes,
+                                    None if seed_labels is None else _dev(seed_labels, torch.int32, "seed_labels"),
+                                    _dev(labels_out, torch.int32, "labels_out"), None, None, _opt(options),
+                                    _stream(stream))
+        _check(rc, "grem_partition_opt")
+        return labels_out
     fn = lib.grem_partition_seeded if bits == 64 else lib.grem_partition_seeded_r32
     rc = fn(_dev(rowptr, rowptr.dtype, "rowptr"), _colidx(colidx), n, k,
             float(balance_slack), chunk, refine_passes,
@@ -206,7 +227,10 @@ def grem_partition_seeded(rowptr, colidx, n, k, balance_slack, chunk, refine_pas
 
 
 def grem_partition(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, labels_out=None,
-                   stream=None) -> torch.Tensor:
+                   stream=None, options: Optional[Options] = None) -> torch.Tensor:
+    if options is not None:
+        return grem_partition_seeded(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, None, labels_out,
+                                     stream, options)
     lib = load()
     bits = _rowptr_bits(rowptr)
     if labels_out is None:
@@ -220,24 +244,87 @@ def grem_partition(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, la
 
 
 def grem_partition_state(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, seed_labels=None,
-                         want_sizes=True, want_estimates=True, stream=None):
+                         want_sizes=True, want_estimates=True, stream=None, options: Optional[Options] = None):
     """Returns (labels int32[n], sizes int64[k] or None, estimates uint32-as-int32 view [n,k] or
-    None)."""
+    None).  With `options` the call goes through grem_partition_opt."""
     lib = load()
     bits = _rowptr_bits(rowptr)
     dev = colidx.device
     labels = torch.empty(n, dtype=torch.int32, device=dev)
     sizes = torch.empty(k, dtype=torch.int64, device=dev) if want_sizes else None
     est = torch.empty((n, k), dtype=torch.int32, device=dev) if want_estimates else None
-    rc = lib.grem_partition_state(
-        _dev(rowptr, rowptr.dtype, "rowptr"), bits, _colidx(colidx), n, k,
-        float(balance_slack), chunk, refine_passes,
-        None if seed_labels is None else _dev(seed_labels, torch.int32, "seed_labels"),
-        _dev(labels, torch.int32, "labels_out"),
-        None if sizes is None else _dev(sizes, torch.int64, "sizes_out"),
-        None if est is None else _dev(est, torch.int32, "estimates_out"), _stream(stream))
-    _check(rc, "grem_partition_state")
+    args = [_dev(rowptr, rowptr.dtype, "rowptr"), bits, _colidx(colidx), n, k,
+            float(balance_slack), chunk, refine_passes,
+            None if seed_labels is None else _dev(seed_labels, torch.int32, "seed_labels"),
+            _dev(labels, torch.int32, "labels_out"),
+            None if sizes is None else _dev(sizes, torch.int64, "sizes_out"),
+            None if est is None else _dev(est, torch.int32, "estimates_out")]
+    if options is None:
+        _check(lib.grem_partition_state(*args, _stream(stream)), "grem_partition_state")
+    else:
+        _check(lib.grem_partition_opt(*args, _opt(options), _stream(stream)), "grem_partition_opt")
     return labels, sizes, est
+
+
+class Plan:
+    """A grem_plan: the re-laid-out copy of one graph's entries for the two-phase route.  Keeps the
+    rowptr tensor alive (the plan reads it in every run); close() (or the context manager) frees the
+    plan's device memory."""
+
+    def __init__(self, rowptr, colidx, n, chunk, options: Optional[Options] = None, stream=None):
+        lib = load()
+        self._rowptr = rowptr
+        self.n = n
+        h = ctypes.c_void_p()
+        rc = lib.grem_plan_create(_dev(rowptr, rowptr.dtype, "rowptr"), _rowptr_bits(rowptr), _colidx(colidx), n,
+                                  chunk, _opt(options), _stream(stream), ctypes.byref(h))
+        _check(rc, "grem_plan_create")
+        self._h = h
+
+    @property
+    def device_bytes(self) -> int:
+        return int(load().grem_plan_device_bytes(self._h))
+
+    @property
+    def max_k(self) -> int:
+        return int(load().grem_plan_max_k(self._h))
+
+    def close(self):
+        if self._h:
+            _check(load().grem_plan_destroy(self._h), "grem_plan_destroy")
+            self._h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def grem_partition_planned(plan: Plan, k, balance_slack, refine_passes, seed_labels=None, labels_out=None,
+                           want_sizes=False, want_estimates=False, stream=None):
+    """Returns labels, or (labels, sizes, estimates) when either of the two is asked for."""
+    lib = load()
+    dev = plan._rowptr.device
+    if labels_out is None:
+        labels_out = torch.empty(plan.n, dtype=torch.int32, device=dev)
+    sizes = torch.empty(k, dtype=torch.int64, device=dev) if want_sizes else None
+    est = torch.empty((plan.n, k), dtype=torch.int32, device=dev) if want_estimates else None
+    rc = lib.grem_partition_planned(plan._h, k, float(balance_slack), refine_passes,
+                                    None if seed_labels is None else _dev(seed_labels, torch.int32, "seed_labels"),
+                                    _dev(labels_out, torch.int32, "labels_out"),
+                                    None if sizes is None else _dev(sizes, torch.int64, "sizes_out"),
+                                    None if est is None else _dev(est, torch.int32, "estimates_out"), _stream(stream))
+    _check(rc, "grem_partition_planned")
+    if want_sizes or want_estimates:
+        return labels_out, sizes, est
+    return labels_out
 
 
 def grem_edge_cut(rowptr, colidx, n, labels, stream=None) -> torch.Tensor:
@@ -253,8 +340,18 @@ def grem_edge_cut(rowptr, colidx, n, labels, stream=None) -> torch.Tensor:
     return out
 
 
-def grem_profile_enable(on: bool):
-    _check(load().grem_profile_enable(1 if on else 0), "grem_profile_enable")
+def grem_profile_enable(level: int):
+    """0: off; 1: marks at the passes' boundaries; 2: also a pair of events around every launch."""
+    _check(load().grem_profile_enable(int(level)), "grem_profile_enable")
+
+
+def grem_profile_read_marks(capacity: int = 64):
+    """Milliseconds between consecutive marks: [before the first pass, pass 0, pass 1, ..., output expansion]."""
+    buf = (ctypes.c_double * capacity)()
+    cnt = load().grem_profile_read_marks(buf, capacity)
+    if cnt < 0:
+        raise GremError(cnt, "grem_profile_read_marks")
+    return [buf[i] for i in range(cnt)]
 
 
 def grem_profile_reset():

@@ -1,6 +1,14 @@
-// Host side of the GREM library: argument checks, workspace carve-up, and the stream-ordered
-// sequence of launches for each chunk of each pass (Alg. 1's chunk loop).  See include/grem.h for
-// the contract of every entry point.
+// Host side of the GREM library: argument checks, memory carve-up, and the stream-ordered sequence
+// of launches for each chunk of each pass (Alg. 1's chunk loop).  See include/grem.h for the
+// contract of every entry point.
+//
+// Structure:
+//   Arena / carve      device memory for a call: pieces of the caller's workspace, or stream-ordered
+//                      allocations
+//   PlanData           the re-laid-out copy of a graph's entries for the two-phase route (k <= 16):
+//                      built once per call, or once per graph behind a grem_plan
+//   run_two_phase      Alg. 1's loop on a plan
+//   run_plain          Alg. 1's loop straight on the CSR (any k)
 #include "grem.h"
 
 #include <hip/hip_runtime.h>
@@ -9,6 +17,7 @@
 #include <cstdio>
 #include <cstring>
 #include <mutex>
+#include <new>
 #include <vector>
 
 #include "grem_kernels.hip.h"
@@ -23,30 +32,128 @@ constexpr int kLdsMaxK = 1024;             // above this the histograms live in 
 constexpr int kLongRowDegree = 16384;      // plain score kernels: rows this long get a grid of their own ...
 constexpr uint32_t kLongRowPart = 16384;   // ... that many entries per workgroup and turn
 constexpr unsigned kLongRowGrid = 512;
-constexpr int kSweepMaxK = 16;             // two-phase path: 4-bit labels, 16-bit counters, 2048 rows, 64 KB
-constexpr int64_t kSweepMinN = 1 << 22;    // AUTO: label table must exceed L2 for the path to pay
+constexpr int kSweepMaxK = 16;             // two-phase route: 4-bit labels, 16-bit counters, 2048 rows, 64 KB
+constexpr int64_t kSweepMinN = 1 << 22;    // AUTO: label table must exceed L2 for the route to pay
 constexpr int64_t kSweepMinChunk = 1 << 14;   // AUTO: per-chunk launches must have work to do
 constexpr int kDefaultColBits = 17;        // 2^17 labels, two per byte: 64 KB of LDS, two workgroups per CU
+constexpr int kDefaultHubDegree = 2048;
 constexpr int64_t kMaxSegments = 1ll << 22;   // chunks * column blocks
+constexpr int kMaxParts = kPlanParts;      // parts of a slice (hub share) in the re-layout
 
+// ---- process-wide state: the optional workspace and the measurement aids --------------------------
 struct Global {
     std::mutex mu;
     void *ws = nullptr;
     size_t ws_bytes = 0;
-    int hist_mode = GREM_HIST_AUTO;
-    int long_row_degree = kLongRowDegree;
-    int sweep_col_bits = 0;                // 0 = automatic
-    int sweep_hub_degree = 2048;
-    bool prof = false;
+    int prof_level = 0;
     struct Ev { int cls; hipEvent_t a, b; };
-    std::vector<Ev> events;
+    std::vector<Ev> events;            // level 2: a pair per launch
+    std::vector<hipEvent_t> marks;     // level 1: call start, first pass, end of every pass, end of call
     std::vector<hipEvent_t> pool;
 };
 Global g;
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
-// Geometry of the two-phase path: chunks, row slices and column blocks (see grem_twophase.hip.h).
+// ---- options ---------------------------------------------------------------------------------------
+struct Opts {
+    int hist_mode = GREM_HIST_AUTO;
+    int col_bits = 0;                       // 0 = automatic
+    int hub_degree = kDefaultHubDegree;
+    int long_row_degree = kLongRowDegree;
+};
+
+bool resolve_options(const grem_options *o, Opts *out) {
+    Opts r;
+    if (o) {
+        if (o->histogram_mode != GREM_HIST_AUTO && o->histogram_mode != GREM_HIST_LDS &&
+            o->histogram_mode != GREM_HIST_GLOBAL && o->histogram_mode != GREM_HIST_SWEEP)
+            return false;
+        if (o->col_bits != 0 && (o->col_bits < 4 || o->col_bits > kMaxColBits)) return false;
+        if (o->hub_degree < 0 || o->hub_degree > 65535) return false;
+        if (o->long_row_degree < 0) return false;
+        for (int i = 0; i < 4; ++i)
+            if (o->reserved[i] != 0) return false;
+        r.hist_mode = o->histogram_mode;
+        r.col_bits = o->col_bits;
+        if (o->hub_degree) r.hub_degree = o->hub_degree;
+        if (o->long_row_degree) r.long_row_degree = o->long_row_degree;
+    }
+    *out = r;
+    return true;
+}
+
+// ---- device memory of a call -----------------------------------------------------------------------
+// Bump mode: pieces of one caller-owned block, released by moving the top back.  Otherwise every
+// request is an allocation of its own: stream-ordered (released stream-ordered) or, for memory that
+// outlives the call, hipMalloc.
+struct Arena {
+    char *base = nullptr;
+    size_t cap = 0, off = 0;
+    hipStream_t stream = nullptr;
+    bool persistent = false;
+    std::vector<void *> owned;
+    size_t total = 0;                       // bytes handed out (allocation modes)
+
+    char *alloc(size_t bytes) {
+        bytes = align_up(bytes ? bytes : 1);
+        if (base) {
+            if (off + bytes > cap) return nullptr;
+            char *p = base + off;
+            off += bytes;
+            return p;
+        }
+        void *p = nullptr;
+        const hipError_t e = persistent ? hipMalloc(&p, bytes) : hipMallocAsync(&p, bytes, stream);
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        owned.push_back(p);
+        total += bytes;
+        return (char *)p;
+    }
+    struct Mark { size_t off, count; };
+    Mark mark() const { return {off, owned.size()}; }
+    // gives back everything handed out since `m` (work already enqueued on the stream may still use it:
+    // stream-ordered release, and in bump mode whatever takes the space next runs later on the same stream)
+    void release_to(Mark m) {
+        off = m.off;
+        while (owned.size() > m.count) {
+            if (persistent) (void)hipFree(owned.back());
+            else (void)hipFreeAsync(owned.back(), stream);
+            owned.pop_back();
+        }
+    }
+    void release_all() { release_to({0, 0}); }
+};
+
+// Several arrays out of one request: the same function lays them out twice, first against a null
+// base to find the size, then against the block.
+struct Carver {
+    char *base;
+    size_t off = 0;
+    template <typename T> void take(T *&p, size_t count) {
+        p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += align_up(count * sizeof(T));
+    }
+};
+template <typename F> bool carve(Arena &A, F &&f) {
+    Carver dry{nullptr};
+    f(dry);
+    char *p = A.alloc(dry.off);
+    if (!p) return false;
+    Carver wet{p};
+    f(wet);
+    return true;
+}
+template <typename F> size_t carve_size(F &&f) {
+    Carver dry{nullptr};
+    f(dry);
+    return align_up(dry.off ? dry.off : 1);
+}
+
+// ---- geometry of the two-phase route: chunks, row slices and column blocks (grem_twophase.hip.h) ---
 struct TpGeom {
     int cb = 0, nbc = 0, nblk = 0, nch = 0, nsl = 0, shift = -1, gb = 0, ngroups = 1;
     uint32_t chunk = 0;
@@ -80,94 +187,6 @@ TpGeom tp_geometry(int64_t n, int64_t chunk, int col_bits_setting) {
     return t;
 }
 
-struct Layout {
-    size_t E, Lc, prop, S, cnt, tot, room, ocnt, fillRank, fillSorted, fillC, misc, long_cnt, long_list;
-    // plan of the two-phase path (k <= 16 only)
-    size_t sl_reg_cnt, sl_reg_start, sl_nh, sl_hub_start, sl_hent, sl_hent_start, share_h0, share_nhs,
-        ch_regtot, ch_nh, ch_H, ch_nvs, ch_hbase, hub_row, hub_off;
-    size_t total;
-    size_t subR, subH, xstart, tstart, lo, loh, Hhub, T, R, Lx, Rdyn, U, Uh, E16, total_sweep;   // extras of the two-phase path, after `total`
-    size_t hub_rows_cap;                                          // rows of Hhub
-};
-
-inline int64_t slices_per_chunk(int64_t n, int64_t chunk) {
-    const int64_t cl = chunk < n ? chunk : n;
-    return (cl + kSliceRows - 1) / kSliceRows;
-}
-
-constexpr int kMaxParts = 8;      // parts of a slice (hub share) in the re-layout
-
-Layout make_layout(int64_t n, int64_t nnz, int64_t hub_entries, int32_t k, int64_t chunk, bool external_E,
-                   const TpGeom &tp, int hub_degree, bool seeded, int npr = kMaxParts, int nps = kMaxParts) {
-    Layout L{};
-    const int64_t cl = chunk < n ? chunk : n;
-    const size_t lab = k <= 255 ? 1 : 2;
-    const int64_t ntiles = (cl + kAdmitTile - 1) / kAdmitTile;
-    const int64_t nchunks = (n + chunk - 1) / chunk;
-    const size_t G = (size_t)nchunks * (size_t)slices_per_chunk(n, chunk);
-    size_t off = 0;
-    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
-    L.E = take(external_E ? 0 : (size_t)n * (size_t)k * 4);
-    L.Lc = take((size_t)n * lab);
-    L.prop = take((size_t)cl * lab);
-    L.S = take((size_t)k * 8);
-    L.cnt = take((size_t)ntiles * (size_t)k * 4);
-    L.tot = take(2 * (size_t)k * 4);
-    L.room = take((size_t)k * 8);
-    L.ocnt = take((size_t)ntiles * 4);
-    L.fillRank = take((size_t)k * 4);
-    L.fillSorted = take((size_t)k * 8);
-    L.fillC = take(((size_t)k + 1) * 8);
-    L.misc = take(16 * 8);
-    L.long_cnt = take((size_t)nchunks * 4);
-    L.long_list = take((size_t)cl * 4);
-    const bool tp_possible = k <= kSweepMaxK && tp.ok;
-    if (tp_possible) {
-        L.sl_reg_cnt = take(G * 4);
-        L.sl_reg_start = take(G * 8);
-        L.sl_nh = take(G * 4);
-        L.sl_hub_start = take(G * 4);
-        L.sl_hent = take(G * 8);
-        L.sl_hent_start = take(G * 8);
-        L.share_h0 = take(G * 4);
-        L.share_nhs = take(G * 4);
-        L.ch_regtot = take((size_t)nchunks * 8);
-        L.ch_nh = take((size_t)nchunks * 4);
-        L.ch_H = take((size_t)nchunks * 8);
-        L.ch_nvs = take((size_t)nchunks * 4);
-        L.ch_hbase = take(((size_t)nchunks + 1) * 8);
-        L.hub_row = take((size_t)n * 4);
-        L.hub_off = take((size_t)(n + nchunks) * 8);
-    }
-    L.total = off;
-    if (tp_possible) {
-        // a chunk cannot hold more hubs than rows, nor more than entries / hub_degree
-        size_t hubs = (size_t)(nnz / (hub_degree > 0 ? hub_degree : 1)) + 1;
-        if (hubs > (size_t)cl) hubs = (size_t)cl;
-        L.hub_rows_cap = hubs;
-        const size_t segs = (size_t)tp.nch * (size_t)tp.nblk;
-        const size_t rows = (size_t)tp.nch * ((size_t)tp.nsl + 1);
-        L.subR = take(rows * (size_t)tp.nblk * 4);
-        L.subH = take(rows * (size_t)tp.nblk * 4);
-        L.xstart = take((segs + 1) * 8);
-        L.tstart = take((segs + 1) * 8);
-        L.lo = take(G * (size_t)npr * ((size_t)tp.ngroups + 1) * 4);
-        L.loh = take(G * (size_t)nps * ((size_t)tp.ngroups + 1) * 4);
-        L.Hhub = take(hubs * (size_t)k * 4);
-        // every sub-segment is padded to a multiple of 4 tuples, every segment to a multiple of 8
-        const size_t slots = (size_t)(nnz > 0 ? nnz : 0) + 6 * rows * (size_t)tp.nblk + 8 * segs;
-        L.T = take(slots * 3 + 16);                 // column in block, 3 bytes per tuple
-        L.R = take(slots * 2 + 16);                 // row field, 2 bytes per tuple
-        L.Lx = take(slots / 2 + 16);                // label, 4 bits per tuple
-        L.Rdyn = take(seeded ? slots * 2 + 16 : 0); // seeded runs: R with the unassigned neighbours marked
-        L.U = take((size_t)(nnz > 0 ? nnz : 0) * 4 + 16);
-        L.Uh = take((size_t)(hub_entries > 0 ? hub_entries : 0) * 4 + 16);
-        L.E16 = take((size_t)n * (size_t)k * 2);
-    }
-    L.total_sweep = off;
-    return L;
-}
-
 bool args_ok(const void *rowptr, const int32_t *colidx, int64_t n, int32_t k, double slack,
              int64_t chunk, int32_t R) {
     if (!rowptr || !colidx) return false;
@@ -178,12 +197,16 @@ bool args_ok(const void *rowptr, const int32_t *colidx, int64_t n, int32_t k, do
     return true;
 }
 
-// Launch bracket: optional event pair per launch, error check after it.
+// ---- launch bracket: optional event pair per launch, error check after it --------------------------
 struct Launcher {
     hipStream_t stream;
+    int level = 0;                           // snapshot of the profiling level for this call
     int err = GREM_OK;
     hipEvent_t get_event() {
-        if (!g.pool.empty()) { hipEvent_t e = g.pool.back(); g.pool.pop_back(); return e; }
+        {
+            std::lock_guard<std::mutex> lock(g.mu);
+            if (!g.pool.empty()) { hipEvent_t e = g.pool.back(); g.pool.pop_back(); return e; }
+        }
         hipEvent_t e;
         // timing only: no system-scope fence (and the cache write-back it implies) when the event completes
         if (hipEventCreateWithFlags(&e, hipEventDisableSystemFence) != hipSuccess) { err = GREM_ERR_HIP; return nullptr; }
@@ -192,523 +215,772 @@ struct Launcher {
     template <typename F> void run(int cls, F &&f) {
         if (err) return;
         hipEvent_t a = nullptr, b = nullptr;
-        if (g.prof) {
+        if (level >= 2) {
             a = get_event(); b = get_event();
             if (err) return;
             if (hipEventRecord(a, stream) != hipSuccess) { err = GREM_ERR_HIP; return; }
         }
         f();
         if (hipGetLastError() != hipSuccess) { err = GREM_ERR_HIP; return; }
-        if (g.prof) {
+        if (level >= 2) {
             if (hipEventRecord(b, stream) != hipSuccess) { err = GREM_ERR_HIP; return; }
+            std::lock_guard<std::mutex> lock(g.mu);
             g.events.push_back({cls, a, b});
         }
     }
+    void mark() {
+        if (err || level < 1) return;
+        hipEvent_t e = get_event();
+        if (err) return;
+        if (hipEventRecord(e, stream) != hipSuccess) { err = GREM_ERR_HIP; return; }
+        std::lock_guard<std::mutex> lock(g.mu);
+        g.marks.push_back(e);
+    }
+    bool memset(void *p, int v, size_t bytes) {
+        if (err) return false;
+        if (bytes && hipMemsetAsync(p, v, bytes, stream) != hipSuccess) { err = GREM_ERR_HIP; return false; }
+        return true;
+    }
+    bool read_back(void *host, const void *dev, size_t bytes) {
+        if (err) return false;
+        if (hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+            hipStreamSynchronize(stream) != hipSuccess) { err = GREM_ERR_HIP; return false; }
+        return true;
+    }
 };
 
-template <typename RowT, typename LabelT>
-int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t k, double slack,
-                  int64_t chunk, int32_t R, const int32_t *seed, int32_t *labels_out,
-                  int64_t *sizes_out, uint32_t *estimates_out, hipStream_t stream) {
-    const long long P = grem_capacity(n, k, slack);
-    const bool external_E = estimates_out != nullptr;
-    const int hub_degree = g.sweep_hub_degree;
-    const TpGeom geo = tp_geometry(n, chunk, g.sweep_col_bits);
-    Layout lay = make_layout(n, 0, 0, k, chunk, external_E, geo, hub_degree, seed != nullptr);
+bool set_lds(const void *f, size_t bytes) {
+    return bytes <= 64 * 1024 ||
+           hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+}
 
-    const int hist_mode = g.hist_mode;
-    if (hist_mode == GREM_HIST_LDS && k > kLdsMaxK) return GREM_ERR_ARG;
-    if (hist_mode == GREM_HIST_SWEEP && (k > kSweepMaxK || !geo.ok)) return GREM_ERR_ARG;
-    const bool use_lds = hist_mode != GREM_HIST_GLOBAL && k <= kLdsMaxK;
-
-    // workspace
-    char *ws = nullptr, *ws2 = nullptr;
-    bool own_ws = false;
-    if (g.ws) {
-        if (g.ws_bytes < lay.total) return GREM_ERR_NOMEM;
-        ws = (char *)g.ws;
-    } else {
-        if (hipMallocAsync((void **)&ws, lay.total, stream) != hipSuccess) {
-            (void)hipGetLastError();
-            return GREM_ERR_NOMEM;
-        }
-        own_ws = true;
-    }
-    auto release = [&]() {
-        if (own_ws) (void)hipFreeAsync(ws, stream);
-        if (ws2) (void)hipFreeAsync(ws2, stream);
-    };
-
-    uint32_t *E = external_E ? estimates_out : (uint32_t *)(ws + lay.E);
-    LabelT *Lc = (LabelT *)(ws + lay.Lc);
-    LabelT *prop = (LabelT *)(ws + lay.prop);
-    long long *S = (long long *)(ws + lay.S);
-    uint32_t *cnt = (uint32_t *)(ws + lay.cnt);
-    uint32_t *tot = (uint32_t *)(ws + lay.tot);      // two-phase path: upper bounds of the chunk's movers per partition
-    long long *room = (long long *)(ws + lay.room);
-    uint32_t *ocnt = (uint32_t *)(ws + lay.ocnt);
-    int32_t *fillRank = (int32_t *)(ws + lay.fillRank);
-    long long *fillSorted = (long long *)(ws + lay.fillSorted);
-    long long *fillC = (long long *)(ws + lay.fillC);
-    unsigned long long *misc = (unsigned long long *)(ws + lay.misc);
-    uint32_t *long_cnt = (uint32_t *)(ws + lay.long_cnt);
-    uint32_t *long_list = (uint32_t *)(ws + lay.long_list);
-
-    Launcher L{stream};
-
-    // ---- prepass + the one validation read-back
-    if (hipMemsetAsync(S, 0, (size_t)k * 8, stream) != hipSuccess ||
-        hipMemsetAsync(misc, 0, 16 * 8, stream) != hipSuccess) { release(); return GREM_ERR_HIP; }
-    {
-        int64_t blocks = (n + 255) / 256;
-        if (blocks > 256 * 32) blocks = 256 * 32;
-        L.run(GREM_KERNEL_PREPASS, [&] {
-            hipLaunchKernelGGL((k_prepass<RowT, LabelT>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               rowptr, seed, n, (int)k, Lc, (unsigned long long *)S, misc);
-        });
-        L.run(GREM_KERNEL_PREPASS, [&] {
-            hipLaunchKernelGGL(k_check_seed_sizes, dim3((k + 255) / 256), dim3(256), 0, stream, S, (int)k,
-                               P, misc);
-        });
-    }
-    // plan of the two-phase path (needs only rowptr, so it runs before the read-back)
-    const int64_t nchunks = (n + chunk - 1) / chunk;
-    const int nsl = (int)slices_per_chunk(n, chunk);
-    bool sweep = false;
+// ======================================================================================================
+// The re-laid-out copy of a graph's entries (two-phase route)
+// ======================================================================================================
+struct PlanData {
+    const void *rowptr = nullptr;
+    int rowptr_bits = 0;
+    int64_t n = 0, nnz = 0;
+    int hub_degree = 0;
+    TpGeom geo;
     SweepPlan pl{};
-    if constexpr (sizeof(LabelT) == 1) {
-        const bool can = k <= kSweepMaxK && geo.ok && (((uintptr_t)E) & 15u) == 0;
-        if (hist_mode == GREM_HIST_SWEEP && !can) { release(); return GREM_ERR_ARG; }
-        sweep = can && (hist_mode == GREM_HIST_SWEEP ||
-                        (hist_mode == GREM_HIST_AUTO && n >= kSweepMinN && (int64_t)geo.chunk >= kSweepMinChunk));
-        if (sweep) {
-            pl.sl_reg_cnt = (uint32_t *)(ws + lay.sl_reg_cnt);
-            pl.sl_reg_start = (u64 *)(ws + lay.sl_reg_start);
-            pl.sl_nh = (uint32_t *)(ws + lay.sl_nh);
-            pl.sl_hub_start = (uint32_t *)(ws + lay.sl_hub_start);
-            pl.sl_hent = (u64 *)(ws + lay.sl_hent);
-            pl.sl_hent_start = (u64 *)(ws + lay.sl_hent_start);
-            pl.share_h0 = (uint32_t *)(ws + lay.share_h0);
-            pl.share_nhs = (uint32_t *)(ws + lay.share_nhs);
-            pl.ch_regtot = (u64 *)(ws + lay.ch_regtot);
-            pl.ch_nh = (uint32_t *)(ws + lay.ch_nh);
-            pl.ch_H = (u64 *)(ws + lay.ch_H);
-            pl.ch_nvs = (uint32_t *)(ws + lay.ch_nvs);
-            pl.ch_hbase = (u64 *)(ws + lay.ch_hbase);
-            pl.hub_row = (int32_t *)(ws + lay.hub_row);
-            pl.hub_off = (u64 *)(ws + lay.hub_off);
-            const unsigned G = (unsigned)(nchunks * nsl);
-            const int64_t cl = (int64_t)geo.chunk;
-            L.run(GREM_KERNEL_RELAYOUT, [&] {
-                hipLaunchKernelGGL((k_plan_slices<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, cl, nsl,
-                                   (uint32_t)hub_degree, pl);
-            });
-            L.run(GREM_KERNEL_RELAYOUT, [&] {
-                hipLaunchKernelGGL(k_plan_chunks, dim3((unsigned)nchunks), dim3(256), 0, stream, n, cl, nsl,
-                                   geo.nblk, pl, misc);
-            });
-            {
-                TpTables only_nch{};
-                only_nch.nch = geo.nch;
-                L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL(k_tp_scan_segments, dim3(1), dim3(1024), 0, stream, only_nch, pl.ch_hbase, 2);
-                });
-            }
-
-            L.run(GREM_KERNEL_RELAYOUT, [&] {
-                hipLaunchKernelGGL((k_plan_hubs<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, cl, nsl,
-                                   (uint32_t)hub_degree, pl);
-            });
-            L.run(GREM_KERNEL_RELAYOUT, [&] {
-                hipLaunchKernelGGL(k_plan_shares, dim3((G + 255) / 256), dim3(256), 0, stream, n, cl, nsl,
-                                   (int)G, pl, misc);
-            });
-        }
-    } else {
-        if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
-    }
-    if (L.err) { release(); return L.err; }
-    unsigned long long h_misc[16] = {0};
-    if (hipMemcpyAsync(h_misc, misc, sizeof(h_misc), hipMemcpyDeviceToHost, stream) != hipSuccess ||
-        hipStreamSynchronize(stream) != hipSuccess) { release(); return GREM_ERR_HIP; }
-    if (h_misc[1] != 0 || h_misc[2] != 0) { release(); return GREM_ERR_SEED; }
-    const unsigned long long maxdeg = h_misc[0];
-    const int64_t nnz = (int64_t)h_misc[3];
-    if (R >= 32 || (maxdeg << R) >= (1ull << 32)) { release(); return GREM_ERR_RANGE; }
-
-    // tile shape of the plain score kernels
-    int tv = kGlobalTile;
-    if (use_lds) {
-        tv = 256;
-        while (tv > 1 && (size_t)tv * k * 4 > (size_t)kLdsHistBytes) tv >>= 1;
-    }
-    if (maxdeg * (unsigned long long)tv >= (1ull << 31)) { release(); return GREM_ERR_RANGE; }
-    const size_t score_lds = use_lds ? ((size_t)tv * k + tv + 1 + k) * 4 : ((size_t)tv + 1 + k) * 4;
-    const size_t count_lds = (size_t)k * 4;
-    const size_t apply_lds = ((size_t)k + (size_t)(kAdmitThreads / 64) * k + 2 * (size_t)k) * 4;
-    const size_t fill_lds = (size_t)k * 4;
-
-    if (apply_lds > 64 * 1024 &&
-        (hipFuncSetAttribute((const void *)k_apply<LabelT, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)apply_lds) != hipSuccess ||
-         hipFuncSetAttribute((const void *)k_apply<LabelT, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)apply_lds) != hipSuccess)) { release(); return GREM_ERR_HIP; }
-
-    // ---- two-phase path: allocate its extras, re-lay-out the entries once
     TpTables tb{};
-    uint32_t *T = nullptr, *Hhub = nullptr;
-    uint16_t *Rw = nullptr, *Rdyn = nullptr, *E16 = nullptr;      // Rw: the tuples' row fields
-    uint32_t *Lx = nullptr;
-    // estimates of the regular rows of the two-phase path stay below hub_degree * 2^R: 16 bits when that fits
-    const bool use16 = (((unsigned long long)(hub_degree - 1)) << R) <= 65535ull;
-    size_t tp_score_lds = 0, tp_lookup_lds = 0;
-    const int share_hubs = (int)h_misc[5];
-    const size_t max_chunk_hubs = (size_t)h_misc[6];
-    int lookup_target = 256;                 // workgroups of one look-up launch
-    if constexpr (sizeof(LabelT) == 1) {
-        auto set_lds = [&](const void *f, size_t bytes) {
-            return bytes <= 64 * 1024 ||
-                   hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+    uint32_t *T = nullptr;
+    uint16_t *R = nullptr;
+    u64 *pmisc = nullptr;
+    size_t slots = 0;
+    unsigned long long maxdeg = 0, hub_entries = 0, total_hubs = 0, max_chunk_hubs = 0;
+    bool have_degrees = false;              // maxdeg and nnz have been read back
+    int share_hubs = 0;
+    int max_k = 0;                          // largest k whose score workgroups fit the LDS
+    size_t lookup_lds = 0;
+    int lookup_target = 512;
+};
+
+// Sizes of the plan's pieces as functions of what is known at each stage; the same functions serve the
+// real carve and the workspace bound.
+struct PlanDims {
+    int64_t n, nnz;
+    TpGeom geo;
+    size_t G;                       // slices of all chunks
+    size_t hubs;                    // hubs of all chunks (or a bound)
+    int npr, nps;
+    size_t slots;
+};
+
+size_t plan_slots(int64_t nnz, const TpGeom &geo) {
+    // every sub-segment is padded to a multiple of 4 tuples, every segment to a multiple of 8
+    const size_t segs = (size_t)geo.nch * (size_t)geo.nblk;
+    const size_t rows = (size_t)geo.nch * ((size_t)geo.nsl + 1);
+    return (size_t)(nnz > 0 ? nnz : 0) + 6 * rows * (size_t)geo.nblk + 8 * segs;
+}
+
+void plan_stage1(Carver &c, const PlanDims &d, SweepPlan &pl, u64 *&pmisc) {
+    const size_t nch = (size_t)d.geo.nch;
+    c.take(pl.sl_reg_cnt, d.G);
+    c.take(pl.sl_reg_start, d.G);
+    c.take(pl.sl_nh, d.G);
+    c.take(pl.sl_hub_start, d.G);
+    c.take(pl.sl_hent, d.G);
+    c.take(pl.sl_hent_start, d.G);
+    c.take(pl.sl_part_reg0, d.G * (size_t)kPlanParts);
+    c.take(pl.share_h0, d.G);
+    c.take(pl.share_nhs, d.G);
+    c.take(pl.ch_regtot, nch);
+    c.take(pl.ch_nh, nch);
+    c.take(pl.ch_H, nch);
+    c.take(pl.ch_nvs, nch);
+    c.take(pl.ch_hbase, nch + 1);
+    c.take(pl.ch_reg0, nch + 1);
+    c.take(pl.ch_hub0, nch + 1);
+    c.take(pmisc, 16);
+}
+
+void plan_stage2(Carver &c, const PlanDims &d, SweepPlan &pl) {
+    c.take(pl.hub_row, d.hubs + 1);
+    c.take(pl.hub_off, d.hubs + (size_t)d.geo.nch + 1);
+}
+
+void plan_stage3(Carver &c, const PlanDims &d, TpTables &tb, uint32_t *&T, uint16_t *&R) {
+    const size_t segs = (size_t)d.geo.nch * (size_t)d.geo.nblk;
+    const size_t rows = (size_t)d.geo.nch * ((size_t)d.geo.nsl + 1);
+    c.take(tb.subR, rows * (size_t)d.geo.nblk);
+    c.take(tb.subH, rows * (size_t)d.geo.nblk);
+    c.take(tb.xstart, segs + 1);
+    c.take(tb.tstart, segs + 1);
+    c.take(tb.lo, d.G * (size_t)d.npr * ((size_t)d.geo.ngroups + 1));
+    c.take(tb.loh, d.G * (size_t)d.nps * ((size_t)d.geo.ngroups + 1));
+    c.take(tb.ustart, d.G * (size_t)d.npr);
+    c.take(tb.ustart_h, d.G * (size_t)d.nps);
+    uint8_t *t8 = nullptr;
+    c.take(t8, d.slots * 3 + 16);            // column in block, 3 bytes per tuple
+    T = reinterpret_cast<uint32_t *>(t8);
+    c.take(R, d.slots + 8);                  // row field, 2 bytes per tuple
+}
+
+// Builds the plan for (rowptr, colidx, n, chunk) under `o`.  `keep` receives what the plan consists
+// of, `temp` the intermediate copy (given back before the function returns).  strict: a graph the
+// route cannot take is GREM_ERR_ARG; otherwise the function returns GREM_OK with P.T == nullptr and the
+// caller takes the plain route (P.maxdeg and P.nnz are valid once P.have_degrees is set).
+// k: the number of partitions of the run the plan is built for, or 0 for any k up to 16 (then
+// P.max_k says how far the plan reaches).
+template <typename RowT>
+int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n, int64_t chunk, int32_t k,
+               const Opts &o, Arena &keep, Arena &temp, Launcher &L, bool strict) {
+    hipStream_t stream = L.stream;
+    const TpGeom geo = tp_geometry(n, chunk, o.col_bits);
+    if (!geo.ok) return GREM_ERR_ARG;            // (callers check the geometry first)
+    const int hub_degree = o.hub_degree;
+    P.rowptr = rowptr;
+    P.rowptr_bits = (int)sizeof(RowT) * 8;
+    P.n = n;
+    P.hub_degree = hub_degree;
+    P.geo = geo;
+    PlanDims d{};
+    d.n = n;
+    d.geo = geo;
+    d.G = (size_t)geo.nch * (size_t)geo.nsl;
+    const int64_t cl = (int64_t)geo.chunk;
+    const int nsl = geo.nsl;
+    const unsigned G = (unsigned)d.G;
+    SweepPlan &pl = P.pl;
+    TpTables &tb = P.tb;
+
+    // ---- stage 1: per slice and per chunk, regular entries, hubs, hub entries, shares
+    if (!carve(keep, [&](Carver &c) { plan_stage1(c, d, pl, P.pmisc); })) return GREM_ERR_NOMEM;
+    L.memset(P.pmisc, 0, 16 * 8);
+    L.run(GREM_KERNEL_RELAYOUT, [&] {
+        hipLaunchKernelGGL((k_plan_slices<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, cl, nsl,
+                           (uint32_t)hub_degree, pl, P.pmisc);
+    });
+    L.run(GREM_KERNEL_RELAYOUT, [&] {
+        hipLaunchKernelGGL(k_plan_chunks, dim3((unsigned)geo.nch), dim3(256), 0, stream, n, cl, nsl, geo.nblk, pl,
+                           P.pmisc);
+    });
+    L.run(GREM_KERNEL_RELAYOUT, [&] {
+        hipLaunchKernelGGL(k_tp_scan, dim3(3), dim3(1024), 0, stream, pl.ch_hbase, (int64_t)geo.nch, pl.ch_reg0,
+                           (int64_t)geo.nch, pl.ch_hub0, (int64_t)geo.nch);
+    });
+    unsigned long long h[16] = {0};
+    if (!L.read_back(h, P.pmisc, sizeof(h))) return L.err;
+    P.maxdeg = h[0];
+    P.nnz = (int64_t)h[3];
+    P.have_degrees = true;
+    P.max_chunk_hubs = h[6];
+    P.hub_entries = h[8];
+    P.total_hubs = h[12];
+    d.nnz = P.nnz;
+    d.hubs = (size_t)P.total_hubs;
+
+    // ---- stage 2: the chunks' hub lists, the hubs every share touches
+    if (!carve(keep, [&](Carver &c) { plan_stage2(c, d, pl); })) return GREM_ERR_NOMEM;
+    L.run(GREM_KERNEL_RELAYOUT, [&] {
+        hipLaunchKernelGGL((k_plan_hubs<RowT>), dim3(G), dim3(256), 0, stream, rowptr, n, cl, nsl,
+                           (uint32_t)hub_degree, pl);
+    });
+    L.run(GREM_KERNEL_RELAYOUT, [&] {
+        hipLaunchKernelGGL(k_plan_shares, dim3((G + 255) / 256), dim3(256), 0, stream, n, cl, nsl, (int)G, pl,
+                           P.pmisc);
+    });
+    if (P.total_hubs != 0) {
+        if (!L.read_back(h, P.pmisc, sizeof(h))) return L.err;
+    } else if (L.err) {
+        return L.err;
+    }
+    const int share_hubs = (int)h[5];
+    P.share_hubs = share_hubs;
+
+    // ---- does the route fit?  A score workgroup's LDS (two per CU fit when a share touches few hubs);
+    // a share may touch kMaxShareHubs hubs; sub-segment offsets are 32-bit
+    {
+        auto score_fits = [&](int kk) {
+            const size_t score_lds = ((size_t)kSliceRows / 2 + (size_t)share_hubs * kk + 3 * (size_t)kk) * 4;
+            return score_lds + (size_t)kSliceRows * 32 <= 150 * 1024;
         };
-        if (sweep) {
-            lay = make_layout(n, nnz, (int64_t)h_misc[8], k, chunk, external_E, geo, hub_degree, seed != nullptr);
-            // (dynamic part: the 64 KB of counters are a static array of the kernel)
-            tp_score_lds = ((size_t)kSliceRows / 2 + (size_t)share_hubs * k + 3 * (size_t)k) * 4;
-            tp_lookup_lds = (size_t)1 << (geo.cb > 5 ? geo.cb - 1 : 4);
-            // a score workgroup must fit the 160 KB of LDS (two per CU do when a share touches few hubs);
-            // one share may touch kMaxShareHubs hubs; sub-segment offsets are 32-bit
-            const bool fits = tp_score_lds + (size_t)kSliceRows * 32 <= 150 * 1024 && share_hubs <= kMaxShareHubs &&
-                              max_chunk_hubs <= lay.hub_rows_cap &&
-                              h_misc[7] + 8ull * ((unsigned long long)geo.nsl + 2) * geo.nblk < (1ull << 32);
-            if (!fits) {
-                if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_ARG; }
-                sweep = false;
-            }
-        }
-        if (sweep) {
-            char *xbase = nullptr;
-            if (g.ws) {
-                if (g.ws_bytes >= lay.total_sweep) xbase = ws;
-                else if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_NOMEM; }
-                else sweep = false;
-            } else {
-                if (hipMallocAsync((void **)&ws2, lay.total_sweep - lay.total, stream) != hipSuccess) {
-                    (void)hipGetLastError();
-                    ws2 = nullptr;
-                    if (hist_mode == GREM_HIST_SWEEP) { release(); return GREM_ERR_NOMEM; }
-                    sweep = false;
-                } else {
-                    xbase = ws2 - lay.total;
-                }
-            }
-            if (sweep) {
-                tb.subR = (uint32_t *)(xbase + lay.subR);
-                tb.subH = (uint32_t *)(xbase + lay.subH);
-                tb.xstart = (u64 *)(xbase + lay.xstart);
-                tb.tstart = (u64 *)(xbase + lay.tstart);
-                tb.chunk = geo.chunk;
-                tb.chunk_shift = geo.shift;
-                {   // round-up magic number: exact for dividends below 2^31 (vertex ids are)
-                    uint32_t sh = 0;
-                    while ((1ull << sh) < geo.chunk) ++sh;
-                    tb.chunk_magic_shift = sh > 0 ? sh - 1 : 0;
-                    tb.chunk_magic = geo.chunk > 1
-                        ? (uint32_t)((((unsigned long long)1 << (32 + tb.chunk_magic_shift)) + geo.chunk - 1) / geo.chunk)
-                        : 0u;
-                    if (geo.chunk == 1) tb.chunk_shift = 0;
-                }
-                tb.nch = geo.nch;
-                tb.nsl = geo.nsl;
-                tb.nbc = geo.nbc;
-                tb.nblk = geo.nblk;
-                tb.cb = geo.cb;
-                Hhub = (uint32_t *)(xbase + lay.Hhub);
-                T = (uint32_t *)(xbase + lay.T);
-                Rw = (uint16_t *)(xbase + lay.R);
-                Lx = (uint32_t *)(xbase + lay.Lx);
-                Rdyn = seed ? (uint16_t *)(xbase + lay.Rdyn) : nullptr;
-                E16 = (uint16_t *)(xbase + lay.E16);
-                tb.gb = geo.gb;
-                tb.ngroups = geo.ngroups;
-                tb.lo = (uint32_t *)(xbase + lay.lo);
-                tb.loh = (uint32_t *)(xbase + lay.loh);
-                uint32_t *U = (uint32_t *)(xbase + lay.U);
-                uint32_t *Uh = (uint32_t *)(xbase + lay.Uh);
-                // step 1 collects a unit's tuples in LDS: cut the slices (shares) in as many parts as it
-                // takes for the largest to fit, two workgroups per CU
-                constexpr size_t kGroupLds = 79 * 1024, kPlaceLds = 52 * 1024;
-                auto group_fixed = [&](bool share, int np) {
-                    return (tp_source_words(share, np, share_hubs) + (size_t)geo.nblk + (size_t)geo.ngroups + 1 + kTpThreads / 64) * 4;
-                };
-                auto group_cap = [&](bool share, int np) {
-                    const size_t fixed = group_fixed(share, np);
-                    return (uint32_t)(kGroupLds > fixed ? (kGroupLds - fixed) / 4 : 0);
-                };
-                int npr = 1, nps = 1;
-                // ... and, if that takes no more than kMaxParts, so small that a thread holds its share of the
-                // unit's entries in registers (one round of kTpThreads * kTpBatch entries)
-                const unsigned long long one_round = (unsigned long long)kTpThreads * kTpBatch;
-                auto fits = [&](bool share, int np, unsigned long long most, bool in_regs) {
-                    const unsigned long long unit = most / np + most / (8ull * np) + 64;
-                    return group_cap(share, np) >= unit && (!in_regs || unit <= one_round);
-                };
-                while (npr < kMaxParts && !fits(false, npr, h_misc[9], false)) npr *= 2;
-                while (nps < kMaxParts && !fits(true, nps, h_misc[10], false)) nps += 1;
-                {
-                    // slices differ in size: it is the average one whose parts should take one round (the
-                    // larger ones take two, and their tuples still fit LDS)
-                    const unsigned long long avg_slice =
-                        ((unsigned long long)nnz - h_misc[8]) / (unsigned long long)(nchunks * nsl) + 1;
-                    int a = npr, b = nps;
-                    while (a < kMaxParts && !fits(false, a, avg_slice, true)) a *= 2;
-                    while (b < kMaxParts && !fits(true, b, h_misc[10], true)) b += 1;
-                    if (fits(false, a, avg_slice, true) && fits(false, a, h_misc[9], false)) npr = a;
-                    if (fits(true, b, h_misc[10], true)) nps = b;
-                }
-                tb.npr = npr;
-                tb.nps = nps;
-                const uint32_t capR = group_cap(false, npr), capS = group_cap(true, nps);
-                const size_t groupR_lds = group_fixed(false, npr) + (size_t)capR * 4;
-                const size_t groupS_lds = group_fixed(true, nps) + (size_t)capS * 4;
-                // step 2: up to 8 slices at a time
-                const int nbg = geo.nblk < (1 << geo.gb) ? geo.nblk : (1 << geo.gb);
-                int batch = 8192 / nbg;
-                if (batch > 8) batch = 8;
-                if (batch < 1) batch = 1;
-                const int maxruns = batch * (npr > nps ? npr : nps);
-                const size_t place_fixed = (2 * (size_t)nbg + maxruns) * 8 +
-                                           ((size_t)2 * maxruns + 1 + 2 * (size_t)nbg + 1 + (size_t)batch * nbg) * 4;
-                const uint32_t capP = (uint32_t)(kPlaceLds > place_fixed ? (kPlaceLds - place_fixed) / 4 : 0);
-                const size_t place_lds = place_fixed + (size_t)capP * 4;
-                const size_t rows = (size_t)geo.nch * ((size_t)geo.nsl + 1);
-                if (hipMemsetAsync(Hhub, 0, lay.hub_rows_cap * (size_t)k * 4, stream) != hipSuccess ||
-                    hipMemsetAsync(tb.subR, 0, rows * (size_t)geo.nblk * 4, stream) != hipSuccess ||
-                    hipMemsetAsync(tb.subH, 0, rows * (size_t)geo.nblk * 4, stream) != hipSuccess ||
-                    !set_lds((const void *)k_tp_group<RowT, false>, groupR_lds) ||
-                    !set_lds((const void *)k_tp_group<RowT, true>, groupS_lds) ||
-                    !set_lds((const void *)k_tp_place<RowT>, place_lds) ||
-                    !set_lds((const void *)k_tp_lookup<true, false>, tp_lookup_lds) ||
-                    !set_lds((const void *)k_tp_lookup<true, true>, tp_lookup_lds) ||
-                    !set_lds((const void *)k_tp_score<RowT, uint32_t>, tp_score_lds) ||
-                    !set_lds((const void *)k_tp_score<RowT, uint16_t>, tp_score_lds)) {
-                    release();
-                    return GREM_ERR_HIP;
-                }
-                lookup_target = tp_lookup_lds > 80 * 1024 ? 256 : 512;
-                const unsigned G = (unsigned)(nchunks * nsl);
-                const unsigned segs = (unsigned)((int64_t)geo.nch * geo.nblk);
-                L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_tp_group<RowT, false>), dim3(G * (unsigned)npr), dim3(kTpThreads),
-                                       groupR_lds, stream, rowptr, colidx, n, (uint32_t)hub_degree, pl, tb,
-                                       share_hubs, capR, (int)nsl, U);
-                });
-                // shares: no chunk has more than max_shares of them (none at all: nothing to launch)
-                const unsigned max_shares = (unsigned)h_misc[11];
-                if (max_shares != 0)
-                    L.run(GREM_KERNEL_RELAYOUT, [&] {
-                        hipLaunchKernelGGL((k_tp_group<RowT, true>),
-                                           dim3((unsigned)nchunks * max_shares * (unsigned)nps), dim3(kTpThreads),
-                                           groupS_lds, stream, rowptr, colidx, n, (uint32_t)hub_degree, pl, tb,
-                                           share_hubs, capS, (int)max_shares, Uh);
-                    });
-                L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL(k_tp_scan_slices, dim3((segs + 255) / 256), dim3(256), 0, stream, tb);
-                });
-                L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL(k_tp_scan_segments, dim3(2), dim3(1024), 0, stream, tb, pl.ch_hbase, 0);
-                });
-                L.run(GREM_KERNEL_RELAYOUT, [&] {
-                    hipLaunchKernelGGL((k_tp_place<RowT>), dim3((unsigned)((int64_t)geo.ngroups * geo.nch)),
-                                       dim3(kPlaceThreads), place_lds, stream, rowptr, n, pl, tb, U, Uh, T, Rw, batch,
-                                       capP);
-                });
-            }
+        int max_k = k ? k : kSweepMaxK;
+        while (max_k > 1 && !score_fits(max_k) && k == 0) --max_k;
+        P.max_k = max_k;
+        const bool fits = score_fits(max_k) && share_hubs <= kMaxShareHubs &&
+                          h[7] + 8ull * ((unsigned long long)geo.nsl + 2) * geo.nblk < (1ull << 32);
+        if (!fits) return strict ? GREM_ERR_ARG : GREM_OK;
+    }
+
+    // ---- stage 3: shapes of the re-layout kernels, then the tables and streams
+    // step 1 collects a unit's tuples in LDS: cut the slices (shares) in as many parts as it takes for
+    // the largest to fit, two workgroups per CU
+    constexpr size_t kGroupLds = 79 * 1024, kPlaceLds = 52 * 1024;
+    auto group_fixed = [&](bool share, int np) {
+        return (tp_source_words(share, np, share_hubs) + (size_t)geo.nblk + (size_t)geo.ngroups + 1 + kTpThreads / 64) * 4;
+    };
+    auto group_cap = [&](bool share, int np) {
+        const size_t fixed = group_fixed(share, np);
+        return (uint32_t)(kGroupLds > fixed ? (kGroupLds - fixed) / 4 : 0);
+    };
+    int npr = 1, nps = 1;
+    // ... and, if that takes no more than kMaxParts, so small that a thread holds its share of the unit's
+    // entries in registers (one round of kTpThreads * kTpBatch entries)
+    const unsigned long long one_round = (unsigned long long)kTpThreads * kTpBatch;
+    auto fits_unit = [&](bool share, int np, unsigned long long most, bool in_regs) {
+        const unsigned long long unit = most / np + most / (8ull * np) + 64;
+        return group_cap(share, np) >= unit && (!in_regs || unit <= one_round);
+    };
+    while (npr < kMaxParts && !fits_unit(false, npr, h[9], false)) npr *= 2;
+    while (nps < kMaxParts && !fits_unit(true, nps, h[10], false)) nps += 1;
+    {
+        // slices differ in size: it is the average one whose parts should take one round (the larger ones
+        // take two, and their tuples still fit LDS)
+        const unsigned long long avg_slice =
+            ((unsigned long long)P.nnz - P.hub_entries) / (unsigned long long)(d.G ? d.G : 1) + 1;
+        int a = npr, b = nps;
+        while (a < kMaxParts && !fits_unit(false, a, avg_slice, true)) a *= 2;
+        while (b < kMaxParts && !fits_unit(true, b, h[10], true)) b += 1;
+        if (fits_unit(false, a, avg_slice, true) && fits_unit(false, a, h[9], false)) npr = a;
+        if (fits_unit(true, b, h[10], true)) nps = b;
+    }
+    d.npr = npr;
+    d.nps = nps;
+    d.slots = plan_slots(P.nnz, geo);
+    P.slots = d.slots;
+    if (!carve(keep, [&](Carver &c) { plan_stage3(c, d, tb, P.T, P.R); })) { P.T = nullptr; return GREM_ERR_NOMEM; }
+    tb.chunk = geo.chunk;
+    tb.chunk_shift = geo.shift;
+    {   // round-up magic number: exact for dividends below 2^31 (vertex ids are)
+        uint32_t sh = 0;
+        while ((1ull << sh) < geo.chunk) ++sh;
+        tb.chunk_magic_shift = sh > 0 ? sh - 1 : 0;
+        tb.chunk_magic = geo.chunk > 1
+            ? (uint32_t)((((unsigned long long)1 << (32 + tb.chunk_magic_shift)) + geo.chunk - 1) / geo.chunk)
+            : 0u;
+        if (geo.chunk == 1) tb.chunk_shift = 0;
+    }
+    tb.nch = geo.nch;
+    tb.nsl = geo.nsl;
+    tb.nbc = geo.nbc;
+    tb.nblk = geo.nblk;
+    tb.cb = geo.cb;
+    tb.gb = geo.gb;
+    tb.ngroups = geo.ngroups;
+    tb.npr = npr;
+    tb.nps = nps;
+    P.lookup_lds = (size_t)1 << (geo.cb > 5 ? geo.cb - 1 : 4);
+    P.lookup_target = P.lookup_lds > 80 * 1024 ? 256 : 512;
+
+    const Arena::Mark tmark = temp.mark();
+    uint32_t *U = (uint32_t *)temp.alloc((size_t)(P.nnz > 0 ? P.nnz : 0) * 4 + 16);
+    if (!U) { P.T = nullptr; return GREM_ERR_NOMEM; }
+    const u64 hub_base = (u64)P.nnz - P.hub_entries;        // U: the regular entries, then the hub streams
+
+    const uint32_t capR = group_cap(false, npr), capS = group_cap(true, nps);
+    const size_t groupR_lds = group_fixed(false, npr) + (size_t)capR * 4;
+    const size_t groupS_lds = group_fixed(true, nps) + (size_t)capS * 4;
+    // step 2: up to 8 slices at a time
+    const int nbg = geo.nblk < (1 << geo.gb) ? geo.nblk : (1 << geo.gb);
+    int batch = 8192 / nbg;
+    if (batch > 8) batch = 8;
+    if (batch < 1) batch = 1;
+    const int maxruns = batch * (npr > nps ? npr : nps);
+    const size_t place_fixed = (2 * (size_t)nbg + maxruns) * 8 +
+                               ((size_t)2 * maxruns + 1 + 2 * (size_t)nbg + 1 + (size_t)batch * nbg) * 4;
+    const uint32_t capP = (uint32_t)(kPlaceLds > place_fixed ? (kPlaceLds - place_fixed) / 4 : 0);
+    const size_t place_lds = place_fixed + (size_t)capP * 4;
+    const size_t rows = (size_t)geo.nch * ((size_t)geo.nsl + 1);
+    L.memset(tb.subR, 0, rows * (size_t)geo.nblk * 4);
+    L.memset(tb.subH, 0, rows * (size_t)geo.nblk * 4);
+    if (L.err || !set_lds((const void *)k_tp_group<RowT, false>, groupR_lds) ||
+        !set_lds((const void *)k_tp_group<RowT, true>, groupS_lds) ||
+        !set_lds((const void *)k_tp_place, place_lds)) {
+        temp.release_to(tmark);
+        P.T = nullptr;
+        return GREM_ERR_HIP;
+    }
+    const unsigned segs = (unsigned)((int64_t)geo.nch * geo.nblk);
+    L.run(GREM_KERNEL_RELAYOUT, [&] {
+        hipLaunchKernelGGL((k_tp_group<RowT, false>), dim3(G * (unsigned)npr), dim3(kTpThreads), groupR_lds, stream,
+                           rowptr, colidx, n, (uint32_t)hub_degree, pl, tb, share_hubs, capR, (int)nsl, U, hub_base);
+    });
+    // shares: no chunk has more than max_shares of them (none at all: nothing to launch)
+    const unsigned max_shares = (unsigned)h[11];
+    if (max_shares != 0)
+        L.run(GREM_KERNEL_RELAYOUT, [&] {
+            hipLaunchKernelGGL((k_tp_group<RowT, true>), dim3((unsigned)geo.nch * max_shares * (unsigned)nps),
+                               dim3(kTpThreads), groupS_lds, stream, rowptr, colidx, n, (uint32_t)hub_degree, pl, tb,
+                               share_hubs, capS, (int)max_shares, U, hub_base);
+        });
+    L.run(GREM_KERNEL_RELAYOUT, [&] {
+        hipLaunchKernelGGL(k_tp_scan_slices, dim3((segs + 255) / 256), dim3(256), 0, stream, tb);
+    });
+    L.run(GREM_KERNEL_RELAYOUT, [&] {
+        hipLaunchKernelGGL(k_tp_scan, dim3(2), dim3(1024), 0, stream, tb.xstart, (int64_t)segs, tb.tstart, (int64_t)segs,
+                           (u64 *)nullptr, (int64_t)0);
+    });
+    L.run(GREM_KERNEL_RELAYOUT, [&] {
+        hipLaunchKernelGGL(k_tp_place, dim3((unsigned)((int64_t)geo.ngroups * geo.nch)), dim3(kPlaceThreads), place_lds,
+                           stream, n, pl, tb, U, P.T, P.R, batch, capP);
+    });
+    temp.release_to(tmark);
+    if (L.err) { P.T = nullptr; return L.err; }
+    return GREM_OK;
+}
+
+// ======================================================================================================
+// State of one run (Alg. 1's parts, sizes, nbr_counts and the admission tables)
+// ======================================================================================================
+template <typename LabelT> struct CallState {
+    LabelT *Lc = nullptr, *prop = nullptr;
+    long long *S = nullptr, *room = nullptr, *fillSorted = nullptr, *fillC = nullptr;
+    uint32_t *cnt = nullptr, *tot = nullptr, *ocnt = nullptr;
+    int32_t *fillRank = nullptr;
+    unsigned long long *misc = nullptr;
+};
+
+template <typename LabelT>
+void state_common(Carver &c, CallState<LabelT> &st, int64_t n, int64_t cl, int32_t k) {
+    const size_t ntiles = (size_t)((cl + kAdmitTile - 1) / kAdmitTile);
+    c.take(st.Lc, (size_t)n);
+    c.take(st.prop, (size_t)cl);
+    c.take(st.S, (size_t)k);
+    c.take(st.cnt, ntiles * (size_t)k);
+    c.take(st.tot, 2 * (size_t)k);
+    c.take(st.room, (size_t)k);
+    c.take(st.ocnt, ntiles);
+    c.take(st.fillRank, (size_t)k);
+    c.take(st.fillSorted, (size_t)k);
+    c.take(st.fillC, (size_t)k + 1);
+    c.take(st.misc, 16);
+}
+
+// prepass: compact labels and sizes from the seed, its validity; with rowptr also the largest degree
+template <typename RowT, typename LabelT>
+void launch_prepass(Launcher &L, const RowT *rowptr_or_null, const int32_t *seed, int64_t n, int32_t k, long long P,
+                    CallState<LabelT> &st) {
+    hipStream_t stream = L.stream;
+    L.memset(st.S, 0, (size_t)k * 8);
+    L.memset(st.misc, 0, 16 * 8);
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    L.run(GREM_KERNEL_PREPASS, [&] {
+        hipLaunchKernelGGL((k_prepass<RowT, LabelT>), dim3((unsigned)blocks), dim3(256), 0, stream, rowptr_or_null, seed,
+                           n, (int)k, st.Lc, (unsigned long long *)st.S, st.misc);
+    });
+    if (seed)
+        L.run(GREM_KERNEL_PREPASS, [&] {
+            hipLaunchKernelGGL(k_check_seed_sizes, dim3((k + 255) / 256), dim3(256), 0, stream, st.S, (int)k, P, st.misc);
+        });
+}
+
+template <typename LabelT>
+void launch_spill(Launcher &L, CallState<LabelT> &st, int64_t lo, int64_t hi, int32_t k, unsigned admit_blocks) {
+    hipStream_t stream = L.stream;
+    L.run(GREM_KERNEL_SPILL_SCAN, [&] {
+        hipLaunchKernelGGL(k_spill_scan, dim3(1), dim3(kScanThreads), 0, stream, st.ocnt, (int)admit_blocks, (int)k, st.S,
+                           st.fillRank, st.fillSorted, st.fillC, st.misc);
+    });
+    L.run(GREM_KERNEL_SPILL_FILL, [&] {
+        hipLaunchKernelGGL((k_spill_fill<LabelT>), dim3(admit_blocks), dim3(kAdmitThreads), (size_t)k * 4, stream, st.Lc, lo,
+                           hi, (int)k, st.ocnt, st.fillRank, st.fillC, (unsigned long long *)st.S, st.misc);
+    });
+}
+
+template <typename LabelT>
+void launch_outputs(Launcher &L, CallState<LabelT> &st, int64_t n, int32_t k, int32_t *labels_out, int64_t *sizes_out) {
+    hipStream_t stream = L.stream;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    L.run(GREM_KERNEL_EXPAND, [&] {
+        hipLaunchKernelGGL((k_expand<LabelT>), dim3((unsigned)blocks), dim3(256), 0, stream, st.Lc, n, labels_out);
+    });
+    if (sizes_out)
+        L.run(GREM_KERNEL_EXPAND, [&] {
+            hipLaunchKernelGGL(k_copy_sizes, dim3((k + 255) / 256), dim3(256), 0, stream, st.S, (int)k, sizes_out);
+        });
+}
+
+// ---- two-phase route: per-call arrays beside the common state ---------------------------------------
+struct TpState {
+    uint32_t *Lx = nullptr, *Hhub = nullptr, *E32 = nullptr, *Ehub = nullptr;
+    uint16_t *Rdyn = nullptr, *E16 = nullptr;
+};
+
+void state_two_phase(Carver &c, TpState &t, int64_t n, int32_t k, size_t slots, size_t max_chunk_hubs, size_t total_hubs,
+                     bool seeded, bool use16, bool external_E) {
+    uint8_t *lx = nullptr;
+    c.take(lx, slots / 2 + 16);                                   // label, 4 bits per tuple
+    t.Lx = reinterpret_cast<uint32_t *>(lx);
+    c.take(t.Hhub, (max_chunk_hubs + 1) * (size_t)k);
+    c.take(t.Rdyn, seeded ? slots + 8 : 0);                       // seeded runs: R with the unassigned neighbours marked
+    c.take(t.E16, use16 ? (size_t)n * (size_t)k : 0);
+    c.take(t.E32, (!use16 && !external_E) ? (size_t)n * (size_t)k : 0);
+    c.take(t.Ehub, (use16 && !external_E) ? (total_hubs + 1) * (size_t)k : 0);
+}
+
+// Alg. 1's loop on a plan.  `prepared`: the common state with the prepass run and the seed validated by
+// the caller; otherwise this function does both (one read-back when there is a seed).
+template <typename RowT>
+int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const int32_t *seed, int32_t *labels_out,
+                  int64_t *sizes_out, uint32_t *estimates_out, Arena &mem, Launcher &L, CallState<uint8_t> *prepared) {
+    hipStream_t stream = L.stream;
+    const RowT *rowptr = (const RowT *)P.rowptr;
+    const int64_t n = P.n;
+    const TpGeom &geo = P.geo;
+    const TpTables &tb = P.tb;
+    const SweepPlan &pl = P.pl;
+    const int64_t cl = (int64_t)geo.chunk;
+    const long long cap = grem_capacity(n, k, slack);
+    const bool external_E = estimates_out != nullptr;
+    const int hub_degree = P.hub_degree;
+    if (R >= 32 || (P.maxdeg << R) >= (1ull << 32)) return GREM_ERR_RANGE;
+    if (external_E && (((uintptr_t)estimates_out) & 15u) != 0) return GREM_ERR_ARG;
+    // estimates of the regular rows stay below hub_degree * 2^R: 16 bits when that fits
+    const bool use16 = (((unsigned long long)(hub_degree - 1)) << R) <= 65535ull;
+
+    CallState<uint8_t> st;
+    if (prepared) {
+        st = *prepared;
+    } else {
+        if (!carve(mem, [&](Carver &c) { state_common(c, st, n, cl, k); })) return GREM_ERR_NOMEM;
+    }
+    TpState t;
+    if (!carve(mem, [&](Carver &c) {
+            state_two_phase(c, t, n, k, P.slots, (size_t)P.max_chunk_hubs, (size_t)P.total_hubs, seed != nullptr, use16,
+                            external_E);
+        }))
+        return GREM_ERR_NOMEM;
+    if (!prepared) {
+        launch_prepass<RowT, uint8_t>(L, (const RowT *)nullptr, seed, n, k, cap, st);
+        if (seed) {
+            unsigned long long h[16] = {0};
+            if (!L.read_back(h, st.misc, sizeof(h))) return L.err;
+            if (h[1] != 0 || h[2] != 0) return GREM_ERR_SEED;
         }
     }
+    uint32_t *E32 = external_E ? estimates_out : t.E32;
+    uint32_t *Ehub_rows = (use16 && !external_E) ? nullptr : E32;    // hubs: rows of E32 when there is one, else Ehub
+    const size_t score_lds = ((size_t)kSliceRows / 2 + (size_t)P.share_hubs * k + 3 * (size_t)k) * 4;
+    if (!set_lds((const void *)k_tp_lookup<true, false>, P.lookup_lds) ||
+        !set_lds((const void *)k_tp_lookup<true, true>, P.lookup_lds) ||
+        !set_lds((const void *)k_tp_score<RowT, uint32_t>, score_lds) ||
+        !set_lds((const void *)k_tp_score<RowT, uint16_t>, score_lds))
+        return GREM_ERR_HIP;
+    L.memset(t.Hhub, 0, ((size_t)P.max_chunk_hubs + 1) * (size_t)k * 4);
 
     // look-ups of the labels of chunks [c0, c0 + count): shares per column block sized so that one
     // launch fills the chip without cutting the blocks' streams into crumbs
     // `mark`: seeded runs, first pass: the row fields the score kernels read are those of Rdyn, where
-    // bit 15 also marks the tuples whose neighbour is unassigned (set by the initial look-up from global
+    // bit 0 also marks the tuples whose neighbour is unassigned (set by the initial look-up from global
     // memory, cleared by the look-up of the neighbour's chunk)
     auto lookup = [&](int c0, int count, int cmin, bool from_lds, bool mark) {
-        if constexpr (sizeof(LabelT) == 1) {
-            if (cmin >= geo.nch) return;
-            const int64_t per_block = nnz / geo.nblk + 1;
-            int spb = lookup_target / geo.nbc;
-            const int64_t by_work = per_block / 8192 + 1;
-            if (spb > by_work) spb = (int)by_work;
-            if (spb < 1) spb = 1;
-            const dim3 grid((unsigned)(geo.nbc * spb), (unsigned)count);
-            L.run(GREM_KERNEL_LOOKUP, [&] {
-                if (!from_lds)
-                    hipLaunchKernelGGL((k_tp_lookup<false, true>), grid, dim3(kTpThreads), 0, stream, T, Lx, Rw, Rdyn,
-                                       tb, (const uint8_t *)Lc, n, c0, cmin, spb);
-                else if (mark)
-                    hipLaunchKernelGGL((k_tp_lookup<true, true>), grid, dim3(kTpThreads), tp_lookup_lds, stream, T,
-                                       Lx, Rw, Rdyn, tb, (const uint8_t *)Lc, n, c0, cmin, spb);
-                else
-                    hipLaunchKernelGGL((k_tp_lookup<true, false>), grid, dim3(kTpThreads), tp_lookup_lds, stream, T,
-                                       Lx, Rw, Rdyn, tb, (const uint8_t *)Lc, n, c0, cmin, spb);
-            });
-        }
+        if (cmin >= geo.nch) return;
+        const int64_t per_block = P.nnz / geo.nblk + 1;
+        int spb = P.lookup_target / geo.nbc;
+        const int64_t by_work = per_block / 8192 + 1;
+        if (spb > by_work) spb = (int)by_work;
+        if (spb < 1) spb = 1;
+        const dim3 grid((unsigned)(geo.nbc * spb), (unsigned)count);
+        L.run(GREM_KERNEL_LOOKUP, [&] {
+            if (!from_lds)
+                hipLaunchKernelGGL((k_tp_lookup<false, true>), grid, dim3(kTpThreads), 0, stream, P.T, t.Lx, P.R, t.Rdyn,
+                                   tb, (const uint8_t *)st.Lc, n, c0, cmin, spb);
+            else if (mark)
+                hipLaunchKernelGGL((k_tp_lookup<true, true>), grid, dim3(kTpThreads), P.lookup_lds, stream, P.T, t.Lx,
+                                   P.R, t.Rdyn, tb, (const uint8_t *)st.Lc, n, c0, cmin, spb);
+            else
+                hipLaunchKernelGGL((k_tp_lookup<true, false>), grid, dim3(kTpThreads), P.lookup_lds, stream, P.T, t.Lx,
+                                   P.R, t.Rdyn, tb, (const uint8_t *)st.Lc, n, c0, cmin, spb);
+        });
     };
-    if (sweep && seed) {        // the seeds are the labels every first-pass look-up starts from
+    if (seed) {        // the seeds are the labels every first-pass look-up starts from
         for (int c0 = 0; c0 < geo.nch; c0 += 32768) {
             const int count = geo.nch - c0 < 32768 ? geo.nch - c0 : 32768;
             lookup(c0, count, 0, false, true);
         }
     }
-
-    // plain score kernels: rows this long are taken out of their tile and spread over a grid of their own
-    const bool split_long = !sweep && maxdeg >= (unsigned long long)g.long_row_degree;
-    const size_t long_lds = (size_t)k * 4;
-    if (split_long && long_lds > 64 * 1024 &&
-        hipFuncSetAttribute((const void *)k_long_rows<RowT, LabelT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)long_lds) != hipSuccess) { release(); return GREM_ERR_HIP; }
-
+    L.mark();
+    const size_t max_chunk_hubs = (size_t)P.max_chunk_hubs;
     for (int pass = 0; pass <= R && !L.err; ++pass) {
-        if (split_long && hipMemsetAsync(long_cnt, 0, (size_t)nchunks * 4, stream) != hipSuccess) {
-            release();
-            return GREM_ERR_HIP;
-        }
-        for (int64_t c = 0; c < nchunks && !L.err; ++c) {
-            const int64_t lo = c * chunk;
-            const int64_t hi = (lo + chunk < n) ? lo + chunk : n;
+        for (int64_t c = 0; c < geo.nch && !L.err; ++c) {
+            const int64_t lo = c * cl;
+            const int64_t hi = (lo + cl < n) ? lo + cl : n;
             const int64_t len = hi - lo;
-            const int64_t gather_limit = (pass == 0 && !seed) ? lo : n;
             const unsigned admit_blocks = (unsigned)((len + kAdmitTile - 1) / kAdmitTile);
-            if (sweep) {
-                if constexpr (sizeof(LabelT) == 1) {
-                    const unsigned blocks = (unsigned)((len + kSliceRows - 1) / kSliceRows);
-                    const int jlim = (pass == 0 && !seed) ? (int)c * geo.nbc : geo.nblk;
-                    // the estimates are state between passes and, if the caller asked for them, output:
-                    // the last pass does not store them otherwise
-                    const int store_e = (pass < R || external_E) ? 1 : 0;
-                    const uint16_t *rows_now = (seed && pass == 0) ? Rdyn : Rw;
-                    L.run(GREM_KERNEL_SCORE, [&] {
-                        if (use16)
-                            hipLaunchKernelGGL((k_tp_score<RowT, uint16_t>), dim3(blocks), dim3(kTpThreads),
-                                               tp_score_lds, stream, rowptr, rows_now, Lx, tb, pl, (const uint8_t *)Lc, S, E16,
-                                               Hhub, (uint8_t *)prop, cnt, room, (int)c, lo, hi, (int)k, jlim,
-                                               share_hubs, (uint32_t)hub_degree, pass, P, store_e);
-                        else
-                            hipLaunchKernelGGL((k_tp_score<RowT, uint32_t>), dim3(blocks), dim3(kTpThreads),
-                                               tp_score_lds, stream, rowptr, rows_now, Lx, tb, pl, (const uint8_t *)Lc, S, E,
-                                               Hhub, (uint8_t *)prop, cnt, room, (int)c, lo, hi, (int)k, jlim,
-                                               share_hubs, (uint32_t)hub_degree, pass, P, store_e);
-                    });
-                    // (one workgroup more than the hubs need: it adds up the chunk's mover counts)
-                    L.run(GREM_KERNEL_HUBS, [&] {
-                        hipLaunchKernelGGL(k_hub_finalize, dim3((unsigned)((max_chunk_hubs + 15) / 16) + 1),
-                                           dim3(256), 0, stream, pl, (const uint8_t *)Lc, room, E, Hhub,
-                                           (uint8_t *)prop, cnt, (int)c, lo, (int)k, pass, store_e,
-                                           (int)admit_blocks, tot);
-                    });
-                }
-            } else {
-                const LongRows lr{split_long ? (uint32_t)g.long_row_degree : 0xFFFFFFFFu, kLongRowPart,
-                                  long_cnt + c, long_list};
-                const unsigned score_blocks = (unsigned)((len + tv - 1) / tv);
-                L.run(GREM_KERNEL_SCORE, [&] {
-                    if (use_lds)
-                        hipLaunchKernelGGL((k_score_lds<RowT, LabelT>), dim3(score_blocks),
-                                           dim3(kScoreThreads), score_lds, stream, rowptr, colidx, Lc, S, E,
-                                           prop, lo, hi, (int)k, tv, pass, P, gather_limit, lr);
-                    else
-                        hipLaunchKernelGGL((k_score_global<RowT, LabelT>), dim3(score_blocks),
-                                           dim3(kScoreThreads), score_lds, stream, rowptr, colidx, Lc, S, E,
-                                           prop, lo, hi, (int)k, pass, P, gather_limit, lr);
-                });
-                if (split_long) {
-                    L.run(GREM_KERNEL_HUBS, [&] {
-                        hipLaunchKernelGGL((k_long_rows<RowT, LabelT>), dim3(kLongRowGrid), dim3(kScoreThreads),
-                                           long_lds, stream, rowptr, colidx, Lc, E, (int)k, pass, gather_limit, lr);
-                    });
-                    L.run(GREM_KERNEL_HUBS, [&] {
-                        hipLaunchKernelGGL((k_long_propose<LabelT>), dim3(64), dim3(64), 0, stream, Lc, S, E, prop,
-                                           lo, (int)k, pass, P, lr);
-                    });
-                }
-            }
-            // admission: per-tile mover counts, their prefix over the tiles, ranks.  The two-phase score
-            // kernel has already counted the movers and taken the sizes' snapshot, and its tiles are few
-            // enough per partition that every k_apply workgroup adds up the earlier tiles' counts itself.
-            if (!sweep) {
-                L.run(GREM_KERNEL_COUNT, [&] {
-                    hipLaunchKernelGGL((k_count<LabelT>), dim3(admit_blocks), dim3(kAdmitThreads), count_lds,
-                                       stream, Lc, prop, lo, hi, (int)k, cnt);
-                });
-                L.run(GREM_KERNEL_SCAN, [&] {
-                    hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), 0, stream, cnt, (int)admit_blocks,
-                                       (int)k, S, P, room);
-                });
-                L.run(GREM_KERNEL_APPLY, [&] {
-                    hipLaunchKernelGGL((k_apply<LabelT, false>), dim3(admit_blocks), dim3(kAdmitThreads),
-                                       apply_lds, stream, Lc, prop, lo, hi, (int)k, cnt, room,
-                                       (unsigned long long *)S, ocnt, pass);
-                });
-            } else {
-                if constexpr (sizeof(LabelT) == 1) {
-                    L.run(GREM_KERNEL_APPLY, [&] {
-                        hipLaunchKernelGGL(k_apply16, dim3((admit_blocks + kApply16Tiles - 1) / kApply16Tiles), dim3(kAdmitTile), 0, stream,
-                                           (uint8_t *)Lc, (const uint8_t *)prop, lo, hi, (int)k, cnt, room,
-                                           tot, (unsigned long long *)S, ocnt, pass);
-                    });
-                }
-            }
-            if (pass == 0) {
-                L.run(GREM_KERNEL_SPILL_SCAN, [&] {
-                    hipLaunchKernelGGL(k_spill_scan, dim3(1), dim3(kScanThreads), 0, stream, ocnt,
-                                       (int)admit_blocks, (int)k, S, fillRank, fillSorted, fillC, misc);
-                });
-                L.run(GREM_KERNEL_SPILL_FILL, [&] {
-                    hipLaunchKernelGGL((k_spill_fill<LabelT>), dim3(admit_blocks), dim3(kAdmitThreads),
-                                       fill_lds, stream, Lc, lo, hi, (int)k, ocnt, fillRank, fillC,
-                                       (unsigned long long *)S, misc);
-                });
-            }
-            // the chunk's new labels, looked up for every row that will read them: rows of later
-            // chunks in this pass, rows of this and earlier chunks in the next pass (if there is one)
-            if (sweep) lookup((int)c, 1, pass == R ? (int)c + 1 : 0, true, seed != nullptr && pass == 0);
+            const unsigned blocks = (unsigned)((len + kSliceRows - 1) / kSliceRows);
+            const int jlim = (pass == 0 && !seed) ? (int)c * geo.nbc : geo.nblk;
+            // the estimates are state between passes and, if the caller asked for them, output: the last
+            // pass does not store them otherwise
+            const int store_e = (pass < R || external_E) ? 1 : 0;
+            const uint16_t *rows_now = (seed && pass == 0) ? t.Rdyn : P.R;
+            L.run(GREM_KERNEL_SCORE, [&] {
+                if (use16)
+                    hipLaunchKernelGGL((k_tp_score<RowT, uint16_t>), dim3(blocks), dim3(kTpThreads), score_lds, stream,
+                                       rowptr, rows_now, t.Lx, tb, pl, (const uint8_t *)st.Lc, st.S, t.E16, t.Hhub,
+                                       (uint8_t *)st.prop, st.cnt, st.room, (int)c, lo, hi, (int)k, jlim, P.share_hubs,
+                                       (uint32_t)hub_degree, pass, cap, store_e);
+                else
+                    hipLaunchKernelGGL((k_tp_score<RowT, uint32_t>), dim3(blocks), dim3(kTpThreads), score_lds, stream,
+                                       rowptr, rows_now, t.Lx, tb, pl, (const uint8_t *)st.Lc, st.S, E32, t.Hhub,
+                                       (uint8_t *)st.prop, st.cnt, st.room, (int)c, lo, hi, (int)k, jlim, P.share_hubs,
+                                       (uint32_t)hub_degree, pass, cap, store_e);
+            });
+            // (one workgroup more than the hubs need: it adds up the chunk's mover counts)
+            L.run(GREM_KERNEL_HUBS, [&] {
+                hipLaunchKernelGGL(k_hub_finalize, dim3((unsigned)((max_chunk_hubs + 15) / 16) + 1), dim3(256), 0, stream,
+                                   pl, (const uint8_t *)st.Lc, st.room, Ehub_rows, t.Ehub, t.Hhub, (uint8_t *)st.prop,
+                                   st.cnt, (int)c, lo, (int)k, pass, store_e, (int)admit_blocks, st.tot);
+            });
+            // admission: the score kernel has counted the movers per tile and taken the sizes' snapshot, and
+            // the tiles are few enough that every workgroup adds up the earlier tiles' counts itself
+            L.run(GREM_KERNEL_APPLY, [&] {
+                hipLaunchKernelGGL(k_apply16, dim3((admit_blocks + kApply16Tiles - 1) / kApply16Tiles), dim3(kAdmitTile), 0,
+                                   stream, (uint8_t *)st.Lc, (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room,
+                                   st.tot, (unsigned long long *)st.S, st.ocnt, pass);
+            });
+            if (pass == 0) launch_spill<uint8_t>(L, st, lo, hi, k, admit_blocks);
+            // the chunk's new labels, looked up for every row that will read them: rows of later chunks in
+            // this pass, rows of this and earlier chunks in the next pass (if there is one)
+            lookup((int)c, 1, pass == R ? (int)c + 1 : 0, true, seed != nullptr && pass == 0);
         }
+        L.mark();
     }
-    {
+    launch_outputs<uint8_t>(L, st, n, k, labels_out, sizes_out);
+    if (use16 && external_E) {
         int64_t blocks = (n + 255) / 256;
         if (blocks > 256 * 32) blocks = 256 * 32;
         L.run(GREM_KERNEL_EXPAND, [&] {
-            hipLaunchKernelGGL((k_expand<LabelT>), dim3((unsigned)blocks), dim3(256), 0, stream, Lc, n,
-                               labels_out);
+            hipLaunchKernelGGL((k_expand_estimates<RowT>), dim3((unsigned)blocks), dim3(256), 0, stream, rowptr, n, (int)k,
+                               (uint32_t)hub_degree, t.E16, estimates_out);
         });
-        if constexpr (sizeof(LabelT) == 1) {
-            if (sweep && use16 && external_E)
-                L.run(GREM_KERNEL_EXPAND, [&] {
-                    hipLaunchKernelGGL((k_expand_estimates<RowT>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                                       rowptr, n, (int)k, (uint32_t)hub_degree, E16, estimates_out);
-                });
-        }
-        if (sizes_out)
-            L.run(GREM_KERNEL_EXPAND, [&] {
-                hipLaunchKernelGGL(k_copy_sizes, dim3((k + 255) / 256), dim3(256), 0, stream, S, (int)k,
-                                   sizes_out);
-            });
     }
-    release();
+    L.mark();
     return L.err;
+}
+
+// ---- plain route ------------------------------------------------------------------------------------
+struct PlainExtra {
+    uint32_t *E = nullptr, *long_cnt = nullptr, *long_list = nullptr;
+};
+
+void state_plain(Carver &c, PlainExtra &x, int64_t n, int64_t cl, int32_t k, int64_t nchunks, bool external_E) {
+    c.take(x.E, external_E ? 0 : (size_t)n * (size_t)k);
+    c.take(x.long_cnt, (size_t)nchunks);
+    c.take(x.long_list, (size_t)cl);
+}
+
+// Alg. 1's loop straight on the CSR.  `st` is prepared (prepass run, seed and degrees validated).
+template <typename RowT, typename LabelT>
+int run_plain(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t k, double slack, int64_t cl, int32_t R,
+              const int32_t *seed, int32_t *labels_out, int64_t *sizes_out, uint32_t *estimates_out, const Opts &o,
+              unsigned long long maxdeg, Arena &mem, Launcher &L, CallState<LabelT> &st) {
+    hipStream_t stream = L.stream;
+    const long long P = grem_capacity(n, k, slack);
+    const bool external_E = estimates_out != nullptr;
+    const int64_t nchunks = (n + cl - 1) / cl;
+    const bool use_lds = o.hist_mode != GREM_HIST_GLOBAL && k <= kLdsMaxK;
+    PlainExtra x;
+    if (!carve(mem, [&](Carver &c) { state_plain(c, x, n, cl, k, nchunks, external_E); })) return GREM_ERR_NOMEM;
+    uint32_t *E = external_E ? estimates_out : x.E;
+
+    // tile shape of the score kernels
+    int tv = kGlobalTile;
+    if (use_lds) {
+        tv = 256;
+        while (tv > 1 && (size_t)tv * k * 4 > (size_t)kLdsHistBytes) tv >>= 1;
+    }
+    if (maxdeg * (unsigned long long)tv >= (1ull << 31)) return GREM_ERR_RANGE;
+    const size_t score_lds = use_lds ? ((size_t)tv * k + tv + 1 + k) * 4 : ((size_t)tv + 1 + k) * 4;
+    const size_t count_lds = (size_t)k * 4;
+    const size_t apply_lds = ((size_t)k + (size_t)(kAdmitThreads / 64) * k + 2 * (size_t)k) * 4;
+    if (!set_lds((const void *)k_apply<LabelT, false>, apply_lds)) return GREM_ERR_HIP;
+
+    // rows this long are taken out of their tile and spread over a grid of their own
+    const bool split_long = maxdeg >= (unsigned long long)o.long_row_degree;
+    const size_t long_lds = (size_t)k * 4;
+    if (split_long && !set_lds((const void *)k_long_rows<RowT, LabelT>, long_lds)) return GREM_ERR_HIP;
+
+    L.mark();
+    for (int pass = 0; pass <= R && !L.err; ++pass) {
+        if (split_long) L.memset(x.long_cnt, 0, (size_t)nchunks * 4);
+        for (int64_t c = 0; c < nchunks && !L.err; ++c) {
+            const int64_t lo = c * cl;
+            const int64_t hi = (lo + cl < n) ? lo + cl : n;
+            const int64_t len = hi - lo;
+            const int64_t gather_limit = (pass == 0 && !seed) ? lo : n;
+            const unsigned admit_blocks = (unsigned)((len + kAdmitTile - 1) / kAdmitTile);
+            const LongRows lr{split_long ? (uint32_t)o.long_row_degree : 0xFFFFFFFFu, kLongRowPart, x.long_cnt + c,
+                              x.long_list};
+            const unsigned score_blocks = (unsigned)((len + tv - 1) / tv);
+            L.run(GREM_KERNEL_SCORE, [&] {
+                if (use_lds)
+                    hipLaunchKernelGGL((k_score_lds<RowT, LabelT>), dim3(score_blocks), dim3(kScoreThreads), score_lds,
+                                       stream, rowptr, colidx, st.Lc, st.S, E, st.prop, lo, hi, (int)k, tv, pass, P,
+                                       gather_limit, lr);
+                else
+                    hipLaunchKernelGGL((k_score_global<RowT, LabelT>), dim3(score_blocks), dim3(kScoreThreads), score_lds,
+                                       stream, rowptr, colidx, st.Lc, st.S, E, st.prop, lo, hi, (int)k, pass, P,
+                                       gather_limit, lr);
+            });
+            if (split_long) {
+                L.run(GREM_KERNEL_HUBS, [&] {
+                    hipLaunchKernelGGL((k_long_rows<RowT, LabelT>), dim3(kLongRowGrid), dim3(kScoreThreads), long_lds, stream,
+                                       rowptr, colidx, st.Lc, E, (int)k, pass, gather_limit, lr);
+                });
+                L.run(GREM_KERNEL_HUBS, [&] {
+                    hipLaunchKernelGGL((k_long_propose<LabelT>), dim3(64), dim3(64), 0, stream, st.Lc, st.S, E, st.prop, lo,
+                                       (int)k, pass, P, lr);
+                });
+            }
+            // admission: per-tile mover counts, their prefix over the tiles, ranks
+            L.run(GREM_KERNEL_COUNT, [&] {
+                hipLaunchKernelGGL((k_count<LabelT>), dim3(admit_blocks), dim3(kAdmitThreads), count_lds, stream, st.Lc,
+                                   st.prop, lo, hi, (int)k, st.cnt);
+            });
+            L.run(GREM_KERNEL_SCAN, [&] {
+                hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), 0, stream, st.cnt, (int)admit_blocks, (int)k, st.S,
+                                   P, st.room);
+            });
+            L.run(GREM_KERNEL_APPLY, [&] {
+                hipLaunchKernelGGL((k_apply<LabelT, false>), dim3(admit_blocks), dim3(kAdmitThreads), apply_lds, stream,
+                                   st.Lc, st.prop, lo, hi, (int)k, st.cnt, st.room, (unsigned long long *)st.S, st.ocnt,
+                                   pass);
+            });
+            if (pass == 0) launch_spill<LabelT>(L, st, lo, hi, k, admit_blocks);
+        }
+        L.mark();
+    }
+    launch_outputs<LabelT>(L, st, n, k, labels_out, sizes_out);
+    L.mark();
+    return L.err;
+}
+
+size_t plain_bytes(int64_t n, int32_t k, int64_t cl, bool external_E) {
+    const int64_t nchunks = (n + cl - 1) / cl;
+    PlainExtra x;
+    size_t a;
+    if (k <= 255) {
+        CallState<uint8_t> st;
+        a = carve_size([&](Carver &c) { state_common(c, st, n, cl, k); });
+    } else {
+        CallState<uint16_t> st;
+        a = carve_size([&](Carver &c) { state_common(c, st, n, cl, k); });
+    }
+    return a + carve_size([&](Carver &c) { state_plain(c, x, n, cl, k, nchunks, external_E); });
+}
+
+// One partition call: route choice, memory, validation, then one of the two loops.
+template <typename RowT, typename LabelT>
+int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t k, double slack, int64_t chunk,
+                  int32_t R, const int32_t *seed, int32_t *labels_out, int64_t *sizes_out, uint32_t *estimates_out,
+                  const Opts &o, hipStream_t stream) {
+    const int64_t cl = chunk < n ? chunk : n;             // a chunk longer than the graph is the whole graph
+    const long long P = grem_capacity(n, k, slack);
+    const bool external_E = estimates_out != nullptr;
+    if (o.hist_mode == GREM_HIST_LDS && k > kLdsMaxK) return GREM_ERR_ARG;
+    const bool forced = o.hist_mode == GREM_HIST_SWEEP;
+    bool try_sweep = false;
+    if constexpr (sizeof(LabelT) == 1) {
+        const TpGeom geo = tp_geometry(n, cl, o.col_bits);
+        const bool can = k <= kSweepMaxK && geo.ok && (((uintptr_t)estimates_out) & 15u) == 0;
+        if (forced && !can) return GREM_ERR_ARG;
+        try_sweep = can && (forced || (o.hist_mode == GREM_HIST_AUTO && n >= kSweepMinN && cl >= kSweepMinChunk));
+    } else {
+        if (forced) return GREM_ERR_ARG;
+    }
+
+    Arena mem;
+    mem.stream = stream;
+    Launcher L{stream};
+    {
+        std::lock_guard<std::mutex> lock(g.mu);
+        mem.base = (char *)g.ws;
+        mem.cap = g.ws_bytes;
+        L.level = g.prof_level;
+    }
+    if (mem.base && mem.cap < plain_bytes(n, k, cl, external_E)) return GREM_ERR_NOMEM;
+    L.mark();
+
+    CallState<LabelT> st;
+    if (!carve(mem, [&](Carver &c) { state_common(c, st, n, cl, k); })) { mem.release_all(); return GREM_ERR_NOMEM; }
+    unsigned long long maxdeg = 0;
+    int rc = GREM_OK;
+    bool done = false;
+    if constexpr (sizeof(LabelT) == 1) {
+        if (try_sweep) {
+            // the plan's first kernels also find the largest degree, so the prepass leaves the rows alone
+            launch_prepass<RowT, LabelT>(L, (const RowT *)nullptr, seed, n, k, P, st);
+            const Arena::Mark before_plan = mem.mark();
+            PlanData plan;
+            rc = build_plan<RowT>(plan, rowptr, colidx, n, cl, k, o, mem, mem, L, forced);
+            if (rc == GREM_ERR_NOMEM && !forced) {       // (a workspace that holds the plain route's state only)
+                rc = GREM_OK;
+                plan.T = nullptr;
+            }
+            if (rc != GREM_OK) { mem.release_all(); return rc; }
+            if (plan.have_degrees) {
+                maxdeg = plan.maxdeg;
+                if (seed) {
+                    unsigned long long h[16] = {0};
+                    if (!L.read_back(h, st.misc, sizeof(h))) { mem.release_all(); return L.err; }
+                    if (h[1] != 0 || h[2] != 0) { mem.release_all(); return GREM_ERR_SEED; }
+                }
+                if (R >= 32 || (maxdeg << R) >= (1ull << 32)) { mem.release_all(); return GREM_ERR_RANGE; }
+            } else {
+                try_sweep = false;                       // the plain route's own prepass finds the degrees
+            }
+            if (plan.T) {
+                rc = run_two_phase<RowT>(plan, k, slack, R, seed, labels_out, sizes_out, estimates_out, mem, L, &st);
+                if (rc == GREM_ERR_NOMEM && !forced) rc = GREM_OK;      // nothing of the loop is enqueued yet
+                else done = true;
+            }
+            if (!done) mem.release_to(before_plan);
+        }
+    }
+    if (!done) {
+        if (!try_sweep) {
+            launch_prepass<RowT, LabelT>(L, rowptr, seed, n, k, P, st);
+            unsigned long long h[16] = {0};
+            if (!L.read_back(h, st.misc, sizeof(h))) { mem.release_all(); return L.err; }
+            if (h[1] != 0 || h[2] != 0) { mem.release_all(); return GREM_ERR_SEED; }
+            maxdeg = h[0];
+            if (R >= 32 || (maxdeg << R) >= (1ull << 32)) { mem.release_all(); return GREM_ERR_RANGE; }
+        }
+        rc = run_plain<RowT, LabelT>(rowptr, colidx, n, k, slack, cl, R, seed, labels_out, sizes_out, estimates_out, o,
+                                     maxdeg, mem, L, st);
+    }
+    mem.release_all();
+    return rc;
 }
 
 template <typename RowT>
 int dispatch_labels(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t k, double slack,
                     int64_t chunk, int32_t R, const int32_t *seed, int32_t *labels_out,
-                    int64_t *sizes_out, uint32_t *estimates_out, void *stream) {
+                    int64_t *sizes_out, uint32_t *estimates_out, const grem_options *options, void *stream) {
     if (!args_ok(rowptr, colidx, n, k, slack, chunk, R) || !labels_out) return GREM_ERR_ARG;
-    std::lock_guard<std::mutex> lock(g.mu);
+    Opts o;
+    if (!resolve_options(options, &o)) return GREM_ERR_ARG;
     hipStream_t s = (hipStream_t)stream;
     if (k <= 255)
         return run_partition<RowT, uint8_t>(rowptr, colidx, n, k, slack, chunk, R, seed, labels_out,
-                                            sizes_out, estimates_out, s);
+                                            sizes_out, estimates_out, o, s);
     return run_partition<RowT, uint16_t>(rowptr, colidx, n, k, slack, chunk, R, seed, labels_out,
-                                         sizes_out, estimates_out, s);
+                                         sizes_out, estimates_out, o, s);
 }
 
 template <typename RowT>
@@ -725,6 +997,12 @@ int run_edge_cut(const RowT *rowptr, const int32_t *colidx, int64_t n, const int
 
 }  // namespace
 
+// A plan: the re-laid-out copy and the memory it lives in.
+struct grem_plan {
+    PlanData data;
+    Arena mem;          // persistent allocations
+};
+
 extern "C" {
 
 int64_t grem_capacity(int64_t n, int32_t k, double balance_slack) {
@@ -736,12 +1014,51 @@ int64_t grem_capacity(int64_t n, int32_t k, double balance_slack) {
     return even > widened ? even : widened;
 }
 
-size_t grem_workspace_bytes(int64_t n, int64_t nnz, int32_t k, int64_t chunk) {
-    if (n < 1 || nnz < 0 || k < 1 || k > GREM_MAX_K || chunk < 1) return 0;
-    std::lock_guard<std::mutex> lock(g.mu);
-    const TpGeom geo = tp_geometry(n, chunk, g.sweep_col_bits);
-    const Layout lay = make_layout(n, nnz, nnz, k, chunk, false, geo, g.sweep_hub_degree, true);
-    return lay.total_sweep;
+size_t grem_workspace_bytes(int64_t n, int32_t k, int64_t chunk) {
+    if (n < 1 || n > (int64_t)INT32_MAX || k < 1 || k > GREM_MAX_K || chunk < 1) return 0;
+    return plain_bytes(n, k, chunk < n ? chunk : n, false);
+}
+
+size_t grem_workspace_bytes_two_phase(int64_t n, int64_t nnz, int32_t k, int64_t chunk, const grem_options *options) {
+    if (n < 1 || n > (int64_t)INT32_MAX || nnz < 0 || k < 1 || k > GREM_MAX_K || chunk < 1) return 0;
+    Opts o;
+    if (!resolve_options(options, &o)) return 0;
+    const int64_t cl = chunk < n ? chunk : n;
+    const size_t plain = plain_bytes(n, k, cl, false);
+    const TpGeom geo = tp_geometry(n, cl, o.col_bits);
+    if (k > kSweepMaxK || !geo.ok) return plain;
+    PlanDims d{};
+    d.n = n;
+    d.nnz = nnz;
+    d.geo = geo;
+    d.G = (size_t)geo.nch * (size_t)geo.nsl;
+    d.hubs = (size_t)(nnz / o.hub_degree);                   // a hub has at least hub_degree entries
+    if (d.hubs > (size_t)n) d.hubs = (size_t)n;
+    d.npr = kMaxParts;
+    d.nps = kMaxParts;
+    d.slots = plan_slots(nnz, geo);
+    SweepPlan pl{};
+    TpTables tb{};
+    u64 *pm = nullptr;
+    uint32_t *T = nullptr;
+    uint16_t *R = nullptr;
+    CallState<uint8_t> st;
+    TpState t;
+    size_t total = carve_size([&](Carver &c) { state_common(c, st, n, cl, k); });
+    total += carve_size([&](Carver &c) { plan_stage1(c, d, pl, pm); });
+    total += carve_size([&](Carver &c) { plan_stage2(c, d, pl); });
+    total += carve_size([&](Carver &c) { plan_stage3(c, d, tb, T, R); });
+    // the intermediate copy and the per-call state take turns in one region; the state is largest for a
+    // seeded run whose estimates need 32 bits
+    const size_t temp = align_up((size_t)nnz * 4 + 16);
+    const size_t chunk_hubs = d.hubs < (size_t)cl ? d.hubs : (size_t)cl;
+    const size_t s16 = carve_size([&](Carver &c) { state_two_phase(c, t, n, k, d.slots, chunk_hubs, d.hubs, true, true, false); });
+    const size_t s32 = carve_size([&](Carver &c) { state_two_phase(c, t, n, k, d.slots, chunk_hubs, d.hubs, true, false, false); });
+    size_t tail = temp;
+    if (s16 > tail) tail = s16;
+    if (s32 > tail) tail = s32;
+    total += tail;
+    return total > plain ? total : plain;
 }
 
 int grem_set_workspace(void *dev_ptr, size_t bytes) {
@@ -753,77 +1070,130 @@ int grem_set_workspace(void *dev_ptr, size_t bytes) {
     return GREM_OK;
 }
 
-int grem_set_histogram_mode(int32_t mode) {
-    if (mode != GREM_HIST_AUTO && mode != GREM_HIST_LDS && mode != GREM_HIST_GLOBAL &&
-        mode != GREM_HIST_SWEEP)
-        return GREM_ERR_ARG;
-    std::lock_guard<std::mutex> lock(g.mu);
-    g.hist_mode = mode;
-    return GREM_OK;
-}
-
-int grem_set_sweep_hub_degree(int32_t degree) {
-    if (degree < 1 || degree > 65535) return GREM_ERR_ARG;
-    std::lock_guard<std::mutex> lock(g.mu);
-    g.sweep_hub_degree = degree;
-    return GREM_OK;
-}
-
-int grem_set_long_row_degree(int32_t degree) {
-    if (degree < 0) return GREM_ERR_ARG;
-    std::lock_guard<std::mutex> lock(g.mu);
-    g.long_row_degree = degree == 0 ? kLongRowDegree : degree;
-    return GREM_OK;
-}
-
-int grem_set_sweep_col_bits(int32_t bits) {
-    if (bits != 0 && (bits < 4 || bits > kMaxColBits)) return GREM_ERR_ARG;
-    std::lock_guard<std::mutex> lock(g.mu);
-    g.sweep_col_bits = bits;
-    return GREM_OK;
-}
-
 int grem_partition(const int64_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
                    double balance_slack, int64_t chunk, int32_t refine_passes, int32_t *labels_out,
                    void *stream) {
     return dispatch_labels<int64_t>(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, nullptr,
-                                    labels_out, nullptr, nullptr, stream);
+                                    labels_out, nullptr, nullptr, nullptr, stream);
 }
 
 int grem_partition_seeded(const int64_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
                           double balance_slack, int64_t chunk, int32_t refine_passes,
                           const int32_t *seed_labels, int32_t *labels_out, void *stream) {
     return dispatch_labels<int64_t>(rowptr, colidx, n, k, balance_slack, chunk, refine_passes,
-                                    seed_labels, labels_out, nullptr, nullptr, stream);
+                                    seed_labels, labels_out, nullptr, nullptr, nullptr, stream);
 }
 
 int grem_partition_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
                        double balance_slack, int64_t chunk, int32_t refine_passes, int32_t *labels_out,
                        void *stream) {
     return dispatch_labels<int32_t>(rowptr, colidx, n, k, balance_slack, chunk, refine_passes, nullptr,
-                                    labels_out, nullptr, nullptr, stream);
+                                    labels_out, nullptr, nullptr, nullptr, stream);
 }
 
 int grem_partition_seeded_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n, int32_t k,
                               double balance_slack, int64_t chunk, int32_t refine_passes,
                               const int32_t *seed_labels, int32_t *labels_out, void *stream) {
     return dispatch_labels<int32_t>(rowptr, colidx, n, k, balance_slack, chunk, refine_passes,
-                                    seed_labels, labels_out, nullptr, nullptr, stream);
+                                    seed_labels, labels_out, nullptr, nullptr, nullptr, stream);
+}
+
+int grem_partition_opt(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
+                       int32_t k, double balance_slack, int64_t chunk, int32_t refine_passes,
+                       const int32_t *seed_labels, int32_t *labels_out, int64_t *sizes_out,
+                       uint32_t *estimates_out, const grem_options *options, void *stream) {
+    if (rowptr_bits == 64)
+        return dispatch_labels<int64_t>((const int64_t *)rowptr, colidx, n, k, balance_slack, chunk,
+                                        refine_passes, seed_labels, labels_out, sizes_out,
+                                        estimates_out, options, stream);
+    if (rowptr_bits == 32)
+        return dispatch_labels<int32_t>((const int32_t *)rowptr, colidx, n, k, balance_slack, chunk,
+                                        refine_passes, seed_labels, labels_out, sizes_out,
+                                        estimates_out, options, stream);
+    return GREM_ERR_ARG;
 }
 
 int grem_partition_state(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
                          int32_t k, double balance_slack, int64_t chunk, int32_t refine_passes,
                          const int32_t *seed_labels, int32_t *labels_out, int64_t *sizes_out,
                          uint32_t *estimates_out, void *stream) {
-    if (rowptr_bits == 64)
-        return dispatch_labels<int64_t>((const int64_t *)rowptr, colidx, n, k, balance_slack, chunk,
-                                        refine_passes, seed_labels, labels_out, sizes_out,
-                                        estimates_out, stream);
-    if (rowptr_bits == 32)
-        return dispatch_labels<int32_t>((const int32_t *)rowptr, colidx, n, k, balance_slack, chunk,
-                                        refine_passes, seed_labels, labels_out, sizes_out,
-                                        estimates_out, stream);
-    return GREM_ERR_ARG;
+    return grem_partition_opt(rowptr, rowptr_bits, colidx, n, k, balance_slack, chunk, refine_passes, seed_labels,
+                              labels_out, sizes_out, estimates_out, nullptr, stream);
+}
+
+int grem_plan_create(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n, int64_t chunk,
+                     const grem_options *options, void *stream, grem_plan **plan_out) {
+    if (!plan_out) return GREM_ERR_ARG;
+    *plan_out = nullptr;
+    if (!rowptr || !colidx || n < 1 || n > (int64_t)INT32_MAX || chunk < 1 || (rowptr_bits != 32 && rowptr_bits != 64))
+        return GREM_ERR_ARG;
+    Opts o;
+    if (!resolve_options(options, &o)) return GREM_ERR_ARG;
+    const int64_t cl = chunk < n ? chunk : n;
+    if (!tp_geometry(n, cl, o.col_bits).ok) return GREM_ERR_ARG;
+    grem_plan *p = new (std::nothrow) grem_plan();
+    if (!p) return GREM_ERR_NOMEM;
+    hipStream_t s = (hipStream_t)stream;
+    p->mem.persistent = true;
+    Arena temp;
+    temp.stream = s;
+    Launcher L{s};
+    {
+        std::lock_guard<std::mutex> lock(g.mu);
+        L.level = g.prof_level;
+    }
+    L.mark();
+    int rc = rowptr_bits == 64
+                 ? build_plan<int64_t>(p->data, (const int64_t *)rowptr, colidx, n, cl, 0, o, p->mem, temp, L, true)
+                 : build_plan<int32_t>(p->data, (const int32_t *)rowptr, colidx, n, cl, 0, o, p->mem, temp, L, true);
+    L.mark();
+    temp.release_all();
+    if (hipStreamSynchronize(s) != hipSuccess && rc == GREM_OK) rc = GREM_ERR_HIP;
+    if (rc != GREM_OK) {
+        p->mem.release_all();
+        delete p;
+        return rc;
+    }
+    *plan_out = p;
+    return GREM_OK;
+}
+
+int grem_plan_destroy(grem_plan *plan) {
+    if (!plan) return GREM_OK;
+    const int rc = hipDeviceSynchronize() == hipSuccess ? GREM_OK : GREM_ERR_HIP;
+    plan->mem.release_all();
+    delete plan;
+    return rc;
+}
+
+size_t grem_plan_device_bytes(const grem_plan *plan) { return plan ? plan->mem.total : 0; }
+
+int32_t grem_plan_max_k(const grem_plan *plan) { return plan ? plan->data.max_k : 0; }
+
+int grem_partition_planned(const grem_plan *plan, int32_t k, double balance_slack, int32_t refine_passes,
+                           const int32_t *seed_labels, int32_t *labels_out, int64_t *sizes_out,
+                           uint32_t *estimates_out, void *stream) {
+    if (!plan || !plan->data.T || !labels_out || k < 1 || k > plan->data.max_k || refine_passes < 0 ||
+        !(balance_slack >= 1.0) || std::isinf(balance_slack))
+        return GREM_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    Arena mem;
+    mem.stream = s;
+    Launcher L{s};
+    {
+        std::lock_guard<std::mutex> lock(g.mu);
+        mem.base = (char *)g.ws;
+        mem.cap = g.ws_bytes;
+        L.level = g.prof_level;
+    }
+    L.mark();
+    const int rc = plan->data.rowptr_bits == 64
+                       ? run_two_phase<int64_t>(plan->data, k, balance_slack, refine_passes, seed_labels, labels_out,
+                                                sizes_out, estimates_out, mem, L, nullptr)
+                       : run_two_phase<int32_t>(plan->data, k, balance_slack, refine_passes, seed_labels, labels_out,
+                                                sizes_out, estimates_out, mem, L, nullptr);
+    mem.release_all();
+    return rc;
 }
 
 int grem_edge_cut(const int64_t *rowptr, const int32_t *colidx, int64_t n, const int32_t *labels,
@@ -836,16 +1206,19 @@ int grem_edge_cut_r32(const int32_t *rowptr, const int32_t *colidx, int64_t n, c
     return run_edge_cut<int32_t>(rowptr, colidx, n, labels, cut_entries_out, stream);
 }
 
-int grem_profile_enable(int32_t on) {
+int grem_profile_enable(int32_t level) {
+    if (level < 0 || level > 2) return GREM_ERR_ARG;
     std::lock_guard<std::mutex> lock(g.mu);
-    g.prof = on != 0;
+    g.prof_level = level;
     return GREM_OK;
 }
 
 int grem_profile_reset(void) {
     std::lock_guard<std::mutex> lock(g.mu);
     for (auto &e : g.events) { g.pool.push_back(e.a); g.pool.push_back(e.b); }
+    for (auto &e : g.marks) g.pool.push_back(e);
     g.events.clear();
+    g.marks.clear();
     return GREM_OK;
 }
 
@@ -866,6 +1239,19 @@ int grem_profile_read(int32_t kernel_class, double *total_ms, int64_t *launches)
     *total_ms = tot;
     *launches = cnt;
     return GREM_OK;
+}
+
+int grem_profile_read_marks(double *ms_out, int32_t capacity) {
+    if (!ms_out || capacity < 0) return GREM_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g.mu);
+    int written = 0;
+    for (size_t i = 1; i < g.marks.size() && written < capacity; ++i) {
+        if (hipEventSynchronize(g.marks[i]) != hipSuccess) return GREM_ERR_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g.marks[i - 1], g.marks[i]) != hipSuccess) return GREM_ERR_HIP;
+        ms_out[written++] = ms;
+    }
+    return written;
 }
 
 const char *grem_status_string(int code) {

@@ -43,7 +43,8 @@ __device__ __forceinline__ int owning_row(const uint32_t *rowrel, uint32_t i, in
 }
 
 // ------------------------------------------------------------------------------------------------
-// prepass: compact labels from the seed, seed sizes, maximum degree, seed validity
+// prepass: compact labels from the seed, seed sizes, seed validity, and (when rowptr is given)
+// the maximum degree
 // misc[0] = max degree, misc[1] = number of invalid seed labels, misc[3] = number of entries
 // ------------------------------------------------------------------------------------------------
 template <typename RowT, typename LabelT>
@@ -60,8 +61,10 @@ __global__ __launch_bounds__(256) void k_prepass(const RowT *__restrict__ rowptr
     unsigned int bad = 0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
-        unsigned long long d = (unsigned long long)(rowptr[v + 1] - rowptr[v]);
-        if (d > mymax) mymax = d;
+        if (rowptr) {
+            unsigned long long d = (unsigned long long)(rowptr[v + 1] - rowptr[v]);
+            if (d > mymax) mymax = d;
+        }
         uint32_t lab = LabelTraits<LabelT>::kUnassigned;
         if (seed) {
             int32_t s = seed[v];
@@ -74,13 +77,13 @@ __global__ __launch_bounds__(256) void k_prepass(const RowT *__restrict__ rowptr
         }
         Lc[v] = (LabelT)lab;
     }
-    atomicMax(&s_maxdeg, mymax);
+    if (mymax) atomicMax(&s_maxdeg, mymax);
     if (bad) atomicAdd(&s_bad, bad);
     __syncthreads();
     if (threadIdx.x == 0) {
-        atomicMax(&misc[0], s_maxdeg);
+        if (s_maxdeg) atomicMax(&misc[0], s_maxdeg);
         if (s_bad) atomicAdd(&misc[1], (unsigned long long)s_bad);
-        if (blockIdx.x == 0) misc[3] = (unsigned long long)rowptr[n];
+        if (blockIdx.x == 0 && rowptr) misc[3] = (unsigned long long)rowptr[n];
     }
 }
 

@@ -49,6 +49,7 @@ namespace grem {
 constexpr int kSliceRowBits = 11;
 constexpr int kSliceRows = 1 << kSliceRowBits;     // rows per slice (row index << 5 fits the 16 bits of R)
 constexpr int kPlanThreads = 256;
+constexpr int kPlanParts = kSliceRows / kPlanThreads;     // finest cut of a slice the re-layout uses
 constexpr int kTpThreads = 1024;                   // k_tp_lookup and k_tp_score
 constexpr int kMaxBlocks = 4096;                   // column blocks (LDS tables in the re-layout kernels)
 constexpr int kMaxShareHubs = 2048;                // hubs one share may touch (index fits the row field)
@@ -67,6 +68,7 @@ struct SweepPlan {
     uint32_t *sl_hub_start;   // index of the slice's first hub in the chunk's hub list
     u64 *sl_hent;             // hub entries in the slice
     u64 *sl_hent_start;       // their start in the chunk's hub entry stream
+    uint32_t *sl_part_reg0;   // [kPlanParts per slice] regular entries of the slice's rows before row 256 * p
     uint32_t *share_h0;       // first hub touched by share gs
     uint32_t *share_nhs;      // hubs touched by share gs
     // per chunk
@@ -75,8 +77,10 @@ struct SweepPlan {
     u64 *ch_H;                // hub entries
     uint32_t *ch_nvs;         // hub shares of the chunk (0 without hubs, else 1 .. its number of slices)
     u64 *ch_hbase;            // start of the chunk's hub entry stream in the stream of all chunks (+1: total)
-    // hub lists: chunk c's hubs at hub_row[chunk_lo + i]; prefix of their degrees at
-    // hub_off[chunk_lo + c + i], i = 0..nh (one more slot per chunk)
+    u64 *ch_reg0;             // regular entries of the chunks before it (+1: total)
+    u64 *ch_hub0;             // hubs of the chunks before it (+1: total)
+    // hub lists: chunk c's hubs at hub_row[ch_hub0[c] + i]; prefix of their degrees at
+    // hub_off[ch_hub0[c] + c + i], i = 0..nh (one more slot per chunk)
     int32_t *hub_row;
     u64 *hub_off;
 };
@@ -89,7 +93,9 @@ struct TpTables {
     u64 *xstart;      // [nch][nblk] (+1): first slot of segment (c, jb) in Lx and R
     u64 *tstart;      // [nblk][nch] (+1): first slot of segment (c, jb) in T
     uint32_t *lo;     // [nch * nsl * npr][ngroups + 1]: start of block group g's run inside the unit's range of U
-    uint32_t *loh;    // [nch * nsl * nps][ngroups + 1]: the same for the parts of the hub shares and Uh
+    uint32_t *loh;    // [nch * nsl * nps][ngroups + 1]: the same for the parts of the hub shares
+    u64 *ustart;      // [nch * nsl * npr]: first tuple of a slice part's range of U (regular entries, compacted)
+    u64 *ustart_h;    // [nch * nsl * nps]: the same for the parts of the hub shares (after all regular entries)
     int npr;          // parts per slice (a power of two: equal row ranges)
     int nps;          // parts per hub share (equal ranges of its entries)
     int gb;           // log2 of the column blocks per group of the intermediate copy U
@@ -140,38 +146,55 @@ __device__ __forceinline__ void block_scan2(uint32_t a, u64 b, uint32_t *ea, u64
 }
 
 // ------------------------------------------------------------------------------------------------
-// plan 1: per slice, regular entries, hubs, hub entries
+// plan 1: per slice, regular entries, hubs, hub entries; misc[0] = the graph's largest degree,
+// misc[3] = its number of entries
 // ------------------------------------------------------------------------------------------------
 template <typename RowT>
 __global__ __launch_bounds__(256) void k_plan_slices(const RowT *__restrict__ rowptr, int64_t n,
                                                      int64_t chunk, int nsl, uint32_t hub_degree,
-                                                     SweepPlan pl) {
-    __shared__ u64 s_reg, s_hent;
-    __shared__ uint32_t s_nh;
+                                                     SweepPlan pl, u64 *__restrict__ misc) {
+    __shared__ u64 s_reg, s_hent, s_maxdeg;
+    __shared__ uint32_t s_nh, s_part[kPlanParts];
     const int tid = threadIdx.x;
     const int64_t c = blockIdx.x / nsl;
     const int i = blockIdx.x % nsl;
     const int64_t chunk_lo = c * chunk;
     const int64_t chunk_hi = (chunk_lo + chunk < n) ? chunk_lo + chunk : n;
     const int64_t v0 = chunk_lo + (int64_t)i * kSliceRows;
-    if (tid == 0) { s_reg = 0; s_hent = 0; s_nh = 0; }
+    if (tid == 0) { s_reg = 0; s_hent = 0; s_nh = 0; s_maxdeg = 0; }
+    if (tid < kPlanParts) s_part[tid] = 0;
     __syncthreads();
-    u64 reg = 0, hent = 0;
+    u64 reg = 0, hent = 0, maxdeg = 0;
     uint32_t nh = 0;
-    for (int q = tid; q < kSliceRows; q += 256) {
-        const int64_t v = v0 + q;
+#pragma unroll
+    for (int p = 0; p < kPlanParts; ++p) {          // rows 256 p .. 256 p + 255: one per thread
+        const int64_t v = v0 + p * kPlanThreads + tid;
+        uint32_t regp = 0;
         if (v < chunk_hi) {
             const u64 d = (u64)(rowptr[v + 1] - rowptr[v]);
-            if (d >= hub_degree) { nh += 1; hent += d; } else reg += d;
+            if (d >= hub_degree) { nh += 1; hent += d; } else { reg += d; regp = (uint32_t)d; }
+            maxdeg = d > maxdeg ? d : maxdeg;
         }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) regp += __shfl_xor(regp, off);
+        if (lane_id() == 0 && regp) atomicAdd(&s_part[p], regp);
     }
     if (reg) atomicAdd(&s_reg, reg);
     if (nh) { atomicAdd(&s_hent, hent); atomicAdd(&s_nh, nh); }
+    // (wavefront maximum first: one LDS atomic per wavefront)
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) { const u64 o = __shfl_xor(maxdeg, off); maxdeg = o > maxdeg ? o : maxdeg; }
+    if (lane_id() == 0 && maxdeg) atomicMax(&s_maxdeg, maxdeg);
     __syncthreads();
     if (tid == 0) {
         pl.sl_reg_cnt[blockIdx.x] = (uint32_t)s_reg;
         pl.sl_nh[blockIdx.x] = s_nh;
         pl.sl_hent[blockIdx.x] = s_hent;
+        uint32_t run = 0;
+        for (int p = 0; p < kPlanParts; ++p) { pl.sl_part_reg0[(size_t)blockIdx.x * kPlanParts + p] = run; run += s_part[p]; }
+        // (few workgroups raise the maximum: the plain read spares the others the atomic)
+        if (s_maxdeg > __hip_atomic_load(&misc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(&misc[0], s_maxdeg);
+        if (blockIdx.x == 0) misc[3] = (u64)rowptr[n];
     }
 }
 
@@ -181,7 +204,7 @@ __global__ __launch_bounds__(256) void k_plan_slices(const RowT *__restrict__ ro
 // column block still holds some 64 entries, at most one per slice.  misc[6] = most hubs in a
 // chunk, misc[7] = most entries in a chunk, misc[9] = most regular entries in a slice (set here
 // from the slices' counts), misc[10] = most entries in a hub share, misc[11] = most hub shares in a
-// chunk, misc[8] = hub entries of all chunks.
+// chunk, misc[8] = hub entries of all chunks, misc[12] = hubs of all chunks.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, int nsl, int nblk,
                                                      SweepPlan pl, u64 *__restrict__ misc) {
@@ -222,8 +245,9 @@ __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, i
         pl.ch_regtot[c] = breg;
         pl.ch_nh[c] = bnh;
         pl.ch_H[c] = bhent;
-        pl.ch_hbase[c] = bhent;             // scanned over the chunks by k_tp_scan_segments
-        pl.hub_off[chunk_lo + c + bnh] = bhent;
+        pl.ch_hbase[c] = bhent;             // these three: scanned over the chunks by k_tp_scan
+        pl.ch_reg0[c] = breg;
+        pl.ch_hub0[c] = (u64)bnh;
         const int64_t chunk_hi = (chunk_lo + chunk < n) ? chunk_lo + chunk : n;
         const u64 nsl_c = (u64)((chunk_hi - chunk_lo + kSliceRows - 1) / kSliceRows);
         u64 nvs = 0;
@@ -240,6 +264,7 @@ __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, i
         if (nvs) atomicMax(&misc[10], bhent / nvs + 1);
         if (nvs) atomicMax(&misc[11], nvs);
         atomicAdd(&misc[8], bhent);
+        atomicAdd(&misc[12], (u64)bnh);
     }
 }
 
@@ -253,9 +278,11 @@ __global__ __launch_bounds__(256) void k_plan_hubs(const RowT *__restrict__ rowp
     __shared__ uint32_t s_a[4];
     __shared__ u64 s_b[4];
     const int tid = threadIdx.x;
-    if (pl.sl_nh[blockIdx.x] == 0) return;
     const int64_t c = blockIdx.x / nsl;
     const int i = blockIdx.x % nsl;
+    const u64 hub0 = pl.ch_hub0[c];
+    if (i == 0 && tid == 0) pl.hub_off[hub0 + (u64)c + pl.ch_nh[c]] = pl.ch_H[c];     // the list's closing offset
+    if (pl.sl_nh[blockIdx.x] == 0) return;
     const int64_t chunk_lo = c * chunk;
     const int64_t chunk_hi = (chunk_lo + chunk < n) ? chunk_lo + chunk : n;
     const int64_t v0 = chunk_lo + (int64_t)i * kSliceRows;
@@ -270,8 +297,8 @@ __global__ __launch_bounds__(256) void k_plan_hubs(const RowT *__restrict__ rowp
         u64 eb, tb;
         block_scan2(hub ? 1u : 0u, hub ? d : 0ull, &ea, &eb, &ta, &tb, s_a, s_b);
         if (hub) {
-            pl.hub_row[chunk_lo + run_nh + ea] = (int32_t)v;
-            pl.hub_off[chunk_lo + c + run_nh + ea] = run_ent + eb;
+            pl.hub_row[hub0 + run_nh + ea] = (int32_t)v;
+            pl.hub_off[hub0 + (u64)c + run_nh + ea] = run_ent + eb;
         }
         run_nh += ta;
         run_ent += tb;
@@ -297,7 +324,7 @@ __global__ __launch_bounds__(256) void k_plan_shares(int64_t n, int64_t chunk, i
         const u64 a = H * (u64)i / NS, b = H * (u64)(i + 1) / NS;
         if (a != b) {
             const uint32_t nh = pl.ch_nh[c];
-            const u64 *goff = pl.hub_off + chunk_lo + c;        // nh + 1 entries, goff[nh] = H
+            const u64 *goff = pl.hub_off + pl.ch_hub0[c] + (u64)c;        // nh + 1 entries, goff[nh] = H
             uint32_t lo = 0, hi = nh;                           // largest idx with goff[idx] <= a
             while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (goff[mid] <= a) lo = mid; else hi = mid; }
             h0 = lo;
@@ -465,9 +492,10 @@ __device__ __forceinline__ bool tp_entry_source(const RowT *__restrict__ rowptr,
         const u64 H = pl.ch_H[c];
         const u64 a = H * (u64)i / nvs, b = H * (u64)(i + 1) / nvs;
         const u64 pa = a + (b - a) * (u64)q / (u64)np, pb = a + (b - a) * (u64)(q + 1) / (u64)np;
-        const u64 *goff = pl.hub_off + chunk_lo + c;
+        const u64 hub0 = pl.ch_hub0[c];
+        const u64 *goff = pl.hub_off + hub0 + (u64)c;
         for (uint32_t t = tid; t <= nhs; t += kTpThreads) hoff[t] = goff[h0 + t];
-        for (uint32_t t = tid; t < nhs; t += kTpThreads) hrow[t] = (u64)rowptr[pl.hub_row[chunk_lo + h0 + t]];
+        for (uint32_t t = tid; t < nhs; t += kTpThreads) hrow[t] = (u64)rowptr[pl.hub_row[hub0 + h0 + t]];
         __syncthreads();
         src->hoff = hoff;
         src->hrow = hrow;
@@ -488,8 +516,9 @@ __device__ __host__ inline size_t tp_source_words(bool share, int np, int share_
 // being nsl for slices and the largest number of shares of a chunk for shares): count the unit's
 // entries per column block (added to subR / subH [row(c,i)][*], which start at zero and become
 // starts in k_tp_scan_slices), and copy its tuples, grouped by column-block GROUP (2^gb consecutive
-// blocks), to the unit's own range of U (Uh for shares): the entries' own positions in the CSR
-// (in the hub entry stream).  Run g of the unit starts at lo[unit][g].  The tuples are collected
+// blocks), to the unit's own range of U: first the regular entries of all rows in CSR order (the
+// hub rows' entries left out), then, from `hub_base` on, the chunks' hub entry streams.  The range
+// starts at ustart[unit]; run g of the unit starts at lo[unit][g] inside it.  The tuples are collected
 // in LDS and written as one contiguous piece (a lane-by-lane scatter would cost one L2 request per
 // tuple); a unit with more than `cap` tuples writes them one by one instead.
 // U tuple: row field << (cb + gb) | block in group << cb | column in block.
@@ -500,7 +529,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
                                                          const int32_t *__restrict__ colidx, int64_t n,
                                                          uint32_t hub_degree, SweepPlan pl, TpTables tb,
                                                          int share_hubs, uint32_t cap, int per_chunk,
-                                                         uint32_t *__restrict__ U) {
+                                                         uint32_t *__restrict__ U, u64 hub_base) {
     extern __shared__ u64 smem64[];
     const int np = SHARE ? tb.nps : tb.npr;
     uint32_t *cntf = reinterpret_cast<uint32_t *>(smem64) + tp_source_words(SHARE, np, share_hubs);   // nblk
@@ -512,14 +541,25 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
     const int q = (int)(blockIdx.x % (unsigned)np);
     const int64_t c = gs / (unsigned)per_chunk;
     const int i = gs % (unsigned)per_chunk;
-    uint32_t *lo_out = (SHARE ? tb.loh : tb.lo) + (((size_t)c * tb.nsl + i) * np + q) * (tb.ngroups + 1);
+    const size_t unit = ((size_t)c * tb.nsl + i) * np + q;
+    uint32_t *lo_out = (SHARE ? tb.loh : tb.lo) + unit * (tb.ngroups + 1);
+    u64 *ustart_out = (SHARE ? tb.ustart_h : tb.ustart) + unit;
     TpEntrySource src;
+    // where the unit's range of U starts: requested now, needed after the counting phase
+    const size_t gs_unit = (size_t)c * tb.nsl + i;
+    const u64 range0 = SHARE ? pl.ch_hbase[c]
+                             : pl.ch_reg0[c] + pl.sl_reg_start[gs_unit] +
+                                   pl.sl_part_reg0[gs_unit * kPlanParts + (size_t)q * (kPlanParts / np)];
     for (int j = tid; j < tb.nblk; j += kTpThreads) cntf[j] = 0;    // the source's closing barrier covers this too
     if (!tp_entry_source<RowT, SHARE>(rowptr, colidx, n, hub_degree, pl, tb, c, i, q, np, share_hubs, smem64,
                                       &src)) {
         for (int j = tid; j <= tb.ngroups; j += kTpThreads) lo_out[j] = 0;
+        if (tid == 0) *ustart_out = 0;
         return;
     }
+    // where the unit's tuples go
+    const u64 ustart = SHARE ? hub_base + range0 + src.a : range0;
+    if (tid == 0) *ustart_out = ustart;
     // a unit of one round (the usual case) keeps its entries in registers between the two phases
     const uint32_t rounds = tp_rounds<SHARE>(src);
     uint32_t row[kTpBatch], col[kTpBatch];
@@ -575,7 +615,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
     const uint32_t total = cg[tb.ngroups];
     const bool staged = total <= cap;
     const uint32_t gmask = (1u << tb.gb) - 1u;
-    uint32_t *ubase = U + (SHARE ? pl.ch_hbase[c] + src.a : (u64)src.e0);
+    uint32_t *ubase = U + ustart;
     for (uint32_t r = 0; r < rounds; ++r) {
         if (rounds > 1) tp_load_round<SHARE>(src, r, row, col, on);
         uint32_t w[kTpBatch], tuple[kTpBatch];
@@ -603,7 +643,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
 // counts -> starts.  One thread per segment (c, jb): exclusive prefix over the slices of the
 // regular counts, then of the share counts, every count rounded up to a multiple of 4 (four tuples
 // are 12 bytes of T, 8 of R, 2 of Lx: sub-segments start on 4-byte boundaries of T); the segment length, rounded up to a multiple of 8, goes to xstart and
-// tstart (each in its own order), to be scanned by k_tp_scan_segments.
+// tstart (each in its own order), to be scanned by k_tp_scan.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_tp_scan_slices(TpTables tb) {
     const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -621,13 +661,13 @@ __global__ __launch_bounds__(256) void k_tp_scan_slices(TpTables tb) {
     tb.tstart[(size_t)jb * tb.nch + c] = padded;
 }
 
-// In-place exclusive prefix of a[0..m) by one workgroup, total in a[m].  Array 0 is xstart, 1 is
-// tstart, 2 (m = nch) the chunks' hub entry counts in ch_hbase; block b scans array first + b.
-__global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb, u64 *__restrict__ ch_hbase, int first) {
+// In-place exclusive prefix of a[0..m) by one workgroup, total in a[m]; workgroup b scans array b
+// (up to three arrays per launch).
+__global__ __launch_bounds__(1024) void k_tp_scan(u64 *__restrict__ a0, int64_t m0, u64 *__restrict__ a1, int64_t m1,
+                                                  u64 *__restrict__ a2, int64_t m2) {
     __shared__ u64 part[1024];
-    const int which = first + (int)blockIdx.x;
-    u64 *a = which == 0 ? tb.xstart : (which == 1 ? tb.tstart : ch_hbase);
-    const int64_t m = which == 2 ? (int64_t)tb.nch : (int64_t)tb.nch * tb.nblk;
+    u64 *a = blockIdx.x == 0 ? a0 : (blockIdx.x == 1 ? a1 : a2);
+    const int64_t m = blockIdx.x == 0 ? m0 : (blockIdx.x == 1 ? m1 : m2);
     const int tid = threadIdx.x;
     const int64_t per = (m + 1023) / 1024;
     const int64_t lo = tid * per;
@@ -644,7 +684,7 @@ __global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb, u64 *__r
 
 // ------------------------------------------------------------------------------------------------
 // Re-layout, step 2: workgroup c * ngroups + g moves the runs of block group g of every unit of
-// chunk c from U (then Uh) to their sub-segments, `batch` slices (shares) at a time: the
+// chunk c (slice parts, then share parts) from U to their sub-segments, `batch` slices (shares) at a time: the
 // sub-segments of consecutive slices are adjacent, so the tuples of a batch form one piece per block
 // of the group; the pieces are put together in LDS, pad tuples included (row field 2048: the score
 // kernel ignores them; they fill every sub-segment up to a multiple of 4), and written out
@@ -656,11 +696,8 @@ __global__ __launch_bounds__(1024) void k_tp_scan_segments(TpTables tb, u64 *__r
 // ------------------------------------------------------------------------------------------------
 constexpr int kPlaceThreads = 512;
 
-template <typename RowT>
-__global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restrict__ rowptr, int64_t n,
-                                                            SweepPlan pl, TpTables tb,
+__global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan pl, TpTables tb,
                                                             const uint32_t *__restrict__ U,
-                                                            const uint32_t *__restrict__ Uh,
                                                             uint32_t *__restrict__ T, uint16_t *__restrict__ R,
                                                             int batch, uint32_t cap) {
     extern __shared__ u64 smem64[];
@@ -703,7 +740,8 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
         const int np = part == 0 ? tb.npr : tb.nps;
         const uint32_t *sub = (part == 0 ? tb.subR : tb.subH) + ((size_t)c * (tb.nsl + 1)) * tb.nblk + jb0;
         const uint32_t *lot = part == 0 ? tb.lo : tb.loh;
-        const uint32_t *src = part == 0 ? U : Uh;
+        const u64 *ust = part == 0 ? tb.ustart : tb.ustart_h;
+        const uint32_t *src = U;
         int i0 = 0;
         while (i0 < count) {
             // the largest batch (<= `batch` slices) whose pieces fit the stage; at least one slice
@@ -715,16 +753,7 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(const RowT *__restri
                     const int t = z / np, q = z % np;
                     const size_t unit = ((size_t)c * tb.nsl + i0 + t) * np + q;
                     const uint32_t a = lot[unit * (tb.ngroups + 1) + g], b = lot[unit * (tb.ngroups + 1) + g + 1];
-                    u64 at;
-                    if (part == 0) {
-                        const int64_t v = chunk_lo + (int64_t)(i0 + t) * kSliceRows + (int64_t)q * (kSliceRows / np);
-                        at = v < chunk_hi ? (u64)rowptr[v] : 0ull;   // a part beyond the chunk has no tuples
-                    } else {
-                        const u64 H = pl.ch_H[c];
-                        const u64 sa = H * (u64)(i0 + t) / (u64)nvs, sb = H * (u64)(i0 + t + 1) / (u64)nvs;
-                        at = pl.ch_hbase[c] + sa + (sb - sa) * (u64)q / (u64)np;
-                    }
-                    runsrc[z] = at + a;
+                    runsrc[z] = ust[unit] + a;                   // (a unit that does not exist has no tuples)
                     runlen[z] = b - a;
                     runsl[z] = (uint32_t)t;
                 }
@@ -1433,9 +1462,12 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
 // propose, add the movers to their tiles' counts; the table row is cleared for the next chunk.
 // 16 lanes per hub, lane j takes partition j (k <= 16).
 // ------------------------------------------------------------------------------------------------
+// Estimates of the hubs: row v of E (n rows) when E is given, else row (ch_hub0[c] + i) of Ehub, the
+// table of the hubs alone.
 __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_t *__restrict__ Lc,
                                                       const long long *__restrict__ room,
-                                                      uint32_t *__restrict__ E, uint32_t *__restrict__ Hhub,
+                                                      uint32_t *__restrict__ E, uint32_t *__restrict__ Ehub,
+                                                      uint32_t *__restrict__ Hhub,
                                                       uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
                                                       int c, int64_t chunk_lo, int k, int pass, int store_e,
                                                       int ntiles, uint32_t *__restrict__ tot) {
@@ -1476,13 +1508,14 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
     int64_t v = 0;
     uint32_t old = 0xFFu;
     if (on) {
-        v = pl.hub_row[chunk_lo + i];
+        const u64 hub = pl.ch_hub0[c] + i;
+        v = pl.hub_row[hub];
         old = (uint32_t)Lc[v];
         if (j < k) {
             uint32_t *hp = Hhub + (size_t)i * k + j;
             const uint32_t h = *hp;
             *hp = 0;
-            uint32_t *ep = E + (size_t)v * (size_t)k + j;
+            uint32_t *ep = E ? E + (size_t)v * (size_t)k + j : Ehub + (size_t)hub * (size_t)k + j;
             const uint32_t e = (pass > 0 ? *ep : 0u) + (h << sh);
             if (store_e) *ep = e;
             const uint32_t rm = (uint32_t)room[j] + ((uint32_t)j == old ? 1u : 0u);

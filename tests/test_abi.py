@@ -53,15 +53,25 @@ def test_host_helpers(lib):
     assert lib.grem_capacity(0, 4, 1.05) == -1
     assert lib.grem_capacity(10, 4, 0.5) == -1
     lib.grem_workspace_bytes.restype = ctypes.c_size_t
-    lib.grem_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64]
+    lib.grem_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int64]
+    lib.grem_workspace_bytes_two_phase.restype = ctypes.c_size_t
+    lib.grem_workspace_bytes_two_phase.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64,
+                                                   ctypes.c_void_p]
     n, nnz, k, chunk = 1 << 20, 30_000_000, 8, 1 << 16
-    w = lib.grem_workspace_bytes(n, nnz, k, chunk)
-    # E, labels, and the re-laid-out entries: 4-byte tuples, 2-byte look-up results, the 4-byte
-    # intermediate copy (regular rows, and room for as many hub entries), plus offset tables
-    assert w >= n * k * 4 + n + 14 * nnz and w < n * k * 4 + 20 * n + 14 * nnz + (64 << 20)
-    w2 = lib.grem_workspace_bytes(n, nnz, 64, chunk)           # no entry copy above k = 16
-    assert n * 64 * 4 + n <= w2 < n * 64 * 4 + 4 * n + (1 << 20)
-    assert lib.grem_workspace_bytes(0, nnz, k, chunk) == 0
+    # plain route: E, compact labels, the chunk's proposals and small tables
+    w = lib.grem_workspace_bytes(n, k, chunk)
+    assert n * k * 4 + n <= w < n * k * 4 + 2 * n + (1 << 20)
+    w64 = lib.grem_workspace_bytes(n, 64, chunk)
+    assert n * 64 * 4 + n <= w64 < n * 64 * 4 + 2 * n + (1 << 20)
+    # two-phase route: the re-laid-out entries (3 + 2 bytes each) and, taking turns in one region, the 4-byte
+    # intermediate copy and the per-call state; offset tables on top
+    w2 = lib.grem_workspace_bytes_two_phase(n, nnz, k, chunk, None)
+    assert w2 >= n + 9 * nnz and w2 < 20 * n + 9 * nnz + (96 << 20)
+    assert lib.grem_workspace_bytes_two_phase(n, nnz, 64, chunk, None) == w64      # no entry copy above k = 16
+    assert lib.grem_workspace_bytes(0, k, chunk) == 0
+    assert lib.grem_workspace_bytes_two_phase(0, nnz, k, chunk, None) == 0
+    # the bench workload: less than three times the 13.7 GB of its CSR
+    assert lib.grem_workspace_bytes_two_phase(111_000_000, 3_193_913_564, 16, 1 << 20, None) < 40e9
     lib.grem_status_string.restype = ctypes.c_char_p
     assert lib.grem_status_string(0) == b"ok"
     assert b"seed" in lib.grem_status_string(-5)

@@ -25,11 +25,10 @@ N, M, K, SLACK, CHUNK = 111_000_000, 1_600_000_000, 16, 1.05, 1 << 20
 @pytest.fixture(scope="module")
 def graph():
     g = synth.chung_lu(N, M, gamma=2.1, cap=50_000.0, seed=0, device=DEV, rowptr_dtype=torch.int64)
-    ws = torch.empty(B.grem_workspace_bytes(g.n, g.nnz, K, CHUNK), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(B.grem_workspace_bytes_two_phase(g.n, g.nnz, K, CHUNK), dtype=torch.uint8, device=DEV)
     B.grem_set_workspace(ws)
     yield g
     B.grem_set_workspace(None)
-    B.grem_set_histogram_mode(B.HIST_AUTO)
 
 
 def _prefix_oracle(g, chunks):
@@ -53,13 +52,11 @@ def test_first_chunks_of_pass0_equal_the_oracle(graph):
     olab, oest = _prefix_oracle(g, chunks)
     rows = chunks * CHUNK
     for mode in (B.HIST_AUTO, B.HIST_LDS):
-        B.grem_set_histogram_mode(mode)
-        lab, sizes, est = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 0)
+        lab, sizes, est = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 0, options=B.options(mode))
         torch.cuda.synchronize()
         assert np.array_equal(lab[:rows].cpu().numpy(), olab), f"mode {mode}"
         assert np.array_equal(est[:rows].cpu().numpy().view(np.uint32), oest), f"mode {mode}"
         del lab, sizes, est
-    B.grem_set_histogram_mode(B.HIST_AUTO)
 
 
 def test_seeded_first_chunks_of_pass0_equal_the_oracle(graph):
@@ -91,13 +88,11 @@ def test_seeded_first_chunks_of_pass0_equal_the_oracle(graph):
     # one refinement pass on top: the two-phase path and the plain path agree on the whole seeded run
     outs = []
     for mode in (B.HIST_AUTO, B.HIST_LDS):
-        B.grem_set_histogram_mode(mode)
         lab, sizes, _ = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 1, seed_d,
-                                               want_estimates=False)
+                                               want_estimates=False, options=B.options(mode))
         torch.cuda.synchronize()
         assert torch.equal(torch.bincount(lab, minlength=K), sizes)
         outs.append(lab)
-    B.grem_set_histogram_mode(B.HIST_AUTO)
     assert torch.equal(outs[0], outs[1])
 
 
@@ -108,16 +103,14 @@ def test_three_pass_run_properties_and_path_agreement(graph):
     outs = []
     for mode in (B.HIST_AUTO, B.HIST_AUTO, B.HIST_LDS):
         print(f"[case] full-size 3-pass run, mode {mode}", flush=True)
-        B.grem_set_histogram_mode(mode)
         lab, sizes, _ = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 2,
-                                               want_estimates=False)
+                                               want_estimates=False, options=B.options(mode))
         cut = B.grem_edge_cut(g.rowptr, g.colidx, g.n, lab)
         torch.cuda.synchronize()
         assert int(lab.min()) >= 0 and int(lab.max()) < K
         cnt = torch.bincount(lab, minlength=K)
         assert torch.equal(cnt, sizes) and int(cnt.max()) <= P and int(cnt.sum()) == g.n
         outs.append((lab, int(cut.item())))
-    B.grem_set_histogram_mode(B.HIST_AUTO)
     assert torch.equal(outs[0][0], outs[1][0])          # same bytes on repeat
     assert torch.equal(outs[0][0], outs[2][0])          # column-sliced path == plain path
     assert outs[0][1] == outs[2][1]

@@ -24,12 +24,10 @@ HUB_DEGREE = 2_000_000
 @pytest.fixture(scope="module")
 def graph():
     g = synth.hub_stress(24, 16, hubs=64, hub_degree=HUB_DEGREE, seed=0, device=DEV, rowptr_dtype=torch.int32)
-    ws = torch.empty(B.grem_workspace_bytes(g.n, g.nnz, K, CHUNK), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(B.grem_workspace_bytes_two_phase(g.n, g.nnz, K, CHUNK), dtype=torch.uint8, device=DEV)
     B.grem_set_workspace(ws)
     yield g
     B.grem_set_workspace(None)
-    B.grem_set_histogram_mode(B.HIST_AUTO)
-    B.grem_set_long_row_degree(0)
 
 
 def test_first_chunks_of_pass0_equal_the_oracle(graph):
@@ -53,14 +51,12 @@ def test_first_chunks_of_pass0_equal_the_oracle(graph):
     olab, oest = st.labels()[:rows].copy(), st.estimates()[:rows].copy()
     st.close()
     for mode, long_deg in ((B.HIST_AUTO, 0), (B.HIST_GLOBAL, 0)):
-        B.grem_set_histogram_mode(mode)
-        B.grem_set_long_row_degree(long_deg)
-        lab, sizes, est = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 0)
+        lab, sizes, est = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, 0,
+                                                 options=B.options(mode, long_row_degree=long_deg))
         torch.cuda.synchronize()
         assert np.array_equal(lab[:rows].cpu().numpy(), olab), f"mode {mode}"
         assert np.array_equal(est[:rows].cpu().numpy().view(np.uint32), oest), f"mode {mode}"
         del lab, sizes, est
-    B.grem_set_histogram_mode(B.HIST_AUTO)
 
 
 def test_four_pass_run_properties_and_route_agreement(graph):
@@ -72,17 +68,14 @@ def test_four_pass_run_properties_and_route_agreement(graph):
                                  (B.HIST_AUTO, 2**31 - 1, "LDS histograms, nothing split off"),
                                  (B.HIST_GLOBAL, 0, "histograms in E's rows")):
         print(f"[case] hub workload 4-pass run: {what}", flush=True)
-        B.grem_set_histogram_mode(mode)
-        B.grem_set_long_row_degree(long_deg)
-        lab, sizes, _ = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, R, want_estimates=False)
+        lab, sizes, _ = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, R, want_estimates=False,
+                                               options=B.options(mode, long_row_degree=long_deg))
         cut = B.grem_edge_cut(g.rowptr, g.colidx, g.n, lab)
         torch.cuda.synchronize()
         assert int(lab.min()) >= 0 and int(lab.max()) < K
         cnt = torch.bincount(lab, minlength=K)
         assert torch.equal(cnt, sizes) and int(cnt.max()) <= P and int(cnt.sum()) == g.n
         outs.append((lab, int(cut.item())))
-    B.grem_set_histogram_mode(B.HIST_AUTO)
-    B.grem_set_long_row_degree(0)
     assert torch.equal(outs[0][0], outs[1][0])
     assert torch.equal(outs[0][0], outs[2][0])
     assert outs[0][1] == outs[1][1] == outs[2][1]

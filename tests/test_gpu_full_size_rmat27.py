@@ -22,12 +22,10 @@ K, SLACK, CHUNK, R = 32, 1.03, 1 << 22, 1
 @pytest.fixture(scope="module")
 def graph():
     g = synth.rmat(27, 32, seed=0, device=DEV, rowptr_dtype=torch.int64)
-    ws = torch.empty(B.grem_workspace_bytes(g.n, g.nnz, K, CHUNK), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(B.grem_workspace_bytes_two_phase(g.n, g.nnz, K, CHUNK), dtype=torch.uint8, device=DEV)
     B.grem_set_workspace(ws)
     yield g
     B.grem_set_workspace(None)
-    B.grem_set_histogram_mode(B.HIST_AUTO)
-    B.grem_set_long_row_degree(0)
 
 
 def test_first_chunks_of_pass0_equal_the_oracle(graph):
@@ -70,17 +68,14 @@ def test_two_pass_run_properties_and_route_agreement(graph):
     for mode, long_deg, what in ((B.HIST_AUTO, 0, "LDS histograms, long rows split off"),
                                  (B.HIST_GLOBAL, 2**31 - 1, "histograms in E's rows, nothing split off")):
         print(f"[case] rmat-27 2-pass run: {what}", flush=True)
-        B.grem_set_histogram_mode(mode)
-        B.grem_set_long_row_degree(long_deg)
-        lab, sizes, _ = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, R, want_estimates=False)
+        lab, sizes, _ = B.grem_partition_state(g.rowptr, g.colidx, g.n, K, SLACK, CHUNK, R, want_estimates=False,
+                                               options=B.options(mode, long_row_degree=long_deg))
         cut = B.grem_edge_cut(g.rowptr, g.colidx, g.n, lab)
         torch.cuda.synchronize()
         assert int(lab.min()) >= 0 and int(lab.max()) < K
         cnt = torch.bincount(lab, minlength=K)
         assert torch.equal(cnt, sizes) and int(cnt.max()) <= P and int(cnt.sum()) == g.n
         outs.append((lab, int(cut.item())))
-    B.grem_set_histogram_mode(B.HIST_AUTO)
-    B.grem_set_long_row_degree(0)
     assert torch.equal(outs[0][0], outs[1][0])
     assert outs[0][1] == outs[1][1]
     assert outs[0][1] / g.nnz < 31 / 32         # better than a random 32-way split

@@ -32,19 +32,10 @@ def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO
           f"seeded={seed is not None} rowptr={rowptr_dtype} mode={mode}", flush=True)
     rp, ci = _to_dev(g, rowptr_dtype)
     seed_d = None if seed is None else torch.as_tensor(seed).to(DEV)
-    B.grem_set_histogram_mode(mode)
-    B.grem_set_sweep_col_bits(col_bits)
-    B.grem_set_sweep_hub_degree(hub_degree)
-    B.grem_set_long_row_degree(long_row_degree)
-    try:
-        lab, sizes, est = B.grem_partition_state(rp, ci, g.n, k, slack, chunk, R, seed_d)
-        cut = B.grem_edge_cut(rp, ci, g.n, lab)
-        torch.cuda.synchronize()
-    finally:
-        B.grem_set_histogram_mode(B.HIST_AUTO)
-        B.grem_set_sweep_col_bits(0)
-        B.grem_set_sweep_hub_degree(2048)
-        B.grem_set_long_row_degree(0)
+    opts = B.options(mode, col_bits, hub_degree, long_row_degree)
+    lab, sizes, est = B.grem_partition_state(rp, ci, g.n, k, slack, chunk, R, seed_d, options=opts)
+    cut = B.grem_edge_cut(rp, ci, g.n, lab)
+    torch.cuda.synchronize()
     olab, osizes, oest = oracle.partition_seeded(g.rowptr, g.colidx, g.n, k, slack, chunk, R, seed,
                                                  return_state=True)
     lab_h = lab.cpu().numpy()
@@ -103,6 +94,10 @@ def test_single_chunk_spill_closed_form(k, slack):
     v = np.arange(g.n)
     expect = np.zeros(g.n, dtype=np.int64) if k == 1 else np.where(v < P, 0, 1 + (v - P) % max(k - 1, 1))
     assert lab.tolist() == expect.tolist()
+    # the largest representable chunk size is the same single chunk
+    assert _check(g, k, slack, 2**63 - 1, 1).shape == lab.shape
+    if k <= 16:
+        assert _check(g, k, slack, 2**63 - 1, 0, mode=B.HIST_SWEEP, hub_degree=20).tolist() == expect.tolist()
 
 
 @pytest.mark.parametrize("n,k,slack,chunk", [(1000, 4, 1.05, 64), (997, 7, 1.0, 100), (4096, 16, 1.05, 1000),
@@ -166,13 +161,19 @@ def test_two_phase_path_big_hub():
 def test_two_phase_path_errors():
     g = synth.random_graph_np(100, 300, 0)
     rp, ci = _to_dev(g)
-    B.grem_set_histogram_mode(B.HIST_SWEEP)
-    try:
+    with pytest.raises(B.GremError) as e:
+        B.grem_partition(rp, ci, g.n, 17, 1.05, 10, 1, options=B.options(B.HIST_SWEEP))
+    assert e.value.code == B.ERR_ARG
+    for bad in (B.options(histogram_mode=7), B.options(col_bits=3), B.options(col_bits=19), B.options(hub_degree=-1),
+                B.options(hub_degree=65536), B.options(long_row_degree=-5)):
         with pytest.raises(B.GremError) as e:
-            B.grem_partition(rp, ci, g.n, 17, 1.05, 10, 1)
+            B.grem_partition(rp, ci, g.n, 4, 1.05, 10, 1, options=bad)
         assert e.value.code == B.ERR_ARG
-    finally:
-        B.grem_set_histogram_mode(B.HIST_AUTO)
+    bad = B.options()
+    bad.reserved[2] = 1
+    with pytest.raises(B.GremError) as e:
+        B.grem_partition(rp, ci, g.n, 4, 1.05, 10, 1, options=bad)
+    assert e.value.code == B.ERR_ARG
 
 
 def test_rmat_ragged_chunks_and_tiles():
@@ -240,11 +241,23 @@ def test_determinism_and_workspace():
     g = synth.rmat(16, 16, seed=5, device=DEV, rowptr_dtype=torch.int32)
     k, chunk = 16, 5000
     a = B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2)
-    ws = torch.empty(B.grem_workspace_bytes(g.n, g.nnz, k, chunk), dtype=torch.uint8, device=DEV)
+    sweep = B.options(B.HIST_SWEEP, col_bits=10, hub_degree=300)
+    small_ws, big_ws = B.grem_workspace_bytes(g.n, k, chunk), B.grem_workspace_bytes_two_phase(g.n, g.nnz, k, chunk, sweep)
+    assert 0 < small_ws < big_ws
+    ws = torch.empty(big_ws, dtype=torch.uint8, device=DEV)
     B.grem_set_workspace(ws)
     try:
         b = B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2)
         c = B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2)
+        # the two-phase route inside the same workspace, and refused in one that only holds the plain route
+        d = B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2, options=sweep)
+        assert torch.equal(a, d)
+        B.grem_set_workspace(ws[:small_ws])
+        e_ = B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2)
+        assert torch.equal(a, e_)
+        with pytest.raises(B.GremError) as e:
+            B.grem_partition(g.rowptr, g.colidx, g.n, k, 1.05, chunk, 2, options=sweep)
+        assert e.value.code == B.ERR_NOMEM
         small = torch.empty(1024, dtype=torch.uint8, device=DEV)
         B.grem_set_workspace(small)
         with pytest.raises(B.GremError) as e:
