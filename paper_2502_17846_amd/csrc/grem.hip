@@ -271,6 +271,7 @@ struct PlanData {
     size_t slots = 0;
     unsigned long long maxdeg = 0, hub_entries = 0, total_hubs = 0, max_chunk_hubs = 0;
     bool have_degrees = false;              // maxdeg and nnz have been read back
+    std::vector<uint32_t> nvs;              // hub shares per chunk (host copy of pl.ch_nvs)
     int share_hubs = 0;
     int max_k = 0;                          // largest k whose score workgroups fit the LDS
     size_t lookup_lds = 0;
@@ -285,14 +286,14 @@ struct PlanDims {
     size_t G;                       // slices of all chunks
     size_t hubs;                    // hubs of all chunks (or a bound)
     int npr, nps;
+    int nr;                         // rows per chunk: slices, then the most hub shares any chunk has
     size_t slots;
 };
 
-size_t plan_slots(int64_t nnz, const TpGeom &geo) {
-    // every sub-segment is padded to a multiple of 4 tuples, every segment to a multiple of 8
-    const size_t segs = (size_t)geo.nch * (size_t)geo.nblk;
-    const size_t rows = (size_t)geo.nch * ((size_t)geo.nsl + 1);
-    return (size_t)(nnz > 0 ? nnz : 0) + 6 * rows * (size_t)geo.nblk + 8 * segs;
+size_t plan_slots(int64_t nnz, const TpGeom &geo, int nr) {
+    // every sub-segment is padded to a multiple of kSubPad tuples
+    const size_t subs = (size_t)geo.nch * (size_t)nr * (size_t)geo.nblk;
+    return (size_t)(nnz > 0 ? nnz : 0) + (kSubPad - 1) * subs;
 }
 
 void plan_stage1(Carver &c, const PlanDims &d, SweepPlan &pl, u64 *&pmisc) {
@@ -323,11 +324,11 @@ void plan_stage2(Carver &c, const PlanDims &d, SweepPlan &pl) {
 
 void plan_stage3(Carver &c, const PlanDims &d, TpTables &tb, uint32_t *&T, uint16_t *&R) {
     const size_t segs = (size_t)d.geo.nch * (size_t)d.geo.nblk;
-    const size_t rows = (size_t)d.geo.nch * ((size_t)d.geo.nsl + 1);
-    c.take(tb.subR, rows * (size_t)d.geo.nblk);
-    c.take(tb.subH, rows * (size_t)d.geo.nblk);
-    c.take(tb.xstart, segs + 1);
+    const size_t rows = (size_t)d.geo.nch * (size_t)d.nr;
+    c.take(tb.ta, segs * ((size_t)d.nr + 1));
+    c.take(tb.dd, segs * (size_t)d.nr);
     c.take(tb.tstart, segs + 1);
+    c.take(tb.sstart, rows + 1);
     c.take(tb.lo, d.G * (size_t)d.npr * ((size_t)d.geo.ngroups + 1));
     c.take(tb.loh, d.G * (size_t)d.nps * ((size_t)d.geo.ngroups + 1));
     c.take(tb.ustart, d.G * (size_t)d.npr);
@@ -402,7 +403,10 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
         hipLaunchKernelGGL(k_plan_shares, dim3((G + 255) / 256), dim3(256), 0, stream, n, cl, nsl, (int)G, pl,
                            P.pmisc);
     });
+    P.nvs.assign((size_t)geo.nch, 0u);
     if (P.total_hubs != 0) {
+        if (hipMemcpyAsync(P.nvs.data(), pl.ch_nvs, (size_t)geo.nch * 4, hipMemcpyDeviceToHost, stream) != hipSuccess)
+            return GREM_ERR_HIP;
         if (!L.read_back(h, P.pmisc, sizeof(h))) return L.err;
     } else if (L.err) {
         return L.err;
@@ -420,8 +424,10 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
         int max_k = k ? k : kSweepMaxK;
         while (max_k > 1 && !score_fits(max_k) && k == 0) --max_k;
         P.max_k = max_k;
+        // (the index of a word of Lx -- eight labels -- travels in 32 bits of T)
         const bool fits = score_fits(max_k) && share_hubs <= kMaxShareHubs &&
-                          h[7] + 8ull * ((unsigned long long)geo.nsl + 2) * geo.nblk < (1ull << 32);
+                          plan_slots(P.nnz, geo, 2 * geo.nsl) < (1ull << 35) &&
+                          h[7] + 8ull * (2ull * (unsigned long long)geo.nsl + 2) * geo.nblk < (1ull << 32);
         if (!fits) return strict ? GREM_ERR_ARG : GREM_OK;
     }
 
@@ -459,7 +465,9 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
     }
     d.npr = npr;
     d.nps = nps;
-    d.slots = plan_slots(P.nnz, geo);
+    const unsigned max_shares = (unsigned)h[11];            // no chunk has more hub shares than this
+    d.nr = geo.nsl + (int)max_shares;
+    d.slots = plan_slots(P.nnz, geo, d.nr);
     P.slots = d.slots;
     if (!carve(keep, [&](Carver &c) { plan_stage3(c, d, tb, P.T, P.R); })) { P.T = nullptr; return GREM_ERR_NOMEM; }
     tb.chunk = geo.chunk;
@@ -475,6 +483,7 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
     }
     tb.nch = geo.nch;
     tb.nsl = geo.nsl;
+    tb.nr = d.nr;
     tb.nbc = geo.nbc;
     tb.nblk = geo.nblk;
     tb.cb = geo.cb;
@@ -486,8 +495,10 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
     P.lookup_target = P.lookup_lds > 80 * 1024 ? 256 : 512;
 
     const Arena::Mark tmark = temp.mark();
+    const size_t subs = (size_t)geo.nch * (size_t)d.nr * (size_t)geo.nblk;
     uint32_t *U = (uint32_t *)temp.alloc((size_t)(P.nnz > 0 ? P.nnz : 0) * 4 + 16);
-    if (!U) { P.T = nullptr; return GREM_ERR_NOMEM; }
+    tb.cnt = U ? (uint32_t *)temp.alloc(subs * 4) : nullptr;
+    if (!U || !tb.cnt) { temp.release_to(tmark); P.T = nullptr; return GREM_ERR_NOMEM; }
     const u64 hub_base = (u64)P.nnz - P.hub_entries;        // U: the regular entries, then the hub streams
 
     const uint32_t capR = group_cap(false, npr), capS = group_cap(true, nps);
@@ -499,13 +510,10 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
     if (batch > 8) batch = 8;
     if (batch < 1) batch = 1;
     const int maxruns = batch * (npr > nps ? npr : nps);
-    const size_t place_fixed = (2 * (size_t)nbg + maxruns) * 8 +
-                               ((size_t)2 * maxruns + 1 + 2 * (size_t)nbg + 1 + (size_t)batch * nbg) * 4;
+    const size_t place_fixed = tp_place_fixed_bytes(nbg, batch, maxruns);
     const uint32_t capP = (uint32_t)(kPlaceLds > place_fixed ? (kPlaceLds - place_fixed) / 4 : 0);
     const size_t place_lds = place_fixed + (size_t)capP * 4;
-    const size_t rows = (size_t)geo.nch * ((size_t)geo.nsl + 1);
-    L.memset(tb.subR, 0, rows * (size_t)geo.nblk * 4);
-    L.memset(tb.subH, 0, rows * (size_t)geo.nblk * 4);
+    L.memset(tb.cnt, 0, subs * 4);
     if (L.err || !set_lds((const void *)k_tp_group<RowT, false>, groupR_lds) ||
         !set_lds((const void *)k_tp_group<RowT, true>, groupS_lds) ||
         !set_lds((const void *)k_tp_place, place_lds)) {
@@ -519,19 +527,22 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
                            rowptr, colidx, n, (uint32_t)hub_degree, pl, tb, share_hubs, capR, (int)nsl, U, hub_base);
     });
     // shares: no chunk has more than max_shares of them (none at all: nothing to launch)
-    const unsigned max_shares = (unsigned)h[11];
     if (max_shares != 0)
         L.run(GREM_KERNEL_RELAYOUT, [&] {
             hipLaunchKernelGGL((k_tp_group<RowT, true>), dim3((unsigned)geo.nch * max_shares * (unsigned)nps),
                                dim3(kTpThreads), groupS_lds, stream, rowptr, colidx, n, (uint32_t)hub_degree, pl, tb,
                                share_hubs, capS, (int)max_shares, U, hub_base);
         });
+    const unsigned rows_all = (unsigned)((int64_t)geo.nch * d.nr);
     L.run(GREM_KERNEL_RELAYOUT, [&] {
-        hipLaunchKernelGGL(k_tp_scan_slices, dim3((segs + 255) / 256), dim3(256), 0, stream, tb);
+        hipLaunchKernelGGL(k_tp_scan_t, dim3((segs + 255) / 256), dim3(256), 0, stream, tb);
     });
     L.run(GREM_KERNEL_RELAYOUT, [&] {
-        hipLaunchKernelGGL(k_tp_scan, dim3(2), dim3(1024), 0, stream, tb.xstart, (int64_t)segs, tb.tstart, (int64_t)segs,
-                           (u64 *)nullptr, (int64_t)0);
+        hipLaunchKernelGGL(k_tp_scan_d, dim3((rows_all + 255) / 256), dim3(256), 0, stream, tb);
+    });
+    L.run(GREM_KERNEL_RELAYOUT, [&] {
+        hipLaunchKernelGGL(k_tp_scan, dim3(2), dim3(1024), 0, stream, tb.tstart, (int64_t)segs, tb.sstart,
+                           (int64_t)rows_all, (u64 *)nullptr, (int64_t)0);
     });
     L.run(GREM_KERNEL_RELAYOUT, [&] {
         hipLaunchKernelGGL(k_tp_place, dim3((unsigned)((int64_t)geo.ngroups * geo.nch)), dim3(kPlaceThreads), place_lds,
@@ -678,8 +689,8 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
     const size_t score_lds = ((size_t)kSliceRows / 2 + (size_t)P.share_hubs * k + 3 * (size_t)k) * 4;
     if (!set_lds((const void *)k_tp_lookup<true, false>, P.lookup_lds) ||
         !set_lds((const void *)k_tp_lookup<true, true>, P.lookup_lds) ||
-        !set_lds((const void *)k_tp_score<RowT, uint32_t>, score_lds) ||
-        !set_lds((const void *)k_tp_score<RowT, uint16_t>, score_lds))
+        !set_lds((const void *)k_tp_score<uint32_t>, score_lds) ||
+        !set_lds((const void *)k_tp_score<uint16_t>, score_lds))
         return GREM_ERR_HIP;
     L.memset(t.Hhub, 0, ((size_t)P.max_chunk_hubs + 1) * (size_t)k * 4);
 
@@ -730,15 +741,15 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             const uint16_t *rows_now = (seed && pass == 0) ? t.Rdyn : P.R;
             L.run(GREM_KERNEL_SCORE, [&] {
                 if (use16)
-                    hipLaunchKernelGGL((k_tp_score<RowT, uint16_t>), dim3(blocks), dim3(kTpThreads), score_lds, stream,
-                                       rowptr, rows_now, t.Lx, tb, pl, (const uint8_t *)st.Lc, st.S, t.E16, t.Hhub,
+                    hipLaunchKernelGGL((k_tp_score<uint16_t>), dim3(blocks), dim3(kTpThreads), score_lds, stream,
+                                       rows_now, t.Lx, tb, pl, (const uint8_t *)st.Lc, st.S, t.E16, t.Hhub,
                                        (uint8_t *)st.prop, st.cnt, st.room, (int)c, lo, hi, (int)k, jlim, P.share_hubs,
-                                       (uint32_t)hub_degree, pass, cap, store_e);
+                                       P.nvs[(size_t)c], pass, cap, store_e);
                 else
-                    hipLaunchKernelGGL((k_tp_score<RowT, uint32_t>), dim3(blocks), dim3(kTpThreads), score_lds, stream,
-                                       rowptr, rows_now, t.Lx, tb, pl, (const uint8_t *)st.Lc, st.S, E32, t.Hhub,
+                    hipLaunchKernelGGL((k_tp_score<uint32_t>), dim3(blocks), dim3(kTpThreads), score_lds, stream,
+                                       rows_now, t.Lx, tb, pl, (const uint8_t *)st.Lc, st.S, E32, t.Hhub,
                                        (uint8_t *)st.prop, st.cnt, st.room, (int)c, lo, hi, (int)k, jlim, P.share_hubs,
-                                       (uint32_t)hub_degree, pass, cap, store_e);
+                                       P.nvs[(size_t)c], pass, cap, store_e);
             });
             // (one workgroup more than the hubs need: it adds up the chunk's mover counts)
             L.run(GREM_KERNEL_HUBS, [&] {
@@ -1036,7 +1047,13 @@ size_t grem_workspace_bytes_two_phase(int64_t n, int64_t nnz, int32_t k, int64_t
     if (d.hubs > (size_t)n) d.hubs = (size_t)n;
     d.npr = kMaxParts;
     d.nps = kMaxParts;
-    d.slots = plan_slots(nnz, geo);
+    {   // a chunk has at most one hub share per 64 * nblk hub entries (and at least one per 1024 hubs), never
+        // more than slices
+        size_t shares = (size_t)nnz / (64 * (size_t)geo.nblk) + d.hubs / 1024 + 1;
+        if (shares > (size_t)geo.nsl) shares = (size_t)geo.nsl;
+        d.nr = geo.nsl + (int)shares;
+    }
+    d.slots = plan_slots(nnz, geo, d.nr);
     SweepPlan pl{};
     TpTables tb{};
     u64 *pm = nullptr;
@@ -1050,7 +1067,7 @@ size_t grem_workspace_bytes_two_phase(int64_t n, int64_t nnz, int32_t k, int64_t
     total += carve_size([&](Carver &c) { plan_stage3(c, d, tb, T, R); });
     // the intermediate copy and the per-call state take turns in one region; the state is largest for a
     // seeded run whose estimates need 32 bits
-    const size_t temp = align_up((size_t)nnz * 4 + 16);
+    const size_t temp = align_up((size_t)nnz * 4 + 16) + align_up((size_t)geo.nch * (size_t)d.nr * (size_t)geo.nblk * 4);
     const size_t chunk_hubs = d.hubs < (size_t)cl ? d.hubs : (size_t)cl;
     const size_t s16 = carve_size([&](Carver &c) { state_two_phase(c, t, n, k, d.slots, chunk_hubs, d.hubs, true, true, false); });
     const size_t s32 = carve_size([&](Carver &c) { state_two_phase(c, t, n, k, d.slots, chunk_hubs, d.hubs, true, false, false); });

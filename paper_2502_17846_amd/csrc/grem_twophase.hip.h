@@ -9,35 +9,35 @@
 // chunk, by workgroups that hold those labels in LDS -- for every row that refers to them, in this
 // pass (rows of later chunks) or the next (rows of earlier chunks and of the chunk itself).
 //
-// How: once per call the CSR entries are re-laid-out into tuples (row in slice, column in block),
-// grouped by (column block, row chunk):
+// How: once per graph the CSR entries are re-laid-out into tuples (row in slice, column in block):
 //   * a column block is 2^cb consecutive vertices counted from the start of their chunk;
 //   * a row slice is 2048 consecutive rows counted from the start of their chunk;
-//   * segment (c, jb) holds the entries of the rows of chunk c whose column lies in block jb:
-//     first the entries of the regular rows, slice by slice, then the entries of the chunk's
-//     high-degree rows ("hubs"), share by share (see below).
+//   * rows of degree >= hub_degree ("hubs") are taken out of their slice: the chunk's hub entries,
+//     concatenated in row order, are cut in equal shares (k_plan_chunks picks how many);
+//   * a "row" r of chunk c is slice r (r < nsl) or share r - nsl; there are nr = nsl + (the largest
+//     number of shares of any chunk) rows per chunk;
+//   * sub-segment (c, r, jb) holds the tuples of row r of chunk c whose column lies in block jb,
+//     padded to a multiple of 8 tuples.
 // A tuple lives in three streams, each with as few bytes as its reader needs:
-//   T  : its column in the block, 3 bytes, segments ordered (jb, c)   -- read by k_tp_lookup
-//   Lx : the label of that column, 4 bits, segments ordered (c, jb)   -- written by k_tp_lookup,
-//                                                                        read by k_tp_score
+//   T  : its column in the block, 3 bytes; sub-segments ordered (jb, c, r): all tuples that refer
+//        to one column block are contiguous                            -- read by k_tp_lookup
+//   Lx : the label of that column, 4 bits; sub-segments ordered (c, r, jb): all tuples of one row
+//        slice are contiguous                    -- written by k_tp_lookup, read by k_tp_score
 //   R  : its row in the slice << 5, 16 bits (bit 0 = padding), ordered like Lx; written once by the
 //        re-layout, read by k_tp_score (row << 5 is the byte offset of the row's 16-bit counters)
-// A segment occupies the same number of slots in all three, padded to a multiple of 8; every
-// sub-segment is padded to a multiple of 4.  After chunk c has been relabelled, k_tp_lookup streams
-// the columns of c's column blocks (contiguous in T), looks the labels up in an LDS copy of the
-// block's labels (two per byte) and writes Lx (contiguous per segment).  Before chunk c is
-// relabelled, k_tp_score has one workgroup per row slice gather that slice's sub-segment from
-// every segment (c, *) -- each a few hundred bytes, contiguous -- into 16-bit LDS counters, then
-// blends E and proposes.  (Seeded runs: in their first pass a neighbour may be unassigned; the
-// score kernel then reads the row fields from a copy of R in which bit 0 marks such tuples.)
+// After chunk c has been relabelled, k_tp_lookup streams the columns of c's column blocks
+// (contiguous in T), looks the labels up in an LDS copy of the block's labels (two per byte) and
+// writes them to Lx, sub-segment by sub-segment (each a contiguous piece of some 40 bytes).  Before
+// chunk c is relabelled, k_tp_score has one workgroup per row slice stream that slice's tuples -- one
+// contiguous piece of R and of Lx -- into 16-bit LDS counters, then blends E and proposes.  (Seeded
+// runs: in their first pass a neighbour may be unassigned; the score kernel then reads the row
+// fields from a copy of R in which bit 0 marks such tuples.)
 //
-// Balance: rows of degree >= hub_degree are taken out of their slice.  Their entries,
-// concatenated in row order, are cut in equal shares (k_plan_chunks picks how many); every
-// workgroup of k_tp_score also counts one share's sub-segments of some of the column blocks
-// (32-bit counters per hub touched), so that each gets the same part of the hub entries, and adds
-// its partial counts to a per-chunk table in global memory with integer atomics; k_hub_finalize
-// then blends and proposes for the hubs.  The order of entries inside a sub-segment and the order of the atomic
-// adds are arbitrary; all of it is integer sums, so the result is not.
+// Balance: every workgroup of k_tp_score also counts an equal part of one hub share's stream (32-bit
+// counters per hub the share touches) and adds its partial counts to a per-chunk table in global
+// memory with integer atomics; k_hub_finalize then blends and proposes for the hubs.  The order of
+// entries inside a sub-segment and the order of the atomic adds are arbitrary; all of it is integer
+// sums, so the result is not.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -85,13 +85,17 @@ struct SweepPlan {
     u64 *hub_off;
 };
 
-// Geometry and offset tables of the re-laid-out entries.
+// Geometry and offset tables of the re-laid-out entries.  A sub-segment's length is its tuple count
+// rounded up to a multiple of kSubPad.
+constexpr uint32_t kSubPad = 8;
+
 struct TpTables {
-    uint32_t *subR;   // [nch * (nsl + 1)][nblk]: start of slice i's regular sub-segment inside segment
-                      // (c, jb), row c * (nsl + 1) + i; row i = nsl: end of the regular part
-    uint32_t *subH;   // same shape: start of share i's sub-segment; row nsl: end of the segment
-    u64 *xstart;      // [nch][nblk] (+1): first slot of segment (c, jb) in Lx and R
-    u64 *tstart;      // [nblk][nch] (+1): first slot of segment (c, jb) in T
+    uint32_t *cnt;    // [nch][nr][nblk]: tuples of sub-segment (c, r, jb) (re-layout only)
+    uint32_t *ta;     // [nblk][nch][nr + 1]: start of sub-segment (c, r, jb) inside segment (jb, c) of T;
+                      // entry nr: the segment's length
+    uint32_t *dd;     // [nblk][nch][nr]: start of sub-segment (c, r, jb) inside row stream (c, r) of Lx / R
+    u64 *tstart;      // [nblk][nch] (+1): first slot of segment (jb, c) in T
+    u64 *sstart;      // [nch][nr] (+1): first slot of row stream (c, r) in Lx and R
     uint32_t *lo;     // [nch * nsl * npr][ngroups + 1]: start of block group g's run inside the unit's range of U
     uint32_t *loh;    // [nch * nsl * nps][ngroups + 1]: the same for the parts of the hub shares
     u64 *ustart;      // [nch * nsl * npr]: first tuple of a slice part's range of U (regular entries, compacted)
@@ -105,6 +109,7 @@ struct TpTables {
     uint32_t chunk_magic, chunk_magic_shift;   // u / chunk = mulhi(u, magic) >> shift for every u < 2^31
     int nch;          // chunks
     int nsl;          // row slices per chunk
+    int nr;           // rows (slices, then hub shares) per chunk
     int nbc;          // column blocks per chunk
     int nblk;         // nch * nbc
     int cb;           // log2 of the vertices per column block
@@ -514,8 +519,7 @@ __device__ __host__ inline size_t tp_source_words(bool share, int np, int share_
 // ------------------------------------------------------------------------------------------------
 // Re-layout, step 1 (one unit per workgroup, blockIdx.x = (c * per_chunk + i) * np + q, per_chunk
 // being nsl for slices and the largest number of shares of a chunk for shares): count the unit's
-// entries per column block (added to subR / subH [row(c,i)][*], which start at zero and become
-// starts in k_tp_scan_slices), and copy its tuples, grouped by column-block GROUP (2^gb consecutive
+// entries per column block (added to cnt[c][row][*], which starts at zero), and copy its tuples, grouped by column-block GROUP (2^gb consecutive
 // blocks), to the unit's own range of U: first the regular entries of all rows in CSR order (the
 // hub rows' entries left out), then, from `hub_base` on, the chunks' hub entry streams.  The range
 // starts at ustart[unit]; run g of the unit starts at lo[unit][g] inside it.  The tuples are collected
@@ -579,7 +583,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
     {
         constexpr int kPer = kMaxBlocks / kTpThreads;
         const int lane = lane_id(), wave = tid >> 6;
-        uint32_t *row_out = (SHARE ? tb.subH : tb.subR) + ((size_t)c * (tb.nsl + 1) + i) * tb.nblk;
+        uint32_t *row_out = tb.cnt + ((size_t)c * tb.nr + (SHARE ? tb.nsl + i : i)) * tb.nblk;
         uint32_t mine[kPer], sum = 0;
 #pragma unroll
         for (int x = 0; x < kPer; ++x) {
@@ -640,25 +644,45 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
 }
 
 // ------------------------------------------------------------------------------------------------
-// counts -> starts.  One thread per segment (c, jb): exclusive prefix over the slices of the
-// regular counts, then of the share counts, every count rounded up to a multiple of 4 (four tuples
-// are 12 bytes of T, 8 of R, 2 of Lx: sub-segments start on 4-byte boundaries of T); the segment length, rounded up to a multiple of 8, goes to xstart and
-// tstart (each in its own order), to be scanned by k_tp_scan.
+// counts -> starts, T side.  One thread per segment (jb, c): exclusive prefix over the chunk's rows of
+// the padded counts -> ta[jb][c][0 .. nr]; the segment's length also goes to tstart[jb][c], to be
+// scanned by k_tp_scan.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_tp_scan_slices(TpTables tb) {
+__global__ __launch_bounds__(256) void k_tp_scan_t(TpTables tb) {
     const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (id >= (int64_t)tb.nch * tb.nblk) return;
     const int c = (int)(id / tb.nblk), jb = (int)(id % tb.nblk);
+    const uint32_t *p = tb.cnt + ((size_t)c * tb.nr) * tb.nblk + jb;
+    uint32_t *out = tb.ta + ((size_t)jb * tb.nch + c) * (tb.nr + 1);
     uint32_t run = 0;
-    uint32_t *p = tb.subR + ((size_t)c * (tb.nsl + 1)) * tb.nblk + jb;
-    for (int i = 0; i < tb.nsl; ++i, p += tb.nblk) { const uint32_t t = (*p + 3u) & ~3u; *p = run; run += t; }
-    *p = run;
-    p = tb.subH + ((size_t)c * (tb.nsl + 1)) * tb.nblk + jb;
-    for (int i = 0; i < tb.nsl; ++i, p += tb.nblk) { const uint32_t t = (*p + 3u) & ~3u; *p = run; run += t; }
-    *p = run;
-    const u64 padded = ((u64)run + 7ull) & ~7ull;
-    tb.xstart[(size_t)c * tb.nblk + jb] = padded;
-    tb.tstart[(size_t)jb * tb.nch + c] = padded;
+    for (int r = 0; r < tb.nr; ++r, p += tb.nblk) { out[r] = run; run += (*p + kSubPad - 1u) & ~(kSubPad - 1u); }
+    out[tb.nr] = run;
+    tb.tstart[(size_t)jb * tb.nch + c] = run;
+}
+
+// ------------------------------------------------------------------------------------------------
+// counts -> starts, Lx / R side.  One thread per row (c, r): exclusive prefix over the column blocks of
+// the padded counts -> dd[jb][c][r]; the row stream's length goes to sstart[c][r], to be scanned.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_tp_scan_d(TpTables tb) {
+    const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= (int64_t)tb.nch * tb.nr) return;
+    const int c = (int)(id / tb.nr), r = (int)(id % tb.nr);
+    const uint32_t *p = tb.cnt + ((size_t)c * tb.nr + r) * tb.nblk;
+    uint32_t *out = tb.dd + (size_t)c * tb.nr + r;
+    const size_t step = (size_t)tb.nch * tb.nr;
+    uint32_t run = 0;
+    for (int jb0 = 0; jb0 < tb.nblk; jb0 += 4) {          // four counts per turn: the loads side by side
+        uint32_t x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u] = jb0 + u < tb.nblk ? p[jb0 + u] : 0u;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (jb0 + u < tb.nblk) out[(size_t)(jb0 + u) * step] = run;
+            run += (x[u] + kSubPad - 1u) & ~(kSubPad - 1u);
+        }
+    }
+    tb.sstart[(size_t)c * tb.nr + r] = run;
 }
 
 // In-place exclusive prefix of a[0..m) by one workgroup, total in a[m]; workgroup b scans array b
@@ -684,17 +708,29 @@ __global__ __launch_bounds__(1024) void k_tp_scan(u64 *__restrict__ a0, int64_t 
 
 // ------------------------------------------------------------------------------------------------
 // Re-layout, step 2: workgroup c * ngroups + g moves the runs of block group g of every unit of
-// chunk c (slice parts, then share parts) from U to their sub-segments, `batch` slices (shares) at a time: the
-// sub-segments of consecutive slices are adjacent, so the tuples of a batch form one piece per block
-// of the group; the pieces are put together in LDS, pad tuples included (row field 2048: the score
-// kernel ignores them; they fill every sub-segment up to a multiple of 4), and written out
-// contiguously, the columns (3 bytes each) to T, the row fields (16 bits each) to R.  A batch that
-// does not fit `cap` slots is cut down to one slice; a slice that does not fit is written tuple by
-// tuple.
-// LDS: tbase[nbg], xbase[nbg] (u64), runsrc[batch * npmax] (u64), runlen[batch * npmax + 1], runsl[batch * npmax],
-//      joff[nbg + 1], s0[nbg], cur[batch * nbg], stage[cap]
+// chunk c (slice parts, then share parts) from U to their sub-segments, `batch` rows (slices, then
+// shares) at a time.  In T the sub-segments of consecutive rows are adjacent, so the tuples of a
+// batch form one piece per block of the group; the pieces are put together in LDS, pad tuples
+// included (row field 2048: the score kernel ignores them; they fill every sub-segment up to a
+// multiple of kSubPad), and written out contiguously: the columns (3 bytes each) to T piece by
+// piece, the row fields (16 bits each) to R sub-segment by sub-segment (in R the sub-segments of one
+// row for consecutive blocks are adjacent).  A batch that does not fit `cap` slots is cut down to one
+// row; a row that does not fit is written tuple by tuple.
+// LDS: tbase[nbg], sbase[batch], runsrc[batch * npmax] (u64), runlen[batch * npmax + 1],
+//      runsl[batch * npmax], joff[nbg + 1], s0[nbg], cur / sub0 / sublen / ddv [batch * nbg], stage[cap]
 // ------------------------------------------------------------------------------------------------
 constexpr int kPlaceThreads = 512;
+
+// Every group of eight tuples of T carries, four bits per tuple above the column, the index of the
+// 32-bit word of Lx (eight labels) its labels go to: the tuple in slot p of R / Lx holds bits
+// 4 (p % 8) .. 4 (p % 8) + 3 of p / 8.
+__device__ __forceinline__ uint32_t tp_dest_nibble(u64 at) {
+    return (uint32_t)((at >> 3) >> (4u * ((uint32_t)at & 7u))) & 15u;
+}
+
+__device__ __host__ inline size_t tp_place_fixed_bytes(int nbg, int batch, int maxruns) {
+    return ((size_t)nbg + batch + maxruns) * 8 + ((size_t)2 * maxruns + 1 + 2 * (size_t)nbg + 1 + 4 * (size_t)batch * nbg) * 4;
+}
 
 __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan pl, TpTables tb,
                                                             const uint32_t *__restrict__ U,
@@ -707,14 +743,17 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
     const int npmax = tb.npr > tb.nps ? tb.npr : tb.nps;
     const int maxruns = batch * npmax;
     u64 *tbase = smem64;                                        // nbg        segment (jb, c) in T
-    u64 *xbase = tbase + nbg;                                   // nbg        segment (c, jb) in R
-    u64 *runsrc = xbase + nbg;                                  // maxruns    first tuple of the run
+    u64 *sbase = tbase + nbg;                                   // batch      row stream (c, r) in R
+    u64 *runsrc = sbase + batch;                                // maxruns    first tuple of the run
     uint32_t *runlen = reinterpret_cast<uint32_t *>(runsrc + maxruns);  // maxruns + 1   tuples in the run
-    uint32_t *runsl = runlen + maxruns + 1;                     // maxruns    slice (in the batch) of the run
+    uint32_t *runsl = runlen + maxruns + 1;                     // maxruns    row (in the batch) of the run
     uint32_t *joff = runsl + maxruns;                           // nbg + 1    start of block j's piece in stage
     uint32_t *s0 = joff + nbg + 1;                              // nbg        start of the piece in the segment
-    uint32_t *cur = s0 + nbg;                                   // batch * nbg  next free slot (in stage)
-    uint32_t *stage = cur + batch * nbg;                        // cap
+    uint32_t *cur = s0 + nbg;                                   // batch * nbg  next free slot of sub-segment (t, j)
+    uint32_t *sub0 = cur + batch * nbg;                         // batch * nbg  its first slot (in stage, or in the segment)
+    uint32_t *sublen = sub0 + batch * nbg;                      // batch * nbg  its padded length
+    uint32_t *ddv = sublen + batch * nbg;                       // batch * nbg  its start in the row stream
+    uint32_t *stage = ddv + batch * nbg;                        // cap
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int kNW = kPlaceThreads / 64, kRU = 4, kXU = 3;
     const int64_t chunk_lo = (int64_t)c * tb.chunk;
@@ -723,29 +762,28 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
     const int nvs = (int)pl.ch_nvs[c];
     const uint32_t gmask = (1u << tb.gb) - 1u, cmask = (1u << tb.cb) - 1u;
     const uint32_t pad = 2048u << tb.cb;
-    for (int j = tid; j < nbg; j += kPlaceThreads) {
-        tbase[j] = tb.tstart[(size_t)(jb0 + j) * tb.nch + c];
-        xbase[j] = tb.xstart[(size_t)c * tb.nblk + jb0 + j];
-    }
+    for (int j = tid; j < nbg; j += kPlaceThreads) tbase[j] = tb.tstart[(size_t)(jb0 + j) * tb.nch + c];
     uint8_t *T8 = reinterpret_cast<uint8_t *>(T);
-    // entry w of segment j, written on its own (the slow way): 3 bytes of T, 2 of R
-    auto put_entry = [&](uint32_t j, uint32_t w, uint32_t tuple) {
-        const uint32_t col = tuple & cmask, row = tuple >> tb.cb;
+    // slot w of sub-segment z = (t, j), written on its own (the slow way): 3 bytes of T, 2 of R
+    auto put_entry = [&](uint32_t j, uint32_t z, uint32_t w, uint32_t tuple) {
+        const uint32_t row = tuple >> tb.cb;
+        const u64 at = sbase[z / (uint32_t)nbg] + ddv[z] + (w - sub0[z]);      // the tuple's slot in R / Lx
+        const uint32_t col = (tuple & cmask) | (tp_dest_nibble(at) << tb.cb);
         uint8_t *t3 = T8 + (tbase[j] + w) * 3ull;
         t3[0] = (uint8_t)col; t3[1] = (uint8_t)(col >> 8); t3[2] = (uint8_t)(col >> 16);
-        R[xbase[j] + w] = (uint16_t)(row >= (uint32_t)kSliceRows ? 1u : row << 5);
+        R[at] = (uint16_t)(row >= (uint32_t)kSliceRows ? 1u : row << 5);
     };
     for (int part = 0; part < 2; ++part) {                      // 0: regular slices, 1: hub shares
         const int count = part == 0 ? nsl_c : nvs;
         const int np = part == 0 ? tb.npr : tb.nps;
-        const uint32_t *sub = (part == 0 ? tb.subR : tb.subH) + ((size_t)c * (tb.nsl + 1)) * tb.nblk + jb0;
+        const int rfirst = part == 0 ? 0 : tb.nsl;              // the part's first row of the chunk
         const uint32_t *lot = part == 0 ? tb.lo : tb.loh;
         const u64 *ust = part == 0 ? tb.ustart : tb.ustart_h;
-        const uint32_t *src = U;
         int i0 = 0;
         while (i0 < count) {
-            // the largest batch (<= `batch` slices) whose pieces fit the stage; at least one slice
+            // the largest batch (<= `batch` rows) whose pieces fit the stage; at least one row
             int nb = count - i0 < batch ? count - i0 : batch;
+            const int r0 = rfirst + i0;
             uint32_t need;
             for (;;) {
                 __syncthreads();                                // previous batch (attempt) done with the LDS tables
@@ -758,9 +796,10 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
                     runsl[z] = (uint32_t)t;
                 }
                 for (int j = tid; j < nbg; j += kPlaceThreads) {
-                    const uint32_t a = sub[(size_t)i0 * tb.nblk + j];
+                    const uint32_t *taj = tb.ta + ((size_t)(jb0 + j) * tb.nch + c) * (tb.nr + 1);
+                    const uint32_t a = taj[r0];
                     s0[j] = a;
-                    joff[j + 1] = sub[(size_t)(i0 + nb) * tb.nblk + j] - a;
+                    joff[j + 1] = taj[r0 + nb] - a;
                 }
                 __syncthreads();
                 if (nbg <= 64) {                                // lengths of the pieces -> their starts in stage
@@ -787,10 +826,16 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
             const bool staged = need <= cap;
             for (int z = tid; z < nb * nbg; z += kPlaceThreads) {
                 const int t = z / nbg, j = z % nbg;
+                const uint32_t *taj = tb.ta + ((size_t)(jb0 + j) * tb.nch + c) * (tb.nr + 1);
+                const uint32_t a = taj[r0 + t], e = taj[r0 + t + 1];
                 // staged: slot in stage; else: slot in the segment
-                const uint32_t a = sub[(size_t)(i0 + t) * tb.nblk + j];
-                cur[z] = staged ? joff[j] + (a - s0[j]) : a;
+                const uint32_t first = staged ? joff[j] + (a - s0[j]) : a;
+                sub0[z] = first;
+                cur[z] = first;
+                sublen[z] = e - a;
+                ddv[z] = tb.dd[((size_t)(jb0 + j) * tb.nch + c) * tb.nr + r0 + t];
             }
+            for (int t = tid; t < nb; t += kPlaceThreads) sbase[t] = tb.sstart[(size_t)c * tb.nr + r0 + t];
             if (staged)
                 for (uint32_t z = tid; z < need; z += kPlaceThreads) stage[z] = pad;
             __syncthreads();
@@ -799,10 +844,11 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
             const int nruns = nb * np;
             auto put = [&](uint32_t u, uint32_t sl) {
                 const uint32_t j = (u >> tb.cb) & gmask;
-                const uint32_t w = atomicAdd(&cur[sl * nbg + j], 1u);
+                const uint32_t z = sl * (uint32_t)nbg + j;
+                const uint32_t w = atomicAdd(&cur[z], 1u);
                 const uint32_t tuple = ((u >> (tb.cb + tb.gb)) << tb.cb) | (u & cmask);
                 if (staged) stage[w] = tuple;
-                else put_entry(j, w, tuple);
+                else put_entry(j, z, w, tuple);
             };
             for (int z0 = wave; z0 < nruns; z0 += kNW * kRU) {
                 uint32_t u[kRU][kXU], len[kRU], sl[kRU];
@@ -814,8 +860,8 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
                     len[r] = z < nruns ? (uint32_t)__builtin_amdgcn_readfirstlane((int)runlen[zz]) : 0u;
                     sl[r] = (uint32_t)__builtin_amdgcn_readfirstlane((int)runsl[zz]);
                     const u64 at = runsrc[zz];
-                    from[r] = src + (((u64)(uint32_t)__builtin_amdgcn_readfirstlane((int)(at >> 32)) << 32) |
-                                     (u64)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)at));
+                    from[r] = U + (((u64)(uint32_t)__builtin_amdgcn_readfirstlane((int)(at >> 32)) << 32) |
+                                   (u64)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)at));
 #pragma unroll
                     for (int x = 0; x < kXU; ++x) {
                         const uint32_t p = (uint32_t)(x * 64 + lane);
@@ -835,37 +881,48 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
             }
             __syncthreads();
             if (staged) {
-                // a piece per wavefront, four tuples (12 bytes of T, 8 of R) per lane; starts and lengths are
-                // multiples of 4 tuples
+                // T: a piece per wavefront, four tuples (12 bytes) per lane; starts and lengths are
+                // multiples of 8 tuples
                 for (int j = wave; j < nbg; j += kNW) {
                     const uint32_t a = joff[j], len4 = (joff[j + 1] - a) >> 2;
                     uint32_t *outT = T + ((tbase[j] + s0[j]) >> 2) * 3ull;
-                    uint32_t *outR = reinterpret_cast<uint32_t *>(R + xbase[j] + s0[j]);
                     for (uint32_t z = lane; z < len4; z += 64) {
-                        uint32_t col[4], row[4];
+                        // the row of the batch whose sub-segment holds these four tuples, and their slots in R / Lx
+                        const uint32_t x = a + 4 * z;
+                        int t = 0;
+                        while (t + 1 < nb && x >= sub0[(t + 1) * nbg + j]) ++t;
+                        const u64 at = sbase[t] + ddv[t * nbg + j] + (x - sub0[t * nbg + j]);
+                        uint32_t col[4];
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const uint32_t tuple = stage[a + 4 * z + q];
-                            col[q] = tuple & cmask;
-                            const uint32_t r = tuple >> tb.cb;
-                            row[q] = r >= (uint32_t)kSliceRows ? 1u : r << 5;
-                        }
+                        for (int q = 0; q < 4; ++q) col[q] = (stage[x + q] & cmask) | (tp_dest_nibble(at + q) << tb.cb);
                         u32x3a t3;
                         t3.x = col[0] | (col[1] << 24);
                         t3.y = (col[1] >> 8) | (col[2] << 16);
                         t3.z = (col[2] >> 16) | (col[3] << 8);
                         __builtin_nontemporal_store(t3, reinterpret_cast<u32x3a *>(outT + 3 * z));
+                    }
+                }
+                // R: a sub-segment per quarter wavefront, four tuples (8 bytes) per lane
+                for (int z = wave * 4 + (lane >> 4); z < nb * nbg; z += kNW * 4) {
+                    const uint32_t a = sub0[z], len4 = sublen[z] >> 2;
+                    uint32_t *outR = reinterpret_cast<uint32_t *>(R + sbase[z / nbg] + ddv[z]);
+                    for (uint32_t y = (uint32_t)(lane & 15); y < len4; y += 16) {
+                        uint32_t row[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const uint32_t r = stage[a + 4 * y + q] >> tb.cb;
+                            row[q] = r >= (uint32_t)kSliceRows ? 1u : r << 5;
+                        }
                         u32x2 r2;
                         r2.x = row[0] | (row[1] << 16);
                         r2.y = row[2] | (row[3] << 16);
-                        __builtin_nontemporal_store(r2, reinterpret_cast<u32x2 *>(outR + 2 * z));
+                        __builtin_nontemporal_store(r2, reinterpret_cast<u32x2 *>(outR + 2 * y));
                     }
                 }
             } else {
                 for (int z = tid; z < nb * nbg; z += kPlaceThreads) {
-                    const int t = z / nbg, j = z % nbg;
-                    const uint32_t end = sub[(size_t)(i0 + t + 1) * tb.nblk + j];
-                    for (uint32_t w = cur[z]; w < end; ++w) put_entry((uint32_t)j, w, pad);
+                    const uint32_t end = sub0[z] + sublen[z];
+                    for (uint32_t w = cur[z]; w < end; ++w) put_entry((uint32_t)(z % nbg), (uint32_t)z, w, pad);
                 }
             }
             i0 += nb;
@@ -876,9 +933,15 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
 // ------------------------------------------------------------------------------------------------
 // look-up (phase 1 of the score): the tuples of the column blocks of chunk `c0 + blockIdx.y`,
 // restricted to row chunks >= cmin, get their labels.  Workgroup blockIdx.x handles share
-// (blockIdx.x % spb) of block (blockIdx.x / spb) of the chunk.
-//   T  (read)   : the column in its block of every tuple, 3 bytes each, segments ordered (jb, c')
-//   Lx (written): the label of every tuple, 4 bits each, segments ordered (c', jb)
+// (blockIdx.x % spb) of block (blockIdx.x / spb) of the chunk: an equal part of the block's tuples
+// in T, which are one contiguous piece.
+//   T  (read)   : per tuple 3 bytes: the column in its block, and above it 4 of the 32 bits of the
+//                 index of the word of Lx the labels of the tuple's group of eight go to
+//   Lx (written): the label of every tuple, 4 bits each, sub-segments ordered (c', r, jb): a group's
+//                 word lies in the stream of its row slice, so the writes of one sub-segment are a
+//                 contiguous piece of some 40 bytes; the pieces of the chunk's column blocks are
+//                 neighbours and are written by workgroups of one XCD at about the same time, so that
+//                 they meet in its L2 (plain stores: the line is kept there until it is complete)
 //   R           : the row field of every tuple << 5 (bit 0: padding), 16 bits each, ordered like Lx; written
 //                 once by the re-layout
 //   FROM_LDS = true : the block's labels are copied to LDS, two per byte (every vertex of the
@@ -890,8 +953,10 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
 //                     look-up (FROM_LDS = false) sets it, the first pass's look-ups clear it.
 // A thread takes 8 tuples at a time: 24 bytes of T, one 32-bit word of Lx (16 bytes of R / Rdyn).
 // ------------------------------------------------------------------------------------------------
+constexpr int kLookupUnroll = 2;       // groups of eight per thread in flight
+
 template <bool FROM_LDS, bool WRITE_R>
-__global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__restrict__ T,
+__global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tp_lookup(const uint32_t *__restrict__ T,
                                                           uint32_t *__restrict__ Lx,
                                                           const uint16_t *__restrict__ R,
                                                           uint16_t *__restrict__ Rdyn, TpTables tb,
@@ -908,30 +973,15 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
     const int jb = c * tb.nbc + m;
     const u64 *ts = tb.tstart + (size_t)jb * tb.nch;       // ts[c'] for c' = 0..nch (ts[nch] = end of block)
     const u64 lo = ts[cmin], hi = ts[tb.nch];
-    const u64 units = (hi - lo) >> 3;
-    const u64 p0 = lo + ((units * (u64)s / (u64)spb) << 3);
-    const u64 p1 = lo + ((units * (u64)(s + 1) / (u64)spb) << 3);
-    if (p0 >= p1) return;
+    const u64 groups = (hi - lo) >> 3;                      // (every sub-segment is a multiple of 8 tuples)
+    const u64 g0 = groups * (u64)s / (u64)spb, g1 = groups * (u64)(s + 1) / (u64)spb;
+    if (g0 >= g1) return;
+    const uint32_t ng = (uint32_t)(g1 - g0);
+    const uint32_t *src = T + ((lo >> 2) + 2 * g0) * 3ull;  // 6 words per group
 
-    // first row chunk whose segment ends after p0
-    int cc = cmin;
-    {
-        int a = cmin, b = tb.nch - 1;       // ts[b + 1] = hi > p0 always holds
-        while (a < b) { const int mid = (a + b) >> 1; if (ts[mid + 1] > p0) b = mid; else a = mid + 1; }
-        cc = a;
-    }
-    // The share's range [p0, p1) of T crosses a few segments (c', jb), each with its own place in Lx.
-    // Their ends and offsets are fetched side by side, kSegBatch segments at a time, so that the
-    // stream over the tuples never waits for them: a thread walks its groups of eight tuples in
-    // ascending order and steps to the next segment when it passes an end.  The first tuples are
-    // requested before the label table is built, so that the two latencies overlap.
-    constexpr int kSegBatch = 64;
-    constexpr int U = 1;
-    __shared__ u64 s_end[kSegBatch];        // end of segment cc + i in T, cut at p1
-    __shared__ u64 s_xoff[kSegBatch];       // its start in Lx minus its start in T (in tuples)
+    constexpr int U = kLookupUnroll;
     u32x3a t[U][2];
-    auto load_groups = [&](u64 from, uint32_t ng, uint32_t base) {
-        const uint32_t *src = T + (from >> 2) * 3ull;       // `from` is a multiple of 8 tuples
+    auto load_groups = [&](uint32_t base) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint32_t gi = base + u * kTpThreads;
@@ -943,18 +993,13 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
             }
         }
     };
-    {
-        const int cend = cc + kSegBatch < tb.nch ? cc + kSegBatch : tb.nch;
-        u64 pe = ts[cend];
-        if (pe > p1) pe = p1;
-        load_groups(p0, (uint32_t)((pe - p0) >> 3), (uint32_t)tid);
-    }
+    load_groups((uint32_t)tid);             // on their way while the label table is built
 
     if (FROM_LDS) {
         const int64_t bv = (chunk_hi - block_lo) < (1ll << tb.cb) ? (chunk_hi - block_lo) : (1ll << tb.cb);
         const int words = (int)((bv + 7) >> 3);
-        const uint8_t *src = Lc + block_lo;
-        const bool aligned = (((uintptr_t)src) & 15u) == 0;
+        const uint8_t *lsrc = Lc + block_lo;
+        const bool aligned = (((uintptr_t)lsrc) & 15u) == 0;
         auto pack4 = [](uint32_t a) {       // four labels, one per byte -> 16 bits
             return (a & 15u) | ((a >> 4) & 0xF0u) | ((a >> 8) & 0xF00u) | ((a >> 12) & 0xF000u);
         };
@@ -968,7 +1013,7 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
 #pragma unroll
                 for (int i = 0; i < kFill; ++i)
                     if (i0 + i < per)
-                        v[i] = *reinterpret_cast<const u32x4 *>(src + ((size_t)(i0 + i) * kTpThreads + tid) * 16);
+                        v[i] = *reinterpret_cast<const u32x4 *>(lsrc + ((size_t)(i0 + i) * kTpThreads + tid) * 16);
 #pragma unroll
                 for (int i = 0; i < kFill; ++i)
                     if (i0 + i < per) {
@@ -981,86 +1026,60 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_lookup(const uint32_t *__rest
         } else {
             for (int w = tid; w < words; w += kTpThreads) {
                 uint32_t packed = 0;
-                for (int q = 0; q < 8; ++q) {
-                    const int64_t o = (int64_t)w * 8 + q;
-                    if (o < bv) packed |= ((uint32_t)src[o] & 15u) << (4 * q);
+                for (int qq = 0; qq < 8; ++qq) {
+                    const int64_t o = (int64_t)w * 8 + qq;
+                    if (o < bv) packed |= ((uint32_t)lsrc[o] & 15u) << (4 * qq);
                 }
                 tab[w] = packed;
             }
         }
+        __syncthreads();
     }
     const uint8_t *tbytes = reinterpret_cast<const uint8_t *>(tab);
     const uint32_t cmask = (1u << tb.cb) - 1u;
 
-    u64 p = p0;
-    bool first = true;
-    while (p < p1 && cc < tb.nch) {
-        if (!first) __syncthreads();        // the previous batch is done with the tables
-        if (tid < kSegBatch) {
-            const int ci = cc + tid;
-            u64 e = p1, xo = 0;
-            if (ci < tb.nch) {
-                const u64 seg_lo = ts[ci], seg_hi = ts[ci + 1];
-                e = seg_hi < p1 ? seg_hi : p1;
-                if (e < p) e = p;
-                xo = tb.xstart[(size_t)ci * tb.nblk + jb] - seg_lo;
-            }
-            s_end[tid] = e;
-            s_xoff[tid] = xo;
-        }
-        __syncthreads();                    // also: the label table is complete
-        const u64 pe = s_end[kSegBatch - 1];
-        const uint32_t ng = (uint32_t)((pe - p) >> 3);
-        int si = 0;
-        for (uint32_t base = tid; base < ng; base += kTpThreads * U) {
-            if (!(first && base == (uint32_t)tid)) load_groups(p, ng, base);    // (the first turn is on its way)
+    for (uint32_t base = tid; base < ng; base += kTpThreads * U) {
+        if (base != (uint32_t)tid) load_groups(base);       // (the first turn is on its way)
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t gi = base + u * kTpThreads;
-                if (gi < ng) {
-                    const u64 pos = p + ((u64)gi << 3);
-                    while (pos >= s_end[si]) ++si;          // s_end[kSegBatch - 1] = pe > pos
-                    const u64 q = s_xoff[si] + pos;         // the group's place in Lx / R (a multiple of 8)
-                    uint32_t col[8];
+        for (int u = 0; u < U; ++u) {
+            if (base + u * kTpThreads >= ng) continue;
+            uint32_t raw[8];
+            raw[0] = t[u][0].x & 0xFFFFFFu;
+            raw[1] = ((t[u][0].x >> 24) | (t[u][0].y << 8)) & 0xFFFFFFu;
+            raw[2] = ((t[u][0].y >> 16) | (t[u][0].z << 16)) & 0xFFFFFFu;
+            raw[3] = t[u][0].z >> 8;
+            raw[4] = t[u][1].x & 0xFFFFFFu;
+            raw[5] = ((t[u][1].x >> 24) | (t[u][1].y << 8)) & 0xFFFFFFu;
+            raw[6] = ((t[u][1].y >> 16) | (t[u][1].z << 16)) & 0xFFFFFFu;
+            raw[7] = t[u][1].z >> 8;
+            uint32_t word = 0, unassigned = 0, dest = 0;
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const u32x3a d = t[u][h];
-                        // (masked: the few slots between a segment's last tuple and its end hold anything)
-                        col[4 * h + 0] = d.x & cmask;
-                        col[4 * h + 1] = ((d.x >> 24) | (d.y << 8)) & cmask;
-                        col[4 * h + 2] = ((d.y >> 16) | (d.z << 16)) & cmask;
-                        col[4 * h + 3] = (d.z >> 8) & cmask;
-                    }
-                    uint32_t word = 0, unassigned = 0;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        uint32_t lab;
-                        if (FROM_LDS) {
-                            lab = ((uint32_t)tbytes[col[e] >> 1] >> (4 * (col[e] & 1u))) & 15u;
-                        } else {
-                            const int64_t v = block_lo + (int64_t)col[e];
-                            const uint32_t l = v < chunk_hi ? (uint32_t)Lc[v] : 0xFFu;
-                            if (l == 0xFFu) unassigned |= 1u << e;
-                            lab = l & 15u;
-                        }
-                        word |= lab << (4 * e);
-                    }
-                    __builtin_nontemporal_store(word, Lx + (q >> 3));
-                    if (WRITE_R) {
-                        const u32x4 r = *reinterpret_cast<const u32x4 *>(R + q);
-                        u32x4 o;
-                        o.x = r.x | (unassigned & 1u) | ((unassigned & 2u) << 15);
-                        o.y = r.y | ((unassigned >> 2) & 1u) | ((unassigned & 8u) << 13);
-                        o.z = r.z | ((unassigned >> 4) & 1u) | ((unassigned & 32u) << 11);
-                        o.w = r.w | ((unassigned >> 6) & 1u) | ((unassigned & 128u) << 9);
-                        *reinterpret_cast<u32x4 *>(Rdyn + q) = o;
-                    }
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t col = raw[e] & cmask;
+                dest |= ((raw[e] >> tb.cb) & 15u) << (4 * e);
+                uint32_t lab;
+                if (FROM_LDS) {
+                    lab = ((uint32_t)tbytes[col >> 1] >> (4 * (col & 1u))) & 15u;
+                } else {
+                    const int64_t v = block_lo + (int64_t)col;
+                    const uint32_t l = v < chunk_hi ? (uint32_t)Lc[v] : 0xFFu;
+                    if (l == 0xFFu) unassigned |= 1u << e;
+                    lab = l & 15u;
                 }
+                word |= lab << (4 * e);
+            }
+            Lx[dest] = word;
+            if (WRITE_R) {
+                const u64 at = (u64)dest << 3;
+                const u32x4 rr = *reinterpret_cast<const u32x4 *>(R + at);
+                u32x4 o;
+                o.x = rr.x | (unassigned & 1u) | ((unassigned & 2u) << 15);
+                o.y = rr.y | ((unassigned >> 2) & 1u) | ((unassigned & 8u) << 13);
+                o.z = rr.z | ((unassigned >> 4) & 1u) | ((unassigned & 32u) << 11);
+                o.w = rr.w | ((unassigned >> 6) & 1u) | ((unassigned & 128u) << 9);
+                *reinterpret_cast<u32x4 *>(Rdyn + at) = o;
             }
         }
-        first = false;
-        p = pe;
-        cc += kSegBatch;
     }
 }
 
@@ -1071,37 +1090,14 @@ __device__ __forceinline__ uint32_t quad_swap(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 
-// Counting the tuples of sub-segments: row fields from R (16 bits each, bit 0 set: not to be
-// counted), labels from Lx (4 bits each).  A sub-segment holds some 70 tuples, so a whole
-// wavefront on one of them would leave half its lanes idle: a QUARTER of the wavefront takes one,
-// six tuples (12 bytes of R, 3 of Lx) per lane, which covers 96 at once; longer ones take further
-// turns.
-typedef uint32_t u32a1 __attribute__((aligned(1)));      // four bytes at any address
-
-struct TpSix {
-    u32x3a rows;        // six row fields
-    uint32_t labels;    // six labels in the low 24 bits
-};
-
-// The six tuples of a sub-segment from tuple `off` (a multiple of 6, below its length) on.  The
-// loads may reach 8 bytes (R) or 3 bytes (Lx) past the sub-segment: the arrays have that much
-// slack; what lies past the end is not counted.
-__device__ __forceinline__ TpSix tp_load_six(const uint32_t *__restrict__ R32, const uint8_t *__restrict__ Lx8,
-                                             uint32_t start, uint32_t off) {
-    TpSix x;
-    const uint32_t at = (start + off) >> 1;        // start and off are even
-    x.rows = __builtin_nontemporal_load(reinterpret_cast<const u32x3a *>(R32 + at));
-    x.labels = *reinterpret_cast<const u32a1 *>(Lx8 + at);
-    return x;
-}
-
-// The two tuples of one 32-bit word w of R; their labels are bits sh .. sh + 7 of `labels`; `on`:
-// the word lies inside the sub-segment.  16 bits of R: row field << 5 | skip (bit 0: padding, or an
-// unassigned neighbour), so row field << 5 is the byte offset of the row's 16 counters of 16 bits,
-// to which (label >> 1) << 2 adds the counter pair's; the label's bit 0 picks the half.
+// Counting tuples: row fields from R (16 bits each, bit 0 set: not to be counted), labels from Lx (4
+// bits each).  The two tuples of one 32-bit word w of R; their labels are bits SH .. SH + 7 of
+// `labels`.  16 bits of R: row field << 5 | skip (bit 0: padding, or an unassigned neighbour), so
+// row field << 5 is the byte offset of the row's 16 counters of 16 bits, to which (label >> 1) << 2
+// adds the counter pair's; the label's bit 0 picks the half.
 template <bool COUNT16, int SH>
-__device__ __forceinline__ void tp_count_word(uint32_t w, uint32_t labels, bool on, int k, uint32_t *hist) {
-    const uint32_t live = on ? ~w : 0u;                 // bit 0 / bit 16: the tuple is to be counted
+__device__ __forceinline__ void tp_count_word(uint32_t w, uint32_t labels, int k, uint32_t *hist) {
+    const uint32_t live = ~w;                           // bit 0 / bit 16: the tuple is to be counted
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const uint32_t lab = (labels >> (SH + 4 * h)) & 15u;
@@ -1117,87 +1113,62 @@ __device__ __forceinline__ void tp_count_word(uint32_t w, uint32_t labels, bool 
     }
 }
 
+// a group of eight tuples: 16 bytes of R, one word of Lx
 template <bool COUNT16>
-__device__ __forceinline__ void tp_count_six(const TpSix &x, uint32_t rem, int k, uint32_t *hist) {
-    tp_count_word<COUNT16, 0>(x.rows.x, x.labels, true, k, hist);
-    tp_count_word<COUNT16, 8>(x.rows.y, x.labels, rem > 2, k, hist);        // rem is even
-    tp_count_word<COUNT16, 16>(x.rows.z, x.labels, rem > 4, k, hist);
+__device__ __forceinline__ void tp_count_eight(const u32x4 rows, uint32_t labels, int k, uint32_t *hist) {
+    tp_count_word<COUNT16, 0>(rows.x, labels, k, hist);
+    tp_count_word<COUNT16, 8>(rows.y, labels, k, hist);
+    tp_count_word<COUNT16, 16>(rows.z, labels, k, hist);
+    tp_count_word<COUNT16, 24>(rows.w, labels, k, hist);
 }
 
-// The sub-segments a wavefront owns, 4 * NBQ at a time: lane t of (s0, l0) holds start and length
-// (multiples of 4) of the t-th of them, t < tmax <= 64.  All loads of a turn are issued before the
-// first tuple is counted.
-template <bool COUNT16, int NBQ>
-__device__ __forceinline__ void tp_count_list(const uint32_t *__restrict__ R32, const uint8_t *__restrict__ Lx8,
-                                              uint32_t s0, uint32_t l0, int tmax, int lane, int k,
-                                              uint32_t *hist) {
-    const int quarter = lane >> 4;
-    const uint32_t off = 6u * (uint32_t)(lane & 15);
-    for (int t = 0; t < tmax; t += 4 * NBQ) {
-        uint32_t st[NBQ], ln[NBQ];
-        TpSix w[NBQ];
+// Groups [g0, g1) of a row stream that starts at slot `base` (a multiple of 8) of R and Lx, counted by
+// the whole workgroup, NU groups per thread in flight.
+template <bool COUNT16, int NU>
+__device__ __forceinline__ void tp_count_stream(const uint16_t *__restrict__ R, const uint32_t *__restrict__ Lx, u64 base,
+                                                uint32_t g0, uint32_t g1, int k, uint32_t *hist) {
+    const u32x4 *R4 = reinterpret_cast<const u32x4 *>(R + base);
+    const uint32_t *L1 = Lx + (base >> 3);
+    for (uint32_t g = g0 + threadIdx.x; g < g1; g += kTpThreads * NU) {
+        u32x4 rows[NU];
+        uint32_t labs[NU];
 #pragma unroll
-        for (int b = 0; b < NBQ; ++b) {
-            const int tq = t + 4 * b + quarter;
-            st[b] = (uint32_t)__shfl((int)s0, tq & 63);
-            ln[b] = (uint32_t)__shfl((int)l0, tq & 63);
-            if (tq >= tmax) ln[b] = 0;
-            w[b].rows = (u32x3a){0u, 0u, 0u};
-            w[b].labels = 0;
-            if (off < ln[b]) w[b] = tp_load_six(R32, Lx8, st[b], off);
-        }
-#pragma unroll
-        for (int b = 0; b < NBQ; ++b)
-            if (off < ln[b]) tp_count_six<COUNT16>(w[b], ln[b] - off, k, hist);
-#pragma unroll
-        for (int b = 0; b < NBQ; ++b) {         // the rare sub-segment of more than 96 tuples
-            for (uint32_t r = 96; __any(r < ln[b]); r += 96) {
-                if (r + off < ln[b]) {
-                    const TpSix v = tp_load_six(R32, Lx8, st[b], r + off);
-                    tp_count_six<COUNT16>(v, ln[b] - (r + off), k, hist);
-                }
+        for (int u = 0; u < NU; ++u) {
+            const uint32_t gi = g + u * kTpThreads;
+            rows[u] = (u32x4)(1u | (1u << 16));         // nothing to count
+            labs[u] = 0;
+            if (gi < g1) {
+                rows[u] = __builtin_nontemporal_load(R4 + gi);
+                labs[u] = __builtin_nontemporal_load(L1 + gi);
             }
         }
-    }
-}
-
-// start (in tuples from the chunk's first slot of Lx / R) and length of the share's sub-segment of
-// its ml-th block
-__device__ __forceinline__ void tp_hub_offsets(const TpTables &tb, const u64 *__restrict__ xs, u64 xs0,
-                                               const uint32_t *__restrict__ q0, int cls, int ncls, int mlim,
-                                               int ml, uint32_t *s0, uint32_t *l0) {
-    *s0 = 0;
-    *l0 = 0;
-    if (ml < mlim) {
-        const int jl = cls + ncls * ml;
-        const uint32_t a0 = q0[jl];
-        *s0 = (uint32_t)(xs[jl] - xs0) + a0;
-        *l0 = q0[tb.nblk + jl] - a0;
+#pragma unroll
+        for (int u = 0; u < NU; ++u)
+            if (g + u * kTpThreads < g1) tp_count_eight<COUNT16>(rows[u], labs[u], k, hist);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// score (phase 2): one workgroup per row slice of chunk c.  It counts the slice's sub-segment of
-// every column block in [0, jlim) (in the first pass of an unseeded run the blocks of chunks >= c
-// hold no label yet and their part of Lx has not been written), and, of hub share
-// (blockIdx.x % nvs), the sub-segments of the blocks congruent to (blockIdx.x / nvs) modulo the
-// number of workgroups per share, so that the hub entries are spread evenly too.  Then it blends E,
-// proposes, and counts the movers of its two admission tiles per proposed partition (cnt, the input
-// of the admission; k_hub_finalize adds the hubs).
+// score (phase 2): one workgroup per row slice of chunk c.  It counts the slice's row stream: the
+// sub-segments of the column blocks in [0, jlim), a prefix of the stream (in the first pass of an
+// unseeded run the blocks of chunks >= c hold no label yet and their part of Lx has not been
+// written); and, of hub share (slice % nvs), an equal part of that share's stream (same prefix
+// rule), so that the hub entries are spread evenly too.  Then it blends E, proposes, and counts the
+// movers of its two admission tiles per proposed partition (cnt, the input of the admission;
+// k_hub_finalize adds the hubs).
 //
 // Four lanes share a vertex in the blend: lane q owns partitions 4q .. 4q+3 when k % 4 == 0 (one
 // 16-byte piece of E's row), else q, q+4, q+8, q+12.
 // LDS: hist[kSliceRows * 8] (16-bit counters, 16 per row), meta[kSliceRows / 2] (per row: old label,
 //      hub flag << 8), hhist[share_hubs * k], room[k], tcnt[2 * k]
 // ------------------------------------------------------------------------------------------------
-template <typename RowT, typename ET>
-__global__ __launch_bounds__(kTpThreads) void k_tp_score(
-    const RowT *__restrict__ rowptr, const uint16_t *__restrict__ R, const uint32_t *__restrict__ Lx,
-    TpTables tb, SweepPlan pl,
+template <typename ET>
+__global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tp_score(
+    const uint16_t *__restrict__ R, const uint32_t *__restrict__ Lx, TpTables tb, SweepPlan pl,
     const uint8_t *__restrict__ Lc, const long long *__restrict__ S, ET *__restrict__ E,
     uint32_t *__restrict__ Hhub, uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
     long long *__restrict__ room_out, int c, int64_t chunk_lo, int64_t chunk_hi, int k, int jlim,
-    int share_hubs, uint32_t hub_degree, int pass, long long P, int store_e) {
+    int share_hubs, uint32_t nvs, int pass, long long P, int store_e) {
     extern __shared__ uint32_t smem[];
     constexpr int hist_words = kSliceRows * 8;
     constexpr int BU = kSliceRows * 4 / kTpThreads;     // (vertex, quarter) pairs per thread
@@ -1209,11 +1180,10 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     uint32_t *hhist = smem + kSliceRows / 2;                            // share_hubs * k, 32-bit
     uint32_t *room = hhist + share_hubs * k;    // k
     uint32_t *tcnt = room + k;                  // 2 * k
-    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    constexpr int NW = kTpThreads / 64;
+    const int tid = threadIdx.x;
     // Workgroups are dispatched round-robin over the 8 XCDs, each with its own L2: give XCD x a
-    // contiguous range of slices, so that neighbouring slices, whose sub-segments share cache lines
-    // of R and Lx, meet in one L2.
+    // contiguous range of slices, so that neighbouring slices, whose streams and rows of E are
+    // neighbours in memory, meet in one L2.
     const unsigned xcd = blockIdx.x & 7u, turn = blockIdx.x >> 3;
     const unsigned slice = xcd * (gridDim.x >> 3) + (xcd < (gridDim.x & 7u) ? xcd : (gridDim.x & 7u)) + turn;
     const int64_t v0 = chunk_lo + (int64_t)slice * kSliceRows;
@@ -1221,13 +1191,33 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     const int nv = left < kSliceRows ? (int)left : kSliceRows;
     const bool vec = (k & 3) == 0;
 
-    // the hub share this workgroup helps with
-    const uint32_t nvs = pl.ch_nvs[c];
+    // the hub share this workgroup helps with (nvs: the chunk's number of shares, known to the host, so
+    // that everything this workgroup has to fetch before it can start is requested at once)
     const uint32_t share = nvs ? slice % nvs : 0u;
     const int cls = nvs ? (int)(slice / nvs) : 0;
     const int ncls = nvs ? (int)((gridDim.x - share + nvs - 1) / nvs) : 1;   // workgroups that took this share
+    // what to count: a prefix of the slice's stream, and this workgroup's part of the share's (all
+    // addresses follow from the arguments: the loads are independent of each other)
+    const size_t gs = (size_t)c * tb.nsl + slice;
+    const u64 *ss = tb.sstart + (size_t)c * tb.nr;
+    const size_t ddrow = ((size_t)(jlim < tb.nblk ? jlim : 0) * tb.nch + c) * tb.nr;     // dd[jlim][c][*]
+    const bool whole = jlim >= tb.nblk;
+    const uint32_t hr = (uint32_t)tb.nsl + share;
+    const u64 sbeg = ss[slice], send = ss[slice + 1];
+    const u64 hbeg = nvs ? ss[hr] : 0ull, hend = nvs ? ss[hr + 1] : 0ull;
+    const uint32_t sdd = (!whole && jlim > 0) ? tb.dd[ddrow + slice] : 0u;
+    const uint32_t hdd = (!whole && jlim > 0 && nvs) ? tb.dd[ddrow + hr] : 0u;
     const bool any_hub = nvs != 0 && pl.share_nhs[(size_t)c * tb.nsl + share] != 0;
     const uint32_t share_h0 = pl.share_h0[(size_t)c * tb.nsl + share];
+    const uint32_t snh = pl.sl_nh[gs];
+    const u64 slice_hub0 = pl.ch_hub0[c] + pl.sl_hub_start[gs];
+    const uint32_t slen = whole ? (uint32_t)(send - sbeg) : sdd;
+    uint32_t hg0 = 0, hg1 = 0;
+    if (any_hub) {
+        const u64 groups = (whole ? (uint32_t)(hend - hbeg) : hdd) >> 3;
+        hg0 = (uint32_t)(groups * (u64)cls / (u64)ncls);
+        hg1 = (uint32_t)(groups * (u64)(cls + 1) / (u64)ncls);
+    }
 
     {
         u32x4 *z = reinterpret_cast<u32x4 *>(hist);
@@ -1239,48 +1229,27 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
             if (slice == 0) room_out[j] = rj;           // the sizes' snapshot k_apply admits against
         }
         for (int j = tid; j < 2 * k; j += kTpThreads) tcnt[j] = 0;
-        for (int t = tid; t < nv; t += kTpThreads) {
-            const int64_t v = v0 + t;
-            const uint32_t hub = (u64)(rowptr[v + 1] - rowptr[v]) >= hub_degree ? 0x100u : 0u;
-            meta[t] = (uint16_t)((uint32_t)Lc[v] | hub);
-        }
+        for (int t = tid; t < nv; t += kTpThreads) meta[t] = (uint16_t)Lc[v0 + t];
     }
     __syncthreads();
+    // the slice's hubs, from the chunk's list (read by the blend, after the next barrier)
+    for (uint32_t i = tid; i < snh; i += kTpThreads) meta[(int64_t)pl.hub_row[slice_hub0 + i] - v0] |= (uint16_t)0x100u;
 
-    const u64 *xs = tb.xstart + (size_t)c * tb.nblk;
-    const u64 xs0 = xs[0];
-    const uint32_t *R32 = reinterpret_cast<const uint32_t *>(R + xs0);      // xs0 is a multiple of 8
-    const uint8_t *Lx8 = reinterpret_cast<const uint8_t *>(Lx) + (xs0 >> 1);
-    // hub sub-segments: blocks cls + ncls * m < jlim; their offsets are fetched now, counted last
-    const uint32_t *hq0 = tb.subH + ((size_t)c * (tb.nsl + 1) + share) * tb.nblk;
-    const int mlim = (any_hub && jlim > cls) ? (jlim - cls + ncls - 1) / ncls : 0;
-    uint32_t hs0 = 0, hl0 = 0;
-    if (any_hub) tp_hub_offsets(tb, xs, xs0, hq0, cls, ncls, mlim, wave + NW * lane, &hs0, &hl0);
-    {
-        const uint32_t *r0 = tb.subR + ((size_t)c * (tb.nsl + 1) + slice) * tb.nblk;
-        const uint32_t *r1 = r0 + tb.nblk;
-        for (int base = 0; base < jlim; base += NW * 64) {
-            // lane l of wave w holds the sub-segment of block base + w + NW * l
-            const int jl = base + wave + NW * lane;
-            uint32_t s0 = 0, l0 = 0;
-            if (jl < jlim) {
-                const uint32_t a0 = r0[jl];
-                s0 = (uint32_t)(xs[jl] - xs0) + a0;
-                l0 = r1[jl] - a0;
-            }
-            int tmax = (jlim - base - wave + NW - 1) / NW;      // blocks of this wave in this round
-            if (tmax > 64) tmax = 64;
-            tp_count_list<true, 4>(R32, Lx8, s0, l0, tmax, lane, k, hist);
-        }
-    }
-    if (any_hub) {
-        for (int base = 0; base < mlim; base += NW * 64) {
-            uint32_t s0 = hs0, l0 = hl0;                 // first round: loaded before the regular blocks
-            if (base > 0) tp_hub_offsets(tb, xs, xs0, hq0, cls, ncls, mlim, base + wave + NW * lane, &s0, &l0);
-            int tmax = (mlim - base - wave + NW - 1) / NW;
-            if (tmax > 64) tmax = 64;
-            tp_count_list<false, 2>(R32, Lx8, s0, l0, tmax, lane, k, hhist);
-        }
+    tp_count_stream<true, 4>(R, Lx, sbeg, 0u, slen >> 3, k, hist);
+    if (any_hub) tp_count_stream<false, 2>(R, Lx, hbeg, hg0, hg1, k, hhist);
+    // the stored estimates are requested before the barrier, so that they arrive while the slower
+    // wavefronts are still counting
+    const bool fast = sizeof(ET) == 2 && vec && P < (1ll << 27);
+    const int q4 = tid & 3;
+    const bool mine = 4 * q4 < k;
+    u32x2 e[BU];
+#pragma unroll
+    for (int u = 0; u < BU; ++u) {
+        const int g = tid + u * kTpThreads;
+        e[u] = (u32x2)(0u);
+        if (fast && pass > 0 && mine && g < nv * 4)
+            e[u] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x2 *>(E + (size_t)(v0 + (g >> 2)) * (size_t)k + 4 * q4));
     }
     __syncthreads();
 
@@ -1297,19 +1266,9 @@ __global__ __launch_bounds__(kTpThreads) void k_tp_score(
     // halves: an estimate stays below 2^16), and the arg-max by (E desc, room desc, id asc) is the
     // maximum of one 64-bit key per partition, E << 40 | room << 4 | 15 - id, 0 if the partition is
     // full (or does not exist: the lanes past k of a vertex's quad hold no partition).
-    if (sizeof(ET) == 2 && vec && P < (1ll << 27)) {
-        const int q = tid & 3;
-        const bool mine = 4 * q < k;
+    if (fast) {
+        const int q = q4;
         const int sh = pass > 0 ? pass - 1 : 0;
-        u32x2 e[BU];
-#pragma unroll
-        for (int u = 0; u < BU; ++u) {
-            const int g = tid + u * kTpThreads;
-            e[u] = (u32x2)(0u);
-            if (pass > 0 && mine && g < nv * 4)
-                e[u] = __builtin_nontemporal_load(
-                    reinterpret_cast<const u32x2 *>(E + (size_t)(v0 + (g >> 2)) * (size_t)k + 4 * q));
-        }
         uint32_t lo_base[4];
 #pragma unroll
         for (int z = 0; z < 4; ++z) lo_base[z] = mine ? (room[4 * q + z] << 4) | (uint32_t)(15 - (4 * q + z)) : 0u;
