@@ -594,6 +594,7 @@ def main():
           file=sys.stderr, flush=True)
 
     opts = B.options(col_bits=args.col_bits, hub_degree=args.hub_degree) if (args.col_bits or args.hub_degree) else None
+    plan_opts = B.options(col_bits=args.col_bits, hub_degree=args.hub_degree, plan_max_k=k if k > 16 else 0)
     ws_bytes = B.grem_workspace_bytes_two_phase(n, nnz, k, chunk, opts)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     B.grem_set_workspace(ws)
@@ -707,10 +708,12 @@ def main():
             del ws
             torch.cuda.empty_cache()
             t_plan = time.perf_counter()
-            plan = B.Plan(g.rowptr, g.colidx, n, chunk, opts)
+            plan = B.Plan(g.rowptr, g.colidx, n, chunk, plan_opts)
             torch.cuda.synchronize()
             t_plan = 1e3 * (time.perf_counter() - t_plan)
             plabels = torch.empty(n, dtype=torch.int32, device=dev)
+            pws = torch.empty(plan.call_bytes(k, R), dtype=torch.uint8, device=dev)
+            B.grem_set_workspace(pws)
 
             def pstep():
                 B.grem_partition_planned(plan, k, w["slack"], R, labels_out=plabels)
@@ -721,10 +724,12 @@ def main():
             assert torch.equal(plabels, labels)
             planned = stats(pms)
             planned.update(plan_create_ms=round(t_plan, 3), plan_device_bytes=plan.device_bytes,
+                           call_workspace_bytes=pws.numel(),
                            value=g.directed_edges / (planned["mean_ms"] * 1e-3 / passes), unit="edges/s",
                            whole_call_frac=frac_of_peak(b_total, planned["mean_ms"]))
             planned.update(pass_report(per_pass_marks(pstep)))
             roofline["planned_call_frac"] = planned["whole_call_frac"]
+            B.grem_set_workspace(None)
             plan.close()
 
     out = {

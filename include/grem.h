@@ -74,7 +74,7 @@ extern "C" {
                                 chunk is relabelled its labels are looked up, from LDS, for every
                                 entry that refers to them, and the rows' workgroups later count
                                 the stored results into LDS histograms (GREM_ERR_ARG unless
-                                k <= 16 and the plan fits its limits).  AUTO takes it for k <= 16
+                                k <= 32 and the plan fits its limits).  AUTO takes it for k <= 32
                                 when the label table is larger than L2 and chunks are large. */
 
 /* Sec. 4.1 (Alg. 1 with all nodes unassigned at the start).  rowptr: n+1 entries; colidx:
@@ -121,7 +121,10 @@ typedef struct grem_options {
     int32_t long_row_degree;  /* plain route: a tile of rows is scored by one workgroup; rows of at least
                                  this many entries are taken out of their tile and spread over a grid of
                                  their own; 0 = default (16384) */
-    int32_t reserved[4];      /* must be zero */
+    int32_t plan_max_k;       /* grem_plan_create: the largest k the plan is to serve, 0 = 16, at most 32.
+                                 Above 16 the plan is laid out with narrower column blocks (2^16 vertices)
+                                 and more hub shares; it still serves every smaller k */
+    int32_t reserved[3];      /* must be zero */
 } grem_options;
 
 /* grem_partition_state with options.  GREM_ERR_ARG also for an unknown histogram mode, an option out
@@ -133,7 +136,7 @@ int grem_partition_opt(const void *rowptr, int32_t rowptr_bits, const int32_t *c
                        uint32_t *estimates_out, const grem_options *options, void *stream);
 
 /* ---- Several runs on one graph -----------------------------------------------------------------
- * The two-phase route (k <= 16) works on a re-laid-out copy of the CSR entries that depends only on
+ * The two-phase route (k <= 32) works on a re-laid-out copy of the CSR entries that depends only on
  * the graph, `chunk` and the two-phase options -- not on k, the slack, the seed or the number of
  * passes.  A plan holds that copy, so that further runs on the same graph (other seeds, slacks, k,
  * pass counts; the levels of a recursive driver) skip the re-layout, which otherwise is about half
@@ -147,7 +150,7 @@ int grem_partition_opt(const void *rowptr, int32_t rowptr_bits, const int32_t *c
  * take: more than 4096 column blocks, ...), GREM_ERR_NOMEM, GREM_ERR_HIP, GREM_ERR_RANGE.
  * grem_plan_destroy synchronises the device and frees the plan (NULL is allowed).
  *
- * grem_partition_planned: the run of grem_partition_opt for the plan's graph and chunk size, k <= 16,
+ * grem_partition_planned: the run of grem_partition_opt for the plan's graph and chunk size, k <= grem_plan_max_k,
  * same result bit for bit.  Per-call state (labels, estimates, the looked-up labels: about 0.5
  * bytes per entry plus n*(2k+1) bytes) comes from the workspace or a stream-ordered allocation.
  * Several runs may use one plan at the same time (it is read-only).  Without a seed the call reads
@@ -157,9 +160,16 @@ int grem_plan_create(const void *rowptr, int32_t rowptr_bits, const int32_t *col
                      int64_t chunk, const grem_options *options, void *stream, grem_plan **plan_out);
 int grem_plan_destroy(grem_plan *plan);
 size_t grem_plan_device_bytes(const grem_plan *plan);
-/* Largest k the plan serves: 16, or less for a graph so full of hubs that the hub counters of a
- * workgroup would not fit its LDS at k = 16 (GREM_ERR_ARG beyond it). */
+/* Largest k the plan serves: options.plan_max_k (16 by default), or less for a graph so full of hubs that the hub counters of a
+ * workgroup would not fit its LDS at that k (GREM_ERR_ARG beyond it). */
 int32_t grem_plan_max_k(const grem_plan *plan);
+/* Bytes of workspace (grem_set_workspace) with which such a grem_partition_planned call allocates
+ * nothing: the run's labels, estimates and looked-up labels.  seeded / with_estimates_out: whether
+ * seed_labels / estimates_out will be passed.  0 on bad arguments.  (Without a workspace every call
+ * allocates this much stream-ordered and gives it back when its work is done; for large graphs
+ * that alone can take longer than the run.) */
+size_t grem_plan_call_bytes(const grem_plan *plan, int32_t k, int32_t refine_passes, int32_t seeded,
+                            int32_t with_estimates_out);
 int grem_partition_planned(const grem_plan *plan, int32_t k, double balance_slack,
                            int32_t refine_passes, const int32_t *seed_labels, int32_t *labels_out,
                            int64_t *sizes_out, uint32_t *estimates_out, void *stream);
@@ -181,7 +191,7 @@ int64_t grem_capacity(int64_t n, int32_t k, double balance_slack);
  * chunk's proposals and the admission tables.  0 on bad arguments. */
 size_t grem_workspace_bytes(int64_t n, int32_t k, int64_t chunk);
 
-/* Bytes with which a call can also take the two-phase route (k <= 16) without allocating: an upper
+/* Bytes with which a call can also take the two-phase route (k <= 32) without allocating: an upper
  * bound for any graph of n rows and nnz entries under the given options (NULL = defaults): the
  * re-laid-out copy and its tables, and, sharing one region, the intermediate copy of the re-layout
  * (4 bytes per entry) and the per-call state.  Never less than grem_workspace_bytes.  A workspace

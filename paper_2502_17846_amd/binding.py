@@ -23,7 +23,7 @@ KERNEL_SCORE = 1
 EXPORTS = [
     "grem_partition", "grem_partition_seeded", "grem_partition_r32", "grem_partition_seeded_r32",
     "grem_partition_state", "grem_partition_opt", "grem_plan_create", "grem_plan_destroy",
-    "grem_plan_device_bytes", "grem_plan_max_k", "grem_partition_planned", "grem_edge_cut", "grem_edge_cut_r32", "grem_capacity",
+    "grem_plan_device_bytes", "grem_plan_max_k", "grem_plan_call_bytes", "grem_partition_planned", "grem_edge_cut", "grem_edge_cut_r32", "grem_capacity",
     "grem_workspace_bytes", "grem_workspace_bytes_two_phase", "grem_set_workspace", "grem_profile_enable",
     "grem_profile_reset", "grem_profile_read", "grem_profile_read_marks", "grem_status_string", "grem_kernel_name",
     "grem_edge_stream_bipartition", "grem_edge_list_cut", "grem_edge_stream_profile_enable",
@@ -36,12 +36,14 @@ EDGE_REFINE, EDGE_FIXED = 0, 1
 class Options(ctypes.Structure):
     """grem_options of include/grem.h: how a run is carried out, never what it computes."""
     _fields_ = [("histogram_mode", ctypes.c_int32), ("col_bits", ctypes.c_int32), ("hub_degree", ctypes.c_int32),
-                ("long_row_degree", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+                ("long_row_degree", ctypes.c_int32), ("plan_max_k", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
 
-def options(histogram_mode: int = 0, col_bits: int = 0, hub_degree: int = 0, long_row_degree: int = 0) -> Options:
+def options(histogram_mode: int = 0, col_bits: int = 0, hub_degree: int = 0, long_row_degree: int = 0,
+            plan_max_k: int = 0) -> Options:
     o = Options()
     o.histogram_mode, o.col_bits, o.hub_degree, o.long_row_degree = histogram_mode, col_bits, hub_degree, long_row_degree
+    o.plan_max_k = plan_max_k
     return o
 
 
@@ -92,6 +94,8 @@ def load():
     lib.grem_plan_device_bytes.argtypes = [vp]
     lib.grem_plan_max_k.restype = ctypes.c_int32
     lib.grem_plan_max_k.argtypes = [vp]
+    lib.grem_plan_call_bytes.restype = ctypes.c_size_t
+    lib.grem_plan_call_bytes.argtypes = [vp, i32, i32, i32, i32]
     lib.grem_partition_planned.restype = ctypes.c_int
     lib.grem_partition_planned.argtypes = [vp, i32, dbl, i32, vp, vp, vp, vp, vp]
     lib.grem_workspace_bytes.restype = ctypes.c_size_t
@@ -288,6 +292,9 @@ class Plan:
     @property
     def max_k(self) -> int:
         return int(load().grem_plan_max_k(self._h))
+
+    def call_bytes(self, k: int, refine_passes: int, seeded: bool = False, with_estimates_out: bool = False) -> int:
+        return int(load().grem_plan_call_bytes(self._h, k, refine_passes, int(seeded), int(with_estimates_out)))
 
     def close(self):
         if self._h:

@@ -32,10 +32,14 @@ constexpr int kLdsMaxK = 1024;             // above this the histograms live in 
 constexpr int kLongRowDegree = 16384;      // plain score kernels: rows this long get a grid of their own ...
 constexpr uint32_t kLongRowPart = 16384;   // ... that many entries per workgroup and turn
 constexpr unsigned kLongRowGrid = 512;
-constexpr int kSweepMaxK = 16;             // two-phase route: 4-bit labels, 16-bit counters, 2048 rows, 64 KB
+constexpr int kSweepMaxK = 32;             // two-phase route: 16-bit counters for 2048 rows: 64 KB of LDS up to k = 16
+                                           // (4-bit labels), 128 KB up to k = 32 (8-bit labels)
+constexpr int kHubsPerShare16 = 1024;      // hubs one hub share may touch: their 32-bit counters share the
+constexpr int kHubsPerShare32 = 96;        // workgroup's LDS with the slice's counters
 constexpr int64_t kSweepMinN = 1 << 22;    // AUTO: label table must exceed L2 for the route to pay
 constexpr int64_t kSweepMinChunk = 1 << 14;   // AUTO: per-chunk launches must have work to do
 constexpr int kDefaultColBits = 17;        // 2^17 labels, two per byte: 64 KB of LDS, two workgroups per CU
+constexpr int kDefaultColBits32 = 16;      // k > 16: 2^16 labels, a byte each
 constexpr int kDefaultHubDegree = 2048;
 constexpr int64_t kMaxSegments = 1ll << 22;   // chunks * column blocks
 constexpr int kMaxParts = kPlanParts;      // parts of a slice (hub share) in the re-layout
@@ -61,6 +65,7 @@ struct Opts {
     int col_bits = 0;                       // 0 = automatic
     int hub_degree = kDefaultHubDegree;
     int long_row_degree = kLongRowDegree;
+    int plan_max_k = 16;
 };
 
 bool resolve_options(const grem_options *o, Opts *out) {
@@ -72,12 +77,14 @@ bool resolve_options(const grem_options *o, Opts *out) {
         if (o->col_bits != 0 && (o->col_bits < 4 || o->col_bits > kMaxColBits)) return false;
         if (o->hub_degree < 0 || o->hub_degree > 65535) return false;
         if (o->long_row_degree < 0) return false;
-        for (int i = 0; i < 4; ++i)
+        if (o->plan_max_k < 0 || o->plan_max_k > kSweepMaxK) return false;
+        for (int i = 0; i < 3; ++i)
             if (o->reserved[i] != 0) return false;
         r.hist_mode = o->histogram_mode;
         r.col_bits = o->col_bits;
         if (o->hub_degree) r.hub_degree = o->hub_degree;
         if (o->long_row_degree) r.long_row_degree = o->long_row_degree;
+        if (o->plan_max_k) r.plan_max_k = o->plan_max_k;
     }
     *out = r;
     return true;
@@ -160,15 +167,17 @@ struct TpGeom {
     bool ok = false;
 };
 
-TpGeom tp_geometry(int64_t n, int64_t chunk, int col_bits_setting) {
+// kmax: the largest k the layout is to serve (above 16 the look-up keeps a byte per label in LDS)
+TpGeom tp_geometry(int64_t n, int64_t chunk, int col_bits_setting, int kmax) {
     TpGeom t;
     const int64_t cl = chunk < n ? chunk : n;
     const int64_t nch = (n + cl - 1) / cl;
     const int64_t nsl = (cl + kSliceRows - 1) / kSliceRows;
     int cb = col_bits_setting;
     if (cb == 0) {
+        const int want = kmax > 16 ? kDefaultColBits32 : kDefaultColBits;
         cb = 4;
-        while (cb < kDefaultColBits && (1ll << cb) < cl) ++cb;
+        while (cb < want && (1ll << cb) < cl) ++cb;
     }
     const int64_t nbc = (cl + (1ll << cb) - 1) >> cb;
     const int64_t nblk = nch * nbc;
@@ -274,7 +283,6 @@ struct PlanData {
     std::vector<uint32_t> nvs;              // hub shares per chunk (host copy of pl.ch_nvs)
     int share_hubs = 0;
     int max_k = 0;                          // largest k whose score workgroups fit the LDS
-    size_t lookup_lds = 0;
     int lookup_target = 512;
 };
 
@@ -349,7 +357,8 @@ template <typename RowT>
 int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n, int64_t chunk, int32_t k,
                const Opts &o, Arena &keep, Arena &temp, Launcher &L, bool strict) {
     hipStream_t stream = L.stream;
-    const TpGeom geo = tp_geometry(n, chunk, o.col_bits);
+    const int kmax = k ? k : o.plan_max_k;
+    const TpGeom geo = tp_geometry(n, chunk, o.col_bits, kmax);
     if (!geo.ok) return GREM_ERR_ARG;            // (callers check the geometry first)
     const int hub_degree = o.hub_degree;
     P.rowptr = rowptr;
@@ -375,8 +384,8 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
                            (uint32_t)hub_degree, pl, P.pmisc);
     });
     L.run(GREM_KERNEL_RELAYOUT, [&] {
-        hipLaunchKernelGGL(k_plan_chunks, dim3((unsigned)geo.nch), dim3(256), 0, stream, n, cl, nsl, geo.nblk, pl,
-                           P.pmisc);
+        hipLaunchKernelGGL(k_plan_chunks, dim3((unsigned)geo.nch), dim3(256), 0, stream, n, cl, nsl, geo.nblk,
+                           (uint32_t)(kmax > 16 ? kHubsPerShare32 : kHubsPerShare16), pl, P.pmisc);
     });
     L.run(GREM_KERNEL_RELAYOUT, [&] {
         hipLaunchKernelGGL(k_tp_scan, dim3(3), dim3(1024), 0, stream, pl.ch_hbase, (int64_t)geo.nch, pl.ch_reg0,
@@ -418,10 +427,11 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
     // a share may touch kMaxShareHubs hubs; sub-segment offsets are 32-bit
     {
         auto score_fits = [&](int kk) {
-            const size_t score_lds = ((size_t)kSliceRows / 2 + (size_t)share_hubs * kk + 3 * (size_t)kk) * 4;
-            return score_lds + (size_t)kSliceRows * 32 <= 150 * 1024;
+            const size_t dyn = ((size_t)kSliceRows / 2 + (size_t)share_hubs * kk + 3 * (size_t)kk) * 4;
+            if (kk <= 16) return dyn + (size_t)kSliceRows * 32 <= 150 * 1024;
+            return geo.cb <= 16 && dyn + (size_t)kSliceRows * 64 <= 158 * 1024;    // (a byte per label in the look-up's LDS)
         };
-        int max_k = k ? k : kSweepMaxK;
+        int max_k = kmax;
         while (max_k > 1 && !score_fits(max_k) && k == 0) --max_k;
         P.max_k = max_k;
         // (the index of a word of Lx -- eight labels -- travels in 32 bits of T)
@@ -491,8 +501,7 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
     tb.ngroups = geo.ngroups;
     tb.npr = npr;
     tb.nps = nps;
-    P.lookup_lds = (size_t)1 << (geo.cb > 5 ? geo.cb - 1 : 4);
-    P.lookup_target = P.lookup_lds > 80 * 1024 ? 256 : 512;
+    P.lookup_target = geo.cb > 17 ? 256 : 512;
 
     const Arena::Mark tmark = temp.mark();
     const size_t subs = (size_t)geo.nch * (size_t)d.nr * (size_t)geo.nblk;
@@ -635,7 +644,7 @@ struct TpState {
 void state_two_phase(Carver &c, TpState &t, int64_t n, int32_t k, size_t slots, size_t max_chunk_hubs, size_t total_hubs,
                      bool seeded, bool use16, bool external_E) {
     uint8_t *lx = nullptr;
-    c.take(lx, slots / 2 + 16);                                   // label, 4 bits per tuple
+    c.take(lx, (k <= 16 ? slots / 2 : slots) + 16);               // label, 4 bits per tuple (8 when k > 16)
     t.Lx = reinterpret_cast<uint32_t *>(lx);
     c.take(t.Hhub, (max_chunk_hubs + 1) * (size_t)k);
     c.take(t.Rdyn, seeded ? slots + 8 : 0);                       // seeded runs: R with the unassigned neighbours marked
@@ -686,12 +695,25 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
     }
     uint32_t *E32 = external_E ? estimates_out : t.E32;
     uint32_t *Ehub_rows = (use16 && !external_E) ? nullptr : E32;    // hubs: rows of E32 when there is one, else Ehub
-    const size_t score_lds = ((size_t)kSliceRows / 2 + (size_t)P.share_hubs * k + 3 * (size_t)k) * 4;
-    if (!set_lds((const void *)k_tp_lookup<true, false>, P.lookup_lds) ||
-        !set_lds((const void *)k_tp_lookup<true, true>, P.lookup_lds) ||
-        !set_lds((const void *)k_tp_score<uint32_t>, score_lds) ||
-        !set_lds((const void *)k_tp_score<uint16_t>, score_lds))
-        return GREM_ERR_HIP;
+    if (k > P.max_k) return GREM_ERR_ARG;
+    const bool wide = k > 16;                     // 8-bit labels in Lx, 128 KB of counters per slice
+    const size_t score_lds = ((size_t)kSliceRows / 2 + (size_t)P.share_hubs * k + 3 * (size_t)k) * 4 +
+                             (wide ? (size_t)kSliceRows * 64 : 0);
+    const size_t lookup_lds = wide ? ((size_t)1 << (geo.cb > 4 ? geo.cb : 4)) : ((size_t)1 << (geo.cb > 5 ? geo.cb - 1 : 4));
+    if (wide) {
+        if (!set_lds((const void *)k_tp_lookup<true, false, 8>, lookup_lds) ||
+            !set_lds((const void *)k_tp_lookup<true, true, 8>, lookup_lds) ||
+            !set_lds((const void *)k_tp_score<uint32_t, 32>, score_lds) ||
+            !set_lds((const void *)k_tp_score<uint16_t, 32>, score_lds) ||
+            !set_lds((const void *)k_apply<uint8_t, false>, ((size_t)k + (size_t)(kAdmitThreads / 64) * k + 2 * (size_t)k) * 4))
+            return GREM_ERR_HIP;
+    } else {
+        if (!set_lds((const void *)k_tp_lookup<true, false, 4>, lookup_lds) ||
+            !set_lds((const void *)k_tp_lookup<true, true, 4>, lookup_lds) ||
+            !set_lds((const void *)k_tp_score<uint32_t, 16>, score_lds) ||
+            !set_lds((const void *)k_tp_score<uint16_t, 16>, score_lds))
+            return GREM_ERR_HIP;
+    }
     L.memset(t.Hhub, 0, ((size_t)P.max_chunk_hubs + 1) * (size_t)k * 4);
 
     // look-ups of the labels of chunks [c0, c0 + count): shares per column block sized so that one
@@ -707,16 +729,20 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
         if (spb > by_work) spb = (int)by_work;
         if (spb < 1) spb = 1;
         const dim3 grid((unsigned)(geo.nbc * spb), (unsigned)count);
+        auto go = [&](auto kernel, size_t lds) {
+            hipLaunchKernelGGL(kernel, grid, dim3(kTpThreads), lds, stream, P.T, t.Lx, P.R, t.Rdyn, tb,
+                               (const uint8_t *)st.Lc, n, c0, cmin, spb);
+        };
         L.run(GREM_KERNEL_LOOKUP, [&] {
-            if (!from_lds)
-                hipLaunchKernelGGL((k_tp_lookup<false, true>), grid, dim3(kTpThreads), 0, stream, P.T, t.Lx, P.R, t.Rdyn,
-                                   tb, (const uint8_t *)st.Lc, n, c0, cmin, spb);
-            else if (mark)
-                hipLaunchKernelGGL((k_tp_lookup<true, true>), grid, dim3(kTpThreads), P.lookup_lds, stream, P.T, t.Lx,
-                                   P.R, t.Rdyn, tb, (const uint8_t *)st.Lc, n, c0, cmin, spb);
-            else
-                hipLaunchKernelGGL((k_tp_lookup<true, false>), grid, dim3(kTpThreads), P.lookup_lds, stream, P.T, t.Lx,
-                                   P.R, t.Rdyn, tb, (const uint8_t *)st.Lc, n, c0, cmin, spb);
+            if (wide) {
+                if (!from_lds) go(k_tp_lookup<false, true, 8>, 0);
+                else if (mark) go(k_tp_lookup<true, true, 8>, lookup_lds);
+                else go(k_tp_lookup<true, false, 8>, lookup_lds);
+            } else {
+                if (!from_lds) go(k_tp_lookup<false, true, 4>, 0);
+                else if (mark) go(k_tp_lookup<true, true, 4>, lookup_lds);
+                else go(k_tp_lookup<true, false, 4>, lookup_lds);
+            }
         });
     };
     if (seed) {        // the seeds are the labels every first-pass look-up starts from
@@ -739,31 +765,57 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             // pass does not store them otherwise
             const int store_e = (pass < R || external_E) ? 1 : 0;
             const uint16_t *rows_now = (seed && pass == 0) ? t.Rdyn : P.R;
+            auto score = [&](auto kernel, auto *Eptr) {
+                hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kTpThreads), score_lds, stream, rows_now, t.Lx, tb, pl,
+                                   (const uint8_t *)st.Lc, st.S, Eptr, t.Hhub, (uint8_t *)st.prop, st.cnt, st.room, (int)c,
+                                   lo, hi, (int)k, jlim, P.share_hubs, P.nvs[(size_t)c], pass, cap, store_e);
+            };
             L.run(GREM_KERNEL_SCORE, [&] {
-                if (use16)
-                    hipLaunchKernelGGL((k_tp_score<uint16_t>), dim3(blocks), dim3(kTpThreads), score_lds, stream,
-                                       rows_now, t.Lx, tb, pl, (const uint8_t *)st.Lc, st.S, t.E16, t.Hhub,
-                                       (uint8_t *)st.prop, st.cnt, st.room, (int)c, lo, hi, (int)k, jlim, P.share_hubs,
-                                       P.nvs[(size_t)c], pass, cap, store_e);
-                else
-                    hipLaunchKernelGGL((k_tp_score<uint32_t>), dim3(blocks), dim3(kTpThreads), score_lds, stream,
-                                       rows_now, t.Lx, tb, pl, (const uint8_t *)st.Lc, st.S, E32, t.Hhub,
-                                       (uint8_t *)st.prop, st.cnt, st.room, (int)c, lo, hi, (int)k, jlim, P.share_hubs,
-                                       P.nvs[(size_t)c], pass, cap, store_e);
+                if (wide) {
+                    if (use16) score(k_tp_score<uint16_t, 32>, t.E16);
+                    else score(k_tp_score<uint32_t, 32>, E32);
+                } else {
+                    if (use16) score(k_tp_score<uint16_t, 16>, t.E16);
+                    else score(k_tp_score<uint32_t, 16>, E32);
+                }
             });
-            // (one workgroup more than the hubs need: it adds up the chunk's mover counts)
+            // (k <= 16: one workgroup more than the hubs need: it adds up the chunk's mover counts)
             L.run(GREM_KERNEL_HUBS, [&] {
-                hipLaunchKernelGGL(k_hub_finalize, dim3((unsigned)((max_chunk_hubs + 15) / 16) + 1), dim3(256), 0, stream,
-                                   pl, (const uint8_t *)st.Lc, st.room, Ehub_rows, t.Ehub, t.Hhub, (uint8_t *)st.prop,
-                                   st.cnt, (int)c, lo, (int)k, pass, store_e, (int)admit_blocks, st.tot);
+                if (wide)
+                    hipLaunchKernelGGL(k_hub_finalize<32>, dim3((unsigned)((max_chunk_hubs + 7) / 8) + 1), dim3(256), 0,
+                                       stream, pl, (const uint8_t *)st.Lc, st.room, Ehub_rows, t.Ehub, t.Hhub,
+                                       (uint8_t *)st.prop, st.cnt, (int)c, lo, (int)k, pass, store_e, (int)admit_blocks,
+                                       st.tot, 0);
+                else
+                    hipLaunchKernelGGL(k_hub_finalize<16>, dim3((unsigned)((max_chunk_hubs + 15) / 16) + 1), dim3(256), 0,
+                                       stream, pl, (const uint8_t *)st.Lc, st.room, Ehub_rows, t.Ehub, t.Hhub,
+                                       (uint8_t *)st.prop, st.cnt, (int)c, lo, (int)k, pass, store_e, (int)admit_blocks,
+                                       st.tot, 1);
             });
-            // admission: the score kernel has counted the movers per tile and taken the sizes' snapshot, and
-            // the tiles are few enough that every workgroup adds up the earlier tiles' counts itself
-            L.run(GREM_KERNEL_APPLY, [&] {
-                hipLaunchKernelGGL(k_apply16, dim3((admit_blocks + kApply16Tiles - 1) / kApply16Tiles), dim3(kAdmitTile), 0,
-                                   stream, (uint8_t *)st.Lc, (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room,
-                                   st.tot, (unsigned long long *)st.S, st.ocnt, pass);
-            });
+            if (!wide) {
+                // admission: the score kernel has counted the movers per tile and taken the sizes' snapshot, and
+                // the tiles are few enough that every workgroup adds up the earlier tiles' counts itself
+                L.run(GREM_KERNEL_APPLY, [&] {
+                    hipLaunchKernelGGL(k_apply16, dim3((admit_blocks + kApply16Tiles - 1) / kApply16Tiles), dim3(kAdmitTile),
+                                       0, stream, (uint8_t *)st.Lc, (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room,
+                                       st.tot, (unsigned long long *)st.S, st.ocnt, pass);
+                });
+            } else {
+                // admission as on the plain route: per-tile mover counts, their prefix over the tiles, ranks
+                L.run(GREM_KERNEL_COUNT, [&] {
+                    hipLaunchKernelGGL((k_count<uint8_t>), dim3(admit_blocks), dim3(kAdmitThreads), (size_t)k * 4, stream,
+                                       st.Lc, st.prop, lo, hi, (int)k, st.cnt);
+                });
+                L.run(GREM_KERNEL_SCAN, [&] {
+                    hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), 0, stream, st.cnt, (int)admit_blocks, (int)k,
+                                       st.S, cap, st.room);
+                });
+                L.run(GREM_KERNEL_APPLY, [&] {
+                    hipLaunchKernelGGL((k_apply<uint8_t, false>), dim3(admit_blocks), dim3(kAdmitThreads),
+                                       ((size_t)k + (size_t)(kAdmitThreads / 64) * k + 2 * (size_t)k) * 4, stream, st.Lc,
+                                       st.prop, lo, hi, (int)k, st.cnt, st.room, (unsigned long long *)st.S, st.ocnt, pass);
+                });
+            }
             if (pass == 0) launch_spill<uint8_t>(L, st, lo, hi, k, admit_blocks);
             // the chunk's new labels, looked up for every row that will read them: rows of later chunks in
             // this pass, rows of this and earlier chunks in the next pass (if there is one)
@@ -907,7 +959,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
     const bool forced = o.hist_mode == GREM_HIST_SWEEP;
     bool try_sweep = false;
     if constexpr (sizeof(LabelT) == 1) {
-        const TpGeom geo = tp_geometry(n, cl, o.col_bits);
+        const TpGeom geo = tp_geometry(n, cl, o.col_bits, k);
         const bool can = k <= kSweepMaxK && geo.ok && (((uintptr_t)estimates_out) & 15u) == 0;
         if (forced && !can) return GREM_ERR_ARG;
         try_sweep = can && (forced || (o.hist_mode == GREM_HIST_AUTO && n >= kSweepMinN && cl >= kSweepMinChunk));
@@ -1036,7 +1088,7 @@ size_t grem_workspace_bytes_two_phase(int64_t n, int64_t nnz, int32_t k, int64_t
     if (!resolve_options(options, &o)) return 0;
     const int64_t cl = chunk < n ? chunk : n;
     const size_t plain = plain_bytes(n, k, cl, false);
-    const TpGeom geo = tp_geometry(n, cl, o.col_bits);
+    const TpGeom geo = tp_geometry(n, cl, o.col_bits, k);
     if (k > kSweepMaxK || !geo.ok) return plain;
     PlanDims d{};
     d.n = n;
@@ -1147,7 +1199,7 @@ int grem_plan_create(const void *rowptr, int32_t rowptr_bits, const int32_t *col
     Opts o;
     if (!resolve_options(options, &o)) return GREM_ERR_ARG;
     const int64_t cl = chunk < n ? chunk : n;
-    if (!tp_geometry(n, cl, o.col_bits).ok) return GREM_ERR_ARG;
+    if (!tp_geometry(n, cl, o.col_bits, o.plan_max_k).ok) return GREM_ERR_ARG;
     grem_plan *p = new (std::nothrow) grem_plan();
     if (!p) return GREM_ERR_NOMEM;
     hipStream_t s = (hipStream_t)stream;
@@ -1186,6 +1238,20 @@ int grem_plan_destroy(grem_plan *plan) {
 size_t grem_plan_device_bytes(const grem_plan *plan) { return plan ? plan->mem.total : 0; }
 
 int32_t grem_plan_max_k(const grem_plan *plan) { return plan ? plan->data.max_k : 0; }
+
+size_t grem_plan_call_bytes(const grem_plan *plan, int32_t k, int32_t refine_passes, int32_t seeded,
+                            int32_t with_estimates_out) {
+    if (!plan || !plan->data.T || k < 1 || k > plan->data.max_k || refine_passes < 0 || refine_passes >= 32) return 0;
+    const PlanData &P = plan->data;
+    const bool use16 = (((unsigned long long)(P.hub_degree - 1)) << refine_passes) <= 65535ull;
+    CallState<uint8_t> st;
+    TpState t;
+    return carve_size([&](Carver &c) { state_common(c, st, P.n, (int64_t)P.geo.chunk, k); }) +
+           carve_size([&](Carver &c) {
+               state_two_phase(c, t, P.n, k, P.slots, (size_t)P.max_chunk_hubs, (size_t)P.total_hubs, seeded != 0, use16,
+                               with_estimates_out != 0);
+           });
+}
 
 int grem_partition_planned(const grem_plan *plan, int32_t k, double balance_slack, int32_t refine_passes,
                            const int32_t *seed_labels, int32_t *labels_out, int64_t *sizes_out,

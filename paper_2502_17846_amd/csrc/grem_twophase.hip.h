@@ -205,14 +205,14 @@ __global__ __launch_bounds__(256) void k_plan_slices(const RowT *__restrict__ ro
 
 // ------------------------------------------------------------------------------------------------
 // plan 2: per chunk, exclusive prefixes over its slices, and the number of hub shares: enough
-// shares that one touches at most about 1024 hubs, few enough that a share's sub-segment of a
+// shares that one touches at most about hubs_per_share hubs, few enough that a share's sub-segment of a
 // column block still holds some 64 entries, at most one per slice.  misc[6] = most hubs in a
 // chunk, misc[7] = most entries in a chunk, misc[9] = most regular entries in a slice (set here
 // from the slices' counts), misc[10] = most entries in a hub share, misc[11] = most hub shares in a
 // chunk, misc[8] = hub entries of all chunks, misc[12] = hubs of all chunks.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, int nsl, int nblk,
-                                                     SweepPlan pl, u64 *__restrict__ misc) {
+                                                     uint32_t hubs_per_share, SweepPlan pl, u64 *__restrict__ misc) {
     __shared__ u64 p_reg[256], p_hent[256];
     __shared__ uint32_t p_nh[256];
     const int tid = threadIdx.x;
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(256) void k_plan_chunks(int64_t n, int64_t chunk, i
         u64 nvs = 0;
         if (bnh != 0) {
             nvs = bhent / (64ull * (u64)nblk);
-            const u64 by_hubs = ((u64)bnh + 1023ull) / 1024ull;
+            const u64 by_hubs = ((u64)bnh + hubs_per_share - 1ull) / (u64)hubs_per_share;
             if (nvs < by_hubs) nvs = by_hubs;
             if (nvs < 1) nvs = 1;
             if (nvs > nsl_c) nvs = nsl_c;
@@ -937,7 +937,7 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
 // in T, which are one contiguous piece.
 //   T  (read)   : per tuple 3 bytes: the column in its block, and above it 4 of the 32 bits of the
 //                 index of the word of Lx the labels of the tuple's group of eight go to
-//   Lx (written): the label of every tuple, 4 bits each, sub-segments ordered (c', r, jb): a group's
+//   Lx (written): the label of every tuple, LB = 4 bits each (8 when k > 16), sub-segments ordered (c', r, jb): a group's
 //                 word lies in the stream of its row slice, so the writes of one sub-segment are a
 //                 contiguous piece of some 40 bytes; the pieces of the chunk's column blocks are
 //                 neighbours and are written by workgroups of one XCD at about the same time, so that
@@ -955,14 +955,14 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
 // ------------------------------------------------------------------------------------------------
 constexpr int kLookupUnroll = 2;       // groups of eight per thread in flight
 
-template <bool FROM_LDS, bool WRITE_R>
+template <bool FROM_LDS, bool WRITE_R, int LB>
 __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tp_lookup(const uint32_t *__restrict__ T,
                                                           uint32_t *__restrict__ Lx,
                                                           const uint16_t *__restrict__ R,
                                                           uint16_t *__restrict__ Rdyn, TpTables tb,
                                                           const uint8_t *__restrict__ Lc, int64_t n, int c0,
                                                           int cmin, int spb) {
-    extern __shared__ uint32_t tab[];      // 2^cb / 8 words (FROM_LDS)
+    extern __shared__ uint32_t tab[];      // FROM_LDS: 2^cb labels, LB bits each
     const int tid = threadIdx.x;
     const int c = c0 + (int)blockIdx.y;
     const int m = (int)blockIdx.x / spb, s = (int)blockIdx.x % spb;
@@ -995,7 +995,22 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
     };
     load_groups((uint32_t)tid);             // on their way while the label table is built
 
-    if (FROM_LDS) {
+    if (FROM_LDS && LB == 8) {
+        // the block's labels as they are, a byte each
+        const int64_t bv = (chunk_hi - block_lo) < (1ll << tb.cb) ? (chunk_hi - block_lo) : (1ll << tb.cb);
+        const uint8_t *lsrc = Lc + block_lo;
+        uint8_t *tb8 = reinterpret_cast<uint8_t *>(tab);
+        if ((((uintptr_t)lsrc) & 15u) == 0) {
+            const int64_t pieces = bv >> 4;
+            for (int64_t i = tid; i < pieces; i += kTpThreads)
+                reinterpret_cast<u32x4 *>(tab)[i] = *reinterpret_cast<const u32x4 *>(lsrc + i * 16);
+            for (int64_t o = (pieces << 4) + tid; o < bv; o += kTpThreads) tb8[o] = lsrc[o];
+        } else {
+            for (int64_t o = tid; o < bv; o += kTpThreads) tb8[o] = lsrc[o];
+        }
+        __syncthreads();
+    }
+    if (FROM_LDS && LB == 4) {
         const int64_t bv = (chunk_hi - block_lo) < (1ll << tb.cb) ? (chunk_hi - block_lo) : (1ll << tb.cb);
         const int words = (int)((bv + 7) >> 3);
         const uint8_t *lsrc = Lc + block_lo;
@@ -1052,23 +1067,31 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
             raw[5] = ((t[u][1].x >> 24) | (t[u][1].y << 8)) & 0xFFFFFFu;
             raw[6] = ((t[u][1].y >> 16) | (t[u][1].z << 16)) & 0xFFFFFFu;
             raw[7] = t[u][1].z >> 8;
-            uint32_t word = 0, unassigned = 0, dest = 0;
+            uint32_t word = 0, word2 = 0, unassigned = 0, dest = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const uint32_t col = raw[e] & cmask;
                 dest |= ((raw[e] >> tb.cb) & 15u) << (4 * e);
                 uint32_t lab;
                 if (FROM_LDS) {
-                    lab = ((uint32_t)tbytes[col >> 1] >> (4 * (col & 1u))) & 15u;
+                    lab = LB == 4 ? ((uint32_t)tbytes[col >> 1] >> (4 * (col & 1u))) & 15u : (uint32_t)tbytes[col];
                 } else {
                     const int64_t v = block_lo + (int64_t)col;
                     const uint32_t l = v < chunk_hi ? (uint32_t)Lc[v] : 0xFFu;
                     if (l == 0xFFu) unassigned |= 1u << e;
-                    lab = l & 15u;
+                    lab = LB == 4 ? (l & 15u) : (l == 0xFFu ? 0u : l);
                 }
-                word |= lab << (4 * e);
+                if (LB == 4) word |= lab << (4 * e);
+                else if (e < 4) word |= lab << (8 * e);
+                else word2 |= lab << (8 * (e - 4));
             }
-            Lx[dest] = word;
+            if (LB == 4) {
+                Lx[dest] = word;
+            } else {
+                u32x2 o;
+                o.x = word; o.y = word2;
+                reinterpret_cast<u32x2 *>(Lx)[dest] = o;
+            }
             if (WRITE_R) {
                 const u64 at = (u64)dest << 3;
                 const u32x4 rr = *reinterpret_cast<const u32x4 *>(R + at);
@@ -1090,22 +1113,46 @@ __device__ __forceinline__ uint32_t quad_swap(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 
-// Counting tuples: row fields from R (16 bits each, bit 0 set: not to be counted), labels from Lx (4
-// bits each).  The two tuples of one 32-bit word w of R; their labels are bits SH .. SH + 7 of
-// `labels`.  16 bits of R: row field << 5 | skip (bit 0: padding, or an unassigned neighbour), so
-// row field << 5 is the byte offset of the row's 16 counters of 16 bits, to which (label >> 1) << 2
-// adds the counter pair's; the label's bit 0 picks the half.
-template <bool COUNT16, int SH>
-__device__ __forceinline__ void tp_count_word(uint32_t w, uint32_t labels, int k, uint32_t *hist) {
-    const uint32_t live = ~w;                           // bit 0 / bit 16: the tuple is to be counted
+// Counting tuples: row fields from R (16 bits each, bit 0 set: not to be counted), labels from Lx (LB
+// = 4 or 8 bits each: 4 while k <= 16).  16 bits of R: row field << 5 | skip (bit 0: padding, or an
+// unassigned neighbour).  The row's KP (16 or 32) counters of 16 bits start at byte (row field << 5)
+// * KP / 16, to which (label >> 1) << 2 adds the counter pair's; the label's bit 0 picks the half.
+template <int LB> struct TpLabels;                      // the labels of a group of eight tuples
+template <> struct TpLabels<4> {
+    uint32_t w;
+    __device__ __forceinline__ uint32_t get(int e) const { return (w >> (4 * e)) & 15u; }
+    __device__ __forceinline__ static TpLabels load(const uint32_t *__restrict__ Lx, u64 base, uint32_t g) {
+        TpLabels x;
+        x.w = __builtin_nontemporal_load(Lx + (base >> 3) + g);
+        return x;
+    }
+    __device__ __forceinline__ static TpLabels none() { TpLabels x; x.w = 0; return x; }
+};
+template <> struct TpLabels<8> {
+    u32x2 w;
+    __device__ __forceinline__ uint32_t get(int e) const { return ((e < 4 ? w.x : w.y) >> (8 * (e & 3))) & 255u; }
+    __device__ __forceinline__ static TpLabels load(const uint32_t *__restrict__ Lx, u64 base, uint32_t g) {
+        TpLabels x;
+        x.w = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(Lx + (base >> 2)) + g);
+        return x;
+    }
+    __device__ __forceinline__ static TpLabels none() { TpLabels x; x.w = (u32x2)(0u); return x; }
+};
+
+// a group of eight tuples: 16 bytes of R, their labels
+template <bool COUNT16, int KP, int LB>
+__device__ __forceinline__ void tp_count_eight(const u32x4 rows, const TpLabels<LB> labels, int k, uint32_t *hist) {
+    const uint32_t w[4] = {rows.x, rows.y, rows.z, rows.w};
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const uint32_t lab = (labels >> (SH + 4 * h)) & 15u;
-        const uint32_t r = h == 0 ? (w & 0xFFE0u) : ((w >> 16) & 0xFFE0u);
-        const uint32_t one = (live >> (16 * h)) & 1u;
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t half = (e & 1) ? (w[e >> 1] >> 16) : w[e >> 1];
+        const uint32_t lab = labels.get(e);
+        const uint32_t r = half & 0xFFE0u;
+        const uint32_t one = (~half) & 1u;                // bit 0 clear: the tuple is to be counted
         if (COUNT16) {
             // no branch: what is not to be counted adds zero (to a counter its bits happen to name)
-            uint32_t *ctr = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(hist) + (r | ((lab & 14u) << 1)));
+            const uint32_t off = (KP == 16 ? r : r << 1) | ((lab & ~1u) << 1);
+            uint32_t *ctr = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(hist) + off);
             atomicAdd(ctr, one << ((lab & 1u) << 4));
         } else if (one) {
             atomicAdd(&hist[(r >> 5) * (uint32_t)k + lab], 1u);
@@ -1113,39 +1160,35 @@ __device__ __forceinline__ void tp_count_word(uint32_t w, uint32_t labels, int k
     }
 }
 
-// a group of eight tuples: 16 bytes of R, one word of Lx
-template <bool COUNT16>
-__device__ __forceinline__ void tp_count_eight(const u32x4 rows, uint32_t labels, int k, uint32_t *hist) {
-    tp_count_word<COUNT16, 0>(rows.x, labels, k, hist);
-    tp_count_word<COUNT16, 8>(rows.y, labels, k, hist);
-    tp_count_word<COUNT16, 16>(rows.z, labels, k, hist);
-    tp_count_word<COUNT16, 24>(rows.w, labels, k, hist);
-}
-
 // Groups [g0, g1) of a row stream that starts at slot `base` (a multiple of 8) of R and Lx, counted by
 // the whole workgroup, NU groups per thread in flight.
-template <bool COUNT16, int NU>
+template <bool COUNT16, int KP, int LB, int NU>
 __device__ __forceinline__ void tp_count_stream(const uint16_t *__restrict__ R, const uint32_t *__restrict__ Lx, u64 base,
                                                 uint32_t g0, uint32_t g1, int k, uint32_t *hist) {
     const u32x4 *R4 = reinterpret_cast<const u32x4 *>(R + base);
-    const uint32_t *L1 = Lx + (base >> 3);
     for (uint32_t g = g0 + threadIdx.x; g < g1; g += kTpThreads * NU) {
         u32x4 rows[NU];
-        uint32_t labs[NU];
+        TpLabels<LB> labs[NU];
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
             const uint32_t gi = g + u * kTpThreads;
             rows[u] = (u32x4)(1u | (1u << 16));         // nothing to count
-            labs[u] = 0;
+            labs[u] = TpLabels<LB>::none();
             if (gi < g1) {
                 rows[u] = __builtin_nontemporal_load(R4 + gi);
-                labs[u] = __builtin_nontemporal_load(L1 + gi);
+                labs[u] = TpLabels<LB>::load(Lx, base, gi);
             }
         }
 #pragma unroll
         for (int u = 0; u < NU; ++u)
-            if (g + u * kTpThreads < g1) tp_count_eight<COUNT16>(rows[u], labs[u], k, hist);
+            if (g + u * kTpThreads < g1) tp_count_eight<COUNT16, KP, LB>(rows[u], labs[u], k, hist);
     }
+}
+
+// The value of lane (l ^ 4), (l ^ 8): through the LDS crossbar.
+__device__ __forceinline__ unsigned long long tp_xor_lane64(unsigned long long v, int mask) {
+    return ((unsigned long long)(uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), mask) << 32) |
+           (unsigned long long)(uint32_t)__shfl_xor((int)(uint32_t)v, mask);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1157,27 +1200,34 @@ __device__ __forceinline__ void tp_count_stream(const uint16_t *__restrict__ R, 
 // movers of its two admission tiles per proposed partition (cnt, the input of the admission;
 // k_hub_finalize adds the hubs).
 //
-// Four lanes share a vertex in the blend: lane q owns partitions 4q .. 4q+3 when k % 4 == 0 (one
-// 16-byte piece of E's row), else q, q+4, q+8, q+12.
-// LDS: hist[kSliceRows * 8] (16-bit counters, 16 per row), meta[kSliceRows / 2] (per row: old label,
-//      hub flag << 8), hhist[share_hubs * k], room[k], tcnt[2 * k]
+// KP = 16 (k <= 16, 4-bit labels in Lx, 64 KB of counters: two workgroups per CU) or 32 (k <= 32,
+// 8-bit labels, 128 KB of counters: one workgroup per CU).  KP / 4 lanes share a vertex in the
+// blend: lane q owns partitions 4q .. 4q+3 when k % 4 == 0 (one 8- or 16-byte piece of E's row), else
+// q, q + KP/4, q + 2 KP/4, q + 3 KP/4.
+// LDS: hist[kSliceRows * KP / 2] (16-bit counters, KP per row; a static array when KP = 16),
+//      meta[kSliceRows / 2] (per row: old label, hub flag << 8), hhist[share_hubs * k], room[k], tcnt[2 * k]
 // ------------------------------------------------------------------------------------------------
-template <typename ET>
-__global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tp_score(
+template <typename ET, int KP>
+__global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP == 16 ? 8 : 4, KP == 16 ? 8 : 4))) void k_tp_score(
     const uint16_t *__restrict__ R, const uint32_t *__restrict__ Lx, TpTables tb, SweepPlan pl,
     const uint8_t *__restrict__ Lc, const long long *__restrict__ S, ET *__restrict__ E,
     uint32_t *__restrict__ Hhub, uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
     long long *__restrict__ room_out, int c, int64_t chunk_lo, int64_t chunk_hi, int k, int jlim,
     int share_hubs, uint32_t nvs, int pass, long long P, int store_e) {
     extern __shared__ uint32_t smem[];
-    constexpr int hist_words = kSliceRows * 8;
-    constexpr int BU = kSliceRows * 4 / kTpThreads;     // (vertex, quarter) pairs per thread
+    constexpr int LB = KP == 16 ? 4 : 8;
+    constexpr int LPV = KP / 4;                                 // lanes per vertex in the blend
+    constexpr int hist_words = kSliceRows * KP / 2;
+    constexpr int BU = kSliceRows * LPV / kTpThreads;           // (vertex, lane of the vertex) pairs per thread
+    constexpr int IDB = KP == 16 ? 4 : 5;                       // bits of a partition id in the arg-max key
     static_assert(kSliceRows == 2 * kAdmitTile, "a slice is two admission tiles");
-    // the counters are a static array: its address is a compile-time constant, which spares an add
-    // per counted entry
-    __shared__ uint32_t hist[hist_words];
-    uint16_t *meta = reinterpret_cast<uint16_t *>(smem);                // kSliceRows
-    uint32_t *hhist = smem + kSliceRows / 2;                            // share_hubs * k, 32-bit
+    // KP = 16: the counters are a static array: its address is a compile-time constant, which spares an
+    // add per counted entry
+    __shared__ uint32_t hist_static[KP == 16 ? hist_words : 1];
+    uint32_t *hist = KP == 16 ? hist_static : smem;
+    uint32_t *dyn = KP == 16 ? smem : smem + hist_words;
+    uint16_t *meta = reinterpret_cast<uint16_t *>(dyn);                 // kSliceRows
+    uint32_t *hhist = dyn + kSliceRows / 2;                             // share_hubs * k, 32-bit
     uint32_t *room = hhist + share_hubs * k;    // k
     uint32_t *tcnt = room + k;                  // 2 * k
     const int tid = threadIdx.x;
@@ -1226,7 +1276,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
         for (int j = tid; j < k; j += kTpThreads) {
             const long long rj = P - S[j];
             room[j] = (uint32_t)rj;
-            if (slice == 0) room_out[j] = rj;           // the sizes' snapshot k_apply admits against
+            if (slice == 0) room_out[j] = rj;           // the sizes' snapshot the admission works against
         }
         for (int j = tid; j < 2 * k; j += kTpThreads) tcnt[j] = 0;
         for (int t = tid; t < nv; t += kTpThreads) meta[t] = (uint16_t)Lc[v0 + t];
@@ -1235,22 +1285,8 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
     // the slice's hubs, from the chunk's list (read by the blend, after the next barrier)
     for (uint32_t i = tid; i < snh; i += kTpThreads) meta[(int64_t)pl.hub_row[slice_hub0 + i] - v0] |= (uint16_t)0x100u;
 
-    tp_count_stream<true, 4>(R, Lx, sbeg, 0u, slen >> 3, k, hist);
-    if (any_hub) tp_count_stream<false, 2>(R, Lx, hbeg, hg0, hg1, k, hhist);
-    // the stored estimates are requested before the barrier, so that they arrive while the slower
-    // wavefronts are still counting
-    const bool fast = sizeof(ET) == 2 && vec && P < (1ll << 27);
-    const int q4 = tid & 3;
-    const bool mine = 4 * q4 < k;
-    u32x2 e[BU];
-#pragma unroll
-    for (int u = 0; u < BU; ++u) {
-        const int g = tid + u * kTpThreads;
-        e[u] = (u32x2)(0u);
-        if (fast && pass > 0 && mine && g < nv * 4)
-            e[u] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x2 *>(E + (size_t)(v0 + (g >> 2)) * (size_t)k + 4 * q4));
-    }
+    tp_count_stream<true, KP, LB, 4>(R, Lx, sbeg, 0u, slen >> 3, k, hist);
+    if (any_hub) tp_count_stream<false, KP, LB, 2>(R, Lx, hbeg, hg0, hg1, k, hhist);
     __syncthreads();
 
     // partial counts of the share's hubs -> the chunk's hub table
@@ -1261,27 +1297,37 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
         }
     }
 
-    // k a multiple of 4 with 16-bit estimates (and sizes below 2^27): a thread's four partitions are
-    // one 8-byte piece of E and one of the counters; two packed adds blend them (no carry between the
-    // halves: an estimate stays below 2^16), and the arg-max by (E desc, room desc, id asc) is the
-    // maximum of one 64-bit key per partition, E << 40 | room << 4 | 15 - id, 0 if the partition is
-    // full (or does not exist: the lanes past k of a vertex's quad hold no partition).
-    if (fast) {
-        const int q = q4;
-        const int sh = pass > 0 ? pass - 1 : 0;
-        uint32_t lo_base[4];
-#pragma unroll
-        for (int z = 0; z < 4; ++z) lo_base[z] = mine ? (room[4 * q + z] << 4) | (uint32_t)(15 - (4 * q + z)) : 0u;
+    const int sh = pass > 0 ? pass - 1 : 0;
+    const int q = tid & (LPV - 1);                              // this thread's lane of its vertices
+    // k a multiple of 4 with 16-bit estimates (and sizes below 2^27 - IDB): a thread's four partitions
+    // are one 8-byte piece of E and one of the counters; two packed adds blend them (no carry between
+    // the halves: an estimate stays below 2^16), and the arg-max by (E desc, room desc, id asc) is the
+    // maximum of one 64-bit key per partition, E << 40 | room << IDB | KP - 1 - id, 0 if the partition
+    // is full (or does not exist: the lanes past k of a vertex hold no partition).
+    if (sizeof(ET) == 2 && vec && P < (1ll << (31 - IDB))) {
+        const bool mine = 4 * q < k;
+        u32x2 e[BU];
 #pragma unroll
         for (int u = 0; u < BU; ++u) {
             const int g = tid + u * kTpThreads;
-            if (g >= nv * 4) continue;
-            const int t = g >> 2;
+            e[u] = (u32x2)(0u);
+            if (pass > 0 && mine && g < nv * LPV)
+                e[u] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x2 *>(E + (size_t)(v0 + g / LPV) * (size_t)k + 4 * q));
+        }
+        uint32_t lo_base[4];
+#pragma unroll
+        for (int z = 0; z < 4; ++z) lo_base[z] = mine ? (room[4 * q + z] << IDB) | (uint32_t)(KP - 1 - (4 * q + z)) : 0u;
+#pragma unroll
+        for (int u = 0; u < BU; ++u) {
+            const int g = tid + u * kTpThreads;
+            if (g >= nv * LPV) continue;
+            const int t = g / LPV;
             const uint32_t mt = meta[t];
             if (mt & 0x100u) continue;                              // hubs are k_hub_finalize's
             const uint32_t old = mt & 0xFFu;
             const uint32_t oldz = old - 4u * (uint32_t)q;           // < 4: the old label is one of this thread's
-            const uint2 hw = *reinterpret_cast<const uint2 *>(hist + t * 8 + 2 * q);
+            const uint2 hw = *reinterpret_cast<const uint2 *>(hist + t * (KP / 2) + 2 * q);
             u32x2 o;
             o.x = e[u].x + (hw.x << sh);
             o.y = e[u].y + (hw.y << sh);
@@ -1291,8 +1337,8 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
 #pragma unroll
             for (int z = 0; z < 4; ++z) {
                 const uint32_t ez = z == 0 ? (o.x & 0xFFFFu) : z == 1 ? (o.x >> 16) : z == 2 ? (o.y & 0xFFFFu) : (o.y >> 16);
-                const uint32_t lo = lo_base[z] + (oldz == (uint32_t)z ? 16u : 0u);      // room + 1 without the vertex itself
-                const unsigned long long key = lo >= 16u ? (((unsigned long long)(ez << 8) << 32) | lo) : 0ull;
+                const uint32_t lo = lo_base[z] + (oldz == (uint32_t)z ? (1u << IDB) : 0u);    // room + 1 without the vertex itself
+                const unsigned long long key = lo >= (1u << IDB) ? (((unsigned long long)(ez << 8) << 32) | lo) : 0ull;
                 best = key > best ? key : best;
             }
 #pragma unroll
@@ -1302,8 +1348,12 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
                               : (((unsigned long long)quad_swap<0x4E>((uint32_t)(best >> 32)) << 32) | quad_swap<0x4E>((uint32_t)best));
                 best = other > best ? other : best;
             }
+            if (LPV > 4) {
+                const unsigned long long other = tp_xor_lane64(best, 4);
+                best = other > best ? other : best;
+            }
             if (q == 0) {
-                uint32_t bj = 15u - ((uint32_t)best & 15u);
+                uint32_t bj = (uint32_t)(KP - 1) - ((uint32_t)best & (uint32_t)(KP - 1));
                 if (pass == 0 && old != 0xFFu) bj = old;        // seeded vertex keeps its label
                 prop[v0 + t - chunk_lo] = (uint8_t)bj;
                 if (bj != old) atomicAdd(&tcnt[(t >> 10) * k + (int)bj], 1u);
@@ -1316,58 +1366,47 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
         return;
     }
 
-    // this thread's pieces of E, all loads in flight together
-    uint32_t ev[BU][4];
-#pragma unroll
-    for (int u = 0; u < BU; ++u) {
-#pragma unroll
-        for (int z = 0; z < 4; ++z) ev[u][z] = 0;
-        const int g = tid + u * kTpThreads;
-        if (pass > 0 && g < nv * 4) {
-            const int t = g >> 2, q = g & 3;
-            const ET *Erow = E + (size_t)(v0 + t) * (size_t)k;
-            if (vec) {
-                if (4 * q < k) {
-                    if (sizeof(ET) == 4) {
-                        const u32x4 e = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Erow + 4 * q));
-                        ev[u][0] = e.x; ev[u][1] = e.y; ev[u][2] = e.z; ev[u][3] = e.w;
-                    } else {
-                        const u32x2 e = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(Erow + 4 * q));
-                        ev[u][0] = e.x & 0xFFFFu; ev[u][1] = e.x >> 16; ev[u][2] = e.y & 0xFFFFu; ev[u][3] = e.y >> 16;
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int z = 0; z < 4; ++z)
-                    if (q + 4 * z < k) ev[u][z] = (uint32_t)Erow[q + 4 * z];
-            }
-        }
-    }
-
-    // blend and propose; arg-max by (E desc, room desc, id asc).  The four lanes of a vertex are a quad
-    // of the wavefront.
-    const int sh = pass > 0 ? pass - 1 : 0;
-#pragma unroll
+    // any k, 16- or 32-bit estimates: partition j = 4q + z (k % 4 == 0) or q + LPV z of lane q, a (vertex,
+    // lane) pair at a time; arg-max by (E desc, room desc, id asc)
+#pragma unroll 2
     for (int u = 0; u < BU; ++u) {
         const int g = tid + u * kTpThreads;
-        if (g >= nv * 4) continue;
-        const int t = g >> 2, q = g & 3;
+        if (g >= nv * LPV) continue;                            // (whole vertices: the lanes of a vertex agree)
+        const int t = g / LPV;
         const uint32_t mt = meta[t];
         if (mt & 0x100u) continue;                              // hubs are k_hub_finalize's
         const uint32_t old = mt & 0xFFu;
         const int64_t v = v0 + t;
         ET *Erow = E + (size_t)v * (size_t)k;
+        uint32_t ev[4] = {0u, 0u, 0u, 0u};
+        if (pass > 0) {
+            if (vec) {
+                if (4 * q < k) {
+                    if (sizeof(ET) == 4) {
+                        const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Erow + 4 * q));
+                        ev[0] = x.x; ev[1] = x.y; ev[2] = x.z; ev[3] = x.w;
+                    } else {
+                        const u32x2 x = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(Erow + 4 * q));
+                        ev[0] = x.x & 0xFFFFu; ev[1] = x.x >> 16; ev[2] = x.y & 0xFFFFu; ev[3] = x.y >> 16;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int z = 0; z < 4; ++z)
+                    if (q + LPV * z < k) ev[z] = (uint32_t)Erow[q + LPV * z];
+            }
+        }
         unsigned long long bestkey = 0;
         int bestj = 0x7fffffff;
 #pragma unroll
         for (int z = 0; z < 4; ++z) {
-            const int j = vec ? 4 * q + z : q + 4 * z;
+            const int j = vec ? 4 * q + z : q + LPV * z;
             if (j < k) {
-                const uint32_t cidx = (uint32_t)t * 16u + (uint32_t)j;
+                const uint32_t cidx = (uint32_t)t * (uint32_t)KP + (uint32_t)j;
                 const uint32_t h = (hist[cidx >> 1] >> (16 * (cidx & 1u))) & 0xFFFFu;
-                ev[u][z] += h << sh;
+                ev[z] += h << sh;
                 const uint32_t rm = room[j] + ((uint32_t)j == old ? 1u : 0u);
-                const unsigned long long key = rm ? (((unsigned long long)ev[u][z] << 32) | rm) : 0ull;
+                const unsigned long long key = rm ? (((unsigned long long)ev[z] << 32) | rm) : 0ull;
                 if (key > bestkey) { bestkey = key; bestj = j; }
             }
         }
@@ -1376,22 +1415,22 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
                 if (4 * q < k) {
                     if (sizeof(ET) == 4) {
                         u32x4 o;
-                        o.x = ev[u][0]; o.y = ev[u][1]; o.z = ev[u][2]; o.w = ev[u][3];
+                        o.x = ev[0]; o.y = ev[1]; o.z = ev[2]; o.w = ev[3];
                         __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(Erow + 4 * q));
                     } else {
                         u32x2 o;
-                        o.x = ev[u][0] | (ev[u][1] << 16);
-                        o.y = ev[u][2] | (ev[u][3] << 16);
+                        o.x = ev[0] | (ev[1] << 16);
+                        o.y = ev[2] | (ev[3] << 16);
                         __builtin_nontemporal_store(o, reinterpret_cast<u32x2 *>(Erow + 4 * q));
                     }
                 }
             } else {
 #pragma unroll
                 for (int z = 0; z < 4; ++z)
-                    if (q + 4 * z < k) Erow[q + 4 * z] = (ET)ev[u][z];
+                    if (q + LPV * z < k) Erow[q + LPV * z] = (ET)ev[z];
             }
         }
-        {   // lanes q ^ 1, then q ^ 2, by quad permutes
+        {   // lanes q ^ 1, then q ^ 2, by quad permutes; q ^ 4 through the crossbar
             unsigned long long okey = ((unsigned long long)quad_swap<0xB1>((uint32_t)(bestkey >> 32)) << 32) |
                                       quad_swap<0xB1>((uint32_t)bestkey);
             int oj = (int)quad_swap<0xB1>((uint32_t)bestj);
@@ -1400,6 +1439,11 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
                    quad_swap<0x4E>((uint32_t)bestkey);
             oj = (int)quad_swap<0x4E>((uint32_t)bestj);
             if (okey > bestkey || (okey == bestkey && oj < bestj)) { bestkey = okey; bestj = oj; }
+            if (LPV > 4) {
+                okey = tp_xor_lane64(bestkey, 4);
+                oj = __shfl_xor(bestj, 4);
+                if (okey > bestkey || (okey == bestkey && oj < bestj)) { bestkey = okey; bestj = oj; }
+            }
         }
         if (q == 0) {
             uint32_t best = (uint32_t)bestj;
@@ -1419,21 +1463,23 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
 // ------------------------------------------------------------------------------------------------
 // hubs of the chunk: counts from the hub table (complete once k_tp_score has finished), blend,
 // propose, add the movers to their tiles' counts; the table row is cleared for the next chunk.
-// 16 lanes per hub, lane j takes partition j (k <= 16).
-// ------------------------------------------------------------------------------------------------
+// KP lanes per hub, lane j takes partition j (k <= KP).
 // Estimates of the hubs: row v of E (n rows) when E is given, else row (ch_hub0[c] + i) of Ehub, the
 // table of the hubs alone.
+// The last workgroup (k <= 16 only: with_tot): tot[t] = an upper bound of the chunk's movers to
+// partition t, for k_apply16.
+// ------------------------------------------------------------------------------------------------
+template <int KP>
 __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_t *__restrict__ Lc,
                                                       const long long *__restrict__ room,
                                                       uint32_t *__restrict__ E, uint32_t *__restrict__ Ehub,
                                                       uint32_t *__restrict__ Hhub,
                                                       uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
                                                       int c, int64_t chunk_lo, int k, int pass, int store_e,
-                                                      int ntiles, uint32_t *__restrict__ tot) {
+                                                      int ntiles, uint32_t *__restrict__ tot, int with_tot) {
     const uint32_t nh = pl.ch_nh[c];
-    if (blockIdx.x == gridDim.x - 1) {
-        // the last workgroup: tot[t] = an upper bound of the chunk's movers to partition t, for
-        // k_apply16: the tiles' counts as far as they are complete, plus one for every hub
+    if (with_tot && blockIdx.x == gridDim.x - 1) {
+        // the tiles' counts as far as they are complete, plus one for every hub
         __shared__ uint32_t part[256];
         const int col = threadIdx.x & 15, seg = threadIdx.x >> 4;
         uint32_t sum = 0;
@@ -1458,8 +1504,9 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
         }
         return;
     }
-    const uint32_t i = blockIdx.x * 16u + (threadIdx.x >> 4);
-    const int j = threadIdx.x & 15;
+    constexpr int kPerBlock = 256 / KP;
+    const uint32_t i = blockIdx.x * (uint32_t)kPerBlock + (threadIdx.x / KP);
+    const int j = threadIdx.x & (KP - 1);
     const bool on = i < nh;
     const int sh = pass > 0 ? pass - 1 : 0;
     unsigned long long key = 0;
@@ -1483,7 +1530,7 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
         }
     }
 #pragma unroll
-    for (int off = 1; off <= 8; off <<= 1) {      // every lane of the wavefront takes part
+    for (int off = 1; off <= KP / 2; off <<= 1) {      // every lane of the wavefront takes part
         const unsigned long long okey = __shfl_xor(key, off);
         const int oj = __shfl_xor(bj, off);
         if (okey > key || (okey == key && oj < bj)) { key = okey; bj = oj; }

@@ -152,6 +152,22 @@ def test_two_phase_path_seeded_and_edge_cases():
     _check(h, 7, 1.1, 8192, 1, mode=B.HIST_SWEEP, col_bits=10, hub_degree=40)
 
 
+@pytest.mark.parametrize("k", [17, 20, 23, 32])
+def test_two_phase_path_17_to_32_partitions(k):
+    # 8-bit labels in the look-up results, 32 counters per row, eight lanes per vertex in the blend
+    g = synth.planted_partition(n=6000, blocks=3, mean_degree=10.0, seed=2)
+    _check(g, k, 1.05, 2500, 2, mode=B.HIST_SWEEP, col_bits=9, hub_degree=25, tag="wide")
+    _check(g, k, 1.0, 2049, 3, mode=B.HIST_SWEEP, col_bits=7, hub_degree=16, tag="wide, odd chunk")
+    _check(g, k, 1.05, 3000, 6, mode=B.HIST_SWEEP, hub_degree=2049, tag="wide, 32-bit estimates")
+    rng = np.random.default_rng(k)
+    seed = np.where(rng.random(g.n) < 0.3, rng.integers(0, k, g.n), -1).astype(np.int32)
+    _check(g, k, 1.1, 2500, 2, seed=seed, mode=B.HIST_SWEEP, col_bits=8, hub_degree=30, tag="wide, seeded")
+    r = synth.rmat(15, 16, seed=3, rowptr_dtype=torch.int64)
+    _check(r, k, 1.05, 1 << 13, 2, mode=B.HIST_SWEEP, col_bits=11, hub_degree=300, tag="wide, rmat")
+    h = synth.hub_stress(scale=14, edge_factor=8, hubs=3, hub_degree=3000, seed=2)
+    _check(h, k, 1.05, 3000, 2, mode=B.HIST_SWEEP, col_bits=9, hub_degree=200, tag="wide, hubs")
+
+
 def test_two_phase_path_big_hub():
     # one row longer than 65535 entries: 16-bit counters would overflow if it were not a hub
     h = synth.hub_stress(scale=17, edge_factor=4, hubs=2, hub_degree=100_000, seed=1, rowptr_dtype=torch.int64)
@@ -162,7 +178,10 @@ def test_two_phase_path_errors():
     g = synth.random_graph_np(100, 300, 0)
     rp, ci = _to_dev(g)
     with pytest.raises(B.GremError) as e:
-        B.grem_partition(rp, ci, g.n, 17, 1.05, 10, 1, options=B.options(B.HIST_SWEEP))
+        B.grem_partition(rp, ci, g.n, 33, 1.05, 10, 1, options=B.options(B.HIST_SWEEP))
+    assert e.value.code == B.ERR_ARG
+    with pytest.raises(B.GremError) as e:      # more than 16 partitions need column blocks of at most 2^16 vertices
+        B.grem_partition(rp, ci, g.n, 17, 1.05, 10, 1, options=B.options(B.HIST_SWEEP, col_bits=17))
     assert e.value.code == B.ERR_ARG
     for bad in (B.options(histogram_mode=7), B.options(col_bits=3), B.options(col_bits=19), B.options(hub_degree=-1),
                 B.options(hub_degree=65536), B.options(long_row_degree=-5)):

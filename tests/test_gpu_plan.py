@@ -35,6 +35,21 @@ def test_one_plan_many_runs(rdt):
     seed = np.where(rng.random(g.n) < 0.2, rng.integers(0, 3, g.n), -1).astype(np.int32)
     with B.Plan(rp, ci, g.n, chunk, B.options(col_bits=9, hub_degree=300)) as plan:
         assert plan.device_bytes > 5 * g.nnz and plan.max_k == 16
+        assert plan.call_bytes(17, 1) == 0 and plan.call_bytes(16, 2) > g.n * 33
+        # runs inside a workspace of the size the plan asks for
+        ws = torch.empty(plan.call_bytes(3, 2, seeded=True), dtype=torch.uint8, device=DEV)
+        B.grem_set_workspace(ws)
+        try:
+            sd_d = torch.as_tensor(seed).to(DEV)
+            out = B.grem_partition_planned(plan, 3, 1.05, 2, sd_d, want_sizes=True, want_estimates=False)
+            torch.cuda.synchronize()
+            assert np.array_equal(out[0].cpu().numpy(), oracle.partition_seeded(g.rowptr, g.colidx, g.n, 3, 1.05, chunk, 2, seed))
+            B.grem_set_workspace(ws[:1 << 16])
+            with pytest.raises(B.GremError) as e:
+                B.grem_partition_planned(plan, 16, 1.05, 2)
+            assert e.value.code == B.ERR_NOMEM
+        finally:
+            B.grem_set_workspace(None)
         del ci                                  # the plan does not read colidx after it has been built
         torch.cuda.empty_cache()
         for k, slack, R, sd in ((16, 1.05, 2, None), (3, 1.0, 1, seed), (16, 1.05, 2, None), (7, 1.3, 0, None),
@@ -48,6 +63,23 @@ def test_one_plan_many_runs(rdt):
             lab = B.grem_partition_planned(plan, k, slack, R, sd_d)
             torch.cuda.synchronize()
             assert torch.equal(lab, out[0])
+
+
+def test_a_plan_for_up_to_32_partitions():
+    g, rp, ci = _dev(synth.hub_stress(scale=14, edge_factor=8, hubs=3, hub_degree=3000, seed=2))
+    chunk = 3000
+    with B.Plan(rp, ci, g.n, chunk, B.options(col_bits=9, hub_degree=300, plan_max_k=32)) as plan:
+        assert plan.max_k == 32
+        for k, slack, R in ((32, 1.05, 2), (8, 1.05, 1), (21, 1.0, 2), (16, 1.1, 0)):
+            print(f"[case] planned run on a plan for 32: k={k} slack={slack} R={R}", flush=True)
+            out = B.grem_partition_planned(plan, k, slack, R, want_sizes=True, want_estimates=True)
+            torch.cuda.synchronize()
+            _same_as_oracle(g, out, k, slack, chunk, R)
+    with B.Plan(rp, ci, g.n, chunk, B.options(col_bits=9, hub_degree=300)) as plan:
+        assert plan.max_k == 16
+        with pytest.raises(B.GremError) as e:
+            B.grem_partition_planned(plan, 17, 1.05, 1)
+        assert e.value.code == B.ERR_ARG
 
 
 def test_planned_run_equals_the_unplanned_call():
