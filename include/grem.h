@@ -128,7 +128,7 @@ typedef struct grem_options {
 } grem_options;
 
 /* grem_partition_state with options.  GREM_ERR_ARG also for an unknown histogram mode, an option out
- * of range, GREM_HIST_LDS with k > 1024, GREM_HIST_SWEEP with k > 16 or a geometry the two-phase
+ * of range, GREM_HIST_LDS with k > 1024, GREM_HIST_SWEEP with k > 32 or a geometry the two-phase
  * route cannot take. */
 int grem_partition_opt(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
                        int32_t k, double balance_slack, int64_t chunk, int32_t refine_passes,
@@ -143,7 +143,8 @@ int grem_partition_opt(const void *rowptr, int32_t rowptr_bits, const int32_t *c
  * of a call.
  *
  * grem_plan_create re-lays the entries out (synchronous: it returns when the plan is complete) into
- * device memory the plan owns (hipMalloc; about 5.2 bytes per entry plus tables; an intermediate
+ * device memory the plan owns (hipMalloc; 5 bytes per entry and per pad slot plus the offset tables, 5.9 per
+ * entry in all on a 3.2e9-entry power-law graph; an intermediate
  * copy of 4 bytes per entry is allocated stream-ordered and released before the call returns).
  * rowptr must stay valid and unchanged while the plan lives; colidx is not read after the call
  * returns.  Errors: GREM_ERR_ARG (bad arguments or options, or a geometry the two-phase route cannot
@@ -152,7 +153,7 @@ int grem_partition_opt(const void *rowptr, int32_t rowptr_bits, const int32_t *c
  *
  * grem_partition_planned: the run of grem_partition_opt for the plan's graph and chunk size, k <= grem_plan_max_k,
  * same result bit for bit.  Per-call state (labels, estimates, the looked-up labels: about 0.5
- * bytes per entry plus n*(2k+1) bytes) comes from the workspace or a stream-ordered allocation.
+ * bytes per entry -- 1 byte when k > 16 -- plus n*(2k+1) bytes) comes from the workspace or a stream-ordered allocation.
  * Several runs may use one plan at the same time (it is read-only).  Without a seed the call reads
  * nothing back and returns as soon as its work is enqueued. */
 typedef struct grem_plan grem_plan;

@@ -5,7 +5,7 @@
 // Structure:
 //   Arena / carve      device memory for a call: pieces of the caller's workspace, or stream-ordered
 //                      allocations
-//   PlanData           the re-laid-out copy of a graph's entries for the two-phase route (k <= 16):
+//   PlanData           the re-laid-out copy of a graph's entries for the two-phase route (k <= 32):
 //                      built once per call, or once per graph behind a grem_plan
 //   run_two_phase      Alg. 1's loop on a plan
 //   run_plain          Alg. 1's loop straight on the CSR (any k)
@@ -704,8 +704,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
         if (!set_lds((const void *)k_tp_lookup<true, false, 8>, lookup_lds) ||
             !set_lds((const void *)k_tp_lookup<true, true, 8>, lookup_lds) ||
             !set_lds((const void *)k_tp_score<uint32_t, 32>, score_lds) ||
-            !set_lds((const void *)k_tp_score<uint16_t, 32>, score_lds) ||
-            !set_lds((const void *)k_apply<uint8_t, false>, ((size_t)k + (size_t)(kAdmitThreads / 64) * k + 2 * (size_t)k) * 4))
+            !set_lds((const void *)k_tp_score<uint16_t, 32>, score_lds))
             return GREM_ERR_HIP;
     } else {
         if (!set_lds((const void *)k_tp_lookup<true, false, 4>, lookup_lds) ||
@@ -779,43 +778,32 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                     else score(k_tp_score<uint32_t, 16>, E32);
                 }
             });
-            // (k <= 16: one workgroup more than the hubs need: it adds up the chunk's mover counts)
+            // (one workgroup more than the hubs need: it adds up the chunk's mover counts)
             L.run(GREM_KERNEL_HUBS, [&] {
                 if (wide)
                     hipLaunchKernelGGL(k_hub_finalize<32>, dim3((unsigned)((max_chunk_hubs + 7) / 8) + 1), dim3(256), 0,
                                        stream, pl, (const uint8_t *)st.Lc, st.room, Ehub_rows, t.Ehub, t.Hhub,
                                        (uint8_t *)st.prop, st.cnt, (int)c, lo, (int)k, pass, store_e, (int)admit_blocks,
-                                       st.tot, 0);
+                                       st.tot, 1);
                 else
                     hipLaunchKernelGGL(k_hub_finalize<16>, dim3((unsigned)((max_chunk_hubs + 15) / 16) + 1), dim3(256), 0,
                                        stream, pl, (const uint8_t *)st.Lc, st.room, Ehub_rows, t.Ehub, t.Hhub,
                                        (uint8_t *)st.prop, st.cnt, (int)c, lo, (int)k, pass, store_e, (int)admit_blocks,
                                        st.tot, 1);
             });
-            if (!wide) {
-                // admission: the score kernel has counted the movers per tile and taken the sizes' snapshot, and
-                // the tiles are few enough that every workgroup adds up the earlier tiles' counts itself
-                L.run(GREM_KERNEL_APPLY, [&] {
-                    hipLaunchKernelGGL(k_apply16, dim3((admit_blocks + kApply16Tiles - 1) / kApply16Tiles), dim3(kAdmitTile),
-                                       0, stream, (uint8_t *)st.Lc, (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room,
-                                       st.tot, (unsigned long long *)st.S, st.ocnt, pass);
-                });
-            } else {
-                // admission as on the plain route: per-tile mover counts, their prefix over the tiles, ranks
-                L.run(GREM_KERNEL_COUNT, [&] {
-                    hipLaunchKernelGGL((k_count<uint8_t>), dim3(admit_blocks), dim3(kAdmitThreads), (size_t)k * 4, stream,
-                                       st.Lc, st.prop, lo, hi, (int)k, st.cnt);
-                });
-                L.run(GREM_KERNEL_SCAN, [&] {
-                    hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), 0, stream, st.cnt, (int)admit_blocks, (int)k,
-                                       st.S, cap, st.room);
-                });
-                L.run(GREM_KERNEL_APPLY, [&] {
-                    hipLaunchKernelGGL((k_apply<uint8_t, false>), dim3(admit_blocks), dim3(kAdmitThreads),
-                                       ((size_t)k + (size_t)(kAdmitThreads / 64) * k + 2 * (size_t)k) * 4, stream, st.Lc,
-                                       st.prop, lo, hi, (int)k, st.cnt, st.room, (unsigned long long *)st.S, st.ocnt, pass);
-                });
-            }
+            // admission: the score kernel has counted the movers per tile and taken the sizes' snapshot, and
+            // the tiles are few enough that every workgroup adds up the earlier tiles' counts itself
+            L.run(GREM_KERNEL_APPLY, [&] {
+                const dim3 grid((admit_blocks + kApply16Tiles - 1) / kApply16Tiles);
+                if (wide)
+                    hipLaunchKernelGGL(k_apply_small<32>, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc,
+                                       (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room, st.tot,
+                                       (unsigned long long *)st.S, st.ocnt, pass);
+                else
+                    hipLaunchKernelGGL(k_apply_small<16>, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc,
+                                       (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room, st.tot,
+                                       (unsigned long long *)st.S, st.ocnt, pass);
+            });
             if (pass == 0) launch_spill<uint8_t>(L, st, lo, hi, k, admit_blocks);
             // the chunk's new labels, looked up for every row that will read them: rows of later chunks in
             // this pass, rows of this and earlier chunks in the next pass (if there is one)

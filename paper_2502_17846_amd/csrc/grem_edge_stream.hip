@@ -140,12 +140,17 @@ __global__ __launch_bounds__(kCountBlock) void k_es_count(const int32_t* __restr
     }
 }
 
-// assign (Alg. 2) on sizes from which the node itself has been taken out; arg_min ties -> 0
+// The two-partition choice of Alg. 2, on sizes from which the node itself has been taken out: the
+// side that holds strictly more of the node's neighbours wins when it still has room; with no such
+// side (equal estimates, or the richer side full) the smaller partition takes the node, 0 on a tie.
 __device__ __forceinline__ int es_assign(double nbrs0, double nbrs1, long long s0, long long s1, long long P)
 {
-    if (nbrs0 < nbrs1 && s1 < P) return 1;
-    if (nbrs1 < nbrs0 && s0 < P) return 0;
-    return s1 < s0 ? 1 : 0;
+    const int lean = (nbrs1 > nbrs0) - (nbrs0 > nbrs1);   // +1: towards 1, -1: towards 0, 0: neither
+    if (lean != 0) {
+        const int p = lean > 0;
+        if ((p ? s1 : s0) < P) return p;
+    }
+    return s1 < s0;
 }
 
 // value of x in lane i, i uniform over the wave

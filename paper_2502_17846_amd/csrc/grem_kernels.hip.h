@@ -685,28 +685,31 @@ __global__ __launch_bounds__(kAdmitThreads) void k_apply(
 }
 
 // ------------------------------------------------------------------------------------------------
-// apply for k <= 16: the same admission, one vertex of each of kApply16Tiles neighbouring tiles per
-// thread, a workgroup of kAdmitTile threads per such group of tiles.  cnt[tile][t] = movers to t in that tile,
-// tot[t] >= movers to t in the whole chunk, room[t] = P - S[t] as of the chunk's start.  A partition
-// with no room admits nobody, one with room for all its movers admits everybody; only for the
-// others (room for some) are ranks needed: the workgroup adds up their columns of the earlier tiles'
-// counts and takes one ballot per such partition and tile.
+// apply for k <= KP (16 or 32): the same admission, one vertex of each of kApply16Tiles neighbouring
+// tiles per thread, a workgroup of kAdmitTile threads per such group of tiles.  cnt[tile][t] = movers
+// to t in that tile, tot[t] >= movers to t in the whole chunk, room[t] = P - S[t] as of the chunk's
+// start.  A partition with no room admits nobody, one with room for all its movers admits everybody;
+// only for the others (room for some) are ranks needed: the workgroup adds up their columns of the
+// earlier tiles' counts and takes one ballot per such partition and tile.
 // ------------------------------------------------------------------------------------------------
-constexpr int kApply16Tiles = 4;     // neighbouring tiles per workgroup of k_apply16
+constexpr int kApply16Tiles = 4;     // neighbouring tiles per workgroup of k_apply_small
 
-__global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc, const uint8_t *__restrict__ prop,
-                                                        int64_t chunk_lo, int64_t chunk_hi, int k,
-                                                        const uint32_t *__restrict__ cnt,
-                                                        const long long *__restrict__ room,
-                                                        const uint32_t *__restrict__ tot,
-                                                        unsigned long long *__restrict__ S,
-                                                        uint32_t *__restrict__ ocnt, int pass) {
+template <int KP>
+__global__ __launch_bounds__(kAdmitTile) void k_apply_small(uint8_t *__restrict__ Lc, const uint8_t *__restrict__ prop,
+                                                            int64_t chunk_lo, int64_t chunk_hi, int k,
+                                                            const uint32_t *__restrict__ cnt,
+                                                            const long long *__restrict__ room,
+                                                            const uint32_t *__restrict__ tot,
+                                                            unsigned long long *__restrict__ S,
+                                                            uint32_t *__restrict__ ocnt, int pass) {
+    static_assert(KP == 16 || KP == 32, "partitions per workgroup table");
     constexpr int nwaves = kAdmitTile / 64;
     constexpr int TPW = kApply16Tiles;
-    __shared__ uint32_t tbl[16];                    // movers in the tiles before the workgroup's
-    __shared__ uint32_t wcnt[TPW][nwaves][16];      // movers per tile and wave, then their exclusive prefix
-    __shared__ int32_t dS[16];
-    __shared__ long long s_room[16];
+    constexpr int SEGS = kAdmitTile / KP;           // threads per column when the earlier tiles are added up
+    __shared__ uint32_t tbl[KP];                    // movers in the tiles before the workgroup's
+    __shared__ uint32_t wcnt[TPW][nwaves][KP];      // movers per tile and wave, then their exclusive prefix
+    __shared__ int32_t dS[KP];
+    __shared__ long long s_room[KP];
     __shared__ uint32_t s_ranked;                   // bit t: partition t has room for some of its movers only
     __shared__ uint32_t s_unassigned[TPW];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -730,7 +733,7 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
             some = rm > 0 && (long long)tot[tid] > rm;
         }
         const unsigned long long m = __ballot(some);
-        if (tid < 16) { tbl[tid] = 0; dS[tid] = 0; s_room[tid] = rm; }
+        if (tid < KP) { tbl[tid] = 0; dS[tid] = 0; s_room[tid] = rm; }
         if (tid < TPW) s_unassigned[tid] = 0;
         if (tid == 0) s_ranked = (uint32_t)m;
     }
@@ -741,10 +744,10 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
 #pragma unroll
     for (int h = 0; h < TPW; ++h) { mover[h] = inside[h] && t[h] != old[h]; wrank[h] = 0; }
     if (ranked) {
-        const int col = tid & 15, seg = tid >> 4;
-        if ((ranked >> col) & 1u) {   // earlier tiles: thread (seg, col) adds up rows seg, seg + 64, ...
+        const int col = tid & (KP - 1), seg = tid / KP;
+        if ((ranked >> col) & 1u) {   // earlier tiles: thread (seg, col) adds up rows seg, seg + SEGS, ...
             uint32_t sum = 0;
-            for (int r = seg; r < tile0; r += kAdmitTile / 16) sum += cnt[(size_t)r * k + col];
+            for (int r = seg; r < tile0; r += SEGS) sum += cnt[(size_t)r * k + col];
             if (sum) atomicAdd(&tbl[col], sum);
         }
         // movers of the workgroup's own tiles (a tile past the chunk's end has none)
@@ -761,10 +764,10 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply16(uint8_t *__restrict__ Lc
                 if (mover[h] && t[h] == j) wrank[h] = (uint32_t)__popcll(m & lanes_below(lane));
                 if ((uint32_t)lane == j) mine = (uint32_t)__popcll(m);
             }
-            if (lane < 16) wcnt[h][wave][lane] = mine;
+            if (lane < KP) wcnt[h][wave][lane] = mine;
         }
         __syncthreads();
-        if (tid < 16) {
+        if (tid < KP) {
             uint32_t before = 0;                    // movers in the workgroup's earlier tiles
 #pragma unroll
             for (int h = 0; h < TPW; ++h) {

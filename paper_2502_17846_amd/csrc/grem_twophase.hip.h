@@ -1,4 +1,4 @@
-// Two-phase score path (k <= 16): the same counts as k_score_lds (Alg. 2 cnt_nbrs, Alg. 1 blend,
+// Two-phase score path (k <= 32): the same counts as k_score_lds (Alg. 2 cnt_nbrs, Alg. 1 blend,
 // Alg. 2 assign), organised so that every neighbour-label look-up is served from LDS and every
 // byte that crosses HBM is part of a long sequential stream.
 //
@@ -21,7 +21,7 @@
 // A tuple lives in three streams, each with as few bytes as its reader needs:
 //   T  : its column in the block, 3 bytes; sub-segments ordered (jb, c, r): all tuples that refer
 //        to one column block are contiguous                            -- read by k_tp_lookup
-//   Lx : the label of that column, 4 bits; sub-segments ordered (c, r, jb): all tuples of one row
+//   Lx : the label of that column, 4 bits (8 when k > 16); sub-segments ordered (c, r, jb): all tuples of one row
 //        slice are contiguous                    -- written by k_tp_lookup, read by k_tp_score
 //   R  : its row in the slice << 5, 16 bits (bit 0 = padding), ordered like Lx; written once by the
 //        re-layout, read by k_tp_score (row << 5 is the byte offset of the row's 16-bit counters)
@@ -1466,8 +1466,8 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP =
 // KP lanes per hub, lane j takes partition j (k <= KP).
 // Estimates of the hubs: row v of E (n rows) when E is given, else row (ch_hub0[c] + i) of Ehub, the
 // table of the hubs alone.
-// The last workgroup (k <= 16 only: with_tot): tot[t] = an upper bound of the chunk's movers to
-// partition t, for k_apply16.
+// The last workgroup (with_tot): tot[t] = an upper bound of the chunk's movers to partition t, for
+// k_apply_small.
 // ------------------------------------------------------------------------------------------------
 template <int KP>
 __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_t *__restrict__ Lc,
@@ -1481,14 +1481,15 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
     if (with_tot && blockIdx.x == gridDim.x - 1) {
         // the tiles' counts as far as they are complete, plus one for every hub
         __shared__ uint32_t part[256];
-        const int col = threadIdx.x & 15, seg = threadIdx.x >> 4;
+        constexpr int SEGS = 256 / KP;                           // threads per column
+        const int col = threadIdx.x & (KP - 1), seg = threadIdx.x / KP;
         uint32_t sum = 0;
         if (col < k) {
-            for (int r0 = seg; r0 < ntiles; r0 += 16 * 16) {    // 16 loads side by side
+            for (int r0 = seg; r0 < ntiles; r0 += SEGS * 16) {   // 16 loads side by side
                 uint32_t x[16];
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
-                    const int r = r0 + 16 * u;
+                    const int r = r0 + SEGS * u;
                     x[u] = r < ntiles ? cnt[(size_t)r * k + col] : 0u;
                 }
 #pragma unroll
@@ -1497,9 +1498,9 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
         }
         part[threadIdx.x] = sum;
         __syncthreads();
-        if (threadIdx.x < 16 && threadIdx.x < (unsigned)k) {
+        if (threadIdx.x < KP && threadIdx.x < (unsigned)k) {
             uint32_t total = nh;
-            for (int q = 0; q < 16; ++q) total += part[q * 16 + threadIdx.x];
+            for (int q = 0; q < SEGS; ++q) total += part[q * KP + threadIdx.x];
             tot[threadIdx.x] = total;
         }
         return;
