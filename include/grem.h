@@ -117,7 +117,9 @@ typedef struct grem_options {
                                  shorter), else 4..18.  Small values only make sense on small graphs */
     int32_t hub_degree;       /* two-phase route: rows of at least this many entries are "hubs", whose
                                  entries are spread evenly over the chunk's workgroups; 0 = default
-                                 (2048), else 1..65535 */
+                                 (8192), else 1..65535.  The other rows' estimates are kept in 16 bits
+                                 while (hub_degree - 1) * 2^refine_passes < 65536 (the default: up to 3
+                                 refinement passes), else in 32 */
     int32_t long_row_degree;  /* plain route: a tile of rows is scored by one workgroup; rows of at least
                                  this many entries are taken out of their tile and spread over a grid of
                                  their own; 0 = default (16384) */

@@ -40,7 +40,7 @@ constexpr int64_t kSweepMinN = 1 << 22;    // AUTO: label table must exceed L2 f
 constexpr int64_t kSweepMinChunk = 1 << 14;   // AUTO: per-chunk launches must have work to do
 constexpr int kDefaultColBits = 17;        // 2^17 labels, two per byte: 64 KB of LDS, two workgroups per CU
 constexpr int kDefaultColBits32 = 16;      // k > 16: 2^16 labels, a byte each
-constexpr int kDefaultHubDegree = 2048;
+constexpr int kDefaultHubDegree = 8192;
 constexpr int64_t kMaxSegments = 1ll << 22;   // chunks * column blocks
 constexpr int kMaxParts = kPlanParts;      // parts of a slice (hub share) in the re-layout
 
@@ -342,7 +342,7 @@ void plan_stage3(Carver &c, const PlanDims &d, TpTables &tb, uint32_t *&T, uint1
     c.take(tb.ustart, d.G * (size_t)d.npr);
     c.take(tb.ustart_h, d.G * (size_t)d.nps);
     uint8_t *t8 = nullptr;
-    c.take(t8, d.slots * 3 + 16);            // column in block, 3 bytes per tuple
+    c.take(t8, d.slots * 3 + 16);            // 24 bytes per group of eight tuples: their place in Lx, their columns
     T = reinterpret_cast<uint32_t *>(t8);
     c.take(R, d.slots + 8);                  // row field, 2 bytes per tuple
 }
@@ -639,6 +639,7 @@ void launch_outputs(Launcher &L, CallState<LabelT> &st, int64_t n, int32_t k, in
 struct TpState {
     uint32_t *Lx = nullptr, *Hhub = nullptr, *E32 = nullptr, *Ehub = nullptr;
     uint16_t *Rdyn = nullptr, *E16 = nullptr;
+    uint8_t *Lc4 = nullptr;            // k <= 16: the labels two per byte, kept by the admission from the second pass on
 };
 
 void state_two_phase(Carver &c, TpState &t, int64_t n, int32_t k, size_t slots, size_t max_chunk_hubs, size_t total_hubs,
@@ -651,6 +652,7 @@ void state_two_phase(Carver &c, TpState &t, int64_t n, int32_t k, size_t slots, 
     c.take(t.E16, use16 ? (size_t)n * (size_t)k : 0);
     c.take(t.E32, (!use16 && !external_E) ? (size_t)n * (size_t)k : 0);
     c.take(t.Ehub, (use16 && !external_E) ? (total_hubs + 1) * (size_t)k : 0);
+    c.take(t.Lc4, k <= 16 ? (size_t)n / 2 + 16 : 0);
 }
 
 // Alg. 1's loop on a plan.  `prepared`: the common state with the prepass run and the seed validated by
@@ -720,7 +722,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
     // `mark`: seeded runs, first pass: the row fields the score kernels read are those of Rdyn, where
     // bit 0 also marks the tuples whose neighbour is unassigned (set by the initial look-up from global
     // memory, cleared by the look-up of the neighbour's chunk)
-    auto lookup = [&](int c0, int count, int cmin, bool from_lds, bool mark) {
+    auto lookup = [&](int c0, int count, int cmin, bool from_lds, bool mark, const uint8_t *labels4 = nullptr) {
         if (cmin >= geo.nch) return;
         const int64_t per_block = P.nnz / geo.nblk + 1;
         int spb = P.lookup_target / geo.nbc;
@@ -730,7 +732,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
         const dim3 grid((unsigned)(geo.nbc * spb), (unsigned)count);
         auto go = [&](auto kernel, size_t lds) {
             hipLaunchKernelGGL(kernel, grid, dim3(kTpThreads), lds, stream, P.T, t.Lx, P.R, t.Rdyn, tb,
-                               (const uint8_t *)st.Lc, n, c0, cmin, spb);
+                               (const uint8_t *)st.Lc, labels4, n, c0, cmin, spb);
         };
         L.run(GREM_KERNEL_LOOKUP, [&] {
             if (wide) {
@@ -764,6 +766,9 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             // pass does not store them otherwise
             const int store_e = (pass < R || external_E) ? 1 : 0;
             const uint16_t *rows_now = (seed && pass == 0) ? t.Rdyn : P.R;
+            // from the second pass on every vertex has a label before its chunk's admission, which then
+            // also leaves the chunk's labels two per byte for the look-ups (chunk starts must be even)
+            uint8_t *packed_now = (pass >= 1 && t.Lc4 && (cl & 1) == 0) ? t.Lc4 : nullptr;
             auto score = [&](auto kernel, auto *Eptr) {
                 hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kTpThreads), score_lds, stream, rows_now, t.Lx, tb, pl,
                                    (const uint8_t *)st.Lc, st.S, Eptr, t.Hhub, (uint8_t *)st.prop, st.cnt, st.room, (int)c,
@@ -798,16 +803,16 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                 if (wide)
                     hipLaunchKernelGGL(k_apply_small<32>, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc,
                                        (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room, st.tot,
-                                       (unsigned long long *)st.S, st.ocnt, pass);
+                                       (unsigned long long *)st.S, st.ocnt, pass, (uint8_t *)nullptr);
                 else
                     hipLaunchKernelGGL(k_apply_small<16>, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc,
                                        (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room, st.tot,
-                                       (unsigned long long *)st.S, st.ocnt, pass);
+                                       (unsigned long long *)st.S, st.ocnt, pass, packed_now);
             });
             if (pass == 0) launch_spill<uint8_t>(L, st, lo, hi, k, admit_blocks);
             // the chunk's new labels, looked up for every row that will read them: rows of later chunks in
             // this pass, rows of this and earlier chunks in the next pass (if there is one)
-            lookup((int)c, 1, pass == R ? (int)c + 1 : 0, true, seed != nullptr && pass == 0);
+            lookup((int)c, 1, pass == R ? (int)c + 1 : 0, true, seed != nullptr && pass == 0, packed_now);
         }
         L.mark();
     }

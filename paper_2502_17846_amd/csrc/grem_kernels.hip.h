@@ -701,7 +701,8 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply_small(uint8_t *__restrict_
                                                             const long long *__restrict__ room,
                                                             const uint32_t *__restrict__ tot,
                                                             unsigned long long *__restrict__ S,
-                                                            uint32_t *__restrict__ ocnt, int pass) {
+                                                            uint32_t *__restrict__ ocnt, int pass,
+                                                            uint8_t *__restrict__ Lc4) {
     static_assert(KP == 16 || KP == 32, "partitions per workgroup table");
     constexpr int nwaves = kAdmitTile / 64;
     constexpr int TPW = kApply16Tiles;
@@ -796,6 +797,13 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply_small(uint8_t *__restrict_
             if (old[h] != 0xFFu) atomicAdd(&dS[old[h]], -1);
         } else if (pass == 0 && inside[h] && old[h] == 0xFFu) {
             atomicAdd(&s_unassigned[h], 1u);    // rejected new vertex (a new vertex is always a mover)
+        }
+        if (Lc4) {
+            // the tile's labels as they now stand, two per byte (chunk_lo is even: the lanes 2i, 2i + 1
+            // hold the vertices 2j, 2j + 1); only meaningful once every vertex has a label
+            const uint32_t now = admitted ? t[h] : old[h];
+            const uint32_t next = (uint32_t)__shfl_xor((int)now, 1);
+            if (!(tid & 1) && inside[h]) Lc4[v[h] >> 1] = (uint8_t)((now & 15u) | (next << 4));
         }
     }
     __syncthreads();

@@ -19,8 +19,9 @@
 //   * sub-segment (c, r, jb) holds the tuples of row r of chunk c whose column lies in block jb,
 //     padded to a multiple of 8 tuples.
 // A tuple lives in three streams, each with as few bytes as its reader needs:
-//   T  : its column in the block, 3 bytes; sub-segments ordered (jb, c, r): all tuples that refer
-//        to one column block are contiguous                            -- read by k_tp_lookup
+//   T  : its column in the block, 20 bits, and per group of eight tuples the place of their labels in
+//        Lx (24 bytes per group); sub-segments ordered (jb, c, r): all tuples that refer to one
+//        column block are contiguous                                   -- read by k_tp_lookup
 //   Lx : the label of that column, 4 bits (8 when k > 16); sub-segments ordered (c, r, jb): all tuples of one row
 //        slice are contiguous                    -- written by k_tp_lookup, read by k_tp_score
 //   R  : its row in the slice << 5, 16 bits (bit 0 = padding), ordered like Lx; written once by the
@@ -712,7 +713,7 @@ __global__ __launch_bounds__(1024) void k_tp_scan(u64 *__restrict__ a0, int64_t 
 // shares) at a time.  In T the sub-segments of consecutive rows are adjacent, so the tuples of a
 // batch form one piece per block of the group; the pieces are put together in LDS, pad tuples
 // included (row field 2048: the score kernel ignores them; they fill every sub-segment up to a
-// multiple of kSubPad), and written out contiguously: the columns (3 bytes each) to T piece by
+// multiple of kSubPad), and written out contiguously: the columns (24 bytes per group of eight) to T piece by
 // piece, the row fields (16 bits each) to R sub-segment by sub-segment (in R the sub-segments of one
 // row for consecutive blocks are adjacent).  A batch that does not fit `cap` slots is cut down to one
 // row; a row that does not fit is written tuple by tuple.
@@ -721,11 +722,25 @@ __global__ __launch_bounds__(1024) void k_tp_scan(u64 *__restrict__ a0, int64_t 
 // ------------------------------------------------------------------------------------------------
 constexpr int kPlaceThreads = 512;
 
-// Every group of eight tuples of T carries, four bits per tuple above the column, the index of the
-// 32-bit word of Lx (eight labels) its labels go to: the tuple in slot p of R / Lx holds bits
-// 4 (p % 8) .. 4 (p % 8) + 3 of p / 8.
-__device__ __forceinline__ uint32_t tp_dest_nibble(u64 at) {
-    return (uint32_t)((at >> 3) >> (4u * ((uint32_t)at & 7u))) & 15u;
+// T holds the tuples in groups of eight, 24 bytes each: a 32-bit word with the index of the 32-bit word
+// of Lx (eight labels of 4 bits; the pair of words when labels take 8 bits) the group's labels go to,
+// then the eight columns, 20 bits each, as one little-endian number of 160 bits.
+__device__ __forceinline__ void tp_pack_columns(const uint32_t (&c)[8], uint32_t (&w)[5]) {
+    w[0] = c[0] | (c[1] << 20);
+    w[1] = (c[1] >> 12) | (c[2] << 8) | (c[3] << 28);
+    w[2] = (c[3] >> 4) | (c[4] << 16);
+    w[3] = (c[4] >> 16) | (c[5] << 4) | (c[6] << 24);
+    w[4] = (c[6] >> 8) | (c[7] << 12);
+}
+__device__ __forceinline__ void tp_unpack_columns(const uint32_t (&w)[5], uint32_t (&c)[8]) {
+    c[0] = w[0] & 0xFFFFFu;
+    c[1] = ((w[0] >> 20) | (w[1] << 12)) & 0xFFFFFu;
+    c[2] = (w[1] >> 8) & 0xFFFFFu;
+    c[3] = ((w[1] >> 28) | (w[2] << 4)) & 0xFFFFFu;
+    c[4] = ((w[2] >> 16) | (w[3] << 16)) & 0xFFFFFu;
+    c[5] = (w[3] >> 4) & 0xFFFFFu;
+    c[6] = ((w[3] >> 24) | (w[4] << 8)) & 0xFFFFFu;
+    c[7] = w[4] >> 12;
 }
 
 __device__ __host__ inline size_t tp_place_fixed_bytes(int nbg, int batch, int maxruns) {
@@ -763,14 +778,19 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
     const uint32_t gmask = (1u << tb.gb) - 1u, cmask = (1u << tb.cb) - 1u;
     const uint32_t pad = 2048u << tb.cb;
     for (int j = tid; j < nbg; j += kPlaceThreads) tbase[j] = tb.tstart[(size_t)(jb0 + j) * tb.nch + c];
-    uint8_t *T8 = reinterpret_cast<uint8_t *>(T);
-    // slot w of sub-segment z = (t, j), written on its own (the slow way): 3 bytes of T, 2 of R
+    // slot w of sub-segment z = (t, j), written on its own (the slow way): its column into the group's
+    // 160 bits, which the caller has cleared (the group's first word set), 2 bytes of R
     auto put_entry = [&](uint32_t j, uint32_t z, uint32_t w, uint32_t tuple) {
         const uint32_t row = tuple >> tb.cb;
         const u64 at = sbase[z / (uint32_t)nbg] + ddv[z] + (w - sub0[z]);      // the tuple's slot in R / Lx
-        const uint32_t col = (tuple & cmask) | (tp_dest_nibble(at) << tb.cb);
-        uint8_t *t3 = T8 + (tbase[j] + w) * 3ull;
-        t3[0] = (uint8_t)col; t3[1] = (uint8_t)(col >> 8); t3[2] = (uint8_t)(col >> 16);
+        const uint32_t col = tuple & cmask;
+        if (col) {
+            const u64 slot = tbase[j] + w;
+            uint32_t *grp = T + (slot >> 3) * 6ull + 1;
+            const uint32_t bit = 20u * ((uint32_t)slot & 7u);
+            atomicOr(grp + (bit >> 5), col << (bit & 31u));
+            if ((bit & 31u) > 12u) atomicOr(grp + (bit >> 5) + 1, col >> (32u - (bit & 31u)));
+        }
         R[at] = (uint16_t)(row >= (uint32_t)kSliceRows ? 1u : row << 5);
     };
     for (int part = 0; part < 2; ++part) {                      // 0: regular slices, 1: hub shares
@@ -836,8 +856,22 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
                 ddv[z] = tb.dd[((size_t)(jb0 + j) * tb.nch + c) * tb.nr + r0 + t];
             }
             for (int t = tid; t < nb; t += kPlaceThreads) sbase[t] = tb.sstart[(size_t)c * tb.nr + r0 + t];
-            if (staged)
+            if (staged) {
                 for (uint32_t z = tid; z < need; z += kPlaceThreads) stage[z] = pad;
+            } else {
+                // the slow way: every group of the sub-segments gets its first word, its columns start at zero
+                __syncthreads();                                // sub0 / sublen / ddv / sbase are complete
+                for (int z = 0; z < nb * nbg; ++z) {
+                    const int j = z % nbg;
+                    const u64 first = (tbase[j] + sub0[z]) >> 3, dest = (sbase[z / nbg] + ddv[z]) >> 3;
+                    for (uint32_t q = tid; q < (sublen[z] >> 3); q += kPlaceThreads) {
+                        uint32_t *grp = T + (first + q) * 6ull;
+                        grp[0] = (uint32_t)(dest + q);
+                        grp[1] = 0; grp[2] = 0; grp[3] = 0; grp[4] = 0; grp[5] = 0;
+                    }
+                }
+                __threadfence();
+            }
             __syncthreads();
             // a wavefront takes whole runs, kRU at a time, the first kXU * 64 tuples of each loaded side
             // by side before any is placed
@@ -881,25 +915,26 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
             }
             __syncthreads();
             if (staged) {
-                // T: a piece per wavefront, four tuples (12 bytes) per lane; starts and lengths are
-                // multiples of 8 tuples
+                // T: a piece per wavefront, a group of eight tuples (24 bytes) per lane; starts and lengths
+                // are multiples of 8 tuples
                 for (int j = wave; j < nbg; j += kNW) {
-                    const uint32_t a = joff[j], len4 = (joff[j + 1] - a) >> 2;
-                    uint32_t *outT = T + ((tbase[j] + s0[j]) >> 2) * 3ull;
-                    for (uint32_t z = lane; z < len4; z += 64) {
-                        // the row of the batch whose sub-segment holds these four tuples, and their slots in R / Lx
-                        const uint32_t x = a + 4 * z;
+                    const uint32_t a = joff[j], len8 = (joff[j + 1] - a) >> 3;
+                    uint32_t *outT = T + ((tbase[j] + s0[j]) >> 3) * 6ull;
+                    for (uint32_t z = lane; z < len8; z += 64) {
+                        // the row of the batch whose sub-segment holds the group, and its slot in R / Lx
+                        const uint32_t x = a + 8 * z;
                         int t = 0;
                         while (t + 1 < nb && x >= sub0[(t + 1) * nbg + j]) ++t;
                         const u64 at = sbase[t] + ddv[t * nbg + j] + (x - sub0[t * nbg + j]);
-                        uint32_t col[4];
+                        uint32_t col[8], w[5];
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) col[q] = (stage[x + q] & cmask) | (tp_dest_nibble(at + q) << tb.cb);
-                        u32x3a t3;
-                        t3.x = col[0] | (col[1] << 24);
-                        t3.y = (col[1] >> 8) | (col[2] << 16);
-                        t3.z = (col[2] >> 16) | (col[3] << 8);
-                        __builtin_nontemporal_store(t3, reinterpret_cast<u32x3a *>(outT + 3 * z));
+                        for (int q = 0; q < 8; ++q) col[q] = stage[x + q] & cmask;
+                        tp_pack_columns(col, w);
+                        u32x3a lo3, hi3;
+                        lo3.x = (uint32_t)(at >> 3); lo3.y = w[0]; lo3.z = w[1];
+                        hi3.x = w[2]; hi3.y = w[3]; hi3.z = w[4];
+                        __builtin_nontemporal_store(lo3, reinterpret_cast<u32x3a *>(outT + 6 * z));
+                        __builtin_nontemporal_store(hi3, reinterpret_cast<u32x3a *>(outT + 6 * z + 3));
                     }
                 }
                 // R: a sub-segment per quarter wavefront, four tuples (8 bytes) per lane
@@ -935,8 +970,8 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
 // restricted to row chunks >= cmin, get their labels.  Workgroup blockIdx.x handles share
 // (blockIdx.x % spb) of block (blockIdx.x / spb) of the chunk: an equal part of the block's tuples
 // in T, which are one contiguous piece.
-//   T  (read)   : per tuple 3 bytes: the column in its block, and above it 4 of the 32 bits of the
-//                 index of the word of Lx the labels of the tuple's group of eight go to
+//   T  (read)   : per group of eight tuples 24 bytes: the index of the word of Lx their labels go to,
+//                 then their columns in the block, 20 bits each
 //   Lx (written): the label of every tuple, LB = 4 bits each (8 when k > 16), sub-segments ordered (c', r, jb): a group's
 //                 word lies in the stream of its row slice, so the writes of one sub-segment are a
 //                 contiguous piece of some 40 bytes; the pieces of the chunk's column blocks are
@@ -945,7 +980,8 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
 //   R           : the row field of every tuple << 5 (bit 0: padding), 16 bits each, ordered like Lx; written
 //                 once by the re-layout
 //   FROM_LDS = true : the block's labels are copied to LDS, two per byte (every vertex of the
-//                     block is assigned: the chunk has just been relabelled)
+//                     block is assigned: the chunk has just been relabelled), from Lc, or from Lc4
+//                     (the same labels already two per byte) when that is given
 //   FROM_LDS = false: labels are read from global memory and may be unassigned; used once, for the
 //                     initial labels of a seeded run
 //   WRITE_R         : seeded runs only.  Their first pass reads the row fields from a copy Rdyn in
@@ -960,7 +996,8 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
                                                           uint32_t *__restrict__ Lx,
                                                           const uint16_t *__restrict__ R,
                                                           uint16_t *__restrict__ Rdyn, TpTables tb,
-                                                          const uint8_t *__restrict__ Lc, int64_t n, int c0,
+                                                          const uint8_t *__restrict__ Lc,
+                                                          const uint8_t *__restrict__ Lc4, int64_t n, int c0,
                                                           int cmin, int spb) {
     extern __shared__ uint32_t tab[];      // FROM_LDS: 2^cb labels, LB bits each
     const int tid = threadIdx.x;
@@ -977,7 +1014,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
     const u64 g0 = groups * (u64)s / (u64)spb, g1 = groups * (u64)(s + 1) / (u64)spb;
     if (g0 >= g1) return;
     const uint32_t ng = (uint32_t)(g1 - g0);
-    const uint32_t *src = T + ((lo >> 2) + 2 * g0) * 3ull;  // 6 words per group
+    const uint32_t *src = T + ((lo >> 3) + g0) * 6ull;      // 6 words per group
 
     constexpr int U = kLookupUnroll;
     u32x3a t[U][2];
@@ -993,7 +1030,14 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
             }
         }
     };
-    load_groups((uint32_t)tid);             // on their way while the label table is built
+    // The first tuples are requested while the label table is built -- after the table's own loads,
+    // whose data is needed first (a wavefront's loads complete in the order they were issued).
+    bool requested = false;
+    auto first_groups = [&] {
+        if (!requested) load_groups((uint32_t)tid);
+        requested = true;
+    };
+    if (!FROM_LDS) first_groups();
 
     if (FROM_LDS && LB == 8) {
         // the block's labels as they are, a byte each
@@ -1001,13 +1045,18 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
         const uint8_t *lsrc = Lc + block_lo;
         uint8_t *tb8 = reinterpret_cast<uint8_t *>(tab);
         if ((((uintptr_t)lsrc) & 15u) == 0) {
+            // (every workgroup of the block starts its copy at a place of its own: see below)
             const int64_t pieces = bv >> 4;
-            for (int64_t i = tid; i < pieces; i += kTpThreads)
-                reinterpret_cast<u32x4 *>(tab)[i] = *reinterpret_cast<const u32x4 *>(lsrc + i * 16);
+            const int64_t start = (pieces * (int64_t)s / (int64_t)spb) & ~(int64_t)7;
+            for (int64_t i = tid; i < pieces; i += kTpThreads) {
+                const int64_t at = i + start < pieces ? i + start : i + start - pieces;
+                reinterpret_cast<u32x4 *>(tab)[at] = *reinterpret_cast<const u32x4 *>(lsrc + at * 16);
+            }
             for (int64_t o = (pieces << 4) + tid; o < bv; o += kTpThreads) tb8[o] = lsrc[o];
         } else {
             for (int64_t o = tid; o < bv; o += kTpThreads) tb8[o] = lsrc[o];
         }
+        first_groups();
         __syncthreads();
     }
     if (FROM_LDS && LB == 4) {
@@ -1018,24 +1067,54 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
         auto pack4 = [](uint32_t a) {       // four labels, one per byte -> 16 bits
             return (a & 15u) | ((a >> 4) & 0xF0u) | ((a >> 8) & 0xF00u) | ((a >> 12) & 0xF000u);
         };
-        if (aligned && bv == (1ll << tb.cb) && (words % (2 * kTpThreads)) == 0) {
+        const uint8_t *packed = Lc4 ? Lc4 + (block_lo >> 1) : nullptr;
+        if (packed && bv == (1ll << tb.cb) && (words % (4 * kTpThreads)) == 0 && (((uintptr_t)packed) & 15u) == 0) {
+            // the labels are at hand two per byte (Lc4: kept by the admission once every vertex has a
+            // label): a plain copy, 32 labels per load; every workgroup of the block starts at a place
+            // of its own (see below)
+            const uint32_t pieces = (uint32_t)words / 4u;       // a power of two
+            const uint32_t start = (uint32_t)(((u64)pieces * (u64)s) / (u64)spb) & ~7u;
+            constexpr int kFill = 4;
+            for (uint32_t i0 = 0; i0 < pieces; i0 += kFill * kTpThreads) {
+                u32x4 v[kFill];
+#pragma unroll
+                for (int i = 0; i < kFill; ++i) {
+                    const uint32_t at = (i0 + (uint32_t)i * kTpThreads + tid + start) & (pieces - 1u);
+                    if (i0 + (uint32_t)i * kTpThreads + tid < pieces) v[i] = reinterpret_cast<const u32x4 *>(packed)[at];
+                }
+                first_groups();
+#pragma unroll
+                for (int i = 0; i < kFill; ++i) {
+                    const uint32_t at = (i0 + (uint32_t)i * kTpThreads + tid + start) & (pieces - 1u);
+                    if (i0 + (uint32_t)i * kTpThreads + tid < pieces) reinterpret_cast<u32x4 *>(tab)[at] = v[i];
+                }
+            }
+        } else if (aligned && bv == (1ll << tb.cb) && (words % (2 * kTpThreads)) == 0) {
             // a whole block at a 16-byte boundary (the usual case): 16 labels per load, all loads of a
             // thread side by side
+            // The workgroups of a block all copy the same labels at the same time: each starts at a place
+            // of its own and wraps around, so that they do not all queue at the same few L2 channels.
             constexpr int kFill = 8;
             const int per = words / (2 * kTpThreads);          // 16-label pieces per thread
+            const uint32_t pieces = (uint32_t)per * kTpThreads;   // a power of two
+            const uint32_t start = (uint32_t)(((u64)pieces * (u64)s) / (u64)spb) & ~7u;
             for (int i0 = 0; i0 < per; i0 += kFill) {
                 u32x4 v[kFill];
 #pragma unroll
                 for (int i = 0; i < kFill; ++i)
-                    if (i0 + i < per)
-                        v[i] = *reinterpret_cast<const u32x4 *>(lsrc + ((size_t)(i0 + i) * kTpThreads + tid) * 16);
+                    if (i0 + i < per) {
+                        const uint32_t at = ((uint32_t)(i0 + i) * kTpThreads + tid + start) & (pieces - 1u);
+                        v[i] = *reinterpret_cast<const u32x4 *>(lsrc + (size_t)at * 16);
+                    }
+                first_groups();
 #pragma unroll
                 for (int i = 0; i < kFill; ++i)
                     if (i0 + i < per) {
+                        const uint32_t at = ((uint32_t)(i0 + i) * kTpThreads + tid + start) & (pieces - 1u);
                         u32x2 o;
                         o.x = pack4(v[i].x) | (pack4(v[i].y) << 16);
                         o.y = pack4(v[i].z) | (pack4(v[i].w) << 16);
-                        *reinterpret_cast<u32x2 *>(tab + 2 * ((size_t)(i0 + i) * kTpThreads + tid)) = o;
+                        *reinterpret_cast<u32x2 *>(tab + 2 * (size_t)at) = o;
                     }
             }
         } else {
@@ -1048,35 +1127,28 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
                 tab[w] = packed;
             }
         }
+        first_groups();
         __syncthreads();
     }
     const uint8_t *tbytes = reinterpret_cast<const uint8_t *>(tab);
-    const uint32_t cmask = (1u << tb.cb) - 1u;
 
     for (uint32_t base = tid; base < ng; base += kTpThreads * U) {
         if (base != (uint32_t)tid) load_groups(base);       // (the first turn is on its way)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (base + u * kTpThreads >= ng) continue;
-            uint32_t raw[8];
-            raw[0] = t[u][0].x & 0xFFFFFFu;
-            raw[1] = ((t[u][0].x >> 24) | (t[u][0].y << 8)) & 0xFFFFFFu;
-            raw[2] = ((t[u][0].y >> 16) | (t[u][0].z << 16)) & 0xFFFFFFu;
-            raw[3] = t[u][0].z >> 8;
-            raw[4] = t[u][1].x & 0xFFFFFFu;
-            raw[5] = ((t[u][1].x >> 24) | (t[u][1].y << 8)) & 0xFFFFFFu;
-            raw[6] = ((t[u][1].y >> 16) | (t[u][1].z << 16)) & 0xFFFFFFu;
-            raw[7] = t[u][1].z >> 8;
-            uint32_t word = 0, word2 = 0, unassigned = 0, dest = 0;
+            const uint32_t w5[5] = {t[u][0].y, t[u][0].z, t[u][1].x, t[u][1].y, t[u][1].z};
+            uint32_t col[8];
+            tp_unpack_columns(w5, col);
+            const uint32_t dest = t[u][0].x;
+            uint32_t word = 0, word2 = 0, unassigned = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const uint32_t col = raw[e] & cmask;
-                dest |= ((raw[e] >> tb.cb) & 15u) << (4 * e);
                 uint32_t lab;
                 if (FROM_LDS) {
-                    lab = LB == 4 ? ((uint32_t)tbytes[col >> 1] >> (4 * (col & 1u))) & 15u : (uint32_t)tbytes[col];
+                    lab = LB == 4 ? ((uint32_t)tbytes[col[e] >> 1] >> (4 * (col[e] & 1u))) & 15u : (uint32_t)tbytes[col[e]];
                 } else {
-                    const int64_t v = block_lo + (int64_t)col;
+                    const int64_t v = block_lo + (int64_t)col[e];
                     const uint32_t l = v < chunk_hi ? (uint32_t)Lc[v] : 0xFFu;
                     if (l == 0xFFu) unassigned |= 1u << e;
                     lab = LB == 4 ? (l & 15u) : (l == 0xFFu ? 0u : l);
