@@ -28,11 +28,11 @@ HBM_PEAK_GBPS = 8000.0
 # at that time, and `traffic` is reported as null when the sources have changed since.
 PMC = {
     "workload": "chunglu-111M",
-    "sources_sha256": "924f71701811d9bbb16e675b2d82608d8605cd5075c4f20a3b0ea40be9623407",
+    "sources_sha256": "77f981cafaf7e3494067709c7629d3f9a0251d5b64919bdb40b5b6d3421a3ada",
     "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,590 KiB
-    "write_factor": 1.0,        # 2 GiB written -> WRITE_SIZE 2,097,150 KiB
-    "fetch_kib": {"k_tp_score": 1.83367e+07, "k_tp_lookup": 1.35275e+07},
-    "write_kib": {"k_tp_score": 7.36998e+06, "k_tp_lookup": 4.55374e+06},
+    "write_factor": 1.0,        # 2 GiB written -> WRITE_SIZE 2,097,152 KiB
+    "fetch_kib": {"k_tp_score": 1.42294e+07, "k_tp_lookup": 1.36585e+07},
+    "write_kib": {"k_tp_score": 7.31457e+06, "k_tp_lookup": 5.5874e+06},
     "launches": {"k_tp_score": 318, "k_tp_lookup": 317},
 }
 
