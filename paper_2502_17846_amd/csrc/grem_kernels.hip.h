@@ -726,6 +726,26 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply_small(uint8_t *__restrict_
         old[h] = 0;
         if (inside[h]) { t[h] = prop[v[h] - chunk_lo]; old[h] = (uint32_t)Lc[v[h]]; }
     }
+    // the earlier tiles' counts, column `col` by SEGS threads: asked for now, together with the labels, when
+    // the tiles are few (needed only if the partition turns out to be one with room for some: then the
+    // loads' latency is already behind us), else after that is known
+    const int col = tid & (KP - 1), seg = tid / KP;
+    const bool early = tile0 <= 16 * SEGS;
+    uint32_t before = 0;
+    if (early && col < k) {
+        uint32_t x[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int r = seg + SEGS * u;
+            x[u] = r < tile0 ? cnt[(size_t)r * k + col] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) before += x[u];
+    }
+    uint32_t own[TPW];
+#pragma unroll
+    for (int h = 0; h < TPW; ++h)
+        own[h] = (tid < k && chunk_lo + (int64_t)(tile0 + h) * kAdmitTile < chunk_hi) ? cnt[(size_t)(tile0 + h) * k + tid] : 0u;
     if (tid < 64) {
         long long rm = 0;
         bool some = false;
@@ -745,17 +765,12 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply_small(uint8_t *__restrict_
 #pragma unroll
     for (int h = 0; h < TPW; ++h) { mover[h] = inside[h] && t[h] != old[h]; wrank[h] = 0; }
     if (ranked) {
-        const int col = tid & (KP - 1), seg = tid / KP;
         if ((ranked >> col) & 1u) {   // earlier tiles: thread (seg, col) adds up rows seg, seg + SEGS, ...
-            uint32_t sum = 0;
-            for (int r = seg; r < tile0; r += SEGS) sum += cnt[(size_t)r * k + col];
+            uint32_t sum = before;
+            if (!early)
+                for (int r = seg; r < tile0; r += SEGS) sum += cnt[(size_t)r * k + col];
             if (sum) atomicAdd(&tbl[col], sum);
         }
-        // movers of the workgroup's own tiles (a tile past the chunk's end has none)
-        uint32_t own[TPW];
-#pragma unroll
-        for (int h = 0; h < TPW; ++h)
-            own[h] = (tid < k && chunk_lo + (int64_t)(tile0 + h) * kAdmitTile < chunk_hi) ? cnt[(size_t)(tile0 + h) * k + tid] : 0u;
 #pragma unroll
         for (int h = 0; h < TPW; ++h) {
             uint32_t mine = 0;
