@@ -281,6 +281,8 @@ struct PlanData {
     unsigned long long maxdeg = 0, hub_entries = 0, total_hubs = 0, max_chunk_hubs = 0;
     bool have_degrees = false;              // maxdeg and nnz have been read back
     std::vector<uint32_t> nvs;              // hub shares per chunk (host copy of pl.ch_nvs)
+    std::vector<uint32_t> chunk_hubs;       // hubs per chunk (host copy of pl.ch_nh)
+    std::vector<u64> chunk_hub0;            // hubs of the chunks before it (host copy of pl.ch_hub0)
     int share_hubs = 0;
     int max_k = 0;                          // largest k whose score workgroups fit the LDS
     int lookup_target = 512;
@@ -413,8 +415,13 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
                            P.pmisc);
     });
     P.nvs.assign((size_t)geo.nch, 0u);
+    P.chunk_hubs.assign((size_t)geo.nch, 0u);
+    P.chunk_hub0.assign((size_t)geo.nch + 1, 0ull);
     if (P.total_hubs != 0) {
-        if (hipMemcpyAsync(P.nvs.data(), pl.ch_nvs, (size_t)geo.nch * 4, hipMemcpyDeviceToHost, stream) != hipSuccess)
+        if (hipMemcpyAsync(P.nvs.data(), pl.ch_nvs, (size_t)geo.nch * 4, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+            hipMemcpyAsync(P.chunk_hubs.data(), pl.ch_nh, (size_t)geo.nch * 4, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+            hipMemcpyAsync(P.chunk_hub0.data(), pl.ch_hub0, ((size_t)geo.nch + 1) * 8, hipMemcpyDeviceToHost, stream) !=
+                hipSuccess)
             return GREM_ERR_HIP;
         if (!L.read_back(h, P.pmisc, sizeof(h))) return L.err;
     } else if (L.err) {
@@ -567,7 +574,7 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
 // ======================================================================================================
 template <typename LabelT> struct CallState {
     LabelT *Lc = nullptr, *prop = nullptr;
-    long long *S = nullptr, *room = nullptr, *fillSorted = nullptr, *fillC = nullptr;
+    long long *S = nullptr, *S2 = nullptr, *room = nullptr, *fillSorted = nullptr, *fillC = nullptr;
     uint32_t *cnt = nullptr, *tot = nullptr, *ocnt = nullptr;
     int32_t *fillRank = nullptr;
     unsigned long long *misc = nullptr;
@@ -579,6 +586,7 @@ void state_common(Carver &c, CallState<LabelT> &st, int64_t n, int64_t cl, int32
     c.take(st.Lc, (size_t)n);
     c.take(st.prop, (size_t)cl);
     c.take(st.S, (size_t)k);
+    c.take(st.S2, (size_t)k);                // the sizes' other copy (the one-launch spill reads one, writes the other)
     c.take(st.cnt, ntiles * (size_t)k);
     c.take(st.tot, 2 * (size_t)k);
     c.take(st.room, (size_t)k);
@@ -642,17 +650,26 @@ struct TpState {
     uint8_t *Lc4 = nullptr;            // k <= 16: the labels two per byte, kept by the admission from the second pass on
 };
 
+// twice: two tables of the chunk's hub counts and of the hubs' estimates (the admission that also does the
+// hubs' part reads one and writes the other)
 void state_two_phase(Carver &c, TpState &t, int64_t n, int32_t k, size_t slots, size_t max_chunk_hubs, size_t total_hubs,
-                     bool seeded, bool use16, bool external_E) {
+                     bool seeded, bool use16, bool external_E, bool twice) {
     uint8_t *lx = nullptr;
     c.take(lx, (k <= 16 ? slots / 2 : slots) + 16);               // label, 4 bits per tuple (8 when k > 16)
     t.Lx = reinterpret_cast<uint32_t *>(lx);
-    c.take(t.Hhub, (max_chunk_hubs + 1) * (size_t)k);
+    c.take(t.Hhub, (twice ? 2 : 1) * (max_chunk_hubs + 1) * (size_t)k);
     c.take(t.Rdyn, seeded ? slots + 8 : 0);                       // seeded runs: R with the unassigned neighbours marked
     c.take(t.E16, use16 ? (size_t)n * (size_t)k : 0);
     c.take(t.E32, (!use16 && !external_E) ? (size_t)n * (size_t)k : 0);
-    c.take(t.Ehub, (use16 && !external_E) ? (total_hubs + 1) * (size_t)k : 0);
+    c.take(t.Ehub, (use16 && !external_E) ? (twice ? 2 : 1) * (total_hubs + 1) * (size_t)k : 0);
     c.take(t.Lc4, k <= 16 ? (size_t)n / 2 + 16 : 0);
+}
+
+// The admission kernel does the hubs' blend and proposal itself when every chunk has few hubs and few
+// tiles and the hubs' estimates live in a table of their own (16-bit estimates, no caller's array).
+bool admission_takes_hubs(const PlanData &P, bool use16, bool external_E) {
+    const int64_t tiles = ((int64_t)P.geo.chunk + kAdmitTile - 1) / kAdmitTile;
+    return use16 && !external_E && P.max_chunk_hubs <= (unsigned long long)kAdmitHubsMax && tiles <= kAdmitTilesMax;
 }
 
 // Alg. 1's loop on a plan.  `prepared`: the common state with the prepass run and the seed validated by
@@ -675,6 +692,8 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
     // estimates of the regular rows stay below hub_degree * 2^R: 16 bits when that fits
     const bool use16 = (((unsigned long long)(hub_degree - 1)) << R) <= 65535ull;
 
+    const bool hubs_in_admission = admission_takes_hubs(P, use16, external_E);
+
     CallState<uint8_t> st;
     if (prepared) {
         st = *prepared;
@@ -684,7 +703,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
     TpState t;
     if (!carve(mem, [&](Carver &c) {
             state_two_phase(c, t, n, k, P.slots, (size_t)P.max_chunk_hubs, (size_t)P.total_hubs, seed != nullptr, use16,
-                            external_E);
+                            external_E, hubs_in_admission);
         }))
         return GREM_ERR_NOMEM;
     if (!prepared) {
@@ -715,7 +734,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             !set_lds((const void *)k_tp_score<uint16_t, 16>, score_lds))
             return GREM_ERR_HIP;
     }
-    L.memset(t.Hhub, 0, ((size_t)P.max_chunk_hubs + 1) * (size_t)k * 4);
+    L.memset(t.Hhub, 0, (hubs_in_admission ? 2 : 1) * ((size_t)P.max_chunk_hubs + 1) * (size_t)k * 4);
 
     // look-ups of the labels of chunks [c0, c0 + count): shares per column block sized so that one
     // launch fills the chip without cutting the blocks' streams into crumbs
@@ -754,6 +773,11 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
     }
     L.mark();
     const size_t max_chunk_hubs = (size_t)P.max_chunk_hubs;
+    uint32_t prev_hubs = 0;                 // hubs of the chunk before (whose counts the admission clears)
+    // first pass, chunks of at most kAdmitTile tiles: the spill is one launch that reads the sizes from one
+    // array and writes them to the other; the two take turns from chunk to chunk
+    const bool spill_small = (cl + kAdmitTile - 1) / kAdmitTile <= kAdmitTile;
+    long long *Snow = st.S;
     for (int pass = 0; pass <= R && !L.err; ++pass) {
         for (int64_t c = 0; c < geo.nch && !L.err; ++c) {
             const int64_t lo = c * cl;
@@ -769,9 +793,11 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             // from the second pass on every vertex has a label before its chunk's admission, which then
             // also leaves the chunk's labels two per byte for the look-ups (chunk starts must be even)
             uint8_t *packed_now = (pass >= 1 && t.Lc4 && (cl & 1) == 0) ? t.Lc4 : nullptr;
+            const int64_t step = (int64_t)pass * geo.nch + c;
+            uint32_t *Hnow = t.Hhub + (hubs_in_admission ? (size_t)(step & 1) * ((size_t)max_chunk_hubs + 1) * (size_t)k : 0);
             auto score = [&](auto kernel, auto *Eptr) {
                 hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kTpThreads), score_lds, stream, rows_now, t.Lx, tb, pl,
-                                   (const uint8_t *)st.Lc, st.S, Eptr, t.Hhub, (uint8_t *)st.prop, st.cnt, st.room, (int)c,
+                                   (const uint8_t *)st.Lc, Snow, Eptr, Hnow, (uint8_t *)st.prop, st.cnt, st.room, (int)c,
                                    lo, hi, (int)k, jlim, P.share_hubs, P.nvs[(size_t)c], pass, cap, store_e);
             };
             L.run(GREM_KERNEL_SCORE, [&] {
@@ -783,6 +809,29 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                     else score(k_tp_score<uint32_t, 16>, E32);
                 }
             });
+            if (hubs_in_admission) {
+                // one launch: every workgroup works out the chunk's hubs for itself; two tables of hub counts
+                // take turns from chunk to chunk, two tables of hub estimates from pass to pass
+                const size_t hrow = (size_t)max_chunk_hubs + 1, erow = (size_t)P.total_hubs + 1;
+                const uint32_t nh = P.chunk_hubs[(size_t)c];
+                const size_t hub0 = (size_t)P.chunk_hub0[(size_t)c];
+                uint32_t *Hother = t.Hhub + (size_t)((step + 1) & 1) * hrow * (size_t)k;
+                const uint32_t *Eold = t.Ehub + ((size_t)((pass + 1) & 1) * erow + hub0) * (size_t)k;
+                uint32_t *Enew = t.Ehub + ((size_t)(pass & 1) * erow + hub0) * (size_t)k;
+                L.run(GREM_KERNEL_APPLY, [&] {
+                    const dim3 grid((admit_blocks + kApply16Tiles - 1) / kApply16Tiles);
+                    auto go = [&](auto kernel) {
+                        hipLaunchKernelGGL(kernel, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc, (const uint8_t *)st.prop,
+                                           lo, hi, (int)k, (const uint32_t *)st.cnt, (int)admit_blocks,
+                                           (const long long *)st.room, (unsigned long long *)Snow, st.ocnt, pass, packed_now,
+                                           (const int32_t *)(pl.hub_row + hub0), nh, (const uint32_t *)Hnow, Hother,
+                                           prev_hubs, Eold, Enew, store_e);
+                    };
+                    if (wide) go(k_admit_hubs<32>);
+                    else go(k_admit_hubs<16>);
+                });
+                prev_hubs = nh;
+            } else {
             // (one workgroup more than the hubs need: it adds up the chunk's mover counts)
             L.run(GREM_KERNEL_HUBS, [&] {
                 if (wide)
@@ -803,19 +852,39 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                 if (wide)
                     hipLaunchKernelGGL(k_apply_small<32>, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc,
                                        (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room, st.tot,
-                                       (unsigned long long *)st.S, st.ocnt, pass, (uint8_t *)nullptr);
+                                       (unsigned long long *)Snow, st.ocnt, pass, (uint8_t *)nullptr);
                 else
                     hipLaunchKernelGGL(k_apply_small<16>, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc,
                                        (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room, st.tot,
-                                       (unsigned long long *)st.S, st.ocnt, pass, packed_now);
+                                       (unsigned long long *)Snow, st.ocnt, pass, packed_now);
             });
-            if (pass == 0) launch_spill<uint8_t>(L, st, lo, hi, k, admit_blocks);
+            }
+            if (pass == 0) {
+                if (spill_small) {
+                    long long *Snext = Snow == st.S ? st.S2 : st.S;
+                    L.run(GREM_KERNEL_SPILL_FILL, [&] {
+                        const dim3 grid((admit_blocks + kApply16Tiles - 1) / kApply16Tiles);
+                        if (wide)
+                            hipLaunchKernelGGL(k_spill_small<32>, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc, lo, hi,
+                                               (int)k, (const uint32_t *)st.ocnt, (int)admit_blocks, (const long long *)Snow,
+                                               Snext);
+                        else
+                            hipLaunchKernelGGL(k_spill_small<16>, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc, lo, hi,
+                                               (int)k, (const uint32_t *)st.ocnt, (int)admit_blocks, (const long long *)Snow,
+                                               Snext);
+                    });
+                    Snow = Snext;
+                } else {
+                    launch_spill<uint8_t>(L, st, lo, hi, k, admit_blocks);
+                }
+            }
             // the chunk's new labels, looked up for every row that will read them: rows of later chunks in
             // this pass, rows of this and earlier chunks in the next pass (if there is one)
             lookup((int)c, 1, pass == R ? (int)c + 1 : 0, true, seed != nullptr && pass == 0, packed_now);
         }
         L.mark();
     }
+    st.S = Snow;
     launch_outputs<uint8_t>(L, st, n, k, labels_out, sizes_out);
     if (use16 && external_E) {
         int64_t blocks = (n + 255) / 256;
@@ -1114,8 +1183,8 @@ size_t grem_workspace_bytes_two_phase(int64_t n, int64_t nnz, int32_t k, int64_t
     // seeded run whose estimates need 32 bits
     const size_t temp = align_up((size_t)nnz * 4 + 16) + align_up((size_t)geo.nch * (size_t)d.nr * (size_t)geo.nblk * 4);
     const size_t chunk_hubs = d.hubs < (size_t)cl ? d.hubs : (size_t)cl;
-    const size_t s16 = carve_size([&](Carver &c) { state_two_phase(c, t, n, k, d.slots, chunk_hubs, d.hubs, true, true, false); });
-    const size_t s32 = carve_size([&](Carver &c) { state_two_phase(c, t, n, k, d.slots, chunk_hubs, d.hubs, true, false, false); });
+    const size_t s16 = carve_size([&](Carver &c) { state_two_phase(c, t, n, k, d.slots, chunk_hubs, d.hubs, true, true, false, true); });
+    const size_t s32 = carve_size([&](Carver &c) { state_two_phase(c, t, n, k, d.slots, chunk_hubs, d.hubs, true, false, false, true); });
     size_t tail = temp;
     if (s16 > tail) tail = s16;
     if (s32 > tail) tail = s32;
@@ -1242,7 +1311,7 @@ size_t grem_plan_call_bytes(const grem_plan *plan, int32_t k, int32_t refine_pas
     return carve_size([&](Carver &c) { state_common(c, st, P.n, (int64_t)P.geo.chunk, k); }) +
            carve_size([&](Carver &c) {
                state_two_phase(c, t, P.n, k, P.slots, (size_t)P.max_chunk_hubs, (size_t)P.total_hubs, seeded != 0, use16,
-                               with_estimates_out != 0);
+                               with_estimates_out != 0, admission_takes_hubs(P, use16, with_estimates_out != 0));
            });
 }
 

@@ -977,6 +977,116 @@ __global__ __launch_bounds__(kAdmitThreads) void k_spill_fill(
 }
 
 // ------------------------------------------------------------------------------------------------
+// The spill of a chunk of few tiles into k <= KP partitions in one launch (k_spill_scan and
+// k_spill_fill in one): every workgroup (kApply16Tiles tiles, a thread per vertex and tile) adds up the
+// tiles' counts of rejected new vertices and builds the level tables for itself.  With nothing to
+// place it ends there.  The sizes are read from Sin (as the admission left them) and written, by
+// workgroup 0 and in closed form, to another array Sout: partition j, at position pos among the a
+// smallest partitions by id, takes len / a + (pos < len % a) of the len placements made while a
+// partitions are level.  (The callers alternate between two arrays from chunk to chunk; Sout is
+// written in full in every launch.)
+// ------------------------------------------------------------------------------------------------
+template <int KP>
+__global__ __launch_bounds__(kAdmitTile) void k_spill_small(uint8_t *__restrict__ Lc, int64_t chunk_lo, int64_t chunk_hi,
+                                                            int k, const uint32_t *__restrict__ ocnt, int ntiles,
+                                                            const long long *__restrict__ Sin,
+                                                            long long *__restrict__ Sout) {
+    constexpr int nwaves = kAdmitTile / 64;
+    constexpr int TPW = kApply16Tiles;
+    __shared__ uint32_t wtot[nwaves];
+    __shared__ uint32_t s_base[TPW + 1];            // rejected vertices before each of the workgroup's tiles
+    __shared__ uint32_t s_total;
+    __shared__ long long Sl[KP], sorted[KP], C[KP + 1];
+    __shared__ int rnk[KP];
+    __shared__ uint32_t wun[TPW][nwaves];
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int tile0 = TPW * (int)blockIdx.x;
+    // exclusive prefix of the tiles' counts (at most kAdmitTile tiles: one per thread)
+    const uint32_t mine = tid < ntiles ? ocnt[tid] : 0u;
+    long long sj = 0;
+    if (tid < k) sj = Sin[tid];
+    uint32_t inc = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_up(inc, off);
+        if (lane >= off) inc += o;
+    }
+    if (lane == 63) wtot[wave] = inc;
+    if (tid < k) Sl[tid] = sj;
+    __syncthreads();
+    uint32_t before = inc - mine;
+    for (int w = 0; w < wave; ++w) before += wtot[w];
+    if (tid >= tile0 && tid < tile0 + TPW) s_base[tid - tile0] = before;
+    if (tid == kAdmitTile - 1) s_total = before + mine;
+    __syncthreads();
+    const uint32_t total = s_total;
+    if (total == 0) {
+        if (blockIdx.x == 0 && tid < k) Sout[tid] = sj;
+        return;
+    }
+    // level tables: order the partitions by (size, id); C[a] = placements made before a + 1 partitions are level
+    if (tid < k) {
+        int r = 0;
+        for (int i = 0; i < k; ++i) r += (Sl[i] < sj || (Sl[i] == sj && i < tid)) ? 1 : 0;
+        rnk[tid] = r;
+        sorted[r] = sj;
+    }
+    __syncthreads();
+    if (tid <= k) {
+        long long ps = 0;
+        for (int q = 0; q < tid && q < k; ++q) ps += sorted[q];
+        C[tid] = tid < k ? (long long)tid * sorted[tid] - ps : 0x7fffffffffffffffLL;
+    }
+    __syncthreads();
+    // the rejected new vertices of the workgroup's tiles, in ascending id
+    bool un[TPW];
+    int64_t v[TPW];
+#pragma unroll
+    for (int h = 0; h < TPW; ++h) {
+        v[h] = chunk_lo + (int64_t)(tile0 + h) * kAdmitTile + tid;
+        un[h] = v[h] < chunk_hi && Lc[v[h]] == 0xFFu;
+    }
+    uint32_t within[TPW];
+#pragma unroll
+    for (int h = 0; h < TPW; ++h) {
+        const unsigned long long m = __ballot(un[h]);
+        within[h] = (uint32_t)__popcll(m & lanes_below(lane));
+        if (lane == 0) wun[h][wave] = (uint32_t)__popcll(m);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < TPW; ++h) {
+        if (!un[h]) continue;
+        long long i = (long long)s_base[h] + within[h];
+        for (int w = 0; w < wave; ++w) i += wun[h][w];
+        int a = 1;
+        while (a < k && i >= C[a]) ++a;                 // smallest a in [1, k] with i < C[a]
+        int idx = (int)((unsigned long long)(i - C[a - 1]) % (unsigned)a);
+        int j = idx;
+        if (a < k) {            // the idx-th smallest id among the a smallest partitions
+            for (j = 0; j < k - 1; ++j)
+                if (rnk[j] < a) { if (idx == 0) break; idx -= 1; }
+        }
+        Lc[v[h]] = (uint8_t)j;
+    }
+    if (blockIdx.x == 0 && tid < k) {
+        long long add = 0;
+        for (int a = 1; a <= k; ++a) {
+            const long long hi = C[a] < (long long)total ? C[a] : (long long)total;
+            if (C[a - 1] >= (long long)total) break;
+            const long long len = hi - C[a - 1];
+            if (len <= 0) continue;
+            if (rnk[tid] < a) {
+                int pos = 0;
+                for (int q = 0; q < tid; ++q) pos += rnk[q] < a ? 1 : 0;
+                add += len / a + (pos < (int)(len % a) ? 1 : 0);
+            }
+        }
+        Sout[tid] = sj + add;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // expand: compact labels -> int32 output
 // ------------------------------------------------------------------------------------------------
 template <typename LabelT>

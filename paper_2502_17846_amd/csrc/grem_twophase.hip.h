@@ -1617,6 +1617,221 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
 }
 
 // ------------------------------------------------------------------------------------------------
+// Admission of a chunk with the hubs' part folded in, for chunks of few hubs and few tiles: what
+// k_hub_finalize and k_apply_small do in two launches.  Every workgroup works the chunk's hubs out for
+// itself (blend, proposal: nh * KP lanes of work), so nothing has to pass between workgroups:
+//   - the hubs' counts are read from Hnow and left alone (the host alternates between two tables
+//     from chunk to chunk; workgroup 0 clears the rows the chunk before used in the other one);
+//   - their estimates are read from Eold and written to Enew (two tables of the hubs' rows, alternating
+//     from pass to pass) by the one workgroup whose tiles hold the hub;
+//   - a hub's proposal reaches the thread of its vertex through LDS (`over`); its move counts for the
+//     tiles' mover counts exactly as the atomic add of k_hub_finalize did;
+//   - every workgroup adds up all tiles' counts itself: the chunk's movers per partition (exact, where
+//     k_apply_small gets an upper bound) and those of the tiles before its own.
+// cnt[tile][t]: movers to t among the tile's regular rows (from k_tp_score).
+// ------------------------------------------------------------------------------------------------
+constexpr int kAdmitHubsMax = 512;        // hubs of a chunk
+constexpr int kAdmitTilesMax = 1024;      // tiles of a chunk
+
+template <int KP>
+__global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
+    uint8_t *__restrict__ Lc, const uint8_t *__restrict__ prop, int64_t chunk_lo, int64_t chunk_hi, int k,
+    const uint32_t *__restrict__ cnt, int ntiles, const long long *__restrict__ room,
+    unsigned long long *__restrict__ S, uint32_t *__restrict__ ocnt, int pass, uint8_t *__restrict__ Lc4,
+    const int32_t *__restrict__ hub_row, uint32_t nh, const uint32_t *__restrict__ Hnow,
+    uint32_t *__restrict__ Hclear, uint32_t nclear, const uint32_t *__restrict__ Eold,
+    uint32_t *__restrict__ Enew, int store_e) {
+    static_assert(KP == 16 || KP == 32, "partitions per workgroup table");
+    constexpr int nwaves = kAdmitTile / 64;
+    constexpr int TPW = kApply16Tiles;
+    constexpr int SEGS = kAdmitTile / KP;           // threads per column of cnt
+    constexpr int HPR = kAdmitTile / KP;            // hubs per round of the workgroup
+    constexpr int HB = 4;                           // rounds whose loads are issued side by side
+    __shared__ uint32_t tbl[KP];                    // movers in the tiles before the workgroup's
+    __shared__ uint32_t totl[KP];                   // movers in the whole chunk
+    __shared__ uint32_t ownh[TPW][KP];              // hubs among the movers of the workgroup's tiles
+    __shared__ uint32_t wcnt[TPW][nwaves][KP];      // movers per tile and wave, then their exclusive prefix
+    __shared__ int32_t dS[KP];
+    __shared__ long long s_room[KP];
+    __shared__ uint32_t s_ranked;                   // bit t: partition t has room for some of its movers only
+    __shared__ uint32_t s_unassigned[TPW];
+    __shared__ __align__(16) uint8_t over[TPW * kAdmitTile];   // a hub's proposal, for the thread of its vertex (0xFF: none)
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int tile0 = TPW * (int)blockIdx.x;
+    int64_t v[TPW];
+    bool inside[TPW];
+    uint32_t t[TPW], old[TPW];
+#pragma unroll
+    for (int h = 0; h < TPW; ++h) {
+        v[h] = chunk_lo + (int64_t)(tile0 + h) * kAdmitTile + tid;
+        inside[h] = v[h] < chunk_hi;
+        t[h] = 0;
+        old[h] = 0;
+        if (inside[h]) { t[h] = prop[v[h] - chunk_lo]; old[h] = (uint32_t)Lc[v[h]]; }
+    }
+    // all tiles' counts, column `col` by SEGS threads
+    const int col = tid & (KP - 1), seg = tid / KP;
+    uint32_t all = 0, before = 0;
+    if (col < k) {
+        for (int r0 = seg; r0 < ntiles; r0 += SEGS * 8) {
+            uint32_t x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = r0 + SEGS * u;
+                x[u] = r < ntiles ? cnt[(size_t)r * k + col] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                all += x[u];
+                if (r0 + SEGS * u < tile0) before += x[u];
+            }
+        }
+    }
+    uint32_t own[TPW];
+#pragma unroll
+    for (int h = 0; h < TPW; ++h)
+        own[h] = (tid < k && tile0 + h < ntiles) ? cnt[(size_t)(tile0 + h) * k + tid] : 0u;
+    long long rm0 = 0;
+    if (tid < k) rm0 = room[tid];
+    if (tid < KP) {
+        tbl[tid] = 0; totl[tid] = 0; dS[tid] = 0; s_room[tid] = rm0;
+#pragma unroll
+        for (int h = 0; h < TPW; ++h) ownh[h][tid] = 0;
+    }
+    if (tid < TPW) s_unassigned[tid] = 0;
+    reinterpret_cast<uint32_t *>(over)[tid] = 0xFFFFFFFFu;
+    if (blockIdx.x == 0)
+        for (uint32_t q = tid; q < nclear * (uint32_t)k; q += kAdmitTile) Hclear[q] = 0;
+    __syncthreads();
+    if (all) atomicAdd(&totl[col], all);
+    if (before) atomicAdd(&tbl[col], before);
+    // the chunk's hubs: KP lanes each, lane j takes partition j
+    {
+        const int sh = pass > 0 ? pass - 1 : 0;
+        const int j = col;
+        for (uint32_t i0 = (uint32_t)seg; i0 < nh; i0 += HPR * HB) {
+            int64_t hv[HB];
+            uint32_t hold[HB], hh[HB], he[HB];
+#pragma unroll
+            for (int u = 0; u < HB; ++u) {
+                const uint32_t i = i0 + (uint32_t)u * HPR;
+                hv[u] = i < nh ? (int64_t)hub_row[i] : chunk_lo;
+                hh[u] = (i < nh && j < k) ? Hnow[(size_t)i * k + j] : 0u;
+                he[u] = (i < nh && j < k && pass > 0) ? Eold[(size_t)i * k + j] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < HB; ++u) hold[u] = (uint32_t)Lc[hv[u]];
+#pragma unroll
+            for (int u = 0; u < HB; ++u) {
+                const uint32_t i = i0 + (uint32_t)u * HPR;
+                const bool on = i < nh;                      // (uniform over the KP lanes of a hub)
+                unsigned long long key = 0;
+                int bj = 0x7fffffff;
+                const uint32_t e = he[u] + (hh[u] << sh);
+                if (on && j < k) {
+                    const uint32_t rm = (uint32_t)s_room[j] + ((uint32_t)j == hold[u] ? 1u : 0u);
+                    key = rm ? (((unsigned long long)e << 32) | rm) : 0ull;
+                    bj = j;
+                }
+#pragma unroll
+                for (int off = 1; off <= KP / 2; off <<= 1) {      // the KP lanes of a hub are on or off together
+                    const unsigned long long okey = __shfl_xor(key, off);
+                    const int oj = __shfl_xor(bj, off);
+                    if (okey > key || (okey == key && oj < bj)) { key = okey; bj = oj; }
+                }
+                if (!on) continue;
+                const int tile = (int)((hv[u] - chunk_lo) / kAdmitTile);
+                const bool mine = tile >= tile0 && tile < tile0 + TPW;
+                if (mine && store_e && j < k) Enew[(size_t)i * k + j] = e;
+                if (j == 0) {
+                    uint32_t best = (uint32_t)bj;
+                    if (pass == 0 && hold[u] != 0xFFu) best = hold[u];      // a seeded vertex keeps its label
+                    if (best != hold[u]) {
+                        atomicAdd(&totl[best], 1u);
+                        if (tile < tile0) atomicAdd(&tbl[best], 1u);
+                        else if (mine) atomicAdd(&ownh[tile - tile0][best], 1u);
+                    }
+                    if (mine) over[(tile - tile0) * kAdmitTile + (int)((hv[u] - chunk_lo) % kAdmitTile)] = (uint8_t)best;
+                }
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < TPW; ++h) {
+        const uint32_t o = over[h * kAdmitTile + tid];
+        if (o != 0xFFu) t[h] = o;
+        own[h] += tid < KP ? ownh[h][tid] : 0u;
+    }
+    if (tid < 64) {
+        const bool some = tid < k && rm0 > 0 && (long long)totl[tid] > rm0;
+        const unsigned long long m = __ballot(some);
+        if (tid == 0) s_ranked = (uint32_t)m;
+    }
+    __syncthreads();
+    const uint32_t ranked = s_ranked;
+    bool mover[TPW];
+    uint32_t wrank[TPW];
+#pragma unroll
+    for (int h = 0; h < TPW; ++h) { mover[h] = inside[h] && t[h] != old[h]; wrank[h] = 0; }
+    if (ranked) {
+#pragma unroll
+        for (int h = 0; h < TPW; ++h) {
+            uint32_t mine = 0;
+            for (uint32_t left = ranked; left; left &= left - 1) {
+                const uint32_t j = (uint32_t)__ffs(left) - 1u;
+                const unsigned long long m = __ballot(mover[h] && t[h] == j);
+                if (mover[h] && t[h] == j) wrank[h] = (uint32_t)__popcll(m & lanes_below(lane));
+                if ((uint32_t)lane == j) mine = (uint32_t)__popcll(m);
+            }
+            if (lane < KP) wcnt[h][wave][lane] = mine;
+        }
+        __syncthreads();
+        if (tid < KP) {
+            uint32_t run0 = 0;                      // movers in the workgroup's earlier tiles
+#pragma unroll
+            for (int h = 0; h < TPW; ++h) {
+                uint32_t run = run0;
+                for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[h][w][tid]; wcnt[h][w][tid] = run; run += c; }
+                run0 += own[h];
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int h = 0; h < TPW; ++h) {
+        bool admitted = false;
+        if (mover[h]) {
+            const long long rm = s_room[t[h]];
+            if ((ranked >> t[h]) & 1u) {
+                const long long rank = (long long)tbl[t[h]] + wcnt[h][wave][t[h]] + wrank[h];
+                admitted = rank < rm;
+            } else {
+                admitted = rm > 0;          // room for all of the partition's movers, or for none
+            }
+        }
+        if (admitted) {
+            Lc[v[h]] = (uint8_t)t[h];
+            atomicAdd(&dS[t[h]], 1);
+            if (old[h] != 0xFFu) atomicAdd(&dS[old[h]], -1);
+        } else if (pass == 0 && inside[h] && old[h] == 0xFFu) {
+            atomicAdd(&s_unassigned[h], 1u);    // rejected new vertex (a new vertex is always a mover)
+        }
+        if (Lc4) {
+            const uint32_t now = admitted ? t[h] : old[h];
+            const uint32_t next = (uint32_t)__shfl_xor((int)now, 1);
+            if (!(tid & 1) && inside[h]) Lc4[v[h] >> 1] = (uint8_t)((now & 15u) | (next << 4));
+        }
+    }
+    __syncthreads();
+    if (tid < k) {
+        const int32_t d = dS[tid];
+        if (d != 0) atomicAdd(&S[tid], (unsigned long long)(long long)d);
+    }
+    if (pass == 0 && tid < TPW && tile0 + tid < ntiles) ocnt[tile0 + tid] = s_unassigned[tid];
+}
+
+// ------------------------------------------------------------------------------------------------
 // 16-bit estimates of the regular rows -> the caller's 32-bit array (hub rows are already there)
 // ------------------------------------------------------------------------------------------------
 template <typename RowT>
