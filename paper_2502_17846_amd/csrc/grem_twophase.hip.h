@@ -1693,6 +1693,23 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
         own[h] = (tid < k && tile0 + h < ntiles) ? cnt[(size_t)(tile0 + h) * k + tid] : 0u;
     long long rm0 = 0;
     if (tid < k) rm0 = room[tid];
+    // the hubs this thread takes part in, HB rounds at a time: KP lanes per hub, lane j takes partition j;
+    // the first rounds' loads are on their way with everything above
+    const int j = col;
+    int64_t hv[HB];
+    uint32_t hold[HB], hh[HB], he[HB];
+    auto load_hubs = [&](uint32_t i0) {
+#pragma unroll
+        for (int u = 0; u < HB; ++u) {
+            const uint32_t i = i0 + (uint32_t)u * HPR;
+            hv[u] = i < nh ? (int64_t)hub_row[i] : chunk_lo;
+            hh[u] = (i < nh && j < k) ? Hnow[(size_t)i * k + j] : 0u;
+            he[u] = (i < nh && j < k && pass > 0) ? Eold[(size_t)i * k + j] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < HB; ++u) hold[u] = (uint32_t)Lc[hv[u]];
+    };
+    load_hubs((uint32_t)seg);
     if (tid < KP) {
         tbl[tid] = 0; totl[tid] = 0; dS[tid] = 0; s_room[tid] = rm0;
 #pragma unroll
@@ -1705,22 +1722,11 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
     __syncthreads();
     if (all) atomicAdd(&totl[col], all);
     if (before) atomicAdd(&tbl[col], before);
-    // the chunk's hubs: KP lanes each, lane j takes partition j
+    // the chunk's hubs
     {
         const int sh = pass > 0 ? pass - 1 : 0;
-        const int j = col;
         for (uint32_t i0 = (uint32_t)seg; i0 < nh; i0 += HPR * HB) {
-            int64_t hv[HB];
-            uint32_t hold[HB], hh[HB], he[HB];
-#pragma unroll
-            for (int u = 0; u < HB; ++u) {
-                const uint32_t i = i0 + (uint32_t)u * HPR;
-                hv[u] = i < nh ? (int64_t)hub_row[i] : chunk_lo;
-                hh[u] = (i < nh && j < k) ? Hnow[(size_t)i * k + j] : 0u;
-                he[u] = (i < nh && j < k && pass > 0) ? Eold[(size_t)i * k + j] : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < HB; ++u) hold[u] = (uint32_t)Lc[hv[u]];
+            if (i0 != (uint32_t)seg) load_hubs(i0);
 #pragma unroll
             for (int u = 0; u < HB; ++u) {
                 const uint32_t i = i0 + (uint32_t)u * HPR;
