@@ -40,8 +40,8 @@ PMC = {
 # The same for the edge-chunk path's dominant kernel on its 111M-node workload.
 PMC_EDGE = {
     "workload": "edges-chunglu-111M-c1pct",
-    "sources_sha256": "601857ae77aedf2c3912dcb6246c98e2a4beb471d353b1c822d94019424e6501",
-    "fetch_kib": {"k_es_count": 1.928343e+08},
+    "sources_sha256": "fc0898c9602363e23af93f339b153a474a59c5ea5fd2393b69a90557244403ac",
+    "fetch_kib": {"k_es_count": 1.928405e+08},
     "write_kib": {"k_es_count": 9.980970e+07},
     "launches": {"k_es_count": 100},
 }
