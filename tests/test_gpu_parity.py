@@ -47,6 +47,13 @@ def _check(g, k, slack, chunk, R, seed=None, rowptr_dtype=None, mode=B.HIST_AUTO
     assert int(cut.item()) == oracle.edge_cut(g.rowptr, g.colidx, g.n, olab)
     assert (np.bincount(lab_h, minlength=k) == osizes).all()
     assert osizes.max() <= B.grem_capacity(g.n, k, slack) == oracle.capacity(g.n, k, slack)
+    # the same run asking for labels and sizes only: the library then keeps the estimates in its own, narrower
+    # tables and takes other kernels for the hubs and the admission
+    lab2, sizes2, _ = B.grem_partition_state(rp, ci, g.n, k, slack, chunk, R, seed_d, want_estimates=False, options=opts)
+    torch.cuda.synchronize()
+    bad = np.nonzero(lab2.cpu().numpy() != olab)[0]
+    assert bad.size == 0, f"labels-only run: {bad.size} labels differ, first at v={bad[:5]}"
+    assert sizes2.cpu().numpy().tolist() == osizes.tolist()
     return lab_h
 
 
