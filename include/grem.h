@@ -223,9 +223,9 @@ int grem_set_workspace(void *dev_ptr, size_t bytes);
                                     two-phase path: histogram of stored look-ups + blend + argmax */
 #define GREM_KERNEL_COUNT 2
 #define GREM_KERNEL_SCAN 3
-#define GREM_KERNEL_APPLY 4
+#define GREM_KERNEL_APPLY 4      /* admission; two-phase path with few hubs per chunk: with the hubs' blend and proposal */
 #define GREM_KERNEL_SPILL_SCAN 5
-#define GREM_KERNEL_SPILL_FILL 6
+#define GREM_KERNEL_SPILL_FILL 6 /* two-phase path, chunks of at most 1024 tiles: the whole spill in one launch */
 #define GREM_KERNEL_EXPAND 7
 #define GREM_KERNEL_RELAYOUT 8   /* one-time planning and re-layout of the entries (two-phase path) */
 #define GREM_KERNEL_LOOKUP 9     /* two-phase path: label look-ups for the entries that refer to a chunk */

@@ -819,7 +819,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                 const uint32_t *Eold = t.Ehub + ((size_t)((pass + 1) & 1) * erow + hub0) * (size_t)k;
                 uint32_t *Enew = t.Ehub + ((size_t)(pass & 1) * erow + hub0) * (size_t)k;
                 L.run(GREM_KERNEL_APPLY, [&] {
-                    const dim3 grid((admit_blocks + kApply16Tiles - 1) / kApply16Tiles);
+                    const dim3 grid((admit_blocks + kSmallApplyTiles - 1) / kSmallApplyTiles);
                     auto go = [&](auto kernel) {
                         hipLaunchKernelGGL(kernel, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc, (const uint8_t *)st.prop,
                                            lo, hi, (int)k, (const uint32_t *)st.cnt, (int)admit_blocks,
@@ -838,17 +838,17 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                     hipLaunchKernelGGL(k_hub_finalize<32>, dim3((unsigned)((max_chunk_hubs + 7) / 8) + 1), dim3(256), 0,
                                        stream, pl, (const uint8_t *)st.Lc, st.room, Ehub_rows, t.Ehub, t.Hhub,
                                        (uint8_t *)st.prop, st.cnt, (int)c, lo, (int)k, pass, store_e, (int)admit_blocks,
-                                       st.tot, 1);
+                                       st.tot);
                 else
                     hipLaunchKernelGGL(k_hub_finalize<16>, dim3((unsigned)((max_chunk_hubs + 15) / 16) + 1), dim3(256), 0,
                                        stream, pl, (const uint8_t *)st.Lc, st.room, Ehub_rows, t.Ehub, t.Hhub,
                                        (uint8_t *)st.prop, st.cnt, (int)c, lo, (int)k, pass, store_e, (int)admit_blocks,
-                                       st.tot, 1);
+                                       st.tot);
             });
             // admission: the score kernel has counted the movers per tile and taken the sizes' snapshot, and
             // the tiles are few enough that every workgroup adds up the earlier tiles' counts itself
             L.run(GREM_KERNEL_APPLY, [&] {
-                const dim3 grid((admit_blocks + kApply16Tiles - 1) / kApply16Tiles);
+                const dim3 grid((admit_blocks + kSmallApplyTiles - 1) / kSmallApplyTiles);
                 if (wide)
                     hipLaunchKernelGGL(k_apply_small<32>, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc,
                                        (const uint8_t *)st.prop, lo, hi, (int)k, st.cnt, st.room, st.tot,
@@ -863,7 +863,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                 if (spill_small) {
                     long long *Snext = Snow == st.S ? st.S2 : st.S;
                     L.run(GREM_KERNEL_SPILL_FILL, [&] {
-                        const dim3 grid((admit_blocks + kApply16Tiles - 1) / kApply16Tiles);
+                        const dim3 grid((admit_blocks + kSmallApplyTiles - 1) / kSmallApplyTiles);
                         if (wide)
                             hipLaunchKernelGGL(k_spill_small<32>, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc, lo, hi,
                                                (int)k, (const uint32_t *)st.ocnt, (int)admit_blocks, (const long long *)Snow,

@@ -685,14 +685,14 @@ __global__ __launch_bounds__(kAdmitThreads) void k_apply(
 }
 
 // ------------------------------------------------------------------------------------------------
-// apply for k <= KP (16 or 32): the same admission, one vertex of each of kApply16Tiles neighbouring
+// apply for k <= KP (16 or 32): the same admission, one vertex of each of kSmallApplyTiles neighbouring
 // tiles per thread, a workgroup of kAdmitTile threads per such group of tiles.  cnt[tile][t] = movers
 // to t in that tile, tot[t] >= movers to t in the whole chunk, room[t] = P - S[t] as of the chunk's
 // start.  A partition with no room admits nobody, one with room for all its movers admits everybody;
 // only for the others (room for some) are ranks needed: the workgroup adds up their columns of the
 // earlier tiles' counts and takes one ballot per such partition and tile.
 // ------------------------------------------------------------------------------------------------
-constexpr int kApply16Tiles = 4;     // neighbouring tiles per workgroup of k_apply_small
+constexpr int kSmallApplyTiles = 4;     // neighbouring tiles per workgroup of k_apply_small
 
 template <int KP>
 __global__ __launch_bounds__(kAdmitTile) void k_apply_small(uint8_t *__restrict__ Lc, const uint8_t *__restrict__ prop,
@@ -705,7 +705,7 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply_small(uint8_t *__restrict_
                                                             uint8_t *__restrict__ Lc4) {
     static_assert(KP == 16 || KP == 32, "partitions per workgroup table");
     constexpr int nwaves = kAdmitTile / 64;
-    constexpr int TPW = kApply16Tiles;
+    constexpr int TPW = kSmallApplyTiles;
     constexpr int SEGS = kAdmitTile / KP;           // threads per column when the earlier tiles are added up
     __shared__ uint32_t tbl[KP];                    // movers in the tiles before the workgroup's
     __shared__ uint32_t wcnt[TPW][nwaves][KP];      // movers per tile and wave, then their exclusive prefix
@@ -978,7 +978,7 @@ __global__ __launch_bounds__(kAdmitThreads) void k_spill_fill(
 
 // ------------------------------------------------------------------------------------------------
 // The spill of a chunk of few tiles into k <= KP partitions in one launch (k_spill_scan and
-// k_spill_fill in one): every workgroup (kApply16Tiles tiles, a thread per vertex and tile) adds up the
+// k_spill_fill in one): every workgroup (kSmallApplyTiles tiles, a thread per vertex and tile) adds up the
 // tiles' counts of rejected new vertices and builds the level tables for itself.  With nothing to
 // place it ends there.  The sizes are read from Sin (as the admission left them) and written, by
 // workgroup 0 and in closed form, to another array Sout: partition j, at position pos among the a
@@ -992,7 +992,7 @@ __global__ __launch_bounds__(kAdmitTile) void k_spill_small(uint8_t *__restrict_
                                                             const long long *__restrict__ Sin,
                                                             long long *__restrict__ Sout) {
     constexpr int nwaves = kAdmitTile / 64;
-    constexpr int TPW = kApply16Tiles;
+    constexpr int TPW = kSmallApplyTiles;
     __shared__ uint32_t wtot[nwaves];
     __shared__ uint32_t s_base[TPW + 1];            // rejected vertices before each of the workgroup's tiles
     __shared__ uint32_t s_total;

@@ -1538,8 +1538,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP =
 // KP lanes per hub, lane j takes partition j (k <= KP).
 // Estimates of the hubs: row v of E (n rows) when E is given, else row (ch_hub0[c] + i) of Ehub, the
 // table of the hubs alone.
-// The last workgroup (with_tot): tot[t] = an upper bound of the chunk's movers to partition t, for
-// k_apply_small.
+// The last workgroup: tot[t] = an upper bound of the chunk's movers to partition t, for k_apply_small.
 // ------------------------------------------------------------------------------------------------
 template <int KP>
 __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_t *__restrict__ Lc,
@@ -1548,9 +1547,9 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
                                                       uint32_t *__restrict__ Hhub,
                                                       uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
                                                       int c, int64_t chunk_lo, int k, int pass, int store_e,
-                                                      int ntiles, uint32_t *__restrict__ tot, int with_tot) {
+                                                      int ntiles, uint32_t *__restrict__ tot) {
     const uint32_t nh = pl.ch_nh[c];
-    if (with_tot && blockIdx.x == gridDim.x - 1) {
+    if (blockIdx.x == gridDim.x - 1) {
         // the tiles' counts as far as they are complete, plus one for every hub
         __shared__ uint32_t part[256];
         constexpr int SEGS = 256 / KP;                           // threads per column
@@ -1643,7 +1642,7 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
     uint32_t *__restrict__ Enew, int store_e) {
     static_assert(KP == 16 || KP == 32, "partitions per workgroup table");
     constexpr int nwaves = kAdmitTile / 64;
-    constexpr int TPW = kApply16Tiles;
+    constexpr int TPW = kSmallApplyTiles;
     constexpr int SEGS = kAdmitTile / KP;           // threads per column of cnt
     constexpr int HPR = kAdmitTile / KP;            // hubs per round of the workgroup
     constexpr int HB = 4;                           // rounds whose loads are issued side by side
