@@ -648,6 +648,7 @@ struct TpState {
     uint32_t *Lx = nullptr, *Hhub = nullptr, *E32 = nullptr, *Ehub = nullptr;
     uint16_t *Rdyn = nullptr, *E16 = nullptr;
     uint8_t *Lc4 = nullptr;            // k <= 16: the labels two per byte, kept by the admission from the second pass on
+    uint8_t *hub_old = nullptr;        // the labels of the chunk's hubs, by their place in its list (see k_admit_hubs)
 };
 
 // twice: two tables of the chunk's hub counts and of the hubs' estimates (the admission that also does the
@@ -663,6 +664,7 @@ void state_two_phase(Carver &c, TpState &t, int64_t n, int32_t k, size_t slots, 
     c.take(t.E32, (!use16 && !external_E) ? (size_t)n * (size_t)k : 0);
     c.take(t.Ehub, (use16 && !external_E) ? (twice ? 2 : 1) * (total_hubs + 1) * (size_t)k : 0);
     c.take(t.Lc4, k <= 16 ? (size_t)n / 2 + 16 : 0);
+    c.take(t.hub_old, twice ? max_chunk_hubs + 16 : 0);
 }
 
 // The admission kernel does the hubs' blend and proposal itself when every chunk has few hubs and few
@@ -798,7 +800,8 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             auto score = [&](auto kernel, auto *Eptr) {
                 hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kTpThreads), score_lds, stream, rows_now, t.Lx, tb, pl,
                                    (const uint8_t *)st.Lc, Snow, Eptr, Hnow, (uint8_t *)st.prop, st.cnt, st.room, (int)c,
-                                   lo, hi, (int)k, jlim, P.share_hubs, P.nvs[(size_t)c], pass, cap, store_e);
+                                   lo, hi, (int)k, jlim, P.share_hubs, P.nvs[(size_t)c], pass, cap, store_e,
+                                   hubs_in_admission ? t.hub_old : (uint8_t *)nullptr);
             };
             L.run(GREM_KERNEL_SCORE, [&] {
                 if (wide) {
@@ -824,7 +827,8 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                         hipLaunchKernelGGL(kernel, grid, dim3(kAdmitTile), 0, stream, (uint8_t *)st.Lc, (const uint8_t *)st.prop,
                                            lo, hi, (int)k, (const uint32_t *)st.cnt, (int)admit_blocks,
                                            (const long long *)st.room, (unsigned long long *)Snow, st.ocnt, pass, packed_now,
-                                           (const int32_t *)(pl.hub_row + hub0), nh, (const uint32_t *)Hnow, Hother,
+                                           (const int32_t *)(pl.hub_row + hub0), (const uint8_t *)t.hub_old, nh,
+                                           (const uint32_t *)Hnow, Hother,
                                            prev_hubs, Eold, Enew, store_e);
                     };
                     if (wide) go(k_admit_hubs<32>);

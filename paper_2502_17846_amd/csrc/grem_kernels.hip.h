@@ -684,6 +684,28 @@ __global__ __launch_bounds__(kAdmitThreads) void k_apply(
     if (pass == 0 && tid == 0) ocnt[blockIdx.x] = s_unassigned;
 }
 
+// The waves' mover counts wcnt[tile][wave][t] of a workgroup's tiles -> the number of movers to t before
+// that wave: in its tile's earlier waves and in the workgroup's earlier tiles (own[tile][t] movers each).
+// One entry per thread and turn, the 16 waves of a (tile, t) pair in 16 neighbouring lanes.
+template <int KP, int TPW>
+__device__ __forceinline__ void wave_counts_to_prefix(uint32_t (*wcnt)[kAdmitTile / 64][KP], const uint32_t (*own)[KP]) {
+    constexpr int nwaves = kAdmitTile / 64;
+    static_assert(nwaves == 16, "a (tile, partition) pair's waves fill a row of 16 lanes");
+    for (int e = threadIdx.x; e < TPW * nwaves * KP; e += kAdmitTile) {
+        const int w = e & (nwaves - 1), col = (e / nwaves) % KP, h = e / (nwaves * KP);
+        const uint32_t c = wcnt[h][w][col];
+        uint32_t inc = c;
+#pragma unroll
+        for (int off = 1; off < nwaves; off <<= 1) {
+            const uint32_t o = __shfl_up(inc, off, nwaves);
+            if (w >= off) inc += o;
+        }
+        uint32_t base = 0;
+        for (int g = 0; g < h; ++g) base += own[g][col];
+        wcnt[h][w][col] = base + inc - c;
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // apply for k <= KP (16 or 32): the same admission, one vertex of each of kSmallApplyTiles neighbouring
 // tiles per thread, a workgroup of kAdmitTile threads per such group of tiles.  cnt[tile][t] = movers
@@ -709,6 +731,7 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply_small(uint8_t *__restrict_
     constexpr int SEGS = kAdmitTile / KP;           // threads per column when the earlier tiles are added up
     __shared__ uint32_t tbl[KP];                    // movers in the tiles before the workgroup's
     __shared__ uint32_t wcnt[TPW][nwaves][KP];      // movers per tile and wave, then their exclusive prefix
+    __shared__ uint32_t s_own[TPW][KP];             // movers of the workgroup's tiles
     __shared__ int32_t dS[KP];
     __shared__ long long s_room[KP];
     __shared__ uint32_t s_ranked;                   // bit t: partition t has room for some of its movers only
@@ -782,16 +805,11 @@ __global__ __launch_bounds__(kAdmitTile) void k_apply_small(uint8_t *__restrict_
             }
             if (lane < KP) wcnt[h][wave][lane] = mine;
         }
-        __syncthreads();
-        if (tid < KP) {
-            uint32_t before = 0;                    // movers in the workgroup's earlier tiles
+        if (tid < KP)
 #pragma unroll
-            for (int h = 0; h < TPW; ++h) {
-                uint32_t run = before;
-                for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[h][w][tid]; wcnt[h][w][tid] = run; run += c; }
-                before += own[h];
-            }
-        }
+            for (int h = 0; h < TPW; ++h) s_own[h][tid] = own[h];
+        __syncthreads();
+        wave_counts_to_prefix<KP, TPW>(wcnt, s_own);
         __syncthreads();
     }
 #pragma unroll

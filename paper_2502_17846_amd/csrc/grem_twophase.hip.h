@@ -1276,6 +1276,7 @@ __device__ __forceinline__ unsigned long long tp_xor_lane64(unsigned long long v
 // 8-bit labels, 128 KB of counters: one workgroup per CU).  KP / 4 lanes share a vertex in the
 // blend: lane q owns partitions 4q .. 4q+3 when k % 4 == 0 (one 8- or 16-byte piece of E's row), else
 // q, q + KP/4, q + 2 KP/4, q + 3 KP/4.
+// hub_old: see below (may be null).
 // LDS: hist[kSliceRows * KP / 2] (16-bit counters, KP per row; a static array when KP = 16),
 //      meta[kSliceRows / 2] (per row: old label, hub flag << 8), hhist[share_hubs * k], room[k], tcnt[2 * k]
 // ------------------------------------------------------------------------------------------------
@@ -1285,7 +1286,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP =
     const uint8_t *__restrict__ Lc, const long long *__restrict__ S, ET *__restrict__ E,
     uint32_t *__restrict__ Hhub, uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
     long long *__restrict__ room_out, int c, int64_t chunk_lo, int64_t chunk_hi, int k, int jlim,
-    int share_hubs, uint32_t nvs, int pass, long long P, int store_e) {
+    int share_hubs, uint32_t nvs, int pass, long long P, int store_e, uint8_t *__restrict__ hub_old) {
     extern __shared__ uint32_t smem[];
     constexpr int LB = KP == 16 ? 4 : 8;
     constexpr int LPV = KP / 4;                                 // lanes per vertex in the blend
@@ -1355,7 +1356,13 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP =
     }
     __syncthreads();
     // the slice's hubs, from the chunk's list (read by the blend, after the next barrier)
-    for (uint32_t i = tid; i < snh; i += kTpThreads) meta[(int64_t)pl.hub_row[slice_hub0 + i] - v0] |= (uint16_t)0x100u;
+    // (hub_old, when given: the hubs' labels, by their place in the chunk's list, for the admission kernel that
+    // also works the hubs out: it then need not look them up through the list)
+    for (uint32_t i = tid; i < snh; i += kTpThreads) {
+        const int64_t at = (int64_t)pl.hub_row[slice_hub0 + i] - v0;
+        if (hub_old) hub_old[pl.sl_hub_start[gs] + i] = (uint8_t)meta[at];
+        meta[at] |= (uint16_t)0x100u;
+    }
 
     tp_count_stream<true, KP, LB, 4>(R, Lx, sbeg, 0u, slen >> 3, k, hist);
     if (any_hub) tp_count_stream<false, KP, LB, 2>(R, Lx, hbeg, hg0, hg1, k, hhist);
@@ -1619,6 +1626,7 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
 // Admission of a chunk with the hubs' part folded in, for chunks of few hubs and few tiles: what
 // k_hub_finalize and k_apply_small do in two launches.  Every workgroup works the chunk's hubs out for
 // itself (blend, proposal: nh * KP lanes of work), so nothing has to pass between workgroups:
+//   - the hubs' labels come from hub_old (k_tp_score leaves them there, by place in the chunk's list);
 //   - the hubs' counts are read from Hnow and left alone (the host alternates between two tables
 //     from chunk to chunk; workgroup 0 clears the rows the chunk before used in the other one);
 //   - their estimates are read from Eold and written to Enew (two tables of the hubs' rows, alternating
@@ -1637,7 +1645,8 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
     uint8_t *__restrict__ Lc, const uint8_t *__restrict__ prop, int64_t chunk_lo, int64_t chunk_hi, int k,
     const uint32_t *__restrict__ cnt, int ntiles, const long long *__restrict__ room,
     unsigned long long *__restrict__ S, uint32_t *__restrict__ ocnt, int pass, uint8_t *__restrict__ Lc4,
-    const int32_t *__restrict__ hub_row, uint32_t nh, const uint32_t *__restrict__ Hnow,
+    const int32_t *__restrict__ hub_row, const uint8_t *__restrict__ hub_old, uint32_t nh,
+    const uint32_t *__restrict__ Hnow,
     uint32_t *__restrict__ Hclear, uint32_t nclear, const uint32_t *__restrict__ Eold,
     uint32_t *__restrict__ Enew, int store_e) {
     static_assert(KP == 16 || KP == 32, "partitions per workgroup table");
@@ -1652,7 +1661,6 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
     __shared__ uint32_t wcnt[TPW][nwaves][KP];      // movers per tile and wave, then their exclusive prefix
     __shared__ int32_t dS[KP];
     __shared__ long long s_room[KP];
-    __shared__ uint32_t s_ranked;                   // bit t: partition t has room for some of its movers only
     __shared__ uint32_t s_unassigned[TPW];
     __shared__ __align__(16) uint8_t over[TPW * kAdmitTile];   // a hub's proposal, for the thread of its vertex (0xFF: none)
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -1672,15 +1680,15 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
     const int col = tid & (KP - 1), seg = tid / KP;
     uint32_t all = 0, before = 0;
     if (col < k) {
-        for (int r0 = seg; r0 < ntiles; r0 += SEGS * 8) {
-            uint32_t x[8];
+        for (int r0 = seg; r0 < ntiles; r0 += SEGS * 16) {      // (16 loads side by side: one turn when KP = 16)
+            uint32_t x[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 const int r = r0 + SEGS * u;
                 x[u] = r < ntiles ? cnt[(size_t)r * k + col] : 0u;
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 all += x[u];
                 if (r0 + SEGS * u < tile0) before += x[u];
             }
@@ -1702,11 +1710,10 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
         for (int u = 0; u < HB; ++u) {
             const uint32_t i = i0 + (uint32_t)u * HPR;
             hv[u] = i < nh ? (int64_t)hub_row[i] : chunk_lo;
+            hold[u] = i < nh ? (uint32_t)hub_old[i] : 0xFFu;     // (left by k_tp_score: no trip through the list)
             hh[u] = (i < nh && j < k) ? Hnow[(size_t)i * k + j] : 0u;
             he[u] = (i < nh && j < k && pass > 0) ? Eold[(size_t)i * k + j] : 0u;
         }
-#pragma unroll
-        for (int u = 0; u < HB; ++u) hold[u] = (uint32_t)Lc[hv[u]];
     };
     load_hubs((uint32_t)seg);
     if (tid < KP) {
@@ -1768,13 +1775,13 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
         if (o != 0xFFu) t[h] = o;
         own[h] += tid < KP ? ownh[h][tid] : 0u;
     }
-    if (tid < 64) {
-        const bool some = tid < k && rm0 > 0 && (long long)totl[tid] > rm0;
-        const unsigned long long m = __ballot(some);
-        if (tid == 0) s_ranked = (uint32_t)m;
+    // bit t: partition t has room for some of its movers only (every wavefront works it out for itself)
+    uint32_t ranked;
+    {
+        const long long rl = lane < k ? s_room[lane] : 0;
+        const bool some = lane < k && rl > 0 && (long long)totl[lane] > rl;
+        ranked = (uint32_t)__ballot(some);
     }
-    __syncthreads();
-    const uint32_t ranked = s_ranked;
     bool mover[TPW];
     uint32_t wrank[TPW];
 #pragma unroll
@@ -1791,16 +1798,11 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
             }
             if (lane < KP) wcnt[h][wave][lane] = mine;
         }
-        __syncthreads();
-        if (tid < KP) {
-            uint32_t run0 = 0;                      // movers in the workgroup's earlier tiles
+        if (tid < KP)
 #pragma unroll
-            for (int h = 0; h < TPW; ++h) {
-                uint32_t run = run0;
-                for (int w = 0; w < nwaves; ++w) { const uint32_t c = wcnt[h][w][tid]; wcnt[h][w][tid] = run; run += c; }
-                run0 += own[h];
-            }
-        }
+            for (int h = 0; h < TPW; ++h) ownh[h][tid] = own[h];    // (regular rows and hubs together now)
+        __syncthreads();
+        wave_counts_to_prefix<KP, TPW>(wcnt, ownh);
         __syncthreads();
     }
 #pragma unroll
