@@ -28,11 +28,11 @@ HBM_PEAK_GBPS = 8000.0
 # at that time, and `traffic` is reported as null when the sources have changed since.
 PMC = {
     "workload": "chunglu-111M",
-    "sources_sha256": "fe69264a44b77e29f17af0026196613782a5fb125a1f0be7bf860d94034f221d",
+    "sources_sha256": "373293b6765c0cf5ff8789aaff5ad37b202b8e86337f45908029674ccaa89273",
     "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,592 KiB
     "write_factor": 1.0,        # 2 GiB written -> WRITE_SIZE 2,097,152 KiB
-    "fetch_kib": {"k_tp_score": 1.42382e+07, "k_tp_lookup": 1.36563e+07},
-    "write_kib": {"k_tp_score": 7.31457e+06, "k_tp_lookup": 5.58949e+06},
+    "fetch_kib": {"k_tp_score": 1.42408e+07, "k_tp_lookup": 1.36641e+07},
+    "write_kib": {"k_tp_score": 7.31471e+06, "k_tp_lookup": 5.57959e+06},
     "launches": {"k_tp_score": 318, "k_tp_lookup": 317},
 }
 
