@@ -44,10 +44,17 @@ __global__ __launch_bounds__(kXcBlock) void k_xc_terms(const RowT* __restrict__ 
     double ec = 0.0, base = 0.0;
     uint32_t c0 = 0, c1 = 0;
     if (v < n) {
+        // (four entries per lane and turn, their loads side by side: a label look-up is a cache miss)
         const int64_t end = (int64_t)rowptr[v + 1];
-        for (int64_t e = (int64_t)rowptr[v] + sub; e < end; e += kXcGroup) {
-            const int32_t l = labels[colidx[e]];
-            c0 += l == 0; c1 += l == 1;
+        constexpr int kTurn = 4;
+        for (int64_t e = (int64_t)rowptr[v] + sub; e < end; e += kTurn * kXcGroup) {
+            int32_t c[kTurn], l[kTurn];
+#pragma unroll
+            for (int u = 0; u < kTurn; ++u) c[u] = e + u * kXcGroup < end ? colidx[e + u * kXcGroup] : -1;
+#pragma unroll
+            for (int u = 0; u < kTurn; ++u) l[u] = c[u] >= 0 ? labels[c[u]] : -1;
+#pragma unroll
+            for (int u = 0; u < kTurn; ++u) { c0 += l[u] == 0; c1 += l[u] == 1; }
         }
     }
 #pragma unroll

@@ -1364,7 +1364,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP =
         meta[at] |= (uint16_t)0x100u;
     }
 
-    tp_count_stream<true, KP, LB, 4>(R, Lx, sbeg, 0u, slen >> 3, k, hist);
+    tp_count_stream<true, KP, LB, 3>(R, Lx, sbeg, 0u, slen >> 3, k, hist);
     if (any_hub) tp_count_stream<false, KP, LB, 2>(R, Lx, hbeg, hg0, hg1, k, hhist);
     __syncthreads();
 
