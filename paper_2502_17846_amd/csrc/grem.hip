@@ -776,9 +776,9 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
     L.mark();
     const size_t max_chunk_hubs = (size_t)P.max_chunk_hubs;
     uint32_t prev_hubs = 0;                 // hubs of the chunk before (whose counts the admission clears)
-    // first pass, chunks of at most kAdmitTile tiles: the spill is one launch that reads the sizes from one
+    // first pass, chunks of at most kSpillSmallTiles tiles: the spill is one launch that reads the sizes from one
     // array and writes them to the other; the two take turns from chunk to chunk
-    const bool spill_small = (cl + kAdmitTile - 1) / kAdmitTile <= kAdmitTile;
+    const bool spill_small = (cl + kAdmitTile - 1) / kAdmitTile <= kSpillSmallTiles;
     long long *Snow = st.S;
     for (int pass = 0; pass <= R && !L.err; ++pass) {
         for (int64_t c = 0; c < geo.nch && !L.err; ++c) {

@@ -1004,6 +1004,9 @@ __global__ __launch_bounds__(kAdmitThreads) void k_spill_fill(
 // partitions are level.  (The callers alternate between two arrays from chunk to chunk; Sout is
 // written in full in every launch.)
 // ------------------------------------------------------------------------------------------------
+constexpr int kSpillPer = 4;                                   // tiles per thread in the prefix
+constexpr int kSpillSmallTiles = kSpillPer * kAdmitTile;       // most tiles of a chunk
+
 template <int KP>
 __global__ __launch_bounds__(kAdmitTile) void k_spill_small(uint8_t *__restrict__ Lc, int64_t chunk_lo, int64_t chunk_hi,
                                                             int k, const uint32_t *__restrict__ ocnt, int ntiles,
@@ -1019,8 +1022,15 @@ __global__ __launch_bounds__(kAdmitTile) void k_spill_small(uint8_t *__restrict_
     __shared__ uint32_t wun[TPW][nwaves];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int tile0 = TPW * (int)blockIdx.x;
-    // exclusive prefix of the tiles' counts (at most kAdmitTile tiles: one per thread)
-    const uint32_t mine = tid < ntiles ? ocnt[tid] : 0u;
+    // exclusive prefix of the tiles' counts (at most kSpillSmallTiles tiles: thread tid takes the tiles
+    // kSpillPer * tid .. kSpillPer * tid + kSpillPer - 1)
+    uint32_t part[kSpillPer], mine = 0;
+#pragma unroll
+    for (int x = 0; x < kSpillPer; ++x) {
+        const int tile = kSpillPer * tid + x;
+        part[x] = tile < ntiles ? ocnt[tile] : 0u;
+        mine += part[x];
+    }
     long long sj = 0;
     if (tid < k) sj = Sin[tid];
     uint32_t inc = mine;
@@ -1034,7 +1044,15 @@ __global__ __launch_bounds__(kAdmitTile) void k_spill_small(uint8_t *__restrict_
     __syncthreads();
     uint32_t before = inc - mine;
     for (int w = 0; w < wave; ++w) before += wtot[w];
-    if (tid >= tile0 && tid < tile0 + TPW) s_base[tid - tile0] = before;
+    {
+        uint32_t run = before;
+#pragma unroll
+        for (int x = 0; x < kSpillPer; ++x) {
+            const int tile = kSpillPer * tid + x;
+            if (tile >= tile0 && tile < tile0 + TPW) s_base[tile - tile0] = run;
+            run += part[x];
+        }
+    }
     if (tid == kAdmitTile - 1) s_total = before + mine;
     __syncthreads();
     const uint32_t total = s_total;
