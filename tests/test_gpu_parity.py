@@ -173,6 +173,19 @@ def test_two_phase_path_17_to_32_partitions(k):
     _check(r, k, 1.05, 1 << 13, 2, mode=B.HIST_SWEEP, col_bits=11, hub_degree=300, tag="wide, rmat")
     h = synth.hub_stress(scale=14, edge_factor=8, hubs=3, hub_degree=3000, seed=2)
     _check(h, k, 1.05, 3000, 2, mode=B.HIST_SWEEP, col_bits=9, hub_degree=200, tag="wide, hubs")
+    # some 160 hubs in the one chunk: the admission kernel that works the hubs out itself takes them in
+    # several turns (32 hubs per turn and workgroup, four turns' loads at a time)
+    _check(g, k, 1.0, 6000, 2, mode=B.HIST_SWEEP, col_bits=8, hub_degree=17, tag="wide, hubs in the admission")
+
+
+def test_admission_with_several_hundred_hubs_per_chunk():
+    # between 256 and 512 hubs per chunk: the one-launch admission takes them in two turns; slack 1.0 keeps
+    # partitions at their capacity, so that ranks decide
+    g = synth.planted_partition(n=6000, blocks=3, mean_degree=10.0, seed=5)
+    _check(g, 16, 1.0, 3000, 2, mode=B.HIST_SWEEP, col_bits=8, hub_degree=14, tag="many hubs in the admission")
+    rng = np.random.default_rng(1)
+    seed = np.where(rng.random(g.n) < 0.2, rng.integers(0, 7, g.n), -1).astype(np.int32)
+    _check(g, 7, 1.02, 3000, 3, seed=seed, mode=B.HIST_SWEEP, col_bits=7, hub_degree=14, tag="many hubs, seeded")
 
 
 def test_two_phase_path_big_hub():
