@@ -525,6 +525,14 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
     int batch = 8192 / nbg;
     if (batch > 8) batch = 8;
     if (batch < 1) batch = 1;
+    {
+        // ... and no more than fit the stage at the average row's size (a batch that does not fit is halved
+        // by the kernel, at the price of setting its tables up again)
+        const size_t fixed8 = tp_place_fixed_bytes(nbg, 8, 8 * (npr > nps ? npr : nps));
+        const double cap8 = kPlaceLds > fixed8 ? (double)(kPlaceLds - fixed8) / 4.0 : 0.0;
+        const double per_row = (double)d.slots / ((double)geo.nch * (double)d.nr) / (double)geo.ngroups;
+        while (batch > 1 && per_row * 1.25 * batch > cap8) --batch;
+    }
     const int maxruns = batch * (npr > nps ? npr : nps);
     const size_t place_fixed = tp_place_fixed_bytes(nbg, batch, maxruns);
     const uint32_t capP = (uint32_t)(kPlaceLds > place_fixed ? (kPlaceLds - place_fixed) / 4 : 0);

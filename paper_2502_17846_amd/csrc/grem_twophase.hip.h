@@ -715,8 +715,8 @@ __global__ __launch_bounds__(1024) void k_tp_scan(u64 *__restrict__ a0, int64_t 
 // included (row field 2048: the score kernel ignores them; they fill every sub-segment up to a
 // multiple of kSubPad), and written out contiguously: the columns (24 bytes per group of eight) to T piece by
 // piece, the row fields (16 bits each) to R sub-segment by sub-segment (in R the sub-segments of one
-// row for consecutive blocks are adjacent).  A batch that does not fit `cap` slots is cut down to one
-// row; a row that does not fit is written tuple by tuple.
+// row for consecutive blocks are adjacent).  A batch that does not fit `cap` slots is halved until it
+// does; a row that does not fit is written tuple by tuple.
 // LDS: tbase[nbg], sbase[batch], runsrc[batch * npmax] (u64), runlen[batch * npmax + 1],
 //      runsl[batch * npmax], joff[nbg + 1], s0[nbg], cur / sub0 / sublen / ddv [batch * nbg], stage[cap]
 // ------------------------------------------------------------------------------------------------
@@ -841,7 +841,7 @@ __global__ __launch_bounds__(kPlaceThreads) void k_tp_place(int64_t n, SweepPlan
                 __syncthreads();
                 need = joff[nbg];
                 if (need <= cap || nb == 1) break;
-                nb = 1;
+                nb >>= 1;
             }
             const bool staged = need <= cap;
             for (int z = tid; z < nb * nbg; z += kPlaceThreads) {
