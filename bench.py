@@ -28,11 +28,11 @@ HBM_PEAK_GBPS = 8000.0
 # at that time, and `traffic` is reported as null when the sources have changed since.
 PMC = {
     "workload": "chunglu-111M",
-    "sources_sha256": "ac5e47560a483c94d530baa7b39279bf74ae340583fcf631e270fa531c98fcd9",
+    "sources_sha256": "cbb6b94c684939d380499baf362d7a6a7697e5c2b134579bc01056bd9fbe26d9",
     "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,592 KiB
     "write_factor": 1.0,        # 2 GiB written -> WRITE_SIZE 2,097,152 KiB
-    "fetch_kib": {"k_tp_score": 1.42604e+07, "k_tp_lookup": 1.36558e+07},
-    "write_kib": {"k_tp_score": 7.31471e+06, "k_tp_lookup": 5.60088e+06},
+    "fetch_kib": {"k_tp_score": 1.42594e+07, "k_tp_lookup": 1.36544e+07},
+    "write_kib": {"k_tp_score": 7.31471e+06, "k_tp_lookup": 5.60043e+06},
     "launches": {"k_tp_score": 318, "k_tp_lookup": 317},
 }
 
