@@ -145,7 +145,7 @@ int grem_partition_opt(const void *rowptr, int32_t rowptr_bits, const int32_t *c
  * of a call.
  *
  * grem_plan_create re-lays the entries out (synchronous: it returns when the plan is complete) into
- * device memory the plan owns (hipMalloc; 5 bytes per entry and per pad slot plus the offset tables, 5.9 per
+ * device memory the plan owns (hipMalloc; 5 bytes per entry and per pad slot plus the offset tables, 5.8 per
  * entry in all on a 3.2e9-entry power-law graph; an intermediate
  * copy of 4 bytes per entry is allocated stream-ordered and released before the call returns).
  * rowptr must stay valid and unchanged while the plan lives; colidx is not read after the call
