@@ -504,6 +504,7 @@ int build_plan(PlanData &P, const RowT *rowptr, const int32_t *colidx, int64_t n
     tb.nbc = geo.nbc;
     tb.nblk = geo.nblk;
     tb.cb = geo.cb;
+    tb.flat = (tb.chunk_shift >= geo.cb && geo.chunk > 1) ? 1 : 0;
     tb.gb = geo.gb;
     tb.ngroups = geo.ngroups;
     tb.npr = npr;

@@ -114,9 +114,14 @@ struct TpTables {
     int nbc;          // column blocks per chunk
     int nblk;         // nch * nbc
     int cb;           // log2 of the vertices per column block
+    int flat;         // chunk is a power of two and at least a block: block of vertex u = u >> cb
 };
 
 __device__ __forceinline__ uint32_t tp_block_of(uint32_t u, const TpTables &g, uint32_t *col_low) {
+    if (g.flat) {                       // chunks are whole numbers of blocks: the blocks tile the vertex ids
+        *col_low = u & ((1u << g.cb) - 1u);
+        return u >> g.cb;
+    }
     const uint32_t cu = g.chunk_shift >= 0 ? (u >> g.chunk_shift) : (__umulhi(u, g.chunk_magic) >> g.chunk_magic_shift);
     const uint32_t rel = u - cu * g.chunk;
     *col_low = rel & ((1u << g.cb) - 1u);
@@ -398,22 +403,23 @@ __device__ __forceinline__ void tp_load_round(const TpEntrySource &src, uint32_t
             row[u] = 0;
         }
         if (blk >= src.ne) return;
-        const uint32_t last = blk + 64u * U - 1u < src.ne ? blk + 64u * U - 1u : src.ne - 1u;
-        uint32_t rlo = 0, rhi = 0;
-        for (int step = src.rp >> 1; step >= 1; step >>= 1) {
-            if (src.rowrel[rlo + step] <= blk) rlo += step;
-            if (src.rowrel[rhi + step] <= last) rhi += step;
+        // The row of an entry p is the largest r with rowrel[r] <= p (empty rows resolve to the last of equal
+        // offsets, the one that holds p).  Lane u < U finds it for the first entry of the wavefront's u-th
+        // run of 64 entries (a binary search each, side by side); every lane then walks on from there: 64
+        // consecutive entries seldom span more than two or three rows.
+        uint32_t first_row = 0;
+        {
+            const uint32_t target = blk + 64u * (uint32_t)(lane < U ? lane : 0);
+            const uint32_t tc = target < src.ne ? target : src.ne - 1u;
+            for (int step = src.rp >> 1; step >= 1; step >>= 1)
+                if (src.rowrel[first_row + step] <= tc) first_row += step;
         }
-        uint32_t span = 1;
-        while (span <= rhi - rlo) span <<= 1;               // > rhi - rlo
 #pragma unroll
-        for (int u = 0; u < U; ++u) row[u] = rlo;
-        for (uint32_t step = span >> 1; step >= 1; step >>= 1) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t cand = row[u] + step;        // largest r in [rlo, rhi] with rowrel[r] <= p
-                const uint32_t cc = cand <= rhi ? cand : rhi;
-                if (cand <= rhi && src.rowrel[cc] <= blk + u * 64 + lane) row[u] = cand;
+        for (int u = 0; u < U; ++u) {
+            row[u] = (uint32_t)__builtin_amdgcn_readlane((int)first_row, u);
+            if (on[u]) {
+                const uint32_t p = blk + u * 64 + lane;
+                while (src.rowrel[row[u] + 1] <= p) ++row[u];
             }
         }
         if (src.has_hubs) {
@@ -569,12 +575,15 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
     const uint32_t rounds = tp_rounds<SHARE>(src);
     uint32_t row[kTpBatch], col[kTpBatch];
     bool on[kTpBatch];
+    // (col[u] becomes block << kMaxColBits | column in block: the second phase does not work it out again)
     for (uint32_t r = 0; r < rounds; ++r) {
         tp_load_round<SHARE>(src, r, row, col, on);
 #pragma unroll
         for (int u = 0; u < kTpBatch; ++u) {
             uint32_t low;
-            if (on[u]) atomicAdd(&cntf[tp_block_of(col[u], tb, &low)], 1u);
+            const uint32_t jb = tp_block_of(col[u], tb, &low);
+            col[u] = (jb << kMaxColBits) | low;
+            if (on[u]) atomicAdd(&cntf[jb], 1u);
         }
     }
     __syncthreads();
@@ -622,12 +631,19 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(8, 8
     const uint32_t gmask = (1u << tb.gb) - 1u;
     uint32_t *ubase = U + ustart;
     for (uint32_t r = 0; r < rounds; ++r) {
-        if (rounds > 1) tp_load_round<SHARE>(src, r, row, col, on);
+        if (rounds > 1) {
+            tp_load_round<SHARE>(src, r, row, col, on);
+#pragma unroll
+            for (int u = 0; u < kTpBatch; ++u) {
+                uint32_t low;
+                const uint32_t jb = tp_block_of(col[u], tb, &low);
+                col[u] = (jb << kMaxColBits) | low;
+            }
+        }
         uint32_t w[kTpBatch], tuple[kTpBatch];
 #pragma unroll
         for (int u = 0; u < kTpBatch; ++u) {
-            uint32_t low;
-            const uint32_t jb = tp_block_of(col[u], tb, &low);
+            const uint32_t jb = col[u] >> kMaxColBits, low = col[u] & ((1u << kMaxColBits) - 1u);
             tuple[u] = (row[u] << (tb.cb + tb.gb)) | ((jb & gmask) << tb.cb) | low;
             w[u] = on[u] ? atomicAdd(&cntf[jb], 1u) : 0u;
         }
