@@ -177,6 +177,28 @@ int grem_partition_planned(const grem_plan *plan, int32_t k, double balance_slac
                            int32_t refine_passes, const int32_t *seed_labels, int32_t *labels_out,
                            int64_t *sizes_out, uint32_t *estimates_out, void *stream);
 
+/* ---- Evaluating a labelling on a plan -----------------------------------------------------------
+ * cnt_nbrs (Alg. 2) of every vertex at once under a labelling that stays as it is:
+ *   counts_out[v*k + j] = number of CSR entries of row v whose column has label j
+ * (columns without a label are in no count).  The plan's copy of the entries serves every label
+ * look-up from LDS, where a walk over the CSR arrays pays a cache miss per entry: on a graph whose
+ * label table exceeds the L2 this is several times faster than grem_edge_cut / grem_expected_cut.
+ * labels: n device int32, each -1 (no label) or in [0, k); k <= grem_plan_max_k.  counts_out: n*k device uint32,
+ * 16-byte aligned.  State comes from the workspace or a stream-ordered allocation:
+ * grem_plan_call_bytes(plan, k, 0, 1, 1) bytes (grem_plan_edge_cut: n*k*4 more).  One read-back (the
+ * labels' validity) happens inside the call.
+ * Errors: GREM_ERR_ARG, GREM_ERR_SEED (a label outside -1 .. k-1), GREM_ERR_NOMEM, GREM_ERR_HIP.
+ *
+ * grem_plan_edge_cut: the result of grem_edge_cut for the plan's graph (a vertex without a label differs
+ * from every labelled neighbour), from those counts.
+ * grem_plan_expected_cut (declared with grem_expected_cut below): Eq. (1) from those counts.
+ * grem_plan_n: the plan's number of vertices (0 for NULL). */
+int64_t grem_plan_n(const grem_plan *plan);
+int grem_plan_neighbour_counts(const grem_plan *plan, int32_t k, const int32_t *labels,
+                               uint32_t *counts_out, void *stream);
+int grem_plan_edge_cut(const grem_plan *plan, int32_t k, const int32_t *labels,
+                       int64_t *cut_entries_out, void *stream);
+
 /* Number of CSR entries (v,u) with labels[v] != labels[u] (Sec. 1: cut edges have their endpoints
  * in different partitions), written to the single device int64 *cut_entries_out.  For a symmetric
  * loop-free CSR the undirected cut is half of it and the cut fraction is cut_entries / nnz.
@@ -316,6 +338,14 @@ int grem_edge_buckets(const int32_t *src, const int32_t *dst, int64_t m, int64_t
  * n < 1, bad rowptr_bits, x outside (0, 1]), GREM_ERR_NOMEM, GREM_ERR_HIP. */
 int grem_expected_cut(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,
                       const int32_t *labels, double x, double *out, void *stream);
+
+/* Eq. (1) for the graph of a plan: the same two sums as grem_expected_cut (up to the order of the
+ * additions: about 1e-13 relative), with the neighbour counts taken from grem_plan_neighbour_counts.
+ * labels: n device int32, each -1, 0 or 1 (GREM_ERR_SEED otherwise).  Allocates n*8 bytes and the
+ * per-workgroup sums stream-ordered, beside what grem_plan_neighbour_counts takes.
+ * Errors: GREM_ERR_ARG (null pointer, x outside (0, 1]), GREM_ERR_SEED, GREM_ERR_NOMEM, GREM_ERR_HIP. */
+int grem_plan_expected_cut(const grem_plan *plan, const int32_t *labels, double x, double *out,
+                           void *stream);
 
 /* grem_expected_cut for callers that cannot allocate device memory: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same

@@ -142,6 +142,18 @@ def edge_cut(rowptr, colidx, n, labels) -> int:
                                             _p(lab, ctypes.c_int32)))
 
 
+def neighbour_counts(rowptr, colidx, n, labels, k):
+    """cnt_nbrs (Alg. 2) of every vertex under a fixed labelling: out[v, j] = number of CSR entries (v, u)
+    with labels[u] == j; entries whose column has no label (-1) are in no count."""
+    rp, ci = _csr(rowptr, colidx)
+    lab = np.asarray(labels).astype(np.int64)
+    rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rp))
+    nl = lab[ci]
+    have = nl >= 0
+    flat = np.bincount(rows[have] * k + nl[have], minlength=n * k)
+    return flat.reshape(n, k).astype(np.int64)
+
+
 class Stepper:
     """The run one chunk at a time, for tests that look at the state between chunks and for the
     bounded CPU-baseline sample."""

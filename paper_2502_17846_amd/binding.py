@@ -29,6 +29,7 @@ EXPORTS = [
     "grem_edge_stream_bipartition", "grem_edge_list_cut", "grem_edge_stream_profile_enable",
     "grem_edge_stream_profile_read", "grem_recursive_bisection", "grem_edge_buckets", "grem_expected_cut",
     "grem_expected_cut_noalloc", "grem_expected_cut_noalloc_max_n",
+    "grem_plan_n", "grem_plan_neighbour_counts", "grem_plan_edge_cut", "grem_plan_expected_cut",
 ]
 EDGE_REFINE, EDGE_FIXED = 0, 1
 
@@ -96,6 +97,14 @@ def load():
     lib.grem_plan_max_k.argtypes = [vp]
     lib.grem_plan_call_bytes.restype = ctypes.c_size_t
     lib.grem_plan_call_bytes.argtypes = [vp, i32, i32, i32, i32]
+    lib.grem_plan_n.restype = ctypes.c_int64
+    lib.grem_plan_n.argtypes = [vp]
+    lib.grem_plan_neighbour_counts.restype = ctypes.c_int
+    lib.grem_plan_neighbour_counts.argtypes = [vp, i32, vp, vp, vp]
+    lib.grem_plan_edge_cut.restype = ctypes.c_int
+    lib.grem_plan_edge_cut.argtypes = [vp, i32, vp, vp, vp]
+    lib.grem_plan_expected_cut.restype = ctypes.c_int
+    lib.grem_plan_expected_cut.argtypes = [vp, vp, dbl, vp, vp]
     lib.grem_partition_planned.restype = ctypes.c_int
     lib.grem_partition_planned.argtypes = [vp, i32, dbl, i32, vp, vp, vp, vp, vp]
     lib.grem_workspace_bytes.restype = ctypes.c_size_t
@@ -332,6 +341,34 @@ def grem_partition_planned(plan: Plan, k, balance_slack, refine_passes, seed_lab
     if want_sizes or want_estimates:
         return labels_out, sizes, est
     return labels_out
+
+
+def grem_plan_neighbour_counts(plan: Plan, k, labels, counts_out=None, stream=None) -> torch.Tensor:
+    """Device int32 tensor (n, k): per vertex, its CSR entries by the label of their column."""
+    if counts_out is None:
+        counts_out = torch.empty((plan.n, k), dtype=torch.int32, device=plan._rowptr.device)
+    rc = load().grem_plan_neighbour_counts(plan._h, k, _dev(labels, torch.int32, "labels"),
+                                           _dev(counts_out, torch.int32, "counts_out"), _stream(stream))
+    _check(rc, "grem_plan_neighbour_counts")
+    return counts_out
+
+
+def grem_plan_edge_cut(plan: Plan, k, labels, stream=None) -> torch.Tensor:
+    """Device int64 tensor with one element: the number of cut CSR entries of the plan's graph."""
+    out = torch.empty(1, dtype=torch.int64, device=plan._rowptr.device)
+    rc = load().grem_plan_edge_cut(plan._h, k, _dev(labels, torch.int32, "labels"),
+                                   _dev(out, torch.int64, "cut_entries_out"), _stream(stream))
+    _check(rc, "grem_plan_edge_cut")
+    return out
+
+
+def grem_plan_expected_cut(plan: Plan, labels, x, stream=None) -> torch.Tensor:
+    """Device float64 tensor [E[C](x), sum_i (k_i - k0_i)] of Eq. (1) for the plan's graph."""
+    out = torch.empty(2, dtype=torch.float64, device=plan._rowptr.device)
+    rc = load().grem_plan_expected_cut(plan._h, _dev(labels, torch.int32, "labels"), float(x),
+                                       _dev(out, torch.float64, "out"), _stream(stream))
+    _check(rc, "grem_plan_expected_cut")
+    return out
 
 
 def grem_edge_cut(rowptr, colidx, n, labels, stream=None) -> torch.Tensor:

@@ -643,9 +643,10 @@ void launch_outputs(Launcher &L, CallState<LabelT> &st, int64_t n, int32_t k, in
     hipStream_t stream = L.stream;
     int64_t blocks = (n + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
-    L.run(GREM_KERNEL_EXPAND, [&] {
-        hipLaunchKernelGGL((k_expand<LabelT>), dim3((unsigned)blocks), dim3(256), 0, stream, st.Lc, n, labels_out);
-    });
+    if (labels_out)
+        L.run(GREM_KERNEL_EXPAND, [&] {
+            hipLaunchKernelGGL((k_expand<LabelT>), dim3((unsigned)blocks), dim3(256), 0, stream, st.Lc, n, labels_out);
+        });
     if (sizes_out)
         L.run(GREM_KERNEL_EXPAND, [&] {
             hipLaunchKernelGGL(k_copy_sizes, dim3((k + 255) / 256), dim3(256), 0, stream, st.S, (int)k, sizes_out);
@@ -685,9 +686,13 @@ bool admission_takes_hubs(const PlanData &P, bool use16, bool external_E) {
 
 // Alg. 1's loop on a plan.  `prepared`: the common state with the prepass run and the seed validated by
 // the caller; otherwise this function does both (one read-back when there is a seed).
+// fixed_labels: nothing is decided.  The seed is a labelling that stays as it is (R = 0, estimates_out
+// given): after the initial look-up of every label, each chunk runs its counting launches only, and
+// estimates_out receives cnt_nbrs (Alg. 2) of every vertex under that labelling.
 template <typename RowT>
 int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const int32_t *seed, int32_t *labels_out,
-                  int64_t *sizes_out, uint32_t *estimates_out, Arena &mem, Launcher &L, CallState<uint8_t> *prepared) {
+                  int64_t *sizes_out, uint32_t *estimates_out, Arena &mem, Launcher &L, CallState<uint8_t> *prepared,
+                  bool fixed_labels = false) {
     hipStream_t stream = L.stream;
     const RowT *rowptr = (const RowT *)P.rowptr;
     const int64_t n = P.n;
@@ -700,6 +705,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
     const int hub_degree = P.hub_degree;
     if (R >= 32 || (P.maxdeg << R) >= (1ull << 32)) return GREM_ERR_RANGE;
     if (external_E && (((uintptr_t)estimates_out) & 15u) != 0) return GREM_ERR_ARG;
+    if (fixed_labels && (!seed || !external_E || R != 0)) return GREM_ERR_ARG;
     // estimates of the regular rows stay below hub_degree * 2^R: 16 bits when that fits
     const bool use16 = (((unsigned long long)(hub_degree - 1)) << R) <= 65535ull;
 
@@ -858,6 +864,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                                        (uint8_t *)st.prop, st.cnt, (int)c, lo, (int)k, pass, store_e, (int)admit_blocks,
                                        st.tot);
             });
+            if (fixed_labels) continue;          // counts only: nothing to admit, no new labels to look up
             // admission: the score kernel has counted the movers per tile and taken the sizes' snapshot, and
             // the tiles are few enough that every workgroup adds up the earlier tiles' counts itself
             L.run(GREM_KERNEL_APPLY, [&] {
@@ -1350,6 +1357,76 @@ int grem_partition_planned(const grem_plan *plan, int32_t k, double balance_slac
                                                 sizes_out, estimates_out, mem, L, nullptr)
                        : run_two_phase<int32_t>(plan->data, k, balance_slack, refine_passes, seed_labels, labels_out,
                                                 sizes_out, estimates_out, mem, L, nullptr);
+    mem.release_all();
+    return rc;
+}
+
+int64_t grem_plan_n(const grem_plan *plan) { return plan ? plan->data.n : 0; }
+
+namespace {
+
+// cnt_nbrs of every vertex under a labelling that stays as it is, on a plan; `mem` supplies the
+// run's state (the caller releases it)
+int plan_counts(const grem_plan *plan, int32_t k, const int32_t *labels, uint32_t *counts_out, Arena &mem, Launcher &L) {
+    // capacity n: whatever the labelling, no partition is over it
+    return plan->data.rowptr_bits == 64
+               ? run_two_phase<int64_t>(plan->data, k, (double)k, 0, labels, nullptr, nullptr, counts_out, mem, L, nullptr, true)
+               : run_two_phase<int32_t>(plan->data, k, (double)k, 0, labels, nullptr, nullptr, counts_out, mem, L, nullptr, true);
+}
+
+void plan_call_setup(Arena &mem, Launcher &L, hipStream_t s) {
+    mem.stream = s;
+    std::lock_guard<std::mutex> lock(g.mu);
+    mem.base = (char *)g.ws;
+    mem.cap = g.ws_bytes;
+    L.level = g.prof_level;
+}
+
+}  // namespace
+
+int grem_plan_neighbour_counts(const grem_plan *plan, int32_t k, const int32_t *labels, uint32_t *counts_out,
+                               void *stream) {
+    if (!plan || !plan->data.T || !labels || !counts_out || k < 1 || k > plan->data.max_k) return GREM_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    Arena mem;
+    Launcher L{s};
+    plan_call_setup(mem, L, s);
+    L.mark();
+    const int rc = plan_counts(plan, k, labels, counts_out, mem, L);
+    mem.release_all();
+    return rc;
+}
+
+int grem_plan_edge_cut(const grem_plan *plan, int32_t k, const int32_t *labels, int64_t *cut_entries_out,
+                       void *stream) {
+    if (!plan || !plan->data.T || !labels || !cut_entries_out || k < 1 || k > plan->data.max_k) return GREM_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    Arena mem;
+    Launcher L{s};
+    plan_call_setup(mem, L, s);
+    L.mark();
+    const int64_t n = plan->data.n;
+    uint32_t *counts = nullptr;
+    if (!carve(mem, [&](Carver &c) { c.take(counts, (size_t)n * (size_t)k); })) return GREM_ERR_NOMEM;
+    int rc = plan_counts(plan, k, labels, counts, mem, L);
+    if (rc == GREM_OK) {
+        int64_t blocks = (n + 255) / 256;
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        L.run(GREM_KERNEL_EXPAND, [&] {
+            hipLaunchKernelGGL(k_zero_u64, dim3(1), dim3(64), 0, s, (unsigned long long *)cut_entries_out, 1);
+        });
+        L.run(GREM_KERNEL_EXPAND, [&] {
+            if (plan->data.rowptr_bits == 64)
+                hipLaunchKernelGGL(k_cut_from_counts<int64_t>, dim3((unsigned)blocks), dim3(256), 0, s,
+                                   (const int64_t *)plan->data.rowptr, labels, (const uint32_t *)counts, n, (int)k,
+                                   (unsigned long long *)cut_entries_out);
+            else
+                hipLaunchKernelGGL(k_cut_from_counts<int32_t>, dim3((unsigned)blocks), dim3(256), 0, s,
+                                   (const int32_t *)plan->data.rowptr, labels, (const uint32_t *)counts, n, (int)k,
+                                   (unsigned long long *)cut_entries_out);
+        });
+        rc = L.err;
+    }
     mem.release_all();
     return rc;
 }

@@ -30,6 +30,35 @@ __device__ __forceinline__ double xc_log_choose(double a, double b)
     return lgamma(a + 1.0) - lgamma(b + 1.0) - lgamma(a - b + 1.0);
 }
 
+// One node's terms of Eq. (1) from its two neighbour counts: *ec = (k - k0)(1 - q) + k0 q, *base = k - k0
+// (both left as they are for a node without labelled neighbours).
+__device__ __forceinline__ void xc_node_terms(uint32_t c0, uint32_t c1, double x, double* ec_out, double* base_out)
+{
+    const long long k = (long long)c0 + c1, k0 = c0 > c1 ? c0 : c1, r = k - k0;
+    if (k <= 0) return;
+    long long d = (long long)floor((double)k * x + 0.5);
+    if (d > k) d = k;
+    if (d < 0) d = 0;
+    // q = sum of pmf(j) over the support with 2j < d
+    const long long jlo = d - r > 0 ? d - r : 0;
+    long long jhi = (d + 1) / 2 - 1;
+    if (jhi > k0) jhi = k0;
+    double q = 0.0;
+    if (jhi >= jlo) {
+        double logp = xc_log_choose((double)k0, (double)jlo) + xc_log_choose((double)r, (double)(d - jlo)) -
+                      xc_log_choose((double)k, (double)d);
+        q = exp(logp);
+        for (long long j = jlo; j < jhi; ++j) {
+            // pmf(j+1) / pmf(j)
+            logp += log((double)(k0 - j)) + log((double)(d - j)) - log((double)(j + 1)) - log((double)(r - d + j + 1));
+            q += exp(logp);
+        }
+        if (q > 1.0) q = 1.0;
+    }
+    *ec_out = (double)r * (1.0 - q) + (double)k0 * q;
+    *base_out = (double)r;
+}
+
 constexpr int kXcGroup = 16;                       // lanes that share one node's row
 constexpr int kXcRows = kXcBlock / kXcGroup;       // nodes per workgroup
 
@@ -59,31 +88,30 @@ __global__ __launch_bounds__(kXcBlock) void k_xc_terms(const RowT* __restrict__ 
     }
 #pragma unroll
     for (int o = kXcGroup / 2; o > 0; o >>= 1) { c0 += __shfl_xor(c0, o); c1 += __shfl_xor(c1, o); }
-    if (v < n && sub == 0) {
-        const long long k = (long long)c0 + c1, k0 = c0 > c1 ? c0 : c1, r = k - k0;
-        if (k > 0) {
-            long long d = (long long)floor((double)k * x + 0.5);
-            if (d > k) d = k;
-            if (d < 0) d = 0;
-            // q = sum of pmf(j) over the support with 2j < d
-            const long long jlo = d - r > 0 ? d - r : 0;
-            long long jhi = (d + 1) / 2 - 1;
-            if (jhi > k0) jhi = k0;
-            double q = 0.0;
-            if (jhi >= jlo) {
-                double logp = xc_log_choose((double)k0, (double)jlo) + xc_log_choose((double)r, (double)(d - jlo)) -
-                              xc_log_choose((double)k, (double)d);
-                q = exp(logp);
-                for (long long j = jlo; j < jhi; ++j) {
-                    // pmf(j+1) / pmf(j)
-                    logp += log((double)(k0 - j)) + log((double)(d - j)) - log((double)(j + 1)) - log((double)(r - d + j + 1));
-                    q += exp(logp);
-                }
-                if (q > 1.0) q = 1.0;
-            }
-            ec = (double)r * (1.0 - q) + (double)k0 * q;
-            base = (double)r;
-        }
+    if (v < n && sub == 0) xc_node_terms(c0, c1, x, &ec, &base);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { ec += __shfl_down(ec, o); base += __shfl_down(base, o); }
+    if ((threadIdx.x & 63) == 0) { s_ec[threadIdx.x >> 6] = ec; s_base[threadIdx.x >> 6] = base; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double a = 0.0, b = 0.0;
+        for (int q = 0; q < kXcBlock / 64; ++q) { a += s_ec[q]; b += s_base[q]; }
+        partial_ec[blockIdx.x] = a; partial_base[blockIdx.x] = b;
+    }
+}
+
+// The same terms from neighbour counts that are at hand (counts[2 v], counts[2 v + 1]: the labelled
+// neighbours of node v in partition 0 and 1), one lane per node.
+constexpr int kXcCountRows = kXcBlock;
+__global__ __launch_bounds__(kXcBlock) void k_xc_terms_counts(const uint32_t* __restrict__ counts, int64_t n, double x,
+                                                              double* partial_ec, double* partial_base)
+{
+    __shared__ double s_ec[kXcBlock / 64], s_base[kXcBlock / 64];
+    const int64_t v = (int64_t)blockIdx.x * kXcCountRows + threadIdx.x;
+    double ec = 0.0, base = 0.0;
+    if (v < n) {
+        const uint2 c = *reinterpret_cast<const uint2*>(counts + 2 * v);
+        xc_node_terms(c.x, c.y, x, &ec, &base);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) { ec += __shfl_down(ec, o); base += __shfl_down(base, o); }
@@ -179,5 +207,36 @@ extern "C" int grem_expected_cut(const void* rowptr, int32_t rowptr_bits, const 
     else xc_launch<int32_t>(rowptr, colidx, n, labels, x, partial, blocks, out, stream);
     int rc = hipGetLastError() == hipSuccess ? GREM_OK : GREM_ERR_HIP;
     if (hipFreeAsync(partial, stream) != hipSuccess) rc = GREM_ERR_HIP;
+    return rc;
+}
+
+// Eq. (1) on a plan: the neighbour counts come from the plan's re-laid-out copy of the entries (every label
+// look-up served from LDS) instead of one look-up through the caches per CSR entry.
+extern "C" int grem_plan_expected_cut(const grem_plan* plan, const int32_t* labels, double x, double* out, void* stream_)
+{
+    const int64_t n = grem_plan_n(plan);
+    if (!plan || n < 1 || !labels || !out || !(x > 0.0) || !(x <= 1.0)) return GREM_ERR_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    const int64_t blocks = (n + kXcCountRows - 1) / kXcCountRows;
+    uint32_t* counts = nullptr;
+    double* partial = nullptr;
+    if (hipMallocAsync((void**)&counts, (size_t)n * 2 * sizeof(uint32_t), stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return GREM_ERR_NOMEM;
+    }
+    if (hipMallocAsync((void**)&partial, (size_t)blocks * 2 * sizeof(double), stream) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFreeAsync(counts, stream);
+        return GREM_ERR_NOMEM;
+    }
+    int rc = grem_plan_neighbour_counts(plan, 2, labels, counts, stream);
+    if (rc == GREM_OK) {
+        hipLaunchKernelGGL(k_xc_terms_counts, dim3((unsigned)blocks), dim3(kXcBlock), 0, stream, (const uint32_t*)counts, n, x,
+                           partial, partial + blocks);
+        hipLaunchKernelGGL(k_xc_total, dim3(1), dim3(1024), 0, stream, partial, partial + blocks, blocks, out);
+        if (hipGetLastError() != hipSuccess) rc = GREM_ERR_HIP;
+    }
+    if (hipFreeAsync(partial, stream) != hipSuccess) rc = rc == GREM_OK ? GREM_ERR_HIP : rc;
+    if (hipFreeAsync(counts, stream) != hipSuccess) rc = rc == GREM_OK ? GREM_ERR_HIP : rc;
     return rc;
 }

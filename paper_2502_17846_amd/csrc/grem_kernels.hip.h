@@ -1176,6 +1176,35 @@ __global__ __launch_bounds__(256) void k_edge_cut(const RowT *__restrict__ rowpt
     if (tid == 0 && s_sum) atomicAdd(out, s_sum);
 }
 
+// The same sum from the vertices' neighbour counts under the labelling (counts[v * k + j] = entries of
+// row v whose column has label j; columns without a label are in no count): a labelled vertex differs
+// from every neighbour outside its own count, an unlabelled one from every labelled neighbour.
+template <typename RowT>
+__global__ __launch_bounds__(256) void k_cut_from_counts(const RowT *__restrict__ rowptr,
+                                                         const int32_t *__restrict__ labels,
+                                                         const uint32_t *__restrict__ counts, int64_t n, int k,
+                                                         unsigned long long *__restrict__ out) {
+    __shared__ unsigned long long s_sum;
+    if (threadIdx.x == 0) s_sum = 0;
+    __syncthreads();
+    unsigned long long mine = 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
+        const int32_t l = labels[v];
+        const uint32_t *row = counts + (size_t)v * (size_t)k;
+        if (l >= 0 && l < k) {
+            mine += (unsigned long long)(rowptr[v + 1] - rowptr[v]) - (unsigned long long)row[l];
+        } else {
+            for (int j = 0; j < k; ++j) mine += row[j];
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off);
+    if (lane_id() == 0 && mine) atomicAdd(&s_sum, mine);
+    __syncthreads();
+    if (threadIdx.x == 0 && s_sum) atomicAdd(out, s_sum);
+}
+
 __global__ void k_zero_u64(unsigned long long *p, int count) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) p[i] = 0ull;

@@ -359,3 +359,36 @@ def test_errors():
     with pytest.raises(oracle.OracleError) as e:
         oracle.partition_seeded(g.rowptr, g.colidx, 10, 2, 1.05, 4, 0, seed)
     assert e.value.code == oracle.ERR_SEED
+
+
+def test_neighbour_counts_against_a_walk_over_the_entries():
+    # the definition, entry by entry, on a multigraph with loops, repeated entries, vertices without a label
+    # and rows without entries; and its ties to the cut and to the row lengths
+    rng = np.random.default_rng(31)
+    n, k = 57, 5
+    deg = rng.integers(0, 9, n)
+    deg[rng.integers(0, n, 6)] = 0
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    colidx = rng.integers(0, n, int(rowptr[-1])).astype(np.int32)
+    labels = rng.integers(-1, k, n).astype(np.int32)
+    want = [[0] * k for _ in range(n)]
+    for v in range(n):
+        for e in range(int(rowptr[v]), int(rowptr[v + 1])):
+            l = int(labels[int(colidx[e])])
+            if l != -1:
+                want[v][l] += 1
+    got = oracle.neighbour_counts(rowptr, colidx, n, labels, k)
+    assert got.tolist() == want
+    labelled_nbrs = np.array([sum(labels[colidx[rowptr[v]:rowptr[v + 1]]] >= 0) for v in range(n)])
+    assert np.array_equal(got.sum(axis=1), labelled_nbrs)
+    # cut entries: a labelled vertex differs from every entry outside its own count, an unlabelled one from
+    # every labelled neighbour
+    own = np.where(labels >= 0, got[np.arange(n), np.maximum(labels, 0)], 0)
+    cut = int(np.sum(np.where(labels >= 0, deg - own, got.sum(axis=1))))
+    assert cut == oracle.edge_cut(rowptr, colidx, n, labels)
+    # a transposed (column-major) or row/column-swapped count would fail here
+    one = np.zeros(n, np.int32) - 1
+    one[3] = 2
+    c = oracle.neighbour_counts(rowptr, colidx, n, one, k)
+    assert c[:, 2].tolist() == [int(np.sum(colidx[rowptr[v]:rowptr[v + 1]] == 3)) for v in range(n)]
+    assert int(c.sum()) == int(np.sum(colidx == 3))
