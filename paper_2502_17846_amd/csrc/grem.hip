@@ -587,6 +587,7 @@ template <typename LabelT> struct CallState {
     uint32_t *cnt = nullptr, *tot = nullptr, *ocnt = nullptr;
     int32_t *fillRank = nullptr;
     unsigned long long *misc = nullptr;
+    bool seed_complete = false;        // (host) the seed labels every vertex
 };
 
 template <typename LabelT>
@@ -729,6 +730,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             unsigned long long h[16] = {0};
             if (!L.read_back(h, st.misc, sizeof(h))) return L.err;
             if (h[1] != 0 || h[2] != 0) return GREM_ERR_SEED;
+            st.seed_complete = h[5] == 0;
         }
     }
     uint32_t *E32 = external_E ? estimates_out : t.E32;
@@ -782,10 +784,14 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             }
         });
     };
+    // A seed that leaves vertices without a label: the first pass reads its row fields from Rdyn, where the
+    // initial look-up marks the tuples whose neighbour has none.  A seed that labels every vertex marks
+    // nothing: R serves as it is, and the initial look-up is the one that copies the labels to LDS.
+    const bool marks = seed != nullptr && !st.seed_complete;
     if (seed) {        // the seeds are the labels every first-pass look-up starts from
         for (int c0 = 0; c0 < geo.nch; c0 += 32768) {
             const int count = geo.nch - c0 < 32768 ? geo.nch - c0 : 32768;
-            lookup(c0, count, 0, false, true);
+            lookup(c0, count, 0, !marks, marks);
         }
     }
     L.mark();
@@ -806,7 +812,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             // the estimates are state between passes and, if the caller asked for them, output: the last
             // pass does not store them otherwise
             const int store_e = (pass < R || external_E) ? 1 : 0;
-            const uint16_t *rows_now = (seed && pass == 0) ? t.Rdyn : P.R;
+            const uint16_t *rows_now = (marks && pass == 0) ? t.Rdyn : P.R;
             // from the second pass on every vertex has a label before its chunk's admission, which then
             // also leaves the chunk's labels two per byte for the look-ups (chunk starts must be even)
             uint8_t *packed_now = (pass >= 1 && t.Lc4 && (cl & 1) == 0) ? t.Lc4 : nullptr;
@@ -900,7 +906,7 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             }
             // the chunk's new labels, looked up for every row that will read them: rows of later chunks in
             // this pass, rows of this and earlier chunks in the next pass (if there is one)
-            lookup((int)c, 1, pass == R ? (int)c + 1 : 0, true, seed != nullptr && pass == 0, packed_now);
+            lookup((int)c, 1, pass == R ? (int)c + 1 : 0, true, marks && pass == 0, packed_now);
         }
         L.mark();
     }
@@ -1084,6 +1090,7 @@ int run_partition(const RowT *rowptr, const int32_t *colidx, int64_t n, int32_t 
                     unsigned long long h[16] = {0};
                     if (!L.read_back(h, st.misc, sizeof(h))) { mem.release_all(); return L.err; }
                     if (h[1] != 0 || h[2] != 0) { mem.release_all(); return GREM_ERR_SEED; }
+                    st.seed_complete = h[5] == 0;
                 }
                 if (R >= 32 || (maxdeg << R) >= (1ull << 32)) { mem.release_all(); return GREM_ERR_RANGE; }
             } else {

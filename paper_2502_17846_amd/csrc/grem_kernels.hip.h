@@ -45,8 +45,10 @@ __device__ __forceinline__ int owning_row(const uint32_t *rowrel, uint32_t i, in
 // ------------------------------------------------------------------------------------------------
 // prepass: compact labels from the seed, seed sizes, seed validity, and (when rowptr is given)
 // the maximum degree
-// misc[0] = max degree, misc[1] = number of invalid seed labels, misc[3] = number of entries
+// misc[0] = max degree, misc[1] = number of invalid seed labels, misc[3] = number of entries,
+// misc[5] = number of vertices the seed leaves without a label
 // ------------------------------------------------------------------------------------------------
+constexpr int kPrepassLdsK = 1024;      // up to this k the seed sizes are counted in LDS first
 template <typename RowT, typename LabelT>
 __global__ __launch_bounds__(256) void k_prepass(const RowT *__restrict__ rowptr,
                                                  const int32_t *__restrict__ seed, int64_t n, int k,
@@ -54,11 +56,16 @@ __global__ __launch_bounds__(256) void k_prepass(const RowT *__restrict__ rowptr
                                                  unsigned long long *__restrict__ S,
                                                  unsigned long long *__restrict__ misc) {
     __shared__ unsigned long long s_maxdeg;
-    __shared__ unsigned int s_bad;
-    if (threadIdx.x == 0) { s_maxdeg = 0; s_bad = 0; }
+    __shared__ unsigned int s_bad, s_none;
+    // (a workgroup's vertices: at most n / gridDim.x + 256 < 2^32)
+    __shared__ unsigned int s_size[kPrepassLdsK];
+    const bool in_lds = seed && k <= kPrepassLdsK;
+    if (threadIdx.x == 0) { s_maxdeg = 0; s_bad = 0; s_none = 0; }
+    if (in_lds)
+        for (int j = threadIdx.x; j < k; j += 256) s_size[j] = 0;
     __syncthreads();
     unsigned long long mymax = 0;
-    unsigned int bad = 0;
+    unsigned int bad = 0, none = 0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += stride) {
         if (rowptr) {
@@ -70,19 +77,28 @@ __global__ __launch_bounds__(256) void k_prepass(const RowT *__restrict__ rowptr
             int32_t s = seed[v];
             if (s >= 0 && s < k) {
                 lab = (uint32_t)s;
-                atomicAdd(&S[s], 1ull);
+                // (a labelling that covers every vertex would otherwise queue n atomics at k addresses)
+                if (in_lds) atomicAdd(&s_size[s], 1u);
+                else atomicAdd(&S[s], 1ull);
             } else if (s != -1) {
                 bad += 1;
+            } else {
+                none += 1;
             }
         }
         Lc[v] = (LabelT)lab;
     }
     if (mymax) atomicMax(&s_maxdeg, mymax);
     if (bad) atomicAdd(&s_bad, bad);
+    if (none) atomicAdd(&s_none, none);
     __syncthreads();
+    if (in_lds)
+        for (int j = threadIdx.x; j < k; j += 256)
+            if (s_size[j]) atomicAdd(&S[j], (unsigned long long)s_size[j]);
     if (threadIdx.x == 0) {
         if (s_maxdeg) atomicMax(&misc[0], s_maxdeg);
         if (s_bad) atomicAdd(&misc[1], (unsigned long long)s_bad);
+        if (s_none) atomicAdd(&misc[5], (unsigned long long)s_none);
         if (blockIdx.x == 0 && rowptr) misc[3] = (unsigned long long)rowptr[n];
     }
 }

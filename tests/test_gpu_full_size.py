@@ -6,6 +6,8 @@ launch configuration bench.py times:
   * the whole 3-pass run is checked through properties that hold at any size (label range, sizes equal
     the label counts and respect the capacity, two runs give the same bytes) and the two independent
     score paths (plain LDS and two-phase) must agree bit for bit;
+  * a labelling evaluated on a plan (neighbour counts, cut, Eq. (1)): sampled rows of the counts equal the
+    oracle's, the cut equals the walk over the CSR arrays, Eq. (1) agrees with the CSR routine;
   * the complete 3-pass run (pass 0 and two refinement passes, 318 chunk steps) is replayed on the oracle
     (two to three minutes of single-thread CPU time) and labels, sizes and estimates are compared element
     by element with the library's."""
@@ -116,6 +118,38 @@ def test_three_pass_run_properties_and_path_agreement(graph):
     assert outs[0][1] == outs[2][1]
     # the cut of a random 16-way split is 15/16; the run must do better than that
     assert outs[0][1] / g.nnz < 15 / 16
+
+
+def test_a_labelling_evaluated_on_a_plan(graph):
+    g = graph
+    print("[case] full-size plan: neighbour counts, cut, Eq. (1)", flush=True)
+    with B.Plan(g.rowptr, g.colidx, g.n, CHUNK) as plan:
+        lab = B.grem_partition_planned(plan, K, SLACK, 0)
+        lab[::1000] = -1                                   # some vertices without a label
+        counts = B.grem_plan_neighbour_counts(plan, K, lab)
+        cut = B.grem_plan_edge_cut(plan, K, lab)
+        torch.cuda.synchronize()
+        assert int(cut.item()) == int(B.grem_edge_cut(g.rowptr, g.colidx, g.n, lab).item())
+        # rows sampled over the whole range (hubs among them: the 2,000 longest rows), against the oracle
+        rng = np.random.default_rng(3)
+        deg = g.rowptr[1:] - g.rowptr[:-1]
+        rows = torch.cat([torch.as_tensor(rng.integers(0, g.n, 20_000)).to(DEV), torch.topk(deg, 2000).indices,
+                          torch.arange(g.n - 64, g.n, device=DEV)]).unique()
+        lens = deg[rows]
+        sub_rp = torch.zeros(rows.numel() + 1, dtype=torch.int64, device=DEV)
+        sub_rp[1:] = torch.cumsum(lens, 0)
+        pos = torch.arange(int(sub_rp[-1].item()), device=DEV) - torch.repeat_interleave(sub_rp[:-1] - g.rowptr[rows], lens)
+        sub_ci = g.colidx[pos]
+        want = oracle.neighbour_counts(sub_rp.cpu().numpy(), sub_ci.cpu().numpy(), rows.numel(), lab.cpu().numpy(), K)
+        got = counts[rows].cpu().numpy().view(np.uint32).astype(np.int64)
+        assert int(lens.max()) > 40_000 and np.array_equal(got, want)
+        del counts, pos, sub_ci
+        two = torch.where(lab >= 0, lab & 1, lab)
+        a = B.grem_plan_expected_cut(plan, two, 0.01)
+        b = B.grem_expected_cut(g.rowptr, g.colidx, g.n, two, 0.01)
+        torch.cuda.synchronize()
+        a, b = a.cpu().numpy(), b.cpu().numpy()
+        assert a[1] == b[1] and abs(a[0] - b[0]) <= 1e-9 * b[0]
 
 
 def test_whole_run_equals_the_oracle(graph):

@@ -142,6 +142,10 @@ def test_two_phase_path_seeded_and_edge_cases():
     _check(g, 3, 1.05, 2500, 2, seed=seed, mode=B.HIST_SWEEP, col_bits=6, tag="30% seeded")
     _check(g, 3, 1.05, 2500, 2, seed=seed, mode=B.HIST_SWEEP, col_bits=6, hub_degree=14, tag="30% seeded, hubs")
     _check(g, 3, 1.05, 2500, 0, seed=seed, mode=B.HIST_SWEEP, col_bits=6, tag="seeded R=0")
+    # a seed that labels every vertex (no tuple to mark as unassigned): a warm start that is refined
+    full = np.random.default_rng(1).integers(0, 3, g.n).astype(np.int32)
+    _check(g, 3, 1.1, 2500, 2, seed=full, mode=B.HIST_SWEEP, col_bits=6, tag="every vertex seeded")
+    _check(g, 3, 1.1, 2500, 0, seed=full, mode=B.HIST_SWEEP, col_bits=6, hub_degree=14, tag="every vertex seeded, hubs, R=0")
     small = synth.planted_partition(n=1500, blocks=3, seed=4, rowptr_dtype=np.int64)
     _check(small, 4, 1.05, 1, 1, mode=B.HIST_SWEEP, col_bits=5, hub_degree=12, tag="chunk=1")
     _check(small, 5, 1.05, 7, 2, mode=B.HIST_SWEEP, col_bits=4, hub_degree=12, tag="chunk=7")
@@ -169,6 +173,8 @@ def test_two_phase_path_17_to_32_partitions(k):
     rng = np.random.default_rng(k)
     seed = np.where(rng.random(g.n) < 0.3, rng.integers(0, k, g.n), -1).astype(np.int32)
     _check(g, k, 1.1, 2500, 2, seed=seed, mode=B.HIST_SWEEP, col_bits=8, hub_degree=30, tag="wide, seeded")
+    full = rng.integers(0, k, g.n).astype(np.int32)
+    _check(g, k, 1.4, 2500, 1, seed=full, mode=B.HIST_SWEEP, col_bits=8, hub_degree=30, tag="wide, every vertex seeded")
     r = synth.rmat(15, 16, seed=3, rowptr_dtype=torch.int64)
     _check(r, k, 1.05, 1 << 13, 2, mode=B.HIST_SWEEP, col_bits=11, hub_degree=300, tag="wide, rmat")
     h = synth.hub_stress(scale=14, edge_factor=8, hubs=3, hub_degree=3000, seed=2)
