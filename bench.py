@@ -373,6 +373,32 @@ def bench_eq1(args, w, dev):
         "roofline": {"bound": "hbm", "achieved": nbytes / sec / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": nbytes / sec / 1e9 / HBM_PEAK_GBPS, "traffic": None, "kernel": "k_xc_terms"},
     }
+    if not args.no_kernel_timing:
+        # the same evaluation, and the cut, on a plan of the graph (label look-ups served from LDS)
+        def timed(f, reps=5):
+            f()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                t0 = time.perf_counter()
+                r = f()
+                torch.cuda.synchronize()
+                ts.append(1e3 * (time.perf_counter() - t0))
+            return r, sorted(ts)[len(ts) // 2]
+        t0 = time.perf_counter()
+        plan = B.Plan(g.rowptr, g.colidx, n, 1 << 20)
+        torch.cuda.synchronize()
+        plan_ms = 1e3 * (time.perf_counter() - t0)
+        with plan:
+            pe, pe_ms = timed(lambda: B.grem_plan_expected_cut(plan, labels, x))
+            pc, pc_ms = timed(lambda: B.grem_plan_edge_cut(plan, 2, labels))
+            cc, cc_ms = timed(lambda: B.grem_edge_cut(g.rowptr, g.colidx, n, labels))
+        pec, pbase = pe.cpu().numpy().tolist()
+        assert pbase == base and abs(pec - ec) <= 1e-9 * ec and int(pc.item()) == int(cc.item())
+        out["on_a_plan"] = {"plan_create_ms": round(plan_ms, 3), "expected_cut_ms": round(pe_ms, 3),
+                            "edge_cut_ms": round(pc_ms, 3), "edge_cut_csr_walk_ms": round(cc_ms, 3),
+                            "is": "grem_plan_expected_cut / grem_plan_edge_cut on a grem_plan of the same graph "
+                                  "(median of 5), equal to the CSR routines' results"}
     if not args.no_cpu_baseline:
         import oracle
         rows = min(n, 2_000_000)
