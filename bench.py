@@ -390,8 +390,16 @@ def bench_eq1(args, w, dev):
         torch.cuda.synchronize()
         plan_ms = 1e3 * (time.perf_counter() - t0)
         with plan:
-            pe, pe_ms = timed(lambda: B.grem_plan_expected_cut(plan, labels, x))
-            pc, pc_ms = timed(lambda: B.grem_plan_edge_cut(plan, 2, labels))
+            # the calls' state from a workspace, as in the partition bench (stream-ordered allocations of
+            # several GB per call would be most of the time)
+            ws = torch.empty(plan.call_bytes(2, 0, seeded=True, with_estimates_out=True) + 8 * n + 4096,
+                             dtype=torch.uint8, device=dev)
+            B.grem_set_workspace(ws)
+            try:
+                pe, pe_ms = timed(lambda: B.grem_plan_expected_cut(plan, labels, x))
+                pc, pc_ms = timed(lambda: B.grem_plan_edge_cut(plan, 2, labels))
+            finally:
+                B.grem_set_workspace(None)
             cc, cc_ms = timed(lambda: B.grem_edge_cut(g.rowptr, g.colidx, n, labels))
         pec, pbase = pe.cpu().numpy().tolist()
         assert pbase == base and abs(pec - ec) <= 1e-9 * ec and int(pc.item()) == int(cc.item())

@@ -333,7 +333,7 @@ int grem_edge_buckets(const int32_t *src, const int32_t *dst, int64_t m, int64_t
  *   out[1] = sum_i (k_i - k0_i)                        (the value at x = 1)
  * Every edge of a symmetric CSR is seen from both ends.  The expected cuts with refinement over two
  * chunks are the same expression at 2x.  rowptr (rowptr_bits 32 or 64), colidx, labels (n int32), out
- * (2 doubles): device pointers.  Floating point: the tail is summed in the log domain in double;
+ * (2 doubles): device pointers.  Floating point: the tail is summed in double (in the log domain when a node has more than 256 draws);
  * agreement with an exact evaluation to about 1e-9 relative.  Errors: GREM_ERR_ARG (null pointer,
  * n < 1, bad rowptr_bits, x outside (0, 1]), GREM_ERR_NOMEM, GREM_ERR_HIP. */
 int grem_expected_cut(const void *rowptr, int32_t rowptr_bits, const int32_t *colidx, int64_t n,

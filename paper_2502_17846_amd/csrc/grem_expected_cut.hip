@@ -6,8 +6,9 @@
 // Refinement over two chunks is the same expression at 2x (Sec. 4.2, "The Benefit of Refinement").
 //
 // Sixteen lanes per node count its CSR row's labels; one of them then sums the tail of the distribution
-// term by term in the log domain (first term from lgamma, the following ones by the ratio of consecutive probabilities).  Sums
-// are reduced per workgroup and then by one workgroup in a fixed order, so the result is reproducible.
+// term by term: in the log domain (first term from lgamma, the following ones by the ratio of consecutive
+// probabilities), or, for a node with few draws, as plain products of ratios.  Sums are reduced per
+// workgroup and then by one workgroup in a fixed order, so the result is reproducible.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -30,6 +31,8 @@ __device__ __forceinline__ double xc_log_choose(double a, double b)
     return lgamma(a + 1.0) - lgamma(b + 1.0) - lgamma(a - b + 1.0);
 }
 
+constexpr long long kXcFewDraws = 256;     // up to this many draws the tail is summed without logarithms
+
 // One node's terms of Eq. (1) from its two neighbour counts: *ec = (k - k0)(1 - q) + k0 q, *base = k - k0
 // (both left as they are for a node without labelled neighbours).
 __device__ __forceinline__ void xc_node_terms(uint32_t c0, uint32_t c1, double x, double* ec_out, double* base_out)
@@ -44,7 +47,25 @@ __device__ __forceinline__ void xc_node_terms(uint32_t c0, uint32_t c1, double x
     long long jhi = (d + 1) / 2 - 1;
     if (jhi > k0) jhi = k0;
     double q = 0.0;
-    if (jhi >= jlo) {
+    if (jhi >= jlo && jlo == 0 && d <= kXcFewDraws) {
+        // few draws, all of which the minority could fill (the usual node at small x): pmf(0) = C(r, d) / C(k, d)
+        // as a product of d ratios, the following terms by the ratio of consecutive probabilities -- no
+        // lgamma, log or exp.  pmf(0) is about (r/k)^d: whenever the tail is not negligible (at least
+        // 1e-20, which takes (r/k)^(d/2) 2^d >= 1e-20) it stays above 1e-40 / 4^d, far from the smallest
+        // double for d <= 256; where pmf(0) does underflow, the tail is zero to every digit that counts.
+        // (the factors are small integers held in doubles and stepped by one: exact, and no 64-bit
+        // integer-to-double conversions in the loops)
+        double p = 1.0, rr = (double)r, kk = (double)k;
+        for (int i = 0; i < (int)d; ++i) { p *= rr / kk; rr -= 1.0; kk -= 1.0; }
+        q = p;
+        double a = (double)k0, b = (double)d, c = 1.0, e = (double)(r - d + 1);
+        for (int j = 0; j < (int)jhi; ++j) {
+            p *= (a * b) / (c * e);
+            q += p;
+            a -= 1.0; b -= 1.0; c += 1.0; e += 1.0;
+        }
+        if (q > 1.0) q = 1.0;
+    } else if (jhi >= jlo) {
         double logp = xc_log_choose((double)k0, (double)jlo) + xc_log_choose((double)r, (double)(d - jlo)) -
                       xc_log_choose((double)k, (double)d);
         q = exp(logp);
