@@ -584,7 +584,7 @@ def main():
                     help="degree from which a row is spread over the chunk's workgroups (0 = library default)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU; run with --gpus 1 "
+        print("bench.py: the library runs on one GPU; run with --gpus 1 "
               "(the partitioner has no multi-GPU path)", file=sys.stderr)
         sys.exit(2)
 
