@@ -750,7 +750,9 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
         if (!set_lds((const void *)k_tp_lookup<true, false, 4>, lookup_lds) ||
             !set_lds((const void *)k_tp_lookup<true, true, 4>, lookup_lds) ||
             !set_lds((const void *)k_tp_score<uint32_t, 16>, score_lds) ||
-            !set_lds((const void *)k_tp_score<uint16_t, 16>, score_lds))
+            !set_lds((const void *)k_tp_score<uint16_t, 16>, score_lds) ||
+            !set_lds((const void *)k_tp_score<uint32_t, 16, true>, score_lds) ||
+            !set_lds((const void *)k_tp_score<uint16_t, 16, true>, score_lds))
             return GREM_ERR_HIP;
     }
     L.memset(t.Hhub, 0, (hubs_in_admission ? 2 : 1) * ((size_t)P.max_chunk_hubs + 1) * (size_t)k * 4);
@@ -829,8 +831,14 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                     if (use16) score(k_tp_score<uint16_t, 32>, t.E16);
                     else score(k_tp_score<uint32_t, 32>, E32);
                 } else {
-                    if (use16) score(k_tp_score<uint16_t, 16>, t.E16);
-                    else score(k_tp_score<uint32_t, 16>, E32);
+                    // (k <= 8: a row's few counters spread over the LDS banks)
+                    if (k <= 8) {
+                        if (use16) score(k_tp_score<uint16_t, 16, true>, t.E16);
+                        else score(k_tp_score<uint32_t, 16, true>, E32);
+                    } else {
+                        if (use16) score(k_tp_score<uint16_t, 16>, t.E16);
+                        else score(k_tp_score<uint32_t, 16>, E32);
+                    }
                 }
             });
             if (hubs_in_admission) {

@@ -1228,8 +1228,12 @@ template <> struct TpLabels<8> {
 };
 
 // a group of eight tuples: 16 bytes of R, their labels
-template <bool COUNT16, int KP, int LB>
+// SW (k <= 8, KP = 16): a row's eight counter words would use two to four of their places only, and the
+// rows' words eight to thirty-two of the 64 LDS banks; the 8-byte piece of partitions 4p .. 4p+3 of row t
+// therefore sits at place p ^ ((t >> 3) & 3) of the row, which spreads them over all banks.
+template <bool COUNT16, int KP, int LB, bool SW>
 __device__ __forceinline__ void tp_count_eight(const u32x4 rows, const TpLabels<LB> labels, int k, uint32_t *hist) {
+    static_assert(!SW || (COUNT16 && KP == 16), "the swizzle is that of the 16-counter rows");
     const uint32_t w[4] = {rows.x, rows.y, rows.z, rows.w};
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -1239,7 +1243,8 @@ __device__ __forceinline__ void tp_count_eight(const u32x4 rows, const TpLabels<
         const uint32_t one = (~half) & 1u;                // bit 0 clear: the tuple is to be counted
         if (COUNT16) {
             // no branch: what is not to be counted adds zero (to a counter its bits happen to name)
-            const uint32_t off = (KP == 16 ? r : r << 1) | ((lab & ~1u) << 1);
+            uint32_t off = (KP == 16 ? r : r << 1) | ((lab & ~1u) << 1);
+            if (SW) off ^= (r >> 5) & 0x18u;                  // ((row >> 3) & 3) << 3: the piece's place
             uint32_t *ctr = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(hist) + off);
             atomicAdd(ctr, one << ((lab & 1u) << 4));
         } else if (one) {
@@ -1250,7 +1255,7 @@ __device__ __forceinline__ void tp_count_eight(const u32x4 rows, const TpLabels<
 
 // Groups [g0, g1) of a row stream that starts at slot `base` (a multiple of 8) of R and Lx, counted by
 // the whole workgroup, NU groups per thread in flight.
-template <bool COUNT16, int KP, int LB, int NU>
+template <bool COUNT16, int KP, int LB, int NU, bool SW = false>
 __device__ __forceinline__ void tp_count_stream(const uint16_t *__restrict__ R, const uint32_t *__restrict__ Lx, u64 base,
                                                 uint32_t g0, uint32_t g1, int k, uint32_t *hist) {
     const u32x4 *R4 = reinterpret_cast<const u32x4 *>(R + base);
@@ -1269,7 +1274,7 @@ __device__ __forceinline__ void tp_count_stream(const uint16_t *__restrict__ R, 
         }
 #pragma unroll
         for (int u = 0; u < NU; ++u)
-            if (g + u * kTpThreads < g1) tp_count_eight<COUNT16, KP, LB>(rows[u], labs[u], k, hist);
+            if (g + u * kTpThreads < g1) tp_count_eight<COUNT16, KP, LB, SW>(rows[u], labs[u], k, hist);
     }
 }
 
@@ -1288,6 +1293,7 @@ __device__ __forceinline__ unsigned long long tp_xor_lane64(unsigned long long v
 // movers of its two admission tiles per proposed partition (cnt, the input of the admission;
 // k_hub_finalize adds the hubs).
 //
+// SW: k <= 8 (with KP = 16): the rows' counter pieces are swizzled over the LDS banks (tp_count_eight).
 // KP = 16 (k <= 16, 4-bit labels in Lx, 64 KB of counters: two workgroups per CU) or 32 (k <= 32,
 // 8-bit labels, 128 KB of counters: one workgroup per CU).  KP / 4 lanes share a vertex in the
 // blend: lane q owns partitions 4q .. 4q+3 when k % 4 == 0 (one 8- or 16-byte piece of E's row), else
@@ -1296,7 +1302,7 @@ __device__ __forceinline__ unsigned long long tp_xor_lane64(unsigned long long v
 // LDS: hist[kSliceRows * KP / 2] (16-bit counters, KP per row; a static array when KP = 16),
 //      meta[kSliceRows / 2] (per row: old label, hub flag << 8), hhist[share_hubs * k], room[k], tcnt[2 * k]
 // ------------------------------------------------------------------------------------------------
-template <typename ET, int KP>
+template <typename ET, int KP, bool SW = false>
 __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP == 16 ? 8 : 4, KP == 16 ? 8 : 4))) void k_tp_score(
     const uint16_t *__restrict__ R, const uint32_t *__restrict__ Lx, TpTables tb, SweepPlan pl,
     const uint8_t *__restrict__ Lc, const long long *__restrict__ S, ET *__restrict__ E,
@@ -1380,7 +1386,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP =
         meta[at] |= (uint16_t)0x100u;
     }
 
-    tp_count_stream<true, KP, LB, 3>(R, Lx, sbeg, 0u, slen >> 3, k, hist);
+    tp_count_stream<true, KP, LB, 3, SW>(R, Lx, sbeg, 0u, slen >> 3, k, hist);
     if (any_hub) tp_count_stream<false, KP, LB, 2>(R, Lx, hbeg, hg0, hg1, k, hhist);
     __syncthreads();
 
@@ -1422,7 +1428,7 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP =
             if (mt & 0x100u) continue;                              // hubs are k_hub_finalize's
             const uint32_t old = mt & 0xFFu;
             const uint32_t oldz = old - 4u * (uint32_t)q;           // < 4: the old label is one of this thread's
-            const uint2 hw = *reinterpret_cast<const uint2 *>(hist + t * (KP / 2) + 2 * q);
+            const uint2 hw = *reinterpret_cast<const uint2 *>(hist + t * (KP / 2) + 2 * (SW ? (q ^ ((t >> 3) & 3)) : q));
             u32x2 o;
             o.x = e[u].x + (hw.x << sh);
             o.y = e[u].y + (hw.y << sh);
@@ -1497,7 +1503,8 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP =
         for (int z = 0; z < 4; ++z) {
             const int j = vec ? 4 * q + z : q + LPV * z;
             if (j < k) {
-                const uint32_t cidx = (uint32_t)t * (uint32_t)KP + (uint32_t)j;
+                const uint32_t jj = SW ? ((uint32_t)j ^ ((((uint32_t)t >> 3) & 3u) << 2)) : (uint32_t)j;   // (the piece's place)
+                const uint32_t cidx = (uint32_t)t * (uint32_t)KP + jj;
                 const uint32_t h = (hist[cidx >> 1] >> (16 * (cidx & 1u))) & 0xFFFFu;
                 ev[z] += h << sh;
                 const uint32_t rm = room[j] + ((uint32_t)j == old ? 1u : 0u);
