@@ -708,7 +708,8 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
     if (external_E && (((uintptr_t)estimates_out) & 15u) != 0) return GREM_ERR_ARG;
     if (fixed_labels && (!seed || !external_E || R != 0)) return GREM_ERR_ARG;
     // estimates of the regular rows stay below hub_degree * 2^R: 16 bits when that fits
-    const bool use16 = (((unsigned long long)(hub_degree - 1)) << R) <= 65535ull;
+    // (the counts of a fixed labelling go straight to the caller's 32-bit array: no 16-bit copy to expand)
+    const bool use16 = !fixed_labels && (((unsigned long long)(hub_degree - 1)) << R) <= 65535ull;
 
     const bool hubs_in_admission = admission_takes_hubs(P, use16, external_E);
 
