@@ -28,11 +28,11 @@ HBM_PEAK_GBPS = 8000.0
 # at that time, and `traffic` is reported as null when the sources have changed since.
 PMC = {
     "workload": "chunglu-111M",
-    "sources_sha256": "7b89e4b8ae27f7ab111c5833d5436e72cbaa362ff36922dbc27c30ce8ea69bc0",
-    "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,590 KiB
+    "sources_sha256": "d5cb4ad738c4ebb9050a2ddee6690447a0309925a3da1a4f191c7a91a8a83e56",
+    "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,591 KiB
     "write_factor": 1.0,        # 2 GiB written -> WRITE_SIZE 2,097,152 KiB
-    "fetch_kib": {"k_tp_score": 1.4258e+07, "k_tp_lookup": 1.36579e+07},
-    "write_kib": {"k_tp_score": 7.31471e+06, "k_tp_lookup": 5.58724e+06},
+    "fetch_kib": {"k_tp_score": 1.42574e+07, "k_tp_lookup": 1.36583e+07},
+    "write_kib": {"k_tp_score": 7.31471e+06, "k_tp_lookup": 5.5889e+06},
     "launches": {"k_tp_score": 318, "k_tp_lookup": 317},
 }
 
