@@ -85,3 +85,12 @@ def test_capacity_matches_oracle_on_a_grid(lib):
         for k in (1, 2, 3, 16, 100, 256, 4096):
             for slack in (1.0, 1.01, 1.03, 1.05, 1.1, 1.5, 2.0):
                 assert lib.grem_capacity(n, k, slack) == oracle.capacity(n, k, slack)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
