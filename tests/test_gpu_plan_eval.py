@@ -112,3 +112,29 @@ def test_expected_cut_on_a_plan_with_a_row_of_60000_entries(x):
         got, base = out.cpu().numpy().tolist()
         assert base == want_base
         assert abs(got - want) <= RTOL * max(1.0, want), (x, got, want)
+
+
+def test_degenerate_graphs():
+    # no entries at all; fewer vertices than a slice of rows, one ragged chunk, loops and repeated entries
+    e = synth.Graph(np.zeros(5001, dtype=np.int64), np.zeros(0, dtype=np.int32), 5000, 0, 0, None, "edgeless")
+    rp, ci = torch.as_tensor(e.rowptr).to(DEV), torch.zeros(1, dtype=torch.int32, device=DEV)
+    with B.Plan(rp, ci, e.n, 2048) as plan:
+        lab = _labels(e.n, 3, 0.2, 5)
+        counts = B.grem_plan_neighbour_counts(plan, 3, torch.as_tensor(lab).to(DEV))
+        cut = B.grem_plan_edge_cut(plan, 3, torch.as_tensor(lab).to(DEV))
+        out = B.grem_plan_expected_cut(plan, torch.as_tensor(np.minimum(lab, 1)).to(DEV), 0.5)
+        torch.cuda.synchronize()
+        assert int(counts.abs().sum()) == 0 and int(cut.item()) == 0 and out.cpu().numpy().tolist() == [0.0, 0.0]
+    rng = np.random.default_rng(8)
+    n = 37
+    deg = rng.integers(0, 6, n)
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    colidx = rng.integers(0, n, int(rowptr[-1])).astype(np.int32)
+    g = synth.Graph(rowptr, colidx, n, int(rowptr[-1]), 0, None, "tiny multigraph")
+    with B.Plan(torch.as_tensor(rowptr).to(DEV), torch.as_tensor(colidx).to(DEV), n, 1 << 20) as plan:
+        for k, none_share in ((1, 0.0), (2, 0.3), (16, 0.0)):
+            _check_counts_and_cut(g, plan, k, _labels(n, k, none_share, 3 + k))
+        lab = _labels(n, 2, 0.2, 1)
+        want, want_base = oracle.expected_cut(rowptr, colidx, n, lab, 0.7)
+        got, base = B.grem_plan_expected_cut(plan, torch.as_tensor(lab).to(DEV), 0.7).cpu().numpy().tolist()
+        assert base == want_base and abs(got - want) <= RTOL * max(1.0, want)
