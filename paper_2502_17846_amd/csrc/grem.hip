@@ -660,6 +660,7 @@ struct TpState {
     uint16_t *Rdyn = nullptr, *E16 = nullptr;
     uint8_t *Lc4 = nullptr;            // k <= 16: the labels two per byte, kept by the admission from the second pass on
     uint8_t *hub_old = nullptr;        // the labels of the chunk's hubs, by their place in its list (see k_admit_hubs)
+    uint32_t *coarse = nullptr;        // two tables of the tiles' mover counts added up 32 tiles at a time (k_admit_hubs)
 };
 
 // twice: two tables of the chunk's hub counts and of the hubs' estimates (the admission that also does the
@@ -676,6 +677,7 @@ void state_two_phase(Carver &c, TpState &t, int64_t n, int32_t k, size_t slots, 
     c.take(t.Ehub, (use16 && !external_E) ? (twice ? 2 : 1) * (total_hubs + 1) * (size_t)k : 0);
     c.take(t.Lc4, k <= 16 ? (size_t)n / 2 + 16 : 0);
     c.take(t.hub_old, twice ? max_chunk_hubs + 16 : 0);
+    c.take(t.coarse, twice ? 2 * (size_t)(kAdmitTilesMax / kCoarseTiles) * (size_t)k : 0);
 }
 
 // The admission kernel does the hubs' blend and proposal itself when every chunk has few hubs and few
@@ -757,6 +759,8 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
             return GREM_ERR_HIP;
     }
     L.memset(t.Hhub, 0, (hubs_in_admission ? 2 : 1) * ((size_t)P.max_chunk_hubs + 1) * (size_t)k * 4);
+    const size_t coarse_row = (size_t)(kAdmitTilesMax / kCoarseTiles) * (size_t)k;
+    if (hubs_in_admission) L.memset(t.coarse, 0, 2 * coarse_row * 4);
 
     // look-ups of the labels of chunks [c0, c0 + count): shares per column block sized so that one
     // launch fills the chip without cutting the blocks' streams into crumbs
@@ -825,7 +829,8 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                 hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kTpThreads), score_lds, stream, rows_now, t.Lx, tb, pl,
                                    (const uint8_t *)st.Lc, Snow, Eptr, Hnow, (uint8_t *)st.prop, st.cnt, st.room, (int)c,
                                    lo, hi, (int)k, jlim, P.share_hubs, P.nvs[(size_t)c], pass, cap, store_e,
-                                   hubs_in_admission ? t.hub_old : (uint8_t *)nullptr);
+                                   hubs_in_admission ? t.hub_old : (uint8_t *)nullptr,
+                                   hubs_in_admission ? t.coarse + (size_t)(step & 1) * coarse_row : (uint32_t *)nullptr);
             };
             L.run(GREM_KERNEL_SCORE, [&] {
                 if (wide) {
@@ -859,7 +864,9 @@ int run_two_phase(const PlanData &P, int32_t k, double slack, int32_t R, const i
                                            (const long long *)st.room, (unsigned long long *)Snow, st.ocnt, pass, packed_now,
                                            (const int32_t *)(pl.hub_row + hub0), (const uint8_t *)t.hub_old, nh,
                                            (const uint32_t *)Hnow, Hother,
-                                           prev_hubs, Eold, Enew, store_e);
+                                           prev_hubs, Eold, Enew, store_e,
+                                           (const uint32_t *)(t.coarse + (size_t)(step & 1) * coarse_row),
+                                           t.coarse + (size_t)((step + 1) & 1) * coarse_row);
                     };
                     if (wide) go(k_admit_hubs<32>);
                     else go(k_admit_hubs<16>);

@@ -1299,16 +1299,21 @@ __device__ __forceinline__ unsigned long long tp_xor_lane64(unsigned long long v
 // blend: lane q owns partitions 4q .. 4q+3 when k % 4 == 0 (one 8- or 16-byte piece of E's row), else
 // q, q + KP/4, q + 2 KP/4, q + 3 KP/4.
 // hub_old: see below (may be null).
+// coarse (may be null): [tiles / kCoarseTiles][k], the mover counts of kCoarseTiles tiles added up (atomic adds
+// into a table that starts at zero), so that the admission need not read every tile's counts.
 // LDS: hist[kSliceRows * KP / 2] (16-bit counters, KP per row; a static array when KP = 16),
 //      meta[kSliceRows / 2] (per row: old label, hub flag << 8), hhist[share_hubs * k], room[k], tcnt[2 * k]
 // ------------------------------------------------------------------------------------------------
+constexpr int kCoarseTiles = 32;         // tiles per row of the coarse mover counts (a slice's two tiles share one)
+
 template <typename ET, int KP, bool SW = false>
 __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP == 16 ? 8 : 4, KP == 16 ? 8 : 4))) void k_tp_score(
     const uint16_t *__restrict__ R, const uint32_t *__restrict__ Lx, TpTables tb, SweepPlan pl,
     const uint8_t *__restrict__ Lc, const long long *__restrict__ S, ET *__restrict__ E,
     uint32_t *__restrict__ Hhub, uint8_t *__restrict__ prop, uint32_t *__restrict__ cnt,
     long long *__restrict__ room_out, int c, int64_t chunk_lo, int64_t chunk_hi, int k, int jlim,
-    int share_hubs, uint32_t nvs, int pass, long long P, int store_e, uint8_t *__restrict__ hub_old) {
+    int share_hubs, uint32_t nvs, int pass, long long P, int store_e, uint8_t *__restrict__ hub_old,
+    uint32_t *__restrict__ coarse) {
     extern __shared__ uint32_t smem[];
     constexpr int LB = KP == 16 ? 4 : 8;
     constexpr int LPV = KP / 4;                                 // lanes per vertex in the blend
@@ -1464,6 +1469,11 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP =
         const int64_t tile0 = (v0 - chunk_lo) / kAdmitTile;
         const int ntl = nv > kAdmitTile ? 2 : 1;
         for (int j = tid; j < ntl * k; j += kTpThreads) cnt[(size_t)tile0 * k + j] = tcnt[j];
+        if (coarse)
+            for (int j = tid; j < k; j += kTpThreads) {
+                const uint32_t x = tcnt[j] + (ntl > 1 ? tcnt[k + j] : 0u);
+                if (x) atomicAdd(&coarse[(size_t)(tile0 / kCoarseTiles) * k + j], x);
+            }
         return;
     }
 
@@ -1559,6 +1569,11 @@ __global__ __launch_bounds__(kTpThreads) __attribute__((amdgpu_waves_per_eu(KP =
         const int64_t tile0 = (v0 - chunk_lo) / kAdmitTile;
         const int ntl = nv > kAdmitTile ? 2 : 1;
         for (int j = tid; j < ntl * k; j += kTpThreads) cnt[(size_t)tile0 * k + j] = tcnt[j];
+        if (coarse)
+            for (int j = tid; j < k; j += kTpThreads) {
+                const uint32_t x = tcnt[j] + (ntl > 1 ? tcnt[k + j] : 0u);
+                if (x) atomicAdd(&coarse[(size_t)(tile0 / kCoarseTiles) * k + j], x);
+            }
     }
 }
 
@@ -1657,7 +1672,9 @@ __global__ __launch_bounds__(256) void k_hub_finalize(SweepPlan pl, const uint8_
 //   - a hub's proposal reaches the thread of its vertex through LDS (`over`); its move counts for the
 //     tiles' mover counts exactly as the atomic add of k_hub_finalize did;
 //   - every workgroup adds up all tiles' counts itself: the chunk's movers per partition (exact, where
-//     k_apply_small gets an upper bound) and those of the tiles before its own.
+//     k_apply_small gets an upper bound) and those of the tiles before its own -- from the coarse table
+//     k_tp_score leaves (Cnow; two tables take turns from chunk to chunk, workgroup 0 clears the other one,
+//     Cclear) and the rows of the tiles of its own coarse group.
 // cnt[tile][t]: movers to t among the tile's regular rows (from k_tp_score).
 // ------------------------------------------------------------------------------------------------
 constexpr int kAdmitHubsMax = 512;        // hubs of a chunk
@@ -1671,7 +1688,7 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
     const int32_t *__restrict__ hub_row, const uint8_t *__restrict__ hub_old, uint32_t nh,
     const uint32_t *__restrict__ Hnow,
     uint32_t *__restrict__ Hclear, uint32_t nclear, const uint32_t *__restrict__ Eold,
-    uint32_t *__restrict__ Enew, int store_e) {
+    uint32_t *__restrict__ Enew, int store_e, const uint32_t *__restrict__ Cnow, uint32_t *__restrict__ Cclear) {
     static_assert(KP == 16 || KP == 32, "partitions per workgroup table");
     constexpr int nwaves = kAdmitTile / 64;
     constexpr int TPW = kSmallApplyTiles;
@@ -1702,7 +1719,22 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
     // all tiles' counts, column `col` by SEGS threads
     const int col = tid & (KP - 1), seg = tid / KP;
     uint32_t all = 0, before = 0;
-    if (col < k) {
+    if (col < k && Cnow) {
+        // the coarse rows (kCoarseTiles tiles each) for the whole chunk and the groups before the workgroup's,
+        // the tiles' own rows only inside its group: (tiles / 32 + 32) * k counts instead of tiles * k
+        const int g0 = tile0 / kCoarseTiles, ng = (ntiles + kCoarseTiles - 1) / kCoarseTiles;
+        for (int r0 = seg; r0 < ng + kCoarseTiles; r0 += SEGS) {
+            uint32_t x = 0;
+            if (r0 < ng) {
+                x = Cnow[(size_t)r0 * k + col];
+                all += x;
+                if (r0 < g0) before += x;
+            } else {
+                const int r = g0 * kCoarseTiles + (r0 - ng);
+                if (r < tile0 && r < ntiles) before += cnt[(size_t)r * k + col];
+            }
+        }
+    } else if (col < k) {
         for (int r0 = seg; r0 < ntiles; r0 += SEGS * 16) {      // (16 loads side by side: one turn when KP = 16)
             uint32_t x[16];
 #pragma unroll
@@ -1746,8 +1778,11 @@ __global__ __launch_bounds__(kAdmitTile) void k_admit_hubs(
     }
     if (tid < TPW) s_unassigned[tid] = 0;
     reinterpret_cast<uint32_t *>(over)[tid] = 0xFFFFFFFFu;
-    if (blockIdx.x == 0)
+    if (blockIdx.x == 0) {
         for (uint32_t q = tid; q < nclear * (uint32_t)k; q += kAdmitTile) Hclear[q] = 0;
+        if (Cclear)
+            for (int q = tid; q < (kAdmitTilesMax / kCoarseTiles) * k; q += kAdmitTile) Cclear[q] = 0;
+    }
     __syncthreads();
     if (all) atomicAdd(&totl[col], all);
     if (before) atomicAdd(&tbl[col], before);
