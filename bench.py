@@ -28,11 +28,11 @@ HBM_PEAK_GBPS = 8000.0
 # at that time, and `traffic` is reported as null when the sources have changed since.
 PMC = {
     "workload": "chunglu-111M",
-    "sources_sha256": "d5cb4ad738c4ebb9050a2ddee6690447a0309925a3da1a4f191c7a91a8a83e56",
-    "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,591 KiB
+    "sources_sha256": "d438ed37210ba8b5b6655fd31cc71318f87b9405e00e3366d7e276ee67d2242f",
+    "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,592 KiB
     "write_factor": 1.0,        # 2 GiB written -> WRITE_SIZE 2,097,152 KiB
-    "fetch_kib": {"k_tp_score": 1.42574e+07, "k_tp_lookup": 1.36583e+07},
-    "write_kib": {"k_tp_score": 7.31471e+06, "k_tp_lookup": 5.5889e+06},
+    "fetch_kib": {"k_tp_score": 1.42661e+07, "k_tp_lookup": 1.36582e+07},
+    "write_kib": {"k_tp_score": 7.32474e+06, "k_tp_lookup": 5.58996e+06},
     "launches": {"k_tp_score": 318, "k_tp_lookup": 317},
 }
 
