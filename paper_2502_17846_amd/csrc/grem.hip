@@ -140,8 +140,10 @@ struct Arena {
 struct Carver {
     char *base;
     size_t off = 0;
+    // (an array of no elements is a null pointer, not the address of whatever comes next: code that asks
+    // "is there such an array" must not be told yes)
     template <typename T> void take(T *&p, size_t count) {
-        p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        p = (base && count) ? reinterpret_cast<T *>(base + off) : nullptr;
         off += align_up(count * sizeof(T));
     }
 };

@@ -277,6 +277,8 @@ def hub_stress(scale: int = 24, edge_factor: int = 16, hubs: int = 64, hub_degre
     """R-MAT as `rmat`, plus `hubs` distinct vertices each joined to `hub_degree` distinct
     uniformly chosen other vertices."""
     n = 1 << scale
+    if hub_degree >= n or hubs > n:
+        raise ValueError("hub_stress: a hub has at most n - 1 distinct neighbours, and there are at most n hubs")
     m = edge_factor * n
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)

@@ -163,6 +163,15 @@ def test_two_phase_path_seeded_and_edge_cases():
     _check(h, 7, 1.1, 8192, 1, mode=B.HIST_SWEEP, col_bits=10, hub_degree=40)
 
 
+def test_wide_plan_long_even_chunks():
+    # chunks of 40 tiles (two groups of 32 in the admission's coarse counts), of even length, on a plan for up to
+    # 32 partitions: from the second pass on the admission once took the absent packed label table for present
+    g = synth.random_graph_np(110_163, 1_321_956, 90298325, simple=True)
+    _check(g, 32, 1.3, 40_000, 1, mode=B.HIST_SWEEP, col_bits=10, tag="wide, 40 tiles")
+    _check(g, 20, 1.3, 70_000, 2, mode=B.HIST_SWEEP, col_bits=10, tag="wide, 69 tiles")
+    _check(g, 16, 1.3, 70_000, 2, mode=B.HIST_SWEEP, col_bits=10, tag="69 tiles")
+
+
 @pytest.mark.parametrize("k", [17, 20, 23, 32])
 def test_two_phase_path_17_to_32_partitions(k):
     # 8-bit labels in the look-up results, 32 counters per row, eight lanes per vertex in the blend
