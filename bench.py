@@ -28,11 +28,11 @@ HBM_PEAK_GBPS = 8000.0
 # at that time, and `traffic` is reported as null when the sources have changed since.
 PMC = {
     "workload": "chunglu-111M",
-    "sources_sha256": "d438ed37210ba8b5b6655fd31cc71318f87b9405e00e3366d7e276ee67d2242f",
-    "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,592 KiB
+    "sources_sha256": "d80c2ce30746ef584f9bde0885b6fb06e11bf52a7f017ac62f1b875e381130bd",
+    "fetch_factor": 2.0,        # 2 GiB read  -> FETCH_SIZE 1,048,591 KiB
     "write_factor": 1.0,        # 2 GiB written -> WRITE_SIZE 2,097,152 KiB
-    "fetch_kib": {"k_tp_score": 1.42661e+07, "k_tp_lookup": 1.36582e+07},
-    "write_kib": {"k_tp_score": 7.32474e+06, "k_tp_lookup": 5.58996e+06},
+    "fetch_kib": {"k_tp_score": 1.42675e+07, "k_tp_lookup": 1.36588e+07},
+    "write_kib": {"k_tp_score": 7.32475e+06, "k_tp_lookup": 5.58938e+06},
     "launches": {"k_tp_score": 318, "k_tp_lookup": 317},
 }
 
