@@ -66,8 +66,17 @@ def test_random_cases(block):
             if k > plan.max_k:
                 continue
             for want_est in (False, True):
-                lab, sizes, est = B.grem_partition_planned(plan, k, slack, R, sd, want_sizes=True, want_estimates=want_est)
-                torch.cuda.synchronize()
+                # inside a workspace of exactly the advertised size, with a guard area behind it
+                need = plan.call_bytes(k, R, seeded=sd is not None, with_estimates_out=want_est)
+                ws = torch.full((need + 65536,), 0xA5, dtype=torch.uint8, device=DEV)
+                B.grem_set_workspace(ws[:need])
+                try:
+                    lab, sizes, est = B.grem_partition_planned(plan, k, slack, R, sd, want_sizes=True, want_estimates=want_est)
+                    torch.cuda.synchronize()
+                finally:
+                    B.grem_set_workspace(None)
+                assert bool((ws[need:] == 0xA5).all()), f"case {case}: a write beyond the workspace"
+                del ws
                 bad = np.nonzero(lab.cpu().numpy() != olab)[0]
                 assert bad.size == 0, f"case {case}: {bad.size} labels differ, first {bad[:5]}"
                 assert sizes.cpu().numpy().tolist() == osizes.tolist()
